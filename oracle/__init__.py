@@ -1,0 +1,164 @@
+"""CPU oracle for the LookupFFN forward pass -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes loader around ``lookupffn_oracle.c`` (plain C, fp32 hash as the
+paper's precision, fp64 reference accumulation for the gather).  Only tests,
+the smoke check and the bench's ``cpu_baseline`` leg may import this package;
+the GPU library never does and shares no code with it.
+
+numpy conventions: fp32 data are ``float32`` arrays; bf16 data are ``uint16``
+arrays holding the raw bf16 bit patterns.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from pathlib import Path
+
+import numpy as np
+
+_HERE = Path(__file__).resolve().parent
+_SRC = _HERE / "lookupffn_oracle.c"
+_LIB = _HERE / "liblookupffn_oracle.so"
+CFLAGS = ["-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
+          "-shared", "-fPIC", "-Wall", "-Wextra"]
+
+F32, BF16 = 0, 1
+_lib = None
+
+
+def build(force: bool = False) -> Path:
+    """Compile the oracle with gcc (no GPU toolchain involved)."""
+    if force or not _LIB.exists() or _LIB.stat().st_mtime < _SRC.stat().st_mtime:
+        tmp = _LIB.with_suffix(f".so.tmp{os.getpid()}")
+        subprocess.run(["gcc", *CFLAGS, "-o", str(tmp), str(_SRC), "-lm"], check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(str(_LIB))
+        vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+        L.oracle_d_pad.argtypes = [ci]
+        L.oracle_n_proj.argtypes = [ci, ci, ci]
+        L.oracle_fwht.argtypes = [vp, ci]
+        L.oracle_fwht.restype = None
+        L.oracle_set_threads.argtypes = [ci]
+        L.oracle_set_threads.restype = None
+        L.oracle_soft_codes.argtypes = [vp, ci, vp, vp, i64, ci, ci, ci, ci]
+        L.oracle_hash.argtypes = [vp, ci, vp, vp, i64, ci, ci, ci, ci]
+        L.oracle_gather.argtypes = [vp, vp, ci, vp, i64, ci, ci, ci, ci]
+        L.oracle_forward.argtypes = [vp, ci, vp, vp, ci, vp, vp, i64, ci, ci, ci, ci, ci, ci]
+        _lib = L
+    return _lib
+
+
+def _dtype_code(a: np.ndarray) -> int:
+    if a.dtype == np.float32:
+        return F32
+    if a.dtype == np.uint16:
+        return BF16
+    raise TypeError(f"oracle takes float32 or uint16 (raw bf16) arrays, got {a.dtype}")
+
+
+def _ptr(a: np.ndarray):
+    assert a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise ValueError(f"oracle {what} failed with code {rc}")
+
+
+def d_pad(d: int) -> int:
+    return lib().oracle_d_pad(d)
+
+
+def n_proj(d: int, k: int, tau: int) -> int:
+    return lib().oracle_n_proj(d, k, tau)
+
+
+def max_threads() -> int:
+    return lib().oracle_max_threads()
+
+
+def set_threads(n: int) -> None:
+    lib().oracle_set_threads(n)
+
+
+def fwht(v: np.ndarray) -> np.ndarray:
+    """Unnormalised Sylvester-order Walsh-Hadamard transform of a 1-D float32 vector."""
+    out = np.ascontiguousarray(v, dtype=np.float32).copy()
+    n = out.shape[0]
+    assert out.ndim == 1 and n >= 1 and n & (n - 1) == 0
+    lib().oracle_fwht(_ptr(out), n)
+    return out
+
+
+def _check_signs(signs: np.ndarray, d: int, k: int, tau: int, n_rounds: int):
+    assert signs.dtype == np.int8
+    assert signs.shape == (n_proj(d, k, tau), n_rounds, d_pad(d)), signs.shape
+
+
+def soft_codes(x: np.ndarray, signs: np.ndarray, k: int, tau: int) -> np.ndarray:
+    """z = x R, shape [n, P*d_pad] float32."""
+    n, d = x.shape
+    n_rounds = signs.shape[1]
+    _check_signs(signs, d, k, tau, n_rounds)
+    x = np.ascontiguousarray(x)
+    signs = np.ascontiguousarray(signs)
+    z = np.empty((n, signs.shape[0] * signs.shape[2]), dtype=np.float32)
+    _check(lib().oracle_soft_codes(_ptr(x), _dtype_code(x), _ptr(signs), _ptr(z),
+                                   n, d, k, tau, n_rounds), "soft_codes")
+    return z
+
+
+def hash_codes(x: np.ndarray, signs: np.ndarray, k: int, tau: int) -> np.ndarray:
+    """codes[n, k] uint16."""
+    n, d = x.shape
+    n_rounds = signs.shape[1]
+    _check_signs(signs, d, k, tau, n_rounds)
+    x = np.ascontiguousarray(x)
+    signs = np.ascontiguousarray(signs)
+    codes = np.empty((n, k), dtype=np.uint16)
+    _check(lib().oracle_hash(_ptr(x), _dtype_code(x), _ptr(signs), _ptr(codes),
+                             n, d, k, tau, n_rounds), "hash")
+    return codes
+
+
+def gather(codes: np.ndarray, tables: np.ndarray, acc64: bool = True) -> np.ndarray:
+    """y[n, d_out] float32 = sum_j tables[j, codes[:, j], :]."""
+    n, k = codes.shape
+    k2, rows, d_out = tables.shape
+    tau = rows.bit_length() - 1
+    assert k2 == k and 1 << tau == rows and codes.dtype == np.uint16
+    codes = np.ascontiguousarray(codes)
+    tables = np.ascontiguousarray(tables)
+    y = np.empty((n, d_out), dtype=np.float32)
+    _check(lib().oracle_gather(_ptr(codes), _ptr(tables), _dtype_code(tables), _ptr(y),
+                               n, k, tau, d_out, int(acc64)), "gather")
+    return y
+
+
+def forward(x: np.ndarray, signs: np.ndarray, tables: np.ndarray, acc64: bool = True,
+            return_codes: bool = False):
+    """Whole forward pass; y[n, d_out] float32 (and codes[n, k] uint16 on request)."""
+    n, d = x.shape
+    k, rows, d_out = tables.shape
+    tau = rows.bit_length() - 1
+    assert 1 << tau == rows
+    n_rounds = signs.shape[1]
+    _check_signs(signs, d, k, tau, n_rounds)
+    x = np.ascontiguousarray(x)
+    signs = np.ascontiguousarray(signs)
+    tables = np.ascontiguousarray(tables)
+    y = np.empty((n, d_out), dtype=np.float32)
+    codes = np.empty((n, k), dtype=np.uint16)
+    _check(lib().oracle_forward(_ptr(x), _dtype_code(x), _ptr(signs), _ptr(tables),
+                                _dtype_code(tables), _ptr(y), _ptr(codes), n, d, k, tau,
+                                d_out, n_rounds, int(acc64)), "forward")
+    return (y, codes) if return_codes else y

@@ -1,0 +1,271 @@
+/*
+ * CPU oracle for the LookupFFN inference forward pass.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain statement of what
+ * the method computes, used to check the GPU library and to report a host
+ * baseline.  It shares no code with the GPU path and nothing in the product
+ * path may call it.
+ *
+ * What is computed (paper notation; h = number of tables, here `k`):
+ *
+ *   Sec. 3.1, eq. "lookup":        y = sum_{j<k} T_j[ f_j(x) ]          (no 1/k factor)
+ *   Sec. 3.1, hyperplane hash:     f_j(x) = decimal(sign(z_j)),  z_j = x R_j
+ *   Sec. 3.2, "The problem":       all z_j are slices of one wide projection x R,
+ *                                  cut into k consecutive tau-vectors
+ *   Sec. 3.2, eq. "hadamard":      R = D_1 H D_2 H D_3 H   (D_i = +-1 diagonals,
+ *                                  H = Hadamard transform), x a row vector, so
+ *                                  each round flips signs first and transforms second
+ *   Sec. 3.1, eq. "optimal_index": one row per table (the arg-max row = the
+ *                                  sign pattern itself)
+ *
+ * Readings where the paper is silent (all listed in the design notes):
+ *   - H is the Sylvester (natural-order) Walsh-Hadamard matrix scaled by
+ *     d_pad^(-1/2); it is applied as the textbook in-place butterfly with
+ *     ascending stride 1, 2, 4, ... in fp32, round-to-nearest, no fused ops.
+ *   - d that is not a power of two is zero-padded at the tail to
+ *     d_pad = next power of two; when k*tau > d_pad, P = ceil(k*tau/d_pad)
+ *     independent projections (each with its own sign diagonals) are
+ *     concatenated (this is the rule the paper's FLOP tables imply).
+ *   - bit b of code j is [ z[j*tau + b] >= 0 ]  (+1 <-> 1, little-endian);
+ *     +0 and -0 both give 1.
+ *   - codes are 0-based, in [0, 2^tau).
+ *
+ * Parity pins (tests/test_oracle_*.py): dense Sylvester matrix from
+ * scipy.linalg.hadamard, orthonormality, involution, closed-form inputs,
+ * the arg-max form of the hash by brute force over all 2^tau sign rows,
+ * fp64 dense recount of every bit, torch embedding_bag for the gather.
+ *
+ * Build: gcc -O2 -std=c11 -ffp-contract=off -fno-fast-math -fopenmp -shared -fPIC
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+enum { ORACLE_OK = 0, ORACLE_E_ARG = -1, ORACLE_E_NOMEM = -2 };
+
+/* host threads the token loops may use (tokens are independent, Sec. 2.1 "point-wise") */
+int oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void oracle_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
+/* smallest power of two >= d (the padded width of one projection) */
+int oracle_d_pad(int d)
+{
+    int p = 1;
+    while (p < d) p <<= 1;
+    return p;
+}
+
+/* number of independent d_pad-wide projections needed for k*tau sign bits */
+int oracle_n_proj(int d, int k, int tau)
+{
+    int d_pad = oracle_d_pad(d);
+    return (int)(((int64_t)k * tau + d_pad - 1) / d_pad);
+}
+
+/* element `i` of a row stored as fp32 or bf16, widened exactly to fp32 */
+static float load_elt(const void *base, int dtype, int64_t i)
+{
+    if (dtype == ORACLE_F32) return ((const float *)base)[i];
+    uint32_t w = (uint32_t)((const uint16_t *)base)[i] << 16; /* bf16 = top half of fp32 */
+    float f;
+    memcpy(&f, &w, sizeof f);
+    return f;
+}
+
+/*
+ * In-place unnormalised Walsh-Hadamard transform of v[0..n), n a power of two,
+ * Sylvester order: out[i] = sum_j (-1)^popcount(i & j) v[j].
+ * Sec. 3.2, eq. "hadamard" ("H is Hadamard transform").
+ */
+void oracle_fwht(float *v, int n)
+{
+    for (int h = 1; h < n; h <<= 1) {
+        for (int b = 0; b < n; b += 2 * h) {
+            for (int j = b; j < b + h; ++j) {
+                float a = v[j];
+                float c = v[j + h];
+                v[j] = a + c;
+                v[j + h] = a - c;
+            }
+        }
+    }
+}
+
+/*
+ * One structured projection of one token, Sec. 3.2 eq. "hadamard":
+ *   v <- pad(x);  for r = 1..R:  v <- (v D_r) H / sqrt(d_pad)
+ * signs_p points at this projection's R diagonals, [R][d_pad] int8 (+1/-1).
+ * z receives the d_pad soft-hash coordinates.
+ */
+static void project_token(const void *x_row, int x_dtype, int d, int d_pad,
+                          const int8_t *signs_p, int n_rounds, float *z)
+{
+    const float scale = (float)(1.0 / sqrt((double)d_pad));
+    for (int i = 0; i < d; ++i) z[i] = load_elt(x_row, x_dtype, i);
+    for (int i = d; i < d_pad; ++i) z[i] = 0.0f;
+    for (int r = 0; r < n_rounds; ++r) {
+        const int8_t *D = signs_p + (int64_t)r * d_pad;
+        for (int i = 0; i < d_pad; ++i)
+            if (D[i] < 0) z[i] = -z[i];
+        oracle_fwht(z, d_pad);
+        for (int i = 0; i < d_pad; ++i) z[i] = z[i] * scale;
+    }
+}
+
+static int check_shape(int64_t n, int d, int k, int tau, int n_rounds)
+{
+    if (n < 0 || d < 1 || k < 1 || tau < 1 || tau > 16 || n_rounds < 1) return ORACLE_E_ARG;
+    return ORACLE_OK;
+}
+
+/*
+ * Soft hash codes z = x R for every token (Sec. 3.1 "soft hash code";
+ * Sec. 3.2 "The problem": one wide projection for all tables).
+ *   x     [n][d]              fp32 or bf16
+ *   signs [P][n_rounds][d_pad] int8
+ *   z     [n][P*d_pad]        fp32 out (projection 0's coordinates first)
+ */
+int oracle_soft_codes(const void *x, int x_dtype, const int8_t *signs, float *z,
+                      int64_t n, int d, int k, int tau, int n_rounds)
+{
+    if (check_shape(n, d, k, tau, n_rounds) || !x || !signs || !z) return ORACLE_E_ARG;
+    const int d_pad = oracle_d_pad(d);
+    const int P = oracle_n_proj(d, k, tau);
+    const size_t esz = x_dtype == ORACLE_F32 ? 4 : 2;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < n; ++t) {
+        const char *row = (const char *)x + (size_t)t * d * esz;
+        for (int p = 0; p < P; ++p)
+            project_token(row, x_dtype, d, d_pad,
+                          signs + (int64_t)p * n_rounds * d_pad, n_rounds,
+                          z + ((int64_t)t * P + p) * d_pad);
+    }
+    return ORACLE_OK;
+}
+
+/*
+ * decimal(sign(z_j)) for one token (Sec. 3.1): table j owns coordinates
+ * [j*tau, (j+1)*tau) of the concatenated projections; coordinate b of z_j is
+ * bit b of the code; bit = 1 when the coordinate is >= 0.
+ */
+static void pack_codes(const float *z_cat, int k, int tau, uint16_t *codes)
+{
+    for (int j = 0; j < k; ++j) {
+        unsigned c = 0;
+        for (int b = 0; b < tau; ++b)
+            if (z_cat[(int64_t)j * tau + b] >= 0.0f) c |= 1u << b;
+        codes[j] = (uint16_t)c;
+    }
+}
+
+/*
+ * Hash step: codes[n][k] (uint16), code = f_j(x) of Sec. 3.1.
+ */
+int oracle_hash(const void *x, int x_dtype, const int8_t *signs, uint16_t *codes,
+                int64_t n, int d, int k, int tau, int n_rounds)
+{
+    if (check_shape(n, d, k, tau, n_rounds) || !x || !signs || !codes) return ORACLE_E_ARG;
+    const int d_pad = oracle_d_pad(d);
+    const int P = oracle_n_proj(d, k, tau);
+    const size_t esz = x_dtype == ORACLE_F32 ? 4 : 2;
+    int err = 0;
+#pragma omp parallel
+    {
+        float *z = (float *)malloc(sizeof(float) * (size_t)P * d_pad);
+        if (!z) {
+#pragma omp atomic write
+            err = 1;
+        }
+#pragma omp barrier
+        if (!err) {
+#pragma omp for schedule(static)
+            for (int64_t t = 0; t < n; ++t) {
+                const char *row = (const char *)x + (size_t)t * d * esz;
+                for (int p = 0; p < P; ++p)
+                    project_token(row, x_dtype, d, d_pad,
+                                  signs + (int64_t)p * n_rounds * d_pad, n_rounds,
+                                  z + (int64_t)p * d_pad);
+                pack_codes(z, k, tau, codes + t * k);
+            }
+        }
+        free(z);
+    }
+    return err ? ORACLE_E_NOMEM : ORACLE_OK;
+}
+
+/*
+ * Gather step, Sec. 3.1 eq. "lookup": y[t] = sum_{j<k} T_j[codes[t][j]].
+ *   tables [k][2^tau][d_out] fp32 or bf16;  y [n][d_out] fp32.
+ *   acc64 != 0: sum in fp64 in table order, round once to fp32 (the reference
+ *               any summation order is judged against);
+ *   acc64 == 0: sum in fp32 sequentially j = 0, 1, ..., k-1.
+ */
+int oracle_gather(const uint16_t *codes, const void *tables, int table_dtype, float *y,
+                  int64_t n, int k, int tau, int d_out, int acc64)
+{
+    if (n < 0 || k < 1 || tau < 1 || tau > 16 || d_out < 1 || !codes || !tables || !y)
+        return ORACLE_E_ARG;
+    const int64_t rows = (int64_t)1 << tau;
+    int bad = 0;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < n; ++t) {
+        for (int c = 0; c < d_out; ++c) {
+            double s64 = 0.0;
+            float s32 = 0.0f;
+            for (int j = 0; j < k; ++j) {
+                int64_t code = codes[t * k + j];
+                if (code >= rows) {
+#pragma omp atomic write
+                    bad = 1;
+                    code = 0;
+                }
+                float e = load_elt(tables, table_dtype, ((int64_t)j * rows + code) * d_out + c);
+                s64 += (double)e;
+                s32 = s32 + e;
+            }
+            y[t * d_out + c] = acc64 ? (float)s64 : s32;
+        }
+    }
+    return bad ? ORACLE_E_ARG : ORACLE_OK;
+}
+
+/*
+ * Whole forward pass: Hash then Gather (Sec. 3.1 "Two main operations").
+ * codes_out may be NULL.
+ */
+int oracle_forward(const void *x, int x_dtype, const int8_t *signs, const void *tables,
+                   int table_dtype, float *y, uint16_t *codes_out, int64_t n, int d, int k,
+                   int tau, int d_out, int n_rounds, int acc64)
+{
+    if (check_shape(n, d, k, tau, n_rounds) || !y || !tables) return ORACLE_E_ARG;
+    uint16_t *codes = codes_out;
+    if (!codes) {
+        codes = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)(n > 0 ? n : 1) * k);
+        if (!codes) return ORACLE_E_NOMEM;
+    }
+    int rc = oracle_hash(x, x_dtype, signs, codes, n, d, k, tau, n_rounds);
+    if (rc == ORACLE_OK)
+        rc = oracle_gather(codes, tables, table_dtype, y, n, k, tau, d_out, acc64);
+    if (!codes_out) free(codes);
+    return rc;
+}
