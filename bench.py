@@ -1,0 +1,156 @@
+#!/usr/bin/env python3
+"""Benchmark of the LookupFFN forward pass (hash + gather) on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input that is
+already resident in HBM: lookupffn_forward = hash kernel + gather kernel.  The default
+workload is the RoBERTa-base-shaped layer the headline metric is quoted on (config 2:
+16384 tokens, d = 768 padded to 1024, 3 hash rounds, k = 96 tables, tau = 8, fp32).
+
+Prints ONE JSON line: tokens/s of the whole pass, the gather kernel's roofline entry
+(algorithmic bytes / average kernel time from HIP events recorded inside the timed
+region, against the 8 TB/s HBM peak) and the CPU oracle's throughput on this host.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from pathlib import Path
+
+ROOT = Path(__file__).resolve().parent
+sys.path.insert(0, str(ROOT))
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4],
+                    help="benchmark configuration (2 = the headline RoBERTa-base-shaped layer)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle timing")
+    return ap.parse_args()
+
+
+def traffic_from_profiles(w) -> float | None:
+    """HBM bytes per gather launch measured with rocprofv3 --pmc, if a summary is committed."""
+    f = ROOT / "profiles" / f"gather_config{w.index}_hbm_traffic.txt"
+    if not f.exists():
+        return None
+    for line in f.read_text().splitlines():
+        if line.startswith("traffic_bytes_per_launch:"):
+            return float(line.split(":", 1)[1])
+    return None
+
+
+def cpu_baseline(w, x, signs, tables, budget_s: float) -> dict:
+    """The CPU oracle as it stands, on all host threads it gets, on the same batch."""
+    import oracle  # only this leg of the bench touches the oracle
+    threads = oracle.max_threads()
+    n = x.shape[0]
+    sample = min(n, 16384)
+    xs = x[:sample]
+    oracle.forward(xs[:256], signs, tables)            # page in
+    reps, t_total = 0, 0.0
+    while reps < 3 or (t_total < budget_s and reps < 1000):
+        t0 = time.perf_counter()
+        oracle.forward(xs, signs, tables, acc64=True)
+        t_total += time.perf_counter() - t0
+        reps += 1
+        if t_total > 3 * budget_s:
+            break
+    return {"value": sample * reps / t_total, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {sample} tokens of the batch, {reps} passes, {t_total:.1f} s, "
+                      f"gcc -O2 -fopenmp, {os.cpu_count()} logical CPUs visible"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the forward pass is token-parallel with replicated tables and "
+              "needs no collective, so this build reports the single-GPU rate only (run with --gpus 1).",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2403_07221_amd import binding as B
+    from paper_2403_07221_amd import cost, synth
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+    B.lib()
+    w = synth.CONFIGS[args.config]
+    x, signs, tables = synth.make_layer(w)
+    xd, sd, td = B.to_device(x), B.to_device(signs), B.to_device(tables)
+    y = torch.empty((w.n_tokens, w.d_out), dtype=torch.float32, device="cuda")
+    ws = torch.empty(B.lookupffn_workspace_bytes(w.n_tokens, w.k), dtype=torch.uint8, device="cuda")
+
+    def step():
+        B.lookupffn_forward(xd, sd, td, y=y, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    B.lookupffn_timing_reset()
+    B.lookupffn_timing_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    hash_ms, hash_n = B.lookupffn_timing_read(0)
+    gather_ms, gather_n = B.lookupffn_timing_read(1)
+    B.lookupffn_timing_enable(False)
+    B.lookupffn_timing_reset()
+    assert hash_n == args.steps and gather_n == args.steps
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_s = w.n_tokens / (ms_per_step * 1e-3)
+
+    xb = 2 if w.x_dtype == "bf16" else 4
+    tb = 2 if w.table_dtype == "bf16" else 4
+    path_bytes = cost.bytes_per_token(w.d, w.k, w.d_out, xb, tb) * w.n_tokens
+    # the gather kernel alone: k table rows + the y row + the k uint16 codes it reads, per token
+    gather_bytes = (w.k * w.d_out * tb + w.d_out * 4 + w.k * 2) * w.n_tokens
+    gather_avg_ms = gather_ms / gather_n
+    achieved = gather_bytes / (gather_avg_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "tokens/sec and achieved GB/s vs HBM peak for LookupFFN forward at d=768",
+        "value": tokens_per_s,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if tb == 4 else "bf16-storage/f32-accumulate",
+        "data": "synthetic",
+        "config": {"workload": w.name, "n_tokens": w.n_tokens, "d": w.d, "d_pad": w.d_pad,
+                   "hash_rounds": w.n_rounds, "k_tables": w.k, "tau": w.tau, "d_out": w.d_out,
+                   "x_dtype": w.x_dtype, "table_dtype": w.table_dtype,
+                   "table_bytes": w.k * w.rows * w.d_out * tb},
+        "roofline": {"kernel": "gather_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_from_profiles(w),
+                     "algorithmic_bytes_per_launch": gather_bytes, "avg_kernel_ms": gather_avg_ms},
+        "kernels_ms": {"hash": hash_ms / hash_n, "gather": gather_avg_ms},
+        "whole_path": {"algorithmic_bytes_per_step": path_bytes,
+                       "effective_GBps": path_bytes / (ms_per_step * 1e-3) / 1e9},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, x, signs, tables, args.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,122 @@
+/*
+ * lookupffn.h -- C ABI of the MI355X (gfx950) LookupFFN inference forward pass.
+ *
+ * The operation (paper notation, h tables called `k` here):
+ *
+ *   Hash    (Sec. 3.1, hyperplane hash; Sec. 3.2, eq. "hadamard"):
+ *           z = x R,  R = D_1 H D_2 H ... D_R H,  D_r = +-1 diagonals, H = Walsh-Hadamard
+ *           transform in Sylvester order scaled by d_pad^(-1/2); x is zero-padded at the
+ *           tail to d_pad = next power of two >= d.  When k*tau > d_pad, P =
+ *           ceil(k*tau/d_pad) independent projections (own diagonals each) are
+ *           concatenated.  Table j owns coordinates [j*tau, (j+1)*tau) of that
+ *           concatenation (Sec. 3.2, "The problem") and
+ *           code_j = sum_b [ z[j*tau+b] >= 0 ] << b     (decimal(sign(z_j)), 0-based).
+ *   Gather  (Sec. 3.1, eq. "lookup" with the top-1 choice of eq. "optimal_index"):
+ *           y = sum_{j<k} tables[j][code_j][:]          (plain sum, no 1/k)
+ *
+ * Conventions for every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller and valid on the
+ *     current HIP device; the library never frees or retains them.
+ *   - Arrays are dense and row-major:
+ *       x      [n_tokens][d]                 fp32 or bf16 (raw 16-bit patterns)
+ *       signs  [P][n_rounds][d_pad]          int8, a negative entry means "flip"
+ *       codes  [n_tokens][k]                 uint16
+ *       tables [k][2^tau][d_out]             fp32 or bf16
+ *       y      [n_tokens][d_out]             fp32
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is enqueued on it and the call returns without synchronising.
+ *   - Return value: 0 on success, a negative lffn_status otherwise.  Arguments are
+ *     validated before the first HIP call, so error paths need no GPU.
+ *     n_tokens == 0 is a successful no-op.  Nothing is printed, nothing aborts.
+ *   - Arithmetic: the hash runs in fp32 (round to nearest, no fused multiply-add,
+ *     butterflies in ascending stride order), bf16 inputs are widened exactly; the
+ *     gather accumulates in fp32 in table order j = 0..k-1.
+ */
+#ifndef LOOKUPFFN_H
+#define LOOKUPFFN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { LFFN_F32 = 0, LFFN_BF16 = 1 } lffn_dtype;
+
+typedef enum {
+    LFFN_OK = 0,
+    LFFN_E_NULL = -1,         /* a required pointer is NULL */
+    LFFN_E_SIZE = -2,         /* n_tokens < 0, d/k/d_out/n_rounds < 1, or a size product overflows */
+    LFFN_E_TAU = -3,          /* tau outside [1, 16] */
+    LFFN_E_DTYPE = -4,        /* dtype is neither LFFN_F32 nor LFFN_BF16 */
+    LFFN_E_ALIGN = -5,        /* tables or y not 16-byte aligned, x/codes not element aligned,
+                                 or d_out not a multiple of 4 (fp32 tables) / 8 (bf16 tables) */
+    LFFN_E_UNSUPPORTED = -6,  /* d_pad above 4096 */
+    LFFN_E_WORKSPACE = -7,    /* caller workspace smaller than lookupffn_workspace_bytes() */
+    LFFN_E_HIP = -8           /* a HIP call failed; see lookupffn_last_hip_error() */
+} lffn_status;
+
+/*
+ * Hash step alone (Sec. 3.1 "Two main operations", (a)): writes codes[n_tokens][k].
+ */
+int lookupffn_hash(const void *x, const int8_t *signs, uint16_t *codes,
+                   int64_t n_tokens, int d, int k, int tau,
+                   int n_rounds, int x_dtype, void *hip_stream);
+
+/*
+ * Gather step alone (Sec. 3.1 "Two main operations", (b), unweighted; eq. "lookup"):
+ * y[t] = sum_j tables[j][codes[t][j] mod 2^tau].  Codes are reduced modulo 2^tau, so no
+ * value of `codes` can make the kernel read outside `tables`.
+ */
+int lookupffn_gather(const uint16_t *codes, const void *tables, float *y,
+                     int64_t n_tokens, int k, int tau, int d_out,
+                     int table_dtype, void *hip_stream);
+
+/*
+ * Whole forward pass: Hash then Gather on the same stream (Sec. 3.1, eq. "lookup").
+ * The codes live in a scratch buffer of lookupffn_workspace_bytes(n_tokens, k) bytes:
+ * pass a device buffer of at least that size as `workspace` (256-byte aligned), or
+ * workspace == NULL to let the library use a per-device buffer of its own that it grows
+ * with hipMalloc when needed (growing synchronises the device; calls that share that
+ * buffer must be ordered on one stream).
+ */
+int lookupffn_forward(const void *x, const int8_t *signs, const void *tables, float *y,
+                      int64_t n_tokens, int d, int k, int tau, int d_out,
+                      int n_rounds, int x_dtype, int table_dtype,
+                      void *workspace, int64_t workspace_bytes, void *hip_stream);
+
+/* Bytes of scratch lookupffn_forward needs for this problem size (0 if n_tokens == 0). */
+int64_t lookupffn_workspace_bytes(int64_t n_tokens, int k);
+
+/* Frees the library-owned workspaces (all devices).  Safe to call when none exist. */
+int lookupffn_release_workspace(void);
+
+/*
+ * Kernel timing for benchmarks.  While enabled, every kernel the library launches is
+ * bracketed by a pair of HIP events recorded on the launch stream.
+ * lookupffn_timing_read synchronises on the recorded events and returns, for
+ * `which` (0 = hash kernel, 1 = gather kernel), the summed elapsed milliseconds and the
+ * number of launches since the last reset.  Not thread-safe; off by default.
+ */
+int lookupffn_timing_enable(int on);
+int lookupffn_timing_reset(void);
+int lookupffn_timing_read(int which, double *total_ms, int64_t *launches);
+
+/*
+ * Launch-shape knobs of the gather kernel, for tuning sweeps (0 = library default):
+ *   "lanes_per_token"  1,2,4,...,64   lanes (16 bytes each) that share one token's row slice
+ *   "xcd_order"        1 / -1         force the XCD-sliced block order on / off
+ * Returns LFFN_E_SIZE for an unknown key or a value outside the documented set.
+ */
+int lookupffn_set_option(const char *key, int value);
+
+const char *lookupffn_strerror(int status);
+/* Text of the last HIP error seen by this thread's most recent failing call ("" if none). */
+const char *lookupffn_last_hip_error(void);
+/* major*10000 + minor*100 + patch */
+int lookupffn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOOKUPFFN_H */

@@ -1,0 +1,205 @@
+"""ctypes binding of the C-ABI library declared in include/lookupffn.h.
+
+Argument marshalling only: every function takes torch CUDA tensors (used for
+device memory and streams), checks dtypes/contiguity, and passes raw device
+pointers to the entry point of the same name.  There is no fallback: if the
+shared library has not been built the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+
+import torch
+
+_LIB_PATH = Path(__file__).resolve().parent / "liblookupffn.so"
+_lib = None
+
+F32, BF16 = 0, 1
+EXPORTS = (
+    "lookupffn_hash", "lookupffn_gather", "lookupffn_forward", "lookupffn_workspace_bytes",
+    "lookupffn_release_workspace", "lookupffn_timing_enable", "lookupffn_timing_reset",
+    "lookupffn_timing_read", "lookupffn_set_option", "lookupffn_strerror",
+    "lookupffn_last_hip_error", "lookupffn_version",
+)
+
+
+class LookupFFNError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"lookupffn status {status}: {text}")
+        self.status = status
+
+
+def lib() -> ctypes.CDLL:
+    """Load liblookupffn.so (built by paper_2403_07221_amd.build); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not _LIB_PATH.exists():
+            raise FileNotFoundError(
+                f"{_LIB_PATH} not found: build it with `python -m paper_2403_07221_amd.build` "
+                "(there is no CPU fallback)")
+        L = ctypes.CDLL(str(_LIB_PATH))
+        vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+        L.lookupffn_hash.argtypes = [vp, vp, vp, i64, ci, ci, ci, ci, ci, vp]
+        L.lookupffn_gather.argtypes = [vp, vp, vp, i64, ci, ci, ci, ci, vp]
+        L.lookupffn_forward.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, ci, ci, vp, i64, vp]
+        L.lookupffn_workspace_bytes.argtypes = [i64, ci]
+        L.lookupffn_workspace_bytes.restype = i64
+        L.lookupffn_timing_enable.argtypes = [ci]
+        L.lookupffn_timing_read.argtypes = [ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+        L.lookupffn_set_option.argtypes = [ctypes.c_char_p, ci]
+        L.lookupffn_strerror.argtypes = [ci]
+        L.lookupffn_strerror.restype = ctypes.c_char_p
+        L.lookupffn_last_hip_error.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(status: int):
+    if status != 0:
+        L = lib()
+        text = L.lookupffn_strerror(status).decode()
+        if status == -8:
+            text += " (" + L.lookupffn_last_hip_error().decode() + ")"
+        raise LookupFFNError(status, text)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"expected float32 or bfloat16, got {t.dtype}")
+
+
+def _dev(t: torch.Tensor, name: str) -> int:
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(t: torch.Tensor) -> int:
+    return torch.cuda.current_stream(t.device).cuda_stream
+
+
+def _pad(d: int) -> int:
+    p = 1
+    while p < d:
+        p <<= 1
+    return p
+
+
+def _check_signs(signs: torch.Tensor, d: int, k: int, tau: int):
+    if signs.dtype != torch.int8 or signs.dim() != 3:
+        raise TypeError("signs must be int8 [P][n_rounds][d_pad]")
+    n_pad = _pad(d)
+    P = -(-k * tau // n_pad)
+    if signs.shape[0] != P or signs.shape[2] != n_pad:
+        raise ValueError(f"signs has shape {tuple(signs.shape)}, expected ({P}, n_rounds, {n_pad})")
+
+
+def lookupffn_hash(x: torch.Tensor, signs: torch.Tensor, k: int, tau: int,
+                   codes: torch.Tensor | None = None) -> torch.Tensor:
+    """codes[n, k] (int16 storage of the uint16 codes) for x[n, d]."""
+    n, d = x.shape
+    _check_signs(signs, d, k, tau)
+    if codes is None:
+        codes = torch.empty((n, k), dtype=torch.int16, device=x.device)
+    assert codes.dtype == torch.int16 and tuple(codes.shape) == (n, k)
+    if n == 0:
+        return codes            # torch gives empty tensors a NULL data pointer; nothing to launch
+    with torch.cuda.device(x.device):
+        _check(lib().lookupffn_hash(_dev(x, "x"), _dev(signs, "signs"), _dev(codes, "codes"), n, d, k, tau,
+                                    signs.shape[1], _dtype_code(x), _stream(x)))
+    return codes
+
+
+def lookupffn_gather(codes: torch.Tensor, tables: torch.Tensor, y: torch.Tensor | None = None) -> torch.Tensor:
+    """y[n, d_out] = sum_j tables[j, codes[:, j], :]; tables[k, 2^tau, d_out] float32 or bfloat16."""
+    n, k = codes.shape
+    k2, rows, d_out = tables.shape
+    tau = rows.bit_length() - 1
+    if k2 != k or (1 << tau) != rows:
+        raise ValueError("tables must be [k, 2^tau, d_out] with k matching codes")
+    assert codes.dtype == torch.int16
+    if y is None:
+        y = torch.empty((n, d_out), dtype=torch.float32, device=tables.device)
+    assert y.dtype == torch.float32 and tuple(y.shape) == (n, d_out)
+    if n == 0:
+        return y
+    with torch.cuda.device(tables.device):
+        _check(lib().lookupffn_gather(_dev(codes, "codes"), _dev(tables, "tables"), _dev(y, "y"), n, k, tau,
+                                      d_out, _dtype_code(tables), _stream(tables)))
+    return y
+
+
+def lookupffn_workspace_bytes(n_tokens: int, k: int) -> int:
+    return lib().lookupffn_workspace_bytes(n_tokens, k)
+
+
+def lookupffn_forward(x: torch.Tensor, signs: torch.Tensor, tables: torch.Tensor,
+                      y: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """Whole forward pass y[n, d_out]; `workspace` is an optional uint8 CUDA tensor for the codes."""
+    n, d = x.shape
+    k, rows, d_out = tables.shape
+    tau = rows.bit_length() - 1
+    if (1 << tau) != rows:
+        raise ValueError("tables must have 2^tau rows")
+    _check_signs(signs, d, k, tau)
+    if y is None:
+        y = torch.empty((n, d_out), dtype=torch.float32, device=x.device)
+    assert y.dtype == torch.float32 and tuple(y.shape) == (n, d_out)
+    if n == 0:
+        return y
+    ws_ptr, ws_bytes = None, 0
+    if workspace is not None:
+        ws_ptr, ws_bytes = _dev(workspace, "workspace"), workspace.numel() * workspace.element_size()
+    with torch.cuda.device(x.device):
+        _check(lib().lookupffn_forward(_dev(x, "x"), _dev(signs, "signs"), _dev(tables, "tables"), _dev(y, "y"),
+                                       n, d, k, tau, d_out, signs.shape[1], _dtype_code(x), _dtype_code(tables),
+                                       ws_ptr, ws_bytes, _stream(x)))
+    return y
+
+
+def lookupffn_release_workspace() -> None:
+    _check(lib().lookupffn_release_workspace())
+
+
+def lookupffn_timing_enable(on: bool) -> None:
+    _check(lib().lookupffn_timing_enable(int(on)))
+
+
+def lookupffn_timing_reset() -> None:
+    _check(lib().lookupffn_timing_reset())
+
+
+def lookupffn_timing_read(which: int) -> tuple[float, int]:
+    """(total milliseconds, launches) of kernel `which` (0 = hash, 1 = gather) since the last reset."""
+    ms, cnt = ctypes.c_double(0), ctypes.c_int64(0)
+    _check(lib().lookupffn_timing_read(which, ctypes.byref(ms), ctypes.byref(cnt)))
+    return ms.value, cnt.value
+
+
+def lookupffn_set_option(key: str, value: int) -> None:
+    _check(lib().lookupffn_set_option(key.encode(), value))
+
+
+def lookupffn_version() -> int:
+    return lib().lookupffn_version()
+
+
+# ---- helpers for moving the synthetic numpy inputs to the GPU (no arithmetic) -------------
+
+def to_device(a, device="cuda:0") -> torch.Tensor:
+    """numpy array -> CUDA tensor; uint16 arrays are raw bf16 bit patterns -> bfloat16 tensor."""
+    import numpy as np
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(a).to(device)
+
+
+def codes_to_numpy(codes: torch.Tensor):
+    import numpy as np
+    return codes.cpu().numpy().view(np.uint16)

@@ -1,0 +1,173 @@
+// Gather step of the LookupFFN forward pass for gfx950:
+//   y[t][:] = sum_{j<k} tables[j][code[t][j]][:]        (Sec. 3.1, eq. "lookup")
+//
+// Work decomposition.  A table row is cut into column slices of LPT lanes x 16
+// bytes (LPT = "lanes per token"); a wavefront handles 64/LPT tokens of one
+// slice: lane = (token within the wave, 16-byte piece within the slice).  Each
+// lane walks the k tables in order, fetches its 16 bytes of the selected row
+// with one dwordx4 load and adds them into fp32 accumulators -- the same
+// sequential fp32 sum per output element as a plain loop over j.
+//
+// Why slices: one slice of all k tables (k * 2^tau * LPT*16 bytes, 3 MiB for
+// k = 96, tau = 8, LPT = 8) fits the 4 MiB L2 of one XCD while a whole table
+// set (72 MiB) does not.  Blocks are numbered so that the eight XCDs (block b
+// runs on XCD b % 8) each sweep all their tokens for one slice before moving
+// to the next one, so after first touch the row fetches are L2 hits instead of
+// trips to the Infinity Cache / HBM.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lffn {
+
+constexpr int kGatherThreads = 256;
+constexpr int kGatherWaves = kGatherThreads / 64;
+constexpr int kXcds = 8;
+
+struct GatherArgs {
+    const uint16_t *codes;  // [n][k]
+    const char *tables;     // [k][rows][d_out] fp32 or bf16
+    float *y;               // [n][d_out]
+    long long n;
+    int k, tau, d_out;
+    int nvec;          // 16-byte pieces per row
+    int n_slices;      // ceil(nvec / LPT)
+    int n_units;       // n_slices * token_splits; a unit = (slice, contiguous range of token blocks)
+    int tb_per_unit;   // token blocks in one unit
+    int ntb;           // token blocks in total; a token block = kGatherWaves * (64/LPT) tokens
+    int xcd_mode;      // 1: block order is XCD-sliced (see above); 0: plain
+    int codes_vec8;    // 1: k % 8 == 0 and codes 16-byte aligned -> codes read 8 at a time
+    uint32_t row_bytes;
+};
+
+template <bool BF16>
+struct Acc {
+    static constexpr int W = BF16 ? 8 : 4;  // elements in 16 bytes
+    float f[W];
+    __device__ __forceinline__ void zero()
+    {
+#pragma unroll
+        for (int i = 0; i < W; ++i) f[i] = 0.0f;
+    }
+    __device__ __forceinline__ void add(const uint4 &r)
+    {
+        if constexpr (BF16) {
+            // a bf16 is the top half of an fp32: widening is a shift / mask, exact
+            f[0] += __uint_as_float(r.x << 16);
+            f[1] += __uint_as_float(r.x & 0xFFFF0000u);
+            f[2] += __uint_as_float(r.y << 16);
+            f[3] += __uint_as_float(r.y & 0xFFFF0000u);
+            f[4] += __uint_as_float(r.z << 16);
+            f[5] += __uint_as_float(r.z & 0xFFFF0000u);
+            f[6] += __uint_as_float(r.w << 16);
+            f[7] += __uint_as_float(r.w & 0xFFFF0000u);
+        } else {
+            f[0] += __uint_as_float(r.x);
+            f[1] += __uint_as_float(r.y);
+            f[2] += __uint_as_float(r.z);
+            f[3] += __uint_as_float(r.w);
+        }
+    }
+};
+
+__device__ __forceinline__ uint32_t code_of(const uint4 &c, int u)
+{
+    const uint32_t w = u < 2 ? c.x : u < 4 ? c.y : u < 6 ? c.z : c.w;
+    return (u & 1) ? (w >> 16) : (w & 0xFFFFu);
+}
+
+template <bool BF16, int LPT>
+__global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a)
+{
+    constexpr int TPW = 64 / LPT;  // tokens per wave
+    const unsigned lane = threadIdx.x & 63u;
+    const unsigned wave = threadIdx.x >> 6;
+
+    // ---- block -> (slice, token block) -------------------------------------------------
+    int unit, tbl;
+    if (a.xcd_mode) {
+        const int xcd = (int)(blockIdx.x % kXcds);
+        const int q = (int)(blockIdx.x / kXcds);
+        unit = (q / a.tb_per_unit) * kXcds + xcd;
+        tbl = q % a.tb_per_unit;
+    } else {
+        unit = (int)(blockIdx.x % (unsigned)a.n_units);
+        tbl = (int)(blockIdx.x / (unsigned)a.n_units);
+    }
+    if (unit >= a.n_units) return;
+    const int slice = unit % a.n_slices;
+    const int tb = (unit / a.n_slices) * a.tb_per_unit + tbl;
+    if (tb >= a.ntb) return;
+
+    const long long t = ((long long)tb * kGatherWaves + wave) * TPW + lane / LPT;
+    const int vec = slice * LPT + (int)(lane % LPT);
+    if (t >= a.n || vec >= a.nvec) return;  // no barrier below: early exit is safe
+
+    const uint16_t *crow = a.codes + t * a.k;
+    const char *tcol = a.tables + (size_t)vec * 16;
+    const uint32_t rmask = (1u << a.tau) - 1u;
+    const uint32_t row_bytes = a.row_bytes;
+    const int k = a.k, tau = a.tau;
+
+    auto row = [&](int j, uint32_t code) -> uint4 {
+        const uint32_t r = ((uint32_t)j << tau) + (code & rmask);
+        return *reinterpret_cast<const uint4 *>(tcol + (unsigned long long)r * row_bytes);
+    };
+
+    Acc<BF16> acc;
+    acc.zero();
+
+    int j0 = 0;
+    if (a.codes_vec8) {
+        const uint4 *c8 = reinterpret_cast<const uint4 *>(crow);
+        const int nch = k >> 3;  // chunks of 8 codes
+        int ch = 0;
+        if (nch >= 2) {
+            uint4 c0 = c8[0], c1 = c8[1];
+            for (; ch + 2 <= nch; ch += 2) {
+                const uint4 u0 = c0, u1 = c1;
+                // fetch the next two code chunks before the row loads of this pair go out
+                const int nx = ch + 2 <= nch - 2 ? ch + 2 : nch - 2;
+                c0 = c8[nx];
+                c1 = c8[nx + 1];
+                uint4 r[16];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) r[u] = row(ch * 8 + u, code_of(u0, u));
+#pragma unroll
+                for (int u = 0; u < 8; ++u) r[8 + u] = row(ch * 8 + 8 + u, code_of(u1, u));
+#pragma unroll
+                for (int u = 0; u < 16; ++u) acc.add(r[u]);
+            }
+        }
+        if (ch < nch) {
+            const uint4 u0 = c8[ch];
+            uint4 r[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) r[u] = row(ch * 8 + u, code_of(u0, u));
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc.add(r[u]);
+            ++ch;
+        }
+        j0 = nch * 8;
+    }
+    for (; j0 + 4 <= k; j0 += 4) {
+        uint4 r[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) r[u] = row(j0 + u, crow[j0 + u]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc.add(r[u]);
+    }
+    for (; j0 < k; ++j0) acc.add(row(j0, crow[j0]));
+
+    // ---- a6: store, streaming (y is written once and not read again here) -------------
+    float *yp = a.y + t * a.d_out + (size_t)vec * Acc<BF16>::W;
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    f4 o0 = {acc.f[0], acc.f[1], acc.f[2], acc.f[3]};
+    __builtin_nontemporal_store(o0, reinterpret_cast<f4 *>(yp));
+    if constexpr (BF16) {
+        f4 o1 = {acc.f[4], acc.f[5], acc.f[6], acc.f[7]};
+        __builtin_nontemporal_store(o1, reinterpret_cast<f4 *>(yp) + 1);
+    }
+}
+
+}  // namespace lffn

@@ -1,0 +1,276 @@
+// Hash step of the LookupFFN forward pass for gfx950 (wave64):
+//   z = x R,  R = D_1 H D_2 H ... (Sec. 3.2, eq. "hadamard"), code_j = decimal(sign(z_j)) (Sec. 3.1).
+//
+// One wavefront owns one token at a time.  Coordinate i of the padded vector
+// lives in lane (i % 64), register (i / 64), so the Walsh-Hadamard butterflies
+// of stride 1..32 are cross-lane exchanges (DPP for 1, 2, 4, 8; the gfx950
+// v_permlane16_swap / v_permlane32_swap for 16, 32) and those of stride >= 64
+// are plain register pairs.  Stages run in ascending stride and every
+// butterfly is (a + c, a - c) with a the lower index, in fp32 without
+// contraction, so each coordinate goes through the same sequence of roundings
+// as the textbook in-place loop and the sign bits come out identical.
+//
+// Sign bits: `v >= 0` per register is a 64-bit lane mask, i.e. 64 consecutive
+// bits of the token's bit string; the masks go to a small per-wave LDS array
+// and lane j then cuts code j = bits [j*tau, (j+1)*tau) out of it.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lffn {
+
+struct HashArgs {
+    const void *x;        // [n][d] fp32 or bf16
+    const int8_t *signs;  // [P][R][N]
+    uint16_t *codes;      // [n][k]
+    long long n;
+    int d, k, tau, n_rounds, P;
+    int x_bf16;
+    float scale;          // (float)(1 / sqrt(N))
+};
+
+constexpr int kHashThreads = 256;
+constexpr int kHashWaves = kHashThreads / 64;
+
+// words of LDS one wave needs for a token's bit string (P*N bits, one spare word, even count)
+__host__ __device__ inline int hash_bit_words(int P, int N)
+{
+    int w = (P * N + 31) / 32 + 1;
+    return (w + 1) & ~1;
+}
+// 32-bit flip words per (projection, round, lane): bit r = "negate register r"
+__host__ __device__ inline int hash_flip_words(int N) { return N > 2048 ? 2 : 1; }
+
+__host__ inline size_t hash_lds_bytes(int P, int R, int N)
+{
+    return sizeof(uint32_t) * ((size_t)P * R * hash_flip_words(N) * 64 + (size_t)kHashWaves * hash_bit_words(P, N));
+}
+
+__device__ __forceinline__ float fxor(float v, uint32_t m) { return __uint_as_float(__float_as_uint(v) ^ m); }
+
+// value of `v` in lane (lane ^ H), H in {1, 2, 4, 8}, by DPP
+template <int H>
+__device__ __forceinline__ float dpp_xor(float v)
+{
+    int i = __float_as_int(v);
+    if constexpr (H == 1) i = __builtin_amdgcn_update_dpp(0, i, 0xB1, 0xF, 0xF, true);        // quad_perm [1,0,3,2]
+    else if constexpr (H == 2) i = __builtin_amdgcn_update_dpp(0, i, 0x4E, 0xF, 0xF, true);   // quad_perm [2,3,0,1]
+    else if constexpr (H == 4) {
+        i = __builtin_amdgcn_update_dpp(0, i, 0x141, 0xF, 0xF, true);                         // row_half_mirror: l -> l^7
+        i = __builtin_amdgcn_update_dpp(0, i, 0x1B, 0xF, 0xF, true);                          // quad_perm [3,2,1,0]: l -> l^3
+    } else {
+        static_assert(H == 8, "DPP exchange covers strides 1, 2, 4, 8");
+        i = __builtin_amdgcn_update_dpp(0, i, 0x128, 0xF, 0xF, true);                         // row_ror:8: l -> l^8
+    }
+    return __int_as_float(i);
+}
+
+// butterfly of stride H (16 or 32 lanes) on two registers at once:
+// swap halves, add/sub, swap back -- no per-lane sign fix-up needed.
+template <int H>
+__device__ __forceinline__ void swap_butterfly(float &a, float &b)
+{
+    uint32_t ua = __float_as_uint(a), ub = __float_as_uint(b);
+    float lo, hi;
+    if constexpr (H == 16) {
+        auto s = __builtin_amdgcn_permlane16_swap(ua, ub, false, false);
+        lo = __uint_as_float(s[0]);
+        hi = __uint_as_float(s[1]);
+    } else {
+        auto s = __builtin_amdgcn_permlane32_swap(ua, ub, false, false);
+        lo = __uint_as_float(s[0]);
+        hi = __uint_as_float(s[1]);
+    }
+    const float sum = lo + hi, dif = lo - hi;
+    if constexpr (H == 16) {
+        auto s = __builtin_amdgcn_permlane16_swap(__float_as_uint(sum), __float_as_uint(dif), false, false);
+        a = __uint_as_float(s[0]);
+        b = __uint_as_float(s[1]);
+    } else {
+        auto s = __builtin_amdgcn_permlane32_swap(__float_as_uint(sum), __float_as_uint(dif), false, false);
+        a = __uint_as_float(s[0]);
+        b = __uint_as_float(s[1]);
+    }
+}
+
+// one cross-lane stage (stride H < 64) on every register
+template <int H, int NREG>
+__device__ __forceinline__ void lane_stage(float (&v)[NREG], unsigned lane)
+{
+    if constexpr ((H == 16 || H == 32) && NREG >= 2) {
+#pragma unroll
+        for (int r = 0; r < NREG; r += 2) swap_butterfly<H>(v[r], v[r + 1]);
+    } else if constexpr (H == 16 || H == 32) {
+        const uint32_t m = (lane & H) ? 0x80000000u : 0u;
+        const int src = (int)((lane ^ H) << 2);
+#pragma unroll
+        for (int r = 0; r < NREG; ++r) {
+            const float p = __int_as_float(__builtin_amdgcn_ds_bpermute(src, __float_as_int(v[r])));
+            v[r] = p + fxor(v[r], m);
+        }
+    } else {
+        // lower lane: self + partner; upper lane: partner - self  (= a - c with a the lower index)
+        const uint32_t m = (lane & H) ? 0x80000000u : 0u;
+#pragma unroll
+        for (int r = 0; r < NREG; ++r) v[r] = dpp_xor<H>(v[r]) + fxor(v[r], m);
+    }
+}
+
+// one in-register stage: register stride HH = stride / 64
+template <int HH, int NREG>
+__device__ __forceinline__ void reg_stage(float (&v)[NREG])
+{
+#pragma unroll
+    for (int r = 0; r < NREG; ++r) {
+        if ((r & HH) == 0) {
+            const float a = v[r], c = v[r + HH];
+            v[r] = a + c;
+            v[r + HH] = a - c;
+        }
+    }
+}
+
+// unnormalised transform of N = 2^LOG2N coordinates, ascending stride
+template <int LOG2N, int NREG>
+__device__ __forceinline__ void fwht_wave(float (&v)[NREG], unsigned lane)
+{
+    if constexpr (LOG2N > 0) lane_stage<1, NREG>(v, lane);
+    if constexpr (LOG2N > 1) lane_stage<2, NREG>(v, lane);
+    if constexpr (LOG2N > 2) lane_stage<4, NREG>(v, lane);
+    if constexpr (LOG2N > 3) lane_stage<8, NREG>(v, lane);
+    if constexpr (LOG2N > 4) lane_stage<16, NREG>(v, lane);
+    if constexpr (LOG2N > 5) lane_stage<32, NREG>(v, lane);
+    if constexpr (LOG2N > 6) reg_stage<1, NREG>(v);
+    if constexpr (LOG2N > 7) reg_stage<2, NREG>(v);
+    if constexpr (LOG2N > 8) reg_stage<4, NREG>(v);
+    if constexpr (LOG2N > 9) reg_stage<8, NREG>(v);
+    if constexpr (LOG2N > 10) reg_stage<16, NREG>(v);
+    if constexpr (LOG2N > 11) reg_stage<32, NREG>(v);
+}
+
+__device__ __forceinline__ void wave_lds_fence()
+{
+    // LDS operations of one wave complete in issue order; this only stops the compiler
+    // from moving LDS accesses across the point.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int LOG2N>
+__global__ __launch_bounds__(kHashThreads) void hash_kernel(HashArgs a)
+{
+    constexpr int N = 1 << LOG2N;
+    constexpr int NREG = N >= 64 ? N / 64 : 1;
+    constexpr int FW = N > 2048 ? 2 : 1;
+    extern __shared__ uint32_t lds[];
+
+    const unsigned tid = threadIdx.x;
+    const unsigned lane = tid & 63u;
+    const unsigned wave = tid >> 6;
+    const int P = a.P, R = a.n_rounds;
+
+    // ---- block prologue: pack the sign diagonals into per-lane flip words ----------------
+    // flip[(p*R + r)*FW + w][lane] bit b  <->  signs[p][r][lane + 64*(32*w + b)] < 0
+    uint32_t *flip = lds;
+    const int n_flip = P * R * FW * 64;
+    for (int idx = (int)tid; idx < n_flip; idx += kHashThreads) {
+        const int l = idx & 63;
+        const int w = (idx >> 6) % FW;
+        const int pr = (idx >> 6) / FW;
+        const int8_t *D = a.signs + (size_t)pr * N;
+        uint32_t bits = 0;
+#pragma unroll 4
+        for (int b = 0; b < 32; ++b) {
+            const int i = l + 64 * (32 * w + b);
+            if (i < N && D[i] < 0) bits |= 1u << b;
+        }
+        flip[idx] = bits;
+    }
+    uint32_t *bitw = lds + n_flip + wave * hash_bit_words(P, N);
+    const int n_bitw = hash_bit_words(P, N);
+    for (int i = (int)lane; i < n_bitw; i += 64) bitw[i] = 0;
+    __syncthreads();
+
+    const long long wave0 = (long long)blockIdx.x * kHashWaves + wave;
+    const long long n_waves = (long long)gridDim.x * kHashWaves;
+    const float scale = a.scale;
+
+    for (long long t = wave0; t < a.n; t += n_waves) {
+        // ---- a1: load the token's row, widen, zero-pad ----------------------------------
+        float xv[NREG];
+#pragma unroll
+        for (int r = 0; r < NREG; ++r) {
+            const int i = (int)lane + 64 * r;
+            float f = 0.0f;
+            if (i < a.d) {
+                if (a.x_bf16)
+                    f = __uint_as_float((uint32_t)((const uint16_t *)a.x)[t * a.d + i] << 16);
+                else
+                    f = ((const float *)a.x)[t * a.d + i];
+            }
+            xv[r] = f;
+        }
+
+        if constexpr (N < 64) {
+            wave_lds_fence();
+            for (int i = (int)lane; i < n_bitw; i += 64) bitw[i] = 0;
+        }
+
+        for (int p = 0; p < P; ++p) {
+            float v[NREG];
+#pragma unroll
+            for (int r = 0; r < NREG; ++r) v[r] = xv[r];
+
+            for (int rd = 0; rd < R; ++rd) {
+                // ---- a2: sign diagonal ---------------------------------------------------
+                const uint32_t *fw = flip + ((p * R + rd) * FW) * 64 + lane;
+                const uint32_t w0 = fw[0];
+                uint32_t w1 = 0;
+                if constexpr (FW == 2) w1 = fw[64];
+#pragma unroll
+                for (int r = 0; r < NREG; ++r) {
+                    const uint32_t w = r < 32 ? w0 : w1;
+                    v[r] = fxor(v[r], ((w >> (r & 31)) & 1u) << 31);
+                }
+                // ---- a3: Walsh-Hadamard transform, then the d_pad^(-1/2) scale -----------
+                fwht_wave<LOG2N, NREG>(v, lane);
+#pragma unroll
+                for (int r = 0; r < NREG; ++r) v[r] = v[r] * scale;
+            }
+
+            // ---- a4: sign bits of this projection into the wave's bit string ------------
+            if constexpr (N >= 64) {
+                // the mask of register r is bits [64r, 64r+64) of this projection; lane 0 stores them
+                unsigned long long m[NREG];
+#pragma unroll
+                for (int r = 0; r < NREG; ++r) m[r] = __builtin_amdgcn_ballot_w64(v[r] >= 0.0f);
+                if (lane == 0) {
+                    unsigned long long *dst = reinterpret_cast<unsigned long long *>(bitw) + p * (N / 64);
+#pragma unroll
+                    for (int r = 0; r < NREG; ++r) dst[r] = m[r];
+                }
+            } else {
+                const unsigned long long m = __builtin_amdgcn_ballot_w64(v[0] >= 0.0f);
+                if (lane == 0) {
+                    const uint32_t keep = (uint32_t)m & (N == 32 ? 0xFFFFFFFFu : ((1u << (N & 31)) - 1u));
+                    const int bit = p * N;
+                    bitw[bit >> 5] |= keep << (bit & 31);
+                }
+            }
+        }
+        wave_lds_fence();
+
+        // ---- a4: code j = bits [j*tau, (j+1)*tau), little-endian ---------------------------
+        const uint32_t cmask = (1u << a.tau) - 1u;
+        for (int j = (int)lane; j < a.k; j += 64) {
+            const unsigned bit = (unsigned)j * (unsigned)a.tau;
+            const unsigned wi = bit >> 5, sh = bit & 31u;
+            const unsigned long long both = ((unsigned long long)bitw[wi + 1] << 32) | bitw[wi];
+            a.codes[t * a.k + j] = (uint16_t)((uint32_t)(both >> sh) & cmask);
+        }
+        wave_lds_fence();
+    }
+}
+
+}  // namespace lffn

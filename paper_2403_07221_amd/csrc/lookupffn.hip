@@ -1,0 +1,415 @@
+// C ABI of the LookupFFN forward pass (declared in include/lookupffn.h): argument
+// validation, launch-shape planning and kernel launches.  All arithmetic of the
+// method is in hash_kernel.hpp and gather_kernel.hpp.
+#include "lookupffn.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "gather_kernel.hpp"
+#include "hash_kernel.hpp"
+
+namespace {
+
+using namespace lffn;
+
+constexpr int kVersion = 100;  // 0.1.0
+constexpr int kMaxLog2N = 12;  // d_pad <= 4096
+
+thread_local std::string g_hip_error;
+
+int hip_fail(hipError_t e, const char *what)
+{
+    g_hip_error = std::string(what) + ": " + hipGetErrorString(e);
+    return LFFN_E_HIP;
+}
+#define LFFN_HIP(call)                                       \
+    do {                                                     \
+        hipError_t e_ = (call);                              \
+        if (e_ != hipSuccess) return hip_fail(e_, #call);    \
+    } while (0)
+
+int log2_pad(int d)
+{
+    int l = 0;
+    while ((1 << l) < d) ++l;
+    return l;
+}
+
+bool dtype_ok(int t) { return t == LFFN_F32 || t == LFFN_BF16; }
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// ---------------------------------------------------------------- options
+struct Options {
+    int lanes_per_token = 0;  // 0 = default
+    int xcd_order = 0;        // 0 = default, 1 = on, -1 = off
+} g_opt;
+
+// ---------------------------------------------------------------- timing
+struct Timing {
+    bool on = false;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> ev[2];
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> pool;
+} g_tm;
+
+struct TimedLaunch {
+    int which;
+    hipStream_t s;
+    hipEvent_t a = nullptr, b = nullptr;
+    bool ok = true;
+    TimedLaunch(int which_, hipStream_t s_) : which(which_), s(s_)
+    {
+        if (!g_tm.on) return;
+        if (!g_tm.pool.empty()) {
+            a = g_tm.pool.back().first;
+            b = g_tm.pool.back().second;
+            g_tm.pool.pop_back();
+        } else if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
+            ok = false;
+            return;
+        }
+        ok = hipEventRecord(a, s) == hipSuccess;
+    }
+    void done()
+    {
+        if (!g_tm.on || !a || !b) return;
+        (void)hipEventRecord(b, s);
+        g_tm.ev[which].emplace_back(a, b);
+    }
+};
+
+// ---------------------------------------------------------------- library-owned workspace
+struct Workspace {
+    void *ptr = nullptr;
+    size_t bytes = 0;
+};
+std::mutex g_ws_mu;
+std::map<int, Workspace> g_ws;
+
+int own_workspace(size_t need, void **out)
+{
+    int dev = 0;
+    LFFN_HIP(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lk(g_ws_mu);
+    Workspace &w = g_ws[dev];
+    if (w.bytes < need) {
+        if (w.ptr) {
+            LFFN_HIP(hipDeviceSynchronize());
+            LFFN_HIP(hipFree(w.ptr));
+            w.ptr = nullptr;
+            w.bytes = 0;
+        }
+        size_t sz = (need + (size_t(1) << 20) - 1) & ~((size_t(1) << 20) - 1);
+        LFFN_HIP(hipMalloc(&w.ptr, sz));
+        w.bytes = sz;
+    }
+    *out = w.ptr;
+    return LFFN_OK;
+}
+
+// ---------------------------------------------------------------- validation
+int check_hash(const void *x, const int8_t *signs, const uint16_t *codes, int64_t n, int d, int k,
+               int tau, int n_rounds, int x_dtype)
+{
+    if (!x || !signs || !codes) return LFFN_E_NULL;
+    if (n < 0 || d < 1 || k < 1 || n_rounds < 1) return LFFN_E_SIZE;
+    if (tau < 1 || tau > 16) return LFFN_E_TAU;
+    if (!dtype_ok(x_dtype)) return LFFN_E_DTYPE;
+    if (k > (1 << 20) || n > (int64_t(1) << 40) || n_rounds > 64) return LFFN_E_SIZE;
+    if (log2_pad(d) > kMaxLog2N || d > (1 << kMaxLog2N)) return LFFN_E_UNSUPPORTED;
+    const int N = 1 << log2_pad(d);
+    const int64_t P = ((int64_t)k * tau + N - 1) / N;
+    if (P > 4096) return LFFN_E_SIZE;
+    if (hash_lds_bytes((int)P, n_rounds, N) > 64 * 1024) return LFFN_E_UNSUPPORTED;
+    if (!aligned(x, x_dtype == LFFN_F32 ? 4 : 2) || !aligned(codes, 2)) return LFFN_E_ALIGN;
+    return LFFN_OK;
+}
+
+int check_gather(const uint16_t *codes, const void *tables, const float *y, int64_t n, int k, int tau,
+                 int d_out, int table_dtype)
+{
+    if (!codes || !tables || !y) return LFFN_E_NULL;
+    if (n < 0 || k < 1 || d_out < 1) return LFFN_E_SIZE;
+    if (tau < 1 || tau > 16) return LFFN_E_TAU;
+    if (!dtype_ok(table_dtype)) return LFFN_E_DTYPE;
+    if (k > (1 << 20) || n > (int64_t(1) << 40) || d_out > (1 << 24)) return LFFN_E_SIZE;
+    const int w = table_dtype == LFFN_F32 ? 4 : 8;
+    if (d_out % w != 0) return LFFN_E_ALIGN;
+    if (!aligned(tables, 16) || !aligned(y, 16) || !aligned(codes, 2)) return LFFN_E_ALIGN;
+    // row index (j << tau) + code must fit 32 bits
+    if (((int64_t)k << tau) > (int64_t(1) << 31)) return LFFN_E_SIZE;
+    return LFFN_OK;
+}
+
+// ---------------------------------------------------------------- launches
+template <int L>
+void launch_hash_t(const HashArgs &a, dim3 grid, size_t lds, hipStream_t s)
+{
+    hipLaunchKernelGGL(hash_kernel<L>, grid, dim3(kHashThreads), lds, s, a);
+}
+
+int launch_hash(const void *x, const int8_t *signs, uint16_t *codes, int64_t n, int d, int k, int tau,
+                int n_rounds, int x_dtype, hipStream_t s)
+{
+    const int L = log2_pad(d);
+    const int N = 1 << L;
+    HashArgs a;
+    a.x = x;
+    a.signs = signs;
+    a.codes = codes;
+    a.n = n;
+    a.d = d;
+    a.k = k;
+    a.tau = tau;
+    a.n_rounds = n_rounds;
+    a.P = (int)(((int64_t)k * tau + N - 1) / N);
+    a.x_bf16 = x_dtype == LFFN_BF16;
+    a.scale = (float)(1.0 / std::sqrt((double)N));
+    const size_t lds = hash_lds_bytes(a.P, n_rounds, N);
+    int64_t blocks = (n + kHashWaves - 1) / kHashWaves;
+    if (blocks > 2048) blocks = 2048;
+    const dim3 grid((unsigned)blocks);
+    TimedLaunch tl(0, s);
+    switch (L) {
+#define LFFN_CASE(l) case l: launch_hash_t<l>(a, grid, lds, s); break;
+        LFFN_CASE(0) LFFN_CASE(1) LFFN_CASE(2) LFFN_CASE(3) LFFN_CASE(4) LFFN_CASE(5) LFFN_CASE(6)
+        LFFN_CASE(7) LFFN_CASE(8) LFFN_CASE(9) LFFN_CASE(10) LFFN_CASE(11) LFFN_CASE(12)
+#undef LFFN_CASE
+        default: return LFFN_E_UNSUPPORTED;
+    }
+    LFFN_HIP(hipGetLastError());
+    tl.done();
+    return LFFN_OK;
+}
+
+template <bool BF16, int LPT>
+void launch_gather_t(const GatherArgs &a, dim3 grid, hipStream_t s)
+{
+    hipLaunchKernelGGL((gather_kernel<BF16, LPT>), grid, dim3(kGatherThreads), 0, s, a);
+}
+
+template <bool BF16>
+int launch_gather_lpt(int lpt, const GatherArgs &a, dim3 grid, hipStream_t s)
+{
+    switch (lpt) {
+        case 1: launch_gather_t<BF16, 1>(a, grid, s); break;
+        case 2: launch_gather_t<BF16, 2>(a, grid, s); break;
+        case 4: launch_gather_t<BF16, 4>(a, grid, s); break;
+        case 8: launch_gather_t<BF16, 8>(a, grid, s); break;
+        case 16: launch_gather_t<BF16, 16>(a, grid, s); break;
+        case 32: launch_gather_t<BF16, 32>(a, grid, s); break;
+        case 64: launch_gather_t<BF16, 64>(a, grid, s); break;
+        default: return LFFN_E_UNSUPPORTED;
+    }
+    return LFFN_OK;
+}
+
+int gcd(int a, int b) { return b ? gcd(b, a % b) : a; }
+
+int launch_gather(const uint16_t *codes, const void *tables, float *y, int64_t n, int k, int tau,
+                  int d_out, int table_dtype, hipStream_t s)
+{
+    const bool bf16 = table_dtype == LFFN_BF16;
+    const int esz = bf16 ? 2 : 4;
+    GatherArgs a;
+    a.codes = codes;
+    a.tables = static_cast<const char *>(tables);
+    a.y = y;
+    a.n = n;
+    a.k = k;
+    a.tau = tau;
+    a.d_out = d_out;
+    a.row_bytes = (uint32_t)d_out * esz;
+    a.nvec = (int)(a.row_bytes / 16);
+    a.codes_vec8 = (k % 8 == 0) && aligned(codes, 16);
+
+    int lpt = g_opt.lanes_per_token;
+    if (lpt == 0) {
+        lpt = 8;  // 128-byte slices: one L2 line per (token, table)
+        while (lpt > 1 && lpt / 2 >= a.nvec) lpt /= 2;
+    }
+    const int tpw = 64 / lpt;
+    a.n_slices = (a.nvec + lpt - 1) / lpt;
+    const int64_t ntb = (n + (int64_t)kGatherWaves * tpw - 1) / ((int64_t)kGatherWaves * tpw);
+    if (ntb > (int64_t(1) << 30)) return LFFN_E_SIZE;
+    a.ntb = (int)ntb;
+
+    const double table_bytes = (double)k * (double)(1u << tau) * a.row_bytes;
+    bool xcd = table_bytes > 4.0 * 1024 * 1024 && ntb >= 64;
+    if (g_opt.xcd_order == 1) xcd = true;
+    if (g_opt.xcd_order == -1) xcd = false;
+    a.xcd_mode = xcd;
+    int64_t blocks;
+    if (xcd) {
+        // split the token range so that the number of units is a multiple of the XCD count
+        const int splits = kXcds / gcd(a.n_slices, kXcds);
+        a.tb_per_unit = (int)((ntb + splits - 1) / splits);
+        a.n_units = a.n_slices * splits;
+        blocks = (int64_t)(a.n_units / kXcds) * kXcds * a.tb_per_unit;
+    } else {
+        a.tb_per_unit = (int)ntb;
+        a.n_units = a.n_slices;
+        blocks = (int64_t)a.n_units * ntb;
+    }
+    if (blocks > 0x7FFFFFFFLL) return LFFN_E_SIZE;
+    const dim3 grid((unsigned)blocks);
+    TimedLaunch tl(1, s);
+    int rc = bf16 ? launch_gather_lpt<true>(lpt, a, grid, s) : launch_gather_lpt<false>(lpt, a, grid, s);
+    if (rc != LFFN_OK) return rc;
+    LFFN_HIP(hipGetLastError());
+    tl.done();
+    return LFFN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int lookupffn_hash(const void *x, const int8_t *signs, uint16_t *codes, int64_t n_tokens, int d, int k,
+                   int tau, int n_rounds, int x_dtype, void *hip_stream)
+{
+    int rc = check_hash(x, signs, codes, n_tokens, d, k, tau, n_rounds, x_dtype);
+    if (rc != LFFN_OK || n_tokens == 0) return rc;
+    return launch_hash(x, signs, codes, n_tokens, d, k, tau, n_rounds, x_dtype,
+                       static_cast<hipStream_t>(hip_stream));
+}
+
+int lookupffn_gather(const uint16_t *codes, const void *tables, float *y, int64_t n_tokens, int k, int tau,
+                     int d_out, int table_dtype, void *hip_stream)
+{
+    int rc = check_gather(codes, tables, y, n_tokens, k, tau, d_out, table_dtype);
+    if (rc != LFFN_OK || n_tokens == 0) return rc;
+    return launch_gather(codes, tables, y, n_tokens, k, tau, d_out, table_dtype,
+                         static_cast<hipStream_t>(hip_stream));
+}
+
+int64_t lookupffn_workspace_bytes(int64_t n_tokens, int k)
+{
+    if (n_tokens <= 0 || k < 1) return 0;
+    const int64_t b = n_tokens * k * (int64_t)sizeof(uint16_t);
+    return (b + 255) & ~int64_t(255);
+}
+
+int lookupffn_forward(const void *x, const int8_t *signs, const void *tables, float *y, int64_t n_tokens,
+                      int d, int k, int tau, int d_out, int n_rounds, int x_dtype, int table_dtype,
+                      void *workspace, int64_t workspace_bytes, void *hip_stream)
+{
+    // the codes pointer is checked for NULL by the two step checks; give them a stand-in
+    // until the real buffer is known
+    const uint16_t *stand_in = reinterpret_cast<const uint16_t *>(uintptr_t(256));
+    int rc = check_hash(x, signs, stand_in, n_tokens, d, k, tau, n_rounds, x_dtype);
+    if (rc != LFFN_OK) return rc;
+    rc = check_gather(stand_in, tables, y, n_tokens, k, tau, d_out, table_dtype);
+    if (rc != LFFN_OK) return rc;
+    const int64_t need = lookupffn_workspace_bytes(n_tokens, k);
+    if (workspace) {
+        if (workspace_bytes < need) return LFFN_E_WORKSPACE;
+        if (!aligned(workspace, 256)) return LFFN_E_ALIGN;
+    }
+    if (n_tokens == 0) return LFFN_OK;
+    void *ws = workspace;
+    if (!ws) {
+        rc = own_workspace((size_t)need, &ws);
+        if (rc != LFFN_OK) return rc;
+    }
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    uint16_t *codes = static_cast<uint16_t *>(ws);
+    rc = launch_hash(x, signs, codes, n_tokens, d, k, tau, n_rounds, x_dtype, s);
+    if (rc != LFFN_OK) return rc;
+    return launch_gather(codes, tables, y, n_tokens, k, tau, d_out, table_dtype, s);
+}
+
+int lookupffn_release_workspace(void)
+{
+    std::lock_guard<std::mutex> lk(g_ws_mu);
+    int rc = LFFN_OK;
+    for (auto &kv : g_ws) {
+        if (!kv.second.ptr) continue;
+        int cur = 0;
+        if (hipGetDevice(&cur) != hipSuccess || hipSetDevice(kv.first) != hipSuccess ||
+            hipDeviceSynchronize() != hipSuccess || hipFree(kv.second.ptr) != hipSuccess)
+            rc = LFFN_E_HIP;
+        (void)hipSetDevice(cur);
+        kv.second = Workspace();
+    }
+    g_ws.clear();
+    return rc;
+}
+
+int lookupffn_timing_enable(int on)
+{
+    g_tm.on = on != 0;
+    return LFFN_OK;
+}
+
+int lookupffn_timing_reset(void)
+{
+    for (auto &v : g_tm.ev) {
+        for (auto &p : v) {
+            (void)hipEventSynchronize(p.second);
+            g_tm.pool.push_back(p);
+        }
+        v.clear();
+    }
+    return LFFN_OK;
+}
+
+int lookupffn_timing_read(int which, double *total_ms, int64_t *launches)
+{
+    if (which < 0 || which > 1) return LFFN_E_SIZE;
+    if (!total_ms || !launches) return LFFN_E_NULL;
+    double sum = 0.0;
+    for (auto &p : g_tm.ev[which]) {
+        LFFN_HIP(hipEventSynchronize(p.second));
+        float ms = 0.0f;
+        LFFN_HIP(hipEventElapsedTime(&ms, p.first, p.second));
+        sum += ms;
+    }
+    *total_ms = sum;
+    *launches = (int64_t)g_tm.ev[which].size();
+    return LFFN_OK;
+}
+
+int lookupffn_set_option(const char *key, int value)
+{
+    if (!key) return LFFN_E_NULL;
+    if (!std::strcmp(key, "lanes_per_token")) {
+        if (value != 0 && (value < 1 || value > 64 || (value & (value - 1)))) return LFFN_E_SIZE;
+        g_opt.lanes_per_token = value;
+        return LFFN_OK;
+    }
+    if (!std::strcmp(key, "xcd_order")) {
+        if (value < -1 || value > 1) return LFFN_E_SIZE;
+        g_opt.xcd_order = value;
+        return LFFN_OK;
+    }
+    return LFFN_E_SIZE;
+}
+
+const char *lookupffn_strerror(int status)
+{
+    switch (status) {
+        case LFFN_OK: return "success";
+        case LFFN_E_NULL: return "a required pointer is NULL";
+        case LFFN_E_SIZE: return "a size argument is out of range";
+        case LFFN_E_TAU: return "tau must be in [1, 16]";
+        case LFFN_E_DTYPE: return "unknown dtype";
+        case LFFN_E_ALIGN: return "pointer alignment or d_out granularity not met";
+        case LFFN_E_UNSUPPORTED: return "shape not supported (d_pad above 4096)";
+        case LFFN_E_WORKSPACE: return "workspace too small";
+        case LFFN_E_HIP: return "a HIP call failed";
+        default: return "unknown status";
+    }
+}
+
+const char *lookupffn_last_hip_error(void) { return g_hip_error.c_str(); }
+
+int lookupffn_version(void) { return kVersion; }
+
+}  // extern "C"

@@ -1,0 +1,293 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on identical seeded inputs.
+
+Bars: codes bit-exact; y within max|dy| / rms(y) <= 1e-4 (fp32 tables) or 1e-2 (bf16 tables) of the
+oracle's fp64-accumulated reference.  The kernels add in table order in fp32, so y is additionally
+required to equal the oracle's fp32 sequential mode bit for bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2403_07221_amd import binding as B
+from paper_2403_07221_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-4
+TOL_BF16 = 1e-2
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    B.lib()                      # fail loudly if the HIP library is not built
+    yield
+    B.lookupffn_set_option("lanes_per_token", 0)
+    B.lookupffn_set_option("xcd_order", 0)
+
+
+def rel_err(y, ref):
+    ref64 = ref.astype(np.float64)
+    rms = np.sqrt(np.mean(ref64 ** 2))
+    return float(np.max(np.abs(y.astype(np.float64) - ref64)) / rms)
+
+
+def gpu_hash(x, signs, k, tau):
+    codes = B.lookupffn_hash(B.to_device(x), B.to_device(signs), k, tau)
+    torch.cuda.synchronize()
+    return B.codes_to_numpy(codes)
+
+
+def gpu_gather(codes, tables):
+    y = B.lookupffn_gather(torch.from_numpy(codes.view(np.int16)).cuda(), B.to_device(tables))
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+def gpu_forward(x, signs, tables, **kw):
+    y = B.lookupffn_forward(B.to_device(x), B.to_device(signs), B.to_device(tables), **kw)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+def assert_codes_equal(got, want):
+    if not np.array_equal(got, want):
+        t, j = np.argwhere(got != want)[0]
+        raise AssertionError(f"{np.count_nonzero(got != want)} codes differ; first at token {t}, table {j}: "
+                             f"gpu {got[t, j]} oracle {want[t, j]}")
+
+
+# ------------------------------------------------------------------ hash
+
+HASH_SHAPES = [
+    # n, d, k, tau, R, x dtype
+    (64, 64, 8, 8, 2, "f32"),        # tiny benchmark shape
+    (1, 64, 8, 8, 2, "f32"),         # a single token
+    (1003, 768, 96, 8, 3, "f32"),    # 768 -> 1024 padding, ragged token count
+    (517, 768, 96, 8, 3, "bf16"),
+    (300, 1024, 128, 10, 3, "f32"),  # two projections, a code straddles them
+    (129, 48, 6, 8, 3, "f32"),       # 48 -> 64, trailing coordinates unused
+    (200, 100, 20, 5, 3, "f32"),     # d_pad = 128: scale is not a power of two
+    (77, 512, 20, 13, 3, "f32"),     # the paper's tau = 13 ablation shape
+    (77, 768, 170, 9, 3, "f32"),     # the paper's RoBERTa-base shape: two projections
+    (50, 2048, 100, 16, 2, "f32"),   # widest code
+    (33, 4096, 300, 11, 1, "f32"),   # largest supported width
+    (40, 2000, 7, 1, 3, "bf16"),     # tau = 1
+    (65, 16, 3, 10, 3, "f32"),       # sub-wavefront width, two projections
+    (65, 32, 9, 7, 2, "f32"),
+    (65, 8, 5, 4, 1, "f32"),         # three 8-wide projections
+    (9, 1, 2, 1, 2, "f32"),          # degenerate width 1
+    (70, 5, 3, 5, 4, "f32"),
+]
+
+
+@pytest.mark.parametrize("n,d,k,tau,R,xdt", HASH_SHAPES)
+def test_hash_codes_bit_exact(n, d, k, tau, R, xdt):
+    print(f"hash n={n} d={d} k={k} tau={tau} R={R} {xdt}", flush=True)
+    w = synth.Workload("t", 7, n, d, R, k, tau, 8, x_dtype=xdt)
+    signs = synth.make_signs(1000 * d + k, w.n_proj, R, w.d_pad)
+    x = synth.make_x(n + d, n, d, xdt)
+    assert_codes_equal(gpu_hash(x, signs, k, tau), oracle.hash_codes(x, signs, k, tau))
+
+
+def test_hash_special_inputs():
+    print("hash special inputs", flush=True)
+    d, k, tau, R = 64, 8, 8, 3
+    x = np.zeros((6, d), np.float32)
+    x[1, 0] = 1                       # e_0
+    x[2, 0] = -1                      # -e_0
+    x[3, :] = 1                       # ones: z = sqrt(n) e_0, exact zeros elsewhere
+    x[4, :] = 1e-41                   # subnormal inputs must not be flushed
+    x[5, ::2] = 3e-39
+    x[5, 1::2] = -2e-39
+    for s in (1, -1, 0):
+        signs = (np.full((1, R, d), s, np.int8) if s else synth.make_signs(5, 1, R, d))
+        assert_codes_equal(gpu_hash(x, signs, k, tau), oracle.hash_codes(x, signs, k, tau))
+    # zero input with an all -1 diagonal yields -0 at coordinate 0: must still count as bit 1
+    got = gpu_hash(x[:1], np.full((1, 1, d), -1, np.int8), k, tau)
+    assert (got == 255).all()
+
+
+def test_hash_large_dynamic_range_inputs():
+    print("hash dynamic range", flush=True)
+    n, d, k, tau, R = 256, 768, 96, 8, 3
+    rng = np.random.default_rng(12)
+    x = (rng.standard_normal((n, d)) * np.exp(rng.uniform(-30, 30, size=(n, 1)))).astype(np.float32)
+    x[rng.random((n, d)) < 0.3] = 0
+    signs = synth.make_signs(3, 1, R, 1024)
+    assert_codes_equal(gpu_hash(x, signs, k, tau), oracle.hash_codes(x, signs, k, tau))
+
+
+# ------------------------------------------------------------------ gather
+
+GATHER_SHAPES = [
+    # n, k, tau, d_out, table dtype
+    (64, 8, 8, 64, "f32"),
+    (1003, 96, 8, 768, "f32"),      # several token blocks, ragged tail
+    (1003, 96, 8, 768, "bf16"),
+    (130, 128, 10, 1024, "f32"),
+    (77, 7, 5, 20, "f32"),          # k not a multiple of 8, ragged last slice
+    (77, 13, 3, 40, "bf16"),
+    (5, 1, 1, 4, "f32"),
+    (2048, 20, 13, 512, "f32"),
+    (300, 170, 9, 768, "bf16"),
+]
+
+
+@pytest.mark.parametrize("n,k,tau,d_out,tdt", GATHER_SHAPES)
+def test_gather_matches_oracle(n, k, tau, d_out, tdt):
+    print(f"gather n={n} k={k} tau={tau} d_out={d_out} {tdt}", flush=True)
+    tables = synth.make_tables(n + k, k, 1 << tau, d_out, tdt)
+    codes = np.random.default_rng(n).integers(0, 1 << tau, size=(n, k)).astype(np.uint16)
+    y = gpu_gather(codes, tables)
+    assert rel_err(y, oracle.gather(codes, tables, acc64=True)) <= (TOL_BF16 if tdt == "bf16" else TOL_F32)
+    assert np.array_equal(y, oracle.gather(codes, tables, acc64=False))
+
+
+@pytest.mark.parametrize("lpt", [1, 2, 4, 8, 16, 32, 64])
+@pytest.mark.parametrize("xcd", [1, -1])
+def test_gather_every_launch_shape(lpt, xcd):
+    print(f"gather launch shape lpt={lpt} xcd={xcd}", flush=True)
+    B.lookupffn_set_option("lanes_per_token", lpt)
+    B.lookupffn_set_option("xcd_order", xcd)
+    try:
+        for tdt, d_out, n in (("f32", 200, 333), ("bf16", 776, 259)):
+            k, tau = 24, 6
+            tables = synth.make_tables(lpt, k, 1 << tau, d_out, tdt)
+            codes = np.random.default_rng(lpt).integers(0, 1 << tau, size=(n, k)).astype(np.uint16)
+            assert np.array_equal(gpu_gather(codes, tables), oracle.gather(codes, tables, acc64=False))
+    finally:
+        B.lookupffn_set_option("lanes_per_token", 0)
+        B.lookupffn_set_option("xcd_order", 0)
+
+
+def test_gather_reduces_codes_modulo_table_size():
+    print("gather out-of-range codes", flush=True)
+    n, k, tau, d_out = 40, 8, 4, 16
+    tables = synth.make_tables(1, k, 16, d_out)
+    codes = np.random.default_rng(0).integers(0, 65536, size=(n, k)).astype(np.uint16)
+    assert np.array_equal(gpu_gather(codes, tables), oracle.gather(codes & 15, tables, acc64=False))
+
+
+def test_gather_unaligned_code_rows_take_the_scalar_path():
+    print("gather codes not 16-byte aligned", flush=True)
+    n, k, tau, d_out = 100, 16, 5, 64
+    tables = synth.make_tables(2, k, 32, d_out)
+    codes = np.random.default_rng(1).integers(0, 32, size=(n, k)).astype(np.uint16)
+    buf = torch.zeros(n * k + 1, dtype=torch.int16, device="cuda")
+    view = buf[1:].view(n, k)
+    view.copy_(torch.from_numpy(codes.view(np.int16)))
+    y = B.lookupffn_gather(view, B.to_device(tables))
+    torch.cuda.synchronize()
+    assert np.array_equal(y.cpu().numpy(), oracle.gather(codes, tables, acc64=False))
+
+
+# ------------------------------------------------------------------ whole forward pass
+
+def check_forward(w, x, signs, tables, sample=None):
+    tol = TOL_BF16 if w.table_dtype == "bf16" else TOL_F32
+    xd, sd, td = B.to_device(x), B.to_device(signs), B.to_device(tables)
+    codes = B.lookupffn_hash(xd, sd, w.k, w.tau)
+    y = B.lookupffn_forward(xd, sd, td)
+    torch.cuda.synchronize()
+    codes, y = B.codes_to_numpy(codes), y.cpu().numpy()
+    assert_codes_equal(codes, oracle.hash_codes(x, signs, w.k, w.tau))
+    idx = np.arange(x.shape[0]) if sample is None else sample
+    ref64, ref_codes = oracle.forward(x[idx], signs, tables, acc64=True, return_codes=True)
+    assert_codes_equal(codes[idx], ref_codes)
+    err = rel_err(y[idx], ref64)
+    print(f"  {w.name}: max|dy|/rms = {err:.3e} on {len(idx)} tokens", flush=True)
+    assert err <= tol
+    assert np.array_equal(y[idx], oracle.forward(x[idx], signs, tables, acc64=False))
+    return y
+
+
+def test_forward_config1_tiny():
+    print("forward C1", flush=True)
+    w = synth.C1
+    x, signs, tables = synth.make_layer(w)
+    y = check_forward(w, x, signs, tables)
+    # a caller-provided workspace gives the same result as the library-owned one, run to run
+    ws = torch.empty(B.lookupffn_workspace_bytes(w.n_tokens, w.k), dtype=torch.uint8, device="cuda")
+    assert np.array_equal(gpu_forward(x, signs, tables, workspace=ws), y)
+    assert np.array_equal(gpu_forward(x, signs, tables), y)
+
+
+def test_forward_config2_full_size():
+    print("forward C2 (16384 tokens, fp32)", flush=True)
+    w = synth.C2
+    x, signs, tables = synth.make_layer(w)
+    check_forward(w, x, signs, tables)
+
+
+def test_forward_config3_full_size_bf16():
+    print("forward C3 (65536 tokens, bf16)", flush=True)
+    w = synth.C3
+    x, signs, tables = synth.make_layer(w)
+    check_forward(w, x, signs, tables, sample=np.arange(0, w.n_tokens, 8))
+
+
+def test_forward_config4_full_size():
+    print("forward C4 (16384 tokens, tau=10, 512 MB of tables)", flush=True)
+    w = synth.C4
+    x, signs, tables = synth.make_layer(w)
+    check_forward(w, x, signs, tables, sample=np.arange(0, w.n_tokens, 4))
+
+
+def test_forward_config5_stacked_layers():
+    print("forward C5 (8 tokens x 12 layers)", flush=True)
+    w = synth.C5
+    layers = [synth.make_layer(w, layer=l, with_x=(l == 0)) for l in range(w.n_layers)]
+    x0 = layers[0][0]
+    dev = [(B.to_device(s), B.to_device(t)) for _, s, t in layers]
+    # teacher-forced: every GPU layer is fed the oracle's input of that layer
+    h = x0
+    for l, (_, signs, tables) in enumerate(layers):
+        y_ref, c_ref = oracle.forward(h, signs, tables, acc64=True, return_codes=True)
+        hd = B.to_device(h)
+        codes = B.codes_to_numpy(B.lookupffn_hash(hd, dev[l][0], w.k, w.tau))
+        y = B.lookupffn_forward(hd, dev[l][0], dev[l][1]).cpu().numpy()
+        assert_codes_equal(codes, c_ref)
+        assert rel_err(y, y_ref) <= TOL_F32
+        h = oracle.forward(h, signs, tables, acc64=False)
+    # free-running chain on the GPU against the oracle's fp32-sequential chain: identical bits
+    g = B.to_device(x0)
+    for l in range(w.n_layers):
+        g = B.lookupffn_forward(g, dev[l][0], dev[l][1])
+    torch.cuda.synchronize()
+    assert np.array_equal(g.cpu().numpy(), h)
+
+
+def test_forward_is_deterministic_and_stream_ordered():
+    print("forward determinism / side stream", flush=True)
+    w = synth.C2.with_tokens(2000)
+    x, signs, tables = synth.make_layer(w, n_tokens=2000)
+    xd, sd, td = B.to_device(x), B.to_device(signs), B.to_device(tables)
+    a = B.lookupffn_forward(xd, sd, td)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        b = B.lookupffn_forward(xd, sd, td)
+    s.synchronize()
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+
+
+def test_empty_batch_and_timing_counters():
+    print("empty batch / timing", flush=True)
+    w = synth.C1
+    x, signs, tables = synth.make_layer(w)
+    xd, sd, td = B.to_device(x), B.to_device(signs), B.to_device(tables)
+    y = B.lookupffn_forward(xd[:0], sd, td)
+    assert y.shape == (0, w.d_out)
+    B.lookupffn_timing_reset()
+    B.lookupffn_timing_enable(True)
+    try:
+        for _ in range(3):
+            B.lookupffn_forward(xd, sd, td)
+        (h_ms, h_n), (g_ms, g_n) = B.lookupffn_timing_read(0), B.lookupffn_timing_read(1)
+    finally:
+        B.lookupffn_timing_enable(False)
+        B.lookupffn_timing_reset()
+    assert h_n == 3 and g_n == 3 and h_ms > 0 and g_ms > 0

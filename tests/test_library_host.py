@@ -1,0 +1,105 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, and rejects bad arguments before touching HIP."""
+import ctypes
+import re
+from pathlib import Path
+
+import pytest
+
+from paper_2403_07221_amd import binding
+
+ROOT = Path(__file__).resolve().parent.parent
+HEADER = (ROOT / "include" / "lookupffn.h").read_text()
+FAKE = 1 << 20          # a non-NULL, 16-byte aligned stand-in for a device pointer (never dereferenced)
+
+
+@pytest.fixture(scope="module")
+def L():
+    return binding.lib()
+
+
+def declared_functions():
+    body = re.sub(r"/\*.*?\*/", "", HEADER, flags=re.S)
+    return sorted(set(re.findall(r"\b(lookupffn_\w+)\s*\(", body)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = declared_functions()
+    assert len(names) >= 12 and sorted(binding.EXPORTS) == names
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_version_and_strerror(L):
+    assert L.lookupffn_version() >= 100
+    assert L.lookupffn_strerror(0).decode() == "success"
+    for s in range(-8, 0):
+        assert L.lookupffn_strerror(s).decode() not in ("", "unknown status")
+    assert L.lookupffn_strerror(-99).decode() == "unknown status"
+
+
+def hash_call(L, x=FAKE, signs=FAKE, codes=FAKE, n=0, d=768, k=96, tau=8, rounds=3, dt=0):
+    return L.lookupffn_hash(x, signs, codes, n, d, k, tau, rounds, dt, None)
+
+
+def gather_call(L, codes=FAKE, tables=FAKE, y=FAKE, n=0, k=96, tau=8, d_out=768, dt=0):
+    return L.lookupffn_gather(codes, tables, y, n, k, tau, d_out, dt, None)
+
+
+def forward_call(L, x=FAKE, signs=FAKE, tables=FAKE, y=FAKE, n=0, d=768, k=96, tau=8, d_out=768, rounds=3,
+                 xdt=0, tdt=0, ws=None, wsb=0):
+    return L.lookupffn_forward(x, signs, tables, y, n, d, k, tau, d_out, rounds, xdt, tdt, ws, wsb, None)
+
+
+def test_empty_batch_is_a_successful_noop(L):
+    assert hash_call(L) == 0 and gather_call(L) == 0 and forward_call(L) == 0
+
+
+def test_hash_argument_errors(L):
+    assert hash_call(L, x=None) == -1 and hash_call(L, signs=None) == -1 and hash_call(L, codes=None) == -1
+    assert hash_call(L, n=-1) == -2 and hash_call(L, d=0) == -2 and hash_call(L, k=0) == -2
+    assert hash_call(L, rounds=0) == -2
+    assert hash_call(L, tau=0) == -3 and hash_call(L, tau=17) == -3
+    assert hash_call(L, dt=2) == -4
+    assert hash_call(L, x=FAKE + 2) == -5 and hash_call(L, x=FAKE + 2, dt=1) == 0
+    assert hash_call(L, codes=FAKE + 1) == -5
+    assert hash_call(L, d=4097) == -6 and hash_call(L, d=4096, k=512) == 0
+
+
+def test_gather_argument_errors(L):
+    assert gather_call(L, codes=None) == -1 and gather_call(L, tables=None) == -1 and gather_call(L, y=None) == -1
+    assert gather_call(L, n=-5) == -2 and gather_call(L, k=0) == -2 and gather_call(L, d_out=0) == -2
+    assert gather_call(L, tau=0) == -3 and gather_call(L, tau=17) == -3
+    assert gather_call(L, dt=7) == -4
+    assert gather_call(L, d_out=770) == -5                    # fp32 rows must be whole 16-byte pieces
+    assert gather_call(L, d_out=772) == 0 and gather_call(L, d_out=772, dt=1) == -5
+    assert gather_call(L, tables=FAKE + 4) == -5 and gather_call(L, y=FAKE + 8) == -5
+
+
+def test_forward_argument_errors(L):
+    assert forward_call(L, x=None) == -1 and forward_call(L, tables=None) == -1 and forward_call(L, y=None) == -1
+    assert forward_call(L, tau=0) == -3 and forward_call(L, xdt=3) == -4 and forward_call(L, tdt=-1) == -4
+    need = L.lookupffn_workspace_bytes(1000, 96)
+    assert need >= 1000 * 96 * 2 and need % 256 == 0
+    assert L.lookupffn_workspace_bytes(0, 96) == 0
+    # a caller workspace that is too small or misaligned is refused before any launch
+    assert forward_call(L, n=1000, ws=FAKE, wsb=need - 1) == -7
+    assert forward_call(L, n=1000, ws=FAKE + 16, wsb=need) == -5
+
+
+def test_options(L):
+    assert L.lookupffn_set_option(b"lanes_per_token", 16) == 0
+    assert L.lookupffn_set_option(b"lanes_per_token", 3) == -2
+    assert L.lookupffn_set_option(b"lanes_per_token", 128) == -2
+    assert L.lookupffn_set_option(b"lanes_per_token", 0) == 0
+    assert L.lookupffn_set_option(b"xcd_order", 2) == -2 and L.lookupffn_set_option(b"xcd_order", 0) == 0
+    assert L.lookupffn_set_option(b"no_such_key", 1) == -2
+    assert L.lookupffn_set_option(None, 1) == -1
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    x = torch.zeros(4, 64)
+    signs = torch.ones(1, 2, 64, dtype=torch.int8)
+    with pytest.raises(ValueError):
+        binding.lookupffn_hash(x, signs, 8, 8, codes=torch.zeros(4, 8, dtype=torch.int16))
