@@ -34,12 +34,15 @@ def parse_args():
                     help="benchmark configuration (2 = the headline RoBERTa-base-shaped layer)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle timing")
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="after the timed region, also run 3 plain device-to-device copies of this many MiB "
+                         "(a kernel of known traffic, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
     return ap.parse_args()
 
 
 def traffic_from_profiles(w) -> float | None:
     """HBM bytes per gather launch measured with rocprofv3 --pmc, if a summary is committed."""
-    f = ROOT / "profiles" / f"gather_config{w.index}_hbm_traffic.txt"
+    f = ROOT / "profiles" / f"gather_config{w.index}_pmc_hbm_traffic.txt"
     if not f.exists():
         return None
     for line in f.read_text().splitlines():
@@ -140,13 +143,20 @@ def main():
                    "hash_rounds": w.n_rounds, "k_tables": w.k, "tau": w.tau, "d_out": w.d_out,
                    "x_dtype": w.x_dtype, "table_dtype": w.table_dtype,
                    "table_bytes": w.k * w.rows * w.d_out * tb},
-        "roofline": {"kernel": "gather_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"kernel": B.lookupffn_last_gather_kernel(), "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_from_profiles(w),
                      "algorithmic_bytes_per_launch": gather_bytes, "avg_kernel_ms": gather_avg_ms},
         "kernels_ms": {"hash": hash_ms / hash_n, "gather": gather_avg_ms},
         "whole_path": {"algorithmic_bytes_per_step": path_bytes,
                        "effective_GBps": path_bytes / (ms_per_step * 1e-3) / 1e9},
     }
+    if args.copy_calibration_mib > 0:
+        src = torch.ones(args.copy_calibration_mib << 18, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["copy_calibration_bytes_each_way"] = src.numel() * 4
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, x, signs, tables, args.cpu_seconds)
     print(json.dumps(out))

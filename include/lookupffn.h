@@ -106,6 +106,8 @@ int lookupffn_timing_read(int which, double *total_ms, int64_t *launches);
  * Launch-shape knobs of the gather kernel, for tuning sweeps (0 = library default):
  *   "lanes_per_token"  1,2,4,...,64   lanes (16 bytes each) that share one token's row slice
  *   "xcd_order"        1 / -1         force the XCD-sliced block order on / off
+ *   "gather_path"      1 / 2          1: always the direct kernel; 2: the LDS-staged kernel
+ *                                     whenever the shape allows it (tau <= 9, k even)
  * Returns LFFN_E_SIZE for an unknown key or a value outside the documented set.
  */
 int lookupffn_set_option(const char *key, int value);
@@ -113,6 +115,9 @@ int lookupffn_set_option(const char *key, int value);
 const char *lookupffn_strerror(int status);
 /* Text of the last HIP error seen by this thread's most recent failing call ("" if none). */
 const char *lookupffn_last_hip_error(void);
+/* Which gather kernel the most recent gather launch used: "gather_kernel" (direct, rows fetched
+ * through L2) or "gather_lds_kernel" (table slices staged in LDS); "" before the first launch. */
+const char *lookupffn_last_gather_kernel(void);
 /* major*10000 + minor*100 + patch */
 int lookupffn_version(void);
 

@@ -20,7 +20,7 @@ EXPORTS = (
     "lookupffn_hash", "lookupffn_gather", "lookupffn_forward", "lookupffn_workspace_bytes",
     "lookupffn_release_workspace", "lookupffn_timing_enable", "lookupffn_timing_reset",
     "lookupffn_timing_read", "lookupffn_set_option", "lookupffn_strerror",
-    "lookupffn_last_hip_error", "lookupffn_version",
+    "lookupffn_last_hip_error", "lookupffn_last_gather_kernel", "lookupffn_version",
 )
 
 
@@ -51,6 +51,7 @@ def lib() -> ctypes.CDLL:
         L.lookupffn_strerror.argtypes = [ci]
         L.lookupffn_strerror.restype = ctypes.c_char_p
         L.lookupffn_last_hip_error.restype = ctypes.c_char_p
+        L.lookupffn_last_gather_kernel.restype = ctypes.c_char_p
         _lib = L
     return _lib
 
@@ -184,6 +185,10 @@ def lookupffn_timing_read(which: int) -> tuple[float, int]:
 
 def lookupffn_set_option(key: str, value: int) -> None:
     _check(lib().lookupffn_set_option(key.encode(), value))
+
+
+def lookupffn_last_gather_kernel() -> str:
+    return lib().lookupffn_last_gather_kernel().decode()
 
 
 def lookupffn_version() -> int:

@@ -49,6 +49,14 @@ struct Acc {
 #pragma unroll
         for (int i = 0; i < W; ++i) f[i] = 0.0f;
     }
+    // Empty asm that "touches" the accumulators: keeps the compiler from sinking the additions
+    // past this point (it otherwise defers them to the loop latch, stretching the live ranges
+    // of every fetched row).
+    __device__ __forceinline__ void pin()
+    {
+        asm volatile("" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]));
+        if constexpr (BF16) asm volatile("" : "+v"(f[4]), "+v"(f[5]), "+v"(f[6]), "+v"(f[7]));
+    }
     __device__ __forceinline__ void add(const uint4 &r)
     {
         if constexpr (BF16) {

@@ -13,6 +13,7 @@
 #include <vector>
 
 #include "gather_kernel.hpp"
+#include "gather_lds_kernel.hpp"
 #include "hash_kernel.hpp"
 
 namespace {
@@ -23,6 +24,7 @@ constexpr int kVersion = 100;  // 0.1.0
 constexpr int kMaxLog2N = 12;  // d_pad <= 4096
 
 thread_local std::string g_hip_error;
+const char *g_last_gather = "";  // name of the gather kernel the most recent launch used
 
 int hip_fail(hipError_t e, const char *what)
 {
@@ -49,6 +51,7 @@ bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) &
 struct Options {
     int lanes_per_token = 0;  // 0 = default
     int xcd_order = 0;        // 0 = default, 1 = on, -1 = off
+    int gather_path = 0;      // 0 = choose, 1 = direct kernel, 2 = LDS-staged kernel (if the shape allows)
 } g_opt;
 
 // ---------------------------------------------------------------- timing
@@ -212,11 +215,144 @@ int launch_gather_lpt(int lpt, const GatherArgs &a, dim3 grid, hipStream_t s)
 
 int gcd(int a, int b) { return b ? gcd(b, a % b) : a; }
 
+// ---- LDS-staged gather -------------------------------------------------------------------
+constexpr int kLdsMinBytes = 84 * 1024;  // more than half of the 160 KB LDS: one workgroup per CU
+
+int device_cus(int *cus)
+{
+    static std::mutex mu;
+    static std::map<int, int> cache;
+    int dev = 0;
+    LFFN_HIP(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lk(mu);
+    auto it = cache.find(dev);
+    if (it == cache.end()) {
+        int n = 0;
+        LFFN_HIP(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev));
+        it = cache.emplace(dev, n).first;
+    }
+    *cus = it->second;
+    return LFFN_OK;
+}
+
+template <bool BF16, int TOK, int FILL>
+int launch_gather_lds_t(const GatherLdsArgs &a, dim3 grid, size_t lds, hipStream_t s)
+{
+    auto kern = gather_lds_kernel<BF16, TOK, FILL>;
+    static std::mutex mu;
+    static std::map<int, size_t> configured;  // device -> LDS bytes the kernel is set up for
+    int dev = 0;
+    LFFN_HIP(hipGetDevice(&dev));
+    {
+        std::lock_guard<std::mutex> lk(mu);
+        if (configured[dev] < lds) {
+            LFFN_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            configured[dev] = lds;
+        }
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(kLdsThreads), lds, s, a);
+    return LFFN_OK;
+}
+
+template <bool BF16, int TOK>
+int launch_gather_lds_fill(int fill, const GatherLdsArgs &a, dim3 grid, size_t lds, hipStream_t s)
+{
+    switch (fill) {
+        case 1: return launch_gather_lds_t<BF16, TOK, 1>(a, grid, lds, s);
+        case 2: return launch_gather_lds_t<BF16, TOK, 2>(a, grid, lds, s);
+        case 4: return launch_gather_lds_t<BF16, TOK, 4>(a, grid, lds, s);
+        default: return LFFN_E_UNSUPPORTED;
+    }
+}
+
+// Largest number of tokens a workgroup gets in one piece, mirroring the kernel's split.
+int64_t lds_tokens_per_block(int64_t n, int n_units, int token_splits, int Bx)
+{
+    const int m = (n_units + kXcds - 1) / kXcds;  // units of the fullest XCD
+    const int64_t unit_tokens = (n + token_splits - 1) / token_splits;
+    if (m >= Bx) return unit_tokens;
+    const int blocks = Bx / m;  // the unit with the fewest workgroups
+    return (unit_tokens + blocks - 1) / blocks;
+}
+
+// Returns LFFN_OK and sets *launched when the LDS-staged kernel was used.
+int try_launch_gather_lds(const uint16_t *codes, const void *tables, float *y, int64_t n, int k, int tau,
+                          int d_out, bool bf16, hipStream_t s, bool *launched)
+{
+    *launched = false;
+    if (g_opt.gather_path == 1) return LFFN_OK;
+    const int rows = 1 << tau;
+    if (tau > 9 || k % 2 != 0 || !aligned(codes, 4)) return LFFN_OK;
+    // the kernel indexes tokens, code bytes of a chunk and bytes inside one table with 32 bits
+    if (n >= (int64_t(1) << 31) || (int64_t)rows * d_out * 4 >= (int64_t(1) << 32) || k > 32768) return LFFN_OK;
+    int cus = 0;
+    int rc = device_cus(&cus);
+    if (rc != LFFN_OK) return rc;
+    if (cus < kXcds || cus % kXcds != 0) return LFFN_OK;
+    GatherLdsArgs a;
+    a.codes = codes;
+    a.tables = static_cast<const char *>(tables);
+    a.y = y;
+    a.n = n;
+    a.k = k;
+    a.tau = tau;
+    a.d_out = d_out;
+    a.row_bytes = (uint32_t)d_out * (bf16 ? 2 : 4);
+    a.nvec = (int)(a.row_bytes / 16);
+    a.n_slices = (a.nvec + 7) / 8;
+    a.token_splits = kXcds / gcd(a.n_slices, kXcds);
+    a.n_units = a.n_slices * a.token_splits;
+    a.blocks_per_xcd = cus / kXcds;
+    const int64_t tpb = lds_tokens_per_block(n, a.n_units, a.token_splits, a.blocks_per_xcd);
+    const int tok_max = bf16 ? 8 : 13;
+    const int64_t nchunks = (tpb + (int64_t)kLdsGroups * tok_max - 1) / ((int64_t)kLdsGroups * tok_max);
+    const int64_t chunk = (tpb + nchunks - 1) / nchunks;
+    // Staging pays only when a chunk re-uses each staged row a few times.  With bf16 rows the
+    // widening doubles the vector-ALU work per byte and the direct kernel measured faster, so
+    // bf16 tables take the staged kernel only on request.
+    if (g_opt.gather_path != 2 && (bf16 || chunk < 2 * (int64_t)rows)) return LFFN_OK;
+    int tok = (int)((chunk + kLdsGroups - 1) / kLdsGroups);
+    const int fill = rows * 8 <= kLdsThreads ? 1 : rows * 8 / kLdsThreads;
+    size_t lds = (size_t)2 * rows * 128;
+    if (lds < (size_t)kLdsMinBytes) lds = kLdsMinBytes;
+    const dim3 grid((unsigned)cus);
+    TimedLaunch tl(1, s);
+#define LFFN_TOK(T)                                                                   \
+    if (tok <= T) {                                                                   \
+        rc = bf16 ? LFFN_E_UNSUPPORTED : launch_gather_lds_fill<false, T>(fill, a, grid, lds, s); \
+        goto done;                                                                    \
+    }
+#define LFFN_TOK_BF(T)                                                                \
+    if (tok <= T) {                                                                   \
+        rc = launch_gather_lds_fill<true, T>(fill, a, grid, lds, s);                  \
+        goto done;                                                                    \
+    }
+    if (bf16) {
+        LFFN_TOK_BF(4) LFFN_TOK_BF(6) LFFN_TOK_BF(8)
+    } else {
+        LFFN_TOK(4) LFFN_TOK(8) LFFN_TOK(12) LFFN_TOK(13)
+    }
+    return LFFN_E_UNSUPPORTED;
+#undef LFFN_TOK
+#undef LFFN_TOK_BF
+done:
+    if (rc != LFFN_OK) return rc;
+    LFFN_HIP(hipGetLastError());
+    tl.done();
+    *launched = true;
+    g_last_gather = "gather_lds_kernel";
+    return LFFN_OK;
+}
+
 int launch_gather(const uint16_t *codes, const void *tables, float *y, int64_t n, int k, int tau,
                   int d_out, int table_dtype, hipStream_t s)
 {
     const bool bf16 = table_dtype == LFFN_BF16;
     const int esz = bf16 ? 2 : 4;
+    bool launched = false;
+    int rc0 = try_launch_gather_lds(codes, tables, y, n, k, tau, d_out, bf16, s, &launched);
+    if (rc0 != LFFN_OK || launched) return rc0;
     GatherArgs a;
     a.codes = codes;
     a.tables = static_cast<const char *>(tables);
@@ -264,6 +400,7 @@ int launch_gather(const uint16_t *codes, const void *tables, float *y, int64_t n
     if (rc != LFFN_OK) return rc;
     LFFN_HIP(hipGetLastError());
     tl.done();
+    g_last_gather = "gather_kernel";
     return LFFN_OK;
 }
 
@@ -384,6 +521,11 @@ int lookupffn_set_option(const char *key, int value)
         g_opt.lanes_per_token = value;
         return LFFN_OK;
     }
+    if (!std::strcmp(key, "gather_path")) {
+        if (value < 0 || value > 2) return LFFN_E_SIZE;
+        g_opt.gather_path = value;
+        return LFFN_OK;
+    }
     if (!std::strcmp(key, "xcd_order")) {
         if (value < -1 || value > 1) return LFFN_E_SIZE;
         g_opt.xcd_order = value;
@@ -409,6 +551,8 @@ const char *lookupffn_strerror(int status)
 }
 
 const char *lookupffn_last_hip_error(void) { return g_hip_error.c_str(); }
+
+const char *lookupffn_last_gather_kernel(void) { return g_last_gather; }
 
 int lookupffn_version(void) { return kVersion; }
 

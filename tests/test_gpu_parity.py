@@ -25,6 +25,7 @@ def _gpu():
     yield
     B.lookupffn_set_option("lanes_per_token", 0)
     B.lookupffn_set_option("xcd_order", 0)
+    B.lookupffn_set_option("gather_path", 0)
 
 
 def rel_err(y, ref):
@@ -162,12 +163,50 @@ def test_gather_every_launch_shape(lpt, xcd):
         B.lookupffn_set_option("xcd_order", 0)
 
 
+LDS_SHAPES = [
+    # n, k, tau, d_out, table dtype          (gather_path = 2 forces the LDS-staged kernel)
+    (1003, 96, 8, 768, "f32"),       # three slices per XCD, ragged chunks
+    (1003, 96, 8, 768, "bf16"),
+    (16384, 32, 8, 768, "f32"),      # the benchmark's split: 11/11/10 workgroups per slice, 13 tokens per lane
+    (5000, 24, 6, 200, "f32"),       # ragged last slice (50 pieces), fewer rows than fill lanes
+    (3000, 10, 9, 520, "bf16"),      # 512 rows: four fill pieces per thread, 128 KB of LDS
+    (130, 2, 1, 4, "f32"),           # a single 16-byte piece per row
+    (120000, 4, 4, 128, "f32"),      # several chunks per workgroup
+    (300, 2, 3, 8192, "f32"),        # as many slice-units as workgroups
+    (200, 2, 2, 16384, "bf16"),      # more slice-units than workgroups
+    (1, 6, 8, 64, "f32"),            # one token
+]
+
+
+@pytest.mark.parametrize("n,k,tau,d_out,tdt", LDS_SHAPES)
+def test_gather_lds_staged_kernel(n, k, tau, d_out, tdt):
+    print(f"gather (LDS-staged) n={n} k={k} tau={tau} d_out={d_out} {tdt}", flush=True)
+    tables = synth.make_tables(n + k, k, 1 << tau, d_out, tdt)
+    codes = np.random.default_rng(n).integers(0, 1 << tau, size=(n, k)).astype(np.uint16)
+    want = oracle.gather(codes, tables, acc64=False)
+    B.lookupffn_set_option("gather_path", 2)
+    try:
+        y_lds = gpu_gather(codes, tables)
+        B.lookupffn_set_option("gather_path", 1)
+        y_direct = gpu_gather(codes, tables)
+    finally:
+        B.lookupffn_set_option("gather_path", 0)
+    assert np.array_equal(y_lds, want)
+    assert np.array_equal(y_direct, want)
+    assert rel_err(y_lds, oracle.gather(codes, tables, acc64=True)) <= (TOL_BF16 if tdt == "bf16" else TOL_F32)
+
+
 def test_gather_reduces_codes_modulo_table_size():
     print("gather out-of-range codes", flush=True)
     n, k, tau, d_out = 40, 8, 4, 16
     tables = synth.make_tables(1, k, 16, d_out)
     codes = np.random.default_rng(0).integers(0, 65536, size=(n, k)).astype(np.uint16)
-    assert np.array_equal(gpu_gather(codes, tables), oracle.gather(codes & 15, tables, acc64=False))
+    for path in (1, 2):
+        B.lookupffn_set_option("gather_path", path)
+        try:
+            assert np.array_equal(gpu_gather(codes, tables), oracle.gather(codes & 15, tables, acc64=False))
+        finally:
+            B.lookupffn_set_option("gather_path", 0)
 
 
 def test_gather_unaligned_code_rows_take_the_scalar_path():
