@@ -107,7 +107,7 @@ int lookupffn_timing_read(int which, double *total_ms, int64_t *launches);
  *   "lanes_per_token"  1,2,4,...,64   lanes (16 bytes each) that share one token's row slice
  *   "xcd_order"        1 / -1         force the XCD-sliced block order on / off
  *   "gather_path"      1 / 2          1: always the direct kernel; 2: the LDS-staged kernel
- *                                     whenever the shape allows it (tau <= 9, k even)
+ *                                     whenever the shape allows it (tau 7 or 8, k even)
  * Returns LFFN_E_SIZE for an unknown key or a value outside the documented set.
  */
 int lookupffn_set_option(const char *key, int value);

@@ -1,17 +1,27 @@
-// LDS-staged gather for small tables (2^tau * 128 bytes * 2 buffers must fit the 160 KB LDS):
+// LDS-staged gather for small tables (tau <= 8):
 //   y[t][:] = sum_{j<k} tables[j][code[t][j]][:]        (Sec. 3.1, eq. "lookup")
 //
 // With tau = 8 a table has only 256 rows, so a batch of thousands of tokens
 // picks every row many times.  A 1024-thread workgroup owns one 128-byte
-// column slice and a chunk of up to 128*TOK tokens.  For each table j in turn
-// it copies the slice of all 2^tau rows (32 KB at tau = 8) into LDS once --
-// double-buffered, table j+1 is in flight while table j is consumed -- and
-// every (token, 16-byte piece) lane then reads its selected row from LDS with
-// one ds_read_b128 (eight consecutive lanes read one contiguous 128-byte row
-// piece: conflict-free) and adds it to its fp32 accumulators.  Each output
-// element is still the sequential fp32 sum over j = 0..k-1, so results equal
-// the direct kernel's bit for bit, while the L2 -> CU traffic drops from one
-// row per (token, table) to one row per (chunk, table, row).
+// column slice and a chunk of up to 128*TOK tokens.  Tables are taken two at a
+// time ("a stage"): the slice of all 2^tau rows of both tables (64 KB at
+// tau = 8) is copied into LDS once by global_load_lds (memory -> LDS without a
+// trip through registers), double-buffered so that stage s+1 streams in while
+// stage s is consumed.  Every (token, 16-byte piece) lane then reads its
+// selected row from LDS with one ds_read_b128 (eight consecutive lanes read one
+// contiguous 128-byte row piece) and adds it to its fp32 accumulators.  Each
+// output element is still the sequential fp32 sum over j = 0..k-1, so results
+// equal the direct kernel's bit for bit, while the L2 -> CU traffic drops from
+// one row per (token, table) to one row per (chunk, table, row).
+//
+// Codes come in the packed layout written by the hash kernel (one 32-bit word
+// per token and stage holding both tables' LDS row offsets, token-contiguous):
+// a wave's code load touches one cache line and needs no address arithmetic
+// beyond an immediate offset.  The vector-memory instructions of a stage (next
+// stage's row copies and codes) are issued a few at a time between the LDS
+// read batches: a wave issues in order, so a burst of them at the top of the
+// stage would hold every wave at the texture-address queue while LDS and the
+// vector ALU sit idle.
 //
 // Work distribution is static and XCD-aware: slice-units are dealt to the
 // eight XCDs round-robin (block b runs on XCD b % 8), and the workgroups of
@@ -21,15 +31,21 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "gather_kernel.hpp"
+#include "hash_kernel.hpp"
 
 namespace lffn {
 
 constexpr int kLdsThreads = 1024;
 constexpr int kLdsGroups = kLdsThreads / 8;  // token groups per workgroup (8 lanes per token)
+constexpr int kLdsTps = 2;                   // tables per stage
+constexpr int kLdsMaxTok = 16;               // token slots per lane the packed padding allows for
 
 struct GatherLdsArgs {
-    const uint16_t *codes;  // [n][k], k % 2 == 0, 4-byte aligned
+    const uint32_t *packed;  // [k/2][n_pad] packed codes (see hash_kernel.hpp)
+    long long n_pad;
     const char *tables;
     float *y;
     long long n;
@@ -42,6 +58,9 @@ struct GatherLdsArgs {
     uint32_t row_bytes;
 };
 
+// bytes of LDS the kernel needs: two buffers of kLdsTps table slices
+__host__ __device__ inline size_t gather_lds_bytes(int tau) { return (size_t)2 * kLdsTps * ((size_t)128 << tau); }
+
 // balanced split of [0, len) into `parts` pieces: start of piece i (32-bit arithmetic only)
 __device__ __forceinline__ uint32_t split_at(uint32_t len, uint32_t parts, uint32_t i)
 {
@@ -49,17 +68,37 @@ __device__ __forceinline__ uint32_t split_at(uint32_t len, uint32_t parts, uint3
     return base * i + (i < rem ? i : rem);
 }
 
-template <bool BF16, int TOK, int FILL>
+// One global_load_lds_dwordx4: every active lane copies 16 bytes from gbase + voff to LDS byte
+// address lds_base + 16 * lane (lds_base and gbase wave-uniform).  Issued through inline asm so
+// that the compiler does not serialise later LDS reads of the *other* buffer behind it; the
+// caller waits with s_waitcnt vmcnt(0) before the barrier that publishes the buffer.
+__device__ __forceinline__ void lds_dma16(const char *gbase, uint32_t voff, uint32_t lds_base)
+{
+    const uint32_t m = __builtin_amdgcn_readfirstlane(lds_base);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 1\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(m), "v"(voff), "s"(gbase)
+                 : "memory");
+}
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// FR = rounds of 128 rows per table slice: 1 (tau = 7) or 2 (tau = 8)
+template <bool BF16, int TOK, int FR>
 __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a)
 {
+    static_assert(TOK <= kLdsMaxTok, "packed-code padding covers 16 token slots");
+    static_assert(FR == 1 || FR == 2, "table slices of 128 or 256 rows");
     extern __shared__ uint4 sbuf[];
     const uint32_t tid = threadIdx.x;
+    const uint32_t wave = tid >> 6;
     const uint32_t g = tid >> 3, q = tid & 7u;
-    const uint32_t rows = 1u << a.tau;
-    const uint32_t bufsz = rows * 8u;  // uint4 elements per buffer
-    const uint32_t rmask = rows - 1u;
-    const uint32_t k = (uint32_t)a.k;
-    const uint32_t n = (uint32_t)a.n;  // the host uses this kernel only for n < 2^31
+    const uint32_t rows = 128u * FR;               // == 1 << a.tau (checked by the host)
+    const uint32_t tbl_bytes = rows * 128u;          // one table slice in LDS
+    const uint32_t buf_bytes = tbl_bytes * kLdsTps;  // one buffer (one stage)
+    const uint32_t n = (uint32_t)a.n;                // the host uses this kernel only for n < 2^31
+    const uint32_t nstages = (uint32_t)a.k / kLdsTps;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)sbuf;  // LDS byte address of the staging area
 
     // ---- which (unit, token range) pairs does this workgroup own? ---------------------
     const uint32_t xcd = blockIdx.x % kXcds;
@@ -96,95 +135,111 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
         const uint32_t vec = slice * 8u + q;
         const bool vec_ok = vec < (uint32_t)a.nvec;
 
-        // fill role of this thread: pieces tid, tid + 1024, ... of the [rows][8] slice;
-        // byte offsets inside one table fit 32 bits (checked by the host)
-        uint32_t foff[FILL];
-        bool fok[FILL];
-#pragma unroll
-        for (int f = 0; f < FILL; ++f) {
-            const uint32_t p = tid + (uint32_t)f * kLdsThreads;
-            const uint32_t prow = p >> 3, pvec = slice * 8u + (p & 7u);
-            fok[f] = p < bufsz && pvec < (uint32_t)a.nvec;
-            foff[f] = fok[f] ? prow * a.row_bytes + pvec * 16u : 0u;
-        }
+        // Fill role of this thread: piece (row g, column piece q) of each group of 128 rows.
+        // Lanes whose piece lies outside the row (ragged last slice) copy piece 0 instead: they
+        // never store a result, and this keeps the copy free of divergent control flow.
+        // Offsets inside one table fit 32 bits.
+        const uint32_t foff = g * a.row_bytes + (vec_ok ? vec : 0u) * 16u;
         const size_t table_stride = (size_t)rows * a.row_bytes;
+        // piece idx = table-in-stage * FR + round, of stage s, into buffer b
+        auto fill_piece = [&](uint32_t s, uint32_t b, int idx) {
+            const uint32_t tb = (uint32_t)idx / FR, f = (uint32_t)idx % FR;
+            const char *tsrc = a.tables + (size_t)(s * kLdsTps + tb) * table_stride +
+                               (size_t)f * kLdsGroups * a.row_bytes;  // uniform
+            lds_dma16(tsrc, foff, lds0 + b * buf_bytes + tb * tbl_bytes + (f * kLdsThreads + wave * 64u) * 16u);
+        };
 
         const uint32_t len = r1 - r0;
         const uint32_t nchunks = (len + kLdsGroups * TOK - 1) / (kLdsGroups * TOK);
         for (uint32_t ch = 0; ch < nchunks; ++ch) {
             const uint32_t c0 = r0 + split_at(len, nchunks, ch), c1 = r0 + split_at(len, nchunks, ch + 1);
-            // Accumulator i belongs to token c0 + i*128 + g.  Tokens past the chunk end are clamped
-            // to its last token for the loads and skipped at the store.
-            const uint32_t kbytes = k * 2u;
-            const uint32_t last_off = (c1 - 1u - c0) * kbytes;
-            const char *cchunk = reinterpret_cast<const char *>(a.codes) + (size_t)c0 * kbytes;  // uniform
-            const uint32_t goff = g * kbytes;
-            auto load_codes = [&](int i, uint32_t j) -> uint32_t {
-                uint32_t off = goff + (uint32_t)i * (kLdsGroups * kbytes);
-                off = off < last_off ? off : last_off;
-                return *reinterpret_cast<const uint32_t *>(cchunk + (off + j * 2u));
+            // Accumulator i belongs to token c0 + i*128 + g.  Slots past the chunk end read the codes
+            // of later tokens or of the zero padding (always a valid row), add them, and store nothing.
+            const uint32_t g4 = g * 4u;
+            auto load_code = [&](uint32_t s, int i, uint32_t(&cr)[TOK]) {
+                const char *base = reinterpret_cast<const char *>(a.packed) + ((size_t)s * a.n_pad + c0) * 4u;  // uniform
+                cr[i] = *reinterpret_cast<const uint32_t *>(base + i * (kLdsGroups * 4) + g4);
             };
 
+            // codes of a stage's two tables per token slot; two sets so that the next stage's codes
+            // load while the current stage is consumed
+            uint32_t crA[TOK], crB[TOK];
             Acc<BF16> acc[TOK];
 #pragma unroll
             for (int i = 0; i < TOK; ++i) acc[i].zero();
 
-            // prologue: table 0 into buffer 0, first two codes of every token
-            uint4 fill[FILL];
+            // LDS byte address of this lane's piece of row 0, per (buffer, table-in-stage)
+            const uint32_t qb = lds0 + q * 16u;
+
+            // One stage: consume buffer b with codes `cr`; meanwhile start stage s+1 (rows -> buffer
+            // b^1, codes -> cr_next), its vector-memory instructions spread over the read batches.
+            auto run_stage = [&](auto more_tag, uint32_t s, uint32_t b, const uint32_t(&cr)[TOK],
+                                 uint32_t(&cr_next)[TOK]) {
+                constexpr bool MORE = decltype(more_tag)::value;
+                constexpr int RB = 2;                        // row reads per batch
+                constexpr int NB = (TOK + RB - 1) / RB;      // batches per table
+                constexpr int NBT = kLdsTps * NB;            // batches per stage
+                constexpr int CPB = (TOK + NBT - 1) / NBT;   // code loads per batch
+                static_assert(NBT >= kLdsTps * FR, "one row-copy instruction per batch");
+                uint4 r[2][RB];
+                auto issue = [&](int bi, uint4(&dst)[RB]) {  // bi = u * NB + batch within table u
+                    const int u = bi / NB, b0 = (bi % NB) * RB;
+                    const uint32_t base = qb + b * buf_bytes + (uint32_t)u * tbl_bytes;
 #pragma unroll
-            for (int f = 0; f < FILL; ++f)
-                fill[f] = fok[f] ? *reinterpret_cast<const uint4 *>(a.tables + foff[f]) : make_uint4(0, 0, 0, 0);
-            uint32_t cr[TOK];  // codes of tables j, j+1 (low, high half)
+                    for (int i = 0; i < RB; ++i)
+                        if (b0 + i < TOK) {
+                            const uint32_t off = u ? (cr[b0 + i] >> 16) : (cr[b0 + i] & 0xFFFFu);
+                            const u32x4 v = *reinterpret_cast<const __attribute__((address_space(3))) u32x4 *>(
+                                (uintptr_t)(base + off));
+                            dst[i] = make_uint4(v.x, v.y, v.z, v.w);
+                        }
+                };
+                auto consume = [&](int bi, const uint4(&src)[RB]) {
+                    const int b0 = (bi % NB) * RB;
 #pragma unroll
-            for (int i = 0; i < TOK; ++i) cr[i] = load_codes(i, 0);
+                    for (int i = 0; i < RB; ++i)
+                        if (b0 + i < TOK) {
+                            acc[b0 + i].add(src[i]);
+                            acc[b0 + i].pin();
+                        }
+                };
+                issue(0, r[0]);
 #pragma unroll
-            for (int f = 0; f < FILL; ++f)
-                if (tid + f * kLdsThreads < bufsz) sbuf[tid + f * kLdsThreads] = fill[f];
+                for (int bi = 0; bi < NBT; ++bi) {
+                    if (bi + 1 < NBT) issue(bi + 1, r[(bi + 1) & 1]);
+                    if constexpr (MORE) {
+                        if (bi < kLdsTps * FR) fill_piece(s + 1, b ^ 1u, bi);
+#pragma unroll
+                        for (int cI = 0; cI < CPB; ++cI)
+                            if (bi * CPB + cI < TOK) load_code(s + 1, bi * CPB + cI, cr_next);
+                    }
+                    consume(bi, r[bi & 1]);
+                }
+                __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): next stage's rows and codes have landed
+                __syncthreads();
+            };
+            using yes = std::integral_constant<bool, true>;
+            using no = std::integral_constant<bool, false>;
+
+            // prologue: stage 0 into buffer 0, its codes
+#pragma unroll
+            for (int idx = 0; idx < kLdsTps * FR; ++idx) fill_piece(0, 0, idx);
+#pragma unroll
+            for (int i = 0; i < TOK; ++i) load_code(0, i, crA);
+            __builtin_amdgcn_s_waitcnt(0x0F70);
             __syncthreads();
 
-            for (uint32_t j = 0; j < k; j += 2) {
-#pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    const uint32_t jj = j + u;
-                    const bool more = jj + 1 < k;
-                    if (more) {
-                        const char *tnext = a.tables + (size_t)(jj + 1) * table_stride;  // uniform
-#pragma unroll
-                        for (int f = 0; f < FILL; ++f)
-                            fill[f] = fok[f] ? *reinterpret_cast<const uint4 *>(tnext + foff[f])
-                                             : make_uint4(0, 0, 0, 0);
-                    }
-                    const uint4 *buf = sbuf + u * bufsz + q;
-                    // LDS reads in batches of RB tokens: bounds the registers held by rows in flight
-                    constexpr int RB = 4;
-#pragma unroll
-                    for (int b0 = 0; b0 < TOK; b0 += RB) {
-                        uint4 r[RB];
-#pragma unroll
-                        for (int i = 0; i < RB; ++i)
-                            if (b0 + i < TOK) {
-                                const uint32_t code = (u ? (cr[b0 + i] >> 16) : (cr[b0 + i] & 0xFFFFu)) & rmask;
-                                r[i] = buf[code * 8u];
-                            }
-#pragma unroll
-                        for (int i = 0; i < RB; ++i)
-                            if (b0 + i < TOK) {
-                                acc[b0 + i].add(r[i]);
-                                acc[b0 + i].pin();
-                            }
-                    }
-                    if (u == 1 && j + 2 < k) {
-#pragma unroll
-                        for (int i = 0; i < TOK; ++i) cr[i] = load_codes(i, j + 2);
-                    }
-                    if (more) {
-                        uint4 *dst = sbuf + (u ^ 1) * bufsz;
-#pragma unroll
-                        for (int f = 0; f < FILL; ++f)
-                            if (tid + f * kLdsThreads < bufsz) dst[tid + f * kLdsThreads] = fill[f];
-                    }
-                    __syncthreads();
-                }
+            // all stages but the last start their successor; buffers and code sets alternate
+            uint32_t s = 0;
+            for (; s + 2 < nstages; s += 2) {
+                run_stage(yes{}, s, 0u, crA, crB);
+                run_stage(yes{}, s + 1, 1u, crB, crA);
+            }
+            if (s + 1 < nstages) {
+                run_stage(yes{}, s, 0u, crA, crB);
+                run_stage(no{}, s + 1, 1u, crB, crA);
+            } else {
+                run_stage(no{}, s, 0u, crA, crB);
             }
 
             if (vec_ok) {

@@ -19,10 +19,20 @@
 
 namespace lffn {
 
+// Layout of the gather kernels' internal "packed" codes (the scratch buffer of the forward
+// pass when the LDS-staged gather is used): packed[s][t], s < k/2, t < n_pad, one 32-bit word
+// holding the LDS byte offsets (code << 7, i.e. code * 128-byte row pieces) of tables 2s (low
+// half) and 2s+1 (high half).  The token axis is padded so that a workgroup may read a full
+// 16 x 128 token window past any token without leaving the buffer; padding entries are zero.
+__host__ __device__ inline long long packed_n_pad(long long n) { return ((n + 127) / 128) * 128 + 16 * 128; }
+constexpr int kPackedShift = 7;
+
 struct HashArgs {
     const void *x;        // [n][d] fp32 or bf16
     const int8_t *signs;  // [P][R][N]
-    uint16_t *codes;      // [n][k]
+    uint16_t *codes;      // [n][k], or NULL when `packed` is written instead
+    uint32_t *packed;     // packed codes (see above), or NULL
+    long long n_pad;      // token stride of `packed`
     long long n;
     int d, k, tau, n_rounds, P;
     int x_bf16;
@@ -263,13 +273,44 @@ __global__ __launch_bounds__(kHashThreads) void hash_kernel(HashArgs a)
 
         // ---- a4: code j = bits [j*tau, (j+1)*tau), little-endian ---------------------------
         const uint32_t cmask = (1u << a.tau) - 1u;
-        for (int j = (int)lane; j < a.k; j += 64) {
-            const unsigned bit = (unsigned)j * (unsigned)a.tau;
+        auto code_at = [&](unsigned j) -> uint32_t {
+            const unsigned bit = j * (unsigned)a.tau;
             const unsigned wi = bit >> 5, sh = bit & 31u;
             const unsigned long long both = ((unsigned long long)bitw[wi + 1] << 32) | bitw[wi];
-            a.codes[t * a.k + j] = (uint16_t)((uint32_t)(both >> sh) & cmask);
+            return (uint32_t)(both >> sh) & cmask;
+        };
+        if (a.packed) {
+            for (int s = (int)lane; s < a.k / 2; s += 64)
+                a.packed[(long long)s * a.n_pad + t] =
+                    (code_at(2u * s) << kPackedShift) | (code_at(2u * s + 1u) << (16 + kPackedShift));
+        } else {
+            for (int j = (int)lane; j < a.k; j += 64) a.codes[t * a.k + j] = (uint16_t)code_at((unsigned)j);
         }
         wave_lds_fence();
+    }
+
+    // zero the token padding of the packed layout
+    if (a.packed) {
+        for (long long t = a.n + wave0; t < a.n_pad; t += n_waves)
+            for (int s = (int)lane; s < a.k / 2; s += 64) a.packed[(long long)s * a.n_pad + t] = 0u;
+    }
+}
+
+// ABI codes [n][k] -> packed layout (for a stand-alone gather call that takes the LDS-staged kernel)
+__global__ __launch_bounds__(256) void repack_codes_kernel(const uint16_t *codes, uint32_t *packed, long long n,
+                                                           long long n_pad, int k, int tau)
+{
+    const long long total = (long long)(k / 2) * n_pad;
+    const uint32_t cmask = (1u << tau) - 1u;
+    for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+         idx += (long long)gridDim.x * blockDim.x) {
+        const long long s = idx / n_pad, t = idx - s * n_pad;
+        uint32_t w = 0u;
+        if (t < n) {
+            const uint32_t pair = *reinterpret_cast<const uint32_t *>(codes + t * k + 2 * s);
+            w = ((pair & cmask) << kPackedShift) | (((pair >> 16) & cmask) << (16 + kPackedShift));
+        }
+        packed[idx] = w;
     }
 }
 

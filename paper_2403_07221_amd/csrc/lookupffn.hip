@@ -157,8 +157,9 @@ void launch_hash_t(const HashArgs &a, dim3 grid, size_t lds, hipStream_t s)
     hipLaunchKernelGGL(hash_kernel<L>, grid, dim3(kHashThreads), lds, s, a);
 }
 
-int launch_hash(const void *x, const int8_t *signs, uint16_t *codes, int64_t n, int d, int k, int tau,
-                int n_rounds, int x_dtype, hipStream_t s)
+// Writes codes[n][k] when `codes` is given, else the packed layout of the LDS-staged gather.
+int launch_hash(const void *x, const int8_t *signs, uint16_t *codes, uint32_t *packed, int64_t n, int d, int k,
+                int tau, int n_rounds, int x_dtype, hipStream_t s)
 {
     const int L = log2_pad(d);
     const int N = 1 << L;
@@ -166,6 +167,8 @@ int launch_hash(const void *x, const int8_t *signs, uint16_t *codes, int64_t n, 
     a.x = x;
     a.signs = signs;
     a.codes = codes;
+    a.packed = codes ? nullptr : packed;
+    a.n_pad = packed_n_pad(n);
     a.n = n;
     a.d = d;
     a.k = k;
@@ -235,10 +238,10 @@ int device_cus(int *cus)
     return LFFN_OK;
 }
 
-template <bool BF16, int TOK, int FILL>
-int launch_gather_lds_t(const GatherLdsArgs &a, dim3 grid, size_t lds, hipStream_t s)
+template <bool BF16, int TOK, int FR>
+int launch_gather_lds_fr(const GatherLdsArgs &a, dim3 grid, size_t lds, hipStream_t s)
 {
-    auto kern = gather_lds_kernel<BF16, TOK, FILL>;
+    auto kern = gather_lds_kernel<BF16, TOK, FR>;
     static std::mutex mu;
     static std::map<int, size_t> configured;  // device -> LDS bytes the kernel is set up for
     int dev = 0;
@@ -256,14 +259,10 @@ int launch_gather_lds_t(const GatherLdsArgs &a, dim3 grid, size_t lds, hipStream
 }
 
 template <bool BF16, int TOK>
-int launch_gather_lds_fill(int fill, const GatherLdsArgs &a, dim3 grid, size_t lds, hipStream_t s)
+int launch_gather_lds_t(const GatherLdsArgs &a, dim3 grid, size_t lds, hipStream_t s)
 {
-    switch (fill) {
-        case 1: return launch_gather_lds_t<BF16, TOK, 1>(a, grid, lds, s);
-        case 2: return launch_gather_lds_t<BF16, TOK, 2>(a, grid, lds, s);
-        case 4: return launch_gather_lds_t<BF16, TOK, 4>(a, grid, lds, s);
-        default: return LFFN_E_UNSUPPORTED;
-    }
+    return a.tau == 8 ? launch_gather_lds_fr<BF16, TOK, 2>(a, grid, lds, s)
+                      : launch_gather_lds_fr<BF16, TOK, 1>(a, grid, lds, s);
 }
 
 // Largest number of tokens a workgroup gets in one piece, mirroring the kernel's split.
@@ -276,25 +275,30 @@ int64_t lds_tokens_per_block(int64_t n, int n_units, int token_splits, int Bx)
     return (unit_tokens + blocks - 1) / blocks;
 }
 
-// Returns LFFN_OK and sets *launched when the LDS-staged kernel was used.
-int try_launch_gather_lds(const uint16_t *codes, const void *tables, float *y, int64_t n, int k, int tau,
-                          int d_out, bool bf16, hipStream_t s, bool *launched)
+// Launch shape of the LDS-staged gather for one problem size (no pointers involved).
+struct LdsPlan {
+    bool use = false;
+    GatherLdsArgs a;
+    int tok = 0;
+    unsigned grid = 0;
+    size_t lds = 0;
+};
+
+int plan_gather_lds(int64_t n, int k, int tau, int d_out, bool bf16, LdsPlan *p)
 {
-    *launched = false;
+    p->use = false;
     if (g_opt.gather_path == 1) return LFFN_OK;
     const int rows = 1 << tau;
-    if (tau > 9 || k % 2 != 0 || !aligned(codes, 4)) return LFFN_OK;
-    // the kernel indexes tokens, code bytes of a chunk and bytes inside one table with 32 bits
-    if (n >= (int64_t(1) << 31) || (int64_t)rows * d_out * 4 >= (int64_t(1) << 32) || k > 32768) return LFFN_OK;
+    if ((tau != 7 && tau != 8) || k % 2 != 0) return LFFN_OK;  // table slices of 128 or 256 rows
+    // the kernel indexes tokens and bytes inside one table with 32 bits
+    if (n >= (int64_t(1) << 31) - 4096 || (int64_t)rows * d_out * 4 >= (int64_t(1) << 32)) return LFFN_OK;
     int cus = 0;
     int rc = device_cus(&cus);
     if (rc != LFFN_OK) return rc;
     if (cus < kXcds || cus % kXcds != 0) return LFFN_OK;
-    GatherLdsArgs a;
-    a.codes = codes;
-    a.tables = static_cast<const char *>(tables);
-    a.y = y;
+    GatherLdsArgs &a = p->a;
     a.n = n;
+    a.n_pad = packed_n_pad(n);
     a.k = k;
     a.tau = tau;
     a.d_out = d_out;
@@ -312,47 +316,48 @@ int try_launch_gather_lds(const uint16_t *codes, const void *tables, float *y, i
     // widening doubles the vector-ALU work per byte and the direct kernel measured faster, so
     // bf16 tables take the staged kernel only on request.
     if (g_opt.gather_path != 2 && (bf16 || chunk < 2 * (int64_t)rows)) return LFFN_OK;
-    int tok = (int)((chunk + kLdsGroups - 1) / kLdsGroups);
-    const int fill = rows * 8 <= kLdsThreads ? 1 : rows * 8 / kLdsThreads;
-    size_t lds = (size_t)2 * rows * 128;
-    if (lds < (size_t)kLdsMinBytes) lds = kLdsMinBytes;
-    const dim3 grid((unsigned)cus);
+    p->tok = (int)((chunk + kLdsGroups - 1) / kLdsGroups);
+    p->lds = gather_lds_bytes(tau);
+    if (p->lds < (size_t)kLdsMinBytes) p->lds = kLdsMinBytes;
+    p->grid = (unsigned)cus;
+    p->use = true;
+    return LFFN_OK;
+}
+
+int launch_gather_lds(const LdsPlan &p, const uint32_t *packed, const void *tables, float *y, bool bf16,
+                      hipStream_t s)
+{
+    GatherLdsArgs a = p.a;
+    a.packed = packed;
+    a.tables = static_cast<const char *>(tables);
+    a.y = y;
+    const dim3 grid(p.grid);
+    int rc = LFFN_E_UNSUPPORTED;
     TimedLaunch tl(1, s);
-#define LFFN_TOK(T)                                                                   \
-    if (tok <= T) {                                                                   \
-        rc = bf16 ? LFFN_E_UNSUPPORTED : launch_gather_lds_fill<false, T>(fill, a, grid, lds, s); \
-        goto done;                                                                    \
-    }
-#define LFFN_TOK_BF(T)                                                                \
-    if (tok <= T) {                                                                   \
-        rc = launch_gather_lds_fill<true, T>(fill, a, grid, lds, s);                  \
-        goto done;                                                                    \
-    }
     if (bf16) {
-        LFFN_TOK_BF(4) LFFN_TOK_BF(6) LFFN_TOK_BF(8)
+        if (p.tok <= 4) rc = launch_gather_lds_t<true, 4>(a, grid, p.lds, s);
+        else if (p.tok <= 6) rc = launch_gather_lds_t<true, 6>(a, grid, p.lds, s);
+        else if (p.tok <= 8) rc = launch_gather_lds_t<true, 8>(a, grid, p.lds, s);
     } else {
-        LFFN_TOK(4) LFFN_TOK(8) LFFN_TOK(12) LFFN_TOK(13)
+        if (p.tok <= 4) rc = launch_gather_lds_t<false, 4>(a, grid, p.lds, s);
+        else if (p.tok <= 8) rc = launch_gather_lds_t<false, 8>(a, grid, p.lds, s);
+        else if (p.tok <= 12) rc = launch_gather_lds_t<false, 12>(a, grid, p.lds, s);
+        else if (p.tok <= 13) rc = launch_gather_lds_t<false, 13>(a, grid, p.lds, s);
     }
-    return LFFN_E_UNSUPPORTED;
-#undef LFFN_TOK
-#undef LFFN_TOK_BF
-done:
     if (rc != LFFN_OK) return rc;
     LFFN_HIP(hipGetLastError());
     tl.done();
-    *launched = true;
     g_last_gather = "gather_lds_kernel";
     return LFFN_OK;
 }
 
-int launch_gather(const uint16_t *codes, const void *tables, float *y, int64_t n, int k, int tau,
-                  int d_out, int table_dtype, hipStream_t s)
+int64_t packed_bytes(int64_t n, int k) { return ((int64_t)(k + 1) / 2) * packed_n_pad(n) * 4; }
+
+int launch_gather_direct(const uint16_t *codes, const void *tables, float *y, int64_t n, int k, int tau,
+                         int d_out, int table_dtype, hipStream_t s)
 {
     const bool bf16 = table_dtype == LFFN_BF16;
     const int esz = bf16 ? 2 : 4;
-    bool launched = false;
-    int rc0 = try_launch_gather_lds(codes, tables, y, n, k, tau, d_out, bf16, s, &launched);
-    if (rc0 != LFFN_OK || launched) return rc0;
     GatherArgs a;
     a.codes = codes;
     a.tables = static_cast<const char *>(tables);
@@ -413,7 +418,7 @@ int lookupffn_hash(const void *x, const int8_t *signs, uint16_t *codes, int64_t 
 {
     int rc = check_hash(x, signs, codes, n_tokens, d, k, tau, n_rounds, x_dtype);
     if (rc != LFFN_OK || n_tokens == 0) return rc;
-    return launch_hash(x, signs, codes, n_tokens, d, k, tau, n_rounds, x_dtype,
+    return launch_hash(x, signs, codes, nullptr, n_tokens, d, k, tau, n_rounds, x_dtype,
                        static_cast<hipStream_t>(hip_stream));
 }
 
@@ -422,14 +427,33 @@ int lookupffn_gather(const uint16_t *codes, const void *tables, float *y, int64_
 {
     int rc = check_gather(codes, tables, y, n_tokens, k, tau, d_out, table_dtype);
     if (rc != LFFN_OK || n_tokens == 0) return rc;
-    return launch_gather(codes, tables, y, n_tokens, k, tau, d_out, table_dtype,
-                         static_cast<hipStream_t>(hip_stream));
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const bool bf16 = table_dtype == LFFN_BF16;
+    LdsPlan plan;
+    rc = plan_gather_lds(n_tokens, k, tau, d_out, bf16, &plan);
+    if (rc != LFFN_OK) return rc;
+    if (plan.use && aligned(codes, 4)) {
+        // the staged kernel reads codes in its packed layout: repack into the library's buffer
+        void *ws = nullptr;
+        rc = own_workspace((size_t)packed_bytes(n_tokens, k), &ws);
+        if (rc != LFFN_OK) return rc;
+        uint32_t *packed = static_cast<uint32_t *>(ws);
+        const int64_t total = (int64_t)(k / 2) * plan.a.n_pad;
+        int64_t blocks = (total + 255) / 256;
+        if (blocks > 4096) blocks = 4096;
+        hipLaunchKernelGGL(repack_codes_kernel, dim3((unsigned)blocks), dim3(256), 0, s, codes, packed,
+                           (long long)n_tokens, (long long)plan.a.n_pad, k, tau);
+        LFFN_HIP(hipGetLastError());
+        return launch_gather_lds(plan, packed, tables, y, bf16, s);
+    }
+    return launch_gather_direct(codes, tables, y, n_tokens, k, tau, d_out, table_dtype, s);
 }
 
 int64_t lookupffn_workspace_bytes(int64_t n_tokens, int k)
 {
     if (n_tokens <= 0 || k < 1) return 0;
-    const int64_t b = n_tokens * k * (int64_t)sizeof(uint16_t);
+    // room for either code layout: [n][k] uint16, or the packed layout with its token padding
+    const int64_t b = packed_bytes(n_tokens, k);
     return (b + 255) & ~int64_t(255);
 }
 
@@ -456,10 +480,20 @@ int lookupffn_forward(const void *x, const int8_t *signs, const void *tables, fl
         if (rc != LFFN_OK) return rc;
     }
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    uint16_t *codes = static_cast<uint16_t *>(ws);
-    rc = launch_hash(x, signs, codes, n_tokens, d, k, tau, n_rounds, x_dtype, s);
+    const bool bf16 = table_dtype == LFFN_BF16;
+    LdsPlan plan;
+    rc = plan_gather_lds(n_tokens, k, tau, d_out, bf16, &plan);
     if (rc != LFFN_OK) return rc;
-    return launch_gather(codes, tables, y, n_tokens, k, tau, d_out, table_dtype, s);
+    if (plan.use) {
+        uint32_t *packed = static_cast<uint32_t *>(ws);
+        rc = launch_hash(x, signs, nullptr, packed, n_tokens, d, k, tau, n_rounds, x_dtype, s);
+        if (rc != LFFN_OK) return rc;
+        return launch_gather_lds(plan, packed, tables, y, bf16, s);
+    }
+    uint16_t *codes = static_cast<uint16_t *>(ws);
+    rc = launch_hash(x, signs, codes, nullptr, n_tokens, d, k, tau, n_rounds, x_dtype, s);
+    if (rc != LFFN_OK) return rc;
+    return launch_gather_direct(codes, tables, y, n_tokens, k, tau, d_out, table_dtype, s);
 }
 
 int lookupffn_release_workspace(void)

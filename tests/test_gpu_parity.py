@@ -164,17 +164,20 @@ def test_gather_every_launch_shape(lpt, xcd):
 
 
 LDS_SHAPES = [
-    # n, k, tau, d_out, table dtype          (gather_path = 2 forces the LDS-staged kernel)
+    # n, k, tau, d_out, table dtype     (gather_path = 2 forces the LDS-staged kernel: tau 7 or 8, k even)
     (1003, 96, 8, 768, "f32"),       # three slices per XCD, ragged chunks
     (1003, 96, 8, 768, "bf16"),
     (16384, 32, 8, 768, "f32"),      # the benchmark's split: 11/11/10 workgroups per slice, 13 tokens per lane
-    (5000, 24, 6, 200, "f32"),       # ragged last slice (50 pieces), fewer rows than fill lanes
-    (3000, 10, 9, 520, "bf16"),      # 512 rows: four fill pieces per thread, 128 KB of LDS
-    (130, 2, 1, 4, "f32"),           # a single 16-byte piece per row
-    (120000, 4, 4, 128, "f32"),      # several chunks per workgroup
-    (300, 2, 3, 8192, "f32"),        # as many slice-units as workgroups
-    (200, 2, 2, 16384, "bf16"),      # more slice-units than workgroups
+    (5000, 24, 7, 200, "f32"),       # ragged last slice (50 pieces), 128-row tables
+    (3000, 10, 8, 520, "bf16"),      # ragged last slice with bf16 rows
+    (130, 2, 7, 4, "f32"),           # a single 16-byte piece per row
+    (120000, 4, 7, 128, "f32"),      # several chunks per workgroup
+    (300, 2, 7, 8192, "f32"),        # as many slice-units as workgroups
+    (200, 2, 8, 16384, "bf16"),      # more slice-units than workgroups
     (1, 6, 8, 64, "f32"),            # one token
+    (777, 2, 8, 64, "f32"),          # a single stage
+    (777, 6, 8, 64, "bf16"),         # an odd number of stages
+    (500, 10, 6, 64, "f32"),         # tau outside the staged kernel's range: falls back to the direct kernel
 ]
 
 
@@ -198,13 +201,13 @@ def test_gather_lds_staged_kernel(n, k, tau, d_out, tdt):
 
 def test_gather_reduces_codes_modulo_table_size():
     print("gather out-of-range codes", flush=True)
-    n, k, tau, d_out = 40, 8, 4, 16
-    tables = synth.make_tables(1, k, 16, d_out)
+    n, k, tau, d_out = 40, 8, 7, 16
+    tables = synth.make_tables(1, k, 128, d_out)
     codes = np.random.default_rng(0).integers(0, 65536, size=(n, k)).astype(np.uint16)
     for path in (1, 2):
         B.lookupffn_set_option("gather_path", path)
         try:
-            assert np.array_equal(gpu_gather(codes, tables), oracle.gather(codes & 15, tables, acc64=False))
+            assert np.array_equal(gpu_gather(codes, tables), oracle.gather(codes & 127, tables, acc64=False))
         finally:
             B.lookupffn_set_option("gather_path", 0)
 
