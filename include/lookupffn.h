@@ -92,13 +92,14 @@ int64_t lookupffn_workspace_bytes(int64_t n_tokens, int k);
 int lookupffn_release_workspace(void);
 
 /*
- * Kernel timing for benchmarks.  While enabled, every kernel the library launches is
- * bracketed by a pair of HIP events recorded on the launch stream.
+ * Kernel timing for benchmarks.  `mask` selects which launches are bracketed by a pair of
+ * HIP events recorded on the launch stream: bit 0 = hash kernel, bit 1 = gather kernel
+ * (0 = off, 3 = both; each bracketed launch costs a few microseconds of queue time).
  * lookupffn_timing_read synchronises on the recorded events and returns, for
  * `which` (0 = hash kernel, 1 = gather kernel), the summed elapsed milliseconds and the
  * number of launches since the last reset.  Not thread-safe; off by default.
  */
-int lookupffn_timing_enable(int on);
+int lookupffn_timing_enable(int mask);
 int lookupffn_timing_reset(void);
 int lookupffn_timing_read(int which, double *total_ms, int64_t *launches);
 

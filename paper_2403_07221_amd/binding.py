@@ -168,8 +168,11 @@ def lookupffn_release_workspace() -> None:
     _check(lib().lookupffn_release_workspace())
 
 
-def lookupffn_timing_enable(on: bool) -> None:
-    _check(lib().lookupffn_timing_enable(int(on)))
+def lookupffn_timing_enable(mask) -> None:
+    """mask: bit 0 = time hash launches, bit 1 = time gather launches; True = both, False = off."""
+    if mask is True:
+        mask = 3
+    _check(lib().lookupffn_timing_enable(int(mask)))
 
 
 def lookupffn_timing_reset() -> None:

@@ -56,7 +56,7 @@ struct Options {
 
 // ---------------------------------------------------------------- timing
 struct Timing {
-    bool on = false;
+    int on = 0;  // bit 0: time hash launches, bit 1: time gather launches
     std::vector<std::pair<hipEvent_t, hipEvent_t>> ev[2];
     std::vector<std::pair<hipEvent_t, hipEvent_t>> pool;
 } g_tm;
@@ -66,9 +66,10 @@ struct TimedLaunch {
     hipStream_t s;
     hipEvent_t a = nullptr, b = nullptr;
     bool ok = true;
+    bool active() const { return (g_tm.on >> which) & 1; }
     TimedLaunch(int which_, hipStream_t s_) : which(which_), s(s_)
     {
-        if (!g_tm.on) return;
+        if (!active()) return;
         if (!g_tm.pool.empty()) {
             a = g_tm.pool.back().first;
             b = g_tm.pool.back().second;
@@ -81,7 +82,7 @@ struct TimedLaunch {
     }
     void done()
     {
-        if (!g_tm.on || !a || !b) return;
+        if (!active() || !a || !b) return;
         (void)hipEventRecord(b, s);
         g_tm.ev[which].emplace_back(a, b);
     }
@@ -513,9 +514,10 @@ int lookupffn_release_workspace(void)
     return rc;
 }
 
-int lookupffn_timing_enable(int on)
+int lookupffn_timing_enable(int mask)
 {
-    g_tm.on = on != 0;
+    if (mask < 0 || mask > 3) return LFFN_E_SIZE;
+    g_tm.on = mask;
     return LFFN_OK;
 }
 

@@ -330,6 +330,6 @@ def test_empty_batch_and_timing_counters():
             B.lookupffn_forward(xd, sd, td)
         (h_ms, h_n), (g_ms, g_n) = B.lookupffn_timing_read(0), B.lookupffn_timing_read(1)
     finally:
-        B.lookupffn_timing_enable(False)
+        B.lookupffn_timing_enable(0)
         B.lookupffn_timing_reset()
     assert h_n == 3 and g_n == 3 and h_ms > 0 and g_ms > 0
