@@ -30,8 +30,9 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4],
-                    help="benchmark configuration (2 = the headline RoBERTa-base-shaped layer)")
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5],
+                    help="benchmark configuration (2 = the headline RoBERTa-base-shaped layer; 5 = the "
+                         "8-token, 12-layer latency chain: a step is one pass through all 12 layers)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle timing")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
@@ -89,13 +90,26 @@ def main():
     torch.cuda.set_device(0)
     B.lib()
     w = synth.CONFIGS[args.config]
-    x, signs, tables = synth.make_layer(w)
-    xd, sd, td = B.to_device(x), B.to_device(signs), B.to_device(tables)
-    y = torch.empty((w.n_tokens, w.d_out), dtype=torch.float32, device="cuda")
     ws = torch.empty(B.lookupffn_workspace_bytes(w.n_tokens, w.k), dtype=torch.uint8, device="cuda")
+    if w.n_layers == 1:
+        x, signs, tables = synth.make_layer(w)
+        xd, sd, td = B.to_device(x), B.to_device(signs), B.to_device(tables)
+        y = torch.empty((w.n_tokens, w.d_out), dtype=torch.float32, device="cuda")
 
-    def step():
-        B.lookupffn_forward(xd, sd, td, y=y, workspace=ws)
+        def step():
+            B.lookupffn_forward(xd, sd, td, y=y, workspace=ws)
+    else:
+        # stacked layers, chained: layer l+1 hashes layer l's output (d_out == d)
+        layers = [synth.make_layer(w, layer=l, with_x=(l == 0)) for l in range(w.n_layers)]
+        x, signs, tables = layers[0]
+        xd = B.to_device(x)
+        dev = [(B.to_device(s_), B.to_device(t_)) for _, s_, t_ in layers]
+        ys = [torch.empty((w.n_tokens, w.d_out), dtype=torch.float32, device="cuda") for _ in range(2)]
+
+        def step():
+            h = xd
+            for l in range(w.n_layers):
+                h = B.lookupffn_forward(h, dev[l][0], dev[l][1], y=ys[l & 1], workspace=ws)
 
     # untimed: the hash kernel's own duration (event pairs around it), outside the timed region so
     # that the timed steps carry only the one event pair the roofline entry needs
@@ -120,14 +134,14 @@ def main():
     gather_ms, gather_n = B.lookupffn_timing_read(1)
     B.lookupffn_timing_enable(0)
     B.lookupffn_timing_reset()
-    assert gather_n == args.steps and hash_n == args.warmup
+    assert gather_n == args.steps * w.n_layers and hash_n == args.warmup * w.n_layers
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tokens_per_s = w.n_tokens / (ms_per_step * 1e-3)
 
     xb = 2 if w.x_dtype == "bf16" else 4
     tb = 2 if w.table_dtype == "bf16" else 4
-    path_bytes = cost.bytes_per_token(w.d, w.k, w.d_out, xb, tb) * w.n_tokens
+    path_bytes = cost.bytes_per_token(w.d, w.k, w.d_out, xb, tb) * w.n_tokens * w.n_layers
     # the gather kernel alone: k table rows + the y row + the k uint16 codes it reads, per token
     gather_bytes = (w.k * w.d_out * tb + w.d_out * 4 + w.k * 2) * w.n_tokens
     gather_avg_ms = gather_ms / gather_n
@@ -157,6 +171,25 @@ def main():
         "whole_path": {"algorithmic_bytes_per_step": path_bytes,
                        "effective_GBps": path_bytes / (ms_per_step * 1e-3) / 1e9},
     }
+    if w.n_layers > 1:
+        # the same chain with every cache flushed before each pass (1 GiB overwrite, untimed):
+        # the configuration is meant to show latency with the tables cold
+        flush = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+        cold_ms = 0.0
+        n_cold = 10
+        for _ in range(n_cold):
+            flush.zero_()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            step()
+            e1.record()
+            torch.cuda.synchronize()
+            cold_ms += e0.elapsed_time(e1)
+        out["latency"] = {"layers": w.n_layers, "warm_us_per_pass": ms_per_step * 1e3,
+                          "warm_us_per_layer": ms_per_step * 1e3 / w.n_layers,
+                          "cold_us_per_pass": cold_ms / n_cold * 1e3,
+                          "cold_us_per_layer": cold_ms / n_cold * 1e3 / w.n_layers}
     if args.copy_calibration_mib > 0:
         src = torch.ones(args.copy_calibration_mib << 18, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
@@ -166,6 +199,8 @@ def main():
         out["copy_calibration_bytes_each_way"] = src.numel() * 4
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, x, signs, tables, args.cpu_seconds)
+        if w.n_layers > 1:
+            out["cpu_baseline"]["sample"] += "; one layer (the first) of the chain"
     print(json.dumps(out))
 
 

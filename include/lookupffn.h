@@ -109,6 +109,9 @@ int lookupffn_timing_read(int which, double *total_ms, int64_t *launches);
  *   "xcd_order"        1 / -1         force the XCD-sliced block order on / off
  *   "gather_path"      1 / 2          1: always the direct kernel; 2: the LDS-staged kernel
  *                                     whenever the shape allows it (tau 7 or 8, k even)
+ *   "hash_path"        1              always the generic hash kernel (default: the two-layout
+ *                                     kernel when d_pad = 1024 and n_rounds <= 4)
+ *   "hash_blocks"      1..65536       grid cap of the d_pad = 1024 hash kernel
  * Returns LFFN_E_SIZE for an unknown key or a value outside the documented set.
  */
 int lookupffn_set_option(const char *key, int value);

@@ -42,6 +42,9 @@ constexpr int kLdsThreads = 1024;
 constexpr int kLdsGroups = kLdsThreads / 8;  // token groups per workgroup (8 lanes per token)
 constexpr int kLdsTps = 2;                   // tables per stage
 constexpr int kLdsMaxTok = 16;               // token slots per lane the packed padding allows for
+#ifndef LFFN_LDS_RB
+#define LFFN_LDS_RB 3
+#endif
 
 struct GatherLdsArgs {
     const uint32_t *packed;  // [k/2][n_pad] packed codes (see hash_kernel.hpp)
@@ -176,7 +179,7 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
             auto run_stage = [&](auto more_tag, uint32_t s, uint32_t b, const uint32_t(&cr)[TOK],
                                  uint32_t(&cr_next)[TOK]) {
                 constexpr bool MORE = decltype(more_tag)::value;
-                constexpr int RB = 2;                        // row reads per batch
+                constexpr int RB = LFFN_LDS_RB;              // row reads per batch
                 constexpr int NB = (TOK + RB - 1) / RB;      // batches per table
                 constexpr int NBT = kLdsTps * NB;            // batches per stage
                 constexpr int CPB = (TOK + NBT - 1) / NBT;   // code loads per batch

@@ -296,6 +296,217 @@ __global__ __launch_bounds__(kHashThreads) void hash_kernel(HashArgs a)
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// d_pad = 1024 variant (RoBERTa-base / -large widths): same butterflies, fewer cross-lane steps.
+//
+// The generic kernel keeps coordinate i in (lane i%64, register i/64) for the whole transform, so
+// six of the ten stages of a round are lane exchanges costing 2-3 instructions per register.
+// Here a round runs in two register layouts and changes between them through LDS:
+//   layout A: lane = i[9:4], register = i[3:0]   strides 1, 2, 4, 8       are register pairs
+//   layout B: lane = (i[9:8], i[3:0]), register = i[7:4]
+//                                                strides 16, 32, 64, 128 are register pairs,
+//                                                strides 256, 512 are the permlane16/32 swaps
+// i.e. eight of ten stages cost one instruction per register.  The per-wave 4 KB transpose
+// area holds coordinate i at word sigma(i) = i ^ ((i >> 4) & 0x3C); with that swizzle the
+// 16-byte accesses of layout A and the 4-byte accesses of layout B are both bank-conflict free.
+// Every butterfly is still (a + c, a - c), a the lower index, strides ascending, fp32, no
+// contraction: the rounding sequence of each coordinate is the textbook loop's.
+// The sign diagonals sit in registers in layout A (16 consecutive int8 per lane and round =
+// one 16-byte load); the token's row is one contiguous 64-byte run per lane.
+constexpr int kH1024TransposeWords = 1024;
+
+__host__ __device__ inline int h1024_wave_words(int P) { return kH1024TransposeWords + hash_bit_words(P, 1024); }
+__host__ inline size_t h1024_lds_bytes(int P) { return sizeof(uint32_t) * (size_t)kHashWaves * h1024_wave_words(P); }
+
+typedef __attribute__((address_space(3))) uint32_t lds_u32;
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) u32x4_t lds_u32x4;
+typedef __attribute__((address_space(3))) uint16_t lds_u16;
+
+template <int R>
+__global__ __launch_bounds__(kHashThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void hash1024_kernel(HashArgs a)
+{
+    constexpr int N = 1024, NREG = 16;
+    extern __shared__ uint32_t lds[];
+    const unsigned lane = threadIdx.x & 63u;
+    const unsigned wave = threadIdx.x >> 6;
+    const int P = a.P;
+    uint32_t *tp = lds + wave * h1024_wave_words(P);  // transpose area, then the bit string
+    uint32_t *bitw = tp + kH1024TransposeWords;
+    const int n_bitw = hash_bit_words(P, N);
+    for (int i = (int)lane; i < n_bitw; i += 64) bitw[i] = 0;
+
+    // LDS byte addresses (32-bit LDS pointers) of this lane's pieces in both layouts
+    const uint32_t tp0 = (uint32_t)(uintptr_t)tp;
+    uint32_t adrA[4];  // quarter m of the lane's 16 consecutive coordinates (16 bytes)
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+        adrA[m] = tp0 + 4u * ((((lane & 0x3Cu) | ((lane ^ (lane >> 4)) & 3u)) << 4) | ((m ^ ((lane >> 2) & 3u)) << 2));
+    uint32_t adrB[NREG];  // register r of layout B
+    {
+        const uint32_t c = lane >> 4, l = lane & 15u;
+        const uint32_t base = (c << 8) | (c << 4) | l;
+#pragma unroll
+        for (int r = 0; r < NREG; ++r) {
+            const uint32_t K = ((uint32_t)(r >> 2) << 6) | ((uint32_t)(r & 3) << 4) | ((uint32_t)(r >> 2) << 2);
+            adrB[r] = tp0 + 4u * (base ^ K);
+        }
+    }
+
+    const long long gw = (long long)blockIdx.x * kHashWaves + wave;
+    const long long n_waves = (long long)gridDim.x * kHashWaves;
+    const float scale = a.scale;
+    const bool vec_ok = (a.d % 4) == 0;  // rows start 16-byte (fp32) / 8-byte (bf16) aligned: checked by the host
+
+    // a1: coordinates lane*16 .. lane*16+15 of token t, widened, zero-padded
+    auto load_x = [&](long long t, float(&xv)[NREG]) {
+        const int i0 = (int)lane * 16;
+        if (vec_ok) {
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (i0 + 4 * m < a.d) {
+                    if (a.x_bf16) {
+                        const uint2 w = *reinterpret_cast<const uint2 *>((const uint16_t *)a.x + t * a.d + i0 + 4 * m);
+                        f = make_float4(__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xFFFF0000u),
+                                        __uint_as_float(w.y << 16), __uint_as_float(w.y & 0xFFFF0000u));
+                    } else {
+                        f = *reinterpret_cast<const float4 *>((const float *)a.x + t * a.d + i0 + 4 * m);
+                    }
+                }
+                xv[4 * m] = f.x;
+                xv[4 * m + 1] = f.y;
+                xv[4 * m + 2] = f.z;
+                xv[4 * m + 3] = f.w;
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < NREG; ++e) {
+                float f = 0.0f;
+                if (i0 + e < a.d) {
+                    if (a.x_bf16)
+                        f = __uint_as_float((uint32_t)((const uint16_t *)a.x)[t * a.d + i0 + e] << 16);
+                    else
+                        f = ((const float *)a.x)[t * a.d + i0 + e];
+                }
+                xv[e] = f;
+            }
+        }
+    };
+    // a2: projection p's diagonals in layout A: 16 consecutive int8 per lane and round, kept as
+    // four words; the XOR mask of coordinate e is the sign bit of byte e moved to bit 31
+    // (signs are 16-byte aligned: host-checked)
+    uint32_t sw[R][4];
+    auto load_masks = [&](int p) {
+#pragma unroll
+        for (int rd = 0; rd < R; ++rd) {
+            const uint4 w = *reinterpret_cast<const uint4 *>(a.signs + ((size_t)p * R + rd) * N + lane * 16);
+            sw[rd][0] = w.x;
+            sw[rd][1] = w.y;
+            sw[rd][2] = w.z;
+            sw[rd][3] = w.w;
+        }
+    };
+    if (P == 1 && gw < a.n) load_masks(0);
+
+    float xn[NREG];
+    if (gw < a.n) load_x(gw, xn);
+    for (long long t = gw; t < a.n; t += n_waves) {
+        float xv[NREG];
+#pragma unroll
+        for (int e = 0; e < NREG; ++e) xv[e] = xn[e];
+        if (t + n_waves < a.n) load_x(t + n_waves, xn);
+
+        for (int p = 0; p < P; ++p) {
+            if (P > 1) load_masks(p);
+            float v[NREG];
+#pragma unroll
+            for (int e = 0; e < NREG; ++e) v[e] = xv[e];
+#pragma unroll
+            for (int rd = 0; rd < R; ++rd) {
+                // ---- layout A: sign diagonal, strides 1, 2, 4, 8 ------------------------------
+#pragma unroll
+                for (int e = 0; e < NREG; ++e)
+                    v[e] = fxor(v[e], (sw[rd][e >> 2] << (24 - 8 * (e & 3))) & 0x80000000u);
+                reg_stage<1, NREG>(v);
+                reg_stage<2, NREG>(v);
+                reg_stage<4, NREG>(v);
+                reg_stage<8, NREG>(v);
+                // ---- A -> B through LDS ---------------------------------------------------------
+                wave_lds_fence();
+#pragma unroll
+                for (int m = 0; m < 4; ++m) {
+                    u32x4_t q = {__float_as_uint(v[4 * m]), __float_as_uint(v[4 * m + 1]),
+                                 __float_as_uint(v[4 * m + 2]), __float_as_uint(v[4 * m + 3])};
+                    *reinterpret_cast<lds_u32x4 *>((uintptr_t)adrA[m]) = q;
+                }
+                wave_lds_fence();
+#pragma unroll
+                for (int r = 0; r < NREG; ++r) v[r] = __uint_as_float(*reinterpret_cast<lds_u32 *>((uintptr_t)adrB[r]));
+                // ---- layout B: strides 16 .. 128 in registers, 256 / 512 across lanes, scale ----
+                reg_stage<1, NREG>(v);
+                reg_stage<2, NREG>(v);
+                reg_stage<4, NREG>(v);
+                reg_stage<8, NREG>(v);
+                lane_stage<16, NREG>(v, lane);
+                lane_stage<32, NREG>(v, lane);
+#pragma unroll
+                for (int r = 0; r < NREG; ++r) v[r] = v[r] * scale;
+                if (rd + 1 < R) {
+                    // ---- B -> A for the next round ------------------------------------------------
+                    wave_lds_fence();
+#pragma unroll
+                    for (int r = 0; r < NREG; ++r) *reinterpret_cast<lds_u32 *>((uintptr_t)adrB[r]) = __float_as_uint(v[r]);
+                    wave_lds_fence();
+#pragma unroll
+                    for (int m = 0; m < 4; ++m) {
+                        const u32x4_t q = *reinterpret_cast<lds_u32x4 *>((uintptr_t)adrA[m]);
+                        v[4 * m] = __uint_as_float(q.x);
+                        v[4 * m + 1] = __uint_as_float(q.y);
+                        v[4 * m + 2] = __uint_as_float(q.z);
+                        v[4 * m + 3] = __uint_as_float(q.w);
+                    }
+                }
+            }
+            // ---- a4: sign bits.  In layout B, bit l of register r's lane mask is coordinate
+            // i = (l[5:4] << 8) | (r << 4) | l[3:0]: each 16-bit quarter c of the mask is the run of
+            // bits [c*256 + r*16, +16) of this projection; lane c stores quarter c of every register.
+            unsigned long long msk[NREG];
+#pragma unroll
+            for (int r = 0; r < NREG; ++r) msk[r] = __builtin_amdgcn_ballot_w64(v[r] >= 0.0f);
+            if (lane < 4) {
+                lds_u16 *dst = reinterpret_cast<lds_u16 *>((uintptr_t)((uint32_t)(uintptr_t)bitw + 2u * (p * 64 + lane * 16)));
+#pragma unroll
+                for (int r = 0; r < NREG; ++r) dst[r] = (uint16_t)(msk[r] >> (16 * lane));
+            }
+        }
+        wave_lds_fence();
+
+        // ---- a4: code j = bits [j*tau, (j+1)*tau), little-endian ---------------------------
+        const uint32_t cmask = (1u << a.tau) - 1u;
+        auto code_at = [&](unsigned j) -> uint32_t {
+            const unsigned bit = j * (unsigned)a.tau;
+            const unsigned wi = bit >> 5, sh = bit & 31u;
+            const unsigned long long both = ((unsigned long long)bitw[wi + 1] << 32) | bitw[wi];
+            return (uint32_t)(both >> sh) & cmask;
+        };
+        if (a.packed) {
+            for (int s = (int)lane; s < a.k / 2; s += 64)
+                a.packed[(long long)s * a.n_pad + t] =
+                    (code_at(2u * s) << kPackedShift) | (code_at(2u * s + 1u) << (16 + kPackedShift));
+        } else {
+            for (int j = (int)lane; j < a.k; j += 64) a.codes[t * a.k + j] = (uint16_t)code_at((unsigned)j);
+        }
+        wave_lds_fence();
+    }
+
+    // zero the token padding of the packed layout
+    if (a.packed) {
+        for (long long t = a.n + gw; t < a.n_pad; t += n_waves)
+            for (int s = (int)lane; s < a.k / 2; s += 64) a.packed[(long long)s * a.n_pad + t] = 0u;
+    }
+}
+
 // ABI codes [n][k] -> packed layout (for a stand-alone gather call that takes the LDS-staged kernel)
 __global__ __launch_bounds__(256) void repack_codes_kernel(const uint16_t *codes, uint32_t *packed, long long n,
                                                            long long n_pad, int k, int tau)

@@ -52,6 +52,8 @@ struct Options {
     int lanes_per_token = 0;  // 0 = default
     int xcd_order = 0;        // 0 = default, 1 = on, -1 = off
     int gather_path = 0;      // 0 = choose, 1 = direct kernel, 2 = LDS-staged kernel (if the shape allows)
+    int hash_path = 0;        // 0 = choose, 1 = generic kernel only
+    int hash_blocks = 0;      // 0 = default grid cap of the d_pad = 1024 hash kernel
 } g_opt;
 
 // ---------------------------------------------------------------- timing
@@ -178,11 +180,31 @@ int launch_hash(const void *x, const int8_t *signs, uint16_t *codes, uint32_t *p
     a.P = (int)(((int64_t)k * tau + N - 1) / N);
     a.x_bf16 = x_dtype == LFFN_BF16;
     a.scale = (float)(1.0 / std::sqrt((double)N));
+    TimedLaunch tl(0, s);
+    // d_pad = 1024 with up to four rounds: the two-layout kernel (needs 16-byte aligned signs, and
+    // rows that start on 16-byte boundaries when it loads them as vectors)
+    const size_t xrow = (size_t)d * (a.x_bf16 ? 2 : 4);
+    if (g_opt.hash_path != 1 && L == 10 && n_rounds <= 4 && aligned(signs, 16) && h1024_lds_bytes(a.P) <= 64 * 1024 &&
+        (d % 4 != 0 || (aligned(x, 16) && xrow % (a.x_bf16 ? 8 : 16) == 0))) {
+        int64_t blocks = (n + kHashWaves - 1) / kHashWaves;
+        const int64_t cap = g_opt.hash_blocks ? g_opt.hash_blocks : 4096;
+        if (blocks > cap) blocks = cap;
+        const dim3 grid((unsigned)blocks);
+        const size_t lds = h1024_lds_bytes(a.P);
+        switch (n_rounds) {
+            case 1: hipLaunchKernelGGL(hash1024_kernel<1>, grid, dim3(kHashThreads), lds, s, a); break;
+            case 2: hipLaunchKernelGGL(hash1024_kernel<2>, grid, dim3(kHashThreads), lds, s, a); break;
+            case 3: hipLaunchKernelGGL(hash1024_kernel<3>, grid, dim3(kHashThreads), lds, s, a); break;
+            default: hipLaunchKernelGGL(hash1024_kernel<4>, grid, dim3(kHashThreads), lds, s, a); break;
+        }
+        LFFN_HIP(hipGetLastError());
+        tl.done();
+        return LFFN_OK;
+    }
     const size_t lds = hash_lds_bytes(a.P, n_rounds, N);
     int64_t blocks = (n + kHashWaves - 1) / kHashWaves;
     if (blocks > 2048) blocks = 2048;
     const dim3 grid((unsigned)blocks);
-    TimedLaunch tl(0, s);
     switch (L) {
 #define LFFN_CASE(l) case l: launch_hash_t<l>(a, grid, lds, s); break;
         LFFN_CASE(0) LFFN_CASE(1) LFFN_CASE(2) LFFN_CASE(3) LFFN_CASE(4) LFFN_CASE(5) LFFN_CASE(6)
@@ -555,6 +577,16 @@ int lookupffn_set_option(const char *key, int value)
     if (!std::strcmp(key, "lanes_per_token")) {
         if (value != 0 && (value < 1 || value > 64 || (value & (value - 1)))) return LFFN_E_SIZE;
         g_opt.lanes_per_token = value;
+        return LFFN_OK;
+    }
+    if (!std::strcmp(key, "hash_path")) {
+        if (value < 0 || value > 1) return LFFN_E_SIZE;
+        g_opt.hash_path = value;
+        return LFFN_OK;
+    }
+    if (!std::strcmp(key, "hash_blocks")) {
+        if (value < 0 || value > 65536) return LFFN_E_SIZE;
+        g_opt.hash_blocks = value;
         return LFFN_OK;
     }
     if (!std::strcmp(key, "gather_path")) {

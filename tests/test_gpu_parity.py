@@ -26,6 +26,8 @@ def _gpu():
     B.lookupffn_set_option("lanes_per_token", 0)
     B.lookupffn_set_option("xcd_order", 0)
     B.lookupffn_set_option("gather_path", 0)
+    B.lookupffn_set_option("hash_path", 0)
+    B.lookupffn_set_option("hash_blocks", 0)
 
 
 def rel_err(y, ref):
@@ -80,6 +82,14 @@ HASH_SHAPES = [
     (65, 8, 5, 4, 1, "f32"),         # three 8-wide projections
     (9, 1, 2, 1, 2, "f32"),          # degenerate width 1
     (70, 5, 3, 5, 4, "f32"),
+    # d_pad = 1024 takes the two-layout kernel: every round count, scalar and vector row loads
+    (37, 1001, 60, 8, 1, "f32"),     # d not a multiple of 4: scalar loads
+    (37, 600, 128, 8, 2, "f32"),
+    (37, 1024, 250, 4, 4, "f32"),
+    (37, 520, 64, 16, 3, "bf16"),
+    (37, 999, 30, 7, 3, "bf16"),
+    (41, 768, 96, 8, 5, "f32"),      # five rounds: back to the generic kernel
+    (5000, 768, 96, 8, 3, "f32"),    # several tokens per wave
 ]
 
 
@@ -108,6 +118,28 @@ def test_hash_special_inputs():
     # zero input with an all -1 diagonal yields -0 at coordinate 0: must still count as bit 1
     got = gpu_hash(x[:1], np.full((1, 1, d), -1, np.int8), k, tau)
     assert (got == 255).all()
+
+
+def test_hash_special_inputs_wide():
+    print("hash special inputs, d_pad = 1024", flush=True)
+    d, k, tau, R = 768, 96, 8, 3
+    x = np.zeros((7, d), np.float32)
+    x[1, 0] = 1
+    x[2, 0] = -1
+    x[3, :] = 1
+    x[4, :] = 1e-41                   # subnormal inputs must not be flushed
+    x[5, ::2] = 3e-39
+    x[5, 1::2] = -2e-39
+    x[6, 5] = 3e38                    # large values: the scale keeps intermediate sums finite
+    for s in (1, -1, 0):
+        signs = (np.full((1, R, 1024), s, np.int8) if s else synth.make_signs(5, 1, R, 1024))
+        assert_codes_equal(gpu_hash(x, signs, k, tau), oracle.hash_codes(x, signs, k, tau))
+    B.lookupffn_set_option("hash_path", 1)      # and the generic kernel on the same inputs
+    try:
+        signs = synth.make_signs(6, 1, R, 1024)
+        assert_codes_equal(gpu_hash(x, signs, k, tau), oracle.hash_codes(x, signs, k, tau))
+    finally:
+        B.lookupffn_set_option("hash_path", 0)
 
 
 def test_hash_large_dynamic_range_inputs():

@@ -94,6 +94,8 @@ def test_options(L):
     assert L.lookupffn_set_option(b"lanes_per_token", 0) == 0
     assert L.lookupffn_set_option(b"xcd_order", 2) == -2 and L.lookupffn_set_option(b"xcd_order", 0) == 0
     assert L.lookupffn_set_option(b"gather_path", 3) == -2 and L.lookupffn_set_option(b"gather_path", 0) == 0
+    assert L.lookupffn_set_option(b"hash_path", 2) == -2 and L.lookupffn_set_option(b"hash_path", 0) == 0
+    assert L.lookupffn_set_option(b"hash_blocks", -1) == -2 and L.lookupffn_set_option(b"hash_blocks", 0) == 0
     assert L.lookupffn_set_option(b"no_such_key", 1) == -2
     assert L.lookupffn_set_option(None, 1) == -1
 
