@@ -30,9 +30,10 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5],
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5, 6, 7, 8],
                     help="benchmark configuration (2 = the headline RoBERTa-base-shaped layer; 5 = the "
-                         "8-token, 12-layer latency chain: a step is one pass through all 12 layers)")
+                         "8-token, 12-layer latency chain: a step is one pass through all 12 layers; 6-8 = the "
+                         "paper's own layer shapes at its 32768-token batch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle timing")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,

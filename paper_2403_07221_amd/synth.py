@@ -66,6 +66,15 @@ C4 = Workload("C4-roberta-large-f32", 4, 16384, 1024, 3, 128, 10, 1024)
 C5 = Workload("C5-latency-12-layers-f32", 5, 8, 768, 3, 96, 8, 768, n_layers=12)
 CONFIGS = {1: C1, 2: C2, 3: C3, 4: C4, 5: C5}
 
+# The paper's own layer shapes (Sec. 4): 4-layer RoBERTa with d = 512 and h = 256 / 128 tables of
+# 2^8 rows (Tab. "baselines"), and RoBERTa-base with h = 170, tau = 9 (the scaling experiment), each
+# at the 32768-token effective batch of the latency study (Sec. 4.3: batch 64 x sequence 512),
+# hashed with the three-round sign-diagonal projection of Sec. 3.2, eq. "hadamard".
+P6 = Workload("P6-paper-small-h256-f32", 6, 32768, 512, 3, 256, 8, 512)
+P7 = Workload("P7-paper-small-h128-f32", 7, 32768, 512, 3, 128, 8, 512)
+P8 = Workload("P8-paper-base-h170-tau9-f32", 8, 32768, 768, 3, 170, 9, 768)
+CONFIGS.update({6: P6, 7: P7, 8: P8})
+
 
 def seed_for(config: int, layer: int, what: int) -> int:
     """what: 0 = sign diagonals, 1 = x, 2 = tables."""

@@ -32,6 +32,7 @@ def test_padding_rule_is_the_one_the_flop_tables_imply():
     for d, h, tau in [(768, 170, 9), (512, 256, 8), (512, 20, 13), (768, 96, 8), (1024, 128, 10), (64, 8, 8)]:
         assert oracle.d_pad(d) == cost.d_pad(d)
         assert oracle.n_proj(d, h, tau) == cost.n_proj(d, h, tau)
+    assert (synth.P6.n_proj, synth.P7.n_proj, synth.P8.n_proj) == (4, 2, 2)
     for w in synth.CONFIGS.values():
         assert (w.d_pad, w.n_proj) == (cost.d_pad(w.d), cost.n_proj(w.d, w.k, w.tau))
 

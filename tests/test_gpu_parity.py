@@ -309,6 +309,13 @@ def test_forward_config4_full_size():
     check_forward(w, x, signs, tables, sample=np.arange(0, w.n_tokens, 4))
 
 
+@pytest.mark.parametrize("w", [synth.P6, synth.P7, synth.P8], ids=lambda w: w.name)
+def test_forward_paper_shapes_full_size(w):
+    print(f"forward {w.name} ({w.n_tokens} tokens, d={w.d}, h={w.k}, tau={w.tau})", flush=True)
+    x, signs, tables = synth.make_layer(w)
+    check_forward(w, x, signs, tables, sample=np.arange(0, w.n_tokens, 8))
+
+
 def test_forward_config5_stacked_layers():
     print("forward C5 (8 tokens x 12 layers)", flush=True)
     w = synth.C5
