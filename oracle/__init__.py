@@ -52,6 +52,10 @@ def lib() -> ctypes.CDLL:
         L.oracle_hash.argtypes = [vp, ci, vp, vp, i64, ci, ci, ci, ci]
         L.oracle_gather.argtypes = [vp, vp, ci, vp, i64, ci, ci, ci, ci]
         L.oracle_forward.argtypes = [vp, ci, vp, vp, ci, vp, vp, i64, ci, ci, ci, ci, ci, ci]
+        L.oracle_weights_from_z.argtypes = [vp, i64, vp, i64, ci, ci]
+        L.oracle_weights.argtypes = [vp, ci, vp, vp, i64, ci, ci, ci, ci]
+        L.oracle_gather_weighted.argtypes = [vp, vp, vp, ci, vp, i64, ci, ci, ci]
+        L.oracle_forward_weighted.argtypes = [vp, ci, vp, vp, ci, vp, vp, vp, i64, ci, ci, ci, ci, ci]
         _lib = L
     return _lib
 
@@ -162,3 +166,61 @@ def forward(x: np.ndarray, signs: np.ndarray, tables: np.ndarray, acc64: bool = 
                                 _dtype_code(tables), _ptr(y), _ptr(codes), n, d, k, tau,
                                 d_out, n_rounds, int(acc64)), "forward")
     return (y, codes) if return_codes else y
+
+
+# ---- weighted variant (Sec. 4 of the paper) ---------------------------------------------------
+
+def weights_from_z(z: np.ndarray, k: int, tau: int) -> np.ndarray:
+    """w[n, k] float64 from soft codes z[n, >= k*tau] float32."""
+    z = np.ascontiguousarray(z, dtype=np.float32)
+    n, zs = z.shape
+    w = np.empty((n, k), dtype=np.float64)
+    _check(lib().oracle_weights_from_z(_ptr(z), zs, _ptr(w), n, k, tau), "weights_from_z")
+    return w
+
+
+def weights(x: np.ndarray, signs: np.ndarray, k: int, tau: int) -> np.ndarray:
+    """w[n, k] float64 for tokens x[n, d]."""
+    n, d = x.shape
+    n_rounds = signs.shape[1]
+    _check_signs(signs, d, k, tau, n_rounds)
+    x = np.ascontiguousarray(x)
+    signs = np.ascontiguousarray(signs)
+    w = np.empty((n, k), dtype=np.float64)
+    _check(lib().oracle_weights(_ptr(x), _dtype_code(x), _ptr(signs), _ptr(w), n, d, k, tau, n_rounds), "weights")
+    return w
+
+
+def gather_weighted(codes: np.ndarray, w: np.ndarray, tables: np.ndarray) -> np.ndarray:
+    """y[n, d_out] float32 = sum_j w[:, j] * tables[j, codes[:, j], :] (fp64 accumulation)."""
+    n, k = codes.shape
+    k2, rows, d_out = tables.shape
+    tau = rows.bit_length() - 1
+    assert k2 == k and 1 << tau == rows and codes.dtype == np.uint16 and w.shape == (n, k)
+    codes = np.ascontiguousarray(codes)
+    w = np.ascontiguousarray(w, dtype=np.float64)
+    tables = np.ascontiguousarray(tables)
+    y = np.empty((n, d_out), dtype=np.float32)
+    _check(lib().oracle_gather_weighted(_ptr(codes), _ptr(w), _ptr(tables), _dtype_code(tables), _ptr(y),
+                                        n, k, tau, d_out), "gather_weighted")
+    return y
+
+
+def forward_weighted(x: np.ndarray, signs: np.ndarray, tables: np.ndarray, return_all: bool = False):
+    """Whole weighted forward pass; y[n, d_out] float32 (and codes, weights on request)."""
+    n, d = x.shape
+    k, rows, d_out = tables.shape
+    tau = rows.bit_length() - 1
+    assert 1 << tau == rows
+    n_rounds = signs.shape[1]
+    _check_signs(signs, d, k, tau, n_rounds)
+    x = np.ascontiguousarray(x)
+    signs = np.ascontiguousarray(signs)
+    tables = np.ascontiguousarray(tables)
+    y = np.empty((n, d_out), dtype=np.float32)
+    codes = np.empty((n, k), dtype=np.uint16)
+    w = np.empty((n, k), dtype=np.float64)
+    _check(lib().oracle_forward_weighted(_ptr(x), _dtype_code(x), _ptr(signs), _ptr(tables), _dtype_code(tables),
+                                         _ptr(y), _ptr(codes), _ptr(w), n, d, k, tau, d_out, n_rounds),
+           "forward_weighted")
+    return (y, codes, w) if return_all else y

@@ -30,6 +30,14 @@
  *     +0 and -0 both give 1.
  *   - codes are 0-based, in [0, 2^tau).
  *
+ * Weighted variant (Sec. 4, the form every experiment of the paper uses; the "linearly scaled"
+ * version of eq. "partial_softmax" with N(z_k) = {g(z_k)}):
+ *
+ *   y = sum_k  <z_k,S_g> exp(<z_k,S_g>) / prod_j (exp(z_kj) + exp(-z_kj))  *  T_k[g(z_k)]
+ *
+ * with S_g the +-1 row selected by the code (Sec. 3.1, eq. "optimal_index").  The soft codes
+ * z stay in fp32 (they are the hash's values); the weights and the weighted sum are fp64.
+ *
  * Parity pins (tests/test_oracle_*.py): dense Sylvester matrix from
  * scipy.linalg.hadamard, orthonormality, involution, closed-form inputs,
  * the arg-max form of the hash by brute force over all 2^tau sign rows,
@@ -247,6 +255,95 @@ int oracle_gather(const uint16_t *codes, const void *tables, int table_dtype, fl
         }
     }
     return bad ? ORACLE_E_ARG : ORACLE_OK;
+}
+
+/*
+ * Gather weights from given soft codes (Sec. 4, weighted variant above), literally:
+ *   s_k = <z_k, S_g>,  S_g[b] = +1 where z_k[b] >= 0 else -1   (the row the code selects)
+ *   w_k = s_k * exp(s_k) / prod_b (exp(z_k[b]) + exp(-z_k[b]))
+ *   z [n][zstride] fp32 (table k owns coordinates [k*tau, (k+1)*tau));  w [n][k] fp64.
+ * The product in the denominator is the closed form of sum_i exp(<z_k, S_i>) over all
+ * 2^tau sign rows (Sec. 3.1, the identity after eq. "full_softmax").
+ */
+int oracle_weights_from_z(const float *z, int64_t zstride, double *w, int64_t n, int k, int tau)
+{
+    if (n < 0 || k < 1 || tau < 1 || tau > 16 || zstride < (int64_t)k * tau || !z || !w) return ORACLE_E_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < n; ++t) {
+        for (int j = 0; j < k; ++j) {
+            const float *zk = z + t * zstride + (int64_t)j * tau;
+            double s = 0.0, denom = 1.0;
+            for (int b = 0; b < tau; ++b) {
+                const double zb = (double)zk[b];
+                s += (zk[b] >= 0.0f) ? zb : -zb;
+                denom *= exp(zb) + exp(-zb);
+            }
+            w[t * k + j] = s * exp(s) / denom;
+        }
+    }
+    return ORACLE_OK;
+}
+
+/* Weights for every token: Hash (fp32) then oracle_weights_from_z. */
+int oracle_weights(const void *x, int x_dtype, const int8_t *signs, double *w, int64_t n, int d, int k,
+                   int tau, int n_rounds)
+{
+    if (check_shape(n, d, k, tau, n_rounds) || !x || !signs || !w) return ORACLE_E_ARG;
+    const int64_t zs = (int64_t)oracle_n_proj(d, k, tau) * oracle_d_pad(d);
+    float *z = (float *)malloc(sizeof(float) * (size_t)(n > 0 ? n : 1) * zs);
+    if (!z) return ORACLE_E_NOMEM;
+    int rc = oracle_soft_codes(x, x_dtype, signs, z, n, d, k, tau, n_rounds);
+    if (rc == ORACLE_OK) rc = oracle_weights_from_z(z, zs, w, n, k, tau);
+    free(z);
+    return rc;
+}
+
+/*
+ * Weighted gather (Sec. 4): y[t] = sum_j w[t][j] * T_j[codes[t][j]], accumulated in fp64 in
+ * table order and rounded once to fp32.
+ */
+int oracle_gather_weighted(const uint16_t *codes, const double *w, const void *tables, int table_dtype,
+                           float *y, int64_t n, int k, int tau, int d_out)
+{
+    if (n < 0 || k < 1 || tau < 1 || tau > 16 || d_out < 1 || !codes || !w || !tables || !y)
+        return ORACLE_E_ARG;
+    const int64_t rows = (int64_t)1 << tau;
+    int bad = 0;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < n; ++t) {
+        for (int c = 0; c < d_out; ++c) {
+            double s = 0.0;
+            for (int j = 0; j < k; ++j) {
+                int64_t code = codes[t * k + j];
+                if (code >= rows) {
+#pragma omp atomic write
+                    bad = 1;
+                    code = 0;
+                }
+                s += w[t * k + j] * (double)load_elt(tables, table_dtype, ((int64_t)j * rows + code) * d_out + c);
+            }
+            y[t * d_out + c] = (float)s;
+        }
+    }
+    return bad ? ORACLE_E_ARG : ORACLE_OK;
+}
+
+/* Whole weighted forward pass (Sec. 4): codes, weights, weighted gather.  w_out may be NULL. */
+int oracle_forward_weighted(const void *x, int x_dtype, const int8_t *signs, const void *tables,
+                            int table_dtype, float *y, uint16_t *codes_out, double *w_out, int64_t n,
+                            int d, int k, int tau, int d_out, int n_rounds)
+{
+    if (check_shape(n, d, k, tau, n_rounds) || !y || !tables || !codes_out) return ORACLE_E_ARG;
+    double *w = w_out;
+    if (!w) {
+        w = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1) * k);
+        if (!w) return ORACLE_E_NOMEM;
+    }
+    int rc = oracle_hash(x, x_dtype, signs, codes_out, n, d, k, tau, n_rounds);
+    if (rc == ORACLE_OK) rc = oracle_weights(x, x_dtype, signs, w, n, d, k, tau, n_rounds);
+    if (rc == ORACLE_OK) rc = oracle_gather_weighted(codes_out, w, tables, table_dtype, y, n, k, tau, d_out);
+    if (!w_out) free(w);
+    return rc;
 }
 
 /*
