@@ -34,6 +34,9 @@ def parse_args():
                     help="benchmark configuration (2 = the headline RoBERTa-base-shaped layer; 5 = the "
                          "8-token, 12-layer latency chain: a step is one pass through all 12 layers; 6-8 = the "
                          "paper's own layer shapes at its 32768-token batch)")
+    ap.add_argument("--weighted", action="store_true",
+                    help="time the weighted variant (lookupffn_forward_weighted: the hash also emits one fp32 "
+                         "weight per token and table, the gather multiplies each row by it) instead of the plain sum")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle timing")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
@@ -42,9 +45,9 @@ def parse_args():
     return ap.parse_args()
 
 
-def traffic_from_profiles(w) -> float | None:
+def traffic_from_profiles(w, weighted: bool = False) -> float | None:
     """HBM bytes per gather launch measured with rocprofv3 --pmc, if a summary is committed."""
-    f = ROOT / "profiles" / f"gather_config{w.index}_pmc_hbm_traffic.txt"
+    f = ROOT / "profiles" / f"gather_config{w.index}{'_weighted' if weighted else ''}_pmc_hbm_traffic.txt"
     if not f.exists():
         return None
     for line in f.read_text().splitlines():
@@ -53,18 +56,19 @@ def traffic_from_profiles(w) -> float | None:
     return None
 
 
-def cpu_baseline(w, x, signs, tables, budget_s: float) -> dict:
+def cpu_baseline(w, x, signs, tables, budget_s: float, weighted: bool = False) -> dict:
     """The CPU oracle as it stands, on all host threads it gets, on the same batch."""
     import oracle  # only this leg of the bench touches the oracle
     threads = oracle.max_threads()
     n = x.shape[0]
     sample = min(n, 16384)
     xs = x[:sample]
-    oracle.forward(xs[:256], signs, tables)            # page in
+    run = oracle.forward_weighted if weighted else oracle.forward
+    run(xs[:256], signs, tables)                       # page in
     reps, t_total = 0, 0.0
     while reps < 3 or (t_total < budget_s and reps < 1000):
         t0 = time.perf_counter()
-        oracle.forward(xs, signs, tables, acc64=True)
+        run(xs, signs, tables)
         t_total += time.perf_counter() - t0
         reps += 1
         if t_total > 3 * budget_s:
@@ -91,14 +95,16 @@ def main():
     torch.cuda.set_device(0)
     B.lib()
     w = synth.CONFIGS[args.config]
-    ws = torch.empty(B.lookupffn_workspace_bytes(w.n_tokens, w.k), dtype=torch.uint8, device="cuda")
+    ws_bytes = (B.lookupffn_workspace_bytes_weighted if args.weighted else B.lookupffn_workspace_bytes)(w.n_tokens, w.k)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    forward = B.lookupffn_forward_weighted if args.weighted else B.lookupffn_forward
     if w.n_layers == 1:
         x, signs, tables = synth.make_layer(w)
         xd, sd, td = B.to_device(x), B.to_device(signs), B.to_device(tables)
         y = torch.empty((w.n_tokens, w.d_out), dtype=torch.float32, device="cuda")
 
         def step():
-            B.lookupffn_forward(xd, sd, td, y=y, workspace=ws)
+            forward(xd, sd, td, y=y, workspace=ws)
     else:
         # stacked layers, chained: layer l+1 hashes layer l's output (d_out == d)
         layers = [synth.make_layer(w, layer=l, with_x=(l == 0)) for l in range(w.n_layers)]
@@ -110,7 +116,7 @@ def main():
         def step():
             h = xd
             for l in range(w.n_layers):
-                h = B.lookupffn_forward(h, dev[l][0], dev[l][1], y=ys[l & 1], workspace=ws)
+                h = forward(h, dev[l][0], dev[l][1], y=ys[l & 1], workspace=ws)
 
     # untimed: the hash kernel's own duration (event pairs around it), outside the timed region so
     # that the timed steps carry only the one event pair the roofline entry needs
@@ -145,6 +151,9 @@ def main():
     path_bytes = cost.bytes_per_token(w.d, w.k, w.d_out, xb, tb) * w.n_tokens * w.n_layers
     # the gather kernel alone: k table rows + the y row + the k uint16 codes it reads, per token
     gather_bytes = (w.k * w.d_out * tb + w.d_out * 4 + w.k * 2) * w.n_tokens
+    if args.weighted:
+        gather_bytes += w.k * 4 * w.n_tokens          # the fp32 weights it reads
+        path_bytes += 2 * w.k * 4 * w.n_tokens * w.n_layers   # written by the hash, read by the gather
     gather_avg_ms = gather_ms / gather_n
     achieved = gather_bytes / (gather_avg_ms * 1e-3) / 1e9
 
@@ -164,9 +173,10 @@ def main():
         "config": {"workload": w.name, "n_tokens": w.n_tokens, "d": w.d, "d_pad": w.d_pad,
                    "hash_rounds": w.n_rounds, "k_tables": w.k, "tau": w.tau, "d_out": w.d_out,
                    "x_dtype": w.x_dtype, "table_dtype": w.table_dtype,
-                   "table_bytes": w.k * w.rows * w.d_out * tb},
+                   "table_bytes": w.k * w.rows * w.d_out * tb,
+                   "variant": "weighted" if args.weighted else "plain-sum"},
         "roofline": {"kernel": B.lookupffn_last_gather_kernel(), "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_from_profiles(w),
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_from_profiles(w, args.weighted),
                      "algorithmic_bytes_per_launch": gather_bytes, "avg_kernel_ms": gather_avg_ms},
         "kernels_ms": {"hash": hash_ms / max(hash_n, 1), "gather": gather_avg_ms},
         "whole_path": {"algorithmic_bytes_per_step": path_bytes,
@@ -199,7 +209,7 @@ def main():
         torch.cuda.synchronize()
         out["copy_calibration_bytes_each_way"] = src.numel() * 4
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, x, signs, tables, args.cpu_seconds)
+        out["cpu_baseline"] = cpu_baseline(w, x, signs, tables, args.cpu_seconds, args.weighted)
         if w.n_layers > 1:
             out["cpu_baseline"]["sample"] += "; one layer (the first) of the chain"
     print(json.dumps(out))

@@ -14,6 +14,11 @@
  *   Gather  (Sec. 3.1, eq. "lookup" with the top-1 choice of eq. "optimal_index"):
  *           y = sum_{j<k} tables[j][code_j][:]          (plain sum, no 1/k)
  *
+ *   Weighted variant (Sec. 4, "Overview"; the form the paper's experiments use; the
+ *           linearly scaled eq. "partial_softmax" with the single row g(z_j)):
+ *           w_j = <z_j,S_g> exp(<z_j,S_g>) / prod_b (exp(z_jb) + exp(-z_jb)),  S_g = sign(z_j)
+ *           y   = sum_{j<k} w_j * tables[j][code_j][:]
+ *
  * Conventions for every entry point
  *   - Every data pointer is a DEVICE pointer owned by the caller and valid on the
  *     current HIP device; the library never frees or retains them.
@@ -21,6 +26,7 @@
  *       x      [n_tokens][d]                 fp32 or bf16 (raw 16-bit patterns)
  *       signs  [P][n_rounds][d_pad]          int8, a negative entry means "flip"
  *       codes  [n_tokens][k]                 uint16
+ *       weights[n_tokens][k]                 fp32 (weighted variant only)
  *       tables [k][2^tau][d_out]             fp32 or bf16
  *       y      [n_tokens][d_out]             fp32
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
@@ -30,7 +36,10 @@
  *     n_tokens == 0 is a successful no-op.  Nothing is printed, nothing aborts.
  *   - Arithmetic: the hash runs in fp32 (round to nearest, no fused multiply-add,
  *     butterflies in ascending stride order), bf16 inputs are widened exactly; the
- *     gather accumulates in fp32 in table order j = 0..k-1.
+ *     gather accumulates in fp32 in table order j = 0..k-1.  The weights are evaluated in
+ *     fp32 as |z_j|_1 / prod_b (1 + exp(-2|z_jb|)) (the same quotient with exp(|z_j|_1) divided
+ *     out, so nothing overflows) with the hardware exp2 and reciprocal; the weighted gather
+ *     is one fused multiply-add per element and table.
  */
 #ifndef LOOKUPFFN_H
 #define LOOKUPFFN_H
@@ -87,6 +96,26 @@ int lookupffn_forward(const void *x, const int8_t *signs, const void *tables, fl
 
 /* Bytes of scratch lookupffn_forward needs for this problem size (0 if n_tokens == 0). */
 int64_t lookupffn_workspace_bytes(int64_t n_tokens, int k);
+
+/*
+ * Weighted variant (Sec. 4, "Overview").  lookupffn_hash_weighted writes codes[n_tokens][k]
+ * and weights[n_tokens][k] (4-byte aligned; LFFN_E_UNSUPPORTED when d_pad = 4096, where the
+ * kernel's working set no longer fits).  lookupffn_gather_weighted computes
+ * y[t] = sum_j weights[t][j] * tables[j][codes[t][j] mod 2^tau].  lookupffn_forward_weighted
+ * chains the two like lookupffn_forward, with a scratch buffer of
+ * lookupffn_workspace_bytes_weighted(n_tokens, k) bytes (same rules as above).
+ */
+int lookupffn_hash_weighted(const void *x, const int8_t *signs, uint16_t *codes, float *weights,
+                            int64_t n_tokens, int d, int k, int tau,
+                            int n_rounds, int x_dtype, void *hip_stream);
+int lookupffn_gather_weighted(const uint16_t *codes, const float *weights, const void *tables, float *y,
+                              int64_t n_tokens, int k, int tau, int d_out,
+                              int table_dtype, void *hip_stream);
+int lookupffn_forward_weighted(const void *x, const int8_t *signs, const void *tables, float *y,
+                               int64_t n_tokens, int d, int k, int tau, int d_out,
+                               int n_rounds, int x_dtype, int table_dtype,
+                               void *workspace, int64_t workspace_bytes, void *hip_stream);
+int64_t lookupffn_workspace_bytes_weighted(int64_t n_tokens, int k);
 
 /* Frees the library-owned workspaces (all devices).  Safe to call when none exist. */
 int lookupffn_release_workspace(void);

@@ -21,6 +21,8 @@ EXPORTS = (
     "lookupffn_release_workspace", "lookupffn_timing_enable", "lookupffn_timing_reset",
     "lookupffn_timing_read", "lookupffn_set_option", "lookupffn_strerror",
     "lookupffn_last_hip_error", "lookupffn_last_gather_kernel", "lookupffn_version",
+    "lookupffn_hash_weighted", "lookupffn_gather_weighted", "lookupffn_forward_weighted",
+    "lookupffn_workspace_bytes_weighted",
 )
 
 
@@ -45,6 +47,11 @@ def lib() -> ctypes.CDLL:
         L.lookupffn_forward.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, ci, ci, vp, i64, vp]
         L.lookupffn_workspace_bytes.argtypes = [i64, ci]
         L.lookupffn_workspace_bytes.restype = i64
+        L.lookupffn_hash_weighted.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, vp]
+        L.lookupffn_gather_weighted.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, vp]
+        L.lookupffn_forward_weighted.argtypes = L.lookupffn_forward.argtypes
+        L.lookupffn_workspace_bytes_weighted.argtypes = [i64, ci]
+        L.lookupffn_workspace_bytes_weighted.restype = i64
         L.lookupffn_timing_enable.argtypes = [ci]
         L.lookupffn_timing_read.argtypes = [ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
         L.lookupffn_set_option.argtypes = [ctypes.c_char_p, ci]
@@ -136,12 +143,65 @@ def lookupffn_gather(codes: torch.Tensor, tables: torch.Tensor, y: torch.Tensor 
     return y
 
 
+def lookupffn_hash_weighted(x: torch.Tensor, signs: torch.Tensor, k: int, tau: int,
+                            codes: torch.Tensor | None = None, weights: torch.Tensor | None = None):
+    """(codes[n, k] int16 storage, weights[n, k] float32) of the weighted variant for x[n, d]."""
+    n, d = x.shape
+    _check_signs(signs, d, k, tau)
+    if codes is None:
+        codes = torch.empty((n, k), dtype=torch.int16, device=x.device)
+    if weights is None:
+        weights = torch.empty((n, k), dtype=torch.float32, device=x.device)
+    assert codes.dtype == torch.int16 and tuple(codes.shape) == (n, k)
+    assert weights.dtype == torch.float32 and tuple(weights.shape) == (n, k)
+    if n == 0:
+        return codes, weights
+    with torch.cuda.device(x.device):
+        _check(lib().lookupffn_hash_weighted(_dev(x, "x"), _dev(signs, "signs"), _dev(codes, "codes"),
+                                             _dev(weights, "weights"), n, d, k, tau, signs.shape[1],
+                                             _dtype_code(x), _stream(x)))
+    return codes, weights
+
+
+def lookupffn_gather_weighted(codes: torch.Tensor, weights: torch.Tensor, tables: torch.Tensor,
+                              y: torch.Tensor | None = None) -> torch.Tensor:
+    """y[n, d_out] = sum_j weights[:, j] * tables[j, codes[:, j], :]."""
+    n, k = codes.shape
+    k2, rows, d_out = tables.shape
+    tau = rows.bit_length() - 1
+    if k2 != k or (1 << tau) != rows:
+        raise ValueError("tables must be [k, 2^tau, d_out] with k matching codes")
+    assert codes.dtype == torch.int16
+    assert weights.dtype == torch.float32 and tuple(weights.shape) == (n, k)
+    if y is None:
+        y = torch.empty((n, d_out), dtype=torch.float32, device=tables.device)
+    assert y.dtype == torch.float32 and tuple(y.shape) == (n, d_out)
+    if n == 0:
+        return y
+    with torch.cuda.device(tables.device):
+        _check(lib().lookupffn_gather_weighted(_dev(codes, "codes"), _dev(weights, "weights"),
+                                               _dev(tables, "tables"), _dev(y, "y"), n, k, tau, d_out,
+                                               _dtype_code(tables), _stream(tables)))
+    return y
+
+
 def lookupffn_workspace_bytes(n_tokens: int, k: int) -> int:
     return lib().lookupffn_workspace_bytes(n_tokens, k)
 
 
+def lookupffn_workspace_bytes_weighted(n_tokens: int, k: int) -> int:
+    return lib().lookupffn_workspace_bytes_weighted(n_tokens, k)
+
+
+def lookupffn_forward_weighted(x: torch.Tensor, signs: torch.Tensor, tables: torch.Tensor,
+                               y: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """Whole weighted forward pass y[n, d_out] (Sec. 4 of the paper)."""
+    return lookupffn_forward(x, signs, tables, y, workspace, _entry="lookupffn_forward_weighted")
+
+
 def lookupffn_forward(x: torch.Tensor, signs: torch.Tensor, tables: torch.Tensor,
-                      y: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+                      y: torch.Tensor | None = None, workspace: torch.Tensor | None = None,
+                      _entry: str = "lookupffn_forward") -> torch.Tensor:
     """Whole forward pass y[n, d_out]; `workspace` is an optional uint8 CUDA tensor for the codes."""
     n, d = x.shape
     k, rows, d_out = tables.shape
@@ -158,9 +218,9 @@ def lookupffn_forward(x: torch.Tensor, signs: torch.Tensor, tables: torch.Tensor
     if workspace is not None:
         ws_ptr, ws_bytes = _dev(workspace, "workspace"), workspace.numel() * workspace.element_size()
     with torch.cuda.device(x.device):
-        _check(lib().lookupffn_forward(_dev(x, "x"), _dev(signs, "signs"), _dev(tables, "tables"), _dev(y, "y"),
-                                       n, d, k, tau, d_out, signs.shape[1], _dtype_code(x), _dtype_code(tables),
-                                       ws_ptr, ws_bytes, _stream(x)))
+        _check(getattr(lib(), _entry)(_dev(x, "x"), _dev(signs, "signs"), _dev(tables, "tables"), _dev(y, "y"),
+                                      n, d, k, tau, d_out, signs.shape[1], _dtype_code(x), _dtype_code(tables),
+                                      ws_ptr, ws_bytes, _stream(x)))
     return y
 
 

@@ -1,5 +1,7 @@
 // Gather step of the LookupFFN forward pass for gfx950:
 //   y[t][:] = sum_{j<k} tables[j][code[t][j]][:]        (Sec. 3.1, eq. "lookup")
+// and its weighted form y[t][:] = sum_j w[t][j] * tables[j][code[t][j]][:] (Sec. 4; one fused
+// multiply-add per element and table, in table order).
 //
 // Work decomposition.  A table row is cut into column slices of LPT lanes x 16
 // bytes (LPT = "lanes per token"); a wavefront handles 64/LPT tokens of one
@@ -26,6 +28,7 @@ constexpr int kXcds = 8;
 
 struct GatherArgs {
     const uint16_t *codes;  // [n][k]
+    const float *weights;   // [n][k] for the weighted form, else NULL
     const char *tables;     // [k][rows][d_out] fp32 or bf16
     float *y;               // [n][d_out]
     long long n;
@@ -36,7 +39,7 @@ struct GatherArgs {
     int tb_per_unit;   // token blocks in one unit
     int ntb;           // token blocks in total; a token block = kGatherWaves * (64/LPT) tokens
     int xcd_mode;      // 1: block order is XCD-sliced (see above); 0: plain
-    int codes_vec8;    // 1: k % 8 == 0 and codes 16-byte aligned -> codes read 8 at a time
+    int codes_vec8;    // 1: k % 8 == 0 and codes (and weights) 16-byte aligned -> read 8 at a time
     uint32_t row_bytes;
 };
 
@@ -76,6 +79,25 @@ struct Acc {
             f[3] += __uint_as_float(r.w);
         }
     }
+    // acc += w * row, one rounding per element
+    __device__ __forceinline__ void fma(const uint4 &r, float w)
+    {
+        if constexpr (BF16) {
+            f[0] = __builtin_fmaf(w, __uint_as_float(r.x << 16), f[0]);
+            f[1] = __builtin_fmaf(w, __uint_as_float(r.x & 0xFFFF0000u), f[1]);
+            f[2] = __builtin_fmaf(w, __uint_as_float(r.y << 16), f[2]);
+            f[3] = __builtin_fmaf(w, __uint_as_float(r.y & 0xFFFF0000u), f[3]);
+            f[4] = __builtin_fmaf(w, __uint_as_float(r.z << 16), f[4]);
+            f[5] = __builtin_fmaf(w, __uint_as_float(r.z & 0xFFFF0000u), f[5]);
+            f[6] = __builtin_fmaf(w, __uint_as_float(r.w << 16), f[6]);
+            f[7] = __builtin_fmaf(w, __uint_as_float(r.w & 0xFFFF0000u), f[7]);
+        } else {
+            f[0] = __builtin_fmaf(w, __uint_as_float(r.x), f[0]);
+            f[1] = __builtin_fmaf(w, __uint_as_float(r.y), f[1]);
+            f[2] = __builtin_fmaf(w, __uint_as_float(r.z), f[2]);
+            f[3] = __builtin_fmaf(w, __uint_as_float(r.w), f[3]);
+        }
+    }
 };
 
 __device__ __forceinline__ uint32_t code_of(const uint4 &c, int u)
@@ -84,7 +106,7 @@ __device__ __forceinline__ uint32_t code_of(const uint4 &c, int u)
     return (u & 1) ? (w >> 16) : (w & 0xFFFFu);
 }
 
-template <bool BF16, int LPT>
+template <bool BF16, int LPT, bool WEIGHTED>
 __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a)
 {
     constexpr int TPW = 64 / LPT;  // tokens per wave
@@ -126,7 +148,37 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a)
     acc.zero();
 
     int j0 = 0;
-    if (a.codes_vec8) {
+    if constexpr (WEIGHTED) {
+        const float *wrow = a.weights + t * a.k;
+        if (a.codes_vec8) {
+            const uint4 *c8 = reinterpret_cast<const uint4 *>(crow);
+            const float4 *w4 = reinterpret_cast<const float4 *>(wrow);
+            const int nch = k >> 3;
+            uint4 cn = c8[0];
+            float4 wan = w4[0], wbn = w4[1];
+            for (int ch = 0; ch < nch; ++ch) {
+                const uint4 c = cn;
+                const float4 wa = wan, wb = wbn;
+                const int nx = ch + 1 < nch ? ch + 1 : ch;  // next chunk's codes and weights go out first
+                cn = c8[nx];
+                wan = w4[2 * nx];
+                wbn = w4[2 * nx + 1];
+                uint4 r[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) r[u] = row(ch * 8 + u, code_of(c, u));
+                acc.fma(r[0], wa.x);
+                acc.fma(r[1], wa.y);
+                acc.fma(r[2], wa.z);
+                acc.fma(r[3], wa.w);
+                acc.fma(r[4], wb.x);
+                acc.fma(r[5], wb.y);
+                acc.fma(r[6], wb.z);
+                acc.fma(r[7], wb.w);
+            }
+            j0 = nch * 8;
+        }
+        for (; j0 < k; ++j0) acc.fma(row(j0, crow[j0]), wrow[j0]);
+    } else if (a.codes_vec8) {
         const uint4 *c8 = reinterpret_cast<const uint4 *>(crow);
         const int nch = k >> 3;  // chunks of 8 codes
         int ch = 0;

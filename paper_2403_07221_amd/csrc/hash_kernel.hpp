@@ -32,6 +32,7 @@ struct HashArgs {
     const int8_t *signs;  // [P][R][N]
     uint16_t *codes;      // [n][k], or NULL when `packed` is written instead
     uint32_t *packed;     // packed codes (see above), or NULL
+    float *weights;       // [n][k] gather weights of the weighted variant (Sec. 4), or NULL
     long long n_pad;      // token stride of `packed`
     long long n;
     int d, k, tau, n_rounds, P;
@@ -51,9 +52,16 @@ __host__ __device__ inline int hash_bit_words(int P, int N)
 // 32-bit flip words per (projection, round, lane): bit r = "negate register r"
 __host__ __device__ inline int hash_flip_words(int N) { return N > 2048 ? 2 : 1; }
 
-__host__ inline size_t hash_lds_bytes(int P, int R, int N)
+// Weighted variant: a wave keeps the soft codes z of the current projection (N words) behind a
+// 16-word tail holding the last 16 coordinates of the projections before it, so that a table
+// whose tau <= 16 coordinates straddle a projection boundary is read from one window.
+constexpr int kZTail = 16;
+__host__ __device__ inline int hash_z_words(int N, bool weighted) { return weighted ? N + kZTail : 0; }
+
+__host__ inline size_t hash_lds_bytes(int P, int R, int N, bool weighted = false)
 {
-    return sizeof(uint32_t) * ((size_t)P * R * hash_flip_words(N) * 64 + (size_t)kHashWaves * hash_bit_words(P, N));
+    return sizeof(uint32_t) * ((size_t)P * R * hash_flip_words(N) * 64 +
+                               (size_t)kHashWaves * (hash_bit_words(P, N) + hash_z_words(N, weighted)));
 }
 
 __device__ __forceinline__ float fxor(float v, uint32_t m) { return __uint_as_float(__float_as_uint(v) ^ m); }
@@ -167,7 +175,34 @@ __device__ __forceinline__ void wave_lds_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int LOG2N>
+// Gather weights of the tables whose last coordinate lies in projection p (Sec. 4, the weighted
+// variant used in the paper's experiments): with S_g the sign row that the code selects,
+//   w_j = <z_j, S_g> exp(<z_j, S_g>) / prod_b (exp(z_jb) + exp(-z_jb))
+//       = |z_j|_1 / prod_b (1 + exp(-2 |z_jb|)),
+// the second form being the first with numerator and denominator divided by exp(|z_j|_1); it
+// cannot overflow.  `z_at(c)` returns coordinate c of projection p for 0 <= c < N and coordinate
+// N + c of the concatenation before it for -16 < c < 0.  One lane per table.
+template <class ZAt>
+__device__ __forceinline__ void emit_weights(const HashArgs &a, long long t, int p, int N, unsigned lane, ZAt z_at)
+{
+    const int tau = a.tau;
+    const long long lo = (long long)p * N;
+    const int jlo = (int)(lo / tau);
+    long long jhi = (lo + N) / tau;
+    if (jhi > a.k) jhi = a.k;
+    for (int j = jlo + (int)lane; j < (int)jhi; j += 64) {
+        const int c0 = (int)((long long)j * tau - lo);
+        float s = 0.0f, q = 1.0f;
+        for (int b = 0; b < tau; ++b) {
+            const float az = __builtin_fabsf(z_at(c0 + b));
+            s += az;
+            q *= 1.0f + __builtin_amdgcn_exp2f(az * -2.885390082f);  // exp(-2 az) = 2^(-2 az log2 e)
+        }
+        a.weights[t * a.k + j] = __fdividef(s, q);
+    }
+}
+
+template <int LOG2N, bool WEIGHTED>
 __global__ __launch_bounds__(kHashThreads) void hash_kernel(HashArgs a)
 {
     constexpr int N = 1 << LOG2N;
@@ -197,8 +232,9 @@ __global__ __launch_bounds__(kHashThreads) void hash_kernel(HashArgs a)
         }
         flip[idx] = bits;
     }
-    uint32_t *bitw = lds + n_flip + wave * hash_bit_words(P, N);
     const int n_bitw = hash_bit_words(P, N);
+    uint32_t *bitw = lds + n_flip + wave * (n_bitw + hash_z_words(N, WEIGHTED));
+    float *zwin = reinterpret_cast<float *>(bitw + n_bitw);  // [kZTail tail][N current projection]
     for (int i = (int)lane; i < n_bitw; i += 64) bitw[i] = 0;
     __syncthreads();
 
@@ -268,6 +304,24 @@ __global__ __launch_bounds__(kHashThreads) void hash_kernel(HashArgs a)
                     bitw[bit >> 5] |= keep << (bit & 31);
                 }
             }
+
+            // ---- weighted variant: weights of the tables that end in this projection ----
+            if constexpr (WEIGHTED) {
+#pragma unroll
+                for (int r = 0; r < NREG; ++r)
+                    if ((int)lane + 64 * r < N) zwin[kZTail + (int)lane + 64 * r] = v[r];
+                wave_lds_fence();
+                emit_weights(a, t, p, N, lane, [&](int c) { return zwin[kZTail + c]; });
+                if (p + 1 < P) {
+                    // slide the tail: it becomes the last 16 coordinates up to the end of projection p
+                    wave_lds_fence();
+                    float keep = 0.0f;
+                    if (lane < kZTail) keep = zwin[(int)lane + N];
+                    wave_lds_fence();
+                    if (lane < kZTail) zwin[lane] = keep;
+                }
+                wave_lds_fence();
+            }
         }
         wave_lds_fence();
 
@@ -315,15 +369,21 @@ __global__ __launch_bounds__(kHashThreads) void hash_kernel(HashArgs a)
 // one 16-byte load); the token's row is one contiguous 64-byte run per lane.
 constexpr int kH1024TransposeWords = 1024;
 
-__host__ __device__ inline int h1024_wave_words(int P) { return kH1024TransposeWords + hash_bit_words(P, 1024); }
-__host__ inline size_t h1024_lds_bytes(int P) { return sizeof(uint32_t) * (size_t)kHashWaves * h1024_wave_words(P); }
+__host__ __device__ inline int h1024_wave_words(int P, bool weighted)
+{
+    return kH1024TransposeWords + hash_bit_words(P, 1024) + (weighted ? kZTail : 0);
+}
+__host__ inline size_t h1024_lds_bytes(int P, bool weighted = false)
+{
+    return sizeof(uint32_t) * (size_t)kHashWaves * h1024_wave_words(P, weighted);
+}
 
 typedef __attribute__((address_space(3))) uint32_t lds_u32;
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) u32x4_t lds_u32x4;
 typedef __attribute__((address_space(3))) uint16_t lds_u16;
 
-template <int R>
+template <int R, bool WEIGHTED>
 __global__ __launch_bounds__(kHashThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void hash1024_kernel(HashArgs a)
 {
     constexpr int N = 1024, NREG = 16;
@@ -331,9 +391,10 @@ __global__ __launch_bounds__(kHashThreads) __attribute__((amdgpu_waves_per_eu(4,
     const unsigned lane = threadIdx.x & 63u;
     const unsigned wave = threadIdx.x >> 6;
     const int P = a.P;
-    uint32_t *tp = lds + wave * h1024_wave_words(P);  // transpose area, then the bit string
+    uint32_t *tp = lds + wave * h1024_wave_words(P, WEIGHTED);  // transpose area, the bit string, the z tail
     uint32_t *bitw = tp + kH1024TransposeWords;
     const int n_bitw = hash_bit_words(P, N);
+    float *ztail = reinterpret_cast<float *>(bitw + n_bitw);
     for (int i = (int)lane; i < n_bitw; i += 64) bitw[i] = 0;
 
     // LDS byte addresses (32-bit LDS pointers) of this lane's pieces in both layouts
@@ -478,6 +539,28 @@ __global__ __launch_bounds__(kHashThreads) __attribute__((amdgpu_waves_per_eu(4,
                 lds_u16 *dst = reinterpret_cast<lds_u16 *>((uintptr_t)((uint32_t)(uintptr_t)bitw + 2u * (p * 64 + lane * 16)));
 #pragma unroll
                 for (int r = 0; r < NREG; ++r) dst[r] = (uint16_t)(msk[r] >> (16 * lane));
+            }
+
+            // ---- weighted variant: z of this projection into the transpose area (coordinate i at
+            // word sigma(i)), then the weights of the tables that end in this projection.
+            if constexpr (WEIGHTED) {
+                wave_lds_fence();
+#pragma unroll
+                for (int r = 0; r < NREG; ++r) *reinterpret_cast<lds_u32 *>((uintptr_t)adrB[r]) = __float_as_uint(v[r]);
+                wave_lds_fence();
+                auto z_at = [&](int c) -> float {
+                    if (c < 0) return ztail[kZTail + c];
+                    return __uint_as_float(tp[c ^ ((c >> 4) & 0x3C)]);
+                };
+                emit_weights(a, t, p, N, lane, z_at);
+                if (p + 1 < P) {
+                    wave_lds_fence();
+                    float keep = 0.0f;
+                    if (lane < kZTail) keep = z_at(N - kZTail + (int)lane);
+                    wave_lds_fence();
+                    if (lane < kZTail) ztail[lane] = keep;
+                }
+                wave_lds_fence();
             }
         }
         wave_lds_fence();

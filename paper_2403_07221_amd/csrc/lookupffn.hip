@@ -121,7 +121,7 @@ int own_workspace(size_t need, void **out)
 
 // ---------------------------------------------------------------- validation
 int check_hash(const void *x, const int8_t *signs, const uint16_t *codes, int64_t n, int d, int k,
-               int tau, int n_rounds, int x_dtype)
+               int tau, int n_rounds, int x_dtype, bool weighted = false)
 {
     if (!x || !signs || !codes) return LFFN_E_NULL;
     if (n < 0 || d < 1 || k < 1 || n_rounds < 1) return LFFN_E_SIZE;
@@ -132,8 +132,15 @@ int check_hash(const void *x, const int8_t *signs, const uint16_t *codes, int64_
     const int N = 1 << log2_pad(d);
     const int64_t P = ((int64_t)k * tau + N - 1) / N;
     if (P > 4096) return LFFN_E_SIZE;
-    if (hash_lds_bytes((int)P, n_rounds, N) > 64 * 1024) return LFFN_E_UNSUPPORTED;
+    if (hash_lds_bytes((int)P, n_rounds, N, weighted) > 64 * 1024) return LFFN_E_UNSUPPORTED;
     if (!aligned(x, x_dtype == LFFN_F32 ? 4 : 2) || !aligned(codes, 2)) return LFFN_E_ALIGN;
+    return LFFN_OK;
+}
+
+int check_weights(const float *weights)
+{
+    if (!weights) return LFFN_E_NULL;
+    if (!aligned(weights, 4)) return LFFN_E_ALIGN;
     return LFFN_OK;
 }
 
@@ -157,12 +164,25 @@ int check_gather(const uint16_t *codes, const void *tables, const float *y, int6
 template <int L>
 void launch_hash_t(const HashArgs &a, dim3 grid, size_t lds, hipStream_t s)
 {
-    hipLaunchKernelGGL(hash_kernel<L>, grid, dim3(kHashThreads), lds, s, a);
+    if (a.weights)
+        hipLaunchKernelGGL((hash_kernel<L, true>), grid, dim3(kHashThreads), lds, s, a);
+    else
+        hipLaunchKernelGGL((hash_kernel<L, false>), grid, dim3(kHashThreads), lds, s, a);
 }
 
-// Writes codes[n][k] when `codes` is given, else the packed layout of the LDS-staged gather.
-int launch_hash(const void *x, const int8_t *signs, uint16_t *codes, uint32_t *packed, int64_t n, int d, int k,
-                int tau, int n_rounds, int x_dtype, hipStream_t s)
+template <int R>
+void launch_hash1024_t(const HashArgs &a, dim3 grid, size_t lds, hipStream_t s)
+{
+    if (a.weights)
+        hipLaunchKernelGGL((hash1024_kernel<R, true>), grid, dim3(kHashThreads), lds, s, a);
+    else
+        hipLaunchKernelGGL((hash1024_kernel<R, false>), grid, dim3(kHashThreads), lds, s, a);
+}
+
+// Writes codes[n][k] when `codes` is given, else the packed layout of the LDS-staged gather;
+// with `weights` also the gather weights [n][k] of the weighted variant.
+int launch_hash(const void *x, const int8_t *signs, uint16_t *codes, uint32_t *packed, float *weights, int64_t n,
+                int d, int k, int tau, int n_rounds, int x_dtype, hipStream_t s)
 {
     const int L = log2_pad(d);
     const int N = 1 << L;
@@ -171,6 +191,7 @@ int launch_hash(const void *x, const int8_t *signs, uint16_t *codes, uint32_t *p
     a.signs = signs;
     a.codes = codes;
     a.packed = codes ? nullptr : packed;
+    a.weights = weights;
     a.n_pad = packed_n_pad(n);
     a.n = n;
     a.d = d;
@@ -184,24 +205,26 @@ int launch_hash(const void *x, const int8_t *signs, uint16_t *codes, uint32_t *p
     // d_pad = 1024 with up to four rounds: the two-layout kernel (needs 16-byte aligned signs, and
     // rows that start on 16-byte boundaries when it loads them as vectors)
     const size_t xrow = (size_t)d * (a.x_bf16 ? 2 : 4);
-    if (g_opt.hash_path != 1 && L == 10 && n_rounds <= 4 && aligned(signs, 16) && h1024_lds_bytes(a.P) <= 64 * 1024 &&
+    const bool weighted = weights != nullptr;
+    if (g_opt.hash_path != 1 && L == 10 && n_rounds <= 4 && aligned(signs, 16) &&
+        h1024_lds_bytes(a.P, weighted) <= 64 * 1024 &&
         (d % 4 != 0 || (aligned(x, 16) && xrow % (a.x_bf16 ? 8 : 16) == 0))) {
         int64_t blocks = (n + kHashWaves - 1) / kHashWaves;
         const int64_t cap = g_opt.hash_blocks ? g_opt.hash_blocks : 4096;
         if (blocks > cap) blocks = cap;
         const dim3 grid((unsigned)blocks);
-        const size_t lds = h1024_lds_bytes(a.P);
+        const size_t lds = h1024_lds_bytes(a.P, weighted);
         switch (n_rounds) {
-            case 1: hipLaunchKernelGGL(hash1024_kernel<1>, grid, dim3(kHashThreads), lds, s, a); break;
-            case 2: hipLaunchKernelGGL(hash1024_kernel<2>, grid, dim3(kHashThreads), lds, s, a); break;
-            case 3: hipLaunchKernelGGL(hash1024_kernel<3>, grid, dim3(kHashThreads), lds, s, a); break;
-            default: hipLaunchKernelGGL(hash1024_kernel<4>, grid, dim3(kHashThreads), lds, s, a); break;
+            case 1: launch_hash1024_t<1>(a, grid, lds, s); break;
+            case 2: launch_hash1024_t<2>(a, grid, lds, s); break;
+            case 3: launch_hash1024_t<3>(a, grid, lds, s); break;
+            default: launch_hash1024_t<4>(a, grid, lds, s); break;
         }
         LFFN_HIP(hipGetLastError());
         tl.done();
         return LFFN_OK;
     }
-    const size_t lds = hash_lds_bytes(a.P, n_rounds, N);
+    const size_t lds = hash_lds_bytes(a.P, n_rounds, N, weighted);
     int64_t blocks = (n + kHashWaves - 1) / kHashWaves;
     if (blocks > 2048) blocks = 2048;
     const dim3 grid((unsigned)blocks);
@@ -220,7 +243,10 @@ int launch_hash(const void *x, const int8_t *signs, uint16_t *codes, uint32_t *p
 template <bool BF16, int LPT>
 void launch_gather_t(const GatherArgs &a, dim3 grid, hipStream_t s)
 {
-    hipLaunchKernelGGL((gather_kernel<BF16, LPT>), grid, dim3(kGatherThreads), 0, s, a);
+    if (a.weights)
+        hipLaunchKernelGGL((gather_kernel<BF16, LPT, true>), grid, dim3(kGatherThreads), 0, s, a);
+    else
+        hipLaunchKernelGGL((gather_kernel<BF16, LPT, false>), grid, dim3(kGatherThreads), 0, s, a);
 }
 
 template <bool BF16>
@@ -376,13 +402,14 @@ int launch_gather_lds(const LdsPlan &p, const uint32_t *packed, const void *tabl
 
 int64_t packed_bytes(int64_t n, int k) { return ((int64_t)(k + 1) / 2) * packed_n_pad(n) * 4; }
 
-int launch_gather_direct(const uint16_t *codes, const void *tables, float *y, int64_t n, int k, int tau,
-                         int d_out, int table_dtype, hipStream_t s)
+int launch_gather_direct(const uint16_t *codes, const float *weights, const void *tables, float *y, int64_t n,
+                         int k, int tau, int d_out, int table_dtype, hipStream_t s)
 {
     const bool bf16 = table_dtype == LFFN_BF16;
     const int esz = bf16 ? 2 : 4;
     GatherArgs a;
     a.codes = codes;
+    a.weights = weights;
     a.tables = static_cast<const char *>(tables);
     a.y = y;
     a.n = n;
@@ -391,7 +418,7 @@ int launch_gather_direct(const uint16_t *codes, const void *tables, float *y, in
     a.d_out = d_out;
     a.row_bytes = (uint32_t)d_out * esz;
     a.nvec = (int)(a.row_bytes / 16);
-    a.codes_vec8 = (k % 8 == 0) && aligned(codes, 16);
+    a.codes_vec8 = (k % 8 == 0) && aligned(codes, 16) && (!weights || aligned(weights, 16));
 
     int lpt = g_opt.lanes_per_token;
     if (lpt == 0) {
@@ -432,6 +459,9 @@ int launch_gather_direct(const uint16_t *codes, const void *tables, float *y, in
     return LFFN_OK;
 }
 
+// workspace of the weighted forward pass: codes [n][k] uint16, then weights [n][k] fp32
+int64_t weighted_codes_bytes(int64_t n, int k) { return ((int64_t)n * k * 2 + 255) & ~int64_t(255); }
+
 }  // namespace
 
 extern "C" {
@@ -441,8 +471,62 @@ int lookupffn_hash(const void *x, const int8_t *signs, uint16_t *codes, int64_t 
 {
     int rc = check_hash(x, signs, codes, n_tokens, d, k, tau, n_rounds, x_dtype);
     if (rc != LFFN_OK || n_tokens == 0) return rc;
-    return launch_hash(x, signs, codes, nullptr, n_tokens, d, k, tau, n_rounds, x_dtype,
+    return launch_hash(x, signs, codes, nullptr, nullptr, n_tokens, d, k, tau, n_rounds, x_dtype,
                        static_cast<hipStream_t>(hip_stream));
+}
+
+int lookupffn_hash_weighted(const void *x, const int8_t *signs, uint16_t *codes, float *weights, int64_t n_tokens,
+                            int d, int k, int tau, int n_rounds, int x_dtype, void *hip_stream)
+{
+    int rc = check_hash(x, signs, codes, n_tokens, d, k, tau, n_rounds, x_dtype, true);
+    if (rc == LFFN_OK) rc = check_weights(weights);
+    if (rc != LFFN_OK || n_tokens == 0) return rc;
+    return launch_hash(x, signs, codes, nullptr, weights, n_tokens, d, k, tau, n_rounds, x_dtype,
+                       static_cast<hipStream_t>(hip_stream));
+}
+
+int lookupffn_gather_weighted(const uint16_t *codes, const float *weights, const void *tables, float *y,
+                              int64_t n_tokens, int k, int tau, int d_out, int table_dtype, void *hip_stream)
+{
+    int rc = check_gather(codes, tables, y, n_tokens, k, tau, d_out, table_dtype);
+    if (rc == LFFN_OK) rc = check_weights(weights);
+    if (rc != LFFN_OK || n_tokens == 0) return rc;
+    return launch_gather_direct(codes, weights, tables, y, n_tokens, k, tau, d_out, table_dtype,
+                                static_cast<hipStream_t>(hip_stream));
+}
+
+int64_t lookupffn_workspace_bytes_weighted(int64_t n_tokens, int k)
+{
+    if (n_tokens <= 0 || k < 1) return 0;
+    return weighted_codes_bytes(n_tokens, k) + (((int64_t)n_tokens * k * 4 + 255) & ~int64_t(255));
+}
+
+int lookupffn_forward_weighted(const void *x, const int8_t *signs, const void *tables, float *y, int64_t n_tokens,
+                               int d, int k, int tau, int d_out, int n_rounds, int x_dtype, int table_dtype,
+                               void *workspace, int64_t workspace_bytes, void *hip_stream)
+{
+    const uint16_t *stand_in = reinterpret_cast<const uint16_t *>(uintptr_t(256));
+    int rc = check_hash(x, signs, stand_in, n_tokens, d, k, tau, n_rounds, x_dtype, true);
+    if (rc != LFFN_OK) return rc;
+    rc = check_gather(stand_in, tables, y, n_tokens, k, tau, d_out, table_dtype);
+    if (rc != LFFN_OK) return rc;
+    const int64_t need = lookupffn_workspace_bytes_weighted(n_tokens, k);
+    if (workspace) {
+        if (workspace_bytes < need) return LFFN_E_WORKSPACE;
+        if (!aligned(workspace, 256)) return LFFN_E_ALIGN;
+    }
+    if (n_tokens == 0) return LFFN_OK;
+    void *ws = workspace;
+    if (!ws) {
+        rc = own_workspace((size_t)need, &ws);
+        if (rc != LFFN_OK) return rc;
+    }
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    uint16_t *codes = static_cast<uint16_t *>(ws);
+    float *weights = reinterpret_cast<float *>(static_cast<char *>(ws) + weighted_codes_bytes(n_tokens, k));
+    rc = launch_hash(x, signs, codes, nullptr, weights, n_tokens, d, k, tau, n_rounds, x_dtype, s);
+    if (rc != LFFN_OK) return rc;
+    return launch_gather_direct(codes, weights, tables, y, n_tokens, k, tau, d_out, table_dtype, s);
 }
 
 int lookupffn_gather(const uint16_t *codes, const void *tables, float *y, int64_t n_tokens, int k, int tau,
@@ -469,7 +553,7 @@ int lookupffn_gather(const uint16_t *codes, const void *tables, float *y, int64_
         LFFN_HIP(hipGetLastError());
         return launch_gather_lds(plan, packed, tables, y, bf16, s);
     }
-    return launch_gather_direct(codes, tables, y, n_tokens, k, tau, d_out, table_dtype, s);
+    return launch_gather_direct(codes, nullptr, tables, y, n_tokens, k, tau, d_out, table_dtype, s);
 }
 
 int64_t lookupffn_workspace_bytes(int64_t n_tokens, int k)
@@ -509,14 +593,14 @@ int lookupffn_forward(const void *x, const int8_t *signs, const void *tables, fl
     if (rc != LFFN_OK) return rc;
     if (plan.use) {
         uint32_t *packed = static_cast<uint32_t *>(ws);
-        rc = launch_hash(x, signs, nullptr, packed, n_tokens, d, k, tau, n_rounds, x_dtype, s);
+        rc = launch_hash(x, signs, nullptr, packed, nullptr, n_tokens, d, k, tau, n_rounds, x_dtype, s);
         if (rc != LFFN_OK) return rc;
         return launch_gather_lds(plan, packed, tables, y, bf16, s);
     }
     uint16_t *codes = static_cast<uint16_t *>(ws);
-    rc = launch_hash(x, signs, codes, nullptr, n_tokens, d, k, tau, n_rounds, x_dtype, s);
+    rc = launch_hash(x, signs, codes, nullptr, nullptr, n_tokens, d, k, tau, n_rounds, x_dtype, s);
     if (rc != LFFN_OK) return rc;
-    return launch_gather_direct(codes, tables, y, n_tokens, k, tau, d_out, table_dtype, s);
+    return launch_gather_direct(codes, nullptr, tables, y, n_tokens, k, tau, d_out, table_dtype, s);
 }
 
 int lookupffn_release_workspace(void)

@@ -87,6 +87,26 @@ def test_forward_argument_errors(L):
     assert forward_call(L, n=1000, ws=FAKE + 16, wsb=need) == -5
 
 
+def test_weighted_argument_errors(L):
+    def hw(x=FAKE, signs=FAKE, codes=FAKE, w=FAKE, n=0, d=768, k=96, tau=8, rounds=3, dt=0):
+        return L.lookupffn_hash_weighted(x, signs, codes, w, n, d, k, tau, rounds, dt, None)
+
+    def gw(codes=FAKE, w=FAKE, tables=FAKE, y=FAKE, n=0, k=96, tau=8, d_out=768, dt=0):
+        return L.lookupffn_gather_weighted(codes, w, tables, y, n, k, tau, d_out, dt, None)
+
+    def fw(x=FAKE, tables=FAKE, y=FAKE, n=0, d=768, tau=8, ws=None, wsb=0):
+        return L.lookupffn_forward_weighted(x, FAKE, tables, y, n, d, 96, tau, 768, 3, 0, 0, ws, wsb, None)
+
+    assert hw() == 0 and gw() == 0 and fw() == 0                      # empty batch: successful no-op
+    assert hw(w=None) == -1 and hw(x=None) == -1 and hw(w=FAKE + 2) == -5 and hw(tau=17) == -3
+    assert hw(d=4096, k=512) == -6 and hw(d=2048, k=256) == 0         # working set of the widest transform
+    assert gw(w=None) == -1 and gw(codes=None) == -1 and gw(w=FAKE + 1) == -5 and gw(d_out=770) == -5
+    assert fw(x=None) == -1 and fw(tau=0) == -3 and fw(d=4096) == -6
+    need = L.lookupffn_workspace_bytes_weighted(1000, 96)
+    assert need >= 1000 * 96 * 6 and need % 256 == 0 and L.lookupffn_workspace_bytes_weighted(0, 96) == 0
+    assert fw(n=1000, ws=FAKE, wsb=need - 1) == -7 and fw(n=1000, ws=FAKE + 16, wsb=need) == -5
+
+
 def test_options(L):
     assert L.lookupffn_set_option(b"lanes_per_token", 16) == 0
     assert L.lookupffn_set_option(b"lanes_per_token", 3) == -2
