@@ -23,6 +23,12 @@
 // stage would hold every wave at the texture-address queue while LDS and the
 // vector ALU sit idle.
 //
+// Weighted form (Sec. 4: y = sum_j w_j T_j[code_j]): the fp32 weights come table-major and
+// token-contiguous (wpk[j][n_pad]).  The eight lanes of a token would all hold the same weight, so
+// each lane keeps only the weights of the token slots i with i % 4 == its position in its quad
+// and the multiply-add takes the weight through a DPP quad broadcast: a quarter of the registers
+// and load instructions.
+//
 // Work distribution is static and XCD-aware: slice-units are dealt to the
 // eight XCDs round-robin (block b runs on XCD b % 8), and the workgroups of
 // one XCD split its units' token ranges evenly, so every CU gets one chunk of
@@ -48,6 +54,7 @@ constexpr int kLdsMaxTok = 16;               // token slots per lane the packed 
 
 struct GatherLdsArgs {
     const uint32_t *packed;  // [k/2][n_pad] packed codes (see hash_kernel.hpp)
+    const float *wpk;        // [k][n_pad] weights (weighted form only)
     long long n_pad;
     const char *tables;
     float *y;
@@ -86,8 +93,19 @@ __device__ __forceinline__ void lds_dma16(const char *gbase, uint32_t voff, uint
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// value of `v` in lane Q of the caller's quad (DPP quad_perm [Q,Q,Q,Q])
+template <int Q>
+__device__ __forceinline__ float quad_bcast(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), Q * 0x55, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float quad_bcast(float v, int q)
+{
+    return q == 0 ? quad_bcast<0>(v) : q == 1 ? quad_bcast<1>(v) : q == 2 ? quad_bcast<2>(v) : quad_bcast<3>(v);
+}
+
 // FR = rounds of 128 rows per table slice: 1 (tau = 7) or 2 (tau = 8)
-template <bool BF16, int TOK, int FR>
+template <bool BF16, int TOK, int FR, bool WEIGHTED>
 __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a)
 {
     static_assert(TOK <= kLdsMaxTok, "packed-code padding covers 16 token slots");
@@ -164,9 +182,19 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
                 cr[i] = *reinterpret_cast<const uint32_t *>(base + i * (kLdsGroups * 4) + g4);
             };
 
+            // weights of table u of stage s for token slots 4m + (lane's position in its quad)
+            constexpr int WQ = (TOK + 3) / 4;
+            const uint32_t lw = (q & 3u) * (kLdsGroups * 4u) + g4;
+            auto load_weight = [&](uint32_t s, int u, int m, float(&wr)[kLdsTps][WQ]) {
+                const char *base = reinterpret_cast<const char *>(a.wpk) +
+                                   ((size_t)(s * kLdsTps + (uint32_t)u) * a.n_pad + c0) * 4u;  // uniform
+                wr[u][m] = *reinterpret_cast<const float *>(base + m * (4 * kLdsGroups * 4) + lw);
+            };
+
             // codes of a stage's two tables per token slot; two sets so that the next stage's codes
             // load while the current stage is consumed
             uint32_t crA[TOK], crB[TOK];
+            float wA[kLdsTps][WQ], wB[kLdsTps][WQ];
             Acc<BF16> acc[TOK];
 #pragma unroll
             for (int i = 0; i < TOK; ++i) acc[i].zero();
@@ -177,12 +205,15 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
             // One stage: consume buffer b with codes `cr`; meanwhile start stage s+1 (rows -> buffer
             // b^1, codes -> cr_next), its vector-memory instructions spread over the read batches.
             auto run_stage = [&](auto more_tag, uint32_t s, uint32_t b, const uint32_t(&cr)[TOK],
-                                 uint32_t(&cr_next)[TOK]) {
+                                 uint32_t(&cr_next)[TOK], const float(&w)[kLdsTps][WQ],
+                                 float(&w_next)[kLdsTps][WQ]) {
                 constexpr bool MORE = decltype(more_tag)::value;
                 constexpr int RB = LFFN_LDS_RB;              // row reads per batch
                 constexpr int NB = (TOK + RB - 1) / RB;      // batches per table
                 constexpr int NBT = kLdsTps * NB;            // batches per stage
                 constexpr int CPB = (TOK + NBT - 1) / NBT;   // code loads per batch
+                constexpr int NWL = kLdsTps * WQ;            // weight loads per stage
+                constexpr int WPB = (NWL + NBT - 1) / NBT;   // weight loads per batch
                 static_assert(NBT >= kLdsTps * FR, "one row-copy instruction per batch");
                 uint4 r[2][RB];
                 auto issue = [&](int bi, uint4(&dst)[RB]) {  // bi = u * NB + batch within table u
@@ -198,11 +229,14 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
                         }
                 };
                 auto consume = [&](int bi, const uint4(&src)[RB]) {
-                    const int b0 = (bi % NB) * RB;
+                    const int u = bi / NB, b0 = (bi % NB) * RB;
 #pragma unroll
                     for (int i = 0; i < RB; ++i)
                         if (b0 + i < TOK) {
-                            acc[b0 + i].add(src[i]);
+                            if constexpr (WEIGHTED)
+                                acc[b0 + i].fma(src[i], quad_bcast(w[u][(b0 + i) >> 2], (b0 + i) & 3));
+                            else
+                                acc[b0 + i].add(src[i]);
                             acc[b0 + i].pin();
                         }
                 };
@@ -215,6 +249,12 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
 #pragma unroll
                         for (int cI = 0; cI < CPB; ++cI)
                             if (bi * CPB + cI < TOK) load_code(s + 1, bi * CPB + cI, cr_next);
+                        if constexpr (WEIGHTED) {
+#pragma unroll
+                            for (int wI = 0; wI < WPB; ++wI)
+                                if (bi * WPB + wI < NWL)
+                                    load_weight(s + 1, (bi * WPB + wI) / WQ, (bi * WPB + wI) % WQ, w_next);
+                        }
                     }
                     consume(bi, r[bi & 1]);
                 }
@@ -229,20 +269,24 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
             for (int idx = 0; idx < kLdsTps * FR; ++idx) fill_piece(0, 0, idx);
 #pragma unroll
             for (int i = 0; i < TOK; ++i) load_code(0, i, crA);
+            if constexpr (WEIGHTED) {
+#pragma unroll
+                for (int i = 0; i < kLdsTps * WQ; ++i) load_weight(0, i / WQ, i % WQ, wA);
+            }
             __builtin_amdgcn_s_waitcnt(0x0F70);
             __syncthreads();
 
             // all stages but the last start their successor; buffers and code sets alternate
             uint32_t s = 0;
             for (; s + 2 < nstages; s += 2) {
-                run_stage(yes{}, s, 0u, crA, crB);
-                run_stage(yes{}, s + 1, 1u, crB, crA);
+                run_stage(yes{}, s, 0u, crA, crB, wA, wB);
+                run_stage(yes{}, s + 1, 1u, crB, crA, wB, wA);
             }
             if (s + 1 < nstages) {
-                run_stage(yes{}, s, 0u, crA, crB);
-                run_stage(no{}, s + 1, 1u, crB, crA);
+                run_stage(yes{}, s, 0u, crA, crB, wA, wB);
+                run_stage(no{}, s + 1, 1u, crB, crA, wB, wA);
             } else {
-                run_stage(no{}, s, 0u, crA, crB);
+                run_stage(no{}, s, 0u, crA, crB, wA, wB);
             }
 
             if (vec_ok) {

@@ -33,6 +33,7 @@ struct HashArgs {
     uint16_t *codes;      // [n][k], or NULL when `packed` is written instead
     uint32_t *packed;     // packed codes (see above), or NULL
     float *weights;       // [n][k] gather weights of the weighted variant (Sec. 4), or NULL
+    float *wpk;           // the same weights table-major, [k][n_pad], for the LDS-staged gather, or NULL
     long long n_pad;      // token stride of `packed`
     long long n;
     int d, k, tau, n_rounds, P;
@@ -198,7 +199,11 @@ __device__ __forceinline__ void emit_weights(const HashArgs &a, long long t, int
             s += az;
             q *= 1.0f + __builtin_amdgcn_exp2f(az * -2.885390082f);  // exp(-2 az) = 2^(-2 az log2 e)
         }
-        a.weights[t * a.k + j] = __fdividef(s, q);
+        const float w = __fdividef(s, q);
+        if (a.wpk)
+            a.wpk[(long long)j * a.n_pad + t] = w;
+        else
+            a.weights[t * a.k + j] = w;
     }
 }
 
@@ -587,6 +592,18 @@ __global__ __launch_bounds__(kHashThreads) __attribute__((amdgpu_waves_per_eu(4,
     if (a.packed) {
         for (long long t = a.n + gw; t < a.n_pad; t += n_waves)
             for (int s = (int)lane; s < a.k / 2; s += 64) a.packed[(long long)s * a.n_pad + t] = 0u;
+    }
+}
+
+// ABI weights [n][k] -> table-major [k][n_pad] (token padding left as it is: those slots are never stored)
+__global__ __launch_bounds__(256) void repack_weights_kernel(const float *weights, float *wpk, long long n,
+                                                             long long n_pad, int k)
+{
+    const long long total = (long long)k * n;
+    for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+         idx += (long long)gridDim.x * blockDim.x) {
+        const long long j = idx / n, t = idx - j * n;
+        wpk[j * n_pad + t] = weights[t * k + j];
     }
 }
 

@@ -164,7 +164,7 @@ int check_gather(const uint16_t *codes, const void *tables, const float *y, int6
 template <int L>
 void launch_hash_t(const HashArgs &a, dim3 grid, size_t lds, hipStream_t s)
 {
-    if (a.weights)
+    if (a.weights || a.wpk)
         hipLaunchKernelGGL((hash_kernel<L, true>), grid, dim3(kHashThreads), lds, s, a);
     else
         hipLaunchKernelGGL((hash_kernel<L, false>), grid, dim3(kHashThreads), lds, s, a);
@@ -173,14 +173,15 @@ void launch_hash_t(const HashArgs &a, dim3 grid, size_t lds, hipStream_t s)
 template <int R>
 void launch_hash1024_t(const HashArgs &a, dim3 grid, size_t lds, hipStream_t s)
 {
-    if (a.weights)
+    if (a.weights || a.wpk)
         hipLaunchKernelGGL((hash1024_kernel<R, true>), grid, dim3(kHashThreads), lds, s, a);
     else
         hipLaunchKernelGGL((hash1024_kernel<R, false>), grid, dim3(kHashThreads), lds, s, a);
 }
 
 // Writes codes[n][k] when `codes` is given, else the packed layout of the LDS-staged gather;
-// with `weights` also the gather weights [n][k] of the weighted variant.
+// with `weights` also the gather weights of the weighted variant ([n][k] beside `codes`,
+// table-major [k][n_pad] beside `packed`).
 int launch_hash(const void *x, const int8_t *signs, uint16_t *codes, uint32_t *packed, float *weights, int64_t n,
                 int d, int k, int tau, int n_rounds, int x_dtype, hipStream_t s)
 {
@@ -191,7 +192,8 @@ int launch_hash(const void *x, const int8_t *signs, uint16_t *codes, uint32_t *p
     a.signs = signs;
     a.codes = codes;
     a.packed = codes ? nullptr : packed;
-    a.weights = weights;
+    a.weights = codes ? weights : nullptr;
+    a.wpk = codes ? nullptr : weights;
     a.n_pad = packed_n_pad(n);
     a.n = n;
     a.d = d;
@@ -287,10 +289,10 @@ int device_cus(int *cus)
     return LFFN_OK;
 }
 
-template <bool BF16, int TOK, int FR>
+template <bool BF16, int TOK, int FR, bool WEIGHTED>
 int launch_gather_lds_fr(const GatherLdsArgs &a, dim3 grid, size_t lds, hipStream_t s)
 {
-    auto kern = gather_lds_kernel<BF16, TOK, FR>;
+    auto kern = gather_lds_kernel<BF16, TOK, FR, WEIGHTED>;
     static std::mutex mu;
     static std::map<int, size_t> configured;  // device -> LDS bytes the kernel is set up for
     int dev = 0;
@@ -307,11 +309,11 @@ int launch_gather_lds_fr(const GatherLdsArgs &a, dim3 grid, size_t lds, hipStrea
     return LFFN_OK;
 }
 
-template <bool BF16, int TOK>
+template <bool BF16, int TOK, bool WEIGHTED = false>
 int launch_gather_lds_t(const GatherLdsArgs &a, dim3 grid, size_t lds, hipStream_t s)
 {
-    return a.tau == 8 ? launch_gather_lds_fr<BF16, TOK, 2>(a, grid, lds, s)
-                      : launch_gather_lds_fr<BF16, TOK, 1>(a, grid, lds, s);
+    return a.tau == 8 ? launch_gather_lds_fr<BF16, TOK, 2, WEIGHTED>(a, grid, lds, s)
+                      : launch_gather_lds_fr<BF16, TOK, 1, WEIGHTED>(a, grid, lds, s);
 }
 
 // Largest number of tokens a workgroup gets in one piece, mirroring the kernel's split.
@@ -333,10 +335,11 @@ struct LdsPlan {
     size_t lds = 0;
 };
 
-int plan_gather_lds(int64_t n, int k, int tau, int d_out, bool bf16, LdsPlan *p)
+int plan_gather_lds(int64_t n, int k, int tau, int d_out, bool bf16, LdsPlan *p, bool weighted = false)
 {
     p->use = false;
     if (g_opt.gather_path == 1) return LFFN_OK;
+    if (weighted && bf16) return LFFN_OK;  // the weighted staged kernel is built for fp32 tables
     const int rows = 1 << tau;
     if ((tau != 7 && tau != 8) || k % 2 != 0) return LFFN_OK;  // table slices of 128 or 256 rows
     // the kernel indexes tokens and bytes inside one table with 32 bits
@@ -358,7 +361,7 @@ int plan_gather_lds(int64_t n, int k, int tau, int d_out, bool bf16, LdsPlan *p)
     a.n_units = a.n_slices * a.token_splits;
     a.blocks_per_xcd = cus / kXcds;
     const int64_t tpb = lds_tokens_per_block(n, a.n_units, a.token_splits, a.blocks_per_xcd);
-    const int tok_max = bf16 ? 8 : 13;
+    const int tok_max = bf16 ? 8 : weighted ? 12 : 13;
     const int64_t nchunks = (tpb + (int64_t)kLdsGroups * tok_max - 1) / ((int64_t)kLdsGroups * tok_max);
     const int64_t chunk = (tpb + nchunks - 1) / nchunks;
     // Staging pays only when a chunk re-uses each staged row a few times.  With bf16 rows the
@@ -373,17 +376,22 @@ int plan_gather_lds(int64_t n, int k, int tau, int d_out, bool bf16, LdsPlan *p)
     return LFFN_OK;
 }
 
-int launch_gather_lds(const LdsPlan &p, const uint32_t *packed, const void *tables, float *y, bool bf16,
-                      hipStream_t s)
+int launch_gather_lds(const LdsPlan &p, const uint32_t *packed, const float *wpk, const void *tables, float *y,
+                      bool bf16, hipStream_t s)
 {
     GatherLdsArgs a = p.a;
     a.packed = packed;
+    a.wpk = wpk;
     a.tables = static_cast<const char *>(tables);
     a.y = y;
     const dim3 grid(p.grid);
     int rc = LFFN_E_UNSUPPORTED;
     TimedLaunch tl(1, s);
-    if (bf16) {
+    if (wpk) {
+        if (p.tok <= 4) rc = launch_gather_lds_t<false, 4, true>(a, grid, p.lds, s);
+        else if (p.tok <= 8) rc = launch_gather_lds_t<false, 8, true>(a, grid, p.lds, s);
+        else if (p.tok <= 12) rc = launch_gather_lds_t<false, 12, true>(a, grid, p.lds, s);
+    } else if (bf16) {
         if (p.tok <= 4) rc = launch_gather_lds_t<true, 4>(a, grid, p.lds, s);
         else if (p.tok <= 6) rc = launch_gather_lds_t<true, 6>(a, grid, p.lds, s);
         else if (p.tok <= 8) rc = launch_gather_lds_t<true, 8>(a, grid, p.lds, s);
@@ -459,8 +467,22 @@ int launch_gather_direct(const uint16_t *codes, const float *weights, const void
     return LFFN_OK;
 }
 
-// workspace of the weighted forward pass: codes [n][k] uint16, then weights [n][k] fp32
+// workspace of the weighted forward pass: codes [n][k] uint16 then weights [n][k] fp32, or (staged
+// gather) packed codes then table-major weights [k][n_pad]
 int64_t weighted_codes_bytes(int64_t n, int k) { return ((int64_t)n * k * 2 + 255) & ~int64_t(255); }
+int64_t round256(int64_t b) { return (b + 255) & ~int64_t(255); }
+
+int launch_repack_codes(const uint16_t *codes, uint32_t *packed, int64_t n, int64_t n_pad, int k, int tau,
+                        hipStream_t s)
+{
+    const int64_t total = (int64_t)(k / 2) * n_pad;
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(repack_codes_kernel, dim3((unsigned)blocks), dim3(256), 0, s, codes, packed, (long long)n,
+                       (long long)n_pad, k, tau);
+    LFFN_HIP(hipGetLastError());
+    return LFFN_OK;
+}
 
 }  // namespace
 
@@ -491,14 +513,36 @@ int lookupffn_gather_weighted(const uint16_t *codes, const float *weights, const
     int rc = check_gather(codes, tables, y, n_tokens, k, tau, d_out, table_dtype);
     if (rc == LFFN_OK) rc = check_weights(weights);
     if (rc != LFFN_OK || n_tokens == 0) return rc;
-    return launch_gather_direct(codes, weights, tables, y, n_tokens, k, tau, d_out, table_dtype,
-                                static_cast<hipStream_t>(hip_stream));
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    LdsPlan plan;
+    rc = plan_gather_lds(n_tokens, k, tau, d_out, table_dtype == LFFN_BF16, &plan, true);
+    if (rc != LFFN_OK) return rc;
+    if (plan.use && aligned(codes, 4)) {
+        // the staged kernel reads packed codes and table-major weights: repack into the library's buffer
+        const int64_t pb = round256(packed_bytes(n_tokens, k));
+        void *ws = nullptr;
+        rc = own_workspace((size_t)(pb + (int64_t)k * plan.a.n_pad * 4), &ws);
+        if (rc != LFFN_OK) return rc;
+        uint32_t *packed = static_cast<uint32_t *>(ws);
+        float *wpk = reinterpret_cast<float *>(static_cast<char *>(ws) + pb);
+        rc = launch_repack_codes(codes, packed, n_tokens, plan.a.n_pad, k, tau, s);
+        if (rc != LFFN_OK) return rc;
+        int64_t blocks = ((int64_t)k * n_tokens + 255) / 256;
+        if (blocks > 4096) blocks = 4096;
+        hipLaunchKernelGGL(repack_weights_kernel, dim3((unsigned)blocks), dim3(256), 0, s, weights, wpk,
+                           (long long)n_tokens, (long long)plan.a.n_pad, k);
+        LFFN_HIP(hipGetLastError());
+        return launch_gather_lds(plan, packed, wpk, tables, y, false, s);
+    }
+    return launch_gather_direct(codes, weights, tables, y, n_tokens, k, tau, d_out, table_dtype, s);
 }
 
 int64_t lookupffn_workspace_bytes_weighted(int64_t n_tokens, int k)
 {
     if (n_tokens <= 0 || k < 1) return 0;
-    return weighted_codes_bytes(n_tokens, k) + (((int64_t)n_tokens * k * 4 + 255) & ~int64_t(255));
+    const int64_t direct = weighted_codes_bytes(n_tokens, k) + round256((int64_t)n_tokens * k * 4);
+    const int64_t staged = round256(packed_bytes(n_tokens, k)) + round256((int64_t)k * packed_n_pad(n_tokens) * 4);
+    return direct > staged ? direct : staged;
 }
 
 int lookupffn_forward_weighted(const void *x, const int8_t *signs, const void *tables, float *y, int64_t n_tokens,
@@ -522,6 +566,16 @@ int lookupffn_forward_weighted(const void *x, const int8_t *signs, const void *t
         if (rc != LFFN_OK) return rc;
     }
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    LdsPlan plan;
+    rc = plan_gather_lds(n_tokens, k, tau, d_out, table_dtype == LFFN_BF16, &plan, true);
+    if (rc != LFFN_OK) return rc;
+    if (plan.use) {
+        uint32_t *packed = static_cast<uint32_t *>(ws);
+        float *wpk = reinterpret_cast<float *>(static_cast<char *>(ws) + round256(packed_bytes(n_tokens, k)));
+        rc = launch_hash(x, signs, nullptr, packed, wpk, n_tokens, d, k, tau, n_rounds, x_dtype, s);
+        if (rc != LFFN_OK) return rc;
+        return launch_gather_lds(plan, packed, wpk, tables, y, false, s);
+    }
     uint16_t *codes = static_cast<uint16_t *>(ws);
     float *weights = reinterpret_cast<float *>(static_cast<char *>(ws) + weighted_codes_bytes(n_tokens, k));
     rc = launch_hash(x, signs, codes, nullptr, weights, n_tokens, d, k, tau, n_rounds, x_dtype, s);
@@ -545,13 +599,9 @@ int lookupffn_gather(const uint16_t *codes, const void *tables, float *y, int64_
         rc = own_workspace((size_t)packed_bytes(n_tokens, k), &ws);
         if (rc != LFFN_OK) return rc;
         uint32_t *packed = static_cast<uint32_t *>(ws);
-        const int64_t total = (int64_t)(k / 2) * plan.a.n_pad;
-        int64_t blocks = (total + 255) / 256;
-        if (blocks > 4096) blocks = 4096;
-        hipLaunchKernelGGL(repack_codes_kernel, dim3((unsigned)blocks), dim3(256), 0, s, codes, packed,
-                           (long long)n_tokens, (long long)plan.a.n_pad, k, tau);
-        LFFN_HIP(hipGetLastError());
-        return launch_gather_lds(plan, packed, tables, y, bf16, s);
+        rc = launch_repack_codes(codes, packed, n_tokens, plan.a.n_pad, k, tau, s);
+        if (rc != LFFN_OK) return rc;
+        return launch_gather_lds(plan, packed, nullptr, tables, y, bf16, s);
     }
     return launch_gather_direct(codes, nullptr, tables, y, n_tokens, k, tau, d_out, table_dtype, s);
 }
@@ -595,7 +645,7 @@ int lookupffn_forward(const void *x, const int8_t *signs, const void *tables, fl
         uint32_t *packed = static_cast<uint32_t *>(ws);
         rc = launch_hash(x, signs, nullptr, packed, nullptr, n_tokens, d, k, tau, n_rounds, x_dtype, s);
         if (rc != LFFN_OK) return rc;
-        return launch_gather_lds(plan, packed, tables, y, bf16, s);
+        return launch_gather_lds(plan, packed, nullptr, tables, y, bf16, s);
     }
     uint16_t *codes = static_cast<uint16_t *>(ws);
     rc = launch_hash(x, signs, codes, nullptr, nullptr, n_tokens, d, k, tau, n_rounds, x_dtype, s);

@@ -26,6 +26,7 @@ def _gpu():
     yield
     B.lookupffn_set_option("hash_path", 0)
     B.lookupffn_set_option("lanes_per_token", 0)
+    B.lookupffn_set_option("gather_path", 0)
 
 
 def rel_err(y, ref):
@@ -155,6 +156,62 @@ def test_gather_weighted_unit_weights_equal_the_plain_gather(lpt):
     finally:
         B.lookupffn_set_option("lanes_per_token", 0)
     assert np.array_equal(yw.cpu().numpy(), oracle.gather(codes, tables, acc64=False))
+
+
+LDS_SHAPES = [
+    # n, k, tau, d_out      (gather_path = 2 forces the LDS-staged kernel: fp32 tables, tau 7 or 8, k even)
+    (1003, 96, 8, 768),      # three slices per XCD, ragged chunks
+    (16384, 32, 8, 768),     # the benchmark's split, two chunks of 6 tokens per lane
+    (5000, 24, 7, 200),      # ragged last slice, 128-row tables
+    (130, 2, 7, 4),          # a single 16-byte piece per row
+    (120000, 4, 7, 128),     # several chunks per workgroup, 12 tokens per lane
+    (300, 2, 7, 8192),       # as many slice-units as workgroups
+    (1, 6, 8, 64),           # one token
+    (777, 2, 8, 64),         # a single stage
+    (700, 6, 8, 64),         # an odd number of stages, 6 tokens per lane
+]
+
+
+@pytest.mark.parametrize("n,k,tau,d_out", LDS_SHAPES)
+def test_gather_weighted_lds_staged_kernel(n, k, tau, d_out):
+    print(f"weighted gather (LDS-staged) n={n} k={k} tau={tau} d_out={d_out}", flush=True)
+    rng = np.random.default_rng(n)
+    tables = synth.make_tables(n + k, k, 1 << tau, d_out)
+    codes = rng.integers(0, 1 << tau, size=(n, k)).astype(np.uint16)
+    wts = rng.uniform(0.0, 4.0, size=(n, k)).astype(np.float32)
+    cd, wd, td = torch.from_numpy(codes.view(np.int16)).cuda(), torch.from_numpy(wts).cuda(), B.to_device(tables)
+    B.lookupffn_set_option("gather_path", 2)
+    try:
+        y_lds = B.lookupffn_gather_weighted(cd, wd, td)
+        torch.cuda.synchronize()
+        assert B.lookupffn_last_gather_kernel() == "gather_lds_kernel"
+        B.lookupffn_set_option("gather_path", 1)
+        y_direct = B.lookupffn_gather_weighted(cd, wd, td)
+        torch.cuda.synchronize()
+        assert B.lookupffn_last_gather_kernel() == "gather_kernel"
+    finally:
+        B.lookupffn_set_option("gather_path", 0)
+    # both kernels do the same fused multiply-adds in the same order
+    assert np.array_equal(y_lds.cpu().numpy(), y_direct.cpu().numpy())
+    assert rel_err(y_lds.cpu().numpy(), oracle.gather_weighted(codes, wts.astype(np.float64), tables)) <= TOL_F32
+
+
+def test_forward_weighted_both_gather_paths_agree():
+    print("weighted forward, staged against direct gather", flush=True)
+    w = synth.C2.with_tokens(3000)
+    x, signs, tables = synth.make_layer(w)
+    xd, sd, td = B.to_device(x), B.to_device(signs), B.to_device(tables)
+    ys = {}
+    try:
+        for path in (2, 1):
+            B.lookupffn_set_option("gather_path", path)
+            ys[path] = B.lookupffn_forward_weighted(xd, sd, td)
+            torch.cuda.synchronize()
+            assert B.lookupffn_last_gather_kernel() == ("gather_lds_kernel" if path == 2 else "gather_kernel")
+    finally:
+        B.lookupffn_set_option("gather_path", 0)
+    assert np.array_equal(ys[1].cpu().numpy(), ys[2].cpu().numpy())
+    assert rel_err(ys[2].cpu().numpy(), oracle.forward_weighted(x, signs, tables)) <= TOL_F32
 
 
 def check_forward_weighted(w, x, signs, tables, sample=None):
