@@ -15,19 +15,20 @@
 // one row per (token, table) to one row per (chunk, table, row).
 //
 // Codes come in the packed layout written by the hash kernel (one 32-bit word
-// per token and stage holding both tables' LDS row offsets, token-contiguous):
-// a wave's code load touches one cache line and needs no address arithmetic
-// beyond an immediate offset.  The vector-memory instructions of a stage (next
+// per token and stage holding both tables' LDS row offsets, token-contiguous).
+// The eight lanes of a token would all hold the same word, so the words are
+// quad-shared: each lane keeps only those of the token slots i with i % 4 ==
+// its position in its quad, and a use takes the word through a DPP quad
+// broadcast -- a quarter of the registers and load instructions, one cache
+// line per load.  The vector-memory instructions of a stage (next
 // stage's row copies and codes) are issued a few at a time between the LDS
 // read batches: a wave issues in order, so a burst of them at the top of the
 // stage would hold every wave at the texture-address queue while LDS and the
 // vector ALU sit idle.
 //
 // Weighted form (Sec. 4: y = sum_j w_j T_j[code_j]): the fp32 weights come table-major and
-// token-contiguous (wpk[j][n_pad]).  The eight lanes of a token would all hold the same weight, so
-// each lane keeps only the weights of the token slots i with i % 4 == its position in its quad
-// and the multiply-add takes the weight through a DPP quad broadcast: a quarter of the registers
-// and load instructions.
+// token-contiguous (wpk[j][n_pad]) and are quad-shared like the code words; each row is
+// accumulated with one fused multiply-add per element.
 //
 // Work distribution is static and XCD-aware: slice-units are dealt to the
 // eight XCDs round-robin (block b runs on XCD b % 8), and the workgroups of
@@ -51,10 +52,16 @@ constexpr int kLdsMaxTok = 16;               // token slots per lane the packed 
 #ifndef LFFN_LDS_RB
 #define LFFN_LDS_RB 3
 #endif
+#ifndef LFFN_LDS_CO
+#define LFFN_LDS_CO 0   // read batch in which the first code load of the next stage is issued
+#endif
+#ifndef LFFN_LDS_WO
+#define LFFN_LDS_WO 4   // same for its first weight load
+#endif
 
 struct GatherLdsArgs {
     const uint32_t *packed;  // [k/2][n_pad] packed codes (see hash_kernel.hpp)
-    const float *wpk;        // [k][n_pad] weights (weighted form only)
+    const float *wpk;        // [k/2][n_pad][2] weights, the two tables of a stage adjacent (weighted form only)
     long long n_pad;
     const char *tables;
     float *y;
@@ -93,6 +100,9 @@ __device__ __forceinline__ void lds_dma16(const char *gbase, uint32_t voff, uint
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// batch that issues the i-th deferred load of a stage with nbt batches: i itself, wrapped
+__host__ __device__ constexpr int vm_slot(int i, int nbt) { return i % nbt; }
+
 // value of `v` in lane Q of the caller's quad (DPP quad_perm [Q,Q,Q,Q])
 template <int Q>
 __device__ __forceinline__ float quad_bcast(float v)
@@ -102,6 +112,10 @@ __device__ __forceinline__ float quad_bcast(float v)
 __device__ __forceinline__ float quad_bcast(float v, int q)
 {
     return q == 0 ? quad_bcast<0>(v) : q == 1 ? quad_bcast<1>(v) : q == 2 ? quad_bcast<2>(v) : quad_bcast<3>(v);
+}
+__device__ __forceinline__ uint32_t quad_bcast(uint32_t v, int q)
+{
+    return __float_as_uint(quad_bcast(__uint_as_float(v), q));
 }
 
 // FR = rounds of 128 rows per table slice: 1 (tau = 7) or 2 (tau = 8)
@@ -174,26 +188,49 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
         const uint32_t nchunks = (len + kLdsGroups * TOK - 1) / (kLdsGroups * TOK);
         for (uint32_t ch = 0; ch < nchunks; ++ch) {
             const uint32_t c0 = r0 + split_at(len, nchunks, ch), c1 = r0 + split_at(len, nchunks, ch + 1);
-            // Accumulator i belongs to token c0 + i*128 + g.  Slots past the chunk end read the codes
-            // of later tokens or of the zero padding (always a valid row), add them, and store nothing.
-            const uint32_t g4 = g * 4u;
-            auto load_code = [&](uint32_t s, int i, uint32_t(&cr)[TOK]) {
-                const char *base = reinterpret_cast<const char *>(a.packed) + ((size_t)s * a.n_pad + c0) * 4u;  // uniform
-                cr[i] = *reinterpret_cast<const uint32_t *>(base + i * (kLdsGroups * 4) + g4);
+            // Token slots.  The eight lanes of a token group would all hold the same code word and
+            // weights, so these are quad-shared: a lane keeps those of the slots 4m + r, r = its
+            // position in its quad, in register m, and a use fetches them with a DPP quad broadcast
+            // (a quarter of the registers and load instructions).  Slot i of group g is token
+            //   c0 + 512*(i/4) + 4g + i%4   for the full quads of slots (i < 4*(TOK/4)),
+            //   c0 + 128*i + g              for the remaining TOK % 4 slots,
+            // so that register m of a wave's lanes covers 32 consecutive tokens: one cache line per
+            // load instruction.  Slots past the chunk end read the codes of later tokens or of the
+            // zero padding (always a valid row), add them, and store nothing.
+            constexpr int WQ = (TOK + 3) / 4, FQ = TOK / 4;
+            const uint32_t r4 = q & 3u;
+            auto slot_token = [&](int i) -> uint32_t {
+                return i < 4 * FQ ? c0 + 512u * (uint32_t)(i >> 2) + 4u * g + (uint32_t)(i & 3)
+                                  : c0 + 128u * (uint32_t)i + g;
             };
-
-            // weights of table u of stage s for token slots 4m + (lane's position in its quad)
-            constexpr int WQ = (TOK + 3) / 4;
-            const uint32_t lw = (q & 3u) * (kLdsGroups * 4u) + g4;
-            auto load_weight = [&](uint32_t s, int u, int m, float(&wr)[kLdsTps][WQ]) {
+            const uint32_t lq_full = (4u * g + r4) * 4u;          // byte offset of the lane's token in a full quad register
+            const uint32_t lq_tail = (r4 * kLdsGroups + g) * 4u;  // same for the tail register
+            auto reg_offset = [&](int m) -> uint32_t {
+                return m < FQ ? (uint32_t)m * 2048u + lq_full : (uint32_t)m * 2048u + lq_tail;
+            };
+            constexpr int NCR = WQ;  // code registers and code loads per stage
+            auto load_code = [&](uint32_t s, int m, uint32_t(&cr)[NCR]) {
+                const char *base = reinterpret_cast<const char *>(a.packed) + ((size_t)s * a.n_pad + c0) * 4u;  // uniform
+                cr[m] = *reinterpret_cast<const uint32_t *>(base + reg_offset(m));
+            };
+            // LDS row offset of slot i in table u of the stage: the low / high half of its code word.
+            // The high halves are shifted down before the broadcast, so the two tables' broadcasts
+            // are distinct values and neither is kept alive across the stage.
+            auto row_offset = [&](const uint32_t(&cr)[NCR], int u, int i) -> uint32_t {
+                return u ? quad_bcast(cr[i >> 2] >> 16, i & 3) : (quad_bcast(cr[i >> 2], i & 3) & 0xFFFFu);
+            };
+            // weights: table u of stage s, register m
+            constexpr int NWL = kLdsTps * WQ;
+            auto load_weight = [&](uint32_t s, int i, float(&wr)[kLdsTps][WQ]) {
+                const int u = i / WQ, m = i % WQ;
                 const char *base = reinterpret_cast<const char *>(a.wpk) +
                                    ((size_t)(s * kLdsTps + (uint32_t)u) * a.n_pad + c0) * 4u;  // uniform
-                wr[u][m] = *reinterpret_cast<const float *>(base + m * (4 * kLdsGroups * 4) + lw);
+                wr[u][m] = *reinterpret_cast<const float *>(base + reg_offset(m));
             };
 
             // codes of a stage's two tables per token slot; two sets so that the next stage's codes
             // load while the current stage is consumed
-            uint32_t crA[TOK], crB[TOK];
+            uint32_t crA[NCR], crB[NCR];
             float wA[kLdsTps][WQ], wB[kLdsTps][WQ];
             Acc<BF16> acc[TOK];
 #pragma unroll
@@ -204,16 +241,13 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
 
             // One stage: consume buffer b with codes `cr`; meanwhile start stage s+1 (rows -> buffer
             // b^1, codes -> cr_next), its vector-memory instructions spread over the read batches.
-            auto run_stage = [&](auto more_tag, uint32_t s, uint32_t b, const uint32_t(&cr)[TOK],
-                                 uint32_t(&cr_next)[TOK], const float(&w)[kLdsTps][WQ],
+            auto run_stage = [&](auto more_tag, uint32_t s, uint32_t b, const uint32_t(&cr)[NCR],
+                                 uint32_t(&cr_next)[NCR], const float(&w)[kLdsTps][WQ],
                                  float(&w_next)[kLdsTps][WQ]) {
                 constexpr bool MORE = decltype(more_tag)::value;
                 constexpr int RB = LFFN_LDS_RB;              // row reads per batch
                 constexpr int NB = (TOK + RB - 1) / RB;      // batches per table
                 constexpr int NBT = kLdsTps * NB;            // batches per stage
-                constexpr int CPB = (TOK + NBT - 1) / NBT;   // code loads per batch
-                constexpr int NWL = kLdsTps * WQ;            // weight loads per stage
-                constexpr int WPB = (NWL + NBT - 1) / NBT;   // weight loads per batch
                 static_assert(NBT >= kLdsTps * FR, "one row-copy instruction per batch");
                 uint4 r[2][RB];
                 auto issue = [&](int bi, uint4(&dst)[RB]) {  // bi = u * NB + batch within table u
@@ -222,7 +256,7 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
 #pragma unroll
                     for (int i = 0; i < RB; ++i)
                         if (b0 + i < TOK) {
-                            const uint32_t off = u ? (cr[b0 + i] >> 16) : (cr[b0 + i] & 0xFFFFu);
+                            const uint32_t off = row_offset(cr, u, b0 + i);
                             const u32x4 v = *reinterpret_cast<const __attribute__((address_space(3))) u32x4 *>(
                                 (uintptr_t)(base + off));
                             dst[i] = make_uint4(v.x, v.y, v.z, v.w);
@@ -245,15 +279,16 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
                 for (int bi = 0; bi < NBT; ++bi) {
                     if (bi + 1 < NBT) issue(bi + 1, r[(bi + 1) & 1]);
                     if constexpr (MORE) {
+                        // vector-memory work of the next stage, a little per batch: row copies first
+                        // (they take longest), then its codes, then its weights
                         if (bi < kLdsTps * FR) fill_piece(s + 1, b ^ 1u, bi);
 #pragma unroll
-                        for (int cI = 0; cI < CPB; ++cI)
-                            if (bi * CPB + cI < TOK) load_code(s + 1, bi * CPB + cI, cr_next);
+                        for (int m = 0; m < NCR; ++m)
+                            if (vm_slot(LFFN_LDS_CO + m, NBT) == bi) load_code(s + 1, m, cr_next);
                         if constexpr (WEIGHTED) {
 #pragma unroll
-                            for (int wI = 0; wI < WPB; ++wI)
-                                if (bi * WPB + wI < NWL)
-                                    load_weight(s + 1, (bi * WPB + wI) / WQ, (bi * WPB + wI) % WQ, w_next);
+                            for (int m = 0; m < NWL; ++m)
+                                if (vm_slot(LFFN_LDS_WO + m, NBT) == bi) load_weight(s + 1, m, w_next);
                         }
                     }
                     consume(bi, r[bi & 1]);
@@ -268,10 +303,10 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
 #pragma unroll
             for (int idx = 0; idx < kLdsTps * FR; ++idx) fill_piece(0, 0, idx);
 #pragma unroll
-            for (int i = 0; i < TOK; ++i) load_code(0, i, crA);
+            for (int i = 0; i < NCR; ++i) load_code(0, i, crA);
             if constexpr (WEIGHTED) {
 #pragma unroll
-                for (int i = 0; i < kLdsTps * WQ; ++i) load_weight(0, i / WQ, i % WQ, wA);
+                for (int i = 0; i < NWL; ++i) load_weight(0, i, wA);
             }
             __builtin_amdgcn_s_waitcnt(0x0F70);
             __syncthreads();
@@ -293,7 +328,7 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
                 typedef float f4 __attribute__((ext_vector_type(4)));
 #pragma unroll
                 for (int i = 0; i < TOK; ++i) {
-                    const uint32_t t = c0 + (uint32_t)i * kLdsGroups + g;
+                    const uint32_t t = slot_token(i);
                     if (t >= c1) continue;
                     float *yp = a.y + (size_t)t * a.d_out + (size_t)vec * Acc<BF16>::W;
                     f4 o0 = {acc[i].f[0], acc[i].f[1], acc[i].f[2], acc[i].f[3]};

@@ -26,6 +26,11 @@ namespace lffn {
 // 16 x 128 token window past any token without leaving the buffer; padding entries are zero.
 __host__ __device__ inline long long packed_n_pad(long long n) { return ((n + 127) / 128) * 128 + 16 * 128; }
 constexpr int kPackedShift = 7;
+// index of (table j, token t) in the staged gather's weight array: table-major, token-contiguous
+__host__ __device__ inline long long wpk_index(long long j, long long t, long long n_pad)
+{
+    return j * n_pad + t;  // [k][n_pad]
+}
 
 struct HashArgs {
     const void *x;        // [n][d] fp32 or bf16
@@ -201,7 +206,7 @@ __device__ __forceinline__ void emit_weights(const HashArgs &a, long long t, int
         }
         const float w = __fdividef(s, q);
         if (a.wpk)
-            a.wpk[(long long)j * a.n_pad + t] = w;
+            a.wpk[wpk_index(j, t, a.n_pad)] = w;
         else
             a.weights[t * a.k + j] = w;
     }
@@ -603,7 +608,7 @@ __global__ __launch_bounds__(256) void repack_weights_kernel(const float *weight
     for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
          idx += (long long)gridDim.x * blockDim.x) {
         const long long j = idx / n, t = idx - j * n;
-        wpk[j * n_pad + t] = weights[t * k + j];
+        wpk[wpk_index(j, t, n_pad)] = weights[t * k + j];
     }
 }
 

@@ -361,7 +361,7 @@ int plan_gather_lds(int64_t n, int k, int tau, int d_out, bool bf16, LdsPlan *p,
     a.n_units = a.n_slices * a.token_splits;
     a.blocks_per_xcd = cus / kXcds;
     const int64_t tpb = lds_tokens_per_block(n, a.n_units, a.token_splits, a.blocks_per_xcd);
-    const int tok_max = bf16 ? 8 : weighted ? 12 : 13;
+    const int tok_max = bf16 ? 8 : 13;
     const int64_t nchunks = (tpb + (int64_t)kLdsGroups * tok_max - 1) / ((int64_t)kLdsGroups * tok_max);
     const int64_t chunk = (tpb + nchunks - 1) / nchunks;
     // Staging pays only when a chunk re-uses each staged row a few times.  With bf16 rows the
@@ -391,6 +391,7 @@ int launch_gather_lds(const LdsPlan &p, const uint32_t *packed, const float *wpk
         if (p.tok <= 4) rc = launch_gather_lds_t<false, 4, true>(a, grid, p.lds, s);
         else if (p.tok <= 8) rc = launch_gather_lds_t<false, 8, true>(a, grid, p.lds, s);
         else if (p.tok <= 12) rc = launch_gather_lds_t<false, 12, true>(a, grid, p.lds, s);
+        else if (p.tok <= 13) rc = launch_gather_lds_t<false, 13, true>(a, grid, p.lds, s);
     } else if (bf16) {
         if (p.tok <= 4) rc = launch_gather_lds_t<true, 4>(a, grid, p.lds, s);
         else if (p.tok <= 6) rc = launch_gather_lds_t<true, 6>(a, grid, p.lds, s);
