@@ -137,7 +137,7 @@ int lookupffn_timing_read(int which, double *total_ms, int64_t *launches);
  *   "lanes_per_token"  1,2,4,...,64   lanes (16 bytes each) that share one token's row slice
  *   "xcd_order"        1 / -1         force the XCD-sliced block order on / off
  *   "gather_path"      1 / 2          1: always the direct kernel; 2: the LDS-staged kernel
- *                                     whenever the shape allows it (tau 7 or 8, k even)
+ *                                     whenever the shape allows it (tau 7, 8 or 9, k even)
  *   "hash_path"        1              always the generic hash kernel (default: the two-layout
  *                                     kernel when d_pad = 1024 and n_rounds <= 4)
  *   "hash_blocks"      1..65536       grid cap of the d_pad = 1024 hash kernel

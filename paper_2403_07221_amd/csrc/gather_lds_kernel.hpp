@@ -47,7 +47,7 @@ namespace lffn {
 
 constexpr int kLdsThreads = 1024;
 constexpr int kLdsGroups = kLdsThreads / 8;  // token groups per workgroup (8 lanes per token)
-constexpr int kLdsTps = 2;                   // tables per stage
+constexpr int kLdsBufBytes = 64 * 1024;      // one staging buffer (two of them are in use)
 constexpr int kLdsMaxTok = 16;               // token slots per lane the packed padding allows for
 #ifndef LFFN_LDS_RB
 #define LFFN_LDS_RB 3
@@ -75,8 +75,14 @@ struct GatherLdsArgs {
     uint32_t row_bytes;
 };
 
-// bytes of LDS the kernel needs: two buffers of kLdsTps table slices
-__host__ __device__ inline size_t gather_lds_bytes(int tau) { return (size_t)2 * kLdsTps * ((size_t)128 << tau); }
+// tables per stage: as many 128-byte-wide table slices as fill one buffer, at most two (a code
+// word holds two tables' offsets)
+__host__ __device__ inline int gather_lds_tps(int tau) { return ((size_t)128 << tau) * 2 <= (size_t)kLdsBufBytes ? 2 : 1; }
+// bytes of LDS the kernel needs: two buffers
+__host__ __device__ inline size_t gather_lds_bytes(int tau)
+{
+    return (size_t)2 * gather_lds_tps(tau) * ((size_t)128 << tau);
+}
 
 // balanced split of [0, len) into `parts` pieces: start of piece i (32-bit arithmetic only)
 __device__ __forceinline__ uint32_t split_at(uint32_t len, uint32_t parts, uint32_t i)
@@ -118,21 +124,25 @@ __device__ __forceinline__ uint32_t quad_bcast(uint32_t v, int q)
     return __float_as_uint(quad_bcast(__uint_as_float(v), q));
 }
 
-// FR = rounds of 128 rows per table slice: 1 (tau = 7) or 2 (tau = 8)
+// FR = rounds of 128 rows per table slice: 1, 2, 4 for tau = 7, 8, 9.  Tables per stage TPS: two
+// (tau 7, 8: both halves of a code word are consumed in one stage) or one (tau = 9: a 512-row slice
+// fills a buffer; even stages take the low half of the code word, odd stages the high half).
 template <bool BF16, int TOK, int FR, bool WEIGHTED>
 __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a)
 {
     static_assert(TOK <= kLdsMaxTok, "packed-code padding covers 16 token slots");
-    static_assert(FR == 1 || FR == 2, "table slices of 128 or 256 rows");
+    static_assert(FR == 1 || FR == 2 || FR == 4, "table slices of 128, 256 or 512 rows");
+    constexpr int TPS = FR <= 2 ? 2 : 1;
+    static_assert(TPS * FR * 128 * 128 <= kLdsBufBytes, "a stage fits one buffer");
     extern __shared__ uint4 sbuf[];
     const uint32_t tid = threadIdx.x;
     const uint32_t wave = tid >> 6;
     const uint32_t g = tid >> 3, q = tid & 7u;
     const uint32_t rows = 128u * FR;               // == 1 << a.tau (checked by the host)
     const uint32_t tbl_bytes = rows * 128u;          // one table slice in LDS
-    const uint32_t buf_bytes = tbl_bytes * kLdsTps;  // one buffer (one stage)
+    const uint32_t buf_bytes = tbl_bytes * TPS;  // one buffer (one stage)
     const uint32_t n = (uint32_t)a.n;                // the host uses this kernel only for n < 2^31
-    const uint32_t nstages = (uint32_t)a.k / kLdsTps;
+    const uint32_t nstages = (uint32_t)a.k / TPS;
     const uint32_t lds0 = (uint32_t)(uintptr_t)sbuf;  // LDS byte address of the staging area
 
     // ---- which (unit, token range) pairs does this workgroup own? ---------------------
@@ -179,7 +189,7 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
         // piece idx = table-in-stage * FR + round, of stage s, into buffer b
         auto fill_piece = [&](uint32_t s, uint32_t b, int idx) {
             const uint32_t tb = (uint32_t)idx / FR, f = (uint32_t)idx % FR;
-            const char *tsrc = a.tables + (size_t)(s * kLdsTps + tb) * table_stride +
+            const char *tsrc = a.tables + (size_t)(s * TPS + tb) * table_stride +
                                (size_t)f * kLdsGroups * a.row_bytes;  // uniform
             lds_dma16(tsrc, foff, lds0 + b * buf_bytes + tb * tbl_bytes + (f * kLdsThreads + wave * 64u) * 16u);
         };
@@ -220,18 +230,18 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
                 return u ? quad_bcast(cr[i >> 2] >> 16, i & 3) : (quad_bcast(cr[i >> 2], i & 3) & 0xFFFFu);
             };
             // weights: table u of stage s, register m
-            constexpr int NWL = kLdsTps * WQ;
-            auto load_weight = [&](uint32_t s, int i, float(&wr)[kLdsTps][WQ]) {
+            constexpr int NWL = TPS * WQ;
+            auto load_weight = [&](uint32_t s, int i, float(&wr)[TPS][WQ]) {
                 const int u = i / WQ, m = i % WQ;
                 const char *base = reinterpret_cast<const char *>(a.wpk) +
-                                   ((size_t)(s * kLdsTps + (uint32_t)u) * a.n_pad + c0) * 4u;  // uniform
+                                   ((size_t)(s * TPS + (uint32_t)u) * a.n_pad + c0) * 4u;  // uniform
                 wr[u][m] = *reinterpret_cast<const float *>(base + reg_offset(m));
             };
 
             // codes of a stage's two tables per token slot; two sets so that the next stage's codes
             // load while the current stage is consumed
             uint32_t crA[NCR], crB[NCR];
-            float wA[kLdsTps][WQ], wB[kLdsTps][WQ];
+            float wA[TPS][WQ], wB[TPS][WQ];
             Acc<BF16> acc[TOK];
 #pragma unroll
             for (int i = 0; i < TOK; ++i) acc[i].zero();
@@ -241,14 +251,17 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
 
             // One stage: consume buffer b with codes `cr`; meanwhile start stage s+1 (rows -> buffer
             // b^1, codes -> cr_next), its vector-memory instructions spread over the read batches.
-            auto run_stage = [&](auto more_tag, uint32_t s, uint32_t b, const uint32_t(&cr)[NCR],
-                                 uint32_t(&cr_next)[NCR], const float(&w)[kLdsTps][WQ],
-                                 float(&w_next)[kLdsTps][WQ]) {
+            // `mode_tag`: TPS == 2: ignored.  TPS == 1: 0 = this stage's table is the low half of `cr`,
+            // 1 = the high half, and the next stage needs the next code word (loaded into cr_next).
+            auto run_stage = [&](auto more_tag, auto mode_tag, uint32_t s, uint32_t b, const uint32_t(&cr)[NCR],
+                                 uint32_t(&cr_next)[NCR], const float(&w)[TPS][WQ],
+                                 float(&w_next)[TPS][WQ]) {
                 constexpr bool MORE = decltype(more_tag)::value;
+                constexpr int HALF = decltype(mode_tag)::value;
+                constexpr bool LOADC = TPS == 2 || HALF == 1;  // does the next stage start a new code word?
                 constexpr int RB = LFFN_LDS_RB;              // row reads per batch
                 constexpr int NB = (TOK + RB - 1) / RB;      // batches per table
-                constexpr int NBT = kLdsTps * NB;            // batches per stage
-                static_assert(NBT >= kLdsTps * FR, "one row-copy instruction per batch");
+                constexpr int NBT = TPS * NB;            // batches per stage
                 uint4 r[2][RB];
                 auto issue = [&](int bi, uint4(&dst)[RB]) {  // bi = u * NB + batch within table u
                     const int u = bi / NB, b0 = (bi % NB) * RB;
@@ -256,7 +269,7 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
 #pragma unroll
                     for (int i = 0; i < RB; ++i)
                         if (b0 + i < TOK) {
-                            const uint32_t off = row_offset(cr, u, b0 + i);
+                            const uint32_t off = row_offset(cr, TPS == 2 ? u : HALF, b0 + i);
                             const u32x4 v = *reinterpret_cast<const __attribute__((address_space(3))) u32x4 *>(
                                 (uintptr_t)(base + off));
                             dst[i] = make_uint4(v.x, v.y, v.z, v.w);
@@ -281,10 +294,14 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
                     if constexpr (MORE) {
                         // vector-memory work of the next stage, a little per batch: row copies first
                         // (they take longest), then its codes, then its weights
-                        if (bi < kLdsTps * FR) fill_piece(s + 1, b ^ 1u, bi);
 #pragma unroll
-                        for (int m = 0; m < NCR; ++m)
-                            if (vm_slot(LFFN_LDS_CO + m, NBT) == bi) load_code(s + 1, m, cr_next);
+                        for (int idx = 0; idx < TPS * FR; ++idx)
+                            if (vm_slot(idx, NBT) == bi) fill_piece(s + 1, b ^ 1u, idx);
+                        if constexpr (LOADC) {
+#pragma unroll
+                            for (int m = 0; m < NCR; ++m)
+                                if (vm_slot(LFFN_LDS_CO + m, NBT) == bi) load_code((s + 1) * TPS / 2, m, cr_next);
+                        }
                         if constexpr (WEIGHTED) {
 #pragma unroll
                             for (int m = 0; m < NWL; ++m)
@@ -301,7 +318,7 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
 
             // prologue: stage 0 into buffer 0, its codes
 #pragma unroll
-            for (int idx = 0; idx < kLdsTps * FR; ++idx) fill_piece(0, 0, idx);
+            for (int idx = 0; idx < TPS * FR; ++idx) fill_piece(0, 0, idx);
 #pragma unroll
             for (int i = 0; i < NCR; ++i) load_code(0, i, crA);
             if constexpr (WEIGHTED) {
@@ -311,17 +328,39 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
             __builtin_amdgcn_s_waitcnt(0x0F70);
             __syncthreads();
 
-            // all stages but the last start their successor; buffers and code sets alternate
+            // all stages but the last start their successor; buffers, code sets and weight sets alternate
+            using t0 = std::integral_constant<int, 0>;
+            using t1 = std::integral_constant<int, 1>;
             uint32_t s = 0;
-            for (; s + 2 < nstages; s += 2) {
-                run_stage(yes{}, s, 0u, crA, crB, wA, wB);
-                run_stage(yes{}, s + 1, 1u, crB, crA, wB, wA);
-            }
-            if (s + 1 < nstages) {
-                run_stage(yes{}, s, 0u, crA, crB, wA, wB);
-                run_stage(no{}, s + 1, 1u, crB, crA, wB, wA);
+            if constexpr (TPS == 2) {
+                for (; s + 2 < nstages; s += 2) {
+                    run_stage(yes{}, t0{}, s, 0u, crA, crB, wA, wB);
+                    run_stage(yes{}, t0{}, s + 1, 1u, crB, crA, wB, wA);
+                }
+                if (s + 1 < nstages) {
+                    run_stage(yes{}, t0{}, s, 0u, crA, crB, wA, wB);
+                    run_stage(no{}, t0{}, s + 1, 1u, crB, crA, wB, wA);
+                } else {
+                    run_stage(no{}, t0{}, s, 0u, crA, crB, wA, wB);
+                }
             } else {
-                run_stage(no{}, s, 0u, crA, crB, wA, wB);
+                // one table per stage, two stages per code word (k is even): word p = s/2 sits in crA for
+                // even p, crB for odd p
+                for (; s + 4 < nstages; s += 4) {
+                    run_stage(yes{}, t0{}, s, 0u, crA, crB, wA, wB);
+                    run_stage(yes{}, t1{}, s + 1, 1u, crA, crB, wB, wA);
+                    run_stage(yes{}, t0{}, s + 2, 0u, crB, crA, wA, wB);
+                    run_stage(yes{}, t1{}, s + 3, 1u, crB, crA, wB, wA);
+                }
+                if (s + 2 < nstages) {
+                    run_stage(yes{}, t0{}, s, 0u, crA, crB, wA, wB);
+                    run_stage(yes{}, t1{}, s + 1, 1u, crA, crB, wB, wA);
+                    run_stage(yes{}, t0{}, s + 2, 0u, crB, crA, wA, wB);
+                    run_stage(no{}, t1{}, s + 3, 1u, crB, crA, wB, wA);
+                } else {
+                    run_stage(yes{}, t0{}, s, 0u, crA, crB, wA, wB);
+                    run_stage(no{}, t1{}, s + 1, 1u, crA, crB, wB, wA);
+                }
             }
 
             if (vec_ok) {

@@ -312,8 +312,9 @@ int launch_gather_lds_fr(const GatherLdsArgs &a, dim3 grid, size_t lds, hipStrea
 template <bool BF16, int TOK, bool WEIGHTED = false>
 int launch_gather_lds_t(const GatherLdsArgs &a, dim3 grid, size_t lds, hipStream_t s)
 {
-    return a.tau == 8 ? launch_gather_lds_fr<BF16, TOK, 2, WEIGHTED>(a, grid, lds, s)
-                      : launch_gather_lds_fr<BF16, TOK, 1, WEIGHTED>(a, grid, lds, s);
+    return a.tau == 9   ? launch_gather_lds_fr<BF16, TOK, 4, WEIGHTED>(a, grid, lds, s)
+           : a.tau == 8 ? launch_gather_lds_fr<BF16, TOK, 2, WEIGHTED>(a, grid, lds, s)
+                        : launch_gather_lds_fr<BF16, TOK, 1, WEIGHTED>(a, grid, lds, s);
 }
 
 // Largest number of tokens a workgroup gets in one piece, mirroring the kernel's split.
@@ -341,7 +342,7 @@ int plan_gather_lds(int64_t n, int k, int tau, int d_out, bool bf16, LdsPlan *p,
     if (g_opt.gather_path == 1) return LFFN_OK;
     if (weighted && bf16) return LFFN_OK;  // the weighted staged kernel is built for fp32 tables
     const int rows = 1 << tau;
-    if ((tau != 7 && tau != 8) || k % 2 != 0) return LFFN_OK;  // table slices of 128 or 256 rows
+    if (tau < 7 || tau > 9 || k % 2 != 0) return LFFN_OK;  // table slices of 128, 256 or 512 rows
     // the kernel indexes tokens and bytes inside one table with 32 bits
     if (n >= (int64_t(1) << 31) - 4096 || (int64_t)rows * d_out * 4 >= (int64_t(1) << 32)) return LFFN_OK;
     int cus = 0;

@@ -196,7 +196,7 @@ def test_gather_every_launch_shape(lpt, xcd):
 
 
 LDS_SHAPES = [
-    # n, k, tau, d_out, table dtype     (gather_path = 2 forces the LDS-staged kernel: tau 7 or 8, k even)
+    # n, k, tau, d_out, table dtype     (gather_path = 2 forces the LDS-staged kernel: tau 7, 8 or 9, k even)
     (1003, 96, 8, 768, "f32"),       # three slices per XCD, ragged chunks
     (1003, 96, 8, 768, "bf16"),
     (16384, 32, 8, 768, "f32"),      # the benchmark's split: 11/11/10 workgroups per slice, 13 tokens per lane
@@ -210,6 +210,11 @@ LDS_SHAPES = [
     (777, 2, 8, 64, "f32"),          # a single stage
     (777, 6, 8, 64, "bf16"),         # an odd number of stages
     (500, 10, 6, 64, "f32"),         # tau outside the staged kernel's range: falls back to the direct kernel
+    (3000, 170, 9, 768, "f32"),      # tau = 9: one 512-row table per stage, 85 code words
+    (1500, 2, 9, 64, "f32"),         # tau = 9, a single code word
+    (1500, 4, 9, 64, "bf16"),        # tau = 9, two code words
+    (9000, 6, 9, 200, "f32"),        # tau = 9, three code words, ragged last slice, several chunks
+    (600, 12, 9, 72, "bf16"),
 ]
 
 
