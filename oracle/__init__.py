@@ -22,6 +22,13 @@ _SRC = _HERE / "lookupffn_oracle.c"
 _LIB = _HERE / "liblookupffn_oracle.so"
 CFLAGS = ["-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
           "-shared", "-fPIC", "-Wall", "-Wextra"]
+# fmaf() is exact either way; with the FMA instruction set it is one instruction instead of a
+# software routine (explicit fmaf calls only: -ffp-contract=off still keeps a*b+c unfused)
+try:
+    if " fma " in open("/proc/cpuinfo").read():
+        CFLAGS.append("-mfma")
+except OSError:
+    pass
 
 F32, BF16 = 0, 1
 _lib = None
@@ -52,6 +59,8 @@ def lib() -> ctypes.CDLL:
         L.oracle_hash.argtypes = [vp, ci, vp, vp, i64, ci, ci, ci, ci]
         L.oracle_gather.argtypes = [vp, vp, ci, vp, i64, ci, ci, ci, ci]
         L.oracle_forward.argtypes = [vp, ci, vp, vp, ci, vp, vp, i64, ci, ci, ci, ci, ci, ci]
+        L.oracle_bh_hash.argtypes = [vp, ci, vp, vp, vp, i64, ci, ci, ci, ci, ci]
+        L.oracle_bh_forward.argtypes = [vp, ci, vp, vp, ci, vp, vp, i64, ci, ci, ci, ci, ci, ci, ci]
         L.oracle_weights_from_z.argtypes = [vp, i64, vp, i64, ci, ci]
         L.oracle_weights.argtypes = [vp, ci, vp, vp, i64, ci, ci, ci, ci]
         L.oracle_gather_weighted.argtypes = [vp, vp, vp, ci, vp, i64, ci, ci, ci]
@@ -224,3 +233,47 @@ def forward_weighted(x: np.ndarray, signs: np.ndarray, tables: np.ndarray, retur
                                          _ptr(y), _ptr(codes), _ptr(w), n, d, k, tau, d_out, n_rounds),
            "forward_weighted")
     return (y, codes, w) if return_all else y
+
+
+# ---- BH4 hash (Sec. 3.2, eq. "block_acdc") -----------------------------------------------------
+
+def _check_bmats(bmats: np.ndarray, d: int, k: int, tau: int):
+    assert bmats.dtype == np.float32 and bmats.ndim == 5, "bmats must be float32 [P][m][d_pad/b][b][b]"
+    P, m, nb, b, b2 = bmats.shape
+    assert b == b2 and nb * b == d_pad(d) and P == n_proj(d, k, tau), bmats.shape
+    return b, m
+
+
+def bh_soft_codes(x: np.ndarray, bmats: np.ndarray, k: int, tau: int) -> np.ndarray:
+    """z = x R with R = prod_i B_i H per projection; z[n, P*d_pad] float32."""
+    n, d = x.shape
+    b, m = _check_bmats(bmats, d, k, tau)
+    x, bmats = np.ascontiguousarray(x), np.ascontiguousarray(bmats)
+    z = np.empty((n, bmats.shape[0] * d_pad(d)), dtype=np.float32)
+    _check(lib().oracle_bh_hash(_ptr(x), _dtype_code(x), _ptr(bmats), _ptr(z), None, n, d, k, tau, b, m), "bh_soft_codes")
+    return z
+
+
+def bh_hash_codes(x: np.ndarray, bmats: np.ndarray, k: int, tau: int) -> np.ndarray:
+    """codes[n, k] uint16 of the BH hash."""
+    n, d = x.shape
+    b, m = _check_bmats(bmats, d, k, tau)
+    x, bmats = np.ascontiguousarray(x), np.ascontiguousarray(bmats)
+    codes = np.empty((n, k), dtype=np.uint16)
+    _check(lib().oracle_bh_hash(_ptr(x), _dtype_code(x), _ptr(bmats), None, _ptr(codes), n, d, k, tau, b, m), "bh_hash")
+    return codes
+
+
+def bh_forward(x: np.ndarray, bmats: np.ndarray, tables: np.ndarray, acc64: bool = True, return_codes: bool = False):
+    """Whole forward pass with the BH hash; y[n, d_out] float32."""
+    n, d = x.shape
+    k, rows, d_out = tables.shape
+    tau = rows.bit_length() - 1
+    assert 1 << tau == rows
+    b, m = _check_bmats(bmats, d, k, tau)
+    x, bmats, tables = np.ascontiguousarray(x), np.ascontiguousarray(bmats), np.ascontiguousarray(tables)
+    y = np.empty((n, d_out), dtype=np.float32)
+    codes = np.empty((n, k), dtype=np.uint16)
+    _check(lib().oracle_bh_forward(_ptr(x), _dtype_code(x), _ptr(bmats), _ptr(tables), _dtype_code(tables), _ptr(y),
+                                   _ptr(codes), n, d, k, tau, d_out, b, m, int(acc64)), "bh_forward")
+    return (y, codes) if return_codes else y

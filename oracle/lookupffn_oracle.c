@@ -38,6 +38,12 @@
  * with S_g the +-1 row selected by the code (Sec. 3.1, eq. "optimal_index").  The soft codes
  * z stay in fp32 (they are the hash's values); the weights and the weighted sum are fp64.
  *
+ * BH4 hash (Sec. 3.2, eq. "block_acdc"): R = prod_{i=1..m} B_i H with block-diagonal B_i
+ * (block size 16/32/64 in the paper, m = 4), applied to the row vector x left to right:
+ * v <- (v B_i) H / sqrt(d_pad).  (v B)_j = sum_c v_c B[c][j] over the block of j, accumulated in
+ * fp32 with one fused multiply-add per term, c ascending, starting from +0 (the order is part of
+ * the definition here: fp32 addition is not associative and the sign bits are compared exactly).
+ *
  * Parity pins (tests/test_oracle_*.py): dense Sylvester matrix from
  * scipy.linalg.hadamard, orthonormality, involution, closed-form inputs,
  * the arg-max form of the hash by brute force over all 2^tau sign rows,
@@ -255,6 +261,89 @@ int oracle_gather(const uint16_t *codes, const void *tables, int table_dtype, fl
         }
     }
     return bad ? ORACLE_E_ARG : ORACLE_OK;
+}
+
+/*
+ * One BH{m} projection of one token (Sec. 3.2, eq. "block_acdc"):
+ *   v <- pad(x);  for i = 1..m:  u_j = sum_{c in block(j)} v_c B_i[c][j];  v <- H u / sqrt(d_pad)
+ * bm_p points at this projection's m block-diagonal factors, [m][d_pad/b][b][b] fp32 with
+ * element [i][blk][c][j] = B_i[blk*b + c][blk*b + j].
+ */
+static void project_token_bh(const void *x_row, int x_dtype, int d, int d_pad, const float *bm_p,
+                             int block, int n_factors, float *z, float *tmp)
+{
+    const float scale = (float)(1.0 / sqrt((double)d_pad));
+    for (int i = 0; i < d; ++i) z[i] = load_elt(x_row, x_dtype, i);
+    for (int i = d; i < d_pad; ++i) z[i] = 0.0f;
+    for (int f = 0; f < n_factors; ++f) {
+        const float *Bf = bm_p + (int64_t)f * d_pad * block;
+        for (int blk = 0; blk < d_pad / block; ++blk) {
+            const float *Bb = Bf + (int64_t)blk * block * block;
+            for (int j = 0; j < block; ++j) {
+                float acc = 0.0f;
+                for (int c = 0; c < block; ++c) acc = fmaf(z[blk * block + c], Bb[c * block + j], acc);
+                tmp[blk * block + j] = acc;
+            }
+        }
+        oracle_fwht(tmp, d_pad);
+        for (int i = 0; i < d_pad; ++i) z[i] = tmp[i] * scale;
+    }
+}
+
+static int check_bh(int64_t n, int d, int k, int tau, int block, int n_factors)
+{
+    if (check_shape(n, d, k, tau, n_factors)) return ORACLE_E_ARG;
+    if (block < 1 || (block & (block - 1)) || block > oracle_d_pad(d)) return ORACLE_E_ARG;
+    return ORACLE_OK;
+}
+
+/*
+ * BH{m} soft codes and hash codes for every token; same conventions as oracle_soft_codes /
+ * oracle_hash with the sign diagonals replaced by
+ *   bmats [P][n_factors][d_pad/block][block][block] fp32.
+ * z (may be NULL) receives [n][P*d_pad]; codes (may be NULL) receives [n][k].
+ */
+int oracle_bh_hash(const void *x, int x_dtype, const float *bmats, float *z, uint16_t *codes, int64_t n, int d,
+                   int k, int tau, int block, int n_factors)
+{
+    if (check_bh(n, d, k, tau, block, n_factors) || !x || !bmats || (!z && !codes)) return ORACLE_E_ARG;
+    const int d_pad = oracle_d_pad(d);
+    const int P = oracle_n_proj(d, k, tau);
+    const size_t esz = x_dtype == ORACLE_F32 ? 4 : 2;
+    int err = 0;
+#pragma omp parallel
+    {
+        float *zt = (float *)malloc(sizeof(float) * (size_t)(P + 1) * d_pad);
+        if (!zt) {
+#pragma omp atomic write
+            err = 1;
+        }
+#pragma omp barrier
+        if (!err) {
+#pragma omp for schedule(static)
+            for (int64_t t = 0; t < n; ++t) {
+                const char *row = (const char *)x + (size_t)t * d * esz;
+                for (int p = 0; p < P; ++p)
+                    project_token_bh(row, x_dtype, d, d_pad, bmats + (int64_t)p * n_factors * d_pad * block, block,
+                                     n_factors, zt + (int64_t)p * d_pad, zt + (int64_t)P * d_pad);
+                if (z) memcpy(z + t * P * d_pad, zt, sizeof(float) * (size_t)P * d_pad);
+                if (codes) pack_codes(zt, k, tau, codes + t * k);
+            }
+        }
+        free(zt);
+    }
+    return err ? ORACLE_E_NOMEM : ORACLE_OK;
+}
+
+/* Whole forward pass with the BH{m} hash: codes, then the plain gather of eq. "lookup". */
+int oracle_bh_forward(const void *x, int x_dtype, const float *bmats, const void *tables, int table_dtype,
+                      float *y, uint16_t *codes_out, int64_t n, int d, int k, int tau, int d_out, int block,
+                      int n_factors, int acc64)
+{
+    if (!y || !tables || !codes_out) return ORACLE_E_ARG;
+    int rc = oracle_bh_hash(x, x_dtype, bmats, NULL, codes_out, n, d, k, tau, block, n_factors);
+    if (rc == ORACLE_OK) rc = oracle_gather(codes_out, tables, table_dtype, y, n, k, tau, d_out, acc64);
+    return rc;
 }
 
 /*

@@ -77,7 +77,7 @@ CONFIGS.update({6: P6, 7: P7, 8: P8})
 
 
 def seed_for(config: int, layer: int, what: int) -> int:
-    """what: 0 = sign diagonals, 1 = x, 2 = tables."""
+    """what: 0 = sign diagonals, 1 = x, 2 = tables, 3 = block-diagonal factors of the BH4 hash."""
     return SEED_BASE + 1000 * config + 10 * layer + what
 
 
@@ -101,6 +101,13 @@ def make_signs(seed: int, n_proj: int, n_rounds: int, d_pad: int) -> np.ndarray:
     """[P][R][d_pad] int8 Rademacher (+1/-1)."""
     r = _rng(seed).integers(0, 2, size=(n_proj, n_rounds, d_pad), dtype=np.int8)
     return (2 * r - 1).astype(np.int8)
+
+
+def make_bmats(seed: int, n_proj: int, n_factors: int, d_pad: int, block: int) -> np.ndarray:
+    """[P][m][d_pad/block][block][block] float32 block-diagonal factors, entries N(0, 1/block)."""
+    b = _rng(seed).standard_normal((n_proj, n_factors, d_pad // block, block, block), dtype=np.float32)
+    b *= np.float32(1.0 / np.sqrt(block))
+    return b
 
 
 def make_x(seed: int, n: int, d: int, dtype: str = "f32") -> np.ndarray:
