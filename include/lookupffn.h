@@ -117,6 +117,26 @@ int lookupffn_forward_weighted(const void *x, const int8_t *signs, const void *t
                                void *workspace, int64_t workspace_bytes, void *hip_stream);
 int64_t lookupffn_workspace_bytes_weighted(int64_t n_tokens, int k);
 
+/*
+ * BH{m} hash (Sec. 3.2, eq. "block_acdc"): z = x R with R = prod_{i=1..n_factors} B_i H per
+ * projection, B_i block-diagonal with `block` x `block` blocks (16, 32 or 64), H as above; codes as
+ * above.  (v B)_j = sum_c v_c B[c][j] over j's block is accumulated in fp32 as a chain of fused
+ * multiply-adds, c ascending, from +0 (on the matrix cores).
+ *   bmats [P][n_factors][d_pad/block][block][block] fp32, element [p][i][blk][c][j] = B_i[blk*block+c][blk*block+j]
+ * Supported: 64 <= d_pad <= 1024 (LFFN_E_UNSUPPORTED otherwise, and for other block sizes).
+ * The kernels read the factors from a re-ordered copy made on every call in the workspace:
+ * lookupffn_workspace_bytes_bh() bytes (256-byte aligned) or workspace == NULL for the library's own
+ * buffer (same rules as lookupffn_forward).  lookupffn_forward_bh = this hash + the plain gather.
+ */
+int lookupffn_hash_bh(const void *x, const float *bmats, uint16_t *codes,
+                      int64_t n_tokens, int d, int k, int tau, int block, int n_factors, int x_dtype,
+                      void *workspace, int64_t workspace_bytes, void *hip_stream);
+int lookupffn_forward_bh(const void *x, const float *bmats, const void *tables, float *y,
+                         int64_t n_tokens, int d, int k, int tau, int d_out, int block, int n_factors,
+                         int x_dtype, int table_dtype,
+                         void *workspace, int64_t workspace_bytes, void *hip_stream);
+int64_t lookupffn_workspace_bytes_bh(int64_t n_tokens, int d, int k, int tau, int block, int n_factors);
+
 /* Frees the library-owned workspaces (all devices).  Safe to call when none exist. */
 int lookupffn_release_workspace(void);
 

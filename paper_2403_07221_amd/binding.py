@@ -23,6 +23,7 @@ EXPORTS = (
     "lookupffn_last_hip_error", "lookupffn_last_gather_kernel", "lookupffn_version",
     "lookupffn_hash_weighted", "lookupffn_gather_weighted", "lookupffn_forward_weighted",
     "lookupffn_workspace_bytes_weighted",
+    "lookupffn_hash_bh", "lookupffn_forward_bh", "lookupffn_workspace_bytes_bh",
 )
 
 
@@ -52,6 +53,10 @@ def lib() -> ctypes.CDLL:
         L.lookupffn_forward_weighted.argtypes = L.lookupffn_forward.argtypes
         L.lookupffn_workspace_bytes_weighted.argtypes = [i64, ci]
         L.lookupffn_workspace_bytes_weighted.restype = i64
+        L.lookupffn_hash_bh.argtypes = [vp, vp, vp, i64, ci, ci, ci, ci, ci, ci, vp, i64, vp]
+        L.lookupffn_forward_bh.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, ci, ci, ci, vp, i64, vp]
+        L.lookupffn_workspace_bytes_bh.argtypes = [i64, ci, ci, ci, ci, ci]
+        L.lookupffn_workspace_bytes_bh.restype = i64
         L.lookupffn_timing_enable.argtypes = [ci]
         L.lookupffn_timing_read.argtypes = [ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
         L.lookupffn_set_option.argtypes = [ctypes.c_char_p, ci]
@@ -221,6 +226,66 @@ def lookupffn_forward(x: torch.Tensor, signs: torch.Tensor, tables: torch.Tensor
         _check(getattr(lib(), _entry)(_dev(x, "x"), _dev(signs, "signs"), _dev(tables, "tables"), _dev(y, "y"),
                                       n, d, k, tau, d_out, signs.shape[1], _dtype_code(x), _dtype_code(tables),
                                       ws_ptr, ws_bytes, _stream(x)))
+    return y
+
+
+def _check_bmats(bmats: torch.Tensor, d: int, k: int, tau: int):
+    if bmats.dtype != torch.float32 or bmats.dim() != 5 or bmats.shape[3] != bmats.shape[4]:
+        raise TypeError("bmats must be float32 [P][n_factors][d_pad/block][block][block]")
+    n_pad = _pad(d)
+    P = -(-k * tau // n_pad)
+    block = bmats.shape[3]
+    if bmats.shape[0] != P or bmats.shape[2] * block != n_pad:
+        raise ValueError(f"bmats has shape {tuple(bmats.shape)}, expected ({P}, m, {n_pad}//block, block, block)")
+    return block, bmats.shape[1]
+
+
+def _ws(workspace):
+    if workspace is None:
+        return None, 0
+    return _dev(workspace, "workspace"), workspace.numel() * workspace.element_size()
+
+
+def lookupffn_workspace_bytes_bh(n_tokens: int, d: int, k: int, tau: int, block: int, n_factors: int) -> int:
+    return lib().lookupffn_workspace_bytes_bh(n_tokens, d, k, tau, block, n_factors)
+
+
+def lookupffn_hash_bh(x: torch.Tensor, bmats: torch.Tensor, k: int, tau: int, codes: torch.Tensor | None = None,
+                      workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """codes[n, k] of the BH hash (Sec. 3.2 of the paper); bmats[P, m, d_pad/b, b, b] float32."""
+    n, d = x.shape
+    block, m = _check_bmats(bmats, d, k, tau)
+    if codes is None:
+        codes = torch.empty((n, k), dtype=torch.int16, device=x.device)
+    assert codes.dtype == torch.int16 and tuple(codes.shape) == (n, k)
+    if n == 0:
+        return codes
+    ws_ptr, ws_bytes = _ws(workspace)
+    with torch.cuda.device(x.device):
+        _check(lib().lookupffn_hash_bh(_dev(x, "x"), _dev(bmats, "bmats"), _dev(codes, "codes"), n, d, k, tau, block,
+                                       m, _dtype_code(x), ws_ptr, ws_bytes, _stream(x)))
+    return codes
+
+
+def lookupffn_forward_bh(x: torch.Tensor, bmats: torch.Tensor, tables: torch.Tensor, y: torch.Tensor | None = None,
+                         workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """Whole forward pass with the BH hash: y[n, d_out]."""
+    n, d = x.shape
+    k, rows, d_out = tables.shape
+    tau = rows.bit_length() - 1
+    if (1 << tau) != rows:
+        raise ValueError("tables must have 2^tau rows")
+    block, m = _check_bmats(bmats, d, k, tau)
+    if y is None:
+        y = torch.empty((n, d_out), dtype=torch.float32, device=x.device)
+    assert y.dtype == torch.float32 and tuple(y.shape) == (n, d_out)
+    if n == 0:
+        return y
+    ws_ptr, ws_bytes = _ws(workspace)
+    with torch.cuda.device(x.device):
+        _check(lib().lookupffn_forward_bh(_dev(x, "x"), _dev(bmats, "bmats"), _dev(tables, "tables"), _dev(y, "y"),
+                                          n, d, k, tau, d_out, block, m, _dtype_code(x), _dtype_code(tables),
+                                          ws_ptr, ws_bytes, _stream(x)))
     return y
 
 

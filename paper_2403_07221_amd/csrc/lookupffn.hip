@@ -12,6 +12,7 @@
 #include <string>
 #include <vector>
 
+#include "bh_hash_kernel.hpp"
 #include "gather_kernel.hpp"
 #include "gather_lds_kernel.hpp"
 #include "hash_kernel.hpp"
@@ -268,6 +269,7 @@ int launch_gather_lpt(int lpt, const GatherArgs &a, dim3 grid, hipStream_t s)
 }
 
 int gcd(int a, int b) { return b ? gcd(b, a % b) : a; }
+int64_t round256(int64_t b) { return (b + 255) & ~int64_t(255); }
 
 // ---- LDS-staged gather -------------------------------------------------------------------
 constexpr int kLdsMinBytes = 84 * 1024;  // more than half of the 160 KB LDS: one workgroup per CU
@@ -469,10 +471,94 @@ int launch_gather_direct(const uint16_t *codes, const float *weights, const void
     return LFFN_OK;
 }
 
+// ---- BH{m} hash --------------------------------------------------------------------------------
+int check_bh(const void *x, const float *bmats, int64_t n, int d, int k, int tau, int block, int n_factors,
+             int x_dtype)
+{
+    if (!x || !bmats) return LFFN_E_NULL;
+    if (n < 0 || d < 1 || k < 1 || n_factors < 1) return LFFN_E_SIZE;
+    if (tau < 1 || tau > 16) return LFFN_E_TAU;
+    if (!dtype_ok(x_dtype)) return LFFN_E_DTYPE;
+    if (k > (1 << 20) || n > (int64_t(1) << 40) || n_factors > 64) return LFFN_E_SIZE;
+    const int L = log2_pad(d);
+    if (L > 10 || d > 1024) return LFFN_E_UNSUPPORTED;
+    const int N = L < 6 ? 64 : 1 << L;  // widths below 64 are not built
+    if (L < 6) return LFFN_E_UNSUPPORTED;
+    if (block != 16 && block != 32 && block != 64) return LFFN_E_UNSUPPORTED;
+    if (block > N) return LFFN_E_SIZE;
+    const int64_t P = ((int64_t)k * tau + N - 1) / N;
+    if (P > 64 || bh_lds_bytes((int)P, N) > 64 * 1024) return LFFN_E_UNSUPPORTED;
+    if (!aligned(x, x_dtype == LFFN_F32 ? 4 : 2) || !aligned(bmats, 4)) return LFFN_E_ALIGN;
+    return LFFN_OK;
+}
+
+int64_t bh_pack_bytes(int d, int k, int tau, int block, int n_factors)
+{
+    const int N = 1 << log2_pad(d);
+    const int64_t P = ((int64_t)k * tau + N - 1) / N;
+    return round256(P * n_factors * (int64_t)N * block * 4);
+}
+
+template <int L>
+int launch_bh_t(const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s)
+{
+    switch (block) {
+        case 16: hipLaunchKernelGGL((bh_hash_kernel<L, 1>), grid, dim3(kBhThreads), lds, s, a); break;
+        case 32: hipLaunchKernelGGL((bh_hash_kernel<L, 2>), grid, dim3(kBhThreads), lds, s, a); break;
+        case 64: hipLaunchKernelGGL((bh_hash_kernel<L, 4>), grid, dim3(kBhThreads), lds, s, a); break;
+        default: return LFFN_E_UNSUPPORTED;
+    }
+    return LFFN_OK;
+}
+
+// Packs the factors into `apack` (bh_pack_bytes) and hashes; writes codes[n][k] or the packed layout.
+int launch_hash_bh(const void *x, const float *bmats, float *apack, uint16_t *codes, uint32_t *packed, int64_t n,
+                   int d, int k, int tau, int block, int n_factors, int x_dtype, hipStream_t s)
+{
+    const int L = log2_pad(d);
+    const int N = 1 << L;
+    BhArgs a;
+    a.x = x;
+    a.apack = apack;
+    a.codes = codes;
+    a.packed = codes ? nullptr : packed;
+    a.n_pad = packed_n_pad(n);
+    a.n = n;
+    a.d = d;
+    a.k = k;
+    a.tau = tau;
+    a.n_factors = n_factors;
+    a.P = (int)(((int64_t)k * tau + N - 1) / N);
+    a.x_bf16 = x_dtype == LFFN_BF16;
+    a.scale = (float)(1.0 / std::sqrt((double)N));
+    const long long total = (long long)a.P * n_factors * N * block;
+    long long pb = (total + 255) / 256;
+    if (pb > 2048) pb = 2048;
+    TimedLaunch tl(0, s);
+    hipLaunchKernelGGL(bh_pack_kernel, dim3((unsigned)pb), dim3(256), 0, s, bmats, apack, N, block, total);
+    LFFN_HIP(hipGetLastError());
+    int64_t blocks = ((n + kBhTok - 1) / kBhTok + kBhWaves - 1) / kBhWaves;
+    if (blocks > 4096) blocks = 4096;
+    const dim3 grid((unsigned)blocks);
+    const size_t lds = bh_lds_bytes(a.P, N);
+    int rc;
+    switch (L) {
+        case 6: rc = launch_bh_t<6>(a, block, grid, lds, s); break;
+        case 7: rc = launch_bh_t<7>(a, block, grid, lds, s); break;
+        case 8: rc = launch_bh_t<8>(a, block, grid, lds, s); break;
+        case 9: rc = launch_bh_t<9>(a, block, grid, lds, s); break;
+        case 10: rc = launch_bh_t<10>(a, block, grid, lds, s); break;
+        default: rc = LFFN_E_UNSUPPORTED;
+    }
+    if (rc != LFFN_OK) return rc;
+    LFFN_HIP(hipGetLastError());
+    tl.done();
+    return LFFN_OK;
+}
+
 // workspace of the weighted forward pass: codes [n][k] uint16 then weights [n][k] fp32, or (staged
 // gather) packed codes then table-major weights [k][n_pad]
 int64_t weighted_codes_bytes(int64_t n, int k) { return ((int64_t)n * k * 2 + 255) & ~int64_t(255); }
-int64_t round256(int64_t b) { return (b + 255) & ~int64_t(255); }
 
 int launch_repack_codes(const uint16_t *codes, uint32_t *packed, int64_t n, int64_t n_pad, int k, int tau,
                         hipStream_t s)
@@ -651,6 +737,75 @@ int lookupffn_forward(const void *x, const int8_t *signs, const void *tables, fl
     }
     uint16_t *codes = static_cast<uint16_t *>(ws);
     rc = launch_hash(x, signs, codes, nullptr, nullptr, n_tokens, d, k, tau, n_rounds, x_dtype, s);
+    if (rc != LFFN_OK) return rc;
+    return launch_gather_direct(codes, nullptr, tables, y, n_tokens, k, tau, d_out, table_dtype, s);
+}
+
+int64_t lookupffn_workspace_bytes_bh(int64_t n_tokens, int d, int k, int tau, int block, int n_factors)
+{
+    if (d < 1 || d > 1024 || k < 1 || tau < 1 || tau > 16 || block < 1 || n_factors < 1 || n_factors > 64) return 0;
+    return bh_pack_bytes(d, k, tau, block, n_factors) + lookupffn_workspace_bytes(n_tokens, k);
+}
+
+int lookupffn_hash_bh(const void *x, const float *bmats, uint16_t *codes, int64_t n_tokens, int d, int k, int tau,
+                      int block, int n_factors, int x_dtype, void *workspace, int64_t workspace_bytes,
+                      void *hip_stream)
+{
+    int rc = check_bh(x, bmats, n_tokens, d, k, tau, block, n_factors, x_dtype);
+    if (rc != LFFN_OK) return rc;
+    if (!codes) return LFFN_E_NULL;
+    if (!aligned(codes, 2)) return LFFN_E_ALIGN;
+    const int64_t need = bh_pack_bytes(d, k, tau, block, n_factors);
+    if (workspace) {
+        if (workspace_bytes < need) return LFFN_E_WORKSPACE;
+        if (!aligned(workspace, 256)) return LFFN_E_ALIGN;
+    }
+    if (n_tokens == 0) return LFFN_OK;
+    void *ws = workspace;
+    if (!ws) {
+        rc = own_workspace((size_t)need, &ws);
+        if (rc != LFFN_OK) return rc;
+    }
+    return launch_hash_bh(x, bmats, static_cast<float *>(ws), codes, nullptr, n_tokens, d, k, tau, block, n_factors,
+                          x_dtype, static_cast<hipStream_t>(hip_stream));
+}
+
+int lookupffn_forward_bh(const void *x, const float *bmats, const void *tables, float *y, int64_t n_tokens, int d,
+                         int k, int tau, int d_out, int block, int n_factors, int x_dtype, int table_dtype,
+                         void *workspace, int64_t workspace_bytes, void *hip_stream)
+{
+    int rc = check_bh(x, bmats, n_tokens, d, k, tau, block, n_factors, x_dtype);
+    if (rc != LFFN_OK) return rc;
+    const uint16_t *stand_in = reinterpret_cast<const uint16_t *>(uintptr_t(256));
+    rc = check_gather(stand_in, tables, y, n_tokens, k, tau, d_out, table_dtype);
+    if (rc != LFFN_OK) return rc;
+    const int64_t pack = bh_pack_bytes(d, k, tau, block, n_factors);
+    const int64_t need = pack + lookupffn_workspace_bytes(n_tokens, k);
+    if (workspace) {
+        if (workspace_bytes < need) return LFFN_E_WORKSPACE;
+        if (!aligned(workspace, 256)) return LFFN_E_ALIGN;
+    }
+    if (n_tokens == 0) return LFFN_OK;
+    void *ws = workspace;
+    if (!ws) {
+        rc = own_workspace((size_t)need, &ws);
+        if (rc != LFFN_OK) return rc;
+    }
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    float *apack = static_cast<float *>(ws);
+    void *scratch = static_cast<char *>(ws) + pack;
+    const bool bf16 = table_dtype == LFFN_BF16;
+    LdsPlan plan;
+    rc = plan_gather_lds(n_tokens, k, tau, d_out, bf16, &plan);
+    if (rc != LFFN_OK) return rc;
+    if (plan.use) {
+        uint32_t *packed = static_cast<uint32_t *>(scratch);
+        rc = launch_hash_bh(x, bmats, apack, nullptr, packed, n_tokens, d, k, tau, block, n_factors, x_dtype, s);
+        if (rc != LFFN_OK) return rc;
+        return launch_gather_lds(plan, packed, nullptr, tables, y, bf16, s);
+    }
+    uint16_t *codes = static_cast<uint16_t *>(scratch);
+    rc = launch_hash_bh(x, bmats, apack, codes, nullptr, n_tokens, d, k, tau, block, n_factors, x_dtype, s);
     if (rc != LFFN_OK) return rc;
     return launch_gather_direct(codes, nullptr, tables, y, n_tokens, k, tau, d_out, table_dtype, s);
 }

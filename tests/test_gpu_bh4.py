@@ -1,0 +1,130 @@
+"""GPU parity of the BH4 hash (Sec. 3.2, eq. "block_acdc") through the C ABI against the CPU oracle.
+
+Bar: codes bit-exact.  The kernel runs the block-diagonal products on the matrix cores; fp32 MFMA
+accumulates as a chain of fused multiply-adds in ascending k, the same sequence as the oracle's loop,
+and the transform executes the same butterflies, so every sign bit must agree.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2403_07221_amd import binding as B
+from paper_2403_07221_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    B.lib()
+    yield
+    B.lookupffn_set_option("gather_path", 0)
+
+
+def gpu_codes(x, bm, k, tau, **kw):
+    codes = B.lookupffn_hash_bh(B.to_device(x), torch.from_numpy(bm).cuda(), k, tau, **kw)
+    torch.cuda.synchronize()
+    return B.codes_to_numpy(codes)
+
+
+def assert_codes_equal(got, want):
+    if not np.array_equal(got, want):
+        t, j = np.argwhere(got != want)[0]
+        raise AssertionError(f"{np.count_nonzero(got != want)} codes differ; first at token {t}, table {j}: "
+                             f"gpu {got[t, j]} oracle {want[t, j]}")
+
+
+SHAPES = [
+    # n, d, k, tau, block, factors, x dtype
+    (64, 64, 8, 8, 16, 4, "f32"),
+    (1, 64, 8, 8, 16, 4, "f32"),         # a single token: 15 idle token lanes
+    (77, 64, 8, 8, 64, 4, "f32"),        # one block spans the vector
+    (200, 100, 20, 5, 32, 4, "f32"),     # 100 -> 128
+    (130, 256, 20, 13, 64, 4, "f32"),    # two projections, a table straddles them
+    (300, 512, 128, 8, 16, 4, "f32"),    # the paper's small model, block 16
+    (300, 512, 128, 8, 32, 4, "f32"),
+    (300, 512, 256, 8, 64, 4, "f32"),    # four projections
+    (517, 768, 96, 8, 64, 4, "f32"),     # RoBERTa-base width, padded to 1024
+    (517, 768, 96, 8, 16, 4, "bf16"),
+    (100, 768, 170, 9, 32, 4, "f32"),    # two projections, tau = 9
+    (100, 1024, 128, 10, 64, 4, "f32"),
+    (50, 1000, 60, 8, 32, 1, "f32"),     # BH1
+    (50, 600, 30, 16, 16, 6, "bf16"),    # six factors, widest code
+    (2100, 768, 96, 8, 32, 4, "f32"),    # several token groups per wave
+]
+
+
+@pytest.mark.parametrize("n,d,k,tau,b,m,xdt", SHAPES)
+def test_bh_codes_bit_exact(n, d, k, tau, b, m, xdt):
+    print(f"bh hash n={n} d={d} k={k} tau={tau} block={b} m={m} {xdt}", flush=True)
+    w = synth.Workload("t", 7, n, d, m, k, tau, 8, x_dtype=xdt)
+    bm = synth.make_bmats(100 * d + b, w.n_proj, m, w.d_pad, b)
+    x = synth.make_x(n + d, n, d, xdt)
+    assert_codes_equal(gpu_codes(x, bm, k, tau), oracle.bh_hash_codes(x, bm, k, tau))
+
+
+def test_bh_signed_identity_blocks_equal_the_sign_diagonal_kernel():
+    print("bh hash with signed-identity blocks against the sign-diagonal hash kernel", flush=True)
+    w = synth.Workload("t", 7, 333, 768, 3, 96, 8, 8)
+    signs = synth.make_signs(11, 1, 3, 1024)
+    b = 32
+    bm = np.zeros((1, 3, 1024 // b, b, b), np.float32)
+    idx = np.arange(b)
+    bm[:, :, :, idx, idx] = signs.reshape(1, 3, 1024 // b, b).astype(np.float32)
+    x = synth.make_x(5, 333, 768)
+    got = gpu_codes(x, bm, 96, 8)
+    plain = B.codes_to_numpy(B.lookupffn_hash(B.to_device(x), B.to_device(signs), 96, 8))
+    assert_codes_equal(got, plain)
+    assert_codes_equal(got, oracle.hash_codes(x, signs, 96, 8))
+
+
+def test_bh_special_inputs_and_workspace():
+    print("bh hash: zero / tiny / huge inputs, caller workspace", flush=True)
+    d, k, tau, b = 256, 32, 8, 16
+    bm = synth.make_bmats(3, 1, 4, d, b)
+    x = synth.make_x(9, 40, d)
+    x[0] = 0.0
+    x[1] *= 1e-12
+    x[2] *= 1e12
+    x[3, 1:] = 0.0
+    want = oracle.bh_hash_codes(x, bm, k, tau)
+    assert (want[0] == 255).all()                       # every z is +0: all bits 1
+    assert_codes_equal(gpu_codes(x, bm, k, tau), want)
+    ws = torch.empty(B.lookupffn_workspace_bytes_bh(40, d, k, tau, b, 4), dtype=torch.uint8, device="cuda")
+    assert_codes_equal(gpu_codes(x, bm, k, tau, workspace=ws), want)
+    with pytest.raises(B.LookupFFNError) as e:
+        gpu_codes(x, bm, k, tau, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == -7
+
+
+def check_forward_bh(w, b, m=4, sample=None):
+    x, _, tables = synth.make_layer(w)
+    bm = synth.make_bmats(synth.seed_for(w.seed_index or w.index, 0, 3) + b, w.n_proj, m, w.d_pad, b)
+    xd, bd, td = B.to_device(x), torch.from_numpy(bm).cuda(), B.to_device(tables)
+    codes = B.lookupffn_hash_bh(xd, bd, w.k, w.tau)
+    y = B.lookupffn_forward_bh(xd, bd, td)
+    torch.cuda.synchronize()
+    codes, y = B.codes_to_numpy(codes), y.cpu().numpy()
+    idx = np.arange(x.shape[0]) if sample is None else sample
+    want = oracle.bh_hash_codes(x[idx], bm, w.k, w.tau)
+    assert_codes_equal(codes[idx], want)
+    assert np.array_equal(y[idx], oracle.gather(want, tables, acc64=False))
+    ref = oracle.bh_forward(x[idx], bm, tables, acc64=True).astype(np.float64)
+    err = float(np.max(np.abs(y[idx] - ref)) / np.sqrt(np.mean(ref ** 2)))
+    print(f"  {w.name} block {b}: max|dy|/rms = {err:.3e} on {len(idx)} tokens", flush=True)
+    assert err <= (1e-2 if w.table_dtype == "bf16" else 1e-4)
+
+
+def test_forward_bh_config1():
+    print("bh forward C1", flush=True)
+    check_forward_bh(synth.C1, 16)
+    check_forward_bh(synth.C1, 64)
+
+
+@pytest.mark.parametrize("w,b,step", [(synth.C2, 64, 4), (synth.C2, 16, 8), (synth.P7, 32, 16), (synth.P8, 64, 16)],
+                         ids=lambda v: getattr(v, "name", str(v)))
+def test_forward_bh_full_size(w, b, step):
+    print(f"bh forward {w.name} block {b} ({w.n_tokens} tokens)", flush=True)
+    check_forward_bh(w, b, sample=np.arange(0, w.n_tokens, step))

@@ -107,6 +107,24 @@ def test_weighted_argument_errors(L):
     assert fw(n=1000, ws=FAKE, wsb=need - 1) == -7 and fw(n=1000, ws=FAKE + 16, wsb=need) == -5
 
 
+def test_bh_argument_errors(L):
+    def hb(x=FAKE, bm=FAKE, codes=FAKE, n=0, d=768, k=96, tau=8, block=64, m=4, dt=0, ws=None, wsb=0):
+        return L.lookupffn_hash_bh(x, bm, codes, n, d, k, tau, block, m, dt, ws, wsb, None)
+
+    def fb(x=FAKE, tables=FAKE, y=FAKE, n=0, d=768, tau=8, block=64, ws=None, wsb=0):
+        return L.lookupffn_forward_bh(x, FAKE, tables, y, n, d, 96, tau, 768, block, 4, 0, 0, ws, wsb, None)
+
+    assert hb() == 0 and fb() == 0
+    assert hb(x=None) == -1 and hb(bm=None) == -1 and hb(codes=None) == -1 and hb(tau=0) == -3 and hb(dt=5) == -4
+    assert hb(block=8) == -6 and hb(block=128) == -6 and hb(d=2000) == -6 and hb(d=20, k=4) == -6
+    assert hb(d=64, k=8, block=64) == 0 and hb(d=60, k=8, block=64) == 0 and hb(m=0) == -2
+    assert fb(tables=None) == -1 and fb(block=48) == -6 and fb(tau=17) == -3
+    need = L.lookupffn_workspace_bytes_bh(1000, 768, 96, 8, 64, 4)
+    assert need >= 4 * 1024 * 64 * 4 + 1000 * 96 * 2 and need % 256 == 0
+    assert hb(n=1000, ws=FAKE, wsb=1024) == -7 and fb(n=1000, ws=FAKE, wsb=need - 1) == -7
+    assert fb(n=1000, ws=FAKE + 16, wsb=need) == -5
+
+
 def test_options(L):
     assert L.lookupffn_set_option(b"lanes_per_token", 16) == 0
     assert L.lookupffn_set_option(b"lanes_per_token", 3) == -2
