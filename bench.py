@@ -37,6 +37,10 @@ def parse_args():
     ap.add_argument("--weighted", action="store_true",
                     help="time the weighted variant (lookupffn_forward_weighted: the hash also emits one fp32 "
                          "weight per token and table, the gather multiplies each row by it) instead of the plain sum")
+    ap.add_argument("--hash", choices=["sign-diagonal", "bh4"], default="sign-diagonal",
+                    help="hash of the pass: the sign-diagonal x Hadamard rounds of the headline metric, or the "
+                         "paper's BH4 (four block-diagonal x Hadamard factors, lookupffn_forward_bh)")
+    ap.add_argument("--block", type=int, default=64, choices=[16, 32, 64], help="block size of the BH4 factors")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle timing")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
@@ -56,14 +60,14 @@ def traffic_from_profiles(w, weighted: bool = False) -> float | None:
     return None
 
 
-def cpu_baseline(w, x, signs, tables, budget_s: float, weighted: bool = False) -> dict:
+def cpu_baseline(w, x, signs, tables, budget_s: float, weighted: bool = False, bh: bool = False) -> dict:
     """The CPU oracle as it stands, on all host threads it gets, on the same batch."""
     import oracle  # only this leg of the bench touches the oracle
     threads = oracle.max_threads()
     n = x.shape[0]
     sample = min(n, 16384)
     xs = x[:sample]
-    run = oracle.forward_weighted if weighted else oracle.forward
+    run = oracle.bh_forward if bh else oracle.forward_weighted if weighted else oracle.forward
     run(xs[:256], signs, tables)                       # page in
     reps, t_total = 0, 0.0
     while reps < 3 or (t_total < budget_s and reps < 1000):
@@ -95,12 +99,21 @@ def main():
     torch.cuda.set_device(0)
     B.lib()
     w = synth.CONFIGS[args.config]
+    bh = args.hash == "bh4"
+    if bh and (args.weighted or w.n_layers > 1):
+        print("--hash bh4 is timed with the plain-sum gather on the single-layer configurations", file=sys.stderr)
+        sys.exit(2)
     ws_bytes = (B.lookupffn_workspace_bytes_weighted if args.weighted else B.lookupffn_workspace_bytes)(w.n_tokens, w.k)
+    if bh:
+        ws_bytes = B.lookupffn_workspace_bytes_bh(w.n_tokens, w.d, w.k, w.tau, args.block, 4)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
-    forward = B.lookupffn_forward_weighted if args.weighted else B.lookupffn_forward
+    forward = B.lookupffn_forward_bh if bh else B.lookupffn_forward_weighted if args.weighted else B.lookupffn_forward
     if w.n_layers == 1:
         x, signs, tables = synth.make_layer(w)
-        xd, sd, td = B.to_device(x), B.to_device(signs), B.to_device(tables)
+        if bh:   # the block-diagonal factors take the place of the sign diagonals
+            signs = synth.make_bmats(synth.seed_for(w.seed_index or w.index, 0, 3) + args.block, w.n_proj, 4,
+                                     w.d_pad, args.block)
+        xd, sd, td = B.to_device(x), torch.from_numpy(signs).cuda(), B.to_device(tables)
         y = torch.empty((w.n_tokens, w.d_out), dtype=torch.float32, device="cuda")
 
         def step():
@@ -174,7 +187,8 @@ def main():
                    "hash_rounds": w.n_rounds, "k_tables": w.k, "tau": w.tau, "d_out": w.d_out,
                    "x_dtype": w.x_dtype, "table_dtype": w.table_dtype,
                    "table_bytes": w.k * w.rows * w.d_out * tb,
-                   "variant": "weighted" if args.weighted else "plain-sum"},
+                   "variant": "weighted" if args.weighted else "plain-sum",
+                   "hash": f"bh4-block{args.block}" if bh else "sign-diagonal"},
         "roofline": {"kernel": B.lookupffn_last_gather_kernel(), "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_from_profiles(w, args.weighted),
                      "algorithmic_bytes_per_launch": gather_bytes, "avg_kernel_ms": gather_avg_ms},
@@ -209,7 +223,7 @@ def main():
         torch.cuda.synchronize()
         out["copy_calibration_bytes_each_way"] = src.numel() * 4
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, x, signs, tables, args.cpu_seconds, args.weighted)
+        out["cpu_baseline"] = cpu_baseline(w, x, signs, tables, args.cpu_seconds, args.weighted, bh)
         if w.n_layers > 1:
             out["cpu_baseline"]["sample"] += "; one layer (the first) of the chain"
     print(json.dumps(out))

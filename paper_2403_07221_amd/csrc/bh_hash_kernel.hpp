@@ -22,6 +22,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "gather_lds_kernel.hpp"
 #include "hash_kernel.hpp"
 
 namespace lffn {
@@ -39,12 +40,24 @@ struct BhArgs {
     long long n;
     int d, k, tau, n_factors, P;
     int x_bf16;
+    int x_vec4;           // rows may be read four coordinates at a time (alignment checked by the host)
     float scale;
 };
 
+// The packed factors stream through LDS in chunks of up to 16 KB (16 tile products), double-buffered
+// and shared by the four waves of a workgroup.
+constexpr int kBhChunkBytes = 16 * 1024;
+__host__ __device__ constexpr int bh_chunk_tiles(int N, int TB)
+{
+    // output tiles per chunk: 16 tile products = 16 / TB output tiles, at most the whole vector
+    return 16 / TB < N / 16 ? 16 / TB : N / 16;
+}
 // words of LDS per wave: one bit string of P*N bits per token
 __host__ __device__ inline int bh_bit_words(int P, int N) { return hash_bit_words(P, N); }
-__host__ inline size_t bh_lds_bytes(int P, int N) { return sizeof(uint32_t) * (size_t)kBhWaves * kBhTok * bh_bit_words(P, N); }
+__host__ inline size_t bh_lds_bytes(int P, int N)
+{
+    return 2 * (size_t)kBhChunkBytes + sizeof(uint32_t) * (size_t)kBhWaves * kBhTok * bh_bit_words(P, N);
+}
 
 // Packed factor layout: apack[p][f][o][ii][l][kk], o < N/16 output tiles, ii < b/16 input tiles of
 // o's block, l < 64 lanes, kk < 4 k-steps; the element is
@@ -73,27 +86,48 @@ __global__ __launch_bounds__(256) void bh_pack_kernel(const float *bmats, float 
 
 typedef float mfma_f4 __attribute__((ext_vector_type(4)));
 
-// LOG2N: d_pad = 2^LOG2N (64 .. 1024); TB = block / 16 (1, 2, 4)
-template <int LOG2N, int TB>
+// LOG2N: d_pad = 2^LOG2N (64 .. 1024); TB = block / 16 (1, 2, 4); VEC4: rows are read four coordinates
+// at a time (d % 4 == 0, aligned rows), else one by one
+template <int LOG2N, int TB, bool VEC4>
 __global__ __launch_bounds__(kBhThreads) void bh_hash_kernel(BhArgs a)
 {
     constexpr int N = 1 << LOG2N;
-    constexpr int NT = N / 16;  // tiles
-    static_assert(NT >= TB && NT >= 4, "d_pad of at least 64 and at least one block");
+    constexpr int NT = N / 16;                  // tiles
+    constexpr int CT = bh_chunk_tiles(N, TB);   // output tiles per chunk
+    constexpr int NCH = NT / CT;                // chunks per factor
+    constexpr int CQ = CT * TB;                 // tile products (1 KB of operands each) per chunk
+    static_assert(NT >= TB && NT >= 4 && NT % CT == 0 && CT % TB == 0, "chunks hold whole blocks");
+    static_assert(CQ * 1024 <= kBhChunkBytes, "a chunk fits its buffer");
     extern __shared__ uint32_t lds[];
     const unsigned lane = threadIdx.x & 63u;
     const unsigned wave = threadIdx.x >> 6;
     const unsigned tl = lane & 15u, g = lane >> 4;
     const int P = a.P;
     const int n_bitw = bh_bit_words(P, N);
-    uint32_t *bits = lds + wave * (kBhTok * n_bitw);  // [16 tokens][n_bitw]
+    const uint32_t lds0 = (uint32_t)(uintptr_t)lds;            // the two operand buffers
+    uint32_t *bits = lds + 2 * (kBhChunkBytes / 4) + wave * (kBhTok * n_bitw);  // [16 tokens][n_bitw]
 
     const long long n_groups = (a.n + kBhTok - 1) / kBhTok;
     const long long gw = (long long)blockIdx.x * kBhWaves + wave;
     const long long n_waves = (long long)gridDim.x * kBhWaves;
+    const long long iters = (n_groups + n_waves - 1) / n_waves;  // the same for every wave: the loop has barriers
     const float scale = a.scale;
 
-    for (long long grp = gw; grp < n_groups; grp += n_waves) {
+    // Operand stream: chunk q = (p * n_factors + f) * NCH + c is CQ KB at apack + q * CQ KB; every
+    // thread copies 16 bytes per KB-quarter.  The chunk after the last one wraps to the first (the
+    // next token group starts over).
+    const uint32_t n_chunks = (uint32_t)(P * a.n_factors * NCH);
+    auto copy_chunk = [&](uint32_t q, uint32_t buf) {
+        const char *src = reinterpret_cast<const char *>(a.apack) + (size_t)q * (CQ * 1024);  // uniform
+#pragma unroll
+        for (int i = 0; i < CQ / 4; ++i)
+            lds_dma16(src + i * 4096, threadIdx.x * 16u, lds0 + buf * kBhChunkBytes + i * 4096 + wave * 1024u);
+    };
+    uint32_t q = 0;  // chunk now in buffer q & 1
+    copy_chunk(0, 0);
+
+    for (long long it = 0; it < iters; ++it) {
+        const long long grp = gw + it * n_waves;
         const long long t = grp * kBhTok + tl;  // this lane's token
         const bool t_ok = t < a.n;
         for (int i = (int)lane; i < kBhTok * n_bitw; i += 64) bits[i] = 0;
@@ -102,43 +136,103 @@ __global__ __launch_bounds__(kBhThreads) void bh_hash_kernel(BhArgs a)
         for (int p = 0; p < P; ++p) {
             // ---- a1: this lane's coordinates of its token: tile beta, register r <-> 16*beta + g + 4r
             float v[NT][4];
-#pragma unroll
-            for (int beta = 0; beta < NT; ++beta)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int c = 16 * beta + (int)g + 4 * r;
-                    float f = 0.0f;
-                    if (t_ok && c < a.d) {
-                        if (a.x_bf16)
-                            f = __uint_as_float((uint32_t)((const uint16_t *)a.x)[t * a.d + c] << 16);
-                        else
-                            f = ((const float *)a.x)[t * a.d + c];
+            const long long tc = t_ok ? t : a.n - 1;  // idle token lanes read the last token and zero it
+            if constexpr (VEC4) {
+                // rows start on 16-byte (fp32) / 8-byte (bf16) boundaries and d % 4 == 0: the lane loads
+                // coordinates 16*beta + 4g .. + 3 in one piece (one base address per lane, the tile is an
+                // immediate offset; tiles wholly inside or outside the row are told apart by uniform
+                // branches), then a 4 x 4 transpose between lane groups and registers (two rounds of
+                // lane-row swaps) gives the layout above
+                const char *xrow = reinterpret_cast<const char *>(a.x) + (tc * a.d + 4 * (long long)g) * (a.x_bf16 ? 2 : 4);
+                auto piece = [&](int beta) -> float4 {
+                    if (a.x_bf16) {
+                        const uint2 w = *reinterpret_cast<const uint2 *>(xrow + beta * 32);
+                        return make_float4(__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xFFFF0000u),
+                                           __uint_as_float(w.y << 16), __uint_as_float(w.y & 0xFFFF0000u));
                     }
-                    v[beta][r] = f;
+                    return *reinterpret_cast<const float4 *>(xrow + beta * 64);
+                };
+#pragma unroll
+                for (int beta = 0; beta < NT; ++beta) {
+                    float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (16 * beta + 16 <= a.d) {
+                        f = piece(beta);
+                    } else if (16 * beta < a.d) {
+                        if (16 * beta + 4 * (int)g < a.d) f = piece(beta);
+                    }
+                    uint32_t e0 = t_ok ? __float_as_uint(f.x) : 0u, e1 = t_ok ? __float_as_uint(f.y) : 0u,
+                             e2 = t_ok ? __float_as_uint(f.z) : 0u, e3 = t_ok ? __float_as_uint(f.w) : 0u;
+                    // rows of 16 lanes = lane groups; swap16 exchanges (first, odd rows) with (second, even rows)
+                    auto s01 = __builtin_amdgcn_permlane16_swap(e0, e1, false, false);
+                    auto s23 = __builtin_amdgcn_permlane16_swap(e2, e3, false, false);
+                    // swap32 exchanges (first, upper half) with (second, lower half)
+                    auto s02 = __builtin_amdgcn_permlane32_swap(s01[0], s23[0], false, false);
+                    auto s13 = __builtin_amdgcn_permlane32_swap(s01[1], s23[1], false, false);
+                    v[beta][0] = __uint_as_float(s02[0]);
+                    v[beta][1] = __uint_as_float(s13[0]);
+                    v[beta][2] = __uint_as_float(s02[1]);
+                    v[beta][3] = __uint_as_float(s13[1]);
                 }
+            } else {
+#pragma unroll
+                for (int beta = 0; beta < NT; ++beta)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int c = 16 * beta + (int)g + 4 * r;
+                        float f = 0.0f;
+                        if (t_ok && c < a.d) {
+                            if (a.x_bf16)
+                                f = __uint_as_float((uint32_t)((const uint16_t *)a.x)[t * a.d + c] << 16);
+                            else
+                                f = ((const float *)a.x)[t * a.d + c];
+                        }
+                        v[beta][r] = f;
+                    }
+            }
 
             for (int f = 0; f < a.n_factors; ++f) {
                 // ---- block-diagonal factor on the matrix cores ---------------------------------
-                const mfma_f4 *ap = reinterpret_cast<const mfma_f4 *>(a.apack) +
-                                    ((size_t)(p * a.n_factors + f) * NT * TB) * 64 + lane;
 #pragma unroll
-                for (int blk = 0; blk < NT / TB; ++blk) {
-                    mfma_f4 acc[TB];
+                for (int c = 0; c < NCH; ++c) {
+                    // chunk q is complete in its buffer once every wave's copies have landed
+                    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+                    __syncthreads();
+                    const uint32_t buf = q & 1u;
+                    copy_chunk(q + 1 < n_chunks ? q + 1 : 0u, buf ^ 1u);
+                    const uint32_t abase = lds0 + buf * kBhChunkBytes + lane * 16u;
+                    // operand quads of the chunk in order ((block, output tile, input tile)); the read of
+                    // quad i+1 is issued before the four MFMAs of quad i so that it overlaps them
+                    auto ld_quad = [&](int qi) -> u32x4 {
+                        return *reinterpret_cast<const __attribute__((address_space(3))) u32x4 *>(
+                            (uintptr_t)(abase + (uint32_t)(qi * 1024)));
+                    };
+                    u32x4 aw = ld_quad(0);
 #pragma unroll
-                    for (int o = 0; o < TB; ++o) {
-                        acc[o] = mfma_f4{0.0f, 0.0f, 0.0f, 0.0f};
+                    for (int blk = 0; blk < CT / TB; ++blk) {
+                        mfma_f4 acc[TB];
 #pragma unroll
-                        for (int ii = 0; ii < TB; ++ii) {
-                            const mfma_f4 am = ap[((blk * TB + o) * TB + ii) * 64];
+                        for (int o = 0; o < TB; ++o) {
+                            acc[o] = mfma_f4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-                            for (int kk = 0; kk < 4; ++kk)
-                                acc[o] = __builtin_amdgcn_mfma_f32_16x16x4f32(am[kk], v[blk * TB + ii][kk], acc[o], 0, 0, 0);
+                            for (int ii = 0; ii < TB; ++ii) {
+                                const int qi = (blk * TB + o) * TB + ii;
+                                const u32x4 cur = aw;
+                                if (qi + 1 < CQ) aw = ld_quad(qi + 1);
+                                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                                for (int kk = 0; kk < 4; ++kk)
+                                    acc[o] = __builtin_amdgcn_mfma_f32_16x16x4f32(
+                                        __uint_as_float(cur[kk]), v[c * CT + blk * TB + ii][kk], acc[o], 0, 0, 0);
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
                         }
+#pragma unroll
+                        for (int o = 0; o < TB; ++o)
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) v[c * CT + blk * TB + o][r] = acc[o][r];
                     }
-#pragma unroll
-                    for (int o = 0; o < TB; ++o)
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) v[blk * TB + o][r] = acc[o][r];
+                    ++q;
+                    if (q == n_chunks) q = 0;
                 }
 
                 // ---- Walsh-Hadamard transform, ascending stride, then the scale -----------------
@@ -218,6 +312,8 @@ __global__ __launch_bounds__(kBhThreads) void bh_hash_kernel(BhArgs a)
         }
         wave_lds_fence();
     }
+
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // the last prefetched chunk is never used: let it land before the wave ends
 
     // zero the token padding of the packed layout
     if (a.packed) {

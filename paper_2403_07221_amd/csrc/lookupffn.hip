@@ -502,11 +502,20 @@ int64_t bh_pack_bytes(int d, int k, int tau, int block, int n_factors)
 template <int L>
 int launch_bh_t(const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s)
 {
-    switch (block) {
-        case 16: hipLaunchKernelGGL((bh_hash_kernel<L, 1>), grid, dim3(kBhThreads), lds, s, a); break;
-        case 32: hipLaunchKernelGGL((bh_hash_kernel<L, 2>), grid, dim3(kBhThreads), lds, s, a); break;
-        case 64: hipLaunchKernelGGL((bh_hash_kernel<L, 4>), grid, dim3(kBhThreads), lds, s, a); break;
-        default: return LFFN_E_UNSUPPORTED;
+    if (a.x_vec4) {
+        switch (block) {
+            case 16: hipLaunchKernelGGL((bh_hash_kernel<L, 1, true>), grid, dim3(kBhThreads), lds, s, a); break;
+            case 32: hipLaunchKernelGGL((bh_hash_kernel<L, 2, true>), grid, dim3(kBhThreads), lds, s, a); break;
+            case 64: hipLaunchKernelGGL((bh_hash_kernel<L, 4, true>), grid, dim3(kBhThreads), lds, s, a); break;
+            default: return LFFN_E_UNSUPPORTED;
+        }
+    } else {
+        switch (block) {
+            case 16: hipLaunchKernelGGL((bh_hash_kernel<L, 1, false>), grid, dim3(kBhThreads), lds, s, a); break;
+            case 32: hipLaunchKernelGGL((bh_hash_kernel<L, 2, false>), grid, dim3(kBhThreads), lds, s, a); break;
+            case 64: hipLaunchKernelGGL((bh_hash_kernel<L, 4, false>), grid, dim3(kBhThreads), lds, s, a); break;
+            default: return LFFN_E_UNSUPPORTED;
+        }
     }
     return LFFN_OK;
 }
@@ -530,6 +539,7 @@ int launch_hash_bh(const void *x, const float *bmats, float *apack, uint16_t *co
     a.n_factors = n_factors;
     a.P = (int)(((int64_t)k * tau + N - 1) / N);
     a.x_bf16 = x_dtype == LFFN_BF16;
+    a.x_vec4 = d % 4 == 0 && aligned(x, a.x_bf16 ? 8 : 16);
     a.scale = (float)(1.0 / std::sqrt((double)N));
     const long long total = (long long)a.P * n_factors * N * block;
     long long pb = (total + 255) / 256;
