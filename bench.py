@@ -196,6 +196,15 @@ def main():
         "whole_path": {"algorithmic_bytes_per_step": path_bytes,
                        "effective_GBps": path_bytes / (ms_per_step * 1e-3) / 1e9},
     }
+    if bh:
+        # the block-diagonal products are the path's one dense contraction: priced against the fp32
+        # matrix-core peak (flops of the products only; the transform and the code extraction ride along).
+        # The time is the hash step's event pair: the operand re-ordering kernel plus the hash kernel.
+        flops = w.n_proj * 4 * 2 * w.d_pad * args.block * w.n_tokens
+        hash_s = hash_ms / max(hash_n, 1) * 1e-3
+        out["hash_roofline"] = {"kernel": "bh_pack_kernel + bh_hash_kernel", "bound": "mfma", "achieved": flops / hash_s / 1e12,
+                                "peak": 157.3, "unit": "TFLOP/s", "frac": flops / hash_s / 1e12 / 157.3,
+                                "flops_per_launch": flops, "avg_kernel_ms": hash_s * 1e3}
     if w.n_layers > 1:
         # the same chain with every cache flushed before each pass (1 GiB overwrite, untimed):
         # the configuration is meant to show latency with the tables cold

@@ -44,9 +44,12 @@ struct BhArgs {
     float scale;
 };
 
-// The packed factors stream through LDS in chunks of up to 16 KB (16 tile products), double-buffered
-// and shared by the four waves of a workgroup.
+// The packed factors stream through LDS in chunks of up to 16 KB (16 tile products) shared by the
+// four waves of a workgroup, through a ring of four buffers: a chunk is requested three chunks
+// ahead of its use (a chunk of block-16 products is consumed in about 0.2 us, far less than a trip
+// to L2), and the requests for the next factor travel while the transform runs.
 constexpr int kBhChunkBytes = 16 * 1024;
+constexpr int kBhRing = 4;
 __host__ __device__ constexpr int bh_chunk_tiles(int N, int TB)
 {
     // output tiles per chunk: 16 tile products = 16 / TB output tiles, at most the whole vector
@@ -56,7 +59,7 @@ __host__ __device__ constexpr int bh_chunk_tiles(int N, int TB)
 __host__ __device__ inline int bh_bit_words(int P, int N) { return hash_bit_words(P, N); }
 __host__ inline size_t bh_lds_bytes(int P, int N)
 {
-    return 2 * (size_t)kBhChunkBytes + sizeof(uint32_t) * (size_t)kBhWaves * kBhTok * bh_bit_words(P, N);
+    return kBhRing * (size_t)kBhChunkBytes + sizeof(uint32_t) * (size_t)kBhWaves * kBhTok * bh_bit_words(P, N);
 }
 
 // Packed factor layout: apack[p][f][o][ii][l][kk], o < N/16 output tiles, ii < b/16 input tiles of
@@ -105,7 +108,7 @@ __global__ __launch_bounds__(kBhThreads) void bh_hash_kernel(BhArgs a)
     const int P = a.P;
     const int n_bitw = bh_bit_words(P, N);
     const uint32_t lds0 = (uint32_t)(uintptr_t)lds;            // the two operand buffers
-    uint32_t *bits = lds + 2 * (kBhChunkBytes / 4) + wave * (kBhTok * n_bitw);  // [16 tokens][n_bitw]
+    uint32_t *bits = lds + kBhRing * (kBhChunkBytes / 4) + wave * (kBhTok * n_bitw);  // [16 tokens][n_bitw]
 
     const long long n_groups = (a.n + kBhTok - 1) / kBhTok;
     const long long gw = (long long)blockIdx.x * kBhWaves + wave;
@@ -113,18 +116,24 @@ __global__ __launch_bounds__(kBhThreads) void bh_hash_kernel(BhArgs a)
     const long long iters = (n_groups + n_waves - 1) / n_waves;  // the same for every wave: the loop has barriers
     const float scale = a.scale;
 
-    // Operand stream: chunk q = (p * n_factors + f) * NCH + c is CQ KB at apack + q * CQ KB; every
-    // thread copies 16 bytes per KB-quarter.  The chunk after the last one wraps to the first (the
-    // next token group starts over).
+    // Operand stream: chunk id (p * n_factors + f) * NCH + c is CQ KB at apack + id * CQ KB; every
+    // thread copies 16 bytes per 4 KB.  The stream is cyclic (the next token group starts over); the
+    // chunk with sequence number `seq` sits in ring buffer seq % kBhRing.
     const uint32_t n_chunks = (uint32_t)(P * a.n_factors * NCH);
-    auto copy_chunk = [&](uint32_t q, uint32_t buf) {
-        const char *src = reinterpret_cast<const char *>(a.apack) + (size_t)q * (CQ * 1024);  // uniform
+    constexpr int kCopies = CQ / 4;  // copy instructions per thread and chunk
+    auto copy_chunk = [&](uint32_t id, uint32_t buf) {
+        const char *src = reinterpret_cast<const char *>(a.apack) + (size_t)id * (CQ * 1024);  // uniform
 #pragma unroll
-        for (int i = 0; i < CQ / 4; ++i)
+        for (int i = 0; i < kCopies; ++i)
             lds_dma16(src + i * 4096, threadIdx.x * 16u, lds0 + buf * kBhChunkBytes + i * 4096 + wave * 1024u);
     };
-    uint32_t q = 0;  // chunk now in buffer q & 1
-    copy_chunk(0, 0);
+    uint32_t seq = 0;      // sequence number of the chunk consumed next
+    uint32_t next_id = 0;  // id of the chunk requested next (sequence number seq + kBhRing - 1 once primed)
+#pragma unroll
+    for (int i = 0; i < kBhRing - 1; ++i) {
+        copy_chunk(next_id, (uint32_t)i);
+        next_id = next_id + 1 < n_chunks ? next_id + 1 : 0u;
+    }
 
     for (long long it = 0; it < iters; ++it) {
         const long long grp = gw + it * n_waves;
@@ -194,11 +203,18 @@ __global__ __launch_bounds__(kBhThreads) void bh_hash_kernel(BhArgs a)
                 // ---- block-diagonal factor on the matrix cores ---------------------------------
 #pragma unroll
                 for (int c = 0; c < NCH; ++c) {
-                    // chunk q is complete in its buffer once every wave's copies have landed
-                    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+                    // This chunk is complete once every wave's copies of it have landed: vector-memory
+                    // operations retire in order, so all but the newest 2 * kCopies (the two chunks
+                    // requested after it) must be done.  The barrier also frees the buffer of the
+                    // previous chunk for the next request.
+                    static_assert(kBhRing == 4 && 2 * kCopies <= 8, "wait count below");
+                    if constexpr (kCopies == 4) __builtin_amdgcn_s_waitcnt(0x0F70 | 8);       // vmcnt(8)
+                    else if constexpr (kCopies == 2) __builtin_amdgcn_s_waitcnt(0x0F70 | 4);  // vmcnt(4)
+                    else __builtin_amdgcn_s_waitcnt(0x0F70 | 2);                               // vmcnt(2)
                     __syncthreads();
-                    const uint32_t buf = q & 1u;
-                    copy_chunk(q + 1 < n_chunks ? q + 1 : 0u, buf ^ 1u);
+                    const uint32_t buf = seq % kBhRing;
+                    copy_chunk(next_id, (seq + kBhRing - 1) % kBhRing);
+                    next_id = next_id + 1 < n_chunks ? next_id + 1 : 0u;
                     const uint32_t abase = lds0 + buf * kBhChunkBytes + lane * 16u;
                     // operand quads of the chunk in order ((block, output tile, input tile)); the read of
                     // quad i+1 is issued before the four MFMAs of quad i so that it overlaps them
@@ -231,8 +247,7 @@ __global__ __launch_bounds__(kBhThreads) void bh_hash_kernel(BhArgs a)
 #pragma unroll
                             for (int r = 0; r < 4; ++r) v[c * CT + blk * TB + o][r] = acc[o][r];
                     }
-                    ++q;
-                    if (q == n_chunks) q = 0;
+                    ++seq;
                 }
 
                 // ---- Walsh-Hadamard transform, ascending stride, then the scale -----------------
@@ -313,7 +328,7 @@ __global__ __launch_bounds__(kBhThreads) void bh_hash_kernel(BhArgs a)
         wave_lds_fence();
     }
 
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // the last prefetched chunk is never used: let it land before the wave ends
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // the last requested chunks are never used: let them land before the wave ends
 
     // zero the token padding of the packed layout
     if (a.packed) {

@@ -487,7 +487,7 @@ int check_bh(const void *x, const float *bmats, int64_t n, int d, int k, int tau
     if (block != 16 && block != 32 && block != 64) return LFFN_E_UNSUPPORTED;
     if (block > N) return LFFN_E_SIZE;
     const int64_t P = ((int64_t)k * tau + N - 1) / N;
-    if (P > 64 || bh_lds_bytes((int)P, N) > 64 * 1024) return LFFN_E_UNSUPPORTED;
+    if (P > 64 || bh_lds_bytes((int)P, N) > 150 * 1024) return LFFN_E_UNSUPPORTED;
     if (!aligned(x, x_dtype == LFFN_F32 ? 4 : 2) || !aligned(bmats, 4)) return LFFN_E_ALIGN;
     return LFFN_OK;
 }
@@ -499,25 +499,50 @@ int64_t bh_pack_bytes(int d, int k, int tau, int block, int n_factors)
     return round256(P * n_factors * (int64_t)N * block * 4);
 }
 
+// kernels that use more than 64 KB of dynamic LDS must be told so once per device
+template <class K>
+int allow_lds(K kern, size_t lds)
+{
+    static std::mutex mu;
+    static std::map<int, size_t> configured;  // device -> LDS bytes this kernel is set up for
+    int dev = 0;
+    LFFN_HIP(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lk(mu);
+    if (configured[dev] < lds) {
+        LFFN_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)lds));
+        configured[dev] = lds;
+    }
+    return LFFN_OK;
+}
+
+template <int L, int TB, bool VEC4>
+int launch_bh_k(const BhArgs &a, dim3 grid, size_t lds, hipStream_t s)
+{
+    auto kern = bh_hash_kernel<L, TB, VEC4>;
+    int rc = allow_lds(kern, lds);
+    if (rc != LFFN_OK) return rc;
+    hipLaunchKernelGGL(kern, grid, dim3(kBhThreads), lds, s, a);
+    return LFFN_OK;
+}
+
 template <int L>
 int launch_bh_t(const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s)
 {
     if (a.x_vec4) {
         switch (block) {
-            case 16: hipLaunchKernelGGL((bh_hash_kernel<L, 1, true>), grid, dim3(kBhThreads), lds, s, a); break;
-            case 32: hipLaunchKernelGGL((bh_hash_kernel<L, 2, true>), grid, dim3(kBhThreads), lds, s, a); break;
-            case 64: hipLaunchKernelGGL((bh_hash_kernel<L, 4, true>), grid, dim3(kBhThreads), lds, s, a); break;
-            default: return LFFN_E_UNSUPPORTED;
+            case 16: return launch_bh_k<L, 1, true>(a, grid, lds, s);
+            case 32: return launch_bh_k<L, 2, true>(a, grid, lds, s);
+            case 64: return launch_bh_k<L, 4, true>(a, grid, lds, s);
         }
     } else {
         switch (block) {
-            case 16: hipLaunchKernelGGL((bh_hash_kernel<L, 1, false>), grid, dim3(kBhThreads), lds, s, a); break;
-            case 32: hipLaunchKernelGGL((bh_hash_kernel<L, 2, false>), grid, dim3(kBhThreads), lds, s, a); break;
-            case 64: hipLaunchKernelGGL((bh_hash_kernel<L, 4, false>), grid, dim3(kBhThreads), lds, s, a); break;
-            default: return LFFN_E_UNSUPPORTED;
+            case 16: return launch_bh_k<L, 1, false>(a, grid, lds, s);
+            case 32: return launch_bh_k<L, 2, false>(a, grid, lds, s);
+            case 64: return launch_bh_k<L, 4, false>(a, grid, lds, s);
         }
     }
-    return LFFN_OK;
+    return LFFN_E_UNSUPPORTED;
 }
 
 // Packs the factors into `apack` (bh_pack_bytes) and hashes; writes codes[n][k] or the packed layout.
