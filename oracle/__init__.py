@@ -61,6 +61,9 @@ def lib() -> ctypes.CDLL:
         L.oracle_forward.argtypes = [vp, ci, vp, vp, ci, vp, vp, i64, ci, ci, ci, ci, ci, ci]
         L.oracle_bh_hash.argtypes = [vp, ci, vp, vp, vp, i64, ci, ci, ci, ci, ci]
         L.oracle_bh_forward.argtypes = [vp, ci, vp, vp, ci, vp, vp, i64, ci, ci, ci, ci, ci, ci, ci]
+        L.oracle_probe_weights_from_z.argtypes = [vp, i64, vp, vp, i64, ci, ci]
+        L.oracle_gather_probes.argtypes = [vp, vp, vp, ci, vp, i64, ci, ci, ci]
+        L.oracle_forward_probes.argtypes = [vp, ci, vp, vp, ci, vp, vp, vp, i64, ci, ci, ci, ci, ci]
         L.oracle_weights_from_z.argtypes = [vp, i64, vp, i64, ci, ci]
         L.oracle_weights.argtypes = [vp, ci, vp, vp, i64, ci, ci, ci, ci]
         L.oracle_gather_weighted.argtypes = [vp, vp, vp, ci, vp, i64, ci, ci, ci]
@@ -277,3 +280,46 @@ def bh_forward(x: np.ndarray, bmats: np.ndarray, tables: np.ndarray, acc64: bool
     _check(lib().oracle_bh_forward(_ptr(x), _dtype_code(x), _ptr(bmats), _ptr(tables), _dtype_code(tables), _ptr(y),
                                    _ptr(codes), n, d, k, tau, d_out, b, m, int(acc64)), "bh_forward")
     return (y, codes) if return_codes else y
+
+
+# ---- multi-probe lookup (Sec. 3.1, eq. "partial_softmax", neighbourhood of l0 radius 1) ---------
+
+def probe_weights_from_z(z: np.ndarray, k: int, tau: int):
+    """(codes[n, k] uint16, p[n, k, 1+tau] float64) from soft codes z[n, >= k*tau] float32."""
+    z = np.ascontiguousarray(z, dtype=np.float32)
+    n, zs = z.shape
+    codes = np.empty((n, k), dtype=np.uint16)
+    p = np.empty((n, k, tau + 1), dtype=np.float64)
+    _check(lib().oracle_probe_weights_from_z(_ptr(z), zs, _ptr(codes), _ptr(p), n, k, tau), "probe_weights_from_z")
+    return codes, p
+
+
+def gather_probes(codes: np.ndarray, p: np.ndarray, tables: np.ndarray) -> np.ndarray:
+    """y[n, d_out] = sum_j sum_probe p[:, j, probe] * tables[j, row(probe), :]."""
+    n, k = codes.shape
+    k2, rows, d_out = tables.shape
+    tau = rows.bit_length() - 1
+    assert k2 == k and 1 << tau == rows and codes.dtype == np.uint16 and p.shape == (n, k, tau + 1)
+    codes, tables = np.ascontiguousarray(codes), np.ascontiguousarray(tables)
+    p = np.ascontiguousarray(p, dtype=np.float64)
+    y = np.empty((n, d_out), dtype=np.float32)
+    _check(lib().oracle_gather_probes(_ptr(codes), _ptr(p), _ptr(tables), _dtype_code(tables), _ptr(y), n, k, tau,
+                                      d_out), "gather_probes")
+    return y
+
+
+def forward_probes(x: np.ndarray, signs: np.ndarray, tables: np.ndarray, return_all: bool = False):
+    """Whole multi-probe forward pass; y[n, d_out] float32 (and codes, probe weights on request)."""
+    n, d = x.shape
+    k, rows, d_out = tables.shape
+    tau = rows.bit_length() - 1
+    assert 1 << tau == rows
+    n_rounds = signs.shape[1]
+    _check_signs(signs, d, k, tau, n_rounds)
+    x, signs, tables = np.ascontiguousarray(x), np.ascontiguousarray(signs), np.ascontiguousarray(tables)
+    y = np.empty((n, d_out), dtype=np.float32)
+    codes = np.empty((n, k), dtype=np.uint16)
+    p = np.empty((n, k, tau + 1), dtype=np.float64)
+    _check(lib().oracle_forward_probes(_ptr(x), _dtype_code(x), _ptr(signs), _ptr(tables), _dtype_code(tables),
+                                       _ptr(y), _ptr(codes), _ptr(p), n, d, k, tau, d_out, n_rounds), "forward_probes")
+    return (y, codes, p) if return_all else y

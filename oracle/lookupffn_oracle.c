@@ -436,6 +436,91 @@ int oracle_forward_weighted(const void *x, int x_dtype, const int8_t *signs, con
 }
 
 /*
+ * Multi-probe lookup (Sec. 3.1, eq. "partial_softmax") with the neighbourhood
+ *   N(z_k) = { i : || S_i - sign(z_k) ||_0 <= 1 }
+ * i.e. the row g(z_k) and the tau rows one sign flip away from it ("sampled according to the l0
+ * difference"), each weighted by its soft-max share:
+ *   y = sum_k sum_{i in N(z_k)} exp(<z_k,S_i>) T_k[i] / prod_j (exp(z_kj) + exp(-z_kj)).
+ * Probe order per table: g, then g with bit 0 flipped, bit 1 flipped, ...  The soft codes z are the
+ * hash's fp32 values; weights and sums are fp64.
+ *   z [n][zstride] fp32;  codes (out, may be NULL) [n][k];  p (out, may be NULL) [n][k][1+tau] fp64
+ */
+int oracle_probe_weights_from_z(const float *z, int64_t zstride, uint16_t *codes, double *p, int64_t n, int k, int tau)
+{
+    if (n < 0 || k < 1 || tau < 1 || tau > 16 || zstride < (int64_t)k * tau || !z) return ORACLE_E_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < n; ++t) {
+        for (int j = 0; j < k; ++j) {
+            const float *zk = z + t * zstride + (int64_t)j * tau;
+            unsigned g = 0;
+            double denom = 1.0;
+            for (int b = 0; b < tau; ++b) {
+                if (zk[b] >= 0.0f) g |= 1u << b;
+                denom *= exp((double)zk[b]) + exp(-(double)zk[b]);
+            }
+            if (codes) codes[t * k + j] = (uint16_t)g;
+            if (!p) continue;
+            for (int probe = 0; probe <= tau; ++probe) {
+                const unsigned i = probe == 0 ? g : g ^ (1u << (probe - 1));
+                double score = 0.0;  /* <z_k, S_i>, S_i[b] = +1 where bit b of i is set, else -1 */
+                for (int b = 0; b < tau; ++b) score += ((i >> b) & 1u) ? (double)zk[b] : -(double)zk[b];
+                p[(t * k + j) * (tau + 1) + probe] = exp(score) / denom;
+            }
+        }
+    }
+    return ORACLE_OK;
+}
+
+/* y[t] = sum_j sum_probe p[t][j][probe] * T_j[row(probe)], fp64 accumulation, one rounding. */
+int oracle_gather_probes(const uint16_t *codes, const double *p, const void *tables, int table_dtype, float *y,
+                         int64_t n, int k, int tau, int d_out)
+{
+    if (n < 0 || k < 1 || tau < 1 || tau > 16 || d_out < 1 || !codes || !p || !tables || !y) return ORACLE_E_ARG;
+    const int64_t rows = (int64_t)1 << tau;
+    int bad = 0;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < n; ++t) {
+        for (int c = 0; c < d_out; ++c) {
+            double s = 0.0;
+            for (int j = 0; j < k; ++j) {
+                int64_t g = codes[t * k + j];
+                if (g >= rows) {
+#pragma omp atomic write
+                    bad = 1;
+                    g = 0;
+                }
+                for (int probe = 0; probe <= tau; ++probe) {
+                    const int64_t i = probe == 0 ? g : g ^ ((int64_t)1 << (probe - 1));
+                    s += p[(t * k + j) * (tau + 1) + probe] *
+                         (double)load_elt(tables, table_dtype, ((int64_t)j * rows + i) * d_out + c);
+                }
+            }
+            y[t * d_out + c] = (float)s;
+        }
+    }
+    return bad ? ORACLE_E_ARG : ORACLE_OK;
+}
+
+/* Whole multi-probe forward pass: sign-diagonal hash (fp32 z), probe weights, weighted sum. */
+int oracle_forward_probes(const void *x, int x_dtype, const int8_t *signs, const void *tables, int table_dtype,
+                          float *y, uint16_t *codes_out, double *p_out, int64_t n, int d, int k, int tau, int d_out,
+                          int n_rounds)
+{
+    if (check_shape(n, d, k, tau, n_rounds) || !y || !tables || !codes_out) return ORACLE_E_ARG;
+    const int64_t zs = (int64_t)oracle_n_proj(d, k, tau) * oracle_d_pad(d);
+    const size_t cnt = (size_t)(n > 0 ? n : 1);
+    float *z = (float *)malloc(sizeof(float) * cnt * zs);
+    double *p = p_out ? p_out : (double *)malloc(sizeof(double) * cnt * k * (tau + 1));
+    int rc = (z && p) ? ORACLE_OK : ORACLE_E_NOMEM;
+    if (rc == ORACLE_OK) rc = oracle_soft_codes(x, x_dtype, signs, z, n, d, k, tau, n_rounds);
+    if (rc == ORACLE_OK) rc = oracle_probe_weights_from_z(z, zs, codes_out, p, n, k, tau);
+    if (rc == ORACLE_OK) rc = oracle_gather_probes(codes_out, p, tables, table_dtype, y, n, k, tau, d_out);
+    free(z);
+    if (!p_out) free(p);
+    return rc;
+}
+
+/*
  * Whole forward pass: Hash then Gather (Sec. 3.1 "Two main operations").
  * codes_out may be NULL.
  */
