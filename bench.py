@@ -37,6 +37,9 @@ def parse_args():
     ap.add_argument("--weighted", action="store_true",
                     help="time the weighted variant (lookupffn_forward_weighted: the hash also emits one fp32 "
                          "weight per token and table, the gather multiplies each row by it) instead of the plain sum")
+    ap.add_argument("--probes", action="store_true",
+                    help="time the multi-probe lookup (lookupffn_forward_probes: 1 + tau rows per token and table, "
+                         "weighted by their soft-max shares)")
     ap.add_argument("--hash", choices=["sign-diagonal", "bh4"], default="sign-diagonal",
                     help="hash of the pass: the sign-diagonal x Hadamard rounds of the headline metric, or the "
                          "paper's BH4 (four block-diagonal x Hadamard factors, lookupffn_forward_bh)")
@@ -60,14 +63,15 @@ def traffic_from_profiles(w, weighted: bool = False) -> float | None:
     return None
 
 
-def cpu_baseline(w, x, signs, tables, budget_s: float, weighted: bool = False, bh: bool = False) -> dict:
+def cpu_baseline(w, x, signs, tables, budget_s: float, weighted: bool = False, bh: bool = False,
+                 probes: bool = False) -> dict:
     """The CPU oracle as it stands, on all host threads it gets, on the same batch."""
     import oracle  # only this leg of the bench touches the oracle
     threads = oracle.max_threads()
     n = x.shape[0]
     sample = min(n, 16384)
     xs = x[:sample]
-    run = oracle.bh_forward if bh else oracle.forward_weighted if weighted else oracle.forward
+    run = oracle.bh_forward if bh else oracle.forward_probes if probes else oracle.forward_weighted if weighted else oracle.forward
     run(xs[:256], signs, tables)                       # page in
     reps, t_total = 0, 0.0
     while reps < 3 or (t_total < budget_s and reps < 1000):
@@ -100,14 +104,20 @@ def main():
     B.lib()
     w = synth.CONFIGS[args.config]
     bh = args.hash == "bh4"
-    if bh and (args.weighted or w.n_layers > 1):
+    if args.probes and args.weighted:
+        print("--probes and --weighted are different variants: pick one", file=sys.stderr)
+        sys.exit(2)
+    if bh and (args.weighted or args.probes or w.n_layers > 1):
         print("--hash bh4 is timed with the plain-sum gather on the single-layer configurations", file=sys.stderr)
         sys.exit(2)
     ws_bytes = (B.lookupffn_workspace_bytes_weighted if args.weighted else B.lookupffn_workspace_bytes)(w.n_tokens, w.k)
+    if args.probes:
+        ws_bytes = B.lookupffn_workspace_bytes_probes(w.n_tokens, w.k, w.tau)
     if bh:
         ws_bytes = B.lookupffn_workspace_bytes_bh(w.n_tokens, w.d, w.k, w.tau, args.block, 4)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
-    forward = B.lookupffn_forward_bh if bh else B.lookupffn_forward_weighted if args.weighted else B.lookupffn_forward
+    forward = (B.lookupffn_forward_bh if bh else B.lookupffn_forward_probes if args.probes
+               else B.lookupffn_forward_weighted if args.weighted else B.lookupffn_forward)
     if w.n_layers == 1:
         x, signs, tables = synth.make_layer(w)
         if bh:   # the block-diagonal factors take the place of the sign diagonals
@@ -164,6 +174,10 @@ def main():
     path_bytes = cost.bytes_per_token(w.d, w.k, w.d_out, xb, tb) * w.n_tokens * w.n_layers
     # the gather kernel alone: k table rows + the y row + the k uint16 codes it reads, per token
     gather_bytes = (w.k * w.d_out * tb + w.d_out * 4 + w.k * 2) * w.n_tokens
+    if args.probes:
+        # (1 + tau) rows and shares per token and table
+        gather_bytes = (w.k * (w.tau + 1) * (w.d_out * tb + 4) + w.d_out * 4 + w.k * 2) * w.n_tokens
+        path_bytes += (w.k * w.tau * w.d_out * tb + 2 * w.k * (w.tau + 1) * 4) * w.n_tokens * w.n_layers
     if args.weighted:
         gather_bytes += w.k * 4 * w.n_tokens          # the fp32 weights it reads
         path_bytes += 2 * w.k * 4 * w.n_tokens * w.n_layers   # written by the hash, read by the gather
@@ -187,7 +201,7 @@ def main():
                    "hash_rounds": w.n_rounds, "k_tables": w.k, "tau": w.tau, "d_out": w.d_out,
                    "x_dtype": w.x_dtype, "table_dtype": w.table_dtype,
                    "table_bytes": w.k * w.rows * w.d_out * tb,
-                   "variant": "weighted" if args.weighted else "plain-sum",
+                   "variant": "weighted" if args.weighted else "multi-probe" if args.probes else "plain-sum",
                    "hash": f"bh4-block{args.block}" if bh else "sign-diagonal"},
         "roofline": {"kernel": B.lookupffn_last_gather_kernel(), "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_from_profiles(w, args.weighted),
@@ -232,7 +246,7 @@ def main():
         torch.cuda.synchronize()
         out["copy_calibration_bytes_each_way"] = src.numel() * 4
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, x, signs, tables, args.cpu_seconds, args.weighted, bh)
+        out["cpu_baseline"] = cpu_baseline(w, x, signs, tables, args.cpu_seconds, args.weighted, bh, args.probes)
         if w.n_layers > 1:
             out["cpu_baseline"]["sample"] += "; one layer (the first) of the chain"
     print(json.dumps(out))

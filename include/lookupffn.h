@@ -118,6 +118,29 @@ int lookupffn_forward_weighted(const void *x, const int8_t *signs, const void *t
 int64_t lookupffn_workspace_bytes_weighted(int64_t n_tokens, int k);
 
 /*
+ * Multi-probe lookup (Sec. 3.1, eq. "partial_softmax" with the neighbourhood "rows within one sign
+ * flip of sign(z_j)"): per table the selected row and its tau one-bit neighbours, each weighted by its
+ * soft-max share exp(<z_j,S_i>) / prod_b (exp(z_jb) + exp(-z_jb)):
+ *   y = sum_j sum_{probe=0..tau} shares[t][j][probe] * tables[j][code_j ^ flip(probe)][:],
+ *   flip(0) = 0, flip(probe) = 1 << (probe-1).
+ * lookupffn_hash_probes writes codes[n_tokens][k] and shares[n_tokens][k][1+tau] (fp32, 4-byte
+ * aligned); lookupffn_gather_probes does the sum ((1 + tau) row reads per token and table);
+ * lookupffn_forward_probes chains them with lookupffn_workspace_bytes_probes() bytes of scratch.
+ * Same hash, conventions and limits as the weighted variant.
+ */
+int lookupffn_hash_probes(const void *x, const int8_t *signs, uint16_t *codes, float *shares,
+                          int64_t n_tokens, int d, int k, int tau,
+                          int n_rounds, int x_dtype, void *hip_stream);
+int lookupffn_gather_probes(const uint16_t *codes, const float *shares, const void *tables, float *y,
+                            int64_t n_tokens, int k, int tau, int d_out,
+                            int table_dtype, void *hip_stream);
+int lookupffn_forward_probes(const void *x, const int8_t *signs, const void *tables, float *y,
+                             int64_t n_tokens, int d, int k, int tau, int d_out,
+                             int n_rounds, int x_dtype, int table_dtype,
+                             void *workspace, int64_t workspace_bytes, void *hip_stream);
+int64_t lookupffn_workspace_bytes_probes(int64_t n_tokens, int k, int tau);
+
+/*
  * BH{m} hash (Sec. 3.2, eq. "block_acdc"): z = x R with R = prod_{i=1..n_factors} B_i H per
  * projection, B_i block-diagonal with `block` x `block` blocks (16, 32 or 64), H as above; codes as
  * above.  (v B)_j = sum_c v_c B[c][j] over j's block is accumulated in fp32 as a chain of fused

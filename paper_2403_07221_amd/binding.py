@@ -24,6 +24,8 @@ EXPORTS = (
     "lookupffn_hash_weighted", "lookupffn_gather_weighted", "lookupffn_forward_weighted",
     "lookupffn_workspace_bytes_weighted",
     "lookupffn_hash_bh", "lookupffn_forward_bh", "lookupffn_workspace_bytes_bh",
+    "lookupffn_hash_probes", "lookupffn_gather_probes", "lookupffn_forward_probes",
+    "lookupffn_workspace_bytes_probes",
 )
 
 
@@ -53,6 +55,11 @@ def lib() -> ctypes.CDLL:
         L.lookupffn_forward_weighted.argtypes = L.lookupffn_forward.argtypes
         L.lookupffn_workspace_bytes_weighted.argtypes = [i64, ci]
         L.lookupffn_workspace_bytes_weighted.restype = i64
+        L.lookupffn_hash_probes.argtypes = L.lookupffn_hash_weighted.argtypes
+        L.lookupffn_gather_probes.argtypes = L.lookupffn_gather_weighted.argtypes
+        L.lookupffn_forward_probes.argtypes = L.lookupffn_forward.argtypes
+        L.lookupffn_workspace_bytes_probes.argtypes = [i64, ci, ci]
+        L.lookupffn_workspace_bytes_probes.restype = i64
         L.lookupffn_hash_bh.argtypes = [vp, vp, vp, i64, ci, ci, ci, ci, ci, ci, vp, i64, vp]
         L.lookupffn_forward_bh.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, ci, ci, ci, vp, i64, vp]
         L.lookupffn_workspace_bytes_bh.argtypes = [i64, ci, ci, ci, ci, ci]
@@ -188,6 +195,52 @@ def lookupffn_gather_weighted(codes: torch.Tensor, weights: torch.Tensor, tables
                                                _dev(tables, "tables"), _dev(y, "y"), n, k, tau, d_out,
                                                _dtype_code(tables), _stream(tables)))
     return y
+
+
+def lookupffn_hash_probes(x: torch.Tensor, signs: torch.Tensor, k: int, tau: int):
+    """(codes[n, k] int16 storage, shares[n, k, 1+tau] float32) of the multi-probe lookup."""
+    n, d = x.shape
+    _check_signs(signs, d, k, tau)
+    codes = torch.empty((n, k), dtype=torch.int16, device=x.device)
+    shares = torch.empty((n, k, tau + 1), dtype=torch.float32, device=x.device)
+    if n == 0:
+        return codes, shares
+    with torch.cuda.device(x.device):
+        _check(lib().lookupffn_hash_probes(_dev(x, "x"), _dev(signs, "signs"), _dev(codes, "codes"),
+                                           _dev(shares, "shares"), n, d, k, tau, signs.shape[1], _dtype_code(x),
+                                           _stream(x)))
+    return codes, shares
+
+
+def lookupffn_gather_probes(codes: torch.Tensor, shares: torch.Tensor, tables: torch.Tensor,
+                            y: torch.Tensor | None = None) -> torch.Tensor:
+    """y[n, d_out] = sum_j sum_probe shares[:, j, probe] * tables[j, codes[:, j] ^ flip(probe), :]."""
+    n, k = codes.shape
+    k2, rows, d_out = tables.shape
+    tau = rows.bit_length() - 1
+    if k2 != k or (1 << tau) != rows:
+        raise ValueError("tables must be [k, 2^tau, d_out] with k matching codes")
+    assert codes.dtype == torch.int16
+    assert shares.dtype == torch.float32 and tuple(shares.shape) == (n, k, tau + 1)
+    if y is None:
+        y = torch.empty((n, d_out), dtype=torch.float32, device=tables.device)
+    assert y.dtype == torch.float32 and tuple(y.shape) == (n, d_out)
+    if n == 0:
+        return y
+    with torch.cuda.device(tables.device):
+        _check(lib().lookupffn_gather_probes(_dev(codes, "codes"), _dev(shares, "shares"), _dev(tables, "tables"),
+                                             _dev(y, "y"), n, k, tau, d_out, _dtype_code(tables), _stream(tables)))
+    return y
+
+
+def lookupffn_workspace_bytes_probes(n_tokens: int, k: int, tau: int) -> int:
+    return lib().lookupffn_workspace_bytes_probes(n_tokens, k, tau)
+
+
+def lookupffn_forward_probes(x: torch.Tensor, signs: torch.Tensor, tables: torch.Tensor,
+                             y: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """Whole multi-probe forward pass y[n, d_out] (Sec. 3.1, eq. "partial_softmax")."""
+    return lookupffn_forward(x, signs, tables, y, workspace, _entry="lookupffn_forward_probes")
 
 
 def lookupffn_workspace_bytes(n_tokens: int, k: int) -> int:

@@ -1,7 +1,9 @@
 // Gather step of the LookupFFN forward pass for gfx950:
 //   y[t][:] = sum_{j<k} tables[j][code[t][j]][:]        (Sec. 3.1, eq. "lookup")
 // and its weighted form y[t][:] = sum_j w[t][j] * tables[j][code[t][j]][:] (Sec. 4; one fused
-// multiply-add per element and table, in table order).
+// multiply-add per element and table, in table order), and the multi-probe form
+//   y[t][:] = sum_j sum_{probe <= tau} p[t][j][probe] * tables[j][code ^ flip(probe)][:]
+// (Sec. 3.1, eq. "partial_softmax": the selected row, then the rows one bit away, bit 0 first).
 //
 // Work decomposition.  A table row is cut into column slices of LPT lanes x 16
 // bytes (LPT = "lanes per token"); a wavefront handles 64/LPT tokens of one
@@ -28,7 +30,8 @@ constexpr int kXcds = 8;
 
 struct GatherArgs {
     const uint16_t *codes;  // [n][k]
-    const float *weights;   // [n][k] for the weighted form, else NULL
+    const float *weights;   // [n][k] for the weighted form, [n][k][1+tau] for the multi-probe form, else NULL
+    int probes;             // 1: multi-probe form
     const char *tables;     // [k][rows][d_out] fp32 or bf16
     float *y;               // [n][d_out]
     long long n;
@@ -148,7 +151,28 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a)
     acc.zero();
 
     int j0 = 0;
-    if constexpr (WEIGHTED) {
+    if (WEIGHTED && a.probes) {
+        const float *wp = a.weights + t * a.k * (tau + 1);
+        const int np = tau + 1;
+        for (int j = 0; j < k; ++j, wp += np) {
+            const uint32_t g = crow[j] & rmask;
+            int pr = 0;
+            for (; pr + 3 <= np; pr += 3) {  // three probes at a time: rows and shares first, then the adds
+                uint4 r[3];
+                float w[3];
+#pragma unroll
+                for (int u = 0; u < 3; ++u) {
+                    const int q = pr + u;
+                    r[u] = row(j, q == 0 ? g : g ^ (1u << (q - 1)));
+                    w[u] = wp[q];
+                }
+#pragma unroll
+                for (int u = 0; u < 3; ++u) acc.fma(r[u], w[u]);
+            }
+            for (; pr < np; ++pr) acc.fma(row(j, pr == 0 ? g : g ^ (1u << (pr - 1))), wp[pr]);
+        }
+        j0 = k;
+    } else if constexpr (WEIGHTED) {
         const float *wrow = a.weights + t * a.k;
         if (a.codes_vec8) {
             const uint4 *c8 = reinterpret_cast<const uint4 *>(crow);

@@ -39,6 +39,7 @@ struct HashArgs {
     uint32_t *packed;     // packed codes (see above), or NULL
     float *weights;       // [n][k] gather weights of the weighted variant (Sec. 4), or NULL
     float *wpk;           // the same weights table-major, [k][n_pad], for the LDS-staged gather, or NULL
+    int probes;           // 1: `weights` receives the multi-probe shares [n][k][1+tau] instead (eq. "partial_softmax")
     long long n_pad;      // token stride of `packed`
     long long n;
     int d, k, tau, n_rounds, P;
@@ -196,6 +197,23 @@ __device__ __forceinline__ void emit_weights(const HashArgs &a, long long t, int
     const int jlo = (int)(lo / tau);
     long long jhi = (lo + N) / tau;
     if (jhi > a.k) jhi = a.k;
+    if (a.probes) {
+        // Multi-probe shares (Sec. 3.1, eq. "partial_softmax", rows within one sign flip of sign(z_j)):
+        // the selected row's soft-max share is prod_b sigmoid(2|z_jb|) = 1 / prod_b (1 + e_b) with
+        // e_b = exp(-2|z_jb|), and flipping bit b multiplies it by e_b.
+        for (int j = jlo + (int)lane; j < (int)jhi; j += 64) {
+            const int c0 = (int)((long long)j * tau - lo);
+            float q = 1.0f;
+            for (int b = 0; b < tau; ++b)
+                q *= 1.0f + __builtin_amdgcn_exp2f(__builtin_fabsf(z_at(c0 + b)) * -2.885390082f);
+            const float p0 = __fdividef(1.0f, q);
+            float *out = a.weights + (t * a.k + j) * (tau + 1);
+            out[0] = p0;
+            for (int b = 0; b < tau; ++b)
+                out[1 + b] = p0 * __builtin_amdgcn_exp2f(__builtin_fabsf(z_at(c0 + b)) * -2.885390082f);
+        }
+        return;
+    }
     for (int j = jlo + (int)lane; j < (int)jhi; j += 64) {
         const int c0 = (int)((long long)j * tau - lo);
         float s = 0.0f, q = 1.0f;

@@ -184,7 +184,7 @@ void launch_hash1024_t(const HashArgs &a, dim3 grid, size_t lds, hipStream_t s)
 // with `weights` also the gather weights of the weighted variant ([n][k] beside `codes`,
 // table-major [k][n_pad] beside `packed`).
 int launch_hash(const void *x, const int8_t *signs, uint16_t *codes, uint32_t *packed, float *weights, int64_t n,
-                int d, int k, int tau, int n_rounds, int x_dtype, hipStream_t s)
+                int d, int k, int tau, int n_rounds, int x_dtype, hipStream_t s, bool probes = false)
 {
     const int L = log2_pad(d);
     const int N = 1 << L;
@@ -195,6 +195,7 @@ int launch_hash(const void *x, const int8_t *signs, uint16_t *codes, uint32_t *p
     a.packed = codes ? nullptr : packed;
     a.weights = codes ? weights : nullptr;
     a.wpk = codes ? nullptr : weights;
+    a.probes = probes;
     a.n_pad = packed_n_pad(n);
     a.n = n;
     a.d = d;
@@ -415,7 +416,7 @@ int launch_gather_lds(const LdsPlan &p, const uint32_t *packed, const float *wpk
 int64_t packed_bytes(int64_t n, int k) { return ((int64_t)(k + 1) / 2) * packed_n_pad(n) * 4; }
 
 int launch_gather_direct(const uint16_t *codes, const float *weights, const void *tables, float *y, int64_t n,
-                         int k, int tau, int d_out, int table_dtype, hipStream_t s)
+                         int k, int tau, int d_out, int table_dtype, hipStream_t s, bool probes = false)
 {
     const bool bf16 = table_dtype == LFFN_BF16;
     const int esz = bf16 ? 2 : 4;
@@ -658,6 +659,60 @@ int lookupffn_gather_weighted(const uint16_t *codes, const float *weights, const
         return launch_gather_lds(plan, packed, wpk, tables, y, false, s);
     }
     return launch_gather_direct(codes, weights, tables, y, n_tokens, k, tau, d_out, table_dtype, s);
+}
+
+int lookupffn_hash_probes(const void *x, const int8_t *signs, uint16_t *codes, float *shares, int64_t n_tokens,
+                          int d, int k, int tau, int n_rounds, int x_dtype, void *hip_stream)
+{
+    int rc = check_hash(x, signs, codes, n_tokens, d, k, tau, n_rounds, x_dtype, true);
+    if (rc == LFFN_OK) rc = check_weights(shares);
+    if (rc != LFFN_OK || n_tokens == 0) return rc;
+    return launch_hash(x, signs, codes, nullptr, shares, n_tokens, d, k, tau, n_rounds, x_dtype,
+                       static_cast<hipStream_t>(hip_stream), true);
+}
+
+int lookupffn_gather_probes(const uint16_t *codes, const float *shares, const void *tables, float *y,
+                            int64_t n_tokens, int k, int tau, int d_out, int table_dtype, void *hip_stream)
+{
+    int rc = check_gather(codes, tables, y, n_tokens, k, tau, d_out, table_dtype);
+    if (rc == LFFN_OK) rc = check_weights(shares);
+    if (rc != LFFN_OK || n_tokens == 0) return rc;
+    return launch_gather_direct(codes, shares, tables, y, n_tokens, k, tau, d_out, table_dtype,
+                                static_cast<hipStream_t>(hip_stream), true);
+}
+
+int64_t lookupffn_workspace_bytes_probes(int64_t n_tokens, int k, int tau)
+{
+    if (n_tokens <= 0 || k < 1 || tau < 1 || tau > 16) return 0;
+    return weighted_codes_bytes(n_tokens, k) + round256((int64_t)n_tokens * k * (tau + 1) * 4);
+}
+
+int lookupffn_forward_probes(const void *x, const int8_t *signs, const void *tables, float *y, int64_t n_tokens,
+                             int d, int k, int tau, int d_out, int n_rounds, int x_dtype, int table_dtype,
+                             void *workspace, int64_t workspace_bytes, void *hip_stream)
+{
+    const uint16_t *stand_in = reinterpret_cast<const uint16_t *>(uintptr_t(256));
+    int rc = check_hash(x, signs, stand_in, n_tokens, d, k, tau, n_rounds, x_dtype, true);
+    if (rc != LFFN_OK) return rc;
+    rc = check_gather(stand_in, tables, y, n_tokens, k, tau, d_out, table_dtype);
+    if (rc != LFFN_OK) return rc;
+    const int64_t need = lookupffn_workspace_bytes_probes(n_tokens, k, tau);
+    if (workspace) {
+        if (workspace_bytes < need) return LFFN_E_WORKSPACE;
+        if (!aligned(workspace, 256)) return LFFN_E_ALIGN;
+    }
+    if (n_tokens == 0) return LFFN_OK;
+    void *ws = workspace;
+    if (!ws) {
+        rc = own_workspace((size_t)need, &ws);
+        if (rc != LFFN_OK) return rc;
+    }
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    uint16_t *codes = static_cast<uint16_t *>(ws);
+    float *shares = reinterpret_cast<float *>(static_cast<char *>(ws) + weighted_codes_bytes(n_tokens, k));
+    rc = launch_hash(x, signs, codes, nullptr, shares, n_tokens, d, k, tau, n_rounds, x_dtype, s, true);
+    if (rc != LFFN_OK) return rc;
+    return launch_gather_direct(codes, shares, tables, y, n_tokens, k, tau, d_out, table_dtype, s, true);
 }
 
 int64_t lookupffn_workspace_bytes_weighted(int64_t n_tokens, int k)

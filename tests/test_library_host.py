@@ -125,6 +125,25 @@ def test_bh_argument_errors(L):
     assert fb(n=1000, ws=FAKE + 16, wsb=need) == -5
 
 
+def test_probe_argument_errors(L):
+    def hp(x=FAKE, signs=FAKE, codes=FAKE, sh=FAKE, n=0, d=768, k=96, tau=8):
+        return L.lookupffn_hash_probes(x, signs, codes, sh, n, d, k, tau, 3, 0, None)
+
+    def gp(codes=FAKE, sh=FAKE, tables=FAKE, y=FAKE, n=0, tau=8, d_out=768):
+        return L.lookupffn_gather_probes(codes, sh, tables, y, n, 96, tau, d_out, 0, None)
+
+    def fp(x=FAKE, y=FAKE, n=0, tau=8, ws=None, wsb=0):
+        return L.lookupffn_forward_probes(x, FAKE, FAKE, y, n, 768, 96, tau, 768, 3, 0, 0, ws, wsb, None)
+
+    assert hp() == 0 and gp() == 0 and fp() == 0
+    assert hp(sh=None) == -1 and hp(sh=FAKE + 2) == -5 and hp(tau=0) == -3 and hp(d=4096, k=512) == -6
+    assert gp(sh=None) == -1 and gp(tables=None) == -1 and gp(d_out=770) == -5 and gp(tau=17) == -3
+    assert fp(x=None) == -1 and fp(y=None) == -1
+    need = L.lookupffn_workspace_bytes_probes(1000, 96, 8)
+    assert need >= 1000 * 96 * (2 + 9 * 4) and need % 256 == 0 and L.lookupffn_workspace_bytes_probes(0, 96, 8) == 0
+    assert fp(n=1000, ws=FAKE, wsb=need - 1) == -7 and fp(n=1000, ws=FAKE + 16, wsb=need) == -5
+
+
 def test_options(L):
     assert L.lookupffn_set_option(b"lanes_per_token", 16) == 0
     assert L.lookupffn_set_option(b"lanes_per_token", 3) == -2
