@@ -31,7 +31,6 @@ constexpr int kXcds = 8;
 struct GatherArgs {
     const uint16_t *codes;  // [n][k]
     const float *weights;   // [n][k] for the weighted form, [n][k][1+tau] for the multi-probe form, else NULL
-    int probes;             // 1: multi-probe form
     const char *tables;     // [k][rows][d_out] fp32 or bf16
     float *y;               // [n][d_out]
     long long n;
@@ -109,7 +108,8 @@ __device__ __forceinline__ uint32_t code_of(const uint4 &c, int u)
     return (u & 1) ? (w >> 16) : (w & 0xFFFFu);
 }
 
-template <bool BF16, int LPT, bool WEIGHTED>
+// WMODE: 0 = plain sum, 1 = weighted form, 2 = multi-probe form
+template <bool BF16, int LPT, int WMODE>
 __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a)
 {
     constexpr int TPW = 64 / LPT;  // tokens per wave
@@ -151,7 +151,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a)
     acc.zero();
 
     int j0 = 0;
-    if (WEIGHTED && a.probes) {
+    if constexpr (WMODE == 2) {
         const float *wp = a.weights + t * a.k * (tau + 1);
         const int np = tau + 1;
         for (int j = 0; j < k; ++j, wp += np) {
@@ -172,7 +172,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a)
             for (; pr < np; ++pr) acc.fma(row(j, pr == 0 ? g : g ^ (1u << (pr - 1))), wp[pr]);
         }
         j0 = k;
-    } else if constexpr (WEIGHTED) {
+    } else if constexpr (WMODE == 1) {
         const float *wrow = a.weights + t * a.k;
         if (a.codes_vec8) {
             const uint4 *c8 = reinterpret_cast<const uint4 *>(crow);

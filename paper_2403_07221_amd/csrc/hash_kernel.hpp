@@ -39,7 +39,6 @@ struct HashArgs {
     uint32_t *packed;     // packed codes (see above), or NULL
     float *weights;       // [n][k] gather weights of the weighted variant (Sec. 4), or NULL
     float *wpk;           // the same weights table-major, [k][n_pad], for the LDS-staged gather, or NULL
-    int probes;           // 1: `weights` receives the multi-probe shares [n][k][1+tau] instead (eq. "partial_softmax")
     long long n_pad;      // token stride of `packed`
     long long n;
     int d, k, tau, n_rounds, P;
@@ -189,7 +188,9 @@ __device__ __forceinline__ void wave_lds_fence()
 // the second form being the first with numerator and denominator divided by exp(|z_j|_1); it
 // cannot overflow.  `z_at(c)` returns coordinate c of projection p for 0 <= c < N and coordinate
 // N + c of the concatenation before it for -16 < c < 0.  One lane per table.
-template <class ZAt>
+// WMODE 1: the weight above; WMODE 2: the multi-probe shares (below), written to `weights` as
+// [n][k][1+tau].  The mode is a template parameter of the kernels, so each variant is its own binary.
+template <int WMODE, class ZAt>
 __device__ __forceinline__ void emit_weights(const HashArgs &a, long long t, int p, int N, unsigned lane, ZAt z_at)
 {
     const int tau = a.tau;
@@ -197,7 +198,7 @@ __device__ __forceinline__ void emit_weights(const HashArgs &a, long long t, int
     const int jlo = (int)(lo / tau);
     long long jhi = (lo + N) / tau;
     if (jhi > a.k) jhi = a.k;
-    if (a.probes) {
+    if constexpr (WMODE == 2) {
         // Multi-probe shares (Sec. 3.1, eq. "partial_softmax", rows within one sign flip of sign(z_j)):
         // the selected row's soft-max share is prod_b sigmoid(2|z_jb|) = 1 / prod_b (1 + e_b) with
         // e_b = exp(-2|z_jb|), and flipping bit b multiplies it by e_b.
@@ -230,9 +231,11 @@ __device__ __forceinline__ void emit_weights(const HashArgs &a, long long t, int
     }
 }
 
-template <int LOG2N, bool WEIGHTED>
+// WMODE: 0 = codes only, 1 = codes and gather weights (Sec. 4), 2 = codes and multi-probe shares
+template <int LOG2N, int WMODE>
 __global__ __launch_bounds__(kHashThreads) void hash_kernel(HashArgs a)
 {
+    constexpr bool WEIGHTED = WMODE != 0;
     constexpr int N = 1 << LOG2N;
     constexpr int NREG = N >= 64 ? N / 64 : 1;
     constexpr int FW = N > 2048 ? 2 : 1;
@@ -339,7 +342,7 @@ __global__ __launch_bounds__(kHashThreads) void hash_kernel(HashArgs a)
                 for (int r = 0; r < NREG; ++r)
                     if ((int)lane + 64 * r < N) zwin[kZTail + (int)lane + 64 * r] = v[r];
                 wave_lds_fence();
-                emit_weights(a, t, p, N, lane, [&](int c) { return zwin[kZTail + c]; });
+                emit_weights<WMODE>(a, t, p, N, lane, [&](int c) { return zwin[kZTail + c]; });
                 if (p + 1 < P) {
                     // slide the tail: it becomes the last 16 coordinates up to the end of projection p
                     wave_lds_fence();
@@ -411,9 +414,10 @@ typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) u32x4_t lds_u32x4;
 typedef __attribute__((address_space(3))) uint16_t lds_u16;
 
-template <int R, bool WEIGHTED>
+template <int R, int WMODE>
 __global__ __launch_bounds__(kHashThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void hash1024_kernel(HashArgs a)
 {
+    constexpr bool WEIGHTED = WMODE != 0;
     constexpr int N = 1024, NREG = 16;
     extern __shared__ uint32_t lds[];
     const unsigned lane = threadIdx.x & 63u;
@@ -580,7 +584,7 @@ __global__ __launch_bounds__(kHashThreads) __attribute__((amdgpu_waves_per_eu(4,
                     if (c < 0) return ztail[kZTail + c];
                     return __uint_as_float(tp[c ^ ((c >> 4) & 0x3C)]);
                 };
-                emit_weights(a, t, p, N, lane, z_at);
+                emit_weights<WMODE>(a, t, p, N, lane, z_at);
                 if (p + 1 < P) {
                     wave_lds_fence();
                     float keep = 0.0f;

@@ -163,21 +163,25 @@ int check_gather(const uint16_t *codes, const void *tables, const float *y, int6
 
 // ---------------------------------------------------------------- launches
 template <int L>
-void launch_hash_t(const HashArgs &a, dim3 grid, size_t lds, hipStream_t s)
+void launch_hash_t(const HashArgs &a, bool probes, dim3 grid, size_t lds, hipStream_t s)
 {
-    if (a.weights || a.wpk)
-        hipLaunchKernelGGL((hash_kernel<L, true>), grid, dim3(kHashThreads), lds, s, a);
+    if (probes)
+        hipLaunchKernelGGL((hash_kernel<L, 2>), grid, dim3(kHashThreads), lds, s, a);
+    else if (a.weights || a.wpk)
+        hipLaunchKernelGGL((hash_kernel<L, 1>), grid, dim3(kHashThreads), lds, s, a);
     else
-        hipLaunchKernelGGL((hash_kernel<L, false>), grid, dim3(kHashThreads), lds, s, a);
+        hipLaunchKernelGGL((hash_kernel<L, 0>), grid, dim3(kHashThreads), lds, s, a);
 }
 
 template <int R>
-void launch_hash1024_t(const HashArgs &a, dim3 grid, size_t lds, hipStream_t s)
+void launch_hash1024_t(const HashArgs &a, bool probes, dim3 grid, size_t lds, hipStream_t s)
 {
-    if (a.weights || a.wpk)
-        hipLaunchKernelGGL((hash1024_kernel<R, true>), grid, dim3(kHashThreads), lds, s, a);
+    if (probes)
+        hipLaunchKernelGGL((hash1024_kernel<R, 2>), grid, dim3(kHashThreads), lds, s, a);
+    else if (a.weights || a.wpk)
+        hipLaunchKernelGGL((hash1024_kernel<R, 1>), grid, dim3(kHashThreads), lds, s, a);
     else
-        hipLaunchKernelGGL((hash1024_kernel<R, false>), grid, dim3(kHashThreads), lds, s, a);
+        hipLaunchKernelGGL((hash1024_kernel<R, 0>), grid, dim3(kHashThreads), lds, s, a);
 }
 
 // Writes codes[n][k] when `codes` is given, else the packed layout of the LDS-staged gather;
@@ -195,7 +199,6 @@ int launch_hash(const void *x, const int8_t *signs, uint16_t *codes, uint32_t *p
     a.packed = codes ? nullptr : packed;
     a.weights = codes ? weights : nullptr;
     a.wpk = codes ? nullptr : weights;
-    a.probes = probes;
     a.n_pad = packed_n_pad(n);
     a.n = n;
     a.d = d;
@@ -219,10 +222,10 @@ int launch_hash(const void *x, const int8_t *signs, uint16_t *codes, uint32_t *p
         const dim3 grid((unsigned)blocks);
         const size_t lds = h1024_lds_bytes(a.P, weighted);
         switch (n_rounds) {
-            case 1: launch_hash1024_t<1>(a, grid, lds, s); break;
-            case 2: launch_hash1024_t<2>(a, grid, lds, s); break;
-            case 3: launch_hash1024_t<3>(a, grid, lds, s); break;
-            default: launch_hash1024_t<4>(a, grid, lds, s); break;
+            case 1: launch_hash1024_t<1>(a, probes, grid, lds, s); break;
+            case 2: launch_hash1024_t<2>(a, probes, grid, lds, s); break;
+            case 3: launch_hash1024_t<3>(a, probes, grid, lds, s); break;
+            default: launch_hash1024_t<4>(a, probes, grid, lds, s); break;
         }
         LFFN_HIP(hipGetLastError());
         tl.done();
@@ -233,7 +236,7 @@ int launch_hash(const void *x, const int8_t *signs, uint16_t *codes, uint32_t *p
     if (blocks > 2048) blocks = 2048;
     const dim3 grid((unsigned)blocks);
     switch (L) {
-#define LFFN_CASE(l) case l: launch_hash_t<l>(a, grid, lds, s); break;
+#define LFFN_CASE(l) case l: launch_hash_t<l>(a, probes, grid, lds, s); break;
         LFFN_CASE(0) LFFN_CASE(1) LFFN_CASE(2) LFFN_CASE(3) LFFN_CASE(4) LFFN_CASE(5) LFFN_CASE(6)
         LFFN_CASE(7) LFFN_CASE(8) LFFN_CASE(9) LFFN_CASE(10) LFFN_CASE(11) LFFN_CASE(12)
 #undef LFFN_CASE
@@ -245,25 +248,27 @@ int launch_hash(const void *x, const int8_t *signs, uint16_t *codes, uint32_t *p
 }
 
 template <bool BF16, int LPT>
-void launch_gather_t(const GatherArgs &a, dim3 grid, hipStream_t s)
+void launch_gather_t(const GatherArgs &a, bool probes, dim3 grid, hipStream_t s)
 {
-    if (a.weights)
-        hipLaunchKernelGGL((gather_kernel<BF16, LPT, true>), grid, dim3(kGatherThreads), 0, s, a);
+    if (probes)
+        hipLaunchKernelGGL((gather_kernel<BF16, LPT, 2>), grid, dim3(kGatherThreads), 0, s, a);
+    else if (a.weights)
+        hipLaunchKernelGGL((gather_kernel<BF16, LPT, 1>), grid, dim3(kGatherThreads), 0, s, a);
     else
-        hipLaunchKernelGGL((gather_kernel<BF16, LPT, false>), grid, dim3(kGatherThreads), 0, s, a);
+        hipLaunchKernelGGL((gather_kernel<BF16, LPT, 0>), grid, dim3(kGatherThreads), 0, s, a);
 }
 
 template <bool BF16>
-int launch_gather_lpt(int lpt, const GatherArgs &a, dim3 grid, hipStream_t s)
+int launch_gather_lpt(int lpt, const GatherArgs &a, bool probes, dim3 grid, hipStream_t s)
 {
     switch (lpt) {
-        case 1: launch_gather_t<BF16, 1>(a, grid, s); break;
-        case 2: launch_gather_t<BF16, 2>(a, grid, s); break;
-        case 4: launch_gather_t<BF16, 4>(a, grid, s); break;
-        case 8: launch_gather_t<BF16, 8>(a, grid, s); break;
-        case 16: launch_gather_t<BF16, 16>(a, grid, s); break;
-        case 32: launch_gather_t<BF16, 32>(a, grid, s); break;
-        case 64: launch_gather_t<BF16, 64>(a, grid, s); break;
+        case 1: launch_gather_t<BF16, 1>(a, probes, grid, s); break;
+        case 2: launch_gather_t<BF16, 2>(a, probes, grid, s); break;
+        case 4: launch_gather_t<BF16, 4>(a, probes, grid, s); break;
+        case 8: launch_gather_t<BF16, 8>(a, probes, grid, s); break;
+        case 16: launch_gather_t<BF16, 16>(a, probes, grid, s); break;
+        case 32: launch_gather_t<BF16, 32>(a, probes, grid, s); break;
+        case 64: launch_gather_t<BF16, 64>(a, probes, grid, s); break;
         default: return LFFN_E_UNSUPPORTED;
     }
     return LFFN_OK;
@@ -464,7 +469,7 @@ int launch_gather_direct(const uint16_t *codes, const float *weights, const void
     if (blocks > 0x7FFFFFFFLL) return LFFN_E_SIZE;
     const dim3 grid((unsigned)blocks);
     TimedLaunch tl(1, s);
-    int rc = bf16 ? launch_gather_lpt<true>(lpt, a, grid, s) : launch_gather_lpt<false>(lpt, a, grid, s);
+    int rc = bf16 ? launch_gather_lpt<true>(lpt, a, probes, grid, s) : launch_gather_lpt<false>(lpt, a, probes, grid, s);
     if (rc != LFFN_OK) return rc;
     LFFN_HIP(hipGetLastError());
     tl.done();
