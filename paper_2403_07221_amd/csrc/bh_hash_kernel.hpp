@@ -89,6 +89,28 @@ __global__ __launch_bounds__(256) void bh_pack_kernel(const float *bmats, float 
 
 typedef float mfma_f4 __attribute__((ext_vector_type(4)));
 
+// Transform stages inside one tile (strides 1, 2: lanes l ^ 16, l ^ 32; strides 4, 8: registers),
+// ascending, each butterfly (a + c, a - c) with a the lower coordinate.
+__device__ __forceinline__ void tile_stages(float (&t)[4])
+{
+    swap_butterfly<16>(t[0], t[1]);
+    swap_butterfly<16>(t[2], t[3]);
+    swap_butterfly<32>(t[0], t[1]);
+    swap_butterfly<32>(t[2], t[3]);
+#pragma unroll
+    for (int r = 0; r < 4; r += 2) {
+        const float x0 = t[r], x1 = t[r + 1];
+        t[r] = x0 + x1;
+        t[r + 1] = x0 - x1;
+    }
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const float x0 = t[r], x1 = t[r + 2];
+        t[r] = x0 + x1;
+        t[r + 2] = x0 - x1;
+    }
+}
+
 // LOG2N: d_pad = 2^LOG2N (64 .. 1024); TB = block / 16 (1, 2, 4); VEC4: rows are read four coordinates
 // at a time (d % 4 == 0, aligned rows), else one by one
 template <int LOG2N, int TB, bool VEC4>
@@ -239,6 +261,16 @@ __global__ __launch_bounds__(kBhThreads) void bh_hash_kernel(BhArgs a)
                                 for (int kk = 0; kk < 4; ++kk)
                                     acc[o] = __builtin_amdgcn_mfma_f32_16x16x4f32(
                                         __uint_as_float(cur[kk]), v[c * CT + blk * TB + ii][kk], acc[o], 0, 0, 0);
+                                // In the shadow of these MFMAs: the tile-local transform stages (strides
+                                // 1 .. 8) of one tile of the previous chunk, whose products are complete.
+                                if (c > 0 && qi % TB == 0) {
+                                    tile_stages(v[(c - 1) * CT + qi / TB]);
+#pragma unroll
+                                    for (int kk = 0; kk < 4; ++kk) {
+                                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+                                        __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);  // six vector-ALU ops
+                                    }
+                                }
                                 __builtin_amdgcn_sched_barrier(0);
                             }
                         }
@@ -251,28 +283,9 @@ __global__ __launch_bounds__(kBhThreads) void bh_hash_kernel(BhArgs a)
                 }
 
                 // ---- Walsh-Hadamard transform, ascending stride, then the scale -----------------
+                // strides 1 .. 8 of the last chunk's tiles (the other tiles had theirs during the products)
 #pragma unroll
-                for (int beta = 0; beta < NT; ++beta) {  // strides 1, 2: lanes l^16, l^32
-                    swap_butterfly<16>(v[beta][0], v[beta][1]);
-                    swap_butterfly<16>(v[beta][2], v[beta][3]);
-                    swap_butterfly<32>(v[beta][0], v[beta][1]);
-                    swap_butterfly<32>(v[beta][2], v[beta][3]);
-                }
-#pragma unroll
-                for (int beta = 0; beta < NT; ++beta) {  // strides 4, 8: registers of a tile
-#pragma unroll
-                    for (int r = 0; r < 4; r += 2) {
-                        const float x0 = v[beta][r], x1 = v[beta][r + 1];
-                        v[beta][r] = x0 + x1;
-                        v[beta][r + 1] = x0 - x1;
-                    }
-#pragma unroll
-                    for (int r = 0; r < 2; ++r) {
-                        const float x0 = v[beta][r], x1 = v[beta][r + 2];
-                        v[beta][r] = x0 + x1;
-                        v[beta][r + 2] = x0 - x1;
-                    }
-                }
+                for (int beta = (NCH - 1) * CT; beta < NT; ++beta) tile_stages(v[beta]);
 #pragma unroll
                 for (int h = 1; h < NT; h <<= 1)  // strides 16 and up: tiles
 #pragma unroll
