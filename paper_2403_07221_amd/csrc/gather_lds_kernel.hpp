@@ -46,7 +46,8 @@
 namespace lffn {
 
 constexpr int kLdsThreads = 1024;
-constexpr int kLdsGroups = kLdsThreads / 8;  // token groups per workgroup (8 lanes per token)
+// Lanes per token SW (8 or 4): a token group reads one SW*16-byte row piece, the workgroup owns a
+// column slice of that width and kLdsThreads / SW token groups.
 constexpr int kLdsBufBytes = 64 * 1024;      // one staging buffer (two of them are in use)
 constexpr int kLdsMaxTok = 16;               // token slots per lane the packed padding allows for
 #ifndef LFFN_LDS_RB
@@ -68,20 +69,18 @@ struct GatherLdsArgs {
     long long n;
     int k, tau, d_out;
     int nvec;           // 16-byte pieces per row
-    int n_slices;       // ceil(nvec / 8)
+    int n_slices;       // ceil(nvec / lanes per token)
     int token_splits;   // a unit = (slice, one of token_splits equal token ranges)
     int n_units;        // n_slices * token_splits
     int blocks_per_xcd; // gridDim.x / kXcds
     uint32_t row_bytes;
 };
 
-// tables per stage: as many 128-byte-wide table slices as fill one buffer, at most two (a code
-// word holds two tables' offsets)
-__host__ __device__ inline int gather_lds_tps(int tau) { return ((size_t)128 << tau) * 2 <= (size_t)kLdsBufBytes ? 2 : 1; }
-// bytes of LDS the kernel needs: two buffers
-__host__ __device__ inline size_t gather_lds_bytes(int tau)
+// bytes of LDS the kernel needs: two buffers (sw = lanes per token)
+__host__ __device__ inline size_t gather_lds_bytes(int tau, int sw)
 {
-    return (size_t)2 * gather_lds_tps(tau) * ((size_t)128 << tau);
+    const size_t tbl = ((size_t)16 * sw) << tau;
+    return 2 * (2 * tbl <= (size_t)kLdsBufBytes ? 2 * tbl : tbl);
 }
 
 // balanced split of [0, len) into `parts` pieces: start of piece i (32-bit arithmetic only)
@@ -124,22 +123,29 @@ __device__ __forceinline__ uint32_t quad_bcast(uint32_t v, int q)
     return __float_as_uint(quad_bcast(__uint_as_float(v), q));
 }
 
-// FR = rounds of 128 rows per table slice: 1, 2, 4 for tau = 7, 8, 9.  Tables per stage TPS: two
-// (tau 7, 8: both halves of a code word are consumed in one stage) or one (tau = 9: a 512-row slice
-// fills a buffer; even stages take the low half of the code word, odd stages the high half).
-template <bool BF16, int TOK, int FR, bool WEIGHTED>
+// FR = 16 KB copy rounds per table slice (one round = every thread copies 16 bytes = G rows): 1, 2, 4.
+// Tables per stage TPS: two (FR <= 2: both halves of a code word are consumed in one stage) or one
+// (FR = 4: a 64 KB slice fills a buffer; even stages take the low half of the code word, odd stages
+// the high half).  SW = lanes per token: 8 (128-byte column slices; tau = 7, 8, 9 <-> FR = 1, 2, 4)
+// or 4 (64-byte slices; tau = 8, 9, 10 <-> FR = 1, 2, 4).  The packed codes must be scaled by the
+// row-piece bytes: code << 7 for SW = 8 (what the hash kernels write), code << 6 for SW = 4 (written
+// by the re-pack kernel from ABI codes; 1023 << 7 would not fit the 16-bit half of a code word).
+template <bool BF16, int TOK, int FR, bool WEIGHTED, int SW = 8>
 __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a)
 {
     static_assert(TOK <= kLdsMaxTok, "packed-code padding covers 16 token slots");
-    static_assert(FR == 1 || FR == 2 || FR == 4, "table slices of 128, 256 or 512 rows");
+    static_assert(FR == 1 || FR == 2 || FR == 4, "table slices of 16, 32 or 64 KB");
+    static_assert(SW == 8 || SW == 4, "128- or 64-byte column slices");
     constexpr int TPS = FR <= 2 ? 2 : 1;
-    static_assert(TPS * FR * 128 * 128 <= kLdsBufBytes, "a stage fits one buffer");
+    constexpr int G = kLdsThreads / SW;   // token groups per workgroup = rows per copy round
+    constexpr uint32_t PIECE = SW * 16u;  // bytes of a row inside the slice
+    static_assert(TPS * FR * 16 * 1024 <= kLdsBufBytes, "a stage fits one buffer");
     extern __shared__ uint4 sbuf[];
     const uint32_t tid = threadIdx.x;
     const uint32_t wave = tid >> 6;
-    const uint32_t g = tid >> 3, q = tid & 7u;
-    const uint32_t rows = 128u * FR;               // == 1 << a.tau (checked by the host)
-    const uint32_t tbl_bytes = rows * 128u;          // one table slice in LDS
+    const uint32_t g = tid / SW, q = tid % SW;
+    const uint32_t rows = (uint32_t)G * FR;          // == 1 << a.tau (checked by the host)
+    const uint32_t tbl_bytes = rows * PIECE;         // one table slice in LDS
     const uint32_t buf_bytes = tbl_bytes * TPS;  // one buffer (one stage)
     const uint32_t n = (uint32_t)a.n;                // the host uses this kernel only for n < 2^31
     const uint32_t nstages = (uint32_t)a.k / TPS;
@@ -177,7 +183,7 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
         const uint32_t r0 = s0 + split_at(s1 - s0, parts, part), r1 = s0 + split_at(s1 - s0, parts, part + 1);
         if (r1 <= r0) continue;  // uniform over the workgroup
 
-        const uint32_t vec = slice * 8u + q;
+        const uint32_t vec = slice * (uint32_t)SW + q;
         const bool vec_ok = vec < (uint32_t)a.nvec;
 
         // Fill role of this thread: piece (row g, column piece q) of each group of 128 rows.
@@ -190,33 +196,33 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
         auto fill_piece = [&](uint32_t s, uint32_t b, int idx) {
             const uint32_t tb = (uint32_t)idx / FR, f = (uint32_t)idx % FR;
             const char *tsrc = a.tables + (size_t)(s * TPS + tb) * table_stride +
-                               (size_t)f * kLdsGroups * a.row_bytes;  // uniform
+                               (size_t)f * G * a.row_bytes;  // uniform
             lds_dma16(tsrc, foff, lds0 + b * buf_bytes + tb * tbl_bytes + (f * kLdsThreads + wave * 64u) * 16u);
         };
 
         const uint32_t len = r1 - r0;
-        const uint32_t nchunks = (len + kLdsGroups * TOK - 1) / (kLdsGroups * TOK);
+        const uint32_t nchunks = (len + G * TOK - 1) / (G * TOK);
         for (uint32_t ch = 0; ch < nchunks; ++ch) {
             const uint32_t c0 = r0 + split_at(len, nchunks, ch), c1 = r0 + split_at(len, nchunks, ch + 1);
             // Token slots.  The eight lanes of a token group would all hold the same code word and
             // weights, so these are quad-shared: a lane keeps those of the slots 4m + r, r = its
             // position in its quad, in register m, and a use fetches them with a DPP quad broadcast
             // (a quarter of the registers and load instructions).  Slot i of group g is token
-            //   c0 + 512*(i/4) + 4g + i%4   for the full quads of slots (i < 4*(TOK/4)),
-            //   c0 + 128*i + g              for the remaining TOK % 4 slots,
-            // so that register m of a wave's lanes covers 32 consecutive tokens: one cache line per
-            // load instruction.  Slots past the chunk end read the codes of later tokens or of the
+            //   c0 + 4G*(i/4) + 4g + i%4   for the full quads of slots (i < 4*(TOK/4)),
+            //   c0 + G*i + g               for the remaining TOK % 4 slots,
+            // so that register m of a wave's lanes covers consecutive tokens: one or two cache lines
+            // per load instruction.  Slots past the chunk end read the codes of later tokens or of the
             // zero padding (always a valid row), add them, and store nothing.
             constexpr int WQ = (TOK + 3) / 4, FQ = TOK / 4;
             const uint32_t r4 = q & 3u;
             auto slot_token = [&](int i) -> uint32_t {
-                return i < 4 * FQ ? c0 + 512u * (uint32_t)(i >> 2) + 4u * g + (uint32_t)(i & 3)
-                                  : c0 + 128u * (uint32_t)i + g;
+                return i < 4 * FQ ? c0 + (4u * G) * (uint32_t)(i >> 2) + 4u * g + (uint32_t)(i & 3)
+                                  : c0 + (uint32_t)G * (uint32_t)i + g;
             };
             const uint32_t lq_full = (4u * g + r4) * 4u;          // byte offset of the lane's token in a full quad register
-            const uint32_t lq_tail = (r4 * kLdsGroups + g) * 4u;  // same for the tail register
+            const uint32_t lq_tail = (r4 * G + g) * 4u;            // same for the tail register
             auto reg_offset = [&](int m) -> uint32_t {
-                return m < FQ ? (uint32_t)m * 2048u + lq_full : (uint32_t)m * 2048u + lq_tail;
+                return m < FQ ? (uint32_t)m * (16u * G) + lq_full : (uint32_t)m * (16u * G) + lq_tail;
             };
             constexpr int NCR = WQ;  // code registers and code loads per stage
             auto load_code = [&](uint32_t s, int m, uint32_t(&cr)[NCR]) {

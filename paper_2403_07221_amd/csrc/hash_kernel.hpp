@@ -23,8 +23,8 @@ namespace lffn {
 // pass when the LDS-staged gather is used): packed[s][t], s < k/2, t < n_pad, one 32-bit word
 // holding the LDS byte offsets (code << 7, i.e. code * 128-byte row pieces) of tables 2s (low
 // half) and 2s+1 (high half).  The token axis is padded so that a workgroup may read a full
-// 16 x 128 token window past any token without leaving the buffer; padding entries are zero.
-__host__ __device__ inline long long packed_n_pad(long long n) { return ((n + 127) / 128) * 128 + 16 * 128; }
+// 16 x 256 token window past any token without leaving the buffer; padding entries are zero.
+__host__ __device__ inline long long packed_n_pad(long long n) { return ((n + 127) / 128) * 128 + 16 * 256; }
 constexpr int kPackedShift = 7;
 // index of (table j, token t) in the staged gather's weight array: table-major, token-contiguous
 __host__ __device__ inline long long wpk_index(long long j, long long t, long long n_pad)
@@ -634,9 +634,10 @@ __global__ __launch_bounds__(256) void repack_weights_kernel(const float *weight
     }
 }
 
-// ABI codes [n][k] -> packed layout (for a stand-alone gather call that takes the LDS-staged kernel)
+// ABI codes [n][k] -> packed layout scaled by 2^shift (for a stand-alone gather call that takes the
+// LDS-staged kernel, and for the staged kernel's 64-byte-slice form, which needs shift 6)
 __global__ __launch_bounds__(256) void repack_codes_kernel(const uint16_t *codes, uint32_t *packed, long long n,
-                                                           long long n_pad, int k, int tau)
+                                                           long long n_pad, int k, int tau, int shift)
 {
     const long long total = (long long)(k / 2) * n_pad;
     const uint32_t cmask = (1u << tau) - 1u;
@@ -646,7 +647,7 @@ __global__ __launch_bounds__(256) void repack_codes_kernel(const uint16_t *codes
         uint32_t w = 0u;
         if (t < n) {
             const uint32_t pair = *reinterpret_cast<const uint32_t *>(codes + t * k + 2 * s);
-            w = ((pair & cmask) << kPackedShift) | (((pair >> 16) & cmask) << (16 + kPackedShift));
+            w = ((pair & cmask) << shift) | (((pair >> 16) & cmask) << (16 + shift));
         }
         packed[idx] = w;
     }

@@ -55,6 +55,7 @@ struct Options {
     int gather_path = 0;      // 0 = choose, 1 = direct kernel, 2 = LDS-staged kernel (if the shape allows)
     int hash_path = 0;        // 0 = choose, 1 = generic kernel only
     int hash_blocks = 0;      // 0 = default grid cap of the d_pad = 1024 hash kernel
+    int slice_lanes = 0;      // 0 = choose, 4 = 64-byte column slices in the staged gather where possible
 } g_opt;
 
 // ---------------------------------------------------------------- timing
@@ -278,6 +279,22 @@ int gcd(int a, int b) { return b ? gcd(b, a % b) : a; }
 int64_t round256(int64_t b) { return (b + 255) & ~int64_t(255); }
 
 // ---- LDS-staged gather -------------------------------------------------------------------
+// kernels that use more than 64 KB of dynamic LDS must be told so, once per device and kernel
+int allow_lds(const void *kern, size_t lds)
+{
+    static std::mutex mu;
+    static std::map<std::pair<int, const void *>, size_t> configured;  // (device, kernel) -> LDS bytes set up
+    int dev = 0;
+    LFFN_HIP(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lk(mu);
+    size_t &have = configured[std::make_pair(dev, kern)];
+    if (have < lds) {
+        LFFN_HIP(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        have = lds;
+    }
+    return LFFN_OK;
+}
+
 constexpr int kLdsMinBytes = 84 * 1024;  // more than half of the 160 KB LDS: one workgroup per CU
 
 int device_cus(int *cus)
@@ -297,32 +314,31 @@ int device_cus(int *cus)
     return LFFN_OK;
 }
 
-template <bool BF16, int TOK, int FR, bool WEIGHTED>
+template <bool BF16, int TOK, int FR, bool WEIGHTED, int SW>
 int launch_gather_lds_fr(const GatherLdsArgs &a, dim3 grid, size_t lds, hipStream_t s)
 {
-    auto kern = gather_lds_kernel<BF16, TOK, FR, WEIGHTED>;
-    static std::mutex mu;
-    static std::map<int, size_t> configured;  // device -> LDS bytes the kernel is set up for
-    int dev = 0;
-    LFFN_HIP(hipGetDevice(&dev));
-    {
-        std::lock_guard<std::mutex> lk(mu);
-        if (configured[dev] < lds) {
-            LFFN_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            configured[dev] = lds;
-        }
-    }
+    auto kern = gather_lds_kernel<BF16, TOK, FR, WEIGHTED, SW>;
+    int rc = allow_lds(reinterpret_cast<const void *>(kern), lds);
+    if (rc != LFFN_OK) return rc;
     hipLaunchKernelGGL(kern, grid, dim3(kLdsThreads), lds, s, a);
     return LFFN_OK;
 }
 
+// fr = 16 KB copy rounds per table slice, sw = lanes per token (both fixed by the plan)
 template <bool BF16, int TOK, bool WEIGHTED = false>
-int launch_gather_lds_t(const GatherLdsArgs &a, dim3 grid, size_t lds, hipStream_t s)
+int launch_gather_lds_t(const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s)
 {
-    return a.tau == 9   ? launch_gather_lds_fr<BF16, TOK, 4, WEIGHTED>(a, grid, lds, s)
-           : a.tau == 8 ? launch_gather_lds_fr<BF16, TOK, 2, WEIGHTED>(a, grid, lds, s)
-                        : launch_gather_lds_fr<BF16, TOK, 1, WEIGHTED>(a, grid, lds, s);
+    if (sw == 8) {
+        return fr == 4   ? launch_gather_lds_fr<BF16, TOK, 4, WEIGHTED, 8>(a, grid, lds, s)
+               : fr == 2 ? launch_gather_lds_fr<BF16, TOK, 2, WEIGHTED, 8>(a, grid, lds, s)
+                         : launch_gather_lds_fr<BF16, TOK, 1, WEIGHTED, 8>(a, grid, lds, s);
+    }
+    if constexpr (!BF16 && (TOK == 8 || TOK == 13)) {  // 64-byte slices: built for fp32 tables
+        return fr == 4   ? launch_gather_lds_fr<false, TOK, 4, WEIGHTED, 4>(a, grid, lds, s)
+               : fr == 2 ? launch_gather_lds_fr<false, TOK, 2, WEIGHTED, 4>(a, grid, lds, s)
+                         : launch_gather_lds_fr<false, TOK, 1, WEIGHTED, 4>(a, grid, lds, s);
+    }
+    return LFFN_E_UNSUPPORTED;
 }
 
 // Largest number of tokens a workgroup gets in one piece, mirroring the kernel's split.
@@ -340,6 +356,10 @@ struct LdsPlan {
     bool use = false;
     GatherLdsArgs a;
     int tok = 0;
+    int sw = 8;     // lanes per token: 8 = 128-byte column slices, 4 = 64-byte ones
+    int fr = 1;     // 16 KB copy rounds per table slice
+    int shift = 7;  // log2 of the row-piece bytes: what the packed codes are scaled by.  The hash kernels
+                    // write shift 7; a plan with shift 6 takes its codes through the re-pack kernel.
     unsigned grid = 0;
     size_t lds = 0;
 };
@@ -350,7 +370,13 @@ int plan_gather_lds(int64_t n, int k, int tau, int d_out, bool bf16, LdsPlan *p,
     if (g_opt.gather_path == 1) return LFFN_OK;
     if (weighted && bf16) return LFFN_OK;  // the weighted staged kernel is built for fp32 tables
     const int rows = 1 << tau;
-    if (tau < 7 || tau > 9 || k % 2 != 0) return LFFN_OK;  // table slices of 128, 256 or 512 rows
+    if (tau < 7 || tau > 10 || k % 2 != 0) return LFFN_OK;
+    // column slices: 128 bytes (8 lanes per token) while a table slice fits a 64 KB buffer (tau <= 9),
+    // else 64 bytes (tau = 10); the 64-byte form exists for fp32 tables and tau >= 8
+    int sw = tau <= 9 ? 8 : 4;
+    if (g_opt.slice_lanes == 4 && tau >= 8) sw = 4;
+    if (sw == 4 && bf16) return LFFN_OK;
+    const int groups = kLdsThreads / sw;
     // the kernel indexes tokens and bytes inside one table with 32 bits
     if (n >= (int64_t(1) << 31) - 4096 || (int64_t)rows * d_out * 4 >= (int64_t(1) << 32)) return LFFN_OK;
     int cus = 0;
@@ -365,20 +391,24 @@ int plan_gather_lds(int64_t n, int k, int tau, int d_out, bool bf16, LdsPlan *p,
     a.d_out = d_out;
     a.row_bytes = (uint32_t)d_out * (bf16 ? 2 : 4);
     a.nvec = (int)(a.row_bytes / 16);
-    a.n_slices = (a.nvec + 7) / 8;
+    a.n_slices = (a.nvec + sw - 1) / sw;
     a.token_splits = kXcds / gcd(a.n_slices, kXcds);
     a.n_units = a.n_slices * a.token_splits;
     a.blocks_per_xcd = cus / kXcds;
     const int64_t tpb = lds_tokens_per_block(n, a.n_units, a.token_splits, a.blocks_per_xcd);
     const int tok_max = bf16 ? 8 : 13;
-    const int64_t nchunks = (tpb + (int64_t)kLdsGroups * tok_max - 1) / ((int64_t)kLdsGroups * tok_max);
+    const int64_t nchunks = (tpb + (int64_t)groups * tok_max - 1) / ((int64_t)groups * tok_max);
     const int64_t chunk = (tpb + nchunks - 1) / nchunks;
     // Staging pays only when a chunk re-uses each staged row a few times.  With bf16 rows the
     // widening doubles the vector-ALU work per byte and the direct kernel measured faster, so
     // bf16 tables take the staged kernel only on request.
     if (g_opt.gather_path != 2 && (bf16 || chunk < 2 * (int64_t)rows)) return LFFN_OK;
-    p->tok = (int)((chunk + kLdsGroups - 1) / kLdsGroups);
-    p->lds = gather_lds_bytes(tau);
+    p->tok = (int)((chunk + groups - 1) / groups);
+    if (sw == 4) p->tok = p->tok > 8 ? 13 : 8;  // the 64-byte form is built for 8 and 13 token slots
+    p->sw = sw;
+    p->fr = rows / groups;
+    p->shift = sw == 8 ? 7 : 6;
+    p->lds = gather_lds_bytes(tau, sw);
     if (p->lds < (size_t)kLdsMinBytes) p->lds = kLdsMinBytes;
     p->grid = (unsigned)cus;
     p->use = true;
@@ -397,19 +427,19 @@ int launch_gather_lds(const LdsPlan &p, const uint32_t *packed, const float *wpk
     int rc = LFFN_E_UNSUPPORTED;
     TimedLaunch tl(1, s);
     if (wpk) {
-        if (p.tok <= 4) rc = launch_gather_lds_t<false, 4, true>(a, grid, p.lds, s);
-        else if (p.tok <= 8) rc = launch_gather_lds_t<false, 8, true>(a, grid, p.lds, s);
-        else if (p.tok <= 12) rc = launch_gather_lds_t<false, 12, true>(a, grid, p.lds, s);
-        else if (p.tok <= 13) rc = launch_gather_lds_t<false, 13, true>(a, grid, p.lds, s);
+        if (p.tok <= 4) rc = launch_gather_lds_t<false, 4, true>(a, p.fr, p.sw, grid, p.lds, s);
+        else if (p.tok <= 8) rc = launch_gather_lds_t<false, 8, true>(a, p.fr, p.sw, grid, p.lds, s);
+        else if (p.tok <= 12) rc = launch_gather_lds_t<false, 12, true>(a, p.fr, p.sw, grid, p.lds, s);
+        else if (p.tok <= 13) rc = launch_gather_lds_t<false, 13, true>(a, p.fr, p.sw, grid, p.lds, s);
     } else if (bf16) {
-        if (p.tok <= 4) rc = launch_gather_lds_t<true, 4>(a, grid, p.lds, s);
-        else if (p.tok <= 6) rc = launch_gather_lds_t<true, 6>(a, grid, p.lds, s);
-        else if (p.tok <= 8) rc = launch_gather_lds_t<true, 8>(a, grid, p.lds, s);
+        if (p.tok <= 4) rc = launch_gather_lds_t<true, 4>(a, p.fr, p.sw, grid, p.lds, s);
+        else if (p.tok <= 6) rc = launch_gather_lds_t<true, 6>(a, p.fr, p.sw, grid, p.lds, s);
+        else if (p.tok <= 8) rc = launch_gather_lds_t<true, 8>(a, p.fr, p.sw, grid, p.lds, s);
     } else {
-        if (p.tok <= 4) rc = launch_gather_lds_t<false, 4>(a, grid, p.lds, s);
-        else if (p.tok <= 8) rc = launch_gather_lds_t<false, 8>(a, grid, p.lds, s);
-        else if (p.tok <= 12) rc = launch_gather_lds_t<false, 12>(a, grid, p.lds, s);
-        else if (p.tok <= 13) rc = launch_gather_lds_t<false, 13>(a, grid, p.lds, s);
+        if (p.tok <= 4) rc = launch_gather_lds_t<false, 4>(a, p.fr, p.sw, grid, p.lds, s);
+        else if (p.tok <= 8) rc = launch_gather_lds_t<false, 8>(a, p.fr, p.sw, grid, p.lds, s);
+        else if (p.tok <= 12) rc = launch_gather_lds_t<false, 12>(a, p.fr, p.sw, grid, p.lds, s);
+        else if (p.tok <= 13) rc = launch_gather_lds_t<false, 13>(a, p.fr, p.sw, grid, p.lds, s);
     }
     if (rc != LFFN_OK) return rc;
     LFFN_HIP(hipGetLastError());
@@ -505,28 +535,11 @@ int64_t bh_pack_bytes(int d, int k, int tau, int block, int n_factors)
     return round256(P * n_factors * (int64_t)N * block * 4);
 }
 
-// kernels that use more than 64 KB of dynamic LDS must be told so once per device
-template <class K>
-int allow_lds(K kern, size_t lds)
-{
-    static std::mutex mu;
-    static std::map<int, size_t> configured;  // device -> LDS bytes this kernel is set up for
-    int dev = 0;
-    LFFN_HIP(hipGetDevice(&dev));
-    std::lock_guard<std::mutex> lk(mu);
-    if (configured[dev] < lds) {
-        LFFN_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     (int)lds));
-        configured[dev] = lds;
-    }
-    return LFFN_OK;
-}
-
 template <int L, int TB, bool VEC4>
 int launch_bh_k(const BhArgs &a, dim3 grid, size_t lds, hipStream_t s)
 {
     auto kern = bh_hash_kernel<L, TB, VEC4>;
-    int rc = allow_lds(kern, lds);
+    int rc = allow_lds(reinterpret_cast<const void *>(kern), lds);
     if (rc != LFFN_OK) return rc;
     hipLaunchKernelGGL(kern, grid, dim3(kBhThreads), lds, s, a);
     return LFFN_OK;
@@ -602,13 +615,23 @@ int launch_hash_bh(const void *x, const float *bmats, float *apack, uint16_t *co
 int64_t weighted_codes_bytes(int64_t n, int k) { return ((int64_t)n * k * 2 + 255) & ~int64_t(255); }
 
 int launch_repack_codes(const uint16_t *codes, uint32_t *packed, int64_t n, int64_t n_pad, int k, int tau,
-                        hipStream_t s)
+                        int shift, hipStream_t s)
 {
     const int64_t total = (int64_t)(k / 2) * n_pad;
     int64_t blocks = (total + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(repack_codes_kernel, dim3((unsigned)blocks), dim3(256), 0, s, codes, packed, (long long)n,
-                       (long long)n_pad, k, tau);
+                       (long long)n_pad, k, tau, shift);
+    LFFN_HIP(hipGetLastError());
+    return LFFN_OK;
+}
+
+int launch_repack_weights(const float *weights, float *wpk, int64_t n, int64_t n_pad, int k, hipStream_t s)
+{
+    int64_t blocks = ((int64_t)k * n + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(repack_weights_kernel, dim3((unsigned)blocks), dim3(256), 0, s, weights, wpk, (long long)n,
+                       (long long)n_pad, k);
     LFFN_HIP(hipGetLastError());
     return LFFN_OK;
 }
@@ -654,13 +677,10 @@ int lookupffn_gather_weighted(const uint16_t *codes, const float *weights, const
         if (rc != LFFN_OK) return rc;
         uint32_t *packed = static_cast<uint32_t *>(ws);
         float *wpk = reinterpret_cast<float *>(static_cast<char *>(ws) + pb);
-        rc = launch_repack_codes(codes, packed, n_tokens, plan.a.n_pad, k, tau, s);
+        rc = launch_repack_codes(codes, packed, n_tokens, plan.a.n_pad, k, tau, plan.shift, s);
         if (rc != LFFN_OK) return rc;
-        int64_t blocks = ((int64_t)k * n_tokens + 255) / 256;
-        if (blocks > 4096) blocks = 4096;
-        hipLaunchKernelGGL(repack_weights_kernel, dim3((unsigned)blocks), dim3(256), 0, s, weights, wpk,
-                           (long long)n_tokens, (long long)plan.a.n_pad, k);
-        LFFN_HIP(hipGetLastError());
+        rc = launch_repack_weights(weights, wpk, n_tokens, plan.a.n_pad, k, s);
+        if (rc != LFFN_OK) return rc;
         return launch_gather_lds(plan, packed, wpk, tables, y, false, s);
     }
     return launch_gather_direct(codes, weights, tables, y, n_tokens, k, tau, d_out, table_dtype, s);
@@ -725,7 +745,7 @@ int64_t lookupffn_workspace_bytes_weighted(int64_t n_tokens, int k)
     if (n_tokens <= 0 || k < 1) return 0;
     const int64_t direct = weighted_codes_bytes(n_tokens, k) + round256((int64_t)n_tokens * k * 4);
     const int64_t staged = round256(packed_bytes(n_tokens, k)) + round256((int64_t)k * packed_n_pad(n_tokens) * 4);
-    return direct > staged ? direct : staged;
+    return direct + staged;  // both: the 64-byte-slice form re-packs from the ABI layout
 }
 
 int lookupffn_forward_weighted(const void *x, const int8_t *signs, const void *tables, float *y, int64_t n_tokens,
@@ -752,6 +772,22 @@ int lookupffn_forward_weighted(const void *x, const int8_t *signs, const void *t
     LdsPlan plan;
     rc = plan_gather_lds(n_tokens, k, tau, d_out, table_dtype == LFFN_BF16, &plan, true);
     if (rc != LFFN_OK) return rc;
+    if (plan.use && plan.shift != 7) {
+        // 64-byte slices: ABI codes and weights, then the two re-pack kernels
+        char *base = static_cast<char *>(ws);
+        uint32_t *packed = reinterpret_cast<uint32_t *>(base);
+        float *wpk = reinterpret_cast<float *>(base + round256(packed_bytes(n_tokens, k)));
+        char *abi = base + round256(packed_bytes(n_tokens, k)) + round256((int64_t)k * packed_n_pad(n_tokens) * 4);
+        uint16_t *codes = reinterpret_cast<uint16_t *>(abi);
+        float *weights = reinterpret_cast<float *>(abi + weighted_codes_bytes(n_tokens, k));
+        rc = launch_hash(x, signs, codes, nullptr, weights, n_tokens, d, k, tau, n_rounds, x_dtype, s);
+        if (rc != LFFN_OK) return rc;
+        rc = launch_repack_codes(codes, packed, n_tokens, plan.a.n_pad, k, tau, plan.shift, s);
+        if (rc != LFFN_OK) return rc;
+        rc = launch_repack_weights(weights, wpk, n_tokens, plan.a.n_pad, k, s);
+        if (rc != LFFN_OK) return rc;
+        return launch_gather_lds(plan, packed, wpk, tables, y, false, s);
+    }
     if (plan.use) {
         uint32_t *packed = static_cast<uint32_t *>(ws);
         float *wpk = reinterpret_cast<float *>(static_cast<char *>(ws) + round256(packed_bytes(n_tokens, k)));
@@ -782,7 +818,7 @@ int lookupffn_gather(const uint16_t *codes, const void *tables, float *y, int64_
         rc = own_workspace((size_t)packed_bytes(n_tokens, k), &ws);
         if (rc != LFFN_OK) return rc;
         uint32_t *packed = static_cast<uint32_t *>(ws);
-        rc = launch_repack_codes(codes, packed, n_tokens, plan.a.n_pad, k, tau, s);
+        rc = launch_repack_codes(codes, packed, n_tokens, plan.a.n_pad, k, tau, plan.shift, s);
         if (rc != LFFN_OK) return rc;
         return launch_gather_lds(plan, packed, nullptr, tables, y, bf16, s);
     }
@@ -792,9 +828,9 @@ int lookupffn_gather(const uint16_t *codes, const void *tables, float *y, int64_
 int64_t lookupffn_workspace_bytes(int64_t n_tokens, int k)
 {
     if (n_tokens <= 0 || k < 1) return 0;
-    // room for either code layout: [n][k] uint16, or the packed layout with its token padding
-    const int64_t b = packed_bytes(n_tokens, k);
-    return (b + 255) & ~int64_t(255);
+    // the packed layout with its token padding, and [n][k] uint16 beside it (the 64-byte-slice form of the
+    // staged gather takes its codes through the re-pack kernel; otherwise only one of the two is used)
+    return round256(packed_bytes(n_tokens, k)) + round256(n_tokens * (int64_t)k * 2);
 }
 
 int lookupffn_forward(const void *x, const int8_t *signs, const void *tables, float *y, int64_t n_tokens,
@@ -824,6 +860,16 @@ int lookupffn_forward(const void *x, const int8_t *signs, const void *tables, fl
     LdsPlan plan;
     rc = plan_gather_lds(n_tokens, k, tau, d_out, bf16, &plan);
     if (rc != LFFN_OK) return rc;
+    if (plan.use && plan.shift != 7) {
+        // 64-byte slices: ABI codes, then the re-pack kernel scales them for 64-byte row pieces
+        uint32_t *packed = static_cast<uint32_t *>(ws);
+        uint16_t *codes = reinterpret_cast<uint16_t *>(static_cast<char *>(ws) + round256(packed_bytes(n_tokens, k)));
+        rc = launch_hash(x, signs, codes, nullptr, nullptr, n_tokens, d, k, tau, n_rounds, x_dtype, s);
+        if (rc != LFFN_OK) return rc;
+        rc = launch_repack_codes(codes, packed, n_tokens, plan.a.n_pad, k, tau, plan.shift, s);
+        if (rc != LFFN_OK) return rc;
+        return launch_gather_lds(plan, packed, nullptr, tables, y, bf16, s);
+    }
     if (plan.use) {
         uint32_t *packed = static_cast<uint32_t *>(ws);
         rc = launch_hash(x, signs, nullptr, packed, nullptr, n_tokens, d, k, tau, n_rounds, x_dtype, s);
@@ -893,7 +939,7 @@ int lookupffn_forward_bh(const void *x, const float *bmats, const void *tables, 
     LdsPlan plan;
     rc = plan_gather_lds(n_tokens, k, tau, d_out, bf16, &plan);
     if (rc != LFFN_OK) return rc;
-    if (plan.use) {
+    if (plan.use && plan.shift == 7) {  // the BH hash writes codes scaled for 128-byte row pieces only
         uint32_t *packed = static_cast<uint32_t *>(scratch);
         rc = launch_hash_bh(x, bmats, apack, nullptr, packed, n_tokens, d, k, tau, block, n_factors, x_dtype, s);
         if (rc != LFFN_OK) return rc;
@@ -973,6 +1019,11 @@ int lookupffn_set_option(const char *key, int value)
     if (!std::strcmp(key, "hash_blocks")) {
         if (value < 0 || value > 65536) return LFFN_E_SIZE;
         g_opt.hash_blocks = value;
+        return LFFN_OK;
+    }
+    if (!std::strcmp(key, "slice_lanes")) {
+        if (value != 0 && value != 4 && value != 8) return LFFN_E_SIZE;
+        g_opt.slice_lanes = value;
         return LFFN_OK;
     }
     if (!std::strcmp(key, "gather_path")) {

@@ -28,6 +28,7 @@ def _gpu():
     B.lookupffn_set_option("gather_path", 0)
     B.lookupffn_set_option("hash_path", 0)
     B.lookupffn_set_option("hash_blocks", 0)
+    B.lookupffn_set_option("slice_lanes", 0)
 
 
 def rel_err(y, ref):
@@ -196,7 +197,7 @@ def test_gather_every_launch_shape(lpt, xcd):
 
 
 LDS_SHAPES = [
-    # n, k, tau, d_out, table dtype     (gather_path = 2 forces the LDS-staged kernel: tau 7, 8 or 9, k even)
+    # n, k, tau, d_out, table dtype     (gather_path = 2 forces the LDS-staged kernel: tau 7 .. 10, k even)
     (1003, 96, 8, 768, "f32"),       # three slices per XCD, ragged chunks
     (1003, 96, 8, 768, "bf16"),
     (16384, 32, 8, 768, "f32"),      # the benchmark's split: 11/11/10 workgroups per slice, 13 tokens per lane
@@ -215,7 +216,42 @@ LDS_SHAPES = [
     (1500, 4, 9, 64, "bf16"),        # tau = 9, two code words
     (9000, 6, 9, 200, "f32"),        # tau = 9, three code words, ragged last slice, several chunks
     (600, 12, 9, 72, "bf16"),
+    (5000, 128, 10, 1024, "f32"),    # tau = 10: 64-byte column slices, one 1024-row table per stage
+    (2500, 2, 10, 16, "f32"),        # tau = 10, a single code word, one piece per row
+    (9000, 6, 10, 200, "f32"),       # tau = 10, ragged last slice (50 pieces in slices of 4)
 ]
+
+
+@pytest.mark.parametrize("n,k,tau,d_out", [(1003, 96, 8, 768), (16384, 32, 8, 768), (3000, 170, 9, 768),
+                                           (9000, 6, 9, 200), (777, 2, 8, 64), (40000, 4, 8, 72)])
+def test_gather_lds_staged_kernel_64_byte_slices(n, k, tau, d_out):
+    print(f"gather (LDS-staged, 4 lanes per token) n={n} k={k} tau={tau} d_out={d_out}", flush=True)
+    tables = synth.make_tables(n + k, k, 1 << tau, d_out)
+    codes = np.random.default_rng(n).integers(0, 1 << tau, size=(n, k)).astype(np.uint16)
+    B.lookupffn_set_option("gather_path", 2)
+    B.lookupffn_set_option("slice_lanes", 4)
+    try:
+        y = gpu_gather(codes, tables)
+        assert B.lookupffn_last_gather_kernel() == "gather_lds_kernel"
+    finally:
+        B.lookupffn_set_option("gather_path", 0)
+        B.lookupffn_set_option("slice_lanes", 0)
+    assert np.array_equal(y, oracle.gather(codes, tables, acc64=False))
+
+
+def test_forward_64_byte_slices_on_request():
+    print("forward with the 64-byte-slice staged gather (codes re-packed from the ABI layout)", flush=True)
+    w = synth.C2.with_tokens(5000)
+    x, signs, tables = synth.make_layer(w)
+    B.lookupffn_set_option("gather_path", 2)
+    B.lookupffn_set_option("slice_lanes", 4)
+    try:
+        y = gpu_forward(x, signs, tables)
+        assert B.lookupffn_last_gather_kernel() == "gather_lds_kernel"
+    finally:
+        B.lookupffn_set_option("gather_path", 0)
+        B.lookupffn_set_option("slice_lanes", 0)
+    assert np.array_equal(y, oracle.forward(x, signs, tables, acc64=False))
 
 
 @pytest.mark.parametrize("n,k,tau,d_out,tdt", LDS_SHAPES)

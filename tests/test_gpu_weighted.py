@@ -159,7 +159,7 @@ def test_gather_weighted_unit_weights_equal_the_plain_gather(lpt):
 
 
 LDS_SHAPES = [
-    # n, k, tau, d_out      (gather_path = 2 forces the LDS-staged kernel: fp32 tables, tau 7, 8 or 9, k even)
+    # n, k, tau, d_out      (gather_path = 2 forces the LDS-staged kernel: fp32 tables, tau 7 .. 10, k even)
     (1003, 96, 8, 768),      # three slices per XCD, ragged chunks
     (16384, 32, 8, 768),     # the benchmark's split, two chunks of 6 tokens per lane
     (5000, 24, 7, 200),      # ragged last slice, 128-row tables
@@ -172,6 +172,8 @@ LDS_SHAPES = [
     (3000, 170, 9, 768),     # tau = 9: one table per stage
     (1500, 2, 9, 64),        # tau = 9, a single code word
     (9000, 6, 9, 200),       # tau = 9, three code words, ragged last slice
+    (5000, 128, 10, 1024),   # tau = 10: 64-byte column slices
+    (9000, 6, 10, 200),
 ]
 
 
