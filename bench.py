@@ -44,6 +44,8 @@ def parse_args():
                     help="hash of the pass: the sign-diagonal x Hadamard rounds of the headline metric, or the "
                          "paper's BH4 (four block-diagonal x Hadamard factors, lookupffn_forward_bh)")
     ap.add_argument("--block", type=int, default=64, choices=[16, 32, 64], help="block size of the BH4 factors")
+    ap.add_argument("--slice-lanes", type=int, default=0, choices=[0, 4, 8],
+                    help="tuning: column-slice width of the staged gather in 16-byte lanes (0 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle timing")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
@@ -102,6 +104,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     torch.cuda.set_device(0)
     B.lib()
+    B.lookupffn_set_option("slice_lanes", args.slice_lanes)
     w = synth.CONFIGS[args.config]
     bh = args.hash == "bh4"
     if args.probes and args.weighted:

@@ -328,12 +328,14 @@ int launch_gather_lds_fr(const GatherLdsArgs &a, dim3 grid, size_t lds, hipStrea
 template <bool BF16, int TOK, bool WEIGHTED = false>
 int launch_gather_lds_t(const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s)
 {
-    if (sw == 8) {
-        return fr == 4   ? launch_gather_lds_fr<BF16, TOK, 4, WEIGHTED, 8>(a, grid, lds, s)
-               : fr == 2 ? launch_gather_lds_fr<BF16, TOK, 2, WEIGHTED, 8>(a, grid, lds, s)
-                         : launch_gather_lds_fr<BF16, TOK, 1, WEIGHTED, 8>(a, grid, lds, s);
+    if constexpr (TOK <= 13) {
+        if (sw == 8)
+            return fr == 4   ? launch_gather_lds_fr<BF16, TOK, 4, WEIGHTED, 8>(a, grid, lds, s)
+                   : fr == 2 ? launch_gather_lds_fr<BF16, TOK, 2, WEIGHTED, 8>(a, grid, lds, s)
+                             : launch_gather_lds_fr<BF16, TOK, 1, WEIGHTED, 8>(a, grid, lds, s);
     }
-    if constexpr (!BF16 && (TOK == 8 || TOK == 13)) {  // 64-byte slices: built for fp32 tables
+    if (sw != 4) return LFFN_E_UNSUPPORTED;
+    if constexpr (!BF16 && (TOK == 8 || TOK == 13 || TOK == 16)) {  // 64-byte slices: built for fp32 tables
         return fr == 4   ? launch_gather_lds_fr<false, TOK, 4, WEIGHTED, 4>(a, grid, lds, s)
                : fr == 2 ? launch_gather_lds_fr<false, TOK, 2, WEIGHTED, 4>(a, grid, lds, s)
                          : launch_gather_lds_fr<false, TOK, 1, WEIGHTED, 4>(a, grid, lds, s);
@@ -396,7 +398,7 @@ int plan_gather_lds(int64_t n, int k, int tau, int d_out, bool bf16, LdsPlan *p,
     a.n_units = a.n_slices * a.token_splits;
     a.blocks_per_xcd = cus / kXcds;
     const int64_t tpb = lds_tokens_per_block(n, a.n_units, a.token_splits, a.blocks_per_xcd);
-    const int tok_max = bf16 ? 8 : 13;
+    const int tok_max = bf16 ? 8 : sw == 4 ? 16 : 13;
     const int64_t nchunks = (tpb + (int64_t)groups * tok_max - 1) / ((int64_t)groups * tok_max);
     const int64_t chunk = (tpb + nchunks - 1) / nchunks;
     // Staging pays only when a chunk re-uses each staged row a few times.  With bf16 rows the
@@ -404,7 +406,7 @@ int plan_gather_lds(int64_t n, int k, int tau, int d_out, bool bf16, LdsPlan *p,
     // bf16 tables take the staged kernel only on request.
     if (g_opt.gather_path != 2 && (bf16 || chunk < 2 * (int64_t)rows)) return LFFN_OK;
     p->tok = (int)((chunk + groups - 1) / groups);
-    if (sw == 4) p->tok = p->tok > 8 ? 13 : 8;  // the 64-byte form is built for 8 and 13 token slots
+    if (sw == 4) p->tok = p->tok > 13 ? 16 : p->tok > 8 ? 13 : 8;  // the 64-byte form is built for 8, 13 and 16 token slots
     p->sw = sw;
     p->fr = rows / groups;
     p->shift = sw == 8 ? 7 : 6;
@@ -431,6 +433,7 @@ int launch_gather_lds(const LdsPlan &p, const uint32_t *packed, const float *wpk
         else if (p.tok <= 8) rc = launch_gather_lds_t<false, 8, true>(a, p.fr, p.sw, grid, p.lds, s);
         else if (p.tok <= 12) rc = launch_gather_lds_t<false, 12, true>(a, p.fr, p.sw, grid, p.lds, s);
         else if (p.tok <= 13) rc = launch_gather_lds_t<false, 13, true>(a, p.fr, p.sw, grid, p.lds, s);
+        else if (p.tok <= 16 && p.sw == 4) rc = launch_gather_lds_t<false, 16, true>(a, p.fr, p.sw, grid, p.lds, s);
     } else if (bf16) {
         if (p.tok <= 4) rc = launch_gather_lds_t<true, 4>(a, p.fr, p.sw, grid, p.lds, s);
         else if (p.tok <= 6) rc = launch_gather_lds_t<true, 6>(a, p.fr, p.sw, grid, p.lds, s);
@@ -440,6 +443,7 @@ int launch_gather_lds(const LdsPlan &p, const uint32_t *packed, const float *wpk
         else if (p.tok <= 8) rc = launch_gather_lds_t<false, 8>(a, p.fr, p.sw, grid, p.lds, s);
         else if (p.tok <= 12) rc = launch_gather_lds_t<false, 12>(a, p.fr, p.sw, grid, p.lds, s);
         else if (p.tok <= 13) rc = launch_gather_lds_t<false, 13>(a, p.fr, p.sw, grid, p.lds, s);
+        else if (p.tok <= 16 && p.sw == 4) rc = launch_gather_lds_t<false, 16>(a, p.fr, p.sw, grid, p.lds, s);
     }
     if (rc != LFFN_OK) return rc;
     LFFN_HIP(hipGetLastError());

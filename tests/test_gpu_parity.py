@@ -223,7 +223,9 @@ LDS_SHAPES = [
 
 
 @pytest.mark.parametrize("n,k,tau,d_out", [(1003, 96, 8, 768), (16384, 32, 8, 768), (3000, 170, 9, 768),
-                                           (9000, 6, 9, 200), (777, 2, 8, 64), (40000, 4, 8, 72)])
+                                           (9000, 6, 9, 200), (777, 2, 8, 64), (40000, 4, 8, 72),
+                                           (65536, 6, 9, 200),      # 16 token slots per lane
+                                           (16384, 8, 10, 1024)])   # tau = 10 at the benchmark's split: 16 slots
 def test_gather_lds_staged_kernel_64_byte_slices(n, k, tau, d_out):
     print(f"gather (LDS-staged, 4 lanes per token) n={n} k={k} tau={tau} d_out={d_out}", flush=True)
     tables = synth.make_tables(n + k, k, 1 << tau, d_out)
