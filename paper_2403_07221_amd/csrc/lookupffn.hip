@@ -373,11 +373,16 @@ int plan_gather_lds(int64_t n, int k, int tau, int d_out, bool bf16, LdsPlan *p,
     if (weighted && bf16) return LFFN_OK;  // the weighted staged kernel is built for fp32 tables
     const int rows = 1 << tau;
     if (tau < 7 || tau > 10 || k % 2 != 0) return LFFN_OK;
-    // column slices: 128 bytes (8 lanes per token) while a table slice fits a 64 KB buffer (tau <= 9),
-    // else 64 bytes (tau = 10); the 64-byte form exists for fp32 tables and tau >= 8
-    int sw = tau <= 9 ? 8 : 4;
+    // column slices: 128 bytes (8 lanes per token) up to tau = 8; 64 bytes from tau = 9 on (two 512-row
+    // tables per stage and half the copy volume per token measured faster than one per stage; tau = 10
+    // fits a 64 KB buffer only this way).  The 64-byte form exists for fp32 tables and tau >= 8.
+    int sw = tau <= 8 ? 8 : 4;
     if (g_opt.slice_lanes == 4 && tau >= 8) sw = 4;
-    if (sw == 4 && bf16) return LFFN_OK;
+    if (g_opt.slice_lanes == 8 && tau <= 9) sw = 8;
+    if (sw == 4 && bf16) {
+        if (tau > 9) return LFFN_OK;
+        sw = 8;
+    }
     const int groups = kLdsThreads / sw;
     // the kernel indexes tokens and bytes inside one table with 32 bits
     if (n >= (int64_t(1) << 31) - 4096 || (int64_t)rows * d_out * 4 >= (int64_t(1) << 32)) return LFFN_OK;

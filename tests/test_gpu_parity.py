@@ -241,6 +241,22 @@ def test_gather_lds_staged_kernel_64_byte_slices(n, k, tau, d_out):
     assert np.array_equal(y, oracle.gather(codes, tables, acc64=False))
 
 
+@pytest.mark.parametrize("n,k,tau,d_out,tdt", [(3000, 170, 9, 768, "f32"), (9000, 6, 9, 200, "f32"), (1500, 2, 9, 64, "f32")])
+def test_gather_lds_staged_kernel_128_byte_slices_at_tau_9(n, k, tau, d_out, tdt):
+    print(f"gather (LDS-staged, 8 lanes per token on request) n={n} k={k} tau={tau} d_out={d_out}", flush=True)
+    tables = synth.make_tables(n + k, k, 1 << tau, d_out, tdt)
+    codes = np.random.default_rng(n).integers(0, 1 << tau, size=(n, k)).astype(np.uint16)
+    B.lookupffn_set_option("gather_path", 2)
+    B.lookupffn_set_option("slice_lanes", 8)
+    try:
+        y = gpu_gather(codes, tables)
+        assert B.lookupffn_last_gather_kernel() == "gather_lds_kernel"
+    finally:
+        B.lookupffn_set_option("gather_path", 0)
+        B.lookupffn_set_option("slice_lanes", 0)
+    assert np.array_equal(y, oracle.gather(codes, tables, acc64=False))
+
+
 def test_forward_64_byte_slices_on_request():
     print("forward with the 64-byte-slice staged gather (codes re-packed from the ABI layout)", flush=True)
     w = synth.C2.with_tokens(5000)
