@@ -130,9 +130,13 @@ __device__ __forceinline__ uint32_t quad_bcast(uint32_t v, int q)
 // or 4 (64-byte slices; tau = 8, 9, 10 <-> FR = 1, 2, 4).  The packed codes must be scaled by the
 // row-piece bytes: code << 7 for SW = 8 (what the hash kernels write), code << 6 for SW = 4 (written
 // by the re-pack kernel from ABI codes; 1023 << 7 would not fit the 16-bit half of a code word).
-template <bool BF16, int TOK, int FR, bool WEIGHTED, int SW = 8>
+// PROBES (with WEIGHTED): the multi-probe form (Sec. 3.1, eq. "partial_softmax"): every stage is swept
+// 1 + tau times, sweep p reading the rows code ^ flip(p) with the shares of probe p
+// (wpk[(j * (1 + tau) + p) * n_pad + t]); the staged slice is copied once per stage.
+template <bool BF16, int TOK, int FR, bool WEIGHTED, int SW = 8, bool PROBES = false>
 __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a)
 {
+    static_assert(!PROBES || WEIGHTED, "the multi-probe form carries weights");
     static_assert(TOK <= kLdsMaxTok, "packed-code padding covers 16 token slots");
     static_assert(FR == 1 || FR == 2 || FR == 4, "table slices of 16, 32 or 64 KB");
     static_assert(SW == 8 || SW == 4, "128- or 64-byte column slices");
@@ -319,6 +323,92 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
                 __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): next stage's rows and codes have landed
                 __syncthreads();
             };
+            // ---- multi-probe form: one sweep of the stage per probe --------------------------------
+            // shares of probe pr for table u of stage s, register m
+            auto load_share = [&](uint32_t s, int i, uint32_t pr, float(&wr)[TPS][WQ]) {
+                const int u = i / WQ, m = i % WQ;
+                const char *base = reinterpret_cast<const char *>(a.wpk) +
+                                   ((size_t)((s * TPS + (uint32_t)u) * ((uint32_t)a.tau + 1u) + pr) * a.n_pad + c0) * 4u;  // uniform
+                wr[u][m] = *reinterpret_cast<const float *>(base + reg_offset(m));
+            };
+            // One sweep: rows code ^ flip with shares `w`; meanwhile the shares of (ns, npr) travel into
+            // w_next and, in a stage's last sweep (FILL), the next stage's row copies and codes.
+            auto sweep = [&](auto fill_tag, auto mode_tag, uint32_t s, uint32_t b, const uint32_t(&cr)[NCR],
+                             uint32_t(&cr_next)[NCR], const float(&w)[TPS][WQ], float(&w_next)[TPS][WQ],
+                             uint32_t flip, bool more_shares, uint32_t ns, uint32_t npr) {
+                constexpr bool FILL = decltype(fill_tag)::value;
+                constexpr int HALF = decltype(mode_tag)::value;
+                constexpr bool LOADC = TPS == 2 || HALF == 1;
+                constexpr int RB = LFFN_LDS_RB;
+                constexpr int NB = (TOK + RB - 1) / RB;
+                constexpr int NBT = TPS * NB;
+                uint4 r[2][RB];
+                auto issue = [&](int bi, uint4(&dst)[RB]) {
+                    const int u = bi / NB, b0 = (bi % NB) * RB;
+                    const uint32_t base = qb + b * buf_bytes + (uint32_t)u * tbl_bytes;
+#pragma unroll
+                    for (int i = 0; i < RB; ++i)
+                        if (b0 + i < TOK) {
+                            const uint32_t off = row_offset(cr, TPS == 2 ? u : HALF, b0 + i) ^ flip;
+                            const u32x4 v = *reinterpret_cast<const __attribute__((address_space(3))) u32x4 *>(
+                                (uintptr_t)(base + off));
+                            dst[i] = make_uint4(v.x, v.y, v.z, v.w);
+                        }
+                };
+                auto consume = [&](int bi, const uint4(&src)[RB]) {
+                    const int u = bi / NB, b0 = (bi % NB) * RB;
+#pragma unroll
+                    for (int i = 0; i < RB; ++i)
+                        if (b0 + i < TOK) {
+                            acc[b0 + i].fma(src[i], quad_bcast(w[u][(b0 + i) >> 2], (b0 + i) & 3));
+                            acc[b0 + i].pin();
+                        }
+                };
+                issue(0, r[0]);
+#pragma unroll
+                for (int bi = 0; bi < NBT; ++bi) {
+                    if (bi + 1 < NBT) issue(bi + 1, r[(bi + 1) & 1]);
+                    // the next sweep's shares first: they are needed soonest
+                    if (more_shares) {
+#pragma unroll
+                        for (int m = 0; m < NWL; ++m)
+                            if (vm_slot(m / 2, NBT) == bi) load_share(ns, m, npr, w_next);  // two per batch, early
+                    }
+                    if constexpr (FILL) {
+#pragma unroll
+                        for (int idx = 0; idx < TPS * FR; ++idx)
+                            if (vm_slot(idx, NBT) == bi) fill_piece(s + 1, b ^ 1u, idx);
+                        if constexpr (LOADC) {
+#pragma unroll
+                            for (int m = 0; m < NCR; ++m)
+                                if (vm_slot(LFFN_LDS_CO + m, NBT) == bi) load_code((s + 1) * TPS / 2, m, cr_next);
+                        }
+                    }
+                    consume(bi, r[bi & 1]);
+                }
+            };
+            // a whole stage: 1 + tau sweeps, then the barrier that publishes the next stage's buffer
+            auto run_stage_probes = [&](auto more_tag, auto mode_tag, uint32_t s, uint32_t b, const uint32_t(&cr)[NCR],
+                                        uint32_t(&cr_next)[NCR], float(&w)[TPS][WQ], float(&w_next)[TPS][WQ]) {
+                constexpr bool MORE = decltype(more_tag)::value;
+                const uint32_t tau = (uint32_t)a.tau;
+                for (uint32_t pr = 0; pr < tau; ++pr) {
+                    sweep(std::integral_constant<bool, false>{}, mode_tag, s, b, cr, cr_next, w, w_next,
+                          pr ? (PIECE << (pr - 1u)) : 0u, true, s, pr + 1u);
+#pragma unroll
+                    for (int u = 0; u < TPS; ++u)
+#pragma unroll
+                        for (int m = 0; m < WQ; ++m) w[u][m] = w_next[u][m];
+                }
+                sweep(more_tag, mode_tag, s, b, cr, cr_next, w, w_next, PIECE << (tau - 1u), MORE, s + 1u, 0u);
+#pragma unroll
+                for (int u = 0; u < TPS; ++u)
+#pragma unroll
+                    for (int m = 0; m < WQ; ++m) w[u][m] = w_next[u][m];
+                __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): next stage's rows, codes and first shares have landed
+                __syncthreads();
+            };
+
             using yes = std::integral_constant<bool, true>;
             using no = std::integral_constant<bool, false>;
 
@@ -327,7 +417,10 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
             for (int idx = 0; idx < TPS * FR; ++idx) fill_piece(0, 0, idx);
 #pragma unroll
             for (int i = 0; i < NCR; ++i) load_code(0, i, crA);
-            if constexpr (WEIGHTED) {
+            if constexpr (PROBES) {
+#pragma unroll
+                for (int i = 0; i < NWL; ++i) load_share(0, i, 0u, wA);
+            } else if constexpr (WEIGHTED) {
 #pragma unroll
                 for (int i = 0; i < NWL; ++i) load_weight(0, i, wA);
             }
@@ -338,7 +431,37 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
             using t0 = std::integral_constant<int, 0>;
             using t1 = std::integral_constant<int, 1>;
             uint32_t s = 0;
-            if constexpr (TPS == 2) {
+            if constexpr (PROBES) {
+                // the shares of the sweep in progress stay in wA, those in flight in wB
+                if constexpr (TPS == 2) {
+                    for (; s + 2 < nstages; s += 2) {
+                        run_stage_probes(yes{}, t0{}, s, 0u, crA, crB, wA, wB);
+                        run_stage_probes(yes{}, t0{}, s + 1, 1u, crB, crA, wA, wB);
+                    }
+                    if (s + 1 < nstages) {
+                        run_stage_probes(yes{}, t0{}, s, 0u, crA, crB, wA, wB);
+                        run_stage_probes(no{}, t0{}, s + 1, 1u, crB, crA, wA, wB);
+                    } else {
+                        run_stage_probes(no{}, t0{}, s, 0u, crA, crB, wA, wB);
+                    }
+                } else {
+                    for (; s + 4 < nstages; s += 4) {
+                        run_stage_probes(yes{}, t0{}, s, 0u, crA, crB, wA, wB);
+                        run_stage_probes(yes{}, t1{}, s + 1, 1u, crA, crB, wA, wB);
+                        run_stage_probes(yes{}, t0{}, s + 2, 0u, crB, crA, wA, wB);
+                        run_stage_probes(yes{}, t1{}, s + 3, 1u, crB, crA, wA, wB);
+                    }
+                    if (s + 2 < nstages) {
+                        run_stage_probes(yes{}, t0{}, s, 0u, crA, crB, wA, wB);
+                        run_stage_probes(yes{}, t1{}, s + 1, 1u, crA, crB, wA, wB);
+                        run_stage_probes(yes{}, t0{}, s + 2, 0u, crB, crA, wA, wB);
+                        run_stage_probes(no{}, t1{}, s + 3, 1u, crB, crA, wA, wB);
+                    } else {
+                        run_stage_probes(yes{}, t0{}, s, 0u, crA, crB, wA, wB);
+                        run_stage_probes(no{}, t1{}, s + 1, 1u, crA, crB, wA, wB);
+                    }
+                }
+            } else if constexpr (TPS == 2) {
                 for (; s + 2 < nstages; s += 2) {
                     run_stage(yes{}, t0{}, s, 0u, crA, crB, wA, wB);
                     run_stage(yes{}, t0{}, s + 1, 1u, crB, crA, wB, wA);

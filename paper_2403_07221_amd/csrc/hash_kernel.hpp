@@ -634,6 +634,18 @@ __global__ __launch_bounds__(256) void repack_weights_kernel(const float *weight
     }
 }
 
+// ABI shares [n][k][1+tau] -> [k][1+tau][n_pad] for the staged multi-probe gather (token padding left as it is)
+__global__ __launch_bounds__(256) void repack_shares_kernel(const float *shares, float *spk, long long n,
+                                                            long long n_pad, int k, int np)
+{
+    const long long total = (long long)k * np * n;
+    for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+         idx += (long long)gridDim.x * blockDim.x) {
+        const long long jp = idx / n, t = idx - jp * n;  // jp = j * np + probe
+        spk[jp * n_pad + t] = shares[t * k * np + jp];
+    }
+}
+
 // ABI codes [n][k] -> packed layout scaled by 2^shift (for a stand-alone gather call that takes the
 // LDS-staged kernel, and for the staged kernel's 64-byte-slice form, which needs shift 6)
 __global__ __launch_bounds__(256) void repack_codes_kernel(const uint16_t *codes, uint32_t *packed, long long n,

@@ -314,10 +314,10 @@ int device_cus(int *cus)
     return LFFN_OK;
 }
 
-template <bool BF16, int TOK, int FR, bool WEIGHTED, int SW>
+template <bool BF16, int TOK, int FR, bool WEIGHTED, int SW, bool PROBES = false>
 int launch_gather_lds_fr(const GatherLdsArgs &a, dim3 grid, size_t lds, hipStream_t s)
 {
-    auto kern = gather_lds_kernel<BF16, TOK, FR, WEIGHTED, SW>;
+    auto kern = gather_lds_kernel<BF16, TOK, FR, WEIGHTED, SW, PROBES>;
     int rc = allow_lds(reinterpret_cast<const void *>(kern), lds);
     if (rc != LFFN_OK) return rc;
     hipLaunchKernelGGL(kern, grid, dim3(kLdsThreads), lds, s, a);
@@ -339,6 +339,21 @@ int launch_gather_lds_t(const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_
         return fr == 4   ? launch_gather_lds_fr<false, TOK, 4, WEIGHTED, 4>(a, grid, lds, s)
                : fr == 2 ? launch_gather_lds_fr<false, TOK, 2, WEIGHTED, 4>(a, grid, lds, s)
                          : launch_gather_lds_fr<false, TOK, 1, WEIGHTED, 4>(a, grid, lds, s);
+    }
+    return LFFN_E_UNSUPPORTED;
+}
+
+// multi-probe form: fp32 tables; 128-byte slices for tau 7, 8, 64-byte slices for tau 9, 10
+template <int TOK>
+int launch_gather_lds_probes(const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s)
+{
+    if constexpr (TOK <= 13 && TOK != 12) {
+        if (sw == 8 && fr == 2) return launch_gather_lds_fr<false, TOK, 2, true, 8, true>(a, grid, lds, s);
+        if (sw == 8 && fr == 1) return launch_gather_lds_fr<false, TOK, 1, true, 8, true>(a, grid, lds, s);
+    }
+    if constexpr (TOK == 8 || TOK == 13 || TOK == 16) {
+        if (sw == 4 && fr == 4) return launch_gather_lds_fr<false, TOK, 4, true, 4, true>(a, grid, lds, s);
+        if (sw == 4 && fr == 2) return launch_gather_lds_fr<false, TOK, 2, true, 4, true>(a, grid, lds, s);
     }
     return LFFN_E_UNSUPPORTED;
 }
@@ -366,7 +381,8 @@ struct LdsPlan {
     size_t lds = 0;
 };
 
-int plan_gather_lds(int64_t n, int k, int tau, int d_out, bool bf16, LdsPlan *p, bool weighted = false)
+int plan_gather_lds(int64_t n, int k, int tau, int d_out, bool bf16, LdsPlan *p, bool weighted = false,
+                    bool probes = false)
 {
     p->use = false;
     if (g_opt.gather_path == 1) return LFFN_OK;
@@ -379,6 +395,7 @@ int plan_gather_lds(int64_t n, int k, int tau, int d_out, bool bf16, LdsPlan *p,
     int sw = tau <= 8 ? 8 : 4;
     if (g_opt.slice_lanes == 4 && tau >= 8) sw = 4;
     if (g_opt.slice_lanes == 8 && tau <= 9) sw = 8;
+    if (probes) sw = tau <= 8 ? 8 : 4;  // the multi-probe form is built for these pairings only
     if (sw == 4 && bf16) {
         if (tau > 9) return LFFN_OK;
         sw = 8;
@@ -411,6 +428,7 @@ int plan_gather_lds(int64_t n, int k, int tau, int d_out, bool bf16, LdsPlan *p,
     // bf16 tables take the staged kernel only on request.
     if (g_opt.gather_path != 2 && (bf16 || chunk < 2 * (int64_t)rows)) return LFFN_OK;
     p->tok = (int)((chunk + groups - 1) / groups);
+    if (probes && sw == 8 && p->tok > 8) p->tok = 13;  // multi-probe form: 4, 8 or 13 slots
     if (sw == 4) p->tok = p->tok > 13 ? 16 : p->tok > 8 ? 13 : 8;  // the 64-byte form is built for 8, 13 and 16 token slots
     p->sw = sw;
     p->fr = rows / groups;
@@ -423,7 +441,7 @@ int plan_gather_lds(int64_t n, int k, int tau, int d_out, bool bf16, LdsPlan *p,
 }
 
 int launch_gather_lds(const LdsPlan &p, const uint32_t *packed, const float *wpk, const void *tables, float *y,
-                      bool bf16, hipStream_t s)
+                      bool bf16, hipStream_t s, bool probes = false)
 {
     GatherLdsArgs a = p.a;
     a.packed = packed;
@@ -433,7 +451,12 @@ int launch_gather_lds(const LdsPlan &p, const uint32_t *packed, const float *wpk
     const dim3 grid(p.grid);
     int rc = LFFN_E_UNSUPPORTED;
     TimedLaunch tl(1, s);
-    if (wpk) {
+    if (probes) {
+        if (p.tok <= 4) rc = launch_gather_lds_probes<4>(a, p.fr, p.sw, grid, p.lds, s);
+        else if (p.tok <= 8) rc = launch_gather_lds_probes<8>(a, p.fr, p.sw, grid, p.lds, s);
+        else if (p.tok <= 13) rc = launch_gather_lds_probes<13>(a, p.fr, p.sw, grid, p.lds, s);
+        else if (p.tok <= 16) rc = launch_gather_lds_probes<16>(a, p.fr, p.sw, grid, p.lds, s);
+    } else if (wpk) {
         if (p.tok <= 4) rc = launch_gather_lds_t<false, 4, true>(a, p.fr, p.sw, grid, p.lds, s);
         else if (p.tok <= 8) rc = launch_gather_lds_t<false, 8, true>(a, p.fr, p.sw, grid, p.lds, s);
         else if (p.tok <= 12) rc = launch_gather_lds_t<false, 12, true>(a, p.fr, p.sw, grid, p.lds, s);
@@ -458,6 +481,7 @@ int launch_gather_lds(const LdsPlan &p, const uint32_t *packed, const float *wpk
 }
 
 int64_t packed_bytes(int64_t n, int k) { return ((int64_t)(k + 1) / 2) * packed_n_pad(n) * 4; }
+int64_t probes_spk_bytes(int64_t n, int k, int tau) { return round256((int64_t)k * (tau + 1) * packed_n_pad(n) * 4); }
 
 int launch_gather_direct(const uint16_t *codes, const float *weights, const void *tables, float *y, int64_t n,
                          int k, int tau, int d_out, int table_dtype, hipStream_t s, bool probes = false)
@@ -635,6 +659,16 @@ int launch_repack_codes(const uint16_t *codes, uint32_t *packed, int64_t n, int6
     return LFFN_OK;
 }
 
+int launch_repack_shares(const float *shares, float *spk, int64_t n, int64_t n_pad, int k, int tau, hipStream_t s)
+{
+    int64_t blocks = ((int64_t)k * (tau + 1) * n + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(repack_shares_kernel, dim3((unsigned)blocks), dim3(256), 0, s, shares, spk, (long long)n,
+                       (long long)n_pad, k, tau + 1);
+    LFFN_HIP(hipGetLastError());
+    return LFFN_OK;
+}
+
 int launch_repack_weights(const float *weights, float *wpk, int64_t n, int64_t n_pad, int k, hipStream_t s)
 {
     int64_t blocks = ((int64_t)k * n + 255) / 256;
@@ -711,14 +745,33 @@ int lookupffn_gather_probes(const uint16_t *codes, const float *shares, const vo
     int rc = check_gather(codes, tables, y, n_tokens, k, tau, d_out, table_dtype);
     if (rc == LFFN_OK) rc = check_weights(shares);
     if (rc != LFFN_OK || n_tokens == 0) return rc;
-    return launch_gather_direct(codes, shares, tables, y, n_tokens, k, tau, d_out, table_dtype,
-                                static_cast<hipStream_t>(hip_stream), true);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    LdsPlan plan;
+    rc = plan_gather_lds(n_tokens, k, tau, d_out, table_dtype == LFFN_BF16, &plan, true, true);
+    if (rc != LFFN_OK) return rc;
+    if (plan.use && aligned(codes, 4)) {
+        // staged form: packed codes and table-major shares in the library's buffer
+        const int64_t pb = round256(packed_bytes(n_tokens, k));
+        void *ws = nullptr;
+        rc = own_workspace((size_t)(pb + probes_spk_bytes(n_tokens, k, tau)), &ws);
+        if (rc != LFFN_OK) return rc;
+        uint32_t *packed = static_cast<uint32_t *>(ws);
+        float *spk = reinterpret_cast<float *>(static_cast<char *>(ws) + pb);
+        rc = launch_repack_codes(codes, packed, n_tokens, plan.a.n_pad, k, tau, plan.shift, s);
+        if (rc != LFFN_OK) return rc;
+        rc = launch_repack_shares(shares, spk, n_tokens, plan.a.n_pad, k, tau, s);
+        if (rc != LFFN_OK) return rc;
+        return launch_gather_lds(plan, packed, spk, tables, y, false, s, true);
+    }
+    return launch_gather_direct(codes, shares, tables, y, n_tokens, k, tau, d_out, table_dtype, s, true);
 }
 
 int64_t lookupffn_workspace_bytes_probes(int64_t n_tokens, int k, int tau)
 {
     if (n_tokens <= 0 || k < 1 || tau < 1 || tau > 16) return 0;
-    return weighted_codes_bytes(n_tokens, k) + round256((int64_t)n_tokens * k * (tau + 1) * 4);
+    // ABI codes and shares, and beside them the staged gather's packed codes and table-major shares
+    return weighted_codes_bytes(n_tokens, k) + round256((int64_t)n_tokens * k * (tau + 1) * 4) +
+           round256(packed_bytes(n_tokens, k)) + probes_spk_bytes(n_tokens, k, tau);
 }
 
 int lookupffn_forward_probes(const void *x, const int8_t *signs, const void *tables, float *y, int64_t n_tokens,
@@ -746,6 +799,20 @@ int lookupffn_forward_probes(const void *x, const int8_t *signs, const void *tab
     float *shares = reinterpret_cast<float *>(static_cast<char *>(ws) + weighted_codes_bytes(n_tokens, k));
     rc = launch_hash(x, signs, codes, nullptr, shares, n_tokens, d, k, tau, n_rounds, x_dtype, s, true);
     if (rc != LFFN_OK) return rc;
+    LdsPlan plan;
+    rc = plan_gather_lds(n_tokens, k, tau, d_out, table_dtype == LFFN_BF16, &plan, true, true);
+    if (rc != LFFN_OK) return rc;
+    if (plan.use) {
+        char *staged = static_cast<char *>(ws) + weighted_codes_bytes(n_tokens, k) +
+                       round256((int64_t)n_tokens * k * (tau + 1) * 4);
+        uint32_t *packed = reinterpret_cast<uint32_t *>(staged);
+        float *spk = reinterpret_cast<float *>(staged + round256(packed_bytes(n_tokens, k)));
+        rc = launch_repack_codes(codes, packed, n_tokens, plan.a.n_pad, k, tau, plan.shift, s);
+        if (rc != LFFN_OK) return rc;
+        rc = launch_repack_shares(shares, spk, n_tokens, plan.a.n_pad, k, tau, s);
+        if (rc != LFFN_OK) return rc;
+        return launch_gather_lds(plan, packed, spk, tables, y, false, s, true);
+    }
     return launch_gather_direct(codes, shares, tables, y, n_tokens, k, tau, d_out, table_dtype, s, true);
 }
 

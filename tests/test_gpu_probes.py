@@ -22,6 +22,7 @@ def _gpu():
     yield
     B.lookupffn_set_option("hash_path", 0)
     B.lookupffn_set_option("lanes_per_token", 0)
+    B.lookupffn_set_option("gather_path", 0)
 
 
 def rel_err(y, ref):
@@ -105,6 +106,45 @@ def test_gather_probes_first_probe_only_equals_the_plain_gather(lpt):
     finally:
         B.lookupffn_set_option("lanes_per_token", 0)
     assert np.array_equal(y.cpu().numpy(), oracle.gather(codes, tables, acc64=False))
+
+
+LDS_SHAPES = [
+    # n, k, tau, d_out      (gather_path = 2 forces the LDS-staged kernel: fp32 tables, tau 7 .. 10, k even)
+    (1003, 96, 8, 768),      # 128-byte slices, two tables per stage
+    (16384, 8, 8, 768),      # 13 token slots per lane
+    (5000, 24, 7, 200),      # 128-row tables, ragged last slice
+    (777, 2, 8, 64),         # a single stage
+    (700, 6, 8, 64),         # an odd number of stages
+    (3000, 20, 9, 768),      # 64-byte slices, two 512-row tables per stage
+    (40000, 4, 9, 72),       # 16 token slots per lane, ragged slice
+    (5000, 6, 10, 256),      # one 1024-row table per stage: code-word halves alternate
+    (2500, 2, 10, 16),
+]
+
+
+@pytest.mark.parametrize("n,k,tau,d_out", LDS_SHAPES)
+def test_gather_probes_lds_staged_kernel(n, k, tau, d_out):
+    print(f"probe gather (LDS-staged) n={n} k={k} tau={tau} d_out={d_out}", flush=True)
+    rng = np.random.default_rng(n)
+    tables = synth.make_tables(n + k, k, 1 << tau, d_out)
+    codes = rng.integers(0, 1 << tau, size=(n, k)).astype(np.uint16)
+    p = rng.uniform(0.0, 1.0, size=(n, k, tau + 1)).astype(np.float32)
+    cd, pd, td = torch.from_numpy(codes.view(np.int16)).cuda(), torch.from_numpy(p).cuda(), B.to_device(tables)
+    B.lookupffn_set_option("gather_path", 2)
+    try:
+        y_lds = B.lookupffn_gather_probes(cd, pd, td)
+        torch.cuda.synchronize()
+        assert B.lookupffn_last_gather_kernel() == "gather_lds_kernel"
+        B.lookupffn_set_option("gather_path", 1)
+        y_direct = B.lookupffn_gather_probes(cd, pd, td)
+        torch.cuda.synchronize()
+        assert B.lookupffn_last_gather_kernel() == "gather_kernel"
+    finally:
+        B.lookupffn_set_option("gather_path", 0)
+    want = oracle.gather_probes(codes, p.astype(np.float64), tables)
+    # the two kernels add the same terms in different orders (probe-major per stage against table-major)
+    assert rel_err(y_lds.cpu().numpy(), want) <= 1e-4
+    assert rel_err(y_direct.cpu().numpy(), want) <= 1e-4
 
 
 def check_forward_probes(w, x, signs, tables, sample=None):
