@@ -44,6 +44,8 @@ def parse_args():
                     help="hash of the pass: the sign-diagonal x Hadamard rounds of the headline metric, or the "
                          "paper's BH4 (four block-diagonal x Hadamard factors, lookupffn_forward_bh)")
     ap.add_argument("--block", type=int, default=64, choices=[16, 32, 64], help="block size of the BH4 factors")
+    ap.add_argument("--gather-path", type=int, default=0, choices=[0, 1, 2],
+                    help="tuning: 1 = always the direct gather kernel, 2 = the LDS-staged one whenever the shape allows")
     ap.add_argument("--slice-lanes", type=int, default=0, choices=[0, 4, 8],
                     help="tuning: column-slice width of the staged gather in 16-byte lanes (0 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -105,6 +107,7 @@ def main():
     torch.cuda.set_device(0)
     B.lib()
     B.lookupffn_set_option("slice_lanes", args.slice_lanes)
+    B.lookupffn_set_option("gather_path", args.gather_path)
     w = synth.CONFIGS[args.config]
     bh = args.hash == "bh4"
     if args.probes and args.weighted:
