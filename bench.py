@@ -75,7 +75,8 @@ def cpu_baseline(w, x, signs, tables, budget_s: float, weighted: bool = False, b
     n = x.shape[0]
     sample = min(n, 16384)
     xs = x[:sample]
-    run = oracle.bh_forward if bh else oracle.forward_probes if probes else oracle.forward_weighted if weighted else oracle.forward
+    run = ((oracle.bh_forward_weighted if weighted else oracle.bh_forward) if bh else oracle.forward_probes if probes
+           else oracle.forward_weighted if weighted else oracle.forward)
     run(xs[:256], signs, tables)                       # page in
     reps, t_total = 0, 0.0
     while reps < 3 or (t_total < budget_s and reps < 1000):
@@ -113,16 +114,19 @@ def main():
     if args.probes and args.weighted:
         print("--probes and --weighted are different variants: pick one", file=sys.stderr)
         sys.exit(2)
-    if bh and (args.weighted or args.probes or w.n_layers > 1):
-        print("--hash bh4 is timed with the plain-sum gather on the single-layer configurations", file=sys.stderr)
+    if bh and (args.probes or w.n_layers > 1):
+        print("--hash bh4 is timed with the plain-sum or the weighted gather on the single-layer configurations",
+              file=sys.stderr)
         sys.exit(2)
     ws_bytes = (B.lookupffn_workspace_bytes_weighted if args.weighted else B.lookupffn_workspace_bytes)(w.n_tokens, w.k)
     if args.probes:
         ws_bytes = B.lookupffn_workspace_bytes_probes(w.n_tokens, w.k, w.tau)
     if bh:
-        ws_bytes = B.lookupffn_workspace_bytes_bh(w.n_tokens, w.d, w.k, w.tau, args.block, 4)
+        ws_bytes = (B.lookupffn_workspace_bytes_bh_weighted if args.weighted else B.lookupffn_workspace_bytes_bh)(
+            w.n_tokens, w.d, w.k, w.tau, args.block, 4)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
-    forward = (B.lookupffn_forward_bh if bh else B.lookupffn_forward_probes if args.probes
+    forward = ((B.lookupffn_forward_bh_weighted if args.weighted else B.lookupffn_forward_bh) if bh
+               else B.lookupffn_forward_probes if args.probes
                else B.lookupffn_forward_weighted if args.weighted else B.lookupffn_forward)
     if w.n_layers == 1:
         x, signs, tables = synth.make_layer(w)

@@ -160,6 +160,24 @@ int lookupffn_forward_bh(const void *x, const float *bmats, const void *tables, 
                          void *workspace, int64_t workspace_bytes, void *hip_stream);
 int64_t lookupffn_workspace_bytes_bh(int64_t n_tokens, int d, int k, int tau, int block, int n_factors);
 
+/*
+ * BH{m} hash with the weighted gather (the configuration of the paper's experiments: Sec. 3.2 hash,
+ * Sec. 4 forward pass): lookupffn_hash_bh_weighted writes codes[n_tokens][k] and weights[n_tokens][k]
+ * (fp32, 4-byte aligned) with w_j as in lookupffn_hash_weighted, computed from the z of the BH hash;
+ * lookupffn_forward_bh_weighted = that + lookupffn_gather_weighted, with
+ * lookupffn_workspace_bytes_bh_weighted() bytes of scratch (or workspace == NULL).
+ * Supported: the shapes of lookupffn_hash_bh with tau = 4, 8 or 16 (LFFN_E_UNSUPPORTED otherwise:
+ * the kernel reduces a table's weight inside one 16-coordinate tile of z).
+ */
+int lookupffn_hash_bh_weighted(const void *x, const float *bmats, uint16_t *codes, float *weights,
+                               int64_t n_tokens, int d, int k, int tau, int block, int n_factors, int x_dtype,
+                               void *workspace, int64_t workspace_bytes, void *hip_stream);
+int lookupffn_forward_bh_weighted(const void *x, const float *bmats, const void *tables, float *y,
+                                  int64_t n_tokens, int d, int k, int tau, int d_out, int block, int n_factors,
+                                  int x_dtype, int table_dtype,
+                                  void *workspace, int64_t workspace_bytes, void *hip_stream);
+int64_t lookupffn_workspace_bytes_bh_weighted(int64_t n_tokens, int d, int k, int tau, int block, int n_factors);
+
 /* Frees the library-owned workspaces (all devices).  Safe to call when none exist. */
 int lookupffn_release_workspace(void);
 

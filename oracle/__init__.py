@@ -282,6 +282,19 @@ def bh_forward(x: np.ndarray, bmats: np.ndarray, tables: np.ndarray, acc64: bool
     return (y, codes) if return_codes else y
 
 
+def bh_forward_weighted(x: np.ndarray, bmats: np.ndarray, tables: np.ndarray, return_all: bool = False):
+    """BH hash (Sec. 3.2) followed by the weighted gather (Sec. 4): the weights come from the z of the BH
+    hash.  A chain of bh_soft_codes / bh_hash_codes, weights_from_z and gather_weighted, nothing more."""
+    k, rows, d_out = tables.shape
+    tau = rows.bit_length() - 1
+    assert 1 << tau == rows
+    z = bh_soft_codes(x, bmats, k, tau)
+    codes = bh_hash_codes(x, bmats, k, tau)
+    w = weights_from_z(z, k, tau)
+    y = gather_weighted(codes, w, tables)
+    return (y, codes, w) if return_all else y
+
+
 # ---- multi-probe lookup (Sec. 3.1, eq. "partial_softmax", neighbourhood of l0 radius 1) ---------
 
 def probe_weights_from_z(z: np.ndarray, k: int, tau: int):

@@ -24,6 +24,7 @@ EXPORTS = (
     "lookupffn_hash_weighted", "lookupffn_gather_weighted", "lookupffn_forward_weighted",
     "lookupffn_workspace_bytes_weighted",
     "lookupffn_hash_bh", "lookupffn_forward_bh", "lookupffn_workspace_bytes_bh",
+    "lookupffn_hash_bh_weighted", "lookupffn_forward_bh_weighted", "lookupffn_workspace_bytes_bh_weighted",
     "lookupffn_hash_probes", "lookupffn_gather_probes", "lookupffn_forward_probes",
     "lookupffn_workspace_bytes_probes",
 )
@@ -64,6 +65,10 @@ def lib() -> ctypes.CDLL:
         L.lookupffn_forward_bh.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, ci, ci, ci, vp, i64, vp]
         L.lookupffn_workspace_bytes_bh.argtypes = [i64, ci, ci, ci, ci, ci]
         L.lookupffn_workspace_bytes_bh.restype = i64
+        L.lookupffn_hash_bh_weighted.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, ci, vp, i64, vp]
+        L.lookupffn_forward_bh_weighted.argtypes = L.lookupffn_forward_bh.argtypes
+        L.lookupffn_workspace_bytes_bh_weighted.argtypes = [i64, ci, ci, ci, ci, ci]
+        L.lookupffn_workspace_bytes_bh_weighted.restype = i64
         L.lookupffn_timing_enable.argtypes = [ci]
         L.lookupffn_timing_read.argtypes = [ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
         L.lookupffn_set_option.argtypes = [ctypes.c_char_p, ci]
@@ -321,7 +326,7 @@ def lookupffn_hash_bh(x: torch.Tensor, bmats: torch.Tensor, k: int, tau: int, co
 
 
 def lookupffn_forward_bh(x: torch.Tensor, bmats: torch.Tensor, tables: torch.Tensor, y: torch.Tensor | None = None,
-                         workspace: torch.Tensor | None = None) -> torch.Tensor:
+                         workspace: torch.Tensor | None = None, _entry: str = "lookupffn_forward_bh") -> torch.Tensor:
     """Whole forward pass with the BH hash: y[n, d_out]."""
     n, d = x.shape
     k, rows, d_out = tables.shape
@@ -336,10 +341,43 @@ def lookupffn_forward_bh(x: torch.Tensor, bmats: torch.Tensor, tables: torch.Ten
         return y
     ws_ptr, ws_bytes = _ws(workspace)
     with torch.cuda.device(x.device):
-        _check(lib().lookupffn_forward_bh(_dev(x, "x"), _dev(bmats, "bmats"), _dev(tables, "tables"), _dev(y, "y"),
-                                          n, d, k, tau, d_out, block, m, _dtype_code(x), _dtype_code(tables),
-                                          ws_ptr, ws_bytes, _stream(x)))
+        _check(getattr(lib(), _entry)(_dev(x, "x"), _dev(bmats, "bmats"), _dev(tables, "tables"), _dev(y, "y"),
+                                      n, d, k, tau, d_out, block, m, _dtype_code(x), _dtype_code(tables),
+                                      ws_ptr, ws_bytes, _stream(x)))
     return y
+
+
+def lookupffn_workspace_bytes_bh_weighted(n_tokens: int, d: int, k: int, tau: int, block: int,
+                                          n_factors: int) -> int:
+    return lib().lookupffn_workspace_bytes_bh_weighted(n_tokens, d, k, tau, block, n_factors)
+
+
+def lookupffn_hash_bh_weighted(x: torch.Tensor, bmats: torch.Tensor, k: int, tau: int,
+                               codes: torch.Tensor | None = None, weights: torch.Tensor | None = None,
+                               workspace: torch.Tensor | None = None):
+    """(codes[n, k], weights[n, k]) of the BH hash with the gather weights of Sec. 4 of the paper."""
+    n, d = x.shape
+    block, m = _check_bmats(bmats, d, k, tau)
+    if codes is None:
+        codes = torch.empty((n, k), dtype=torch.int16, device=x.device)
+    if weights is None:
+        weights = torch.empty((n, k), dtype=torch.float32, device=x.device)
+    assert codes.dtype == torch.int16 and tuple(codes.shape) == (n, k)
+    assert weights.dtype == torch.float32 and tuple(weights.shape) == (n, k)
+    if n == 0:
+        return codes, weights
+    ws_ptr, ws_bytes = _ws(workspace)
+    with torch.cuda.device(x.device):
+        _check(lib().lookupffn_hash_bh_weighted(_dev(x, "x"), _dev(bmats, "bmats"), _dev(codes, "codes"),
+                                                _dev(weights, "weights"), n, d, k, tau, block, m, _dtype_code(x),
+                                                ws_ptr, ws_bytes, _stream(x)))
+    return codes, weights
+
+
+def lookupffn_forward_bh_weighted(x: torch.Tensor, bmats: torch.Tensor, tables: torch.Tensor,
+                                  y: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """Whole forward pass with the BH hash and the weighted gather: y[n, d_out]."""
+    return lookupffn_forward_bh(x, bmats, tables, y, workspace, _entry="lookupffn_forward_bh_weighted")
 
 
 def lookupffn_release_workspace() -> None:

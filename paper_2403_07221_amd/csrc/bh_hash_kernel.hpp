@@ -36,6 +36,8 @@ struct BhArgs {
     const float *apack;   // packed factors, see bh_pack_kernel
     uint16_t *codes;      // [n][k], or NULL when `packed` is written
     uint32_t *packed;     // packed codes of the staged gather, or NULL
+    float *weights;       // weighted variant: gather weights [n][k] (beside `codes`), or NULL
+    float *wpk;           // weighted variant: the same table-major, [k][n_pad] (beside `packed`), or NULL
     long long n_pad;
     long long n;
     int d, k, tau, n_factors, P;
@@ -111,9 +113,23 @@ __device__ __forceinline__ void tile_stages(float (&t)[4])
     }
 }
 
+// Reduction over the four lane groups (rows of 16 lanes) of two registers at once: returns a register
+// whose even rows hold op over all rows of x and whose odd rows hold op over all rows of y.
+template <bool MUL>
+__device__ __forceinline__ float reduce_rows(float x, float y)
+{
+    auto s = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(y), false, false);
+    // s[0] = (x.r0, y.r0, x.r2, y.r2), s[1] = (x.r1, y.r1, x.r3, y.r3)
+    const float c = MUL ? __uint_as_float(s[0]) * __uint_as_float(s[1]) : __uint_as_float(s[0]) + __uint_as_float(s[1]);
+    auto t = __builtin_amdgcn_permlane32_swap(__float_as_uint(c), __float_as_uint(c), false, false);
+    // t[0] = (c.r0, c.r1, c.r0, c.r1), t[1] = (c.r2, c.r3, c.r2, c.r3)
+    return MUL ? __uint_as_float(t[0]) * __uint_as_float(t[1]) : __uint_as_float(t[0]) + __uint_as_float(t[1]);
+}
+
 // LOG2N: d_pad = 2^LOG2N (64 .. 1024); TB = block / 16 (1, 2, 4); VEC4: rows are read four coordinates
-// at a time (d % 4 == 0, aligned rows), else one by one
-template <int LOG2N, int TB, bool VEC4>
+// at a time (d % 4 == 0, aligned rows), else one by one; WEIGHTED: also the gather weights of the
+// weighted variant (Sec. 4), for tau = 4, 8 or 16 (a table then lies inside one tile).
+template <int LOG2N, int TB, bool VEC4, bool WEIGHTED = false>
 __global__ __launch_bounds__(kBhThreads) void bh_hash_kernel(BhArgs a)
 {
     constexpr int N = 1 << LOG2N;
@@ -302,6 +318,62 @@ __global__ __launch_bounds__(kBhThreads) void bh_hash_kernel(BhArgs a)
                 for (int beta = 0; beta < NT; ++beta)
 #pragma unroll
                     for (int r = 0; r < 4; ++r) v[beta][r] = v[beta][r] * scale;
+            }
+
+            // ---- weighted variant: w_j = |z_j|_1 / prod_b (1 + exp(-2|z_jb|)) (Sec. 4) --------------
+            // A tile holds coordinate g + 4r of its 16 in (lane group g, register r): a table of
+            // tau = 8 is registers {0,1} or {2,3} over all four lane groups, tau = 16 the whole tile,
+            // tau = 4 one register.  Lane-local part first, then the lane groups are reduced.
+            if constexpr (WEIGHTED) {
+                const int tau = a.tau;
+#pragma unroll
+                for (int beta = 0; beta < NT; ++beta) {
+                    float az[4], ez[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        az[r] = __builtin_fabsf(v[beta][r]);
+                        ez[r] = 1.0f + __builtin_amdgcn_exp2f(az[r] * -2.885390082f);  // 1 + exp(-2|z|)
+                    }
+                    const long long c0 = (long long)p * N + 16 * beta;  // first coordinate of the tile
+                    // (sum, product) pairs X / Y whose reductions land in even / odd lane groups
+                    float sx, sy, qx, qy, sx2 = 0.f, sy2 = 0.f, qx2 = 1.f, qy2 = 1.f;
+                    if (tau == 16) {
+                        sx = sy = (az[0] + az[1]) + (az[2] + az[3]);
+                        qx = qy = (ez[0] * ez[1]) * (ez[2] * ez[3]);
+                    } else if (tau == 8) {
+                        sx = az[0] + az[1];
+                        qx = ez[0] * ez[1];
+                        sy = az[2] + az[3];
+                        qy = ez[2] * ez[3];
+                    } else {  // tau == 4: register r is table r of the tile; two reductions
+                        sx = az[0];
+                        qx = ez[0];
+                        sy = az[1];
+                        qy = ez[1];
+                        sx2 = az[2];
+                        qx2 = ez[2];
+                        sy2 = az[3];
+                        qy2 = ez[3];
+                    }
+                    const float s1 = reduce_rows<false>(sx, sy), q1 = reduce_rows<true>(qx, qy);
+                    // lane group 0 holds X's table, lane group 1 holds Y's
+                    long long j = tau == 16 ? c0 / 16 : tau == 8 ? c0 / 8 + (long long)g : c0 / 4 + (long long)g;
+                    const bool writer = t_ok && (tau == 16 ? g == 0 : g < 2);
+                    auto put = [&](long long jj, float sv, float qv) {
+                        if (writer && jj < a.k) {
+                            const float wv = __fdividef(sv, qv);
+                            if (a.wpk)
+                                a.wpk[wpk_index(jj, t, a.n_pad)] = wv;
+                            else
+                                a.weights[t * a.k + jj] = wv;
+                        }
+                    };
+                    put(j, s1, q1);
+                    if (tau == 4) {
+                        const float s2 = reduce_rows<false>(sx2, sy2), q2 = reduce_rows<true>(qx2, qy2);
+                        put(j + 2, s2, q2);
+                    }
+                }
             }
 
             // ---- a4: sign bits into the tokens' bit strings: word w covers tiles 2w, 2w+1 --------

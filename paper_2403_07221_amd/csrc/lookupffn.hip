@@ -542,11 +542,13 @@ int launch_gather_direct(const uint16_t *codes, const float *weights, const void
 
 // ---- BH{m} hash --------------------------------------------------------------------------------
 int check_bh(const void *x, const float *bmats, int64_t n, int d, int k, int tau, int block, int n_factors,
-             int x_dtype)
+             int x_dtype, bool weighted = false)
 {
     if (!x || !bmats) return LFFN_E_NULL;
     if (n < 0 || d < 1 || k < 1 || n_factors < 1) return LFFN_E_SIZE;
     if (tau < 1 || tau > 16) return LFFN_E_TAU;
+    // the weights are reduced inside one 16-coordinate tile: a table must not straddle tiles
+    if (weighted && tau != 4 && tau != 8 && tau != 16) return LFFN_E_UNSUPPORTED;
     if (!dtype_ok(x_dtype)) return LFFN_E_DTYPE;
     if (k > (1 << 20) || n > (int64_t(1) << 40) || n_factors > 64) return LFFN_E_SIZE;
     const int L = log2_pad(d);
@@ -568,38 +570,47 @@ int64_t bh_pack_bytes(int d, int k, int tau, int block, int n_factors)
     return round256(P * n_factors * (int64_t)N * block * 4);
 }
 
-template <int L, int TB, bool VEC4>
+template <int L, int TB, bool VEC4, bool WEIGHTED>
 int launch_bh_k(const BhArgs &a, dim3 grid, size_t lds, hipStream_t s)
 {
-    auto kern = bh_hash_kernel<L, TB, VEC4>;
+    auto kern = bh_hash_kernel<L, TB, VEC4, WEIGHTED>;
     int rc = allow_lds(reinterpret_cast<const void *>(kern), lds);
     if (rc != LFFN_OK) return rc;
     hipLaunchKernelGGL(kern, grid, dim3(kBhThreads), lds, s, a);
     return LFFN_OK;
 }
 
-template <int L>
-int launch_bh_t(const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s)
+template <int L, bool WEIGHTED>
+int launch_bh_w(const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s)
 {
     if (a.x_vec4) {
         switch (block) {
-            case 16: return launch_bh_k<L, 1, true>(a, grid, lds, s);
-            case 32: return launch_bh_k<L, 2, true>(a, grid, lds, s);
-            case 64: return launch_bh_k<L, 4, true>(a, grid, lds, s);
+            case 16: return launch_bh_k<L, 1, true, WEIGHTED>(a, grid, lds, s);
+            case 32: return launch_bh_k<L, 2, true, WEIGHTED>(a, grid, lds, s);
+            case 64: return launch_bh_k<L, 4, true, WEIGHTED>(a, grid, lds, s);
         }
     } else {
         switch (block) {
-            case 16: return launch_bh_k<L, 1, false>(a, grid, lds, s);
-            case 32: return launch_bh_k<L, 2, false>(a, grid, lds, s);
-            case 64: return launch_bh_k<L, 4, false>(a, grid, lds, s);
+            case 16: return launch_bh_k<L, 1, false, WEIGHTED>(a, grid, lds, s);
+            case 32: return launch_bh_k<L, 2, false, WEIGHTED>(a, grid, lds, s);
+            case 64: return launch_bh_k<L, 4, false, WEIGHTED>(a, grid, lds, s);
         }
     }
     return LFFN_E_UNSUPPORTED;
 }
 
-// Packs the factors into `apack` (bh_pack_bytes) and hashes; writes codes[n][k] or the packed layout.
+template <int L>
+int launch_bh_t(const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s)
+{
+    return (a.weights || a.wpk) ? launch_bh_w<L, true>(a, block, grid, lds, s)
+                                : launch_bh_w<L, false>(a, block, grid, lds, s);
+}
+
+// Packs the factors into `apack` (bh_pack_bytes) and hashes; writes codes[n][k] (and weights[n][k] if
+// given) or the packed layout (and wpk[k][n_pad] if given).
 int launch_hash_bh(const void *x, const float *bmats, float *apack, uint16_t *codes, uint32_t *packed, int64_t n,
-                   int d, int k, int tau, int block, int n_factors, int x_dtype, hipStream_t s)
+                   int d, int k, int tau, int block, int n_factors, int x_dtype, hipStream_t s,
+                   float *weights = nullptr, float *wpk = nullptr)
 {
     const int L = log2_pad(d);
     const int N = 1 << L;
@@ -608,6 +619,8 @@ int launch_hash_bh(const void *x, const float *bmats, float *apack, uint16_t *co
     a.apack = apack;
     a.codes = codes;
     a.packed = codes ? nullptr : packed;
+    a.weights = codes ? weights : nullptr;
+    a.wpk = codes ? nullptr : wpk;
     a.n_pad = packed_n_pad(n);
     a.n = n;
     a.d = d;
@@ -1025,6 +1038,78 @@ int lookupffn_forward_bh(const void *x, const float *bmats, const void *tables, 
     rc = launch_hash_bh(x, bmats, apack, codes, nullptr, n_tokens, d, k, tau, block, n_factors, x_dtype, s);
     if (rc != LFFN_OK) return rc;
     return launch_gather_direct(codes, nullptr, tables, y, n_tokens, k, tau, d_out, table_dtype, s);
+}
+
+int64_t lookupffn_workspace_bytes_bh_weighted(int64_t n_tokens, int d, int k, int tau, int block, int n_factors)
+{
+    if (d < 1 || d > 1024 || k < 1 || tau < 1 || tau > 16 || block < 1 || n_factors < 1 || n_factors > 64) return 0;
+    return bh_pack_bytes(d, k, tau, block, n_factors) + lookupffn_workspace_bytes_weighted(n_tokens, k);
+}
+
+int lookupffn_hash_bh_weighted(const void *x, const float *bmats, uint16_t *codes, float *weights, int64_t n_tokens,
+                               int d, int k, int tau, int block, int n_factors, int x_dtype, void *workspace,
+                               int64_t workspace_bytes, void *hip_stream)
+{
+    int rc = check_bh(x, bmats, n_tokens, d, k, tau, block, n_factors, x_dtype, true);
+    if (rc != LFFN_OK) return rc;
+    if (!codes || !weights) return LFFN_E_NULL;
+    if (!aligned(codes, 2) || !aligned(weights, 4)) return LFFN_E_ALIGN;
+    const int64_t need = bh_pack_bytes(d, k, tau, block, n_factors);
+    if (workspace) {
+        if (workspace_bytes < need) return LFFN_E_WORKSPACE;
+        if (!aligned(workspace, 256)) return LFFN_E_ALIGN;
+    }
+    if (n_tokens == 0) return LFFN_OK;
+    void *ws = workspace;
+    if (!ws) {
+        rc = own_workspace((size_t)need, &ws);
+        if (rc != LFFN_OK) return rc;
+    }
+    return launch_hash_bh(x, bmats, static_cast<float *>(ws), codes, nullptr, n_tokens, d, k, tau, block, n_factors,
+                          x_dtype, static_cast<hipStream_t>(hip_stream), weights, nullptr);
+}
+
+int lookupffn_forward_bh_weighted(const void *x, const float *bmats, const void *tables, float *y, int64_t n_tokens,
+                                  int d, int k, int tau, int d_out, int block, int n_factors, int x_dtype,
+                                  int table_dtype, void *workspace, int64_t workspace_bytes, void *hip_stream)
+{
+    int rc = check_bh(x, bmats, n_tokens, d, k, tau, block, n_factors, x_dtype, true);
+    if (rc != LFFN_OK) return rc;
+    const uint16_t *stand_in = reinterpret_cast<const uint16_t *>(uintptr_t(256));
+    rc = check_gather(stand_in, tables, y, n_tokens, k, tau, d_out, table_dtype);
+    if (rc != LFFN_OK) return rc;
+    const int64_t pack = bh_pack_bytes(d, k, tau, block, n_factors);
+    const int64_t need = pack + lookupffn_workspace_bytes_weighted(n_tokens, k);
+    if (workspace) {
+        if (workspace_bytes < need) return LFFN_E_WORKSPACE;
+        if (!aligned(workspace, 256)) return LFFN_E_ALIGN;
+    }
+    if (n_tokens == 0) return LFFN_OK;
+    void *ws = workspace;
+    if (!ws) {
+        rc = own_workspace((size_t)need, &ws);
+        if (rc != LFFN_OK) return rc;
+    }
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    float *apack = static_cast<float *>(ws);
+    char *scratch = static_cast<char *>(ws) + pack;
+    LdsPlan plan;
+    rc = plan_gather_lds(n_tokens, k, tau, d_out, table_dtype == LFFN_BF16, &plan, true);
+    if (rc != LFFN_OK) return rc;
+    if (plan.use && plan.shift == 7) {  // the BH hash writes codes scaled for 128-byte row pieces only
+        uint32_t *packed = reinterpret_cast<uint32_t *>(scratch);
+        float *wpk = reinterpret_cast<float *>(scratch + round256(packed_bytes(n_tokens, k)));
+        rc = launch_hash_bh(x, bmats, apack, nullptr, packed, n_tokens, d, k, tau, block, n_factors, x_dtype, s,
+                            nullptr, wpk);
+        if (rc != LFFN_OK) return rc;
+        return launch_gather_lds(plan, packed, wpk, tables, y, false, s);
+    }
+    uint16_t *codes = reinterpret_cast<uint16_t *>(scratch);
+    float *weights = reinterpret_cast<float *>(scratch + weighted_codes_bytes(n_tokens, k));
+    rc = launch_hash_bh(x, bmats, apack, codes, nullptr, n_tokens, d, k, tau, block, n_factors, x_dtype, s, weights,
+                        nullptr);
+    if (rc != LFFN_OK) return rc;
+    return launch_gather_direct(codes, weights, tables, y, n_tokens, k, tau, d_out, table_dtype, s);
 }
 
 int lookupffn_release_workspace(void)

@@ -125,6 +125,24 @@ def test_bh_argument_errors(L):
     assert fb(n=1000, ws=FAKE + 16, wsb=need) == -5
 
 
+def test_bh_weighted_argument_errors(L):
+    def hb(x=FAKE, bm=FAKE, codes=FAKE, w=FAKE, n=0, d=768, k=96, tau=8, block=64, m=4, dt=0, ws=None, wsb=0):
+        return L.lookupffn_hash_bh_weighted(x, bm, codes, w, n, d, k, tau, block, m, dt, ws, wsb, None)
+
+    def fb(x=FAKE, tables=FAKE, y=FAKE, n=0, d=768, tau=8, block=64, ws=None, wsb=0):
+        return L.lookupffn_forward_bh_weighted(x, FAKE, tables, y, n, d, 96, tau, 768, block, 4, 0, 0, ws, wsb, None)
+
+    assert hb() == 0 and fb() == 0 and hb(tau=4) == 0 and hb(tau=16, k=60) == 0
+    assert hb(w=None) == -1 and hb(codes=None) == -1 and hb(w=FAKE + 2) == -5 and hb(x=None) == -1
+    assert hb(tau=9) == -6 and hb(tau=2) == -6 and fb(tau=10) == -6 and hb(tau=17) == -3    # a table per tile part
+    assert hb(block=8) == -6 and hb(d=2000) == -6 and fb(tables=None) == -1
+    need = L.lookupffn_workspace_bytes_bh_weighted(1000, 768, 96, 8, 64, 4)
+    plain = L.lookupffn_workspace_bytes_bh(1000, 768, 96, 8, 64, 4)
+    assert need > plain + 1000 * 96 * 4 and need % 256 == 0
+    assert fb(n=1000, ws=FAKE, wsb=need - 1) == -7 and fb(n=1000, ws=FAKE + 16, wsb=need) == -5
+    assert hb(n=1000, ws=FAKE, wsb=1024) == -7
+
+
 def test_probe_argument_errors(L):
     def hp(x=FAKE, signs=FAKE, codes=FAKE, sh=FAKE, n=0, d=768, k=96, tau=8):
         return L.lookupffn_hash_probes(x, signs, codes, sh, n, d, k, tau, 3, 0, None)

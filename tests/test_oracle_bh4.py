@@ -145,3 +145,30 @@ def test_flop_model_matches_the_loop_counts():
         dp = 1 << (d - 1).bit_length()
         P = -(-h * tau // dp)
         assert cost.hash_flops(d, h, tau, "bh4", b) == P * 4 * (2 * dp * b + dp * int(np.log2(dp)))
+
+
+def test_bh_weighted_forward_from_dense_matrices_and_explicit_softmax():
+    """BH hash + weighted gather (Sec. 3.2 + Sec. 4) rebuilt from dense fp64 matrices, the sign matrix S
+    and the explicit soft-max over all 2^tau rows: y = sum_j (top * softmax_top) T_j[argmax]."""
+    n, d, k, tau, b, m, d_out = 25, 64, 8, 8, 16, 4, 12
+    w = synth.Workload("t", 9, n, d, m, k, tau, d_out)
+    bm = synth.make_bmats(21, w.n_proj, m, w.d_pad, b)
+    x = synth.make_x(4, n, d)
+    tables = synth.make_tables(5, k, 1 << tau, d_out)
+    y, codes, wts = oracle.bh_forward_weighted(x, bm, tables, return_all=True)
+    z64 = x.astype(np.float64) @ dense_R(bm[0], w.d_pad)
+    i = np.arange(1 << tau)
+    S = np.where((i[:, None] >> np.arange(tau)[None, :]) & 1, 1.0, -1.0)
+    want = np.zeros((n, d_out))
+    for j in range(k):
+        scores = z64[:, j * tau:(j + 1) * tau] @ S.T
+        g = np.argmax(scores, axis=1)
+        top = scores[np.arange(n), g]
+        wj = top * np.exp(top) / np.exp(scores).sum(axis=1)
+        sure = np.abs(z64[:, j * tau:(j + 1) * tau]).min(axis=1) > 1e-5
+        assert np.array_equal(codes[sure, j], g[sure])
+        np.testing.assert_allclose(wts[:, j], wj, rtol=2e-5)
+        want += wj[:, None] * tables[j, codes[:, j]].astype(np.float64)
+    assert np.max(np.abs(y - want)) <= 2e-5 * np.sqrt(np.mean(want ** 2))
+    # the weights do not move the codes
+    assert np.array_equal(codes, oracle.bh_hash_codes(x, bm, k, tau))
