@@ -322,58 +322,77 @@ __global__ __launch_bounds__(kBhThreads) void bh_hash_kernel(BhArgs a)
 
             // ---- weighted variant: w_j = |z_j|_1 / prod_b (1 + exp(-2|z_jb|)) (Sec. 4) --------------
             // A tile holds coordinate g + 4r of its 16 in (lane group g, register r): a table of
-            // tau = 8 is registers {0,1} or {2,3} over all four lane groups, tau = 16 the whole tile,
-            // tau = 4 one register.  Lane-local part first, then the lane groups are reduced.
+            // tau = 4 is one register over the four lane groups, tau = 8 two registers, tau = 16 the
+            // whole tile.  Four consecutive tables 4q .. 4q+3 of the projection are reduced together
+            // (two pair reductions, one per half of the lane groups) so that lane group g ends with
+            // the weight of table 4q + g: one store per lane for four tables.  All weights of a chunk
+            // of tables are computed first (straight-line code), then stored.
             if constexpr (WEIGHTED) {
-                const int tau = a.tau;
-#pragma unroll
-                for (int beta = 0; beta < NT; ++beta) {
-                    float az[4], ez[4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        az[r] = __builtin_fabsf(v[beta][r]);
-                        ez[r] = 1.0f + __builtin_amdgcn_exp2f(az[r] * -2.885390082f);  // 1 + exp(-2|z|)
-                    }
-                    const long long c0 = (long long)p * N + 16 * beta;  // first coordinate of the tile
-                    // (sum, product) pairs X / Y whose reductions land in even / odd lane groups
-                    float sx, sy, qx, qy, sx2 = 0.f, sy2 = 0.f, qx2 = 1.f, qy2 = 1.f;
-                    if (tau == 16) {
-                        sx = sy = (az[0] + az[1]) + (az[2] + az[3]);
-                        qx = qy = (ez[0] * ez[1]) * (ez[2] * ez[3]);
-                    } else if (tau == 8) {
-                        sx = az[0] + az[1];
-                        qx = ez[0] * ez[1];
-                        sy = az[2] + az[3];
-                        qy = ez[2] * ez[3];
-                    } else {  // tau == 4: register r is table r of the tile; two reductions
-                        sx = az[0];
-                        qx = ez[0];
-                        sy = az[1];
-                        qy = ez[1];
-                        sx2 = az[2];
-                        qx2 = ez[2];
-                        sy2 = az[3];
-                        qy2 = ez[3];
-                    }
-                    const float s1 = reduce_rows<false>(sx, sy), q1 = reduce_rows<true>(qx, qy);
-                    // lane group 0 holds X's table, lane group 1 holds Y's
-                    long long j = tau == 16 ? c0 / 16 : tau == 8 ? c0 / 8 + (long long)g : c0 / 4 + (long long)g;
-                    const bool writer = t_ok && (tau == 16 ? g == 0 : g < 2);
-                    auto put = [&](long long jj, float sv, float qv) {
-                        if (writer && jj < a.k) {
-                            const float wv = __fdividef(sv, qv);
-                            if (a.wpk)
-                                a.wpk[wpk_index(jj, t, a.n_pad)] = wv;
-                            else
-                                a.weights[t * a.k + jj] = wv;
-                        }
+                auto emit = [&](auto tau_c) {
+                    constexpr int TAU = decltype(tau_c)::value;
+                    constexpr int TPQ = TAU / 4;           // tiles per group of four tables (1, 2, 4)
+                    constexpr int NQ = NT / TPQ;           // groups of four tables in the projection
+                    constexpr int QC = NQ < 32 ? NQ : 32;  // groups computed before their stores
+                    const int jb = p * (N / TAU) + (int)g;  // this lane's table in group 0
+                    auto az = [&](int beta, int r) { return __builtin_fabsf(v[beta][r]); };
+                    auto ez = [&](int beta, int r) {        // 1 + exp(-2|z|)
+                        return 1.0f + __builtin_amdgcn_exp2f(__builtin_fabsf(v[beta][r]) * -2.885390082f);
                     };
-                    put(j, s1, q1);
-                    if (tau == 4) {
-                        const float s2 = reduce_rows<false>(sx2, sy2), q2 = reduce_rows<true>(qx2, qy2);
-                        put(j + 2, s2, q2);
+#pragma unroll
+                    for (int q0 = 0; q0 < NQ; q0 += QC) {
+                        float res[QC];
+#pragma unroll
+                        for (int qi = 0; qi < QC; ++qi) {
+                            const int q = q0 + qi;
+                            float sx[2], sy[2], px[2], py[2];  // [half]: tables 4q + 2*half (x) and + 1 (y)
+#pragma unroll
+                            for (int h = 0; h < 2; ++h) {
+                                if constexpr (TAU == 4) {
+                                    sx[h] = az(q, 2 * h);
+                                    px[h] = ez(q, 2 * h);
+                                    sy[h] = az(q, 2 * h + 1);
+                                    py[h] = ez(q, 2 * h + 1);
+                                } else if constexpr (TAU == 8) {
+                                    const int beta = 2 * q + h;
+                                    sx[h] = az(beta, 0) + az(beta, 1);
+                                    px[h] = ez(beta, 0) * ez(beta, 1);
+                                    sy[h] = az(beta, 2) + az(beta, 3);
+                                    py[h] = ez(beta, 2) * ez(beta, 3);
+                                } else {
+                                    const int bx = 4 * q + 2 * h, by = bx + 1;
+                                    sx[h] = (az(bx, 0) + az(bx, 1)) + (az(bx, 2) + az(bx, 3));
+                                    px[h] = (ez(bx, 0) * ez(bx, 1)) * (ez(bx, 2) * ez(bx, 3));
+                                    sy[h] = (az(by, 0) + az(by, 1)) + (az(by, 2) + az(by, 3));
+                                    py[h] = (ez(by, 0) * ez(by, 1)) * (ez(by, 2) * ez(by, 3));
+                                }
+                            }
+                            // even lane groups get x's total, odd ones y's; groups 0, 1 keep half 0
+                            const float s0 = reduce_rows<false>(sx[0], sy[0]), s1 = reduce_rows<false>(sx[1], sy[1]);
+                            const float p0 = reduce_rows<true>(px[0], py[0]), p1 = reduce_rows<true>(px[1], py[1]);
+                            res[qi] = (g < 2 ? s0 : s1) * __builtin_amdgcn_rcpf(g < 2 ? p0 : p1);
+                        }
+                        if (a.wpk) {
+                            // table-major: the 16 tokens of a lane group are consecutive
+                            float *wp = a.wpk + wpk_index(jb + 4 * q0, t, a.n_pad);
+#pragma unroll
+                            for (int qi = 0; qi < QC; ++qi) {
+                                if (t_ok && jb + 4 * (q0 + qi) < a.k) *wp = res[qi];
+                                wp += 4 * a.n_pad;
+                            }
+                        } else {
+                            float *wq = a.weights + t * a.k + jb + 4 * q0;
+#pragma unroll
+                            for (int qi = 0; qi < QC; ++qi)
+                                if (t_ok && jb + 4 * (q0 + qi) < a.k) wq[4 * qi] = res[qi];
+                        }
                     }
-                }
+                };
+                if (a.tau == 8)
+                    emit(std::integral_constant<int, 8>{});
+                else if (a.tau == 16)
+                    emit(std::integral_constant<int, 16>{});
+                else
+                    emit(std::integral_constant<int, 4>{});
             }
 
             // ---- a4: sign bits into the tokens' bit strings: word w covers tiles 2w, 2w+1 --------
