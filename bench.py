@@ -48,6 +48,8 @@ def parse_args():
                     help="tuning: 1 = always the direct gather kernel, 2 = the LDS-staged one whenever the shape allows")
     ap.add_argument("--slice-lanes", type=int, default=0, choices=[0, 4, 8],
                     help="tuning: column-slice width of the staged gather in 16-byte lanes (0 = library default)")
+    ap.add_argument("--token-slots", type=int, default=0, choices=[0, 4, 8, 13, 16],
+                    help="tuning: most token slots per lane of the staged gather (0 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle timing")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
@@ -108,6 +110,7 @@ def main():
     torch.cuda.set_device(0)
     B.lib()
     B.lookupffn_set_option("slice_lanes", args.slice_lanes)
+    B.lookupffn_set_option("token_slots", args.token_slots)
     B.lookupffn_set_option("gather_path", args.gather_path)
     w = synth.CONFIGS[args.config]
     bh = args.hash == "bh4"

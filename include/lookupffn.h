@@ -202,6 +202,7 @@ int lookupffn_timing_read(int which, double *total_ms, int64_t *launches);
  *   "slice_lanes"      4 / 8          staged kernel: 64-byte column slices (4 lanes per token) where
  *                                     they exist (fp32 tables, tau 8 .. 10) / 128-byte ones (tau 7 .. 9);
  *                                     default: 128 bytes up to tau = 8, 64 bytes from tau = 9 on
+ *   "token_slots"      4,8,13,16      staged kernel: at most this many tokens per lane group and chunk
  *   "hash_path"        1              always the generic hash kernel (default: the two-layout
  *                                     kernel when d_pad = 1024 and n_rounds <= 4)
  *   "hash_blocks"      1..65536       grid cap of the d_pad = 1024 hash kernel

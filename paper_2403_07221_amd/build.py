@@ -12,29 +12,59 @@ SRC = PKG / "csrc" / "lookupffn.hip"
 LIB = PKG / "liblookupffn.so"
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
+N_PARTS = 12         # csrc/lookupffn.hip compiles as parts 0 .. 11 (-DLFFN_PART=i), linked together
+SLOW_FIRST = [10, 11, 8, 9, 6, 5]   # the wide BH kernels take the longest: start them first
+OBJ_DIR = PKG / "_build"
+
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-ffp-contract=off",                                        # butterflies must stay add/sub
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",  # no packed-fp32 code generation
-    "-Wall", "-Wno-unused-command-line-argument",
+    "-Wall", "-Wno-unused-command-line-argument", "-Wno-unused-function",
     f"-I{ROOT / 'include'}", f"-I{PKG / 'csrc'}",
 ]
+_NOISE = "is not a recognized feature for this target"
 
 
-def build_library(verbose: bool = False) -> Path:
-    """Compile csrc/lookupffn.hip -> liblookupffn.so (always recompiles)."""
+def _quiet(stderr: str) -> str:
+    return "\n".join(l for l in stderr.splitlines() if _NOISE not in l)
+
+
+def build_library(verbose: bool = False, jobs: int | None = None) -> Path:
+    """Compile the parts of csrc/lookupffn.hip side by side and link liblookupffn.so (always recompiles)."""
+    jobs = jobs or max(1, min(os.cpu_count() or 1, int(os.environ.get("MAX_JOBS", "16"))))
+    OBJ_DIR.mkdir(exist_ok=True)
+    objs = [OBJ_DIR / f"lookupffn_part{i}.{os.getpid()}.o" for i in range(N_PARTS)]
+    cmds = [[HIPCC, *FLAGS, f"-DLFFN_PART={i}", "-c", "-o", str(objs[i]), str(SRC)] for i in range(N_PARTS)]
     tmp = LIB.with_suffix(f".so.tmp{os.getpid()}")
-    cmd = [HIPCC, *FLAGS, "-o", str(tmp), str(SRC)]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    noise = "is not a recognized feature for this target"
-    err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)
-    if r.returncode != 0:
-        raise RuntimeError(f"hipcc failed:\n{err}")
-    if verbose and err.strip():
-        print(err, file=sys.stderr)
-    os.replace(tmp, LIB)
+    try:
+        order = SLOW_FIRST + [i for i in range(N_PARTS) if i not in SLOW_FIRST]
+        todo, running, errors = [(i, cmds[i]) for i in order], [], []
+        while todo or running:
+            while todo and len(running) < jobs:
+                i, cmd = todo.pop(0)
+                if verbose:
+                    print(" ".join(cmd), flush=True)
+                running.append((i, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True)))
+            i, proc = running.pop(0)
+            _, err = proc.communicate()
+            if proc.returncode != 0:
+                errors.append(f"part {i}:\n{_quiet(err)}")
+            elif verbose and _quiet(err).strip():
+                print(_quiet(err), file=sys.stderr)
+        if errors:
+            raise RuntimeError("hipcc failed:\n" + "\n".join(errors))
+        link = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", str(tmp), *map(str, objs)]
+        if verbose:
+            print(" ".join(link), flush=True)
+        r = subprocess.run(link, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"link failed:\n{_quiet(r.stderr)}")
+        os.replace(tmp, LIB)
+    finally:
+        for o in objs:
+            o.unlink(missing_ok=True)
+        tmp.unlink(missing_ok=True)
     return LIB
 
 

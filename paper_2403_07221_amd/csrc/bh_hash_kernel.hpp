@@ -70,6 +70,7 @@ __host__ inline size_t bh_lds_bytes(int P, int N)
 //                   j = 16*o + (l%16)/4 + 4*((l%16)%4)
 // i.e. exactly the A-operand (row m = l%16, k-slot l/16) of the MFMA that adds input tile ii's
 // k-step kk into output tile o.
+#if !defined(LFFN_PART) || LFFN_PART == 0  // a plain function: defined by part 0 only of a build in parts
 __global__ __launch_bounds__(256) void bh_pack_kernel(const float *bmats, float *apack, int N, int b, long long total)
 {
     const int tb = b / 16, nt = N / 16;
@@ -88,6 +89,7 @@ __global__ __launch_bounds__(256) void bh_pack_kernel(const float *bmats, float 
         apack[idx] = bmats[((pf * (N / b) + blk) * b + (c - blk * b)) * b + (j - blk * b)];
     }
 }
+#endif
 
 typedef float mfma_f4 __attribute__((ext_vector_type(4)));
 

@@ -622,6 +622,8 @@ __global__ __launch_bounds__(kHashThreads) __attribute__((amdgpu_waves_per_eu(4,
     }
 }
 
+// The re-pack kernels are plain functions: when the library is built in parts only part 0 defines them.
+#if !defined(LFFN_PART) || LFFN_PART == 0
 // ABI weights [n][k] -> table-major [k][n_pad] (token padding left as it is: those slots are never stored)
 __global__ __launch_bounds__(256) void repack_weights_kernel(const float *weights, float *wpk, long long n,
                                                              long long n_pad, int k)
@@ -664,5 +666,6 @@ __global__ __launch_bounds__(256) void repack_codes_kernel(const uint16_t *codes
         packed[idx] = w;
     }
 }
+#endif
 
 }  // namespace lffn

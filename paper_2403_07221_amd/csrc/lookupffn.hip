@@ -17,26 +17,306 @@
 #include "gather_lds_kernel.hpp"
 #include "hash_kernel.hpp"
 
+// Build parts.  This file compiles whole (LFFN_PART undefined) or as parts that are linked together, so
+// that the kernel families compile side by side: part 0 holds the C ABI, the host logic and the hash and
+// re-pack kernels; parts 1 .. 11 hold one family of kernel launchers each (declared just below).  No
+// kernel is instantiated in two parts.
+#ifdef LFFN_PART
+#define LFFN_HAS(p) (LFFN_PART == (p))
+#else
+#define LFFN_HAS(p) 1
+#endif
+
+namespace lffn_host {
+using namespace lffn;
+int hip_fail(hipError_t e, const char *what);  // part 0
+int allow_lds(const void *kern, size_t lds);   // part 0
+// part 1: the direct gather kernel
+int gather_direct_part(bool bf16, int lpt, const GatherArgs &a, bool probes, dim3 grid, hipStream_t s);
+// parts 2, 3: the LDS-staged gather kernel (plain sum; weighted and multi-probe)
+int gather_lds_plain_part(bool bf16, int tok, const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds,
+                          hipStream_t s);
+int gather_lds_weighted_part(int tok, const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s);
+int gather_lds_probes_part(int tok, const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s);
+// parts 4 .. 11: the BH hash kernel.  Plain: d_pad = 64 .. 256, 512, 1024; weighted: d_pad = 64 .. 256, then
+// 512 and 1024 each split by the way the rows are read (four coordinates at a time or one by one): the
+// wide weighted kernels are the slowest to compile by far
+int bh_plain_lo_part(int L, const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s);
+int bh_plain_512_part(const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s);
+int bh_plain_1024_part(const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s);
+int bh_weighted_lo_part(int L, const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s);
+int bh_weighted_512_vec4_part(const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s);
+int bh_weighted_512_scalar_part(const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s);
+int bh_weighted_1024_vec4_part(const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s);
+int bh_weighted_1024_scalar_part(const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s);
+}  // namespace lffn_host
+
 namespace {
 
 using namespace lffn;
+using lffn_host::allow_lds;
+using lffn_host::hip_fail;
 
-constexpr int kVersion = 100;  // 0.1.0
-constexpr int kMaxLog2N = 12;  // d_pad <= 4096
-
-thread_local std::string g_hip_error;
-const char *g_last_gather = "";  // name of the gather kernel the most recent launch used
-
-int hip_fail(hipError_t e, const char *what)
-{
-    g_hip_error = std::string(what) + ": " + hipGetErrorString(e);
-    return LFFN_E_HIP;
-}
 #define LFFN_HIP(call)                                       \
     do {                                                     \
         hipError_t e_ = (call);                              \
         if (e_ != hipSuccess) return hip_fail(e_, #call);    \
     } while (0)
+
+#if LFFN_HAS(0)
+constexpr int kVersion = 100;  // 0.1.0
+constexpr int kMaxLog2N = 12;  // d_pad <= 4096
+thread_local std::string g_hip_error;
+const char *g_last_gather = "";  // name of the gather kernel the most recent launch used
+#endif
+
+// ---------------------------------------------------------------- kernel launchers (templates: every part may use them)
+template <bool BF16, int LPT>
+void launch_gather_t(const GatherArgs &a, bool probes, dim3 grid, hipStream_t s)
+{
+    if (probes)
+        hipLaunchKernelGGL((gather_kernel<BF16, LPT, 2>), grid, dim3(kGatherThreads), 0, s, a);
+    else if (a.weights)
+        hipLaunchKernelGGL((gather_kernel<BF16, LPT, 1>), grid, dim3(kGatherThreads), 0, s, a);
+    else
+        hipLaunchKernelGGL((gather_kernel<BF16, LPT, 0>), grid, dim3(kGatherThreads), 0, s, a);
+}
+
+template <bool BF16>
+int launch_gather_lpt(int lpt, const GatherArgs &a, bool probes, dim3 grid, hipStream_t s)
+{
+    switch (lpt) {
+        case 1: launch_gather_t<BF16, 1>(a, probes, grid, s); break;
+        case 2: launch_gather_t<BF16, 2>(a, probes, grid, s); break;
+        case 4: launch_gather_t<BF16, 4>(a, probes, grid, s); break;
+        case 8: launch_gather_t<BF16, 8>(a, probes, grid, s); break;
+        case 16: launch_gather_t<BF16, 16>(a, probes, grid, s); break;
+        case 32: launch_gather_t<BF16, 32>(a, probes, grid, s); break;
+        case 64: launch_gather_t<BF16, 64>(a, probes, grid, s); break;
+        default: return LFFN_E_UNSUPPORTED;
+    }
+    return LFFN_OK;
+}
+
+template <bool BF16, int TOK, int FR, bool WEIGHTED, int SW, bool PROBES = false>
+int launch_gather_lds_fr(const GatherLdsArgs &a, dim3 grid, size_t lds, hipStream_t s)
+{
+    auto kern = gather_lds_kernel<BF16, TOK, FR, WEIGHTED, SW, PROBES>;
+    int rc = allow_lds(reinterpret_cast<const void *>(kern), lds);
+    if (rc != LFFN_OK) return rc;
+    hipLaunchKernelGGL(kern, grid, dim3(kLdsThreads), lds, s, a);
+    return LFFN_OK;
+}
+
+// fr = 16 KB copy rounds per table slice, sw = lanes per token (both fixed by the plan)
+template <bool BF16, int TOK, bool WEIGHTED = false>
+int launch_gather_lds_t(const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s)
+{
+    if constexpr (TOK <= 13) {
+        if (sw == 8)
+            return fr == 4   ? launch_gather_lds_fr<BF16, TOK, 4, WEIGHTED, 8>(a, grid, lds, s)
+                   : fr == 2 ? launch_gather_lds_fr<BF16, TOK, 2, WEIGHTED, 8>(a, grid, lds, s)
+                             : launch_gather_lds_fr<BF16, TOK, 1, WEIGHTED, 8>(a, grid, lds, s);
+    }
+    if (sw != 4) return LFFN_E_UNSUPPORTED;
+    if constexpr (!BF16 && (TOK == 8 || TOK == 13 || TOK == 16)) {  // 64-byte slices: built for fp32 tables
+        return fr == 4   ? launch_gather_lds_fr<false, TOK, 4, WEIGHTED, 4>(a, grid, lds, s)
+               : fr == 2 ? launch_gather_lds_fr<false, TOK, 2, WEIGHTED, 4>(a, grid, lds, s)
+                         : launch_gather_lds_fr<false, TOK, 1, WEIGHTED, 4>(a, grid, lds, s);
+    }
+    return LFFN_E_UNSUPPORTED;
+}
+
+// multi-probe form: fp32 tables; 128-byte slices for tau 7, 8, 64-byte slices for tau 9, 10
+template <int TOK>
+int launch_gather_lds_probes(const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s)
+{
+    if constexpr (TOK <= 13 && TOK != 12) {
+        if (sw == 8 && fr == 2) return launch_gather_lds_fr<false, TOK, 2, true, 8, true>(a, grid, lds, s);
+        if (sw == 8 && fr == 1) return launch_gather_lds_fr<false, TOK, 1, true, 8, true>(a, grid, lds, s);
+    }
+    if constexpr (TOK == 8 || TOK == 13 || TOK == 16) {
+        if (sw == 4 && fr == 4) return launch_gather_lds_fr<false, TOK, 4, true, 4, true>(a, grid, lds, s);
+        if (sw == 4 && fr == 2) return launch_gather_lds_fr<false, TOK, 2, true, 4, true>(a, grid, lds, s);
+    }
+    return LFFN_E_UNSUPPORTED;
+}
+
+template <int L, int TB, bool VEC4, bool WEIGHTED>
+int launch_bh_k(const BhArgs &a, dim3 grid, size_t lds, hipStream_t s)
+{
+    auto kern = bh_hash_kernel<L, TB, VEC4, WEIGHTED>;
+    int rc = allow_lds(reinterpret_cast<const void *>(kern), lds);
+    if (rc != LFFN_OK) return rc;
+    hipLaunchKernelGGL(kern, grid, dim3(kBhThreads), lds, s, a);
+    return LFFN_OK;
+}
+
+template <int L, bool VEC4, bool WEIGHTED>
+int launch_bh_v(const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s)
+{
+    switch (block) {
+        case 16: return launch_bh_k<L, 1, VEC4, WEIGHTED>(a, grid, lds, s);
+        case 32: return launch_bh_k<L, 2, VEC4, WEIGHTED>(a, grid, lds, s);
+        case 64: return launch_bh_k<L, 4, VEC4, WEIGHTED>(a, grid, lds, s);
+    }
+    return LFFN_E_UNSUPPORTED;
+}
+
+template <int L, bool WEIGHTED>
+int launch_bh_w(const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s)
+{
+    return a.x_vec4 ? launch_bh_v<L, true, WEIGHTED>(a, block, grid, lds, s)
+                    : launch_bh_v<L, false, WEIGHTED>(a, block, grid, lds, s);
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------- the parts' launch functions
+namespace lffn_host {
+
+#if LFFN_HAS(1)
+int gather_direct_part(bool bf16, int lpt, const GatherArgs &a, bool probes, dim3 grid, hipStream_t s)
+{
+    return bf16 ? launch_gather_lpt<true>(lpt, a, probes, grid, s) : launch_gather_lpt<false>(lpt, a, probes, grid, s);
+}
+#endif
+
+#if LFFN_HAS(2)
+int gather_lds_plain_part(bool bf16, int tok, const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds,
+                          hipStream_t s)
+{
+    if (bf16) {
+        if (tok <= 4) return launch_gather_lds_t<true, 4>(a, fr, sw, grid, lds, s);
+        if (tok <= 6) return launch_gather_lds_t<true, 6>(a, fr, sw, grid, lds, s);
+        if (tok <= 8) return launch_gather_lds_t<true, 8>(a, fr, sw, grid, lds, s);
+        return LFFN_E_UNSUPPORTED;
+    }
+    if (tok <= 4) return launch_gather_lds_t<false, 4>(a, fr, sw, grid, lds, s);
+    if (tok <= 8) return launch_gather_lds_t<false, 8>(a, fr, sw, grid, lds, s);
+    if (tok <= 12) return launch_gather_lds_t<false, 12>(a, fr, sw, grid, lds, s);
+    if (tok <= 13) return launch_gather_lds_t<false, 13>(a, fr, sw, grid, lds, s);
+    if (tok <= 16 && sw == 4) return launch_gather_lds_t<false, 16>(a, fr, sw, grid, lds, s);
+    return LFFN_E_UNSUPPORTED;
+}
+#endif
+
+#if LFFN_HAS(3)
+int gather_lds_weighted_part(int tok, const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s)
+{
+    if (tok <= 4) return launch_gather_lds_t<false, 4, true>(a, fr, sw, grid, lds, s);
+    if (tok <= 8) return launch_gather_lds_t<false, 8, true>(a, fr, sw, grid, lds, s);
+    if (tok <= 12) return launch_gather_lds_t<false, 12, true>(a, fr, sw, grid, lds, s);
+    if (tok <= 13) return launch_gather_lds_t<false, 13, true>(a, fr, sw, grid, lds, s);
+    if (tok <= 16 && sw == 4) return launch_gather_lds_t<false, 16, true>(a, fr, sw, grid, lds, s);
+    return LFFN_E_UNSUPPORTED;
+}
+
+int gather_lds_probes_part(int tok, const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s)
+{
+    if (tok <= 4) return launch_gather_lds_probes<4>(a, fr, sw, grid, lds, s);
+    if (tok <= 8) return launch_gather_lds_probes<8>(a, fr, sw, grid, lds, s);
+    if (tok <= 13) return launch_gather_lds_probes<13>(a, fr, sw, grid, lds, s);
+    if (tok <= 16) return launch_gather_lds_probes<16>(a, fr, sw, grid, lds, s);
+    return LFFN_E_UNSUPPORTED;
+}
+#endif
+
+#if LFFN_HAS(4)
+int bh_plain_lo_part(int L, const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s)
+{
+    switch (L) {
+        case 6: return launch_bh_w<6, false>(a, block, grid, lds, s);
+        case 7: return launch_bh_w<7, false>(a, block, grid, lds, s);
+        case 8: return launch_bh_w<8, false>(a, block, grid, lds, s);
+    }
+    return LFFN_E_UNSUPPORTED;
+}
+#endif
+
+#if LFFN_HAS(5)
+int bh_plain_512_part(const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s)
+{
+    return launch_bh_w<9, false>(a, block, grid, lds, s);
+}
+#endif
+
+#if LFFN_HAS(6)
+int bh_plain_1024_part(const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s)
+{
+    return launch_bh_w<10, false>(a, block, grid, lds, s);
+}
+#endif
+
+#if LFFN_HAS(7)
+int bh_weighted_lo_part(int L, const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s)
+{
+    switch (L) {
+        case 6: return launch_bh_w<6, true>(a, block, grid, lds, s);
+        case 7: return launch_bh_w<7, true>(a, block, grid, lds, s);
+        case 8: return launch_bh_w<8, true>(a, block, grid, lds, s);
+    }
+    return LFFN_E_UNSUPPORTED;
+}
+#endif
+
+#if LFFN_HAS(8)
+int bh_weighted_512_vec4_part(const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s)
+{
+    return launch_bh_v<9, true, true>(a, block, grid, lds, s);
+}
+#endif
+
+#if LFFN_HAS(9)
+int bh_weighted_512_scalar_part(const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s)
+{
+    return launch_bh_v<9, false, true>(a, block, grid, lds, s);
+}
+#endif
+
+#if LFFN_HAS(10)
+int bh_weighted_1024_vec4_part(const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s)
+{
+    return launch_bh_v<10, true, true>(a, block, grid, lds, s);
+}
+#endif
+
+#if LFFN_HAS(11)
+int bh_weighted_1024_scalar_part(const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s)
+{
+    return launch_bh_v<10, false, true>(a, block, grid, lds, s);
+}
+#endif
+
+#if LFFN_HAS(0)
+int hip_fail(hipError_t e, const char *what)
+{
+    g_hip_error = std::string(what) + ": " + hipGetErrorString(e);
+    return LFFN_E_HIP;
+}
+
+// kernels that use more than 64 KB of dynamic LDS must be told so, once per device and kernel
+int allow_lds(const void *kern, size_t lds)
+{
+    static std::mutex mu;
+    static std::map<std::pair<int, const void *>, size_t> configured;  // (device, kernel) -> LDS bytes set up
+    int dev = 0;
+    LFFN_HIP(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lk(mu);
+    size_t &have = configured[std::make_pair(dev, kern)];
+    if (have < lds) {
+        LFFN_HIP(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        have = lds;
+    }
+    return LFFN_OK;
+}
+#endif
+
+}  // namespace lffn_host
+
+#if LFFN_HAS(0)  // ================ everything below: host logic and the C ABI ================
+namespace {
+
 
 int log2_pad(int d)
 {
@@ -56,6 +336,7 @@ struct Options {
     int hash_path = 0;        // 0 = choose, 1 = generic kernel only
     int hash_blocks = 0;      // 0 = default grid cap of the d_pad = 1024 hash kernel
     int slice_lanes = 0;      // 0 = choose, 4 = 64-byte column slices in the staged gather where possible
+    int token_slots = 0;      // 0 = choose, else the most token slots per lane of the staged gather
 } g_opt;
 
 // ---------------------------------------------------------------- timing
@@ -248,52 +529,8 @@ int launch_hash(const void *x, const int8_t *signs, uint16_t *codes, uint32_t *p
     return LFFN_OK;
 }
 
-template <bool BF16, int LPT>
-void launch_gather_t(const GatherArgs &a, bool probes, dim3 grid, hipStream_t s)
-{
-    if (probes)
-        hipLaunchKernelGGL((gather_kernel<BF16, LPT, 2>), grid, dim3(kGatherThreads), 0, s, a);
-    else if (a.weights)
-        hipLaunchKernelGGL((gather_kernel<BF16, LPT, 1>), grid, dim3(kGatherThreads), 0, s, a);
-    else
-        hipLaunchKernelGGL((gather_kernel<BF16, LPT, 0>), grid, dim3(kGatherThreads), 0, s, a);
-}
-
-template <bool BF16>
-int launch_gather_lpt(int lpt, const GatherArgs &a, bool probes, dim3 grid, hipStream_t s)
-{
-    switch (lpt) {
-        case 1: launch_gather_t<BF16, 1>(a, probes, grid, s); break;
-        case 2: launch_gather_t<BF16, 2>(a, probes, grid, s); break;
-        case 4: launch_gather_t<BF16, 4>(a, probes, grid, s); break;
-        case 8: launch_gather_t<BF16, 8>(a, probes, grid, s); break;
-        case 16: launch_gather_t<BF16, 16>(a, probes, grid, s); break;
-        case 32: launch_gather_t<BF16, 32>(a, probes, grid, s); break;
-        case 64: launch_gather_t<BF16, 64>(a, probes, grid, s); break;
-        default: return LFFN_E_UNSUPPORTED;
-    }
-    return LFFN_OK;
-}
-
 int gcd(int a, int b) { return b ? gcd(b, a % b) : a; }
 int64_t round256(int64_t b) { return (b + 255) & ~int64_t(255); }
-
-// ---- LDS-staged gather -------------------------------------------------------------------
-// kernels that use more than 64 KB of dynamic LDS must be told so, once per device and kernel
-int allow_lds(const void *kern, size_t lds)
-{
-    static std::mutex mu;
-    static std::map<std::pair<int, const void *>, size_t> configured;  // (device, kernel) -> LDS bytes set up
-    int dev = 0;
-    LFFN_HIP(hipGetDevice(&dev));
-    std::lock_guard<std::mutex> lk(mu);
-    size_t &have = configured[std::make_pair(dev, kern)];
-    if (have < lds) {
-        LFFN_HIP(hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        have = lds;
-    }
-    return LFFN_OK;
-}
 
 constexpr int kLdsMinBytes = 84 * 1024;  // more than half of the 160 KB LDS: one workgroup per CU
 
@@ -312,50 +549,6 @@ int device_cus(int *cus)
     }
     *cus = it->second;
     return LFFN_OK;
-}
-
-template <bool BF16, int TOK, int FR, bool WEIGHTED, int SW, bool PROBES = false>
-int launch_gather_lds_fr(const GatherLdsArgs &a, dim3 grid, size_t lds, hipStream_t s)
-{
-    auto kern = gather_lds_kernel<BF16, TOK, FR, WEIGHTED, SW, PROBES>;
-    int rc = allow_lds(reinterpret_cast<const void *>(kern), lds);
-    if (rc != LFFN_OK) return rc;
-    hipLaunchKernelGGL(kern, grid, dim3(kLdsThreads), lds, s, a);
-    return LFFN_OK;
-}
-
-// fr = 16 KB copy rounds per table slice, sw = lanes per token (both fixed by the plan)
-template <bool BF16, int TOK, bool WEIGHTED = false>
-int launch_gather_lds_t(const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s)
-{
-    if constexpr (TOK <= 13) {
-        if (sw == 8)
-            return fr == 4   ? launch_gather_lds_fr<BF16, TOK, 4, WEIGHTED, 8>(a, grid, lds, s)
-                   : fr == 2 ? launch_gather_lds_fr<BF16, TOK, 2, WEIGHTED, 8>(a, grid, lds, s)
-                             : launch_gather_lds_fr<BF16, TOK, 1, WEIGHTED, 8>(a, grid, lds, s);
-    }
-    if (sw != 4) return LFFN_E_UNSUPPORTED;
-    if constexpr (!BF16 && (TOK == 8 || TOK == 13 || TOK == 16)) {  // 64-byte slices: built for fp32 tables
-        return fr == 4   ? launch_gather_lds_fr<false, TOK, 4, WEIGHTED, 4>(a, grid, lds, s)
-               : fr == 2 ? launch_gather_lds_fr<false, TOK, 2, WEIGHTED, 4>(a, grid, lds, s)
-                         : launch_gather_lds_fr<false, TOK, 1, WEIGHTED, 4>(a, grid, lds, s);
-    }
-    return LFFN_E_UNSUPPORTED;
-}
-
-// multi-probe form: fp32 tables; 128-byte slices for tau 7, 8, 64-byte slices for tau 9, 10
-template <int TOK>
-int launch_gather_lds_probes(const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s)
-{
-    if constexpr (TOK <= 13 && TOK != 12) {
-        if (sw == 8 && fr == 2) return launch_gather_lds_fr<false, TOK, 2, true, 8, true>(a, grid, lds, s);
-        if (sw == 8 && fr == 1) return launch_gather_lds_fr<false, TOK, 1, true, 8, true>(a, grid, lds, s);
-    }
-    if constexpr (TOK == 8 || TOK == 13 || TOK == 16) {
-        if (sw == 4 && fr == 4) return launch_gather_lds_fr<false, TOK, 4, true, 4, true>(a, grid, lds, s);
-        if (sw == 4 && fr == 2) return launch_gather_lds_fr<false, TOK, 2, true, 4, true>(a, grid, lds, s);
-    }
-    return LFFN_E_UNSUPPORTED;
 }
 
 // Largest number of tokens a workgroup gets in one piece, mirroring the kernel's split.
@@ -420,7 +613,11 @@ int plan_gather_lds(int64_t n, int k, int tau, int d_out, bool bf16, LdsPlan *p,
     a.n_units = a.n_slices * a.token_splits;
     a.blocks_per_xcd = cus / kXcds;
     const int64_t tpb = lds_tokens_per_block(n, a.n_units, a.token_splits, a.blocks_per_xcd);
-    const int tok_max = bf16 ? 8 : sw == 4 ? 16 : 13;
+    int tok_max = bf16 ? 8 : sw == 4 ? 16 : 13;
+    // the multi-probe form holds a share per probe beside the accumulators: 13 slots spill in its
+    // hot loop, 8 measured faster up to tau = 9 (tau = 10 has 16 copy rounds per table to amortise)
+    if (probes && tau <= 9) tok_max = 8;
+    if (g_opt.token_slots && g_opt.token_slots < tok_max) tok_max = g_opt.token_slots;
     const int64_t nchunks = (tpb + (int64_t)groups * tok_max - 1) / ((int64_t)groups * tok_max);
     const int64_t chunk = (tpb + nchunks - 1) / nchunks;
     // Staging pays only when a chunk re-uses each staged row a few times.  With bf16 rows the
@@ -451,28 +648,12 @@ int launch_gather_lds(const LdsPlan &p, const uint32_t *packed, const float *wpk
     const dim3 grid(p.grid);
     int rc = LFFN_E_UNSUPPORTED;
     TimedLaunch tl(1, s);
-    if (probes) {
-        if (p.tok <= 4) rc = launch_gather_lds_probes<4>(a, p.fr, p.sw, grid, p.lds, s);
-        else if (p.tok <= 8) rc = launch_gather_lds_probes<8>(a, p.fr, p.sw, grid, p.lds, s);
-        else if (p.tok <= 13) rc = launch_gather_lds_probes<13>(a, p.fr, p.sw, grid, p.lds, s);
-        else if (p.tok <= 16) rc = launch_gather_lds_probes<16>(a, p.fr, p.sw, grid, p.lds, s);
-    } else if (wpk) {
-        if (p.tok <= 4) rc = launch_gather_lds_t<false, 4, true>(a, p.fr, p.sw, grid, p.lds, s);
-        else if (p.tok <= 8) rc = launch_gather_lds_t<false, 8, true>(a, p.fr, p.sw, grid, p.lds, s);
-        else if (p.tok <= 12) rc = launch_gather_lds_t<false, 12, true>(a, p.fr, p.sw, grid, p.lds, s);
-        else if (p.tok <= 13) rc = launch_gather_lds_t<false, 13, true>(a, p.fr, p.sw, grid, p.lds, s);
-        else if (p.tok <= 16 && p.sw == 4) rc = launch_gather_lds_t<false, 16, true>(a, p.fr, p.sw, grid, p.lds, s);
-    } else if (bf16) {
-        if (p.tok <= 4) rc = launch_gather_lds_t<true, 4>(a, p.fr, p.sw, grid, p.lds, s);
-        else if (p.tok <= 6) rc = launch_gather_lds_t<true, 6>(a, p.fr, p.sw, grid, p.lds, s);
-        else if (p.tok <= 8) rc = launch_gather_lds_t<true, 8>(a, p.fr, p.sw, grid, p.lds, s);
-    } else {
-        if (p.tok <= 4) rc = launch_gather_lds_t<false, 4>(a, p.fr, p.sw, grid, p.lds, s);
-        else if (p.tok <= 8) rc = launch_gather_lds_t<false, 8>(a, p.fr, p.sw, grid, p.lds, s);
-        else if (p.tok <= 12) rc = launch_gather_lds_t<false, 12>(a, p.fr, p.sw, grid, p.lds, s);
-        else if (p.tok <= 13) rc = launch_gather_lds_t<false, 13>(a, p.fr, p.sw, grid, p.lds, s);
-        else if (p.tok <= 16 && p.sw == 4) rc = launch_gather_lds_t<false, 16>(a, p.fr, p.sw, grid, p.lds, s);
-    }
+    if (probes)
+        rc = lffn_host::gather_lds_probes_part(p.tok, a, p.fr, p.sw, grid, p.lds, s);
+    else if (wpk)
+        rc = lffn_host::gather_lds_weighted_part(p.tok, a, p.fr, p.sw, grid, p.lds, s);
+    else
+        rc = lffn_host::gather_lds_plain_part(bf16, p.tok, a, p.fr, p.sw, grid, p.lds, s);
     if (rc != LFFN_OK) return rc;
     LFFN_HIP(hipGetLastError());
     tl.done();
@@ -532,7 +713,7 @@ int launch_gather_direct(const uint16_t *codes, const float *weights, const void
     if (blocks > 0x7FFFFFFFLL) return LFFN_E_SIZE;
     const dim3 grid((unsigned)blocks);
     TimedLaunch tl(1, s);
-    int rc = bf16 ? launch_gather_lpt<true>(lpt, a, probes, grid, s) : launch_gather_lpt<false>(lpt, a, probes, grid, s);
+    int rc = lffn_host::gather_direct_part(bf16, lpt, a, probes, grid, s);
     if (rc != LFFN_OK) return rc;
     LFFN_HIP(hipGetLastError());
     tl.done();
@@ -570,42 +751,6 @@ int64_t bh_pack_bytes(int d, int k, int tau, int block, int n_factors)
     return round256(P * n_factors * (int64_t)N * block * 4);
 }
 
-template <int L, int TB, bool VEC4, bool WEIGHTED>
-int launch_bh_k(const BhArgs &a, dim3 grid, size_t lds, hipStream_t s)
-{
-    auto kern = bh_hash_kernel<L, TB, VEC4, WEIGHTED>;
-    int rc = allow_lds(reinterpret_cast<const void *>(kern), lds);
-    if (rc != LFFN_OK) return rc;
-    hipLaunchKernelGGL(kern, grid, dim3(kBhThreads), lds, s, a);
-    return LFFN_OK;
-}
-
-template <int L, bool WEIGHTED>
-int launch_bh_w(const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s)
-{
-    if (a.x_vec4) {
-        switch (block) {
-            case 16: return launch_bh_k<L, 1, true, WEIGHTED>(a, grid, lds, s);
-            case 32: return launch_bh_k<L, 2, true, WEIGHTED>(a, grid, lds, s);
-            case 64: return launch_bh_k<L, 4, true, WEIGHTED>(a, grid, lds, s);
-        }
-    } else {
-        switch (block) {
-            case 16: return launch_bh_k<L, 1, false, WEIGHTED>(a, grid, lds, s);
-            case 32: return launch_bh_k<L, 2, false, WEIGHTED>(a, grid, lds, s);
-            case 64: return launch_bh_k<L, 4, false, WEIGHTED>(a, grid, lds, s);
-        }
-    }
-    return LFFN_E_UNSUPPORTED;
-}
-
-template <int L>
-int launch_bh_t(const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s)
-{
-    return (a.weights || a.wpk) ? launch_bh_w<L, true>(a, block, grid, lds, s)
-                                : launch_bh_w<L, false>(a, block, grid, lds, s);
-}
-
 // Packs the factors into `apack` (bh_pack_bytes) and hashes; writes codes[n][k] (and weights[n][k] if
 // given) or the packed layout (and wpk[k][n_pad] if given).
 int launch_hash_bh(const void *x, const float *bmats, float *apack, uint16_t *codes, uint32_t *packed, int64_t n,
@@ -641,15 +786,20 @@ int launch_hash_bh(const void *x, const float *bmats, float *apack, uint16_t *co
     if (blocks > 4096) blocks = 4096;
     const dim3 grid((unsigned)blocks);
     const size_t lds = bh_lds_bytes(a.P, N);
+    const bool weighted = a.weights || a.wpk;
     int rc;
-    switch (L) {
-        case 6: rc = launch_bh_t<6>(a, block, grid, lds, s); break;
-        case 7: rc = launch_bh_t<7>(a, block, grid, lds, s); break;
-        case 8: rc = launch_bh_t<8>(a, block, grid, lds, s); break;
-        case 9: rc = launch_bh_t<9>(a, block, grid, lds, s); break;
-        case 10: rc = launch_bh_t<10>(a, block, grid, lds, s); break;
-        default: rc = LFFN_E_UNSUPPORTED;
-    }
+    if (L <= 8)
+        rc = weighted ? lffn_host::bh_weighted_lo_part(L, a, block, grid, lds, s)
+                      : lffn_host::bh_plain_lo_part(L, a, block, grid, lds, s);
+    else if (!weighted)
+        rc = L == 9 ? lffn_host::bh_plain_512_part(a, block, grid, lds, s)
+                    : lffn_host::bh_plain_1024_part(a, block, grid, lds, s);
+    else if (L == 9)
+        rc = a.x_vec4 ? lffn_host::bh_weighted_512_vec4_part(a, block, grid, lds, s)
+                      : lffn_host::bh_weighted_512_scalar_part(a, block, grid, lds, s);
+    else
+        rc = a.x_vec4 ? lffn_host::bh_weighted_1024_vec4_part(a, block, grid, lds, s)
+                      : lffn_host::bh_weighted_1024_scalar_part(a, block, grid, lds, s);
     if (rc != LFFN_OK) return rc;
     LFFN_HIP(hipGetLastError());
     tl.done();
@@ -1187,6 +1337,11 @@ int lookupffn_set_option(const char *key, int value)
         g_opt.slice_lanes = value;
         return LFFN_OK;
     }
+    if (!std::strcmp(key, "token_slots")) {
+        if (value != 0 && value != 4 && value != 8 && value != 13 && value != 16) return LFFN_E_SIZE;
+        g_opt.token_slots = value;
+        return LFFN_OK;
+    }
     if (!std::strcmp(key, "gather_path")) {
         if (value < 0 || value > 2) return LFFN_E_SIZE;
         g_opt.gather_path = value;
@@ -1223,3 +1378,5 @@ const char *lookupffn_last_gather_kernel(void) { return g_last_gather; }
 int lookupffn_version(void) { return kVersion; }
 
 }  // extern "C"
+
+#endif  // LFFN_HAS(0)

@@ -173,6 +173,8 @@ def test_options(L):
     assert L.lookupffn_set_option(b"hash_blocks", -1) == -2 and L.lookupffn_set_option(b"hash_blocks", 0) == 0
     assert L.lookupffn_set_option(b"slice_lanes", 4) == 0 and L.lookupffn_set_option(b"slice_lanes", 3) == -2
     assert L.lookupffn_set_option(b"slice_lanes", 0) == 0
+    assert L.lookupffn_set_option(b"token_slots", 8) == 0 and L.lookupffn_set_option(b"token_slots", 5) == -2
+    assert L.lookupffn_set_option(b"token_slots", 0) == 0
     assert L.lookupffn_set_option(b"no_such_key", 1) == -2
     assert L.lookupffn_set_option(None, 1) == -1
 
