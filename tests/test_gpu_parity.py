@@ -399,6 +399,48 @@ def test_forward_config5_stacked_layers():
     assert np.array_equal(g.cpu().numpy(), h)
 
 
+def test_forward_with_more_than_4_gib_of_activations():
+    """1.5 M tokens: x and y are 4.8 GB each, so token offsets pass 2^32 bytes in every kernel.  The batch
+    is a 65536-token block repeated 24 times on the device: every repetition of y must equal the first,
+    and sampled rows (the last ones included) must match the oracle."""
+    w = synth.C2
+    reps, block = 24, 65536
+    n = reps * block
+    print(f"forward with {n} tokens ({n * w.d_out * 4 / 2**30:.2f} GiB of y)", flush=True)
+    x, signs, tables = synth.make_layer(w, n_tokens=block)
+    xd = B.to_device(x).repeat(reps, 1)
+    sd, td = B.to_device(signs), B.to_device(tables)
+    assert xd.shape == (n, w.d) and xd.numel() * 4 > 2**32
+    idx = np.unique(np.concatenate([np.arange(0, n, 9973), np.arange(n - 300, n)]))
+    want = oracle.forward(x[idx % block], signs, tables, acc64=False)
+    bm = synth.make_bmats(77, w.n_proj, 4, w.d_pad, 16)
+    bd = torch.from_numpy(bm).cuda()
+    results = {}
+    try:
+        for name, path, fwd, par in (("staged", 2, B.lookupffn_forward, sd), ("direct", 1, B.lookupffn_forward, sd),
+                                     ("weighted staged", 2, B.lookupffn_forward_weighted, sd),
+                                     ("multi-probe staged", 2, B.lookupffn_forward_probes, sd),
+                                     ("bh staged", 2, B.lookupffn_forward_bh, bd),
+                                     ("bh weighted direct", 1, B.lookupffn_forward_bh_weighted, bd)):
+            print(f"  {name}", flush=True)
+            B.lookupffn_set_option("gather_path", path)
+            y = torch.full((n, w.d_out), float("nan"), dtype=torch.float32, device="cuda")
+            fwd(xd, par, td, y=y)
+            torch.cuda.synchronize()
+            yb = y.view(reps, block, w.d_out)
+            assert bool((yb == yb[0]).all()), f"{name}: a repetition of the block differs from the first"
+            results[name] = y[torch.from_numpy(idx).cuda()].cpu().numpy()
+            del y, yb
+    finally:
+        B.lookupffn_set_option("gather_path", 0)
+    assert np.array_equal(results["staged"], want) and np.array_equal(results["direct"], want)
+    xs = x[idx % block]
+    assert rel_err(results["weighted staged"], oracle.forward_weighted(xs, signs, tables)) <= TOL_F32
+    assert rel_err(results["multi-probe staged"], oracle.forward_probes(xs, signs, tables)) <= TOL_F32
+    assert np.array_equal(results["bh staged"], oracle.bh_forward(xs, bm, tables, acc64=False))
+    assert rel_err(results["bh weighted direct"], oracle.bh_forward_weighted(xs, bm, tables)) <= TOL_F32
+
+
 def test_forward_is_deterministic_and_stream_ordered():
     print("forward determinism / side stream", flush=True)
     w = synth.C2.with_tokens(2000)
