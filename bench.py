@@ -224,9 +224,9 @@ def main():
                        "effective_GBps": path_bytes / (ms_per_step * 1e-3) / 1e9},
     }
     if B.lookupffn_last_gather_kernel() == "gather_lds_kernel":
-        # What bounds the staged kernel is the LDS, not HBM: every (token, table[, probe]) reads its row
-        # from the staged copy.  Peak: 256 CUs x 128 bytes per clock x 2.4 GHz.
-        lds_peak = 256 * 128 * 2.4  # GB/s
+        # The staged kernel reads its rows from LDS, not HBM: every (token, table[, probe]) reads its row
+        # piece from the staged copy.  Peak: 256 CUs x 256 bytes per clock (16-byte reads) x 2.4 GHz.
+        lds_peak = 256 * 256 * 2.4  # GB/s
         lds_bytes = w.k * w.d_out * tb * w.n_tokens * ((w.tau + 1) if args.probes else 1)
         out["lds_roofline"] = {"kernel": "gather_lds_kernel", "bound": "lds", "achieved": lds_bytes / (gather_avg_ms * 1e-3) / 1e9,
                                "peak": lds_peak, "unit": "GB/s", "frac": lds_bytes / (gather_avg_ms * 1e-3) / 1e9 / lds_peak,
