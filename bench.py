@@ -255,7 +255,23 @@ def main():
             e1.record()
             torch.cuda.synchronize()
             cold_ms += e0.elapsed_time(e1)
+        # the same chain captured once in a HIP graph (the entry points only launch kernels when given a
+        # workspace and y) and replayed: one submission per pass instead of 2 x layers launches
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        torch.cuda.synchronize()
+        for _ in range(5):
+            graph.replay()
+        torch.cuda.synchronize()
+        n_graph = 200
+        g0 = time.perf_counter()
+        for _ in range(n_graph):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_us = (time.perf_counter() - g0) / n_graph * 1e6
         out["latency"] = {"layers": w.n_layers, "warm_us_per_pass": ms_per_step * 1e3,
+                          "graph_us_per_pass": graph_us, "graph_us_per_layer": graph_us / w.n_layers,
                           "warm_us_per_layer": ms_per_step * 1e3 / w.n_layers,
                           "cold_us_per_pass": cold_ms / n_cold * 1e3,
                           "cold_us_per_layer": cold_ms / n_cold * 1e3 / w.n_layers}
