@@ -180,8 +180,18 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
 
     for (uint32_t ui = u_first; ui < u_end; ui += u_step) {
         const uint32_t unit = ui * kXcds + xcd;
-        const uint32_t slice = unit % (uint32_t)a.n_slices;
+        uint32_t slice = unit % (uint32_t)a.n_slices;
         const uint32_t split = unit / (uint32_t)a.n_slices;
+        if constexpr (SW == 4) {
+            // A 64-byte slice is half of a 128-byte cache line.  Dealt round-robin, the two halves of
+            // every line would go to different XCDs and each L2 would fetch the whole line.  With the
+            // slice count a multiple of 16 (then slice % 8 is the XCD) the XCD's units 2i and 2i + 1,
+            // which run side by side, take the two halves of the same lines instead.
+            if ((uint32_t)a.n_slices % 16u == 0u) {
+                const uint32_t i = slice / kXcds;
+                slice = ((i >> 1) * kXcds + slice % kXcds) * 2u + (i & 1u);
+            }
+        }
         const uint32_t s0 = split_at(n, (uint32_t)a.token_splits, split);
         const uint32_t s1 = split_at(n, (uint32_t)a.token_splits, split + 1);
         const uint32_t r0 = s0 + split_at(s1 - s0, parts, part), r1 = s0 + split_at(s1 - s0, parts, part + 1);
