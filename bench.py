@@ -14,6 +14,8 @@ from __future__ import annotations
 
 import argparse
 import json
+
+import numpy as np
 import os
 import sys
 import time
@@ -50,6 +52,9 @@ def parse_args():
                     help="tuning: column-slice width of the staged gather in 16-byte lanes (0 = library default)")
     ap.add_argument("--token-slots", type=int, default=0, choices=[0, 4, 8, 13, 16],
                     help="tuning: most token slots per lane of the staged gather (0 = library default)")
+    ap.add_argument("--zipf", type=float, default=0.0,
+                    help="also time lookupffn_gather alone on codes with Zipf(s)-skewed buckets (reported beside, "
+                         "never instead of, the hashed codes of the rotated Gaussian input)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle timing")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
@@ -275,6 +280,27 @@ def main():
                           "warm_us_per_layer": ms_per_step * 1e3 / w.n_layers,
                           "cold_us_per_pass": cold_ms / n_cold * 1e3,
                           "cold_us_per_layer": cold_ms / n_cold * 1e3 / w.n_layers}
+    if args.zipf > 0 and w.n_layers == 1:
+        def time_gather(codes_np):
+            cd = torch.from_numpy(codes_np.view(np.int16)).cuda()
+            yz = torch.empty((w.n_tokens, w.d_out), dtype=torch.float32, device="cuda")
+            for _ in range(5):
+                B.lookupffn_gather(cd, td, y=yz)
+            torch.cuda.synchronize()
+            B.lookupffn_timing_reset()
+            B.lookupffn_timing_enable(2)
+            for _ in range(args.steps):
+                B.lookupffn_gather(cd, td, y=yz)
+            torch.cuda.synchronize()
+            ms, cnt = B.lookupffn_timing_read(1)
+            B.lookupffn_timing_enable(0)
+            B.lookupffn_timing_reset()
+            return ms / cnt
+        uni = np.random.default_rng(1).integers(0, w.rows, size=(w.n_tokens, w.k), dtype=np.uint16)
+        zc = synth.make_zipf_codes(synth.seed_for(w.seed_index or w.index, 0, 4), w.n_tokens, w.k, w.tau, args.zipf)
+        out["skewed_gather"] = {"zipf_s": args.zipf, "kernel": None, "uniform_codes_avg_kernel_ms": time_gather(uni),
+                                "zipf_codes_avg_kernel_ms": time_gather(zc)}
+        out["skewed_gather"]["kernel"] = B.lookupffn_last_gather_kernel()
     if args.copy_calibration_mib > 0:
         src = torch.ones(args.copy_calibration_mib << 18, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)

@@ -77,7 +77,7 @@ CONFIGS.update({6: P6, 7: P7, 8: P8})
 
 
 def seed_for(config: int, layer: int, what: int) -> int:
-    """what: 0 = sign diagonals, 1 = x, 2 = tables, 3 = block-diagonal factors of the BH4 hash."""
+    """what: 0 = sign diagonals, 1 = x, 2 = tables, 3 = block-diagonal factors of the BH4 hash, 4 = skewed codes."""
     return SEED_BASE + 1000 * config + 10 * layer + what
 
 
@@ -120,6 +120,21 @@ def make_tables(seed: int, k: int, rows: int, d_out: int, dtype: str = "f32",
     t = _rng(seed).standard_normal((k, rows, d_out), dtype=np.float32)
     t *= np.float32(sigma)
     return to_bf16_bits(t) if dtype == "bf16" else t
+
+
+def make_zipf_codes(seed: int, n: int, k: int, tau: int, s: float = 1.0) -> np.ndarray:
+    """codes[n, k] uint16 with skewed buckets: in every table the rows are ranked by a random permutation
+    and drawn with probability proportional to 1 / rank^s (trained hashes fill their buckets unevenly,
+    Sec. 3.1; the rotation of Gaussian inputs fills them evenly)."""
+    rng = _rng(seed)
+    rows = 1 << tau
+    p = 1.0 / np.arange(1, rows + 1, dtype=np.float64) ** s
+    p /= p.sum()
+    codes = np.empty((n, k), dtype=np.uint16)
+    for j in range(k):
+        perm = rng.permutation(rows).astype(np.uint16)
+        codes[:, j] = perm[rng.choice(rows, size=n, p=p)]
+    return codes
 
 
 def make_layer(w: Workload, layer: int = 0, n_tokens: int | None = None, with_x: bool = True,
