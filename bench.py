@@ -233,8 +233,14 @@ def main():
         # piece from the staged copy.  Peak: 256 CUs x 256 bytes per clock (16-byte reads) x 2.4 GHz.
         lds_peak = 256 * 256 * 2.4  # GB/s
         lds_bytes = w.k * w.d_out * tb * w.n_tokens * ((w.tau + 1) if args.probes else 1)
-        out["lds_roofline"] = {"kernel": "gather_lds_kernel", "bound": "lds", "achieved": lds_bytes / (gather_avg_ms * 1e-3) / 1e9,
-                               "peak": lds_peak, "unit": "GB/s", "frac": lds_bytes / (gather_avg_ms * 1e-3) / 1e9 / lds_peak,
+        # measured with a stand-alone read loop (16 waves per CU, 16-byte reads, row offsets in registers):
+        # contiguous 147.7 TB/s; 8 lanes per random 128-byte row 82.8 TB/s; 4 lanes per random 64-byte row 68.5 TB/s
+        wide = w.tau <= 8 if args.slice_lanes == 0 else args.slice_lanes == 8
+        ceiling = 82800.0 if wide else 68500.0
+        lds_rate = lds_bytes / (gather_avg_ms * 1e-3) / 1e9
+        out["lds_roofline"] = {"kernel": "gather_lds_kernel", "bound": "lds", "achieved": lds_rate,
+                               "peak": lds_peak, "unit": "GB/s", "frac": lds_rate / lds_peak,
+                               "random_row_ceiling": ceiling, "frac_of_random_row_ceiling": lds_rate / ceiling,
                                "lds_read_bytes_per_launch": lds_bytes}
     if bh:
         # the block-diagonal products are the path's one dense contraction: priced against the fp32
