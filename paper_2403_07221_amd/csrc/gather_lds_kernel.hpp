@@ -244,10 +244,10 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
                 cr[m] = *reinterpret_cast<const uint32_t *>(base + reg_offset(m));
             };
             // LDS row offset of slot i in table u of the stage: the low / high half of its code word.
-            // The high halves are shifted down before the broadcast, so the two tables' broadcasts
-            // are distinct values and neither is kept alive across the stage.
+            // Both halves are split off the word before the broadcast (once per register and stage),
+            // so a use is one DPP add and the two tables' broadcasts are distinct values.
             auto row_offset = [&](const uint32_t(&cr)[NCR], int u, int i) -> uint32_t {
-                return u ? quad_bcast(cr[i >> 2] >> 16, i & 3) : (quad_bcast(cr[i >> 2], i & 3) & 0xFFFFu);
+                return u ? quad_bcast(cr[i >> 2] >> 16, i & 3) : quad_bcast(cr[i >> 2] & 0xFFFFu, i & 3);
             };
             // weights: table u of stage s, register m
             constexpr int NWL = TPS * WQ;
