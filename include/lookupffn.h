@@ -60,7 +60,8 @@ typedef enum {
     LFFN_E_DTYPE = -4,        /* dtype is neither LFFN_F32 nor LFFN_BF16 */
     LFFN_E_ALIGN = -5,        /* tables or y not 16-byte aligned, x/codes not element aligned,
                                  or d_out not a multiple of 4 (fp32 tables) / 8 (bf16 tables) */
-    LFFN_E_UNSUPPORTED = -6,  /* d_pad above 4096 */
+    LFFN_E_UNSUPPORTED = -6,  /* a shape the kernels are not built for: d_pad above 4096; the BH
+                                 entry points state their own limits */
     LFFN_E_WORKSPACE = -7,    /* caller workspace smaller than lookupffn_workspace_bytes() */
     LFFN_E_HIP = -8           /* a HIP call failed; see lookupffn_last_hip_error() */
 } lffn_status;
