@@ -18,7 +18,7 @@ _lib = None
 F32, BF16 = 0, 1
 EXPORTS = (
     "lookupffn_hash", "lookupffn_gather", "lookupffn_forward", "lookupffn_workspace_bytes",
-    "lookupffn_release_workspace", "lookupffn_timing_enable", "lookupffn_timing_reset",
+    "lookupffn_release_workspace", "lookupffn_workspace_bytes_tables", "lookupffn_timing_enable", "lookupffn_timing_reset",
     "lookupffn_timing_read", "lookupffn_set_option", "lookupffn_strerror",
     "lookupffn_last_hip_error", "lookupffn_last_gather_kernel", "lookupffn_version",
     "lookupffn_hash_weighted", "lookupffn_gather_weighted", "lookupffn_forward_weighted",
@@ -51,6 +51,8 @@ def lib() -> ctypes.CDLL:
         L.lookupffn_forward.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, ci, ci, vp, i64, vp]
         L.lookupffn_workspace_bytes.argtypes = [i64, ci]
         L.lookupffn_workspace_bytes.restype = i64
+        L.lookupffn_workspace_bytes_tables.argtypes = [ci, ci, ci, ci]
+        L.lookupffn_workspace_bytes_tables.restype = i64
         L.lookupffn_hash_weighted.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, vp]
         L.lookupffn_gather_weighted.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, vp]
         L.lookupffn_forward_weighted.argtypes = L.lookupffn_forward.argtypes
@@ -246,6 +248,12 @@ def lookupffn_forward_probes(x: torch.Tensor, signs: torch.Tensor, tables: torch
                              y: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
     """Whole multi-probe forward pass y[n, d_out] (Sec. 3.1, eq. "partial_softmax")."""
     return lookupffn_forward(x, signs, tables, y, workspace, _entry="lookupffn_forward_probes")
+
+
+def lookupffn_workspace_bytes_tables(k: int, tau: int, d_out: int, table_dtype) -> int:
+    """Extra scratch bytes that let a forward pass with bf16 tables take the LDS-staged gather."""
+    code = table_dtype if isinstance(table_dtype, int) else (BF16 if table_dtype in ("bf16", torch.bfloat16) else F32)
+    return lib().lookupffn_workspace_bytes_tables(k, tau, d_out, code)
 
 
 def lookupffn_workspace_bytes(n_tokens: int, k: int) -> int:

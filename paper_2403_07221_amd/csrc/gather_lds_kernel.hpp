@@ -30,6 +30,11 @@
 // token-contiguous (wpk[j][n_pad]) and are quad-shared like the code words; each row is
 // accumulated with one fused multiply-add per element.
 //
+// bf16 tables: the staged copy is fp32.  Widening inside this kernel (per stage and workgroup, through
+// registers and LDS writes) measured no faster than the direct kernel, so for large batches the host
+// first widens the whole table set once per call into scratch memory (widen_tables_kernel below, exact:
+// a bf16 is the upper half of an fp32) and runs this kernel on the copy.
+//
 // Work distribution is static and XCD-aware: slice-units are dealt to the
 // eight XCDs round-robin (block b runs on XCD b % 8), and the workgroups of
 // one XCD split its units' token ranges evenly, so every CU gets one chunk of
@@ -133,7 +138,7 @@ __device__ __forceinline__ uint32_t quad_bcast(uint32_t v, int q)
 // PROBES (with WEIGHTED): the multi-probe form (Sec. 3.1, eq. "partial_softmax"): every stage is swept
 // 1 + tau times, sweep p reading the rows code ^ flip(p) with the shares of probe p
 // (wpk[(j * (1 + tau) + p) * n_pad + t]); the staged slice is copied once per stage.
-template <bool BF16, int TOK, int FR, bool WEIGHTED, int SW = 8, bool PROBES = false>
+template <int TOK, int FR, bool WEIGHTED, int SW = 8, bool PROBES = false>
 __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a)
 {
     static_assert(!PROBES || WEIGHTED, "the multi-probe form carries weights");
@@ -262,7 +267,7 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
             // load while the current stage is consumed
             uint32_t crA[NCR], crB[NCR];
             float wA[TPS][WQ], wB[TPS][WQ];
-            Acc<BF16> acc[TOK];
+            Acc<false> acc[TOK];
 #pragma unroll
             for (int i = 0; i < TOK; ++i) acc[i].zero();
 
@@ -508,17 +513,26 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
                 for (int i = 0; i < TOK; ++i) {
                     const uint32_t t = slot_token(i);
                     if (t >= c1) continue;
-                    float *yp = a.y + (size_t)t * a.d_out + (size_t)vec * Acc<BF16>::W;
+                    float *yp = a.y + (size_t)t * a.d_out + (size_t)vec * 4u;
                     f4 o0 = {acc[i].f[0], acc[i].f[1], acc[i].f[2], acc[i].f[3]};
                     __builtin_nontemporal_store(o0, reinterpret_cast<f4 *>(yp));
-                    if constexpr (BF16) {
-                        f4 o1 = {acc[i].f[4], acc[i].f[5], acc[i].f[6], acc[i].f[7]};
-                        __builtin_nontemporal_store(o1, reinterpret_cast<f4 *>(yp) + 1);
-                    }
                 }
             }
         }
     }
 }
+
+#if !defined(LFFN_PART) || LFFN_PART == 0  // a plain function: defined by part 0 only of a build in parts
+// bf16 -> fp32, 8 elements per thread and step (n8 = element count / 8; both buffers 16-byte aligned)
+__global__ __launch_bounds__(256) void widen_tables_kernel(const uint4 *src, uint4 *dst, long long n8)
+{
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n8;
+         i += (long long)gridDim.x * blockDim.x) {
+        const uint4 w = src[i];
+        dst[2 * i] = make_uint4(w.x << 16, w.x & 0xFFFF0000u, w.y << 16, w.y & 0xFFFF0000u);
+        dst[2 * i + 1] = make_uint4(w.z << 16, w.z & 0xFFFF0000u, w.w << 16, w.w & 0xFFFF0000u);
+    }
+}
+#endif
 
 }  // namespace lffn

@@ -34,8 +34,7 @@ int allow_lds(const void *kern, size_t lds);   // part 0
 // part 1: the direct gather kernel
 int gather_direct_part(bool bf16, int lpt, const GatherArgs &a, bool probes, dim3 grid, hipStream_t s);
 // parts 2, 3: the LDS-staged gather kernel (plain sum; weighted and multi-probe)
-int gather_lds_plain_part(bool bf16, int tok, const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds,
-                          hipStream_t s);
+int gather_lds_plain_part(int tok, const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s);
 int gather_lds_weighted_part(int tok, const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s);
 int gather_lds_probes_part(int tok, const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s);
 // parts 4 .. 11: the BH hash kernel.  Plain: d_pad = 64 .. 256, 512, 1024; weighted: d_pad = 64 .. 256, then
@@ -98,10 +97,10 @@ int launch_gather_lpt(int lpt, const GatherArgs &a, bool probes, dim3 grid, hipS
     return LFFN_OK;
 }
 
-template <bool BF16, int TOK, int FR, bool WEIGHTED, int SW, bool PROBES = false>
+template <int TOK, int FR, bool WEIGHTED, int SW, bool PROBES = false>
 int launch_gather_lds_fr(const GatherLdsArgs &a, dim3 grid, size_t lds, hipStream_t s)
 {
-    auto kern = gather_lds_kernel<BF16, TOK, FR, WEIGHTED, SW, PROBES>;
+    auto kern = gather_lds_kernel<TOK, FR, WEIGHTED, SW, PROBES>;
     int rc = allow_lds(reinterpret_cast<const void *>(kern), lds);
     if (rc != LFFN_OK) return rc;
     hipLaunchKernelGGL(kern, grid, dim3(kLdsThreads), lds, s, a);
@@ -109,20 +108,20 @@ int launch_gather_lds_fr(const GatherLdsArgs &a, dim3 grid, size_t lds, hipStrea
 }
 
 // fr = 16 KB copy rounds per table slice, sw = lanes per token (both fixed by the plan)
-template <bool BF16, int TOK, bool WEIGHTED = false>
+template <int TOK, bool WEIGHTED = false>
 int launch_gather_lds_t(const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s)
 {
     if constexpr (TOK <= 13) {
         if (sw == 8)
-            return fr == 4   ? launch_gather_lds_fr<BF16, TOK, 4, WEIGHTED, 8>(a, grid, lds, s)
-                   : fr == 2 ? launch_gather_lds_fr<BF16, TOK, 2, WEIGHTED, 8>(a, grid, lds, s)
-                             : launch_gather_lds_fr<BF16, TOK, 1, WEIGHTED, 8>(a, grid, lds, s);
+            return fr == 4   ? launch_gather_lds_fr<TOK, 4, WEIGHTED, 8>(a, grid, lds, s)
+                   : fr == 2 ? launch_gather_lds_fr<TOK, 2, WEIGHTED, 8>(a, grid, lds, s)
+                             : launch_gather_lds_fr<TOK, 1, WEIGHTED, 8>(a, grid, lds, s);
     }
     if (sw != 4) return LFFN_E_UNSUPPORTED;
-    if constexpr (!BF16 && (TOK == 8 || TOK == 13 || TOK == 16)) {  // 64-byte slices: built for fp32 tables
-        return fr == 4   ? launch_gather_lds_fr<false, TOK, 4, WEIGHTED, 4>(a, grid, lds, s)
-               : fr == 2 ? launch_gather_lds_fr<false, TOK, 2, WEIGHTED, 4>(a, grid, lds, s)
-                         : launch_gather_lds_fr<false, TOK, 1, WEIGHTED, 4>(a, grid, lds, s);
+    if constexpr (TOK == 8 || TOK == 13 || TOK == 16) {  // 64-byte slices
+        return fr == 4   ? launch_gather_lds_fr<TOK, 4, WEIGHTED, 4>(a, grid, lds, s)
+               : fr == 2 ? launch_gather_lds_fr<TOK, 2, WEIGHTED, 4>(a, grid, lds, s)
+                         : launch_gather_lds_fr<TOK, 1, WEIGHTED, 4>(a, grid, lds, s);
     }
     return LFFN_E_UNSUPPORTED;
 }
@@ -132,12 +131,12 @@ template <int TOK>
 int launch_gather_lds_probes(const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s)
 {
     if constexpr (TOK <= 13 && TOK != 12) {
-        if (sw == 8 && fr == 2) return launch_gather_lds_fr<false, TOK, 2, true, 8, true>(a, grid, lds, s);
-        if (sw == 8 && fr == 1) return launch_gather_lds_fr<false, TOK, 1, true, 8, true>(a, grid, lds, s);
+        if (sw == 8 && fr == 2) return launch_gather_lds_fr<TOK, 2, true, 8, true>(a, grid, lds, s);
+        if (sw == 8 && fr == 1) return launch_gather_lds_fr<TOK, 1, true, 8, true>(a, grid, lds, s);
     }
     if constexpr (TOK == 8 || TOK == 13 || TOK == 16) {
-        if (sw == 4 && fr == 4) return launch_gather_lds_fr<false, TOK, 4, true, 4, true>(a, grid, lds, s);
-        if (sw == 4 && fr == 2) return launch_gather_lds_fr<false, TOK, 2, true, 4, true>(a, grid, lds, s);
+        if (sw == 4 && fr == 4) return launch_gather_lds_fr<TOK, 4, true, 4, true>(a, grid, lds, s);
+        if (sw == 4 && fr == 2) return launch_gather_lds_fr<TOK, 2, true, 4, true>(a, grid, lds, s);
     }
     return LFFN_E_UNSUPPORTED;
 }
@@ -183,20 +182,13 @@ int gather_direct_part(bool bf16, int lpt, const GatherArgs &a, bool probes, dim
 #endif
 
 #if LFFN_HAS(2)
-int gather_lds_plain_part(bool bf16, int tok, const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds,
-                          hipStream_t s)
+int gather_lds_plain_part(int tok, const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s)
 {
-    if (bf16) {
-        if (tok <= 4) return launch_gather_lds_t<true, 4>(a, fr, sw, grid, lds, s);
-        if (tok <= 6) return launch_gather_lds_t<true, 6>(a, fr, sw, grid, lds, s);
-        if (tok <= 8) return launch_gather_lds_t<true, 8>(a, fr, sw, grid, lds, s);
-        return LFFN_E_UNSUPPORTED;
-    }
-    if (tok <= 4) return launch_gather_lds_t<false, 4>(a, fr, sw, grid, lds, s);
-    if (tok <= 8) return launch_gather_lds_t<false, 8>(a, fr, sw, grid, lds, s);
-    if (tok <= 12) return launch_gather_lds_t<false, 12>(a, fr, sw, grid, lds, s);
-    if (tok <= 13) return launch_gather_lds_t<false, 13>(a, fr, sw, grid, lds, s);
-    if (tok <= 16 && sw == 4) return launch_gather_lds_t<false, 16>(a, fr, sw, grid, lds, s);
+    if (tok <= 4) return launch_gather_lds_t<4>(a, fr, sw, grid, lds, s);
+    if (tok <= 8) return launch_gather_lds_t<8>(a, fr, sw, grid, lds, s);
+    if (tok <= 12) return launch_gather_lds_t<12>(a, fr, sw, grid, lds, s);
+    if (tok <= 13) return launch_gather_lds_t<13>(a, fr, sw, grid, lds, s);
+    if (tok <= 16 && sw == 4) return launch_gather_lds_t<16>(a, fr, sw, grid, lds, s);
     return LFFN_E_UNSUPPORTED;
 }
 #endif
@@ -204,11 +196,11 @@ int gather_lds_plain_part(bool bf16, int tok, const GatherLdsArgs &a, int fr, in
 #if LFFN_HAS(3)
 int gather_lds_weighted_part(int tok, const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s)
 {
-    if (tok <= 4) return launch_gather_lds_t<false, 4, true>(a, fr, sw, grid, lds, s);
-    if (tok <= 8) return launch_gather_lds_t<false, 8, true>(a, fr, sw, grid, lds, s);
-    if (tok <= 12) return launch_gather_lds_t<false, 12, true>(a, fr, sw, grid, lds, s);
-    if (tok <= 13) return launch_gather_lds_t<false, 13, true>(a, fr, sw, grid, lds, s);
-    if (tok <= 16 && sw == 4) return launch_gather_lds_t<false, 16, true>(a, fr, sw, grid, lds, s);
+    if (tok <= 4) return launch_gather_lds_t<4, true>(a, fr, sw, grid, lds, s);
+    if (tok <= 8) return launch_gather_lds_t<8, true>(a, fr, sw, grid, lds, s);
+    if (tok <= 12) return launch_gather_lds_t<12, true>(a, fr, sw, grid, lds, s);
+    if (tok <= 13) return launch_gather_lds_t<13, true>(a, fr, sw, grid, lds, s);
+    if (tok <= 16 && sw == 4) return launch_gather_lds_t<16, true>(a, fr, sw, grid, lds, s);
     return LFFN_E_UNSUPPORTED;
 }
 
@@ -572,14 +564,23 @@ struct LdsPlan {
                     // write shift 7; a plan with shift 6 takes its codes through the re-pack kernel.
     unsigned grid = 0;
     size_t lds = 0;
+    bool widen = false;        // bf16 tables: the kernel reads an fp32 copy made first in `widened`
+    int64_t widen_bytes = 0;   // size of that copy
+    void *widened = nullptr;   // set by the entry point once it has the scratch memory
 };
 
+// `can_widen`: the caller can provide scratch memory for an fp32 copy of bf16 tables (the staged kernel
+// reads fp32 rows only).
 int plan_gather_lds(int64_t n, int k, int tau, int d_out, bool bf16, LdsPlan *p, bool weighted = false,
-                    bool probes = false)
+                    bool probes = false, bool can_widen = false)
 {
+    (void)weighted;
     p->use = false;
+    p->widen = false;
+    p->widen_bytes = 0;
+    p->widened = nullptr;
     if (g_opt.gather_path == 1) return LFFN_OK;
-    if (weighted && bf16) return LFFN_OK;  // the weighted staged kernel is built for fp32 tables
+    if (bf16 && !can_widen) return LFFN_OK;
     const int rows = 1 << tau;
     if (tau < 7 || tau > 10 || k % 2 != 0) return LFFN_OK;
     // column slices: 128 bytes (8 lanes per token) up to tau = 8; 64 bytes from tau = 9 on (two 512-row
@@ -589,10 +590,6 @@ int plan_gather_lds(int64_t n, int k, int tau, int d_out, bool bf16, LdsPlan *p,
     if (g_opt.slice_lanes == 4 && tau >= 8) sw = 4;
     if (g_opt.slice_lanes == 8 && tau <= 9) sw = 8;
     if (probes) sw = tau <= 8 ? 8 : 4;  // the multi-probe form is built for these pairings only
-    if (sw == 4 && bf16) {
-        if (tau > 9) return LFFN_OK;
-        sw = 8;
-    }
     const int groups = kLdsThreads / sw;
     // the kernel indexes tokens and bytes inside one table with 32 bits
     if (n >= (int64_t(1) << 31) - 4096 || (int64_t)rows * d_out * 4 >= (int64_t(1) << 32)) return LFFN_OK;
@@ -606,24 +603,23 @@ int plan_gather_lds(int64_t n, int k, int tau, int d_out, bool bf16, LdsPlan *p,
     a.k = k;
     a.tau = tau;
     a.d_out = d_out;
-    a.row_bytes = (uint32_t)d_out * (bf16 ? 2 : 4);
+    a.row_bytes = (uint32_t)d_out * 4;  // of the fp32 rows the kernel reads
     a.nvec = (int)(a.row_bytes / 16);
     a.n_slices = (a.nvec + sw - 1) / sw;
     a.token_splits = kXcds / gcd(a.n_slices, kXcds);
     a.n_units = a.n_slices * a.token_splits;
     a.blocks_per_xcd = cus / kXcds;
     const int64_t tpb = lds_tokens_per_block(n, a.n_units, a.token_splits, a.blocks_per_xcd);
-    int tok_max = bf16 ? 8 : sw == 4 ? 16 : 13;
+    int tok_max = sw == 4 ? 16 : 13;
     // the multi-probe form holds a share per probe beside the accumulators: 13 slots spill in its
     // hot loop, 8 measured faster up to tau = 9 (tau = 10 has 16 copy rounds per table to amortise)
     if (probes && tau <= 9) tok_max = 8;
     if (g_opt.token_slots && g_opt.token_slots < tok_max) tok_max = g_opt.token_slots;
     const int64_t nchunks = (tpb + (int64_t)groups * tok_max - 1) / ((int64_t)groups * tok_max);
     const int64_t chunk = (tpb + nchunks - 1) / nchunks;
-    // Staging pays only when a chunk re-uses each staged row a few times.  With bf16 rows the
-    // widening doubles the vector-ALU work per byte and the direct kernel measured faster, so
-    // bf16 tables take the staged kernel only on request.
-    if (g_opt.gather_path != 2 && (bf16 || chunk < 2 * (int64_t)rows)) return LFFN_OK;
+    // Staging pays only when a chunk re-uses each staged row a few times; with bf16 tables the whole
+    // table set is widened first (6 bytes moved per element), which a batch of 32 tokens per row repays.
+    if (g_opt.gather_path != 2 && (chunk < 2 * (int64_t)rows || (bf16 && n < 32 * (int64_t)rows))) return LFFN_OK;
     p->tok = (int)((chunk + groups - 1) / groups);
     if (probes && sw == 8 && p->tok > 8) p->tok = 13;  // multi-probe form: 4, 8 or 13 slots
     if (sw == 4) p->tok = p->tok > 13 ? 16 : p->tok > 8 ? 13 : 8;  // the 64-byte form is built for 8, 13 and 16 token slots
@@ -633,8 +629,23 @@ int plan_gather_lds(int64_t n, int k, int tau, int d_out, bool bf16, LdsPlan *p,
     p->lds = gather_lds_bytes(tau, sw);
     if (p->lds < (size_t)kLdsMinBytes) p->lds = kLdsMinBytes;
     p->grid = (unsigned)cus;
+    p->widen = bf16;
+    p->widen_bytes = bf16 ? round256((int64_t)k * rows * d_out * 4) : 0;
     p->use = true;
     return LFFN_OK;
+}
+
+// After the plan: does the scratch memory at hand have room for the widened tables?  `base` bytes are
+// taken by the call itself.  A caller workspace that is too small for the copy turns the staged kernel
+// off (the direct kernel reads bf16 rows); returns the bytes to add to `base`.
+int64_t widen_room(LdsPlan *p, const void *workspace, int64_t workspace_bytes, int64_t base)
+{
+    if (!p->use || !p->widen) return 0;
+    if (workspace && workspace_bytes < base + p->widen_bytes) {
+        p->use = false;
+        return 0;
+    }
+    return p->widen_bytes;
 }
 
 int launch_gather_lds(const LdsPlan &p, const uint32_t *packed, const float *wpk, const void *tables, float *y,
@@ -648,12 +659,22 @@ int launch_gather_lds(const LdsPlan &p, const uint32_t *packed, const float *wpk
     const dim3 grid(p.grid);
     int rc = LFFN_E_UNSUPPORTED;
     TimedLaunch tl(1, s);
+    if (p.widen) {
+        if (!bf16 || !p.widened) return LFFN_E_UNSUPPORTED;
+        const long long n8 = (long long)a.k * (1ll << a.tau) * a.d_out / 8;
+        long long wb = (n8 + 255) / 256;
+        if (wb > 8192) wb = 8192;
+        hipLaunchKernelGGL(widen_tables_kernel, dim3((unsigned)wb), dim3(256), 0, s,
+                           static_cast<const uint4 *>(tables), static_cast<uint4 *>(p.widened), n8);
+        LFFN_HIP(hipGetLastError());
+        a.tables = static_cast<const char *>(p.widened);
+    }
     if (probes)
         rc = lffn_host::gather_lds_probes_part(p.tok, a, p.fr, p.sw, grid, p.lds, s);
     else if (wpk)
         rc = lffn_host::gather_lds_weighted_part(p.tok, a, p.fr, p.sw, grid, p.lds, s);
     else
-        rc = lffn_host::gather_lds_plain_part(bf16, p.tok, a, p.fr, p.sw, grid, p.lds, s);
+        rc = lffn_host::gather_lds_plain_part(p.tok, a, p.fr, p.sw, grid, p.lds, s);
     if (rc != LFFN_OK) return rc;
     LFFN_HIP(hipGetLastError());
     tl.done();
@@ -1002,15 +1023,18 @@ int lookupffn_forward_weighted(const void *x, const int8_t *signs, const void *t
         if (!aligned(workspace, 256)) return LFFN_E_ALIGN;
     }
     if (n_tokens == 0) return LFFN_OK;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const bool bf16 = table_dtype == LFFN_BF16;
+    LdsPlan plan;
+    rc = plan_gather_lds(n_tokens, k, tau, d_out, bf16, &plan, true, false, true);
+    if (rc != LFFN_OK) return rc;
+    const int64_t extra = widen_room(&plan, workspace, workspace_bytes, need);
     void *ws = workspace;
     if (!ws) {
-        rc = own_workspace((size_t)need, &ws);
+        rc = own_workspace((size_t)(need + extra), &ws);
         if (rc != LFFN_OK) return rc;
     }
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    LdsPlan plan;
-    rc = plan_gather_lds(n_tokens, k, tau, d_out, table_dtype == LFFN_BF16, &plan, true);
-    if (rc != LFFN_OK) return rc;
+    plan.widened = extra ? static_cast<char *>(ws) + need : nullptr;
     if (plan.use && plan.shift != 7) {
         // 64-byte slices: ABI codes and weights, then the two re-pack kernels
         char *base = static_cast<char *>(ws);
@@ -1025,14 +1049,14 @@ int lookupffn_forward_weighted(const void *x, const int8_t *signs, const void *t
         if (rc != LFFN_OK) return rc;
         rc = launch_repack_weights(weights, wpk, n_tokens, plan.a.n_pad, k, s);
         if (rc != LFFN_OK) return rc;
-        return launch_gather_lds(plan, packed, wpk, tables, y, false, s);
+        return launch_gather_lds(plan, packed, wpk, tables, y, bf16, s);
     }
     if (plan.use) {
         uint32_t *packed = static_cast<uint32_t *>(ws);
         float *wpk = reinterpret_cast<float *>(static_cast<char *>(ws) + round256(packed_bytes(n_tokens, k)));
         rc = launch_hash(x, signs, nullptr, packed, wpk, n_tokens, d, k, tau, n_rounds, x_dtype, s);
         if (rc != LFFN_OK) return rc;
-        return launch_gather_lds(plan, packed, wpk, tables, y, false, s);
+        return launch_gather_lds(plan, packed, wpk, tables, y, bf16, s);
     }
     uint16_t *codes = static_cast<uint16_t *>(ws);
     float *weights = reinterpret_cast<float *>(static_cast<char *>(ws) + weighted_codes_bytes(n_tokens, k));
@@ -1049,19 +1073,28 @@ int lookupffn_gather(const uint16_t *codes, const void *tables, float *y, int64_
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const bool bf16 = table_dtype == LFFN_BF16;
     LdsPlan plan;
-    rc = plan_gather_lds(n_tokens, k, tau, d_out, bf16, &plan);
+    rc = plan_gather_lds(n_tokens, k, tau, d_out, bf16, &plan, false, false, true);
     if (rc != LFFN_OK) return rc;
     if (plan.use && aligned(codes, 4)) {
         // the staged kernel reads codes in its packed layout: repack into the library's buffer
+        // (bf16 tables: their fp32 copy goes behind it)
         void *ws = nullptr;
-        rc = own_workspace((size_t)packed_bytes(n_tokens, k), &ws);
+        const int64_t pb = round256(packed_bytes(n_tokens, k));
+        rc = own_workspace((size_t)(pb + plan.widen_bytes), &ws);
         if (rc != LFFN_OK) return rc;
+        plan.widened = plan.widen ? static_cast<char *>(ws) + pb : nullptr;
         uint32_t *packed = static_cast<uint32_t *>(ws);
         rc = launch_repack_codes(codes, packed, n_tokens, plan.a.n_pad, k, tau, plan.shift, s);
         if (rc != LFFN_OK) return rc;
         return launch_gather_lds(plan, packed, nullptr, tables, y, bf16, s);
     }
     return launch_gather_direct(codes, nullptr, tables, y, n_tokens, k, tau, d_out, table_dtype, s);
+}
+
+int64_t lookupffn_workspace_bytes_tables(int k, int tau, int d_out, int table_dtype)
+{
+    if (table_dtype != LFFN_BF16 || k < 1 || tau < 1 || tau > 16 || d_out < 1) return 0;
+    return round256((int64_t)k * (int64_t(1) << tau) * d_out * 4);
 }
 
 int64_t lookupffn_workspace_bytes(int64_t n_tokens, int k)
@@ -1089,16 +1122,18 @@ int lookupffn_forward(const void *x, const int8_t *signs, const void *tables, fl
         if (!aligned(workspace, 256)) return LFFN_E_ALIGN;
     }
     if (n_tokens == 0) return LFFN_OK;
-    void *ws = workspace;
-    if (!ws) {
-        rc = own_workspace((size_t)need, &ws);
-        if (rc != LFFN_OK) return rc;
-    }
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const bool bf16 = table_dtype == LFFN_BF16;
     LdsPlan plan;
-    rc = plan_gather_lds(n_tokens, k, tau, d_out, bf16, &plan);
+    rc = plan_gather_lds(n_tokens, k, tau, d_out, bf16, &plan, false, false, true);
     if (rc != LFFN_OK) return rc;
+    const int64_t extra = widen_room(&plan, workspace, workspace_bytes, need);
+    void *ws = workspace;
+    if (!ws) {
+        rc = own_workspace((size_t)(need + extra), &ws);
+        if (rc != LFFN_OK) return rc;
+    }
+    plan.widened = extra ? static_cast<char *>(ws) + need : nullptr;
     if (plan.use && plan.shift != 7) {
         // 64-byte slices: ABI codes, then the re-pack kernel scales them for 64-byte row pieces
         uint32_t *packed = static_cast<uint32_t *>(ws);

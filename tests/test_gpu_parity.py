@@ -361,6 +361,35 @@ def test_forward_config3_full_size_bf16():
     check_forward(w, x, signs, tables, sample=np.arange(0, w.n_tokens, 8))
 
 
+def test_forward_bf16_tables_widened_copy_and_workspace_sizes():
+    """bf16 tables with a large batch: the staged gather runs on an fp32 copy made in scratch memory.  A
+    caller workspace with room for the copy takes that path, one without it the direct gather; same bits."""
+    print("forward bf16 tables, 16384 tokens: workspace with and without room for the widened tables", flush=True)
+    w = synth.C3.with_tokens(16384)
+    x, signs, tables = synth.make_layer(w)
+    xd, sd, td = B.to_device(x), B.to_device(signs), B.to_device(tables)
+    base = B.lookupffn_workspace_bytes(w.n_tokens, w.k)
+    extra = B.lookupffn_workspace_bytes_tables(w.k, w.tau, w.d_out, "bf16")
+    assert extra == w.k * w.rows * w.d_out * 4 and B.lookupffn_workspace_bytes_tables(w.k, w.tau, w.d_out, "f32") == 0
+    want = oracle.forward(x[::16], signs, tables, acc64=False)
+    for nbytes, kernel in ((base + extra, "gather_lds_kernel"), (base, "gather_kernel"), (None, "gather_lds_kernel")):
+        ws = None if nbytes is None else torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        y = B.lookupffn_forward(xd, sd, td, workspace=ws)
+        torch.cuda.synchronize()
+        assert B.lookupffn_last_gather_kernel() == kernel
+        assert np.array_equal(y.cpu().numpy()[::16], want)
+    yw = B.lookupffn_forward_weighted(xd, sd, td)
+    torch.cuda.synchronize()
+    assert B.lookupffn_last_gather_kernel() == "gather_lds_kernel"
+    ref = oracle.forward_weighted(x[::16], signs, tables)
+    assert rel_err(yw.cpu().numpy()[::16], ref) <= TOL_BF16
+    # a small batch does not repay the copy: direct gather
+    small = B.lookupffn_forward(xd[:2000], sd, td)
+    torch.cuda.synchronize()
+    assert B.lookupffn_last_gather_kernel() == "gather_kernel"
+    assert np.array_equal(small.cpu().numpy()[::16], want[:125])
+
+
 def test_forward_config4_full_size():
     print("forward C4 (16384 tokens, tau=10, 512 MB of tables)", flush=True)
     w = synth.C4

@@ -107,6 +107,13 @@ def test_weighted_argument_errors(L):
     assert fw(n=1000, ws=FAKE, wsb=need - 1) == -7 and fw(n=1000, ws=FAKE + 16, wsb=need) == -5
 
 
+def test_workspace_for_widened_tables(L):
+    assert L.lookupffn_workspace_bytes_tables(96, 8, 768, 1) == 96 * 256 * 768 * 4
+    assert L.lookupffn_workspace_bytes_tables(96, 8, 768, 0) == 0           # fp32 tables need no copy
+    assert L.lookupffn_workspace_bytes_tables(3, 7, 8, 1) % 256 == 0
+    assert L.lookupffn_workspace_bytes_tables(0, 8, 768, 1) == 0 and L.lookupffn_workspace_bytes_tables(96, 17, 768, 1) == 0
+
+
 def test_bh_argument_errors(L):
     def hb(x=FAKE, bm=FAKE, codes=FAKE, n=0, d=768, k=96, tau=8, block=64, m=4, dt=0, ws=None, wsb=0):
         return L.lookupffn_hash_bh(x, bm, codes, n, d, k, tau, block, m, dt, ws, wsb, None)
