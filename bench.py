@@ -70,7 +70,7 @@ def traffic_from_profiles(w, weighted: bool = False) -> float | None:
         return None
     for line in f.read_text().splitlines():
         if line.startswith("traffic_bytes_per_launch:"):
-            return float(line.split(":", 1)[1])
+            return float(line.split(":", 1)[1].split()[0])
     return None
 
 
