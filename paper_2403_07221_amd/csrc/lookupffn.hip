@@ -618,8 +618,9 @@ int plan_gather_lds(int64_t n, int k, int tau, int d_out, bool bf16, LdsPlan *p,
     const int64_t nchunks = (tpb + (int64_t)groups * tok_max - 1) / ((int64_t)groups * tok_max);
     const int64_t chunk = (tpb + nchunks - 1) / nchunks;
     // Staging pays only when a chunk re-uses each staged row a few times; with bf16 tables the whole
-    // table set is widened first (6 bytes moved per element), which a batch of 32 tokens per row repays.
-    if (g_opt.gather_path != 2 && (chunk < 2 * (int64_t)rows || (bf16 && n < 32 * (int64_t)rows))) return LFFN_OK;
+    // table set is widened first (6 bytes moved per element), which a batch of 64 tokens per row repays
+    // (configuration 3's shape at 16384 tokens: 108 us against 124 us direct; at 8192 the direct kernel wins).
+    if (g_opt.gather_path != 2 && (chunk < 2 * (int64_t)rows || (bf16 && n < 64 * (int64_t)rows))) return LFFN_OK;
     p->tok = (int)((chunk + groups - 1) / groups);
     if (probes && sw == 8 && p->tok > 8) p->tok = 13;  // multi-probe form: 4, 8 or 13 slots
     if (sw == 4) p->tok = p->tok > 13 ? 16 : p->tok > 8 ? 13 : 8;  // the 64-byte form is built for 8, 13 and 16 token slots
