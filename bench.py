@@ -132,7 +132,7 @@ def main():
     if bh:
         ws_bytes = (B.lookupffn_workspace_bytes_bh_weighted if args.weighted else B.lookupffn_workspace_bytes_bh)(
             w.n_tokens, w.d, w.k, w.tau, args.block, 4)
-    if not bh and not args.probes:   # bf16 tables: room for the fp32 copy the staged gather reads
+    if not args.probes:   # bf16 tables: room for the fp32 copy the staged gather reads
         ws_bytes += B.lookupffn_workspace_bytes_tables(w.k, w.tau, w.d_out, w.table_dtype)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     forward = ((B.lookupffn_forward_bh_weighted if args.weighted else B.lookupffn_forward_bh) if bh

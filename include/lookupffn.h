@@ -99,12 +99,13 @@ int lookupffn_forward(const void *x, const int8_t *signs, const void *tables, fl
 int64_t lookupffn_workspace_bytes(int64_t n_tokens, int k);
 
 /*
- * bf16 tables and large batches: the LDS-staged gather reads fp32 rows, so lookupffn_forward and
- * lookupffn_forward_weighted first widen the whole table set into scratch memory (exact: a bf16 is
+ * bf16 tables and large batches: the LDS-staged gather reads fp32 rows, so the forward entry points
+ * (plain, weighted, and the two BH forms) and the stand-alone lookupffn_gather[_weighted] first widen
+ * the whole table set into scratch memory (exact: a bf16 is
  * the upper half of an fp32; once per call, about 6 bytes moved per table element) when the batch
  * repays it (at least 64 tokens per table row), and run the direct gather on the bf16 rows otherwise.
  * With workspace == NULL the library's own buffer holds the copy.  A caller workspace needs
- * lookupffn_workspace_bytes_tables() bytes on top of lookupffn_workspace_bytes[_weighted]() for that
+ * lookupffn_workspace_bytes_tables() bytes on top of the entry point's own workspace size for that
  * path; with less the call still succeeds and takes the direct gather.  Returns 0 for fp32 tables.
  */
 int64_t lookupffn_workspace_bytes_tables(int k, int tau, int d_out, int table_dtype);

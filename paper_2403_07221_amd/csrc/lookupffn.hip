@@ -895,21 +895,24 @@ int lookupffn_gather_weighted(const uint16_t *codes, const float *weights, const
     if (rc != LFFN_OK || n_tokens == 0) return rc;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     LdsPlan plan;
-    rc = plan_gather_lds(n_tokens, k, tau, d_out, table_dtype == LFFN_BF16, &plan, true);
+    const bool bf16 = table_dtype == LFFN_BF16;
+    rc = plan_gather_lds(n_tokens, k, tau, d_out, bf16, &plan, true, false, true);
     if (rc != LFFN_OK) return rc;
     if (plan.use && aligned(codes, 4)) {
         // the staged kernel reads packed codes and table-major weights: repack into the library's buffer
         const int64_t pb = round256(packed_bytes(n_tokens, k));
         void *ws = nullptr;
-        rc = own_workspace((size_t)(pb + (int64_t)k * plan.a.n_pad * 4), &ws);
+        const int64_t wb = round256((int64_t)k * plan.a.n_pad * 4);
+        rc = own_workspace((size_t)(pb + wb + plan.widen_bytes), &ws);
         if (rc != LFFN_OK) return rc;
+        plan.widened = plan.widen ? static_cast<char *>(ws) + pb + wb : nullptr;
         uint32_t *packed = static_cast<uint32_t *>(ws);
         float *wpk = reinterpret_cast<float *>(static_cast<char *>(ws) + pb);
         rc = launch_repack_codes(codes, packed, n_tokens, plan.a.n_pad, k, tau, plan.shift, s);
         if (rc != LFFN_OK) return rc;
         rc = launch_repack_weights(weights, wpk, n_tokens, plan.a.n_pad, k, s);
         if (rc != LFFN_OK) return rc;
-        return launch_gather_lds(plan, packed, wpk, tables, y, false, s);
+        return launch_gather_lds(plan, packed, wpk, tables, y, bf16, s);
     }
     return launch_gather_direct(codes, weights, tables, y, n_tokens, k, tau, d_out, table_dtype, s);
 }
@@ -1202,19 +1205,22 @@ int lookupffn_forward_bh(const void *x, const float *bmats, const void *tables, 
         if (!aligned(workspace, 256)) return LFFN_E_ALIGN;
     }
     if (n_tokens == 0) return LFFN_OK;
-    void *ws = workspace;
-    if (!ws) {
-        rc = own_workspace((size_t)need, &ws);
-        if (rc != LFFN_OK) return rc;
-    }
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    float *apack = static_cast<float *>(ws);
-    void *scratch = static_cast<char *>(ws) + pack;
     const bool bf16 = table_dtype == LFFN_BF16;
     LdsPlan plan;
-    rc = plan_gather_lds(n_tokens, k, tau, d_out, bf16, &plan);
+    rc = plan_gather_lds(n_tokens, k, tau, d_out, bf16, &plan, false, false, true);
     if (rc != LFFN_OK) return rc;
-    if (plan.use && plan.shift == 7) {  // the BH hash writes codes scaled for 128-byte row pieces only
+    if (plan.shift != 7) plan.use = false;  // the BH hash writes codes scaled for 128-byte row pieces only
+    const int64_t extra = widen_room(&plan, workspace, workspace_bytes, need);
+    void *ws = workspace;
+    if (!ws) {
+        rc = own_workspace((size_t)(need + extra), &ws);
+        if (rc != LFFN_OK) return rc;
+    }
+    plan.widened = extra ? static_cast<char *>(ws) + need : nullptr;
+    float *apack = static_cast<float *>(ws);
+    void *scratch = static_cast<char *>(ws) + pack;
+    if (plan.use) {
         uint32_t *packed = static_cast<uint32_t *>(scratch);
         rc = launch_hash_bh(x, bmats, apack, nullptr, packed, n_tokens, d, k, tau, block, n_factors, x_dtype, s);
         if (rc != LFFN_OK) return rc;
@@ -1271,24 +1277,28 @@ int lookupffn_forward_bh_weighted(const void *x, const float *bmats, const void 
         if (!aligned(workspace, 256)) return LFFN_E_ALIGN;
     }
     if (n_tokens == 0) return LFFN_OK;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const bool bf16 = table_dtype == LFFN_BF16;
+    LdsPlan plan;
+    rc = plan_gather_lds(n_tokens, k, tau, d_out, bf16, &plan, true, false, true);
+    if (rc != LFFN_OK) return rc;
+    if (plan.shift != 7) plan.use = false;  // the BH hash writes codes scaled for 128-byte row pieces only
+    const int64_t extra = widen_room(&plan, workspace, workspace_bytes, need);
     void *ws = workspace;
     if (!ws) {
-        rc = own_workspace((size_t)need, &ws);
+        rc = own_workspace((size_t)(need + extra), &ws);
         if (rc != LFFN_OK) return rc;
     }
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    plan.widened = extra ? static_cast<char *>(ws) + need : nullptr;
     float *apack = static_cast<float *>(ws);
     char *scratch = static_cast<char *>(ws) + pack;
-    LdsPlan plan;
-    rc = plan_gather_lds(n_tokens, k, tau, d_out, table_dtype == LFFN_BF16, &plan, true);
-    if (rc != LFFN_OK) return rc;
-    if (plan.use && plan.shift == 7) {  // the BH hash writes codes scaled for 128-byte row pieces only
+    if (plan.use) {
         uint32_t *packed = reinterpret_cast<uint32_t *>(scratch);
         float *wpk = reinterpret_cast<float *>(scratch + round256(packed_bytes(n_tokens, k)));
         rc = launch_hash_bh(x, bmats, apack, nullptr, packed, n_tokens, d, k, tau, block, n_factors, x_dtype, s,
                             nullptr, wpk);
         if (rc != LFFN_OK) return rc;
-        return launch_gather_lds(plan, packed, wpk, tables, y, false, s);
+        return launch_gather_lds(plan, packed, wpk, tables, y, bf16, s);
     }
     uint16_t *codes = reinterpret_cast<uint16_t *>(scratch);
     float *weights = reinterpret_cast<float *>(scratch + weighted_codes_bytes(n_tokens, k));
