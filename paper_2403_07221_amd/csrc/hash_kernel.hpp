@@ -624,47 +624,51 @@ __global__ __launch_bounds__(kHashThreads) __attribute__((amdgpu_waves_per_eu(4,
 
 // The re-pack kernels are plain functions: when the library is built in parts only part 0 defines them.
 #if !defined(LFFN_PART) || LFFN_PART == 0
-// ABI weights [n][k] -> table-major [k][n_pad] (token padding left as it is: those slots are never stored)
-__global__ __launch_bounds__(256) void repack_weights_kernel(const float *weights, float *wpk, long long n,
-                                                             long long n_pad, int k)
+// The re-pack kernels transpose a token-major matrix src[n][m] into the table-major dst[m][n_pad] the
+// staged gather reads, through 64 x 64 LDS tiles so that both the reads (along m) and the writes (along
+// n) are contiguous; grid-stride over tiles.
+//   ZERO_PAD: also write zeros to the token padding [n, n_pad) (the packed codes need valid rows there).
+template <bool ZERO_PAD, class F>
+__device__ __forceinline__ void transpose_tiles(const uint32_t *src, uint32_t *dst, long long n, long long n_pad,
+                                                long long m, F f)
 {
-    const long long total = (long long)k * n;
-    for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
-         idx += (long long)gridDim.x * blockDim.x) {
-        const long long j = idx / n, t = idx - j * n;
-        wpk[wpk_index(j, t, n_pad)] = weights[t * k + j];
+    __shared__ uint32_t tile[64][65];
+    const long long n_out = ZERO_PAD ? n_pad : n;
+    const long long tiles_m = (m + 63) / 64, tiles_n = (n_out + 63) / 64;
+    const int c = threadIdx.x & 63, r0 = threadIdx.x >> 6;  // column within the tile, first of the thread's rows
+    for (long long tl = blockIdx.x; tl < tiles_m * tiles_n; tl += gridDim.x) {
+        const long long t0 = (tl / tiles_m) * 64, j0 = (tl % tiles_m) * 64;
+        __syncthreads();
+#pragma unroll
+        for (int r = r0; r < 64; r += 4)
+            tile[r][c] = (t0 + r < n && j0 + c < m) ? f(src[(t0 + r) * m + j0 + c]) : 0u;
+        __syncthreads();
+#pragma unroll
+        for (int r = r0; r < 64; r += 4)
+            if (j0 + r < m && t0 + c < n_out) dst[(j0 + r) * n_pad + t0 + c] = tile[c][r];
     }
 }
 
-// ABI shares [n][k][1+tau] -> [k][1+tau][n_pad] for the staged multi-probe gather (token padding left as it is)
+// ABI weights [n][k] -> wpk[k][n_pad]; ABI shares [n][k][1+tau] -> spk[k][1+tau][n_pad]  (m = k or k * (1 + tau);
+// token padding left as it is: those slots are never stored)
 __global__ __launch_bounds__(256) void repack_shares_kernel(const float *shares, float *spk, long long n,
-                                                            long long n_pad, int k, int np)
+                                                            long long n_pad, long long m)
 {
-    const long long total = (long long)k * np * n;
-    for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
-         idx += (long long)gridDim.x * blockDim.x) {
-        const long long jp = idx / n, t = idx - jp * n;  // jp = j * np + probe
-        spk[jp * n_pad + t] = shares[t * k * np + jp];
-    }
+    transpose_tiles<false>(reinterpret_cast<const uint32_t *>(shares), reinterpret_cast<uint32_t *>(spk), n, n_pad, m,
+                           [](uint32_t w) { return w; });
 }
 
-// ABI codes [n][k] -> packed layout scaled by 2^shift (for a stand-alone gather call that takes the
-// LDS-staged kernel, and for the staged kernel's 64-byte-slice form, which needs shift 6)
+// ABI codes [n][k] (k even, rows 4-byte aligned) -> packed[k/2][n_pad]: two codes per word, reduced modulo
+// 2^tau and scaled by 2^shift (for a stand-alone gather call that takes the LDS-staged kernel, and for the
+// staged kernel's 64-byte-slice form, which needs shift 6); zeros in the token padding
 __global__ __launch_bounds__(256) void repack_codes_kernel(const uint16_t *codes, uint32_t *packed, long long n,
                                                            long long n_pad, int k, int tau, int shift)
 {
-    const long long total = (long long)(k / 2) * n_pad;
     const uint32_t cmask = (1u << tau) - 1u;
-    for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
-         idx += (long long)gridDim.x * blockDim.x) {
-        const long long s = idx / n_pad, t = idx - s * n_pad;
-        uint32_t w = 0u;
-        if (t < n) {
-            const uint32_t pair = *reinterpret_cast<const uint32_t *>(codes + t * k + 2 * s);
-            w = ((pair & cmask) << shift) | (((pair >> 16) & cmask) << (16 + shift));
-        }
-        packed[idx] = w;
-    }
+    transpose_tiles<true>(reinterpret_cast<const uint32_t *>(codes), packed, n, n_pad, (long long)(k / 2),
+                          [=](uint32_t pair) {
+                              return ((pair & cmask) << shift) | (((pair >> 16) & cmask) << (16 + shift));
+                          });
 }
 #endif
 

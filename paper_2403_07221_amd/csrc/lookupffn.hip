@@ -832,34 +832,36 @@ int launch_hash_bh(const void *x, const float *bmats, float *apack, uint16_t *co
 // gather) packed codes then table-major weights [k][n_pad]
 int64_t weighted_codes_bytes(int64_t n, int k) { return ((int64_t)n * k * 2 + 255) & ~int64_t(255); }
 
+// grid of the tiled re-pack kernels: one workgroup per 64 x 64 tile, capped (they stride over the rest)
+unsigned repack_grid(int64_t n_rows, int64_t m)
+{
+    int64_t blocks = ((m + 63) / 64) * ((n_rows + 63) / 64);
+    if (blocks > 16384) blocks = 16384;
+    return (unsigned)(blocks < 1 ? 1 : blocks);
+}
+
 int launch_repack_codes(const uint16_t *codes, uint32_t *packed, int64_t n, int64_t n_pad, int k, int tau,
                         int shift, hipStream_t s)
 {
-    const int64_t total = (int64_t)(k / 2) * n_pad;
-    int64_t blocks = (total + 255) / 256;
-    if (blocks > 4096) blocks = 4096;
-    hipLaunchKernelGGL(repack_codes_kernel, dim3((unsigned)blocks), dim3(256), 0, s, codes, packed, (long long)n,
-                       (long long)n_pad, k, tau, shift);
+    hipLaunchKernelGGL(repack_codes_kernel, dim3(repack_grid(n_pad, k / 2)), dim3(256), 0, s, codes, packed,
+                       (long long)n, (long long)n_pad, k, tau, shift);
     LFFN_HIP(hipGetLastError());
     return LFFN_OK;
 }
 
 int launch_repack_shares(const float *shares, float *spk, int64_t n, int64_t n_pad, int k, int tau, hipStream_t s)
 {
-    int64_t blocks = ((int64_t)k * (tau + 1) * n + 255) / 256;
-    if (blocks > 8192) blocks = 8192;
-    hipLaunchKernelGGL(repack_shares_kernel, dim3((unsigned)blocks), dim3(256), 0, s, shares, spk, (long long)n,
-                       (long long)n_pad, k, tau + 1);
+    const int64_t m = (int64_t)k * (tau + 1);
+    hipLaunchKernelGGL(repack_shares_kernel, dim3(repack_grid(n, m)), dim3(256), 0, s, shares, spk, (long long)n,
+                       (long long)n_pad, (long long)m);
     LFFN_HIP(hipGetLastError());
     return LFFN_OK;
 }
 
 int launch_repack_weights(const float *weights, float *wpk, int64_t n, int64_t n_pad, int k, hipStream_t s)
 {
-    int64_t blocks = ((int64_t)k * n + 255) / 256;
-    if (blocks > 4096) blocks = 4096;
-    hipLaunchKernelGGL(repack_weights_kernel, dim3((unsigned)blocks), dim3(256), 0, s, weights, wpk, (long long)n,
-                       (long long)n_pad, k);
+    hipLaunchKernelGGL(repack_shares_kernel, dim3(repack_grid(n, k)), dim3(256), 0, s, weights, wpk, (long long)n,
+                       (long long)n_pad, (long long)k);
     LFFN_HIP(hipGetLastError());
     return LFFN_OK;
 }
