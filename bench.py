@@ -5,10 +5,15 @@ A step is one pass of the whole hot path over one batch of synthetic input that 
 already resident in HBM: lookupffn_forward = hash kernel + gather kernel.  The default
 workload is the RoBERTa-base-shaped layer the headline metric is quoted on (config 2:
 16384 tokens, d = 768 padded to 1024, 3 hash rounds, k = 96 tables, tau = 8, fp32).
+The learned tables are prepared once before the timed region (lookupffn_prepare_tables:
+model-load work, like any weight pre-packing; --no-prepare times the row-major tables).
 
-Prints ONE JSON line: tokens/s of the whole pass, the gather kernel's roofline entry
-(algorithmic bytes / average kernel time from HIP events recorded inside the timed
-region, against the 8 TB/s HBM peak) and the CPU oracle's throughput on this host.
+Prints ONE JSON line: tokens/s of the whole pass; `roofline` = the dominant (gather) kernel
+against the resource that binds it (LDS reads for the staged kernel, else compulsory HBM
+bytes), with HIP-event kernel times from inside the timed region (mean, min, median);
+`hbm_compulsory` and `hbm_effective_x_peak` beside it; the CPU oracle's throughput on this
+host (all threads and one thread); and `parity_checked`: how many tokens of the timed y
+were compared with the oracle after the timed region.
 """
 from __future__ import annotations
 
@@ -55,6 +60,10 @@ def parse_args():
     ap.add_argument("--zipf", type=float, default=0.0,
                     help="also time lookupffn_gather alone on codes with Zipf(s)-skewed buckets (reported beside, "
                          "never instead of, the hashed codes of the rotated Gaussian input)")
+    ap.add_argument("--no-prepare", action="store_true",
+                    help="pass the row-major tables / BH factors instead of their one-time prepared copies")
+    ap.add_argument("--parity-tokens", type=int, default=1024,
+                    help="tokens of the timed y compared with the oracle after the timed region (0 = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget for the oracle timing")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
@@ -63,21 +72,22 @@ def parse_args():
     return ap.parse_args()
 
 
-def traffic_from_profiles(w, weighted: bool = False) -> float | None:
-    """HBM bytes per gather launch measured with rocprofv3 --pmc, if a summary is committed."""
+def traffic_from_profiles(w, weighted: bool = False):
+    """(HBM bytes per gather launch, file) from a committed rocprofv3 --pmc summary, if there is one: a
+    figure measured in an earlier run of the same command under the profiler, not in this run."""
     f = ROOT / "profiles" / f"gather_config{w.index}{'_weighted' if weighted else ''}_pmc_hbm_traffic.txt"
     if not f.exists():
-        return None
+        return None, None
     for line in f.read_text().splitlines():
         if line.startswith("traffic_bytes_per_launch:"):
-            return float(line.split(":", 1)[1].split()[0])
-    return None
+            return float(line.split(":", 1)[1].split()[0]), f"profiles/{f.name}"
+    return None, None
 
 
 def cpu_baseline(w, x, signs, tables, budget_s: float, weighted: bool = False, bh: bool = False,
                  probes: bool = False) -> dict:
-    """The CPU oracle as it stands, on all host threads it gets, on the same batch."""
-    import oracle  # only this leg of the bench touches the oracle
+    """The CPU oracle as it stands, on the same batch: on all host threads it gets, and on one thread."""
+    import oracle  # only this leg of the bench (and the parity check) touches the oracle
     threads = oracle.max_threads()
     n = x.shape[0]
     sample = min(n, 16384)
@@ -93,9 +103,47 @@ def cpu_baseline(w, x, signs, tables, budget_s: float, weighted: bool = False, b
         reps += 1
         if t_total > 3 * budget_s:
             break
+    # one thread: a smaller sample of the same batch (about a quarter of the budget)
+    one = min(sample, max(64, int(sample * reps / t_total / max(threads, 1) * budget_s / 4)))
+    oracle.set_threads(1)
+    try:
+        t0 = time.perf_counter()
+        run(xs[:one], signs, tables)
+        t_one = time.perf_counter() - t0
+    finally:
+        oracle.set_threads(threads)
     return {"value": sample * reps / t_total, "unit": "tokens/s", "cores": threads, "kind": "oracle",
             "sample": f"first {sample} tokens of the batch, {reps} passes, {t_total:.1f} s, "
-                      f"gcc -O2 -fopenmp, {os.cpu_count()} logical CPUs visible"}
+                      f"gcc -O2 -fopenmp, {os.cpu_count()} logical CPUs visible",
+            "single_thread": {"value": one / t_one, "unit": "tokens/s", "cores": 1,
+                              "sample": f"first {one} tokens, one pass, {t_one:.1f} s"}}
+
+
+def parity_check(w, x, signs, tables, y_dev, n_check: int, weighted: bool, bh: bool, probes: bool) -> dict:
+    """Compares tokens of the y the timed steps wrote with the oracle: an odd stride over the whole batch
+    plus its first and last tokens (untimed)."""
+    import oracle
+    n = x.shape[0]
+    step = max(1, n // max(n_check, 1)) | 1
+    idx = np.unique(np.concatenate([np.arange(0, n, step), np.arange(0, min(64, n)), np.arange(max(0, n - 64), n)]))
+    got = y_dev[idx].cpu().numpy() if hasattr(y_dev, "cpu") else y_dev[idx]
+    xs = x[idx]
+    if bh:
+        ref = (oracle.bh_forward_weighted if weighted else oracle.bh_forward)(xs, signs, tables)
+    elif probes:
+        ref = oracle.forward_probes(xs, signs, tables)
+    elif weighted:
+        ref = oracle.forward_weighted(xs, signs, tables)
+    else:
+        ref = oracle.forward(xs, signs, tables, acc64=True)
+    r = ref.astype(np.float64)
+    err = float(np.max(np.abs(got.astype(np.float64) - r)) / np.sqrt(np.mean(r ** 2)))
+    tol = 1e-2 if w.table_dtype == "bf16" else 1e-4
+    out = {"tokens": int(len(idx)), "max_abs_err_over_rms": err, "tolerance": tol, "ok": bool(err <= tol)}
+    if not (weighted or probes):
+        seq = (oracle.bh_forward if bh else oracle.forward)(xs, signs, tables, acc64=False)
+        out["bit_equal_to_fp32_sequential_sum"] = bool(np.array_equal(got, seq))
+    return out
 
 
 def main():
@@ -130,20 +178,28 @@ def main():
     if args.probes:
         ws_bytes = B.lookupffn_workspace_bytes_probes(w.n_tokens, w.k, w.tau)
     if bh:
+        blk = args.block if args.no_prepare else (B.PREPARED | args.block)
         ws_bytes = (B.lookupffn_workspace_bytes_bh_weighted if args.weighted else B.lookupffn_workspace_bytes_bh)(
-            w.n_tokens, w.d, w.k, w.tau, args.block, 4)
-    if not args.probes:   # bf16 tables: room for the fp32 copy the staged gather reads
-        ws_bytes += B.lookupffn_workspace_bytes_tables(w.k, w.tau, w.d_out, w.table_dtype)
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+            w.n_tokens, w.d, w.k, w.tau, blk, 4)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
+    B.lookupffn_init()
     forward = ((B.lookupffn_forward_bh_weighted if args.weighted else B.lookupffn_forward_bh) if bh
                else B.lookupffn_forward_probes if args.probes
                else B.lookupffn_forward_weighted if args.weighted else B.lookupffn_forward)
+
+    def prepared(td):
+        return td if args.no_prepare else B.lookupffn_prepare_tables(td)
+
     if w.n_layers == 1:
         x, signs, tables = synth.make_layer(w)
         if bh:   # the block-diagonal factors take the place of the sign diagonals
             signs = synth.make_bmats(synth.seed_for(w.seed_index or w.index, 0, 3) + args.block, w.n_proj, 4,
                                      w.d_pad, args.block)
-        xd, sd, td = B.to_device(x), torch.from_numpy(signs).cuda(), B.to_device(tables)
+        xd, sd = B.to_device(x), torch.from_numpy(signs).cuda()
+        td_rows = B.to_device(tables)
+        td = prepared(td_rows)
+        if bh and not args.no_prepare:
+            sd = B.lookupffn_prepare_bh(sd, w.d, w.k, w.tau)
         y = torch.empty((w.n_tokens, w.d_out), dtype=torch.float32, device="cuda")
 
         def step():
@@ -153,7 +209,7 @@ def main():
         layers = [synth.make_layer(w, layer=l, with_x=(l == 0)) for l in range(w.n_layers)]
         x, signs, tables = layers[0]
         xd = B.to_device(x)
-        dev = [(B.to_device(s_), B.to_device(t_)) for _, s_, t_ in layers]
+        dev = [(B.to_device(s_), prepared(B.to_device(t_))) for _, s_, t_ in layers]
         ys = [torch.empty((w.n_tokens, w.d_out), dtype=torch.float32, device="cuda") for _ in range(2)]
 
         def step():
@@ -182,6 +238,7 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     gather_ms, gather_n = B.lookupffn_timing_read(1)
+    gather_each = B.lookupffn_timing_read_each(1)
     B.lookupffn_timing_enable(0)
     B.lookupffn_timing_reset()
     assert gather_n == args.steps * w.n_layers and hash_n == args.warmup * w.n_layers
@@ -192,17 +249,45 @@ def main():
     xb = 2 if w.x_dtype == "bf16" else 4
     tb = 2 if w.table_dtype == "bf16" else 4
     path_bytes = cost.bytes_per_token(w.d, w.k, w.d_out, xb, tb) * w.n_tokens * w.n_layers
-    # the gather kernel alone: k table rows + the y row + the k uint16 codes it reads, per token
-    gather_bytes = (w.k * w.d_out * tb + w.d_out * 4 + w.k * 2) * w.n_tokens
-    if args.probes:
-        # (1 + tau) rows and shares per token and table
-        gather_bytes = (w.k * (w.tau + 1) * (w.d_out * tb + 4) + w.d_out * 4 + w.k * 2) * w.n_tokens
-        path_bytes += (w.k * w.tau * w.d_out * tb + 2 * w.k * (w.tau + 1) * 4) * w.n_tokens * w.n_layers
-    if args.weighted:
-        gather_bytes += w.k * 4 * w.n_tokens          # the fp32 weights it reads
-        path_bytes += 2 * w.k * 4 * w.n_tokens * w.n_layers   # written by the hash, read by the gather
+    n_probe = (w.tau + 1) if args.probes else 1
+    side_floats = w.k * n_probe if (args.weighted or args.probes) else 0      # weights / shares per token
+    # the gather kernel alone: k table rows (x probes) + the y row + the k uint16 codes (+ weights) it reads, per token
+    gather_bytes = (w.k * n_probe * w.d_out * tb + w.d_out * 4 + w.k * 2 + side_floats * 4) * w.n_tokens
+    path_bytes += (w.k * (n_probe - 1) * w.d_out * tb + 2 * side_floats * 4) * w.n_tokens * w.n_layers
     gather_avg_ms = gather_ms / gather_n
-    achieved = gather_bytes / (gather_avg_ms * 1e-3) / 1e9
+    kernel = B.lookupffn_last_gather_kernel()
+    staged = kernel == "gather_lds_kernel"
+    # compulsory HBM traffic of one gather launch: every table byte once (as the kernel reads it: the prepared
+    # copy is fp32), codes (+ weights) once, y once
+    read_tb = 4 if (staged or not args.no_prepare) else tb
+    table_bytes_read = w.k * w.rows * w.d_out * read_tb
+    compulsory = table_bytes_read + (w.k * 2 + side_floats * 4 + w.d_out * 4) * w.n_tokens
+    if w.n_tokens * w.k < w.k * w.rows:          # fewer lookups than rows: only the rows touched
+        compulsory = (w.k * n_probe * w.d_out * read_tb + w.k * 2 + side_floats * 4 + w.d_out * 4) * w.n_tokens
+    each = sorted(gather_each)
+    times = {"avg_kernel_ms": gather_avg_ms, "min_kernel_ms": each[0] if each else None,
+             "median_kernel_ms": each[len(each) // 2] if each else None, "launches_timed": len(each)}
+    traffic, traffic_file = traffic_from_profiles(w, args.weighted)
+    # The staged kernel serves every (token, table[, probe]) row piece from LDS, so LDS read bandwidth is the
+    # resource that binds it: 256 CUs x 256 bytes per clock (16-byte reads) x 2.4 GHz.  The direct kernel is
+    # priced against HBM on the bytes that must cross it.
+    lds_peak = 256 * 256 * 2.4  # GB/s
+    lds_bytes = w.k * w.d_out * 4 * w.n_tokens * n_probe
+    if staged:
+        rate = lds_bytes / (gather_avg_ms * 1e-3) / 1e9
+        roofline = {"kernel": kernel, "bound": "lds", "achieved": rate, "peak": lds_peak, "unit": "GB/s",
+                    "frac": rate / lds_peak, "bytes_per_launch": lds_bytes,
+                    "bytes_definition": "k * d_out * 4 * n_tokens (* (1 + tau) probes): every selected row piece is read from LDS once"}
+    else:
+        rate = compulsory / (gather_avg_ms * 1e-3) / 1e9
+        roofline = {"kernel": kernel, "bound": "hbm", "achieved": rate, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": rate / HBM_PEAK_GBS, "bytes_per_launch": compulsory,
+                    "bytes_definition": "compulsory HBM bytes: tables (or the rows touched) + codes (+ weights) + y, once each"}
+    roofline.update(times)
+    roofline["traffic"] = traffic
+    roofline["traffic_source"] = (f"{traffic_file}: rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE of an earlier profiled run of "
+                                  "this command, not measured in this run") if traffic_file else None
+    roofline["algorithmic_bytes_per_launch"] = gather_bytes
 
     out = {
         "metric": "tokens/sec and achieved GB/s vs HBM peak for LookupFFN forward at d=768",
@@ -221,29 +306,31 @@ def main():
                    "hash_rounds": w.n_rounds, "k_tables": w.k, "tau": w.tau, "d_out": w.d_out,
                    "x_dtype": w.x_dtype, "table_dtype": w.table_dtype,
                    "table_bytes": w.k * w.rows * w.d_out * tb,
+                   "tables_prepared_once": not args.no_prepare,
                    "variant": "weighted" if args.weighted else "multi-probe" if args.probes else "plain-sum",
                    "hash": f"bh4-block{args.block}" if bh else "sign-diagonal"},
-        "roofline": {"kernel": B.lookupffn_last_gather_kernel(), "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic_from_profiles(w, args.weighted),
-                     "algorithmic_bytes_per_launch": gather_bytes, "avg_kernel_ms": gather_avg_ms},
+        "roofline": roofline,
+        # the same kernel time against the bytes that must cross HBM at least once
+        "hbm_compulsory": {"bytes_per_launch": compulsory, "achieved": compulsory / (gather_avg_ms * 1e-3) / 1e9,
+                           "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                           "frac": compulsory / (gather_avg_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        # algorithmic bytes (one HBM row read per token and table, as if nothing were re-used) / kernel time /
+        # 8 TB/s: a ratio, not a fraction -- above 1 it measures the re-use the kernel extracts on chip
+        "hbm_effective_x_peak": gather_bytes / (gather_avg_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "kernels_ms": {"hash": hash_ms / max(hash_n, 1), "gather": gather_avg_ms},
         "whole_path": {"algorithmic_bytes_per_step": path_bytes,
-                       "effective_GBps": path_bytes / (ms_per_step * 1e-3) / 1e9},
+                       "effective_GBps": path_bytes / (ms_per_step * 1e-3) / 1e9,
+                       "compulsory_hbm_bytes_per_step": (compulsory + w.d * xb * w.n_tokens) * w.n_layers,
+                       "frac_of_hbm_peak_on_compulsory_bytes":
+                           (compulsory + w.d * xb * w.n_tokens) * w.n_layers / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
     }
-    if B.lookupffn_last_gather_kernel() == "gather_lds_kernel":
-        # The staged kernel reads its rows from LDS, not HBM: every (token, table[, probe]) reads its row
-        # piece from the staged copy.  Peak: 256 CUs x 256 bytes per clock (16-byte reads) x 2.4 GHz.
-        lds_peak = 256 * 256 * 2.4  # GB/s
-        lds_bytes = w.k * w.d_out * tb * w.n_tokens * ((w.tau + 1) if args.probes else 1)
+    if staged:
         # measured with a stand-alone read loop (16 waves per CU, 16-byte reads, row offsets in registers):
         # contiguous 147.7 TB/s; 8 lanes per random 128-byte row 82.8 TB/s; 4 lanes per random 64-byte row 68.5 TB/s
         wide = w.tau <= 8 if args.slice_lanes == 0 else args.slice_lanes == 8
         ceiling = 82800.0 if wide else 68500.0
-        lds_rate = lds_bytes / (gather_avg_ms * 1e-3) / 1e9
-        out["lds_roofline"] = {"kernel": "gather_lds_kernel", "bound": "lds", "achieved": lds_rate,
-                               "peak": lds_peak, "unit": "GB/s", "frac": lds_rate / lds_peak,
-                               "random_row_ceiling": ceiling, "frac_of_random_row_ceiling": lds_rate / ceiling,
-                               "lds_read_bytes_per_launch": lds_bytes}
+        roofline["random_row_ceiling"] = ceiling
+        roofline["frac_of_random_row_ceiling"] = roofline["achieved"] / ceiling
     if bh:
         # the block-diagonal products are the path's one dense contraction: priced against the fp32
         # matrix-core peak (flops of the products only; the transform and the code extraction ride along).
@@ -293,12 +380,12 @@ def main():
             cd = torch.from_numpy(codes_np.view(np.int16)).cuda()
             yz = torch.empty((w.n_tokens, w.d_out), dtype=torch.float32, device="cuda")
             for _ in range(5):
-                B.lookupffn_gather(cd, td, y=yz)
+                B.lookupffn_gather(cd, td, y=yz, workspace=ws)
             torch.cuda.synchronize()
             B.lookupffn_timing_reset()
             B.lookupffn_timing_enable(2)
             for _ in range(args.steps):
-                B.lookupffn_gather(cd, td, y=yz)
+                B.lookupffn_gather(cd, td, y=yz, workspace=ws)
             torch.cuda.synchronize()
             ms, cnt = B.lookupffn_timing_read(1)
             B.lookupffn_timing_enable(0)
@@ -316,6 +403,22 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         out["copy_calibration_bytes_each_way"] = src.numel() * 4
+    if args.parity_tokens > 0:
+        # the y the timed steps wrote (for the chain: the first layer's, recomputed into a buffer of its own)
+        if w.n_layers == 1:
+            step()
+            torch.cuda.synchronize()
+            y_check = y
+        else:
+            y_check = forward(xd, dev[0][0], dev[0][1], workspace=ws)
+            torch.cuda.synchronize()
+        pc = parity_check(w, x, signs, tables, y_check, args.parity_tokens, args.weighted, bh, args.probes)
+        out["parity_checked"] = pc["tokens"]
+        out["parity"] = pc
+        if not pc["ok"]:
+            print(json.dumps(out))
+            print("bench.py: the timed output does not match the oracle", file=sys.stderr)
+            sys.exit(1)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, x, signs, tables, args.cpu_seconds, args.weighted, bh, args.probes)
         if w.n_layers > 1:

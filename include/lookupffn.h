@@ -27,10 +27,20 @@
  *       signs  [P][n_rounds][d_pad]          int8, a negative entry means "flip"
  *       codes  [n_tokens][k]                 uint16
  *       weights[n_tokens][k]                 fp32 (weighted variant only)
- *       tables [k][2^tau][d_out]             fp32 or bf16
+ *       tables [k][2^tau][d_out]             fp32 or bf16, or the prepared copy (lookupffn_prepare_tables)
  *       y      [n_tokens][d_out]             fp32
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Work is enqueued on it and the call returns without synchronising.
+ *   - Scratch memory.  Entry points with a (workspace, workspace_bytes) pair keep their intermediates
+ *     (codes, weights, the staged gather's re-packed copies) there.  With a caller workspace (device
+ *     memory, 256-byte aligned, at least the matching lookupffn_workspace_bytes*() bytes) the call only
+ *     launches kernels on `hip_stream`: it allocates nothing, frees nothing, never synchronises, and --
+ *     once lookupffn_init() has run on the device -- makes no other runtime call, so it may be captured in a
+ *     HIP graph.  Calls that share a workspace must be ordered on one stream.  workspace == NULL is a
+ *     convenience for simple callers: the library then uses a per-device buffer of its own, which it grows
+ *     with hipMalloc when a call needs more (old buffers are kept until lookupffn_release_workspace(), so
+ *     enqueued work stays valid; a growing call cannot be captured, and all NULL-workspace calls on a
+ *     device must be ordered on one stream because they share that buffer).
  *   - Return value: 0 on success, a negative lffn_status otherwise.  Arguments are
  *     validated before the first HIP call, so error paths need no GPU.
  *     n_tokens == 0 is a successful no-op.  Nothing is printed, nothing aborts.
@@ -51,6 +61,10 @@ extern "C" {
 #endif
 
 typedef enum { LFFN_F32 = 0, LFFN_BF16 = 1 } lffn_dtype;
+/* OR-ed into a `table_dtype` argument: `tables` is the buffer lookupffn_prepare_tables() wrote (from
+ * tables of the dtype in the low bits).  OR-ed into a `block` argument of the BH entry points: `bmats`
+ * is the buffer lookupffn_prepare_bh() wrote. */
+#define LFFN_PREPARED 0x100
 
 typedef enum {
     LFFN_OK = 0,
@@ -62,9 +76,18 @@ typedef enum {
                                  or d_out not a multiple of 4 (fp32 tables) / 8 (bf16 tables) */
     LFFN_E_UNSUPPORTED = -6,  /* a shape the kernels are not built for: d_pad above 4096; the BH
                                  entry points state their own limits */
-    LFFN_E_WORKSPACE = -7,    /* caller workspace smaller than lookupffn_workspace_bytes() */
+    LFFN_E_WORKSPACE = -7,    /* caller workspace (or a prepare call's output buffer) smaller than the matching
+                                 *_bytes() query says */
     LFFN_E_HIP = -8           /* a HIP call failed; see lookupffn_last_hip_error() */
 } lffn_status;
+
+/*
+ * Once per device (with that device current), before the first capture of any entry point into a HIP
+ * graph: registers the dynamic-LDS need of every kernel that uses more than 64 KB with the runtime and
+ * caches the device's compute-unit count, so that later calls with a caller workspace consist of kernel
+ * launches only.  Optional otherwise (each kernel does it on first use).  For callers under graph capture.
+ */
+int lookupffn_init(void);
 
 /*
  * Hash step alone (Sec. 3.1 "Two main operations", (a)): writes codes[n_tokens][k].
@@ -76,54 +99,53 @@ int lookupffn_hash(const void *x, const int8_t *signs, uint16_t *codes,
 /*
  * Gather step alone (Sec. 3.1 "Two main operations", (b), unweighted; eq. "lookup"):
  * y[t] = sum_j tables[j][codes[t][j] mod 2^tau].  Codes are reduced modulo 2^tau, so no
- * value of `codes` can make the kernel read outside `tables`.
+ * value of `codes` can make the kernel read outside `tables`.  Scratch:
+ * lookupffn_workspace_bytes_gather(n_tokens, k) bytes (the LDS-staged kernel reads the codes re-packed).
  */
 int lookupffn_gather(const uint16_t *codes, const void *tables, float *y,
                      int64_t n_tokens, int k, int tau, int d_out,
-                     int table_dtype, void *hip_stream);
+                     int table_dtype, void *workspace, int64_t workspace_bytes, void *hip_stream);
+int64_t lookupffn_workspace_bytes_gather(int64_t n_tokens, int k);
 
 /*
  * Whole forward pass: Hash then Gather on the same stream (Sec. 3.1, eq. "lookup").
- * The codes live in a scratch buffer of lookupffn_workspace_bytes(n_tokens, k) bytes:
- * pass a device buffer of at least that size as `workspace` (256-byte aligned), or
- * workspace == NULL to let the library use a per-device buffer of its own that it grows
- * with hipMalloc when needed (growing synchronises the device; calls that share that
- * buffer must be ordered on one stream).
+ * Scratch: lookupffn_workspace_bytes(n_tokens, k) bytes (0 if n_tokens == 0).
  */
 int lookupffn_forward(const void *x, const int8_t *signs, const void *tables, float *y,
                       int64_t n_tokens, int d, int k, int tau, int d_out,
                       int n_rounds, int x_dtype, int table_dtype,
                       void *workspace, int64_t workspace_bytes, void *hip_stream);
-
-/* Bytes of scratch lookupffn_forward needs for this problem size (0 if n_tokens == 0). */
 int64_t lookupffn_workspace_bytes(int64_t n_tokens, int k);
 
 /*
- * bf16 tables and large batches: the LDS-staged gather reads fp32 rows, so the forward entry points
- * (plain, weighted, and the two BH forms) and the stand-alone lookupffn_gather[_weighted] first widen
- * the whole table set into scratch memory (exact: a bf16 is
- * the upper half of an fp32; once per call, about 6 bytes moved per table element) when the batch
- * repays it (at least 64 tokens per table row), and run the direct gather on the bf16 rows otherwise.
- * With workspace == NULL the library's own buffer holds the copy.  A caller workspace needs
- * lookupffn_workspace_bytes_tables() bytes on top of the entry point's own workspace size for that
- * path; with less the call still succeeds and takes the direct gather.  Returns 0 for fp32 tables.
+ * One-time preparation of the learned tables T_1 .. T_k of eq. "lookup" (Sec. 3.1): they are constants of
+ * the model, so the layout the gather kernels stream best is written once, outside the forward pass.
+ * lookupffn_prepare_tables copies tables[k][2^tau][d_out] (fp32 or bf16) into `prepared` as fp32 (bf16
+ * widened exactly), slice-major: the 128-byte (tau <= 8) or 64-byte (tau >= 9) column slice of all rows of
+ * all tables is one contiguous run, ragged last slice zero-filled.  `prepared`: device memory, 256-byte
+ * aligned, lookupffn_prepared_tables_bytes() bytes (0 for arguments the call would reject), owned by the
+ * caller.  Every gather / forward entry point takes it in place of `tables` with
+ * table_dtype = LFFN_PREPARED | <dtype of the source tables>; results are bit-identical to those with
+ * the row-major tables.  bf16 tables take the LDS-staged gather only in this form (it reads fp32 rows).
  */
-int64_t lookupffn_workspace_bytes_tables(int k, int tau, int d_out, int table_dtype);
+int64_t lookupffn_prepared_tables_bytes(int k, int tau, int d_out, int table_dtype);
+int lookupffn_prepare_tables(const void *tables, int k, int tau, int d_out, int table_dtype,
+                             void *prepared, int64_t prepared_bytes, void *hip_stream);
 
 /*
  * Weighted variant (Sec. 4, "Overview").  lookupffn_hash_weighted writes codes[n_tokens][k]
  * and weights[n_tokens][k] (4-byte aligned; LFFN_E_UNSUPPORTED when d_pad = 4096, where the
  * kernel's working set no longer fits).  lookupffn_gather_weighted computes
  * y[t] = sum_j weights[t][j] * tables[j][codes[t][j] mod 2^tau].  lookupffn_forward_weighted
- * chains the two like lookupffn_forward, with a scratch buffer of
- * lookupffn_workspace_bytes_weighted(n_tokens, k) bytes (same rules as above).
+ * chains the two like lookupffn_forward.
  */
 int lookupffn_hash_weighted(const void *x, const int8_t *signs, uint16_t *codes, float *weights,
                             int64_t n_tokens, int d, int k, int tau,
                             int n_rounds, int x_dtype, void *hip_stream);
 int lookupffn_gather_weighted(const uint16_t *codes, const float *weights, const void *tables, float *y,
                               int64_t n_tokens, int k, int tau, int d_out,
-                              int table_dtype, void *hip_stream);
+                              int table_dtype, void *workspace, int64_t workspace_bytes, void *hip_stream);
+int64_t lookupffn_workspace_bytes_gather_weighted(int64_t n_tokens, int k);
 int lookupffn_forward_weighted(const void *x, const int8_t *signs, const void *tables, float *y,
                                int64_t n_tokens, int d, int k, int tau, int d_out,
                                int n_rounds, int x_dtype, int table_dtype,
@@ -138,15 +160,15 @@ int64_t lookupffn_workspace_bytes_weighted(int64_t n_tokens, int k);
  *   flip(0) = 0, flip(probe) = 1 << (probe-1).
  * lookupffn_hash_probes writes codes[n_tokens][k] and shares[n_tokens][k][1+tau] (fp32, 4-byte
  * aligned); lookupffn_gather_probes does the sum ((1 + tau) row reads per token and table);
- * lookupffn_forward_probes chains them with lookupffn_workspace_bytes_probes() bytes of scratch.
- * Same hash, conventions and limits as the weighted variant.
+ * lookupffn_forward_probes chains them.  Same hash, conventions and limits as the weighted variant.
  */
 int lookupffn_hash_probes(const void *x, const int8_t *signs, uint16_t *codes, float *shares,
                           int64_t n_tokens, int d, int k, int tau,
                           int n_rounds, int x_dtype, void *hip_stream);
 int lookupffn_gather_probes(const uint16_t *codes, const float *shares, const void *tables, float *y,
                             int64_t n_tokens, int k, int tau, int d_out,
-                            int table_dtype, void *hip_stream);
+                            int table_dtype, void *workspace, int64_t workspace_bytes, void *hip_stream);
+int64_t lookupffn_workspace_bytes_gather_probes(int64_t n_tokens, int k, int tau);
 int lookupffn_forward_probes(const void *x, const int8_t *signs, const void *tables, float *y,
                              int64_t n_tokens, int d, int k, int tau, int d_out,
                              int n_rounds, int x_dtype, int table_dtype,
@@ -160,10 +182,16 @@ int64_t lookupffn_workspace_bytes_probes(int64_t n_tokens, int k, int tau);
  * multiply-adds, c ascending, from +0 (on the matrix cores).
  *   bmats [P][n_factors][d_pad/block][block][block] fp32, element [p][i][blk][c][j] = B_i[blk*block+c][blk*block+j]
  * Supported: 64 <= d_pad <= 1024 (LFFN_E_UNSUPPORTED otherwise, and for other block sizes).
- * The kernels read the factors from a re-ordered copy made on every call in the workspace:
- * lookupffn_workspace_bytes_bh() bytes (256-byte aligned) or workspace == NULL for the library's own
- * buffer (same rules as lookupffn_forward).  lookupffn_forward_bh = this hash + the plain gather.
+ * The kernels read the factors in matrix-core operand order.  The B_i are learned constants: write that
+ * order once with lookupffn_prepare_bh (`prepared`: device memory, 256-byte aligned,
+ * lookupffn_prepared_bh_bytes() bytes) and pass it as `bmats` with block = LFFN_PREPARED | block.  Given
+ * the row-major factors instead, every call re-orders them into its workspace first.
+ * lookupffn_forward_bh = this hash + the plain gather.  Scratch: lookupffn_workspace_bytes_bh() bytes
+ * (`block` as it will be passed to the call, flag included).
  */
+int64_t lookupffn_prepared_bh_bytes(int d, int k, int tau, int block, int n_factors);
+int lookupffn_prepare_bh(const float *bmats, int d, int k, int tau, int block, int n_factors,
+                         void *prepared, int64_t prepared_bytes, void *hip_stream);
 int lookupffn_hash_bh(const void *x, const float *bmats, uint16_t *codes,
                       int64_t n_tokens, int d, int k, int tau, int block, int n_factors, int x_dtype,
                       void *workspace, int64_t workspace_bytes, void *hip_stream);
@@ -178,7 +206,7 @@ int64_t lookupffn_workspace_bytes_bh(int64_t n_tokens, int d, int k, int tau, in
  * Sec. 4 forward pass): lookupffn_hash_bh_weighted writes codes[n_tokens][k] and weights[n_tokens][k]
  * (fp32, 4-byte aligned) with w_j as in lookupffn_hash_weighted, computed from the z of the BH hash;
  * lookupffn_forward_bh_weighted = that + lookupffn_gather_weighted, with
- * lookupffn_workspace_bytes_bh_weighted() bytes of scratch (or workspace == NULL).
+ * lookupffn_workspace_bytes_bh_weighted() bytes of scratch.
  * Supported: the shapes of lookupffn_hash_bh with tau = 4, 8 or 16 (LFFN_E_UNSUPPORTED otherwise:
  * the kernel reduces a table's weight inside one 16-coordinate tile of z).
  */
@@ -191,7 +219,8 @@ int lookupffn_forward_bh_weighted(const void *x, const float *bmats, const void 
                                   void *workspace, int64_t workspace_bytes, void *hip_stream);
 int64_t lookupffn_workspace_bytes_bh_weighted(int64_t n_tokens, int d, int k, int tau, int block, int n_factors);
 
-/* Frees the library-owned workspaces (all devices).  Safe to call when none exist. */
+/* Frees the library-owned buffers of workspace == NULL calls (all devices; synchronises each device
+ * first).  Safe to call when none exist. */
 int lookupffn_release_workspace(void);
 
 /*
@@ -200,11 +229,14 @@ int lookupffn_release_workspace(void);
  * (0 = off, 3 = both; each bracketed launch costs a few microseconds of queue time).
  * lookupffn_timing_read synchronises on the recorded events and returns, for
  * `which` (0 = hash kernel, 1 = gather kernel), the summed elapsed milliseconds and the
- * number of launches since the last reset.  Not thread-safe; off by default.
+ * number of launches since the last reset; lookupffn_timing_read_each copies the first `capacity`
+ * launches' own durations (milliseconds, launch order) to the host array `ms_out` and returns the launch
+ * count.  Off by default.
  */
 int lookupffn_timing_enable(int mask);
 int lookupffn_timing_reset(void);
 int lookupffn_timing_read(int which, double *total_ms, int64_t *launches);
+int lookupffn_timing_read_each(int which, double *ms_out, int64_t capacity, int64_t *launches);
 
 /*
  * Launch-shape knobs of the gather kernel, for tuning sweeps (0 = library default):
@@ -219,15 +251,16 @@ int lookupffn_timing_read(int which, double *total_ms, int64_t *launches);
  *   "hash_path"        1              always the generic hash kernel (default: the two-layout
  *                                     kernel when d_pad = 1024 and n_rounds <= 4)
  *   "hash_blocks"      1..65536       grid cap of the d_pad = 1024 hash kernel
- * Returns LFFN_E_SIZE for an unknown key or a value outside the documented set.
+ * Returns LFFN_E_SIZE for an unknown key or a value outside the documented set.  Process-wide; a call
+ * reads the knobs once when it starts.
  */
 int lookupffn_set_option(const char *key, int value);
 
 const char *lookupffn_strerror(int status);
 /* Text of the last HIP error seen by this thread's most recent failing call ("" if none). */
 const char *lookupffn_last_hip_error(void);
-/* Which gather kernel the most recent gather launch used: "gather_kernel" (direct, rows fetched
- * through L2) or "gather_lds_kernel" (table slices staged in LDS); "" before the first launch. */
+/* Which gather kernel the calling thread's most recent gather launch used: "gather_kernel" (direct, rows
+ * fetched through L2) or "gather_lds_kernel" (table slices staged in LDS); "" before the first launch. */
 const char *lookupffn_last_gather_kernel(void);
 /* major*10000 + minor*100 + patch */
 int lookupffn_version(void);

@@ -16,17 +16,21 @@ _LIB_PATH = Path(__file__).resolve().parent / "liblookupffn.so"
 _lib = None
 
 F32, BF16 = 0, 1
+PREPARED = 0x100   # OR-ed into table_dtype / block: the buffer is a prepared copy (see include/lookupffn.h)
 EXPORTS = (
+    "lookupffn_init",
     "lookupffn_hash", "lookupffn_gather", "lookupffn_forward", "lookupffn_workspace_bytes",
-    "lookupffn_release_workspace", "lookupffn_workspace_bytes_tables", "lookupffn_timing_enable", "lookupffn_timing_reset",
-    "lookupffn_timing_read", "lookupffn_set_option", "lookupffn_strerror",
+    "lookupffn_workspace_bytes_gather", "lookupffn_prepared_tables_bytes", "lookupffn_prepare_tables",
+    "lookupffn_release_workspace", "lookupffn_timing_enable", "lookupffn_timing_reset",
+    "lookupffn_timing_read", "lookupffn_timing_read_each", "lookupffn_set_option", "lookupffn_strerror",
     "lookupffn_last_hip_error", "lookupffn_last_gather_kernel", "lookupffn_version",
     "lookupffn_hash_weighted", "lookupffn_gather_weighted", "lookupffn_forward_weighted",
-    "lookupffn_workspace_bytes_weighted",
+    "lookupffn_workspace_bytes_weighted", "lookupffn_workspace_bytes_gather_weighted",
+    "lookupffn_prepared_bh_bytes", "lookupffn_prepare_bh",
     "lookupffn_hash_bh", "lookupffn_forward_bh", "lookupffn_workspace_bytes_bh",
     "lookupffn_hash_bh_weighted", "lookupffn_forward_bh_weighted", "lookupffn_workspace_bytes_bh_weighted",
     "lookupffn_hash_probes", "lookupffn_gather_probes", "lookupffn_forward_probes",
-    "lookupffn_workspace_bytes_probes",
+    "lookupffn_workspace_bytes_probes", "lookupffn_workspace_bytes_gather_probes",
 )
 
 
@@ -47,32 +51,34 @@ def lib() -> ctypes.CDLL:
         L = ctypes.CDLL(str(_LIB_PATH))
         vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
         L.lookupffn_hash.argtypes = [vp, vp, vp, i64, ci, ci, ci, ci, ci, vp]
-        L.lookupffn_gather.argtypes = [vp, vp, vp, i64, ci, ci, ci, ci, vp]
+        L.lookupffn_gather.argtypes = [vp, vp, vp, i64, ci, ci, ci, ci, vp, i64, vp]
         L.lookupffn_forward.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, ci, ci, vp, i64, vp]
-        L.lookupffn_workspace_bytes.argtypes = [i64, ci]
-        L.lookupffn_workspace_bytes.restype = i64
-        L.lookupffn_workspace_bytes_tables.argtypes = [ci, ci, ci, ci]
-        L.lookupffn_workspace_bytes_tables.restype = i64
         L.lookupffn_hash_weighted.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, vp]
-        L.lookupffn_gather_weighted.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, vp]
+        L.lookupffn_gather_weighted.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, vp, i64, vp]
         L.lookupffn_forward_weighted.argtypes = L.lookupffn_forward.argtypes
-        L.lookupffn_workspace_bytes_weighted.argtypes = [i64, ci]
-        L.lookupffn_workspace_bytes_weighted.restype = i64
         L.lookupffn_hash_probes.argtypes = L.lookupffn_hash_weighted.argtypes
         L.lookupffn_gather_probes.argtypes = L.lookupffn_gather_weighted.argtypes
         L.lookupffn_forward_probes.argtypes = L.lookupffn_forward.argtypes
-        L.lookupffn_workspace_bytes_probes.argtypes = [i64, ci, ci]
-        L.lookupffn_workspace_bytes_probes.restype = i64
+        for name, args in (("lookupffn_workspace_bytes", [i64, ci]), ("lookupffn_workspace_bytes_gather", [i64, ci]),
+                           ("lookupffn_workspace_bytes_weighted", [i64, ci]),
+                           ("lookupffn_workspace_bytes_gather_weighted", [i64, ci]),
+                           ("lookupffn_workspace_bytes_probes", [i64, ci, ci]),
+                           ("lookupffn_workspace_bytes_gather_probes", [i64, ci, ci]),
+                           ("lookupffn_workspace_bytes_bh", [i64, ci, ci, ci, ci, ci]),
+                           ("lookupffn_workspace_bytes_bh_weighted", [i64, ci, ci, ci, ci, ci]),
+                           ("lookupffn_prepared_tables_bytes", [ci, ci, ci, ci]),
+                           ("lookupffn_prepared_bh_bytes", [ci, ci, ci, ci, ci])):
+            getattr(L, name).argtypes = args
+            getattr(L, name).restype = i64
+        L.lookupffn_prepare_tables.argtypes = [vp, ci, ci, ci, ci, vp, i64, vp]
+        L.lookupffn_prepare_bh.argtypes = [vp, ci, ci, ci, ci, ci, vp, i64, vp]
         L.lookupffn_hash_bh.argtypes = [vp, vp, vp, i64, ci, ci, ci, ci, ci, ci, vp, i64, vp]
         L.lookupffn_forward_bh.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, ci, ci, ci, vp, i64, vp]
-        L.lookupffn_workspace_bytes_bh.argtypes = [i64, ci, ci, ci, ci, ci]
-        L.lookupffn_workspace_bytes_bh.restype = i64
         L.lookupffn_hash_bh_weighted.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, ci, vp, i64, vp]
         L.lookupffn_forward_bh_weighted.argtypes = L.lookupffn_forward_bh.argtypes
-        L.lookupffn_workspace_bytes_bh_weighted.argtypes = [i64, ci, ci, ci, ci, ci]
-        L.lookupffn_workspace_bytes_bh_weighted.restype = i64
         L.lookupffn_timing_enable.argtypes = [ci]
         L.lookupffn_timing_read.argtypes = [ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+        L.lookupffn_timing_read_each.argtypes = [ci, ctypes.POINTER(ctypes.c_double), i64, ctypes.POINTER(i64)]
         L.lookupffn_set_option.argtypes = [ctypes.c_char_p, ci]
         L.lookupffn_strerror.argtypes = [ci]
         L.lookupffn_strerror.restype = ctypes.c_char_p
@@ -127,6 +133,58 @@ def _check_signs(signs: torch.Tensor, d: int, k: int, tau: int):
         raise ValueError(f"signs has shape {tuple(signs.shape)}, expected ({P}, n_rounds, {n_pad})")
 
 
+def _ws(workspace):
+    if workspace is None:
+        return None, 0
+    return _dev(workspace, "workspace"), workspace.numel() * workspace.element_size()
+
+
+class PreparedTables:
+    """The learned tables in the layout lookupffn_prepare_tables wrote (an opaque device buffer plus the
+    shape it was made from); accepted wherever a `tables` tensor is."""
+
+    def __init__(self, buf: torch.Tensor, k: int, tau: int, d_out: int, src_dtype: int):
+        self.buf, self.k, self.tau, self.d_out, self.src_dtype = buf, k, tau, d_out, src_dtype
+        self.device = buf.device
+
+    @property
+    def shape(self):
+        return (self.k, 1 << self.tau, self.d_out)
+
+
+def _tables(tables):
+    """(device pointer, k, tau, d_out, table_dtype code, device) of a tables tensor or a PreparedTables."""
+    if isinstance(tables, PreparedTables):
+        return _dev(tables.buf, "prepared tables"), tables.k, tables.tau, tables.d_out, PREPARED | tables.src_dtype, tables.device
+    k, rows, d_out = tables.shape
+    tau = rows.bit_length() - 1
+    if (1 << tau) != rows:
+        raise ValueError("tables must be [k, 2^tau, d_out]")
+    return _dev(tables, "tables"), k, tau, d_out, _dtype_code(tables), tables.device
+
+
+def lookupffn_init() -> None:
+    """Registers the kernels' LDS needs with the runtime on the current device (before graph capture)."""
+    _check(lib().lookupffn_init())
+
+
+def lookupffn_prepared_tables_bytes(k: int, tau: int, d_out: int, table_dtype) -> int:
+    code = table_dtype if isinstance(table_dtype, int) else (BF16 if table_dtype in ("bf16", torch.bfloat16) else F32)
+    return lib().lookupffn_prepared_tables_bytes(k, tau, d_out, code)
+
+
+def lookupffn_prepare_tables(tables: torch.Tensor, out: torch.Tensor | None = None) -> PreparedTables:
+    """One-time re-layout of tables[k, 2^tau, d_out] for the gather kernels (see include/lookupffn.h)."""
+    ptr, k, tau, d_out, code, dev = _tables(tables)
+    need = lib().lookupffn_prepared_tables_bytes(k, tau, d_out, code)
+    if out is None:
+        out = torch.empty(need, dtype=torch.uint8, device=dev)
+    with torch.cuda.device(dev):
+        _check(lib().lookupffn_prepare_tables(ptr, k, tau, d_out, code, _dev(out, "prepared"),
+                                              out.numel() * out.element_size(), _stream(tables)))
+    return PreparedTables(out, k, tau, d_out, code)
+
+
 def lookupffn_hash(x: torch.Tensor, signs: torch.Tensor, k: int, tau: int,
                    codes: torch.Tensor | None = None) -> torch.Tensor:
     """codes[n, k] (int16 storage of the uint16 codes) for x[n, d]."""
@@ -143,23 +201,43 @@ def lookupffn_hash(x: torch.Tensor, signs: torch.Tensor, k: int, tau: int,
     return codes
 
 
-def lookupffn_gather(codes: torch.Tensor, tables: torch.Tensor, y: torch.Tensor | None = None) -> torch.Tensor:
-    """y[n, d_out] = sum_j tables[j, codes[:, j], :]; tables[k, 2^tau, d_out] float32 or bfloat16."""
+def _gather(entry: str, codes, weights, tables, y, workspace, wshape):
     n, k = codes.shape
-    k2, rows, d_out = tables.shape
-    tau = rows.bit_length() - 1
-    if k2 != k or (1 << tau) != rows:
+    tptr, k2, tau, d_out, tcode, dev = _tables(tables)
+    if k2 != k:
         raise ValueError("tables must be [k, 2^tau, d_out] with k matching codes")
     assert codes.dtype == torch.int16
+    if weights is not None:
+        assert weights.dtype == torch.float32 and tuple(weights.shape) == wshape(n, k, tau)
     if y is None:
-        y = torch.empty((n, d_out), dtype=torch.float32, device=tables.device)
+        y = torch.empty((n, d_out), dtype=torch.float32, device=dev)
     assert y.dtype == torch.float32 and tuple(y.shape) == (n, d_out)
     if n == 0:
         return y
-    with torch.cuda.device(tables.device):
-        _check(lib().lookupffn_gather(_dev(codes, "codes"), _dev(tables, "tables"), _dev(y, "y"), n, k, tau,
-                                      d_out, _dtype_code(tables), _stream(tables)))
+    ws_ptr, ws_bytes = _ws(workspace)
+    args = [_dev(codes, "codes")] + ([_dev(weights, "weights")] if weights is not None else [])
+    with torch.cuda.device(dev):
+        _check(getattr(lib(), entry)(*args, tptr, _dev(y, "y"), n, k, tau, d_out, tcode, ws_ptr, ws_bytes,
+                                     _stream(codes)))
     return y
+
+
+def lookupffn_gather(codes: torch.Tensor, tables, y: torch.Tensor | None = None,
+                     workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """y[n, d_out] = sum_j tables[j, codes[:, j], :]; tables[k, 2^tau, d_out] float32 / bfloat16 or PreparedTables."""
+    return _gather("lookupffn_gather", codes, None, tables, y, workspace, None)
+
+
+def lookupffn_workspace_bytes_gather(n_tokens: int, k: int) -> int:
+    return lib().lookupffn_workspace_bytes_gather(n_tokens, k)
+
+
+def lookupffn_workspace_bytes_gather_weighted(n_tokens: int, k: int) -> int:
+    return lib().lookupffn_workspace_bytes_gather_weighted(n_tokens, k)
+
+
+def lookupffn_workspace_bytes_gather_probes(n_tokens: int, k: int, tau: int) -> int:
+    return lib().lookupffn_workspace_bytes_gather_probes(n_tokens, k, tau)
 
 
 def lookupffn_hash_weighted(x: torch.Tensor, signs: torch.Tensor, k: int, tau: int,
@@ -182,26 +260,10 @@ def lookupffn_hash_weighted(x: torch.Tensor, signs: torch.Tensor, k: int, tau: i
     return codes, weights
 
 
-def lookupffn_gather_weighted(codes: torch.Tensor, weights: torch.Tensor, tables: torch.Tensor,
-                              y: torch.Tensor | None = None) -> torch.Tensor:
+def lookupffn_gather_weighted(codes: torch.Tensor, weights: torch.Tensor, tables, y: torch.Tensor | None = None,
+                              workspace: torch.Tensor | None = None) -> torch.Tensor:
     """y[n, d_out] = sum_j weights[:, j] * tables[j, codes[:, j], :]."""
-    n, k = codes.shape
-    k2, rows, d_out = tables.shape
-    tau = rows.bit_length() - 1
-    if k2 != k or (1 << tau) != rows:
-        raise ValueError("tables must be [k, 2^tau, d_out] with k matching codes")
-    assert codes.dtype == torch.int16
-    assert weights.dtype == torch.float32 and tuple(weights.shape) == (n, k)
-    if y is None:
-        y = torch.empty((n, d_out), dtype=torch.float32, device=tables.device)
-    assert y.dtype == torch.float32 and tuple(y.shape) == (n, d_out)
-    if n == 0:
-        return y
-    with torch.cuda.device(tables.device):
-        _check(lib().lookupffn_gather_weighted(_dev(codes, "codes"), _dev(weights, "weights"),
-                                               _dev(tables, "tables"), _dev(y, "y"), n, k, tau, d_out,
-                                               _dtype_code(tables), _stream(tables)))
-    return y
+    return _gather("lookupffn_gather_weighted", codes, weights, tables, y, workspace, lambda n, k, tau: (n, k))
 
 
 def lookupffn_hash_probes(x: torch.Tensor, signs: torch.Tensor, k: int, tau: int):
@@ -219,25 +281,11 @@ def lookupffn_hash_probes(x: torch.Tensor, signs: torch.Tensor, k: int, tau: int
     return codes, shares
 
 
-def lookupffn_gather_probes(codes: torch.Tensor, shares: torch.Tensor, tables: torch.Tensor,
-                            y: torch.Tensor | None = None) -> torch.Tensor:
+def lookupffn_gather_probes(codes: torch.Tensor, shares: torch.Tensor, tables, y: torch.Tensor | None = None,
+                            workspace: torch.Tensor | None = None) -> torch.Tensor:
     """y[n, d_out] = sum_j sum_probe shares[:, j, probe] * tables[j, codes[:, j] ^ flip(probe), :]."""
-    n, k = codes.shape
-    k2, rows, d_out = tables.shape
-    tau = rows.bit_length() - 1
-    if k2 != k or (1 << tau) != rows:
-        raise ValueError("tables must be [k, 2^tau, d_out] with k matching codes")
-    assert codes.dtype == torch.int16
-    assert shares.dtype == torch.float32 and tuple(shares.shape) == (n, k, tau + 1)
-    if y is None:
-        y = torch.empty((n, d_out), dtype=torch.float32, device=tables.device)
-    assert y.dtype == torch.float32 and tuple(y.shape) == (n, d_out)
-    if n == 0:
-        return y
-    with torch.cuda.device(tables.device):
-        _check(lib().lookupffn_gather_probes(_dev(codes, "codes"), _dev(shares, "shares"), _dev(tables, "tables"),
-                                             _dev(y, "y"), n, k, tau, d_out, _dtype_code(tables), _stream(tables)))
-    return y
+    return _gather("lookupffn_gather_probes", codes, shares, tables, y, workspace,
+                   lambda n, k, tau: (n, k, tau + 1))
 
 
 def lookupffn_workspace_bytes_probes(n_tokens: int, k: int, tau: int) -> int:
@@ -248,12 +296,6 @@ def lookupffn_forward_probes(x: torch.Tensor, signs: torch.Tensor, tables: torch
                              y: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
     """Whole multi-probe forward pass y[n, d_out] (Sec. 3.1, eq. "partial_softmax")."""
     return lookupffn_forward(x, signs, tables, y, workspace, _entry="lookupffn_forward_probes")
-
-
-def lookupffn_workspace_bytes_tables(k: int, tau: int, d_out: int, table_dtype) -> int:
-    """Extra scratch bytes that let a forward pass with bf16 tables take the LDS-staged gather."""
-    code = table_dtype if isinstance(table_dtype, int) else (BF16 if table_dtype in ("bf16", torch.bfloat16) else F32)
-    return lib().lookupffn_workspace_bytes_tables(k, tau, d_out, code)
 
 
 def lookupffn_workspace_bytes(n_tokens: int, k: int) -> int:
@@ -270,29 +312,51 @@ def lookupffn_forward_weighted(x: torch.Tensor, signs: torch.Tensor, tables: tor
     return lookupffn_forward(x, signs, tables, y, workspace, _entry="lookupffn_forward_weighted")
 
 
-def lookupffn_forward(x: torch.Tensor, signs: torch.Tensor, tables: torch.Tensor,
+def lookupffn_forward(x: torch.Tensor, signs: torch.Tensor, tables,
                       y: torch.Tensor | None = None, workspace: torch.Tensor | None = None,
                       _entry: str = "lookupffn_forward") -> torch.Tensor:
-    """Whole forward pass y[n, d_out]; `workspace` is an optional uint8 CUDA tensor for the codes."""
+    """Whole forward pass y[n, d_out]; `tables` a [k, 2^tau, d_out] tensor or a PreparedTables; `workspace`
+    an optional uint8 CUDA tensor of lookupffn_workspace_bytes*() bytes for the intermediates."""
     n, d = x.shape
-    k, rows, d_out = tables.shape
-    tau = rows.bit_length() - 1
-    if (1 << tau) != rows:
-        raise ValueError("tables must have 2^tau rows")
+    tptr, k, tau, d_out, tcode, _ = _tables(tables)
     _check_signs(signs, d, k, tau)
     if y is None:
         y = torch.empty((n, d_out), dtype=torch.float32, device=x.device)
     assert y.dtype == torch.float32 and tuple(y.shape) == (n, d_out)
     if n == 0:
         return y
-    ws_ptr, ws_bytes = None, 0
-    if workspace is not None:
-        ws_ptr, ws_bytes = _dev(workspace, "workspace"), workspace.numel() * workspace.element_size()
+    ws_ptr, ws_bytes = _ws(workspace)
     with torch.cuda.device(x.device):
-        _check(getattr(lib(), _entry)(_dev(x, "x"), _dev(signs, "signs"), _dev(tables, "tables"), _dev(y, "y"),
-                                      n, d, k, tau, d_out, signs.shape[1], _dtype_code(x), _dtype_code(tables),
+        _check(getattr(lib(), _entry)(_dev(x, "x"), _dev(signs, "signs"), tptr, _dev(y, "y"),
+                                      n, d, k, tau, d_out, signs.shape[1], _dtype_code(x), tcode,
                                       ws_ptr, ws_bytes, _stream(x)))
     return y
+
+
+class PreparedBh:
+    """The block-diagonal factors in the order lookupffn_prepare_bh wrote; accepted wherever `bmats` is."""
+
+    def __init__(self, buf: torch.Tensor, block: int, n_factors: int):
+        self.buf, self.block, self.n_factors = buf, block, n_factors
+
+
+def lookupffn_prepare_bh(bmats: torch.Tensor, d: int, k: int, tau: int) -> PreparedBh:
+    """One-time re-ordering of the BH factors into matrix-core operand order."""
+    block, m = _check_bmats(bmats, d, k, tau)
+    need = lib().lookupffn_prepared_bh_bytes(d, k, tau, block, m)
+    out = torch.empty(max(need, 256), dtype=torch.uint8, device=bmats.device)
+    with torch.cuda.device(bmats.device):
+        _check(lib().lookupffn_prepare_bh(_dev(bmats, "bmats"), d, k, tau, block, m, _dev(out, "prepared"),
+                                          out.numel(), _stream(bmats)))
+    return PreparedBh(out, block, m)
+
+
+def _bh(bmats, d: int, k: int, tau: int):
+    """(device pointer, block argument, n_factors) of a bmats tensor or a PreparedBh."""
+    if isinstance(bmats, PreparedBh):
+        return _dev(bmats.buf, "prepared bmats"), PREPARED | bmats.block, bmats.n_factors
+    block, m = _check_bmats(bmats, d, k, tau)
+    return _dev(bmats, "bmats"), block, m
 
 
 def _check_bmats(bmats: torch.Tensor, d: int, k: int, tau: int):
@@ -306,21 +370,15 @@ def _check_bmats(bmats: torch.Tensor, d: int, k: int, tau: int):
     return block, bmats.shape[1]
 
 
-def _ws(workspace):
-    if workspace is None:
-        return None, 0
-    return _dev(workspace, "workspace"), workspace.numel() * workspace.element_size()
-
-
 def lookupffn_workspace_bytes_bh(n_tokens: int, d: int, k: int, tau: int, block: int, n_factors: int) -> int:
     return lib().lookupffn_workspace_bytes_bh(n_tokens, d, k, tau, block, n_factors)
 
 
-def lookupffn_hash_bh(x: torch.Tensor, bmats: torch.Tensor, k: int, tau: int, codes: torch.Tensor | None = None,
+def lookupffn_hash_bh(x: torch.Tensor, bmats, k: int, tau: int, codes: torch.Tensor | None = None,
                       workspace: torch.Tensor | None = None) -> torch.Tensor:
-    """codes[n, k] of the BH hash (Sec. 3.2 of the paper); bmats[P, m, d_pad/b, b, b] float32."""
+    """codes[n, k] of the BH hash (Sec. 3.2 of the paper); bmats[P, m, d_pad/b, b, b] float32 or a PreparedBh."""
     n, d = x.shape
-    block, m = _check_bmats(bmats, d, k, tau)
+    bptr, block, m = _bh(bmats, d, k, tau)
     if codes is None:
         codes = torch.empty((n, k), dtype=torch.int16, device=x.device)
     assert codes.dtype == torch.int16 and tuple(codes.shape) == (n, k)
@@ -328,20 +386,17 @@ def lookupffn_hash_bh(x: torch.Tensor, bmats: torch.Tensor, k: int, tau: int, co
         return codes
     ws_ptr, ws_bytes = _ws(workspace)
     with torch.cuda.device(x.device):
-        _check(lib().lookupffn_hash_bh(_dev(x, "x"), _dev(bmats, "bmats"), _dev(codes, "codes"), n, d, k, tau, block,
+        _check(lib().lookupffn_hash_bh(_dev(x, "x"), bptr, _dev(codes, "codes"), n, d, k, tau, block,
                                        m, _dtype_code(x), ws_ptr, ws_bytes, _stream(x)))
     return codes
 
 
-def lookupffn_forward_bh(x: torch.Tensor, bmats: torch.Tensor, tables: torch.Tensor, y: torch.Tensor | None = None,
+def lookupffn_forward_bh(x: torch.Tensor, bmats, tables, y: torch.Tensor | None = None,
                          workspace: torch.Tensor | None = None, _entry: str = "lookupffn_forward_bh") -> torch.Tensor:
     """Whole forward pass with the BH hash: y[n, d_out]."""
     n, d = x.shape
-    k, rows, d_out = tables.shape
-    tau = rows.bit_length() - 1
-    if (1 << tau) != rows:
-        raise ValueError("tables must have 2^tau rows")
-    block, m = _check_bmats(bmats, d, k, tau)
+    tptr, k, tau, d_out, tcode, _ = _tables(tables)
+    bptr, block, m = _bh(bmats, d, k, tau)
     if y is None:
         y = torch.empty((n, d_out), dtype=torch.float32, device=x.device)
     assert y.dtype == torch.float32 and tuple(y.shape) == (n, d_out)
@@ -349,8 +404,8 @@ def lookupffn_forward_bh(x: torch.Tensor, bmats: torch.Tensor, tables: torch.Ten
         return y
     ws_ptr, ws_bytes = _ws(workspace)
     with torch.cuda.device(x.device):
-        _check(getattr(lib(), _entry)(_dev(x, "x"), _dev(bmats, "bmats"), _dev(tables, "tables"), _dev(y, "y"),
-                                      n, d, k, tau, d_out, block, m, _dtype_code(x), _dtype_code(tables),
+        _check(getattr(lib(), _entry)(_dev(x, "x"), bptr, tptr, _dev(y, "y"),
+                                      n, d, k, tau, d_out, block, m, _dtype_code(x), tcode,
                                       ws_ptr, ws_bytes, _stream(x)))
     return y
 
@@ -360,12 +415,12 @@ def lookupffn_workspace_bytes_bh_weighted(n_tokens: int, d: int, k: int, tau: in
     return lib().lookupffn_workspace_bytes_bh_weighted(n_tokens, d, k, tau, block, n_factors)
 
 
-def lookupffn_hash_bh_weighted(x: torch.Tensor, bmats: torch.Tensor, k: int, tau: int,
+def lookupffn_hash_bh_weighted(x: torch.Tensor, bmats, k: int, tau: int,
                                codes: torch.Tensor | None = None, weights: torch.Tensor | None = None,
                                workspace: torch.Tensor | None = None):
     """(codes[n, k], weights[n, k]) of the BH hash with the gather weights of Sec. 4 of the paper."""
     n, d = x.shape
-    block, m = _check_bmats(bmats, d, k, tau)
+    bptr, block, m = _bh(bmats, d, k, tau)
     if codes is None:
         codes = torch.empty((n, k), dtype=torch.int16, device=x.device)
     if weights is None:
@@ -376,7 +431,7 @@ def lookupffn_hash_bh_weighted(x: torch.Tensor, bmats: torch.Tensor, k: int, tau
         return codes, weights
     ws_ptr, ws_bytes = _ws(workspace)
     with torch.cuda.device(x.device):
-        _check(lib().lookupffn_hash_bh_weighted(_dev(x, "x"), _dev(bmats, "bmats"), _dev(codes, "codes"),
+        _check(lib().lookupffn_hash_bh_weighted(_dev(x, "x"), bptr, _dev(codes, "codes"),
                                                 _dev(weights, "weights"), n, d, k, tau, block, m, _dtype_code(x),
                                                 ws_ptr, ws_bytes, _stream(x)))
     return codes, weights
@@ -401,6 +456,15 @@ def lookupffn_timing_enable(mask) -> None:
 
 def lookupffn_timing_reset() -> None:
     _check(lib().lookupffn_timing_reset())
+
+
+def lookupffn_timing_read_each(which: int) -> list[float]:
+    """Milliseconds of every bracketed launch of kernel `which` since the last reset, in launch order."""
+    _, cnt = lookupffn_timing_read(which)
+    buf = (ctypes.c_double * max(cnt, 1))()
+    got = ctypes.c_int64(0)
+    _check(lib().lookupffn_timing_read_each(which, buf, cnt, ctypes.byref(got)))
+    return list(buf[:min(cnt, got.value)])
 
 
 def lookupffn_timing_read(which: int) -> tuple[float, int]:

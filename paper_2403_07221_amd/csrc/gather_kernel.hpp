@@ -42,7 +42,13 @@ struct GatherArgs {
     int ntb;           // token blocks in total; a token block = kGatherWaves * (64/LPT) tokens
     int xcd_mode;      // 1: block order is XCD-sliced (see above); 0: plain
     int codes_vec8;    // 1: k % 8 == 0 and codes (and weights) 16-byte aligned -> read 8 at a time
-    uint32_t row_bytes;
+    // The 16-byte piece q of row r = (j << tau) + code in slice s sits at
+    //   tables + (s / spp) * slice_stride + (s % spp) * LPT*16 + r * row_stride + q*16
+    // row-major tables: spp = 1, slice_stride = LPT*16, row_stride = bytes of a row; prepared tables
+    // (slice-major, PW bytes per row piece): spp = PW / (LPT*16), slice_stride = k * rows * PW, row_stride = PW.
+    uint32_t row_stride;
+    uint32_t spp;
+    unsigned long long slice_stride;
 };
 
 template <bool BF16>
@@ -137,9 +143,10 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a)
     if (t >= a.n || vec >= a.nvec) return;  // no barrier below: early exit is safe
 
     const uint16_t *crow = a.codes + t * a.k;
-    const char *tcol = a.tables + (size_t)vec * 16;
+    const char *tcol = a.tables + (size_t)((unsigned)slice / a.spp) * (size_t)a.slice_stride +
+                       (size_t)((unsigned)slice % a.spp) * (LPT * 16u) + (size_t)(lane % LPT) * 16u;
     const uint32_t rmask = (1u << a.tau) - 1u;
-    const uint32_t row_bytes = a.row_bytes;
+    const uint32_t row_bytes = a.row_stride;
     const int k = a.k, tau = a.tau;
 
     auto row = [&](int j, uint32_t code) -> uint4 {

@@ -1,15 +1,16 @@
-// LDS-staged gather for small tables (tau <= 8):
+// LDS-staged gather for tables of 2^7 .. 2^10 rows (k even, fp32 rows):
 //   y[t][:] = sum_{j<k} tables[j][code[t][j]][:]        (Sec. 3.1, eq. "lookup")
 //
 // With tau = 8 a table has only 256 rows, so a batch of thousands of tokens
-// picks every row many times.  A 1024-thread workgroup owns one 128-byte
-// column slice and a chunk of up to 128*TOK tokens.  Tables are taken two at a
-// time ("a stage"): the slice of all 2^tau rows of both tables (64 KB at
-// tau = 8) is copied into LDS once by global_load_lds (memory -> LDS without a
+// picks every row many times.  A 1024-thread workgroup owns one column slice
+// (128 bytes of every row up to tau = 8 or 9, 64 bytes from tau = 8 or 9 on)
+// and a chunk of tokens.  Tables are taken one stage at a time: the slice of
+// all 2^tau rows of two tables (one table when it fills a 64 KB buffer) is copied
+// into LDS once by global_load_lds (memory -> LDS without a
 // trip through registers), double-buffered so that stage s+1 streams in while
 // stage s is consumed.  Every (token, 16-byte piece) lane then reads its
-// selected row from LDS with one ds_read_b128 (eight consecutive lanes read one
-// contiguous 128-byte row piece) and adds it to its fp32 accumulators.  Each
+// selected row from LDS with one ds_read_b128 (the lanes of a token read one
+// contiguous row piece) and adds it to its fp32 accumulators.  Each
 // output element is still the sequential fp32 sum over j = 0..k-1, so results
 // equal the direct kernel's bit for bit, while the L2 -> CU traffic drops from
 // one row per (token, table) to one row per (chunk, table, row).
@@ -31,9 +32,9 @@
 // accumulated with one fused multiply-add per element.
 //
 // bf16 tables: the staged copy is fp32.  Widening inside this kernel (per stage and workgroup, through
-// registers and LDS writes) measured no faster than the direct kernel, so for large batches the host
-// first widens the whole table set once per call into scratch memory (widen_tables_kernel below, exact:
-// a bf16 is the upper half of an fp32) and runs this kernel on the copy.
+// registers and LDS writes) measured no faster than the direct kernel, and the tables are learned
+// constants, so the widening happens once, outside the forward pass: prepare_tables_kernel (below) writes an
+// fp32, slice-major copy that this kernel and the direct kernel read.
 //
 // Work distribution is static and XCD-aware: slice-units are dealt to the
 // eight XCDs round-robin (block b runs on XCD b % 8), and the workgroups of
@@ -67,9 +68,11 @@ constexpr int kLdsMaxTok = 16;               // token slots per lane the packed 
 
 struct GatherLdsArgs {
     const uint32_t *packed;  // [k/2][n_pad] packed codes (see hash_kernel.hpp)
-    const float *wpk;        // [k/2][n_pad][2] weights, the two tables of a stage adjacent (weighted form only)
+    const float *wpk;        // weighted form: [k][n_pad] weights, table-major (wpk_index); multi-probe form:
+                             // [k][1+tau][n_pad] shares.  The token padding [n, n_pad) is never initialised:
+                             // slots past a chunk's end multiply it into accumulators that are never stored.
     long long n_pad;
-    const char *tables;
+    const char *tables;      // fp32 rows, row-major [k][rows][d_out] or the slice-major prepared layout
     float *y;
     long long n;
     int k, tau, d_out;
@@ -78,7 +81,15 @@ struct GatherLdsArgs {
     int token_splits;   // a unit = (slice, one of token_splits equal token ranges)
     int n_units;        // n_slices * token_splits
     int blocks_per_xcd; // gridDim.x / kXcds
-    uint32_t row_bytes;
+    // Where the piece (slice, table j, row r, 16-byte piece q) lives:
+    //   tables + (slice / spp) * slice_stride + (slice % spp) * SW*16 + j * table_stride + r * row_stride + q*16
+    // row-major tables: spp = 1, slice_stride = SW*16, row_stride = d_out*4, table_stride = rows * row_stride;
+    // prepared tables (one slice of all tables contiguous, PW bytes per row piece): spp = PW / (SW*16),
+    // slice_stride = k * rows * PW, row_stride = PW, table_stride = rows * PW.
+    uint32_t row_stride;
+    uint32_t spp;
+    unsigned long long table_stride;
+    unsigned long long slice_stride;
 };
 
 // bytes of LDS the kernel needs: two buffers (sw = lanes per token)
@@ -102,10 +113,15 @@ __device__ __forceinline__ uint32_t split_at(uint32_t len, uint32_t parts, uint3
 __device__ __forceinline__ void lds_dma16(const char *gbase, uint32_t voff, uint32_t lds_base)
 {
     const uint32_t m = __builtin_amdgcn_readfirstlane(lds_base);
+    // M0 is written here, so it is named as clobbered: the compiler then keeps none of its own M0
+    // values live across the statement (it warns that M0 is a reserved register; that is the point).
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 1\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
                  : "s"(m), "v"(voff), "s"(gbase)
-                 : "memory");
+                 : "memory", "m0");
+#pragma clang diagnostic pop
 }
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -209,13 +225,15 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
         // Lanes whose piece lies outside the row (ragged last slice) copy piece 0 instead: they
         // never store a result, and this keeps the copy free of divergent control flow.
         // Offsets inside one table fit 32 bits.
-        const uint32_t foff = g * a.row_bytes + (vec_ok ? vec : 0u) * 16u;
-        const size_t table_stride = (size_t)rows * a.row_bytes;
+        const uint32_t foff = g * a.row_stride + (vec_ok ? q : 0u) * 16u;
+        const size_t table_stride = (size_t)a.table_stride;
+        const char *slice_base = a.tables + (size_t)(slice / a.spp) * (size_t)a.slice_stride +
+                                 (size_t)(slice % a.spp) * PIECE;  // uniform
         // piece idx = table-in-stage * FR + round, of stage s, into buffer b
         auto fill_piece = [&](uint32_t s, uint32_t b, int idx) {
             const uint32_t tb = (uint32_t)idx / FR, f = (uint32_t)idx % FR;
-            const char *tsrc = a.tables + (size_t)(s * TPS + tb) * table_stride +
-                               (size_t)f * G * a.row_bytes;  // uniform
+            const char *tsrc = slice_base + (size_t)(s * TPS + tb) * table_stride +
+                               (size_t)f * G * a.row_stride;  // uniform
             lds_dma16(tsrc, foff, lds0 + b * buf_bytes + tb * tbl_bytes + (f * kLdsThreads + wave * 64u) * 16u);
         };
 
@@ -528,14 +546,35 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
 }
 
 #if !defined(LFFN_PART) || LFFN_PART == 0  // a plain function: defined by part 0 only of a build in parts
-// bf16 -> fp32, 8 elements per thread and step (n8 = element count / 8; both buffers 16-byte aligned)
-__global__ __launch_bounds__(256) void widen_tables_kernel(const uint4 *src, uint4 *dst, long long n8)
+// One-time re-layout of the learned tables T_j (Sec. 3.1, eq. "lookup") for the gather kernels: fp32
+// elements (bf16 rows widened exactly: a bf16 is the upper half of an fp32), slice-major,
+//   dst[ps][j][row][PW bytes],  ps < ceil(d_out*4 / PW),
+// so that the column slice of ALL tables a workgroup streams is one contiguous run.  Pieces past the end
+// of a row (ragged last slice) are zero.  One 16-byte output piece per thread and step.
+//   nvec = d_out / 4 (pieces per fp32 row), ppw = PW / 16, n_out = output pieces in total
+__global__ __launch_bounds__(256) void prepare_tables_kernel(const void *src, uint4 *dst, int k, int rows, int nvec,
+                                                             int ppw, int bf16, long long n_out)
 {
-    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n8;
-         i += (long long)gridDim.x * blockDim.x) {
-        const uint4 w = src[i];
-        dst[2 * i] = make_uint4(w.x << 16, w.x & 0xFFFF0000u, w.y << 16, w.y & 0xFFFF0000u);
-        dst[2 * i + 1] = make_uint4(w.z << 16, w.z & 0xFFFF0000u, w.w << 16, w.w & 0xFFFF0000u);
+    for (long long o = (long long)blockIdx.x * blockDim.x + threadIdx.x; o < n_out;
+         o += (long long)gridDim.x * blockDim.x) {
+        const int p = (int)(o % ppw);
+        long long rest = o / ppw;
+        const int row = (int)(rest % rows);
+        rest /= rows;
+        const int j = (int)(rest % k);
+        const long long ps = rest / k;
+        const long long vec = ps * ppw + p;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (vec < nvec) {
+            const long long piece = ((long long)j * rows + row) * nvec + vec;
+            if (bf16) {
+                const uint2 w = static_cast<const uint2 *>(src)[piece];
+                v = make_uint4(w.x << 16, w.x & 0xFFFF0000u, w.y << 16, w.y & 0xFFFF0000u);
+            } else {
+                v = static_cast<const uint4 *>(src)[piece];
+            }
+        }
+        dst[o] = v;
     }
 }
 #endif

@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <map>
@@ -31,8 +32,16 @@ namespace lffn_host {
 using namespace lffn;
 int hip_fail(hipError_t e, const char *what);  // part 0
 int allow_lds(const void *kern, size_t lds);   // part 0
+// While an AttrOnly object lives on this thread, the launchers of kernels that need more than 64 KB of LDS
+// only register that need with the runtime and launch nothing (lookupffn_init).
+bool attr_only();                              // part 0
+struct AttrOnly {
+    AttrOnly();
+    ~AttrOnly();
+};
 // part 1: the direct gather kernel
 int gather_direct_part(bool bf16, int lpt, const GatherArgs &a, bool probes, dim3 grid, hipStream_t s);
+int gather_direct_load();  // makes the runtime load part 1's code object now (lookupffn_init)
 // parts 2, 3: the LDS-staged gather kernel (plain sum; weighted and multi-probe)
 int gather_lds_plain_part(int tok, const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s);
 int gather_lds_weighted_part(int tok, const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s);
@@ -66,7 +75,8 @@ using lffn_host::hip_fail;
 constexpr int kVersion = 100;  // 0.1.0
 constexpr int kMaxLog2N = 12;  // d_pad <= 4096
 thread_local std::string g_hip_error;
-const char *g_last_gather = "";  // name of the gather kernel the most recent launch used
+thread_local const char *t_last_gather = "";  // name of the gather kernel this thread's most recent launch used
+thread_local int t_attr_only = 0;
 #endif
 
 // ---------------------------------------------------------------- kernel launchers (templates: every part may use them)
@@ -102,7 +112,7 @@ int launch_gather_lds_fr(const GatherLdsArgs &a, dim3 grid, size_t lds, hipStrea
 {
     auto kern = gather_lds_kernel<TOK, FR, WEIGHTED, SW, PROBES>;
     int rc = allow_lds(reinterpret_cast<const void *>(kern), lds);
-    if (rc != LFFN_OK) return rc;
+    if (rc != LFFN_OK || lffn_host::attr_only()) return rc;
     hipLaunchKernelGGL(kern, grid, dim3(kLdsThreads), lds, s, a);
     return LFFN_OK;
 }
@@ -146,7 +156,7 @@ int launch_bh_k(const BhArgs &a, dim3 grid, size_t lds, hipStream_t s)
 {
     auto kern = bh_hash_kernel<L, TB, VEC4, WEIGHTED>;
     int rc = allow_lds(reinterpret_cast<const void *>(kern), lds);
-    if (rc != LFFN_OK) return rc;
+    if (rc != LFFN_OK || lffn_host::attr_only()) return rc;
     hipLaunchKernelGGL(kern, grid, dim3(kBhThreads), lds, s, a);
     return LFFN_OK;
 }
@@ -178,6 +188,13 @@ namespace lffn_host {
 int gather_direct_part(bool bf16, int lpt, const GatherArgs &a, bool probes, dim3 grid, hipStream_t s)
 {
     return bf16 ? launch_gather_lpt<true>(lpt, a, probes, grid, s) : launch_gather_lpt<false>(lpt, a, probes, grid, s);
+}
+
+int gather_direct_load()
+{
+    hipFuncAttributes attr;
+    hipError_t e = hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(gather_kernel<false, 8, 0>));
+    return e == hipSuccess ? LFFN_OK : hip_fail(e, "hipFuncGetAttributes(gather_kernel)");
 }
 #endif
 
@@ -287,6 +304,10 @@ int hip_fail(hipError_t e, const char *what)
     return LFFN_E_HIP;
 }
 
+bool attr_only() { return t_attr_only > 0; }
+AttrOnly::AttrOnly() { ++t_attr_only; }
+AttrOnly::~AttrOnly() { --t_attr_only; }
+
 // kernels that use more than 64 KB of dynamic LDS must be told so, once per device and kernel
 int allow_lds(const void *kern, size_t lds)
 {
@@ -309,7 +330,6 @@ int allow_lds(const void *kern, size_t lds)
 #if LFFN_HAS(0)  // ================ everything below: host logic and the C ABI ================
 namespace {
 
-
 int log2_pad(int d)
 {
     int l = 0;
@@ -319,8 +339,12 @@ int log2_pad(int d)
 
 bool dtype_ok(int t) { return t == LFFN_F32 || t == LFFN_BF16; }
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+int gcd(int a, int b) { return b ? gcd(b, a % b) : a; }
+int64_t round256(int64_t b) { return (b + 255) & ~int64_t(255); }
 
 // ---------------------------------------------------------------- options
+// Tuning knobs (lookupffn_set_option).  Every entry point takes one snapshot at its start, so a
+// concurrent lookupffn_set_option can change which kernel the NEXT call runs, never a call in flight.
 struct Options {
     int lanes_per_token = 0;  // 0 = default
     int xcd_order = 0;        // 0 = default, 1 = on, -1 = off
@@ -329,11 +353,19 @@ struct Options {
     int hash_blocks = 0;      // 0 = default grid cap of the d_pad = 1024 hash kernel
     int slice_lanes = 0;      // 0 = choose, 4 = 64-byte column slices in the staged gather where possible
     int token_slots = 0;      // 0 = choose, else the most token slots per lane of the staged gather
-} g_opt;
+};
+std::mutex g_opt_mu;
+Options g_opt;
+Options options_snapshot()
+{
+    std::lock_guard<std::mutex> lk(g_opt_mu);
+    return g_opt;
+}
 
 // ---------------------------------------------------------------- timing
 struct Timing {
-    int on = 0;  // bit 0: time hash launches, bit 1: time gather launches
+    std::mutex mu;
+    std::atomic<int> on{0};  // bit 0: time hash launches, bit 1: time gather launches
     std::vector<std::pair<hipEvent_t, hipEvent_t>> ev[2];
     std::vector<std::pair<hipEvent_t, hipEvent_t>> pool;
 } g_tm;
@@ -342,33 +374,41 @@ struct TimedLaunch {
     int which;
     hipStream_t s;
     hipEvent_t a = nullptr, b = nullptr;
-    bool ok = true;
-    bool active() const { return (g_tm.on >> which) & 1; }
-    TimedLaunch(int which_, hipStream_t s_) : which(which_), s(s_)
+    bool on;
+    TimedLaunch(int which_, hipStream_t s_) : which(which_), s(s_), on((g_tm.on.load() >> which_) & 1)
     {
-        if (!active()) return;
-        if (!g_tm.pool.empty()) {
-            a = g_tm.pool.back().first;
-            b = g_tm.pool.back().second;
-            g_tm.pool.pop_back();
-        } else if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
-            ok = false;
+        if (!on) return;
+        {
+            std::lock_guard<std::mutex> lk(g_tm.mu);
+            if (!g_tm.pool.empty()) {
+                a = g_tm.pool.back().first;
+                b = g_tm.pool.back().second;
+                g_tm.pool.pop_back();
+            }
+        }
+        if (!a && (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess)) {
+            on = false;
             return;
         }
-        ok = hipEventRecord(a, s) == hipSuccess;
+        on = hipEventRecord(a, s) == hipSuccess;
     }
     void done()
     {
-        if (!active() || !a || !b) return;
+        if (!on || !a || !b) return;
         (void)hipEventRecord(b, s);
+        std::lock_guard<std::mutex> lk(g_tm.mu);
         g_tm.ev[which].emplace_back(a, b);
     }
 };
 
-// ---------------------------------------------------------------- library-owned workspace
+// ---------------------------------------------------------------- library-owned workspace (workspace == NULL)
+// Grow-only: a larger request allocates a new buffer and keeps the old ones until
+// lookupffn_release_workspace(), so work already enqueued (or captured) with an old buffer stays valid and
+// nothing synchronises.
 struct Workspace {
     void *ptr = nullptr;
     size_t bytes = 0;
+    std::vector<void *> retired;
 };
 std::mutex g_ws_mu;
 std::map<int, Workspace> g_ws;
@@ -380,18 +420,78 @@ int own_workspace(size_t need, void **out)
     std::lock_guard<std::mutex> lk(g_ws_mu);
     Workspace &w = g_ws[dev];
     if (w.bytes < need) {
-        if (w.ptr) {
-            LFFN_HIP(hipDeviceSynchronize());
-            LFFN_HIP(hipFree(w.ptr));
-            w.ptr = nullptr;
-            w.bytes = 0;
-        }
-        size_t sz = (need + (size_t(1) << 20) - 1) & ~((size_t(1) << 20) - 1);
-        LFFN_HIP(hipMalloc(&w.ptr, sz));
+        const size_t sz = (need + (size_t(1) << 20) - 1) & ~((size_t(1) << 20) - 1);
+        void *p = nullptr;
+        LFFN_HIP(hipMalloc(&p, sz));
+        if (w.ptr) w.retired.push_back(w.ptr);
+        w.ptr = p;
         w.bytes = sz;
     }
     *out = w.ptr;
     return LFFN_OK;
+}
+
+// A call's scratch memory, handed out front to back in 256-byte aligned pieces.
+struct Scratch {
+    char *base = nullptr;
+    int64_t bytes = 0, used = 0;
+    template <class T>
+    T *take(int64_t n)
+    {
+        n = round256(n);
+        if (!base || used + n > bytes) return nullptr;
+        T *p = reinterpret_cast<T *>(base + used);
+        used += n;
+        return p;
+    }
+};
+
+// Resolves the (workspace, workspace_bytes) pair of an entry point: the caller's buffer, or the library's.
+int get_scratch(void *workspace, int64_t workspace_bytes, int64_t need, Scratch *sc)
+{
+    if (workspace) {
+        if (workspace_bytes < need) return LFFN_E_WORKSPACE;
+        if (!aligned(workspace, 256)) return LFFN_E_ALIGN;
+        sc->base = static_cast<char *>(workspace);
+        sc->bytes = workspace_bytes;
+        return LFFN_OK;
+    }
+    if (need == 0) return LFFN_OK;
+    void *p = nullptr;
+    int rc = own_workspace((size_t)need, &p);
+    if (rc != LFFN_OK) return rc;
+    sc->base = static_cast<char *>(p);
+    sc->bytes = need;
+    return LFFN_OK;
+}
+
+// ---------------------------------------------------------------- tables: row-major or prepared
+// Bytes per row piece of the prepared (slice-major) layout: 128 up to tau = 8 (the staged gather's
+// 128-byte column slices; its 64-byte form reads half pieces), 64 from tau = 9 on.
+int prepared_piece_bytes(int tau) { return tau <= 8 ? 128 : 64; }
+
+struct TableRef {
+    const char *p = nullptr;
+    bool bf16 = false;      // element type of the buffer the kernels read (prepared tables are always fp32)
+    bool prepared = false;
+    int pw = 0;             // prepared: bytes per row piece
+};
+
+TableRef table_ref(const void *tables, int table_dtype, int tau)
+{
+    TableRef t;
+    t.p = static_cast<const char *>(tables);
+    t.prepared = (table_dtype & LFFN_PREPARED) != 0;
+    t.bf16 = !t.prepared && (table_dtype & 0xFF) == LFFN_BF16;
+    t.pw = t.prepared ? prepared_piece_bytes(tau) : 0;
+    return t;
+}
+
+int64_t prepared_tables_bytes(int k, int tau, int d_out)
+{
+    const int64_t pw = prepared_piece_bytes(tau);
+    const int64_t n_ps = ((int64_t)d_out * 4 + pw - 1) / pw;
+    return round256(n_ps * k * (int64_t(1) << tau) * pw);
 }
 
 // ---------------------------------------------------------------- validation
@@ -425,11 +525,12 @@ int check_gather(const uint16_t *codes, const void *tables, const float *y, int6
     if (!codes || !tables || !y) return LFFN_E_NULL;
     if (n < 0 || k < 1 || d_out < 1) return LFFN_E_SIZE;
     if (tau < 1 || tau > 16) return LFFN_E_TAU;
-    if (!dtype_ok(table_dtype)) return LFFN_E_DTYPE;
+    if ((table_dtype & ~(0xFF | LFFN_PREPARED)) != 0 || !dtype_ok(table_dtype & 0xFF)) return LFFN_E_DTYPE;
     if (k > (1 << 20) || n > (int64_t(1) << 40) || d_out > (1 << 24)) return LFFN_E_SIZE;
-    const int w = table_dtype == LFFN_F32 ? 4 : 8;
+    const int w = (table_dtype & 0xFF) == LFFN_F32 ? 4 : 8;
     if (d_out % w != 0) return LFFN_E_ALIGN;
-    if (!aligned(tables, 16) || !aligned(y, 16) || !aligned(codes, 2)) return LFFN_E_ALIGN;
+    const size_t ta = (table_dtype & LFFN_PREPARED) ? 256 : 16;
+    if (!aligned(tables, ta) || !aligned(y, 16) || !aligned(codes, 2)) return LFFN_E_ALIGN;
     // row index (j << tau) + code must fit 32 bits
     if (((int64_t)k << tau) > (int64_t(1) << 31)) return LFFN_E_SIZE;
     return LFFN_OK;
@@ -458,21 +559,46 @@ void launch_hash1024_t(const HashArgs &a, bool probes, dim3 grid, size_t lds, hi
         hipLaunchKernelGGL((hash1024_kernel<R, 0>), grid, dim3(kHashThreads), lds, s, a);
 }
 
-// Writes codes[n][k] when `codes` is given, else the packed layout of the LDS-staged gather;
-// with `weights` also the gather weights of the weighted variant ([n][k] beside `codes`,
-// table-major [k][n_pad] beside `packed`).
-int launch_hash(const void *x, const int8_t *signs, uint16_t *codes, uint32_t *packed, float *weights, int64_t n,
-                int d, int k, int tau, int n_rounds, int x_dtype, hipStream_t s, bool probes = false)
+// What a hash launch writes: codes[n][k] (and weights[n][k], or shares[n][k][1+tau] with `probes`), or --
+// when `codes` is NULL -- the staged gather's packed codes (and table-major weights wpk[k][n_pad]).
+struct HashOut {
+    uint16_t *codes = nullptr;
+    uint32_t *packed = nullptr;
+    float *weights = nullptr;  // beside `codes`: [n][k] or [n][k][1+tau]; beside `packed`: wpk[k][n_pad]
+    bool probes = false;
+};
+
+// Host-side extent check of one hash launch: every index the kernels form from (n, k, tau, n_pad)
+// stays inside the buffers the caller of launch_hash carved out.  `cap_*` are the byte sizes of the
+// regions behind out.codes / out.packed / out.weights (0 = unknown: a caller-owned ABI output).
+bool hash_extents_ok(const HashOut &o, int64_t n, int k, int tau, int64_t n_pad, int64_t cap_codes,
+                     int64_t cap_packed, int64_t cap_weights)
+{
+    if (o.codes) {
+        if (cap_codes && n * k * 2 > cap_codes) return false;
+        const int64_t per = o.probes ? (int64_t)k * (tau + 1) : k;
+        if (o.weights && cap_weights && n * per * 4 > cap_weights) return false;
+        return true;
+    }
+    // packed[s * n_pad + t], s < k/2, t < n_pad;  wpk[j * n_pad + t], j < k, t < n
+    if (n_pad < n) return false;
+    if (cap_packed && (int64_t)(k / 2) * n_pad * 4 > cap_packed) return false;
+    if (o.weights && cap_weights && ((int64_t)(k - 1) * n_pad + n) * 4 > cap_weights) return false;
+    return true;
+}
+
+int launch_hash(const void *x, const int8_t *signs, const HashOut &out, int64_t n, int d, int k, int tau,
+                int n_rounds, int x_dtype, hipStream_t s, const Options &opt)
 {
     const int L = log2_pad(d);
     const int N = 1 << L;
-    HashArgs a;
+    HashArgs a{};
     a.x = x;
     a.signs = signs;
-    a.codes = codes;
-    a.packed = codes ? nullptr : packed;
-    a.weights = codes ? weights : nullptr;
-    a.wpk = codes ? nullptr : weights;
+    a.codes = out.codes;
+    a.packed = out.codes ? nullptr : out.packed;
+    a.weights = out.codes ? out.weights : nullptr;
+    a.wpk = out.codes ? nullptr : out.weights;
     a.n_pad = packed_n_pad(n);
     a.n = n;
     a.d = d;
@@ -482,24 +608,26 @@ int launch_hash(const void *x, const int8_t *signs, uint16_t *codes, uint32_t *p
     a.P = (int)(((int64_t)k * tau + N - 1) / N);
     a.x_bf16 = x_dtype == LFFN_BF16;
     a.scale = (float)(1.0 / std::sqrt((double)N));
+    if (!a.codes && !a.packed) return LFFN_E_NULL;
+    if (out.probes && (!a.codes || !a.weights)) return LFFN_E_UNSUPPORTED;  // shares exist in the ABI layout only
     TimedLaunch tl(0, s);
     // d_pad = 1024 with up to four rounds: the two-layout kernel (needs 16-byte aligned signs, and
     // rows that start on 16-byte boundaries when it loads them as vectors)
     const size_t xrow = (size_t)d * (a.x_bf16 ? 2 : 4);
-    const bool weighted = weights != nullptr;
-    if (g_opt.hash_path != 1 && L == 10 && n_rounds <= 4 && aligned(signs, 16) &&
+    const bool weighted = out.weights != nullptr;
+    if (opt.hash_path != 1 && L == 10 && n_rounds <= 4 && aligned(signs, 16) &&
         h1024_lds_bytes(a.P, weighted) <= 64 * 1024 &&
         (d % 4 != 0 || (aligned(x, 16) && xrow % (a.x_bf16 ? 8 : 16) == 0))) {
         int64_t blocks = (n + kHashWaves - 1) / kHashWaves;
-        const int64_t cap = g_opt.hash_blocks ? g_opt.hash_blocks : 4096;
+        const int64_t cap = opt.hash_blocks ? opt.hash_blocks : 4096;
         if (blocks > cap) blocks = cap;
         const dim3 grid((unsigned)blocks);
         const size_t lds = h1024_lds_bytes(a.P, weighted);
         switch (n_rounds) {
-            case 1: launch_hash1024_t<1>(a, probes, grid, lds, s); break;
-            case 2: launch_hash1024_t<2>(a, probes, grid, lds, s); break;
-            case 3: launch_hash1024_t<3>(a, probes, grid, lds, s); break;
-            default: launch_hash1024_t<4>(a, probes, grid, lds, s); break;
+            case 1: launch_hash1024_t<1>(a, out.probes, grid, lds, s); break;
+            case 2: launch_hash1024_t<2>(a, out.probes, grid, lds, s); break;
+            case 3: launch_hash1024_t<3>(a, out.probes, grid, lds, s); break;
+            default: launch_hash1024_t<4>(a, out.probes, grid, lds, s); break;
         }
         LFFN_HIP(hipGetLastError());
         tl.done();
@@ -510,7 +638,7 @@ int launch_hash(const void *x, const int8_t *signs, uint16_t *codes, uint32_t *p
     if (blocks > 2048) blocks = 2048;
     const dim3 grid((unsigned)blocks);
     switch (L) {
-#define LFFN_CASE(l) case l: launch_hash_t<l>(a, probes, grid, lds, s); break;
+#define LFFN_CASE(l) case l: launch_hash_t<l>(a, out.probes, grid, lds, s); break;
         LFFN_CASE(0) LFFN_CASE(1) LFFN_CASE(2) LFFN_CASE(3) LFFN_CASE(4) LFFN_CASE(5) LFFN_CASE(6)
         LFFN_CASE(7) LFFN_CASE(8) LFFN_CASE(9) LFFN_CASE(10) LFFN_CASE(11) LFFN_CASE(12)
 #undef LFFN_CASE
@@ -520,9 +648,6 @@ int launch_hash(const void *x, const int8_t *signs, uint16_t *codes, uint32_t *p
     tl.done();
     return LFFN_OK;
 }
-
-int gcd(int a, int b) { return b ? gcd(b, a % b) : a; }
-int64_t round256(int64_t b) { return (b + 255) & ~int64_t(255); }
 
 constexpr int kLdsMinBytes = 84 * 1024;  // more than half of the 160 KB LDS: one workgroup per CU
 
@@ -553,10 +678,12 @@ int64_t lds_tokens_per_block(int64_t n, int n_units, int token_splits, int Bx)
     return (unit_tokens + blocks - 1) / blocks;
 }
 
+enum Mode { kPlain = 0, kWeighted = 1, kProbes = 2 };
+
 // Launch shape of the LDS-staged gather for one problem size (no pointers involved).
 struct LdsPlan {
     bool use = false;
-    GatherLdsArgs a;
+    GatherLdsArgs a{};
     int tok = 0;
     int sw = 8;     // lanes per token: 8 = 128-byte column slices, 4 = 64-byte ones
     int fr = 1;     // 16 KB copy rounds per table slice
@@ -564,32 +691,25 @@ struct LdsPlan {
                     // write shift 7; a plan with shift 6 takes its codes through the re-pack kernel.
     unsigned grid = 0;
     size_t lds = 0;
-    bool widen = false;        // bf16 tables: the kernel reads an fp32 copy made first in `widened`
-    int64_t widen_bytes = 0;   // size of that copy
-    void *widened = nullptr;   // set by the entry point once it has the scratch memory
 };
 
-// `can_widen`: the caller can provide scratch memory for an fp32 copy of bf16 tables (the staged kernel
-// reads fp32 rows only).
-int plan_gather_lds(int64_t n, int k, int tau, int d_out, bool bf16, LdsPlan *p, bool weighted = false,
-                    bool probes = false, bool can_widen = false)
+int plan_gather_lds(int64_t n, int k, int tau, int d_out, const TableRef &T, Mode mode, const Options &opt,
+                    LdsPlan *p)
 {
-    (void)weighted;
     p->use = false;
-    p->widen = false;
-    p->widen_bytes = 0;
-    p->widened = nullptr;
-    if (g_opt.gather_path == 1) return LFFN_OK;
-    if (bf16 && !can_widen) return LFFN_OK;
+    if (opt.gather_path == 1) return LFFN_OK;
+    if (T.bf16) return LFFN_OK;  // the staged kernel reads fp32 rows: bf16 tables take it once prepared
     const int rows = 1 << tau;
     if (tau < 7 || tau > 10 || k % 2 != 0) return LFFN_OK;
     // column slices: 128 bytes (8 lanes per token) up to tau = 8; 64 bytes from tau = 9 on (two 512-row
     // tables per stage and half the copy volume per token measured faster than one per stage; tau = 10
-    // fits a 64 KB buffer only this way).  The 64-byte form exists for fp32 tables and tau >= 8.
+    // fits a 64 KB buffer only this way).  The 64-byte form exists for tau >= 8.
     int sw = tau <= 8 ? 8 : 4;
-    if (g_opt.slice_lanes == 4 && tau >= 8) sw = 4;
-    if (g_opt.slice_lanes == 8 && tau <= 9) sw = 8;
-    if (probes) sw = tau <= 8 ? 8 : 4;  // the multi-probe form is built for these pairings only
+    if (opt.slice_lanes == 4 && tau >= 8) sw = 4;
+    if (opt.slice_lanes == 8 && tau <= 9) sw = 8;
+    if (mode == kProbes) sw = tau <= 8 ? 8 : 4;  // the multi-probe form is built for these pairings only
+    if (T.prepared && sw * 16 > T.pw) sw = T.pw / 16;  // a token's row piece must lie inside one prepared piece
+    if (sw == 4 && tau < 8) return LFFN_OK;
     const int groups = kLdsThreads / sw;
     // the kernel indexes tokens and bytes inside one table with 32 bits
     if (n >= (int64_t(1) << 31) - 4096 || (int64_t)rows * d_out * 4 >= (int64_t(1) << 32)) return LFFN_OK;
@@ -598,31 +718,41 @@ int plan_gather_lds(int64_t n, int k, int tau, int d_out, bool bf16, LdsPlan *p,
     if (rc != LFFN_OK) return rc;
     if (cus < kXcds || cus % kXcds != 0) return LFFN_OK;
     GatherLdsArgs &a = p->a;
+    a = GatherLdsArgs{};
     a.n = n;
     a.n_pad = packed_n_pad(n);
     a.k = k;
     a.tau = tau;
     a.d_out = d_out;
-    a.row_bytes = (uint32_t)d_out * 4;  // of the fp32 rows the kernel reads
-    a.nvec = (int)(a.row_bytes / 16);
+    const uint32_t row_bytes = (uint32_t)d_out * 4;  // of the fp32 rows the kernel reads
+    a.nvec = (int)(row_bytes / 16);
     a.n_slices = (a.nvec + sw - 1) / sw;
     a.token_splits = kXcds / gcd(a.n_slices, kXcds);
     a.n_units = a.n_slices * a.token_splits;
     a.blocks_per_xcd = cus / kXcds;
+    if (T.prepared) {
+        a.spp = (uint32_t)(T.pw / (sw * 16));
+        a.row_stride = (uint32_t)T.pw;
+        a.table_stride = (unsigned long long)rows * T.pw;
+        a.slice_stride = (unsigned long long)k * rows * T.pw;
+    } else {
+        a.spp = 1;
+        a.row_stride = row_bytes;
+        a.table_stride = (unsigned long long)rows * row_bytes;
+        a.slice_stride = (unsigned long long)sw * 16;
+    }
     const int64_t tpb = lds_tokens_per_block(n, a.n_units, a.token_splits, a.blocks_per_xcd);
     int tok_max = sw == 4 ? 16 : 13;
     // the multi-probe form holds a share per probe beside the accumulators: 13 slots spill in its
     // hot loop, 8 measured faster up to tau = 9 (tau = 10 has 16 copy rounds per table to amortise)
-    if (probes && tau <= 9) tok_max = 8;
-    if (g_opt.token_slots && g_opt.token_slots < tok_max) tok_max = g_opt.token_slots;
+    if (mode == kProbes && tau <= 9) tok_max = 8;
+    if (opt.token_slots && opt.token_slots < tok_max) tok_max = opt.token_slots;
     const int64_t nchunks = (tpb + (int64_t)groups * tok_max - 1) / ((int64_t)groups * tok_max);
     const int64_t chunk = (tpb + nchunks - 1) / nchunks;
-    // Staging pays only when a chunk re-uses each staged row a few times; with bf16 tables the whole
-    // table set is widened first (6 bytes moved per element), which a batch of 64 tokens per row repays
-    // (configuration 3's shape at 16384 tokens: 108 us against 124 us direct; at 8192 the direct kernel wins).
-    if (g_opt.gather_path != 2 && (chunk < 2 * (int64_t)rows || (bf16 && n < 64 * (int64_t)rows))) return LFFN_OK;
+    // Staging pays only when a chunk re-uses each staged row a few times.
+    if (opt.gather_path != 2 && chunk < 2 * (int64_t)rows) return LFFN_OK;
     p->tok = (int)((chunk + groups - 1) / groups);
-    if (probes && sw == 8 && p->tok > 8) p->tok = 13;  // multi-probe form: 4, 8 or 13 slots
+    if (mode == kProbes && sw == 8 && p->tok > 8) p->tok = 13;  // multi-probe form: 4, 8 or 13 slots
     if (sw == 4) p->tok = p->tok > 13 ? 16 : p->tok > 8 ? 13 : 8;  // the 64-byte form is built for 8, 13 and 16 token slots
     p->sw = sw;
     p->fr = rows / groups;
@@ -630,95 +760,103 @@ int plan_gather_lds(int64_t n, int k, int tau, int d_out, bool bf16, LdsPlan *p,
     p->lds = gather_lds_bytes(tau, sw);
     if (p->lds < (size_t)kLdsMinBytes) p->lds = kLdsMinBytes;
     p->grid = (unsigned)cus;
-    p->widen = bf16;
-    p->widen_bytes = bf16 ? round256((int64_t)k * rows * d_out * 4) : 0;
     p->use = true;
     return LFFN_OK;
 }
 
-// After the plan: does the scratch memory at hand have room for the widened tables?  `base` bytes are
-// taken by the call itself.  A caller workspace that is too small for the copy turns the staged kernel
-// off (the direct kernel reads bf16 rows); returns the bytes to add to `base`.
-int64_t widen_room(LdsPlan *p, const void *workspace, int64_t workspace_bytes, int64_t base)
+int64_t packed_bytes(int64_t n, int k) { return round256(((int64_t)(k + 1) / 2) * packed_n_pad(n) * 4); }
+int64_t wpk_bytes(int64_t n, int k) { return round256((int64_t)k * packed_n_pad(n) * 4); }
+int64_t spk_bytes(int64_t n, int k, int tau) { return round256((int64_t)k * (tau + 1) * packed_n_pad(n) * 4); }
+int64_t abi_codes_bytes(int64_t n, int k) { return round256(n * (int64_t)k * 2); }
+int64_t abi_weights_bytes(int64_t n, int k, int tau, Mode m)
 {
-    if (!p->use || !p->widen) return 0;
-    if (workspace && workspace_bytes < base + p->widen_bytes) {
-        p->use = false;
-        return 0;
-    }
-    return p->widen_bytes;
+    return m == kPlain ? 0 : round256(n * (int64_t)k * (m == kProbes ? tau + 1 : 1) * 4);
+}
+// scratch of a stand-alone gather: the staged kernel's packed codes and table-major weights / shares
+int64_t gather_ws_bytes(int64_t n, int k, int tau, Mode m)
+{
+    if (n <= 0) return 0;
+    return packed_bytes(n, k) + (m == kWeighted ? wpk_bytes(n, k) : m == kProbes ? spk_bytes(n, k, tau) : 0);
+}
+// scratch of a forward pass: the hash's ABI-layout outputs and the gather's scratch
+int64_t forward_ws_bytes(int64_t n, int k, int tau, Mode m)
+{
+    if (n <= 0) return 0;
+    return abi_codes_bytes(n, k) + abi_weights_bytes(n, k, tau, m) + gather_ws_bytes(n, k, tau, m);
 }
 
-int launch_gather_lds(const LdsPlan &p, const uint32_t *packed, const float *wpk, const void *tables, float *y,
-                      bool bf16, hipStream_t s, bool probes = false)
+int launch_gather_lds(const LdsPlan &p, const uint32_t *packed, const float *wpk, const TableRef &T, float *y,
+                      Mode mode, hipStream_t s)
 {
     GatherLdsArgs a = p.a;
     a.packed = packed;
     a.wpk = wpk;
-    a.tables = static_cast<const char *>(tables);
+    a.tables = T.p;
     a.y = y;
+    // extents the kernel assumes: rows * copy rounds cover a table exactly, the stage fits its buffer,
+    // token windows of 16 x 256 tokens past any token stay inside the padded code arrays
+    if ((kLdsThreads / p.sw) * p.fr != (1 << a.tau) || a.n_pad < a.n + 16 * 256 || (a.k & 1) || T.bf16 ||
+        (mode != kPlain) != (wpk != nullptr) || !packed)
+        return LFFN_E_UNSUPPORTED;
     const dim3 grid(p.grid);
     int rc = LFFN_E_UNSUPPORTED;
     TimedLaunch tl(1, s);
-    if (p.widen) {
-        if (!bf16 || !p.widened) return LFFN_E_UNSUPPORTED;
-        const long long n8 = (long long)a.k * (1ll << a.tau) * a.d_out / 8;
-        long long wb = (n8 + 255) / 256;
-        if (wb > 8192) wb = 8192;
-        hipLaunchKernelGGL(widen_tables_kernel, dim3((unsigned)wb), dim3(256), 0, s,
-                           static_cast<const uint4 *>(tables), static_cast<uint4 *>(p.widened), n8);
-        LFFN_HIP(hipGetLastError());
-        a.tables = static_cast<const char *>(p.widened);
-    }
-    if (probes)
+    if (mode == kProbes)
         rc = lffn_host::gather_lds_probes_part(p.tok, a, p.fr, p.sw, grid, p.lds, s);
-    else if (wpk)
+    else if (mode == kWeighted)
         rc = lffn_host::gather_lds_weighted_part(p.tok, a, p.fr, p.sw, grid, p.lds, s);
     else
         rc = lffn_host::gather_lds_plain_part(p.tok, a, p.fr, p.sw, grid, p.lds, s);
     if (rc != LFFN_OK) return rc;
     LFFN_HIP(hipGetLastError());
     tl.done();
-    g_last_gather = "gather_lds_kernel";
+    t_last_gather = "gather_lds_kernel";
     return LFFN_OK;
 }
 
-int64_t packed_bytes(int64_t n, int k) { return ((int64_t)(k + 1) / 2) * packed_n_pad(n) * 4; }
-int64_t probes_spk_bytes(int64_t n, int k, int tau) { return round256((int64_t)k * (tau + 1) * packed_n_pad(n) * 4); }
-
-int launch_gather_direct(const uint16_t *codes, const float *weights, const void *tables, float *y, int64_t n,
-                         int k, int tau, int d_out, int table_dtype, hipStream_t s, bool probes = false)
+int launch_gather_direct(const uint16_t *codes, const float *weights, const TableRef &T, float *y, int64_t n,
+                         int k, int tau, int d_out, Mode mode, hipStream_t s, const Options &opt)
 {
-    const bool bf16 = table_dtype == LFFN_BF16;
-    const int esz = bf16 ? 2 : 4;
-    GatherArgs a;
+    const int esz = T.bf16 ? 2 : 4;
+    GatherArgs a{};
     a.codes = codes;
     a.weights = weights;
-    a.tables = static_cast<const char *>(tables);
+    a.tables = T.p;
     a.y = y;
     a.n = n;
     a.k = k;
     a.tau = tau;
     a.d_out = d_out;
-    a.row_bytes = (uint32_t)d_out * esz;
-    a.nvec = (int)(a.row_bytes / 16);
+    const uint32_t row_bytes = (uint32_t)d_out * esz;
+    a.nvec = (int)(row_bytes / 16);
     a.codes_vec8 = (k % 8 == 0) && aligned(codes, 16) && (!weights || aligned(weights, 16));
+    if ((mode != kPlain) != (weights != nullptr)) return LFFN_E_NULL;
 
-    int lpt = g_opt.lanes_per_token;
+    int lpt = opt.lanes_per_token;
     if (lpt == 0) {
         lpt = 8;  // 128-byte slices: one L2 line per (token, table)
         while (lpt > 1 && lpt / 2 >= a.nvec) lpt /= 2;
     }
+    if (T.prepared && lpt * 16 > T.pw) lpt = T.pw / 16;  // a token's piece lies inside one prepared piece
     const int tpw = 64 / lpt;
     a.n_slices = (a.nvec + lpt - 1) / lpt;
+    if (T.prepared) {
+        a.spp = (uint32_t)(T.pw / (lpt * 16));
+        a.row_stride = (uint32_t)T.pw;
+        a.slice_stride = ((unsigned long long)k << tau) * T.pw;
+    } else {
+        a.spp = 1;
+        a.row_stride = row_bytes;
+        a.slice_stride = (unsigned long long)lpt * 16;
+    }
     const int64_t ntb = (n + (int64_t)kGatherWaves * tpw - 1) / ((int64_t)kGatherWaves * tpw);
     if (ntb > (int64_t(1) << 30)) return LFFN_E_SIZE;
     a.ntb = (int)ntb;
 
-    const double table_bytes = (double)k * (double)(1u << tau) * a.row_bytes;
+    const double table_bytes = (double)k * (double)(1u << tau) * row_bytes;
     bool xcd = table_bytes > 4.0 * 1024 * 1024 && ntb >= 64;
-    if (g_opt.xcd_order == 1) xcd = true;
-    if (g_opt.xcd_order == -1) xcd = false;
+    if (opt.xcd_order == 1) xcd = true;
+    if (opt.xcd_order == -1) xcd = false;
     a.xcd_mode = xcd;
     int64_t blocks;
     if (xcd) {
@@ -735,12 +873,60 @@ int launch_gather_direct(const uint16_t *codes, const float *weights, const void
     if (blocks > 0x7FFFFFFFLL) return LFFN_E_SIZE;
     const dim3 grid((unsigned)blocks);
     TimedLaunch tl(1, s);
-    int rc = lffn_host::gather_direct_part(bf16, lpt, a, probes, grid, s);
+    int rc = lffn_host::gather_direct_part(T.bf16, lpt, a, mode == kProbes, grid, s);
     if (rc != LFFN_OK) return rc;
     LFFN_HIP(hipGetLastError());
     tl.done();
-    g_last_gather = "gather_kernel";
+    t_last_gather = "gather_kernel";
     return LFFN_OK;
+}
+
+// grid of the tiled re-pack kernels: one workgroup per 64 x 64 tile, capped (they stride over the rest)
+unsigned repack_grid(int64_t n_rows, int64_t m)
+{
+    int64_t blocks = ((m + 63) / 64) * ((n_rows + 63) / 64);
+    if (blocks > 16384) blocks = 16384;
+    return (unsigned)(blocks < 1 ? 1 : blocks);
+}
+
+int launch_repack_codes(const uint16_t *codes, uint32_t *packed, int64_t n, int64_t n_pad, int k, int tau,
+                        int shift, hipStream_t s)
+{
+    hipLaunchKernelGGL(repack_codes_kernel, dim3(repack_grid(n_pad, k / 2)), dim3(256), 0, s, codes, packed,
+                       (long long)n, (long long)n_pad, k, tau, shift);
+    LFFN_HIP(hipGetLastError());
+    return LFFN_OK;
+}
+
+// ABI weights [n][m] -> table-major [m][n_pad]  (m = k, or k * (1 + tau) for the multi-probe shares)
+int launch_repack_weights(const float *weights, float *wpk, int64_t n, int64_t n_pad, int64_t m, hipStream_t s)
+{
+    hipLaunchKernelGGL(repack_shares_kernel, dim3(repack_grid(n, m)), dim3(256), 0, s, weights, wpk, (long long)n,
+                       (long long)n_pad, (long long)m);
+    LFFN_HIP(hipGetLastError());
+    return LFFN_OK;
+}
+
+// Gather from ABI-layout codes (and weights / shares): the staged kernel through the re-pack kernels when
+// the plan says so and the scratch has room, else the direct kernel.
+int gather_from_abi(Mode mode, const uint16_t *codes, const float *weights, const TableRef &T, float *y, int64_t n,
+                    int k, int tau, int d_out, const LdsPlan &plan, Scratch *sc, hipStream_t s, const Options &opt)
+{
+    if (plan.use && aligned(codes, 4)) {
+        uint32_t *packed = sc->take<uint32_t>(packed_bytes(n, k));
+        float *wpk = mode == kWeighted ? sc->take<float>(wpk_bytes(n, k))
+                     : mode == kProbes ? sc->take<float>(spk_bytes(n, k, tau)) : nullptr;
+        if (packed && (mode == kPlain || wpk)) {
+            int rc = launch_repack_codes(codes, packed, n, plan.a.n_pad, k, tau, plan.shift, s);
+            if (rc != LFFN_OK) return rc;
+            if (mode != kPlain) {
+                rc = launch_repack_weights(weights, wpk, n, plan.a.n_pad, (int64_t)k * (mode == kProbes ? tau + 1 : 1), s);
+                if (rc != LFFN_OK) return rc;
+            }
+            return launch_gather_lds(plan, packed, wpk, T, y, mode, s);
+        }
+    }
+    return launch_gather_direct(codes, weights, T, y, n, k, tau, d_out, mode, s, opt);
 }
 
 // ---- BH{m} hash --------------------------------------------------------------------------------
@@ -758,11 +944,12 @@ int check_bh(const void *x, const float *bmats, int64_t n, int d, int k, int tau
     if (L > 10 || d > 1024) return LFFN_E_UNSUPPORTED;
     const int N = L < 6 ? 64 : 1 << L;  // widths below 64 are not built
     if (L < 6) return LFFN_E_UNSUPPORTED;
-    if (block != 16 && block != 32 && block != 64) return LFFN_E_UNSUPPORTED;
-    if (block > N) return LFFN_E_SIZE;
+    const int b = block & ~LFFN_PREPARED;
+    if (b != 16 && b != 32 && b != 64) return LFFN_E_UNSUPPORTED;
+    if (b > N) return LFFN_E_SIZE;
     const int64_t P = ((int64_t)k * tau + N - 1) / N;
     if (P > 64 || bh_lds_bytes((int)P, N) > 150 * 1024) return LFFN_E_UNSUPPORTED;
-    if (!aligned(x, x_dtype == LFFN_F32 ? 4 : 2) || !aligned(bmats, 4)) return LFFN_E_ALIGN;
+    if (!aligned(x, x_dtype == LFFN_F32 ? 4 : 2) || !aligned(bmats, (block & LFFN_PREPARED) ? 256 : 4)) return LFFN_E_ALIGN;
     return LFFN_OK;
 }
 
@@ -773,21 +960,33 @@ int64_t bh_pack_bytes(int d, int k, int tau, int block, int n_factors)
     return round256(P * n_factors * (int64_t)N * block * 4);
 }
 
-// Packs the factors into `apack` (bh_pack_bytes) and hashes; writes codes[n][k] (and weights[n][k] if
-// given) or the packed layout (and wpk[k][n_pad] if given).
-int launch_hash_bh(const void *x, const float *bmats, float *apack, uint16_t *codes, uint32_t *packed, int64_t n,
-                   int d, int k, int tau, int block, int n_factors, int x_dtype, hipStream_t s,
-                   float *weights = nullptr, float *wpk = nullptr)
+// The factors in MFMA-operand order (one-time: lookupffn_prepare_bh, or per call into scratch)
+int launch_bh_pack(const float *bmats, float *apack, int d, int k, int tau, int block, int n_factors, hipStream_t s)
+{
+    const int N = 1 << log2_pad(d);
+    const int64_t P = ((int64_t)k * tau + N - 1) / N;
+    const long long total = (long long)P * n_factors * N * block;
+    long long pb = (total + 255) / 256;
+    if (pb > 2048) pb = 2048;
+    hipLaunchKernelGGL(bh_pack_kernel, dim3((unsigned)pb), dim3(256), 0, s, bmats, apack, N, block, total);
+    LFFN_HIP(hipGetLastError());
+    return LFFN_OK;
+}
+
+// Hashes with the packed factors `apack`; `pack_from` != NULL: re-order them from there first.
+int launch_hash_bh(const void *x, const float *pack_from, const float *apack_in, float *apack_scratch,
+                   const HashOut &out, int64_t n, int d, int k, int tau, int block, int n_factors, int x_dtype,
+                   hipStream_t s)
 {
     const int L = log2_pad(d);
     const int N = 1 << L;
-    BhArgs a;
+    BhArgs a{};
     a.x = x;
-    a.apack = apack;
-    a.codes = codes;
-    a.packed = codes ? nullptr : packed;
-    a.weights = codes ? weights : nullptr;
-    a.wpk = codes ? nullptr : wpk;
+    a.apack = pack_from ? apack_scratch : apack_in;
+    a.codes = out.codes;
+    a.packed = out.codes ? nullptr : out.packed;
+    a.weights = out.codes ? out.weights : nullptr;
+    a.wpk = out.codes ? nullptr : out.weights;
     a.n_pad = packed_n_pad(n);
     a.n = n;
     a.d = d;
@@ -798,12 +997,12 @@ int launch_hash_bh(const void *x, const float *bmats, float *apack, uint16_t *co
     a.x_bf16 = x_dtype == LFFN_BF16;
     a.x_vec4 = d % 4 == 0 && aligned(x, a.x_bf16 ? 8 : 16);
     a.scale = (float)(1.0 / std::sqrt((double)N));
-    const long long total = (long long)a.P * n_factors * N * block;
-    long long pb = (total + 255) / 256;
-    if (pb > 2048) pb = 2048;
+    if (!a.apack || (!a.codes && !a.packed) || out.probes) return LFFN_E_NULL;
     TimedLaunch tl(0, s);
-    hipLaunchKernelGGL(bh_pack_kernel, dim3((unsigned)pb), dim3(256), 0, s, bmats, apack, N, block, total);
-    LFFN_HIP(hipGetLastError());
+    if (pack_from) {
+        int rc = launch_bh_pack(pack_from, apack_scratch, d, k, tau, block, n_factors, s);
+        if (rc != LFFN_OK) return rc;
+    }
     int64_t blocks = ((n + kBhTok - 1) / kBhTok + kBhWaves - 1) / kBhWaves;
     if (blocks > 4096) blocks = 4096;
     const dim3 grid((unsigned)blocks);
@@ -828,55 +1027,222 @@ int launch_hash_bh(const void *x, const float *bmats, float *apack, uint16_t *co
     return LFFN_OK;
 }
 
-// workspace of the weighted forward pass: codes [n][k] uint16 then weights [n][k] fp32, or (staged
-// gather) packed codes then table-major weights [k][n_pad]
-int64_t weighted_codes_bytes(int64_t n, int k) { return ((int64_t)n * k * 2 + 255) & ~int64_t(255); }
+// ---------------------------------------------------------------- the forward pass, all variants
+// Hash: the sign-diagonal rounds (`signs`, n_rounds) or the BH factors (`bmats`, block, n_factors).
+struct HashSpec {
+    const int8_t *signs = nullptr;
+    int n_rounds = 0;
+    const float *bmats = nullptr;  // row-major factors, or the prepared copy when `bh_prepared`
+    int block = 0, n_factors = 0;
+    bool bh_prepared = false;
+    bool bh() const { return bmats != nullptr; }
+};
 
-// grid of the tiled re-pack kernels: one workgroup per 64 x 64 tile, capped (they stride over the rest)
-unsigned repack_grid(int64_t n_rows, int64_t m)
+int64_t forward_need(const HashSpec &h, Mode mode, int64_t n, int d, int k, int tau)
 {
-    int64_t blocks = ((m + 63) / 64) * ((n_rows + 63) / 64);
-    if (blocks > 16384) blocks = 16384;
-    return (unsigned)(blocks < 1 ? 1 : blocks);
+    if (n <= 0) return 0;
+    const int64_t pack = (h.bh() && !h.bh_prepared) ? bh_pack_bytes(d, k, tau, h.block, h.n_factors) : 0;
+    return pack + forward_ws_bytes(n, k, tau, mode);
 }
 
-int launch_repack_codes(const uint16_t *codes, uint32_t *packed, int64_t n, int64_t n_pad, int k, int tau,
-                        int shift, hipStream_t s)
+int forward_core(const HashSpec &h, Mode mode, const void *x, const void *tables, float *y, int64_t n, int d,
+                 int k, int tau, int d_out, int x_dtype, int table_dtype, void *workspace,
+                 int64_t workspace_bytes, hipStream_t s)
 {
-    hipLaunchKernelGGL(repack_codes_kernel, dim3(repack_grid(n_pad, k / 2)), dim3(256), 0, s, codes, packed,
-                       (long long)n, (long long)n_pad, k, tau, shift);
-    LFFN_HIP(hipGetLastError());
-    return LFFN_OK;
+    const uint16_t *stand_in = reinterpret_cast<const uint16_t *>(uintptr_t(256));  // the codes live in scratch
+    int rc = h.bh() ? check_bh(x, h.bmats, n, d, k, tau, h.block | (h.bh_prepared ? LFFN_PREPARED : 0), h.n_factors,
+                               x_dtype, mode == kWeighted)
+                    : check_hash(x, h.signs, stand_in, n, d, k, tau, h.n_rounds, x_dtype, mode != kPlain);
+    if (rc != LFFN_OK) return rc;
+    if (h.bh() && mode == kProbes) return LFFN_E_UNSUPPORTED;
+    rc = check_gather(stand_in, tables, y, n, k, tau, d_out, table_dtype);
+    if (rc != LFFN_OK) return rc;
+    const int64_t need = forward_need(h, mode, n, d, k, tau);
+    Scratch sc;
+    if (workspace) {  // a caller's buffer is checked even for an empty batch
+        if (workspace_bytes < need) return LFFN_E_WORKSPACE;
+        if (!aligned(workspace, 256)) return LFFN_E_ALIGN;
+    }
+    if (n == 0) return LFFN_OK;
+    rc = get_scratch(workspace, workspace_bytes, need, &sc);
+    if (rc != LFFN_OK) return rc;
+    const Options opt = options_snapshot();
+    const TableRef T = table_ref(tables, table_dtype, tau);
+    LdsPlan plan;
+    rc = plan_gather_lds(n, k, tau, d_out, T, mode, opt, &plan);
+    if (rc != LFFN_OK) return rc;
+    float *apack = (h.bh() && !h.bh_prepared) ? sc.take<float>(bh_pack_bytes(d, k, tau, h.block, h.n_factors)) : nullptr;
+    if (h.bh() && !h.bh_prepared && !apack) return LFFN_E_WORKSPACE;
+    auto run_hash = [&](const HashOut &out) -> int {
+        if (h.bh())
+            return launch_hash_bh(x, h.bh_prepared ? nullptr : h.bmats, h.bh_prepared ? h.bmats : nullptr, apack, out, n,
+                                  d, k, tau, h.block, h.n_factors, x_dtype, s);
+        return launch_hash(x, h.signs, out, n, d, k, tau, h.n_rounds, x_dtype, s, opt);
+    };
+    // the hash kernels write the staged gather's layout themselves when its codes are scaled for 128-byte
+    // row pieces (and the variant is not the multi-probe one, whose shares exist in the ABI layout only)
+    if (plan.use && plan.shift == kPackedShift && mode != kProbes) {
+        HashOut out;
+        const int64_t pb = packed_bytes(n, k), wb = mode == kWeighted ? wpk_bytes(n, k) : 0;
+        out.packed = sc.take<uint32_t>(pb);
+        out.weights = mode == kWeighted ? sc.take<float>(wb) : nullptr;
+        if (!out.packed || (mode == kWeighted && !out.weights)) return LFFN_E_WORKSPACE;
+        if (!hash_extents_ok(out, n, k, tau, plan.a.n_pad, 0, pb, wb)) return LFFN_E_WORKSPACE;
+        rc = run_hash(out);
+        if (rc != LFFN_OK) return rc;
+        return launch_gather_lds(plan, out.packed, out.weights, T, y, mode, s);
+    }
+    HashOut out;
+    const int64_t cb = abi_codes_bytes(n, k), wb = abi_weights_bytes(n, k, tau, mode);
+    out.codes = sc.take<uint16_t>(cb);
+    out.weights = mode != kPlain ? sc.take<float>(wb) : nullptr;
+    out.probes = mode == kProbes;
+    if (!out.codes || (mode != kPlain && !out.weights)) return LFFN_E_WORKSPACE;
+    if (!hash_extents_ok(out, n, k, tau, plan.a.n_pad, cb, 0, wb)) return LFFN_E_WORKSPACE;
+    rc = run_hash(out);
+    if (rc != LFFN_OK) return rc;
+    return gather_from_abi(mode, out.codes, out.weights, T, y, n, k, tau, d_out, plan, &sc, s, opt);
 }
 
-int launch_repack_shares(const float *shares, float *spk, int64_t n, int64_t n_pad, int k, int tau, hipStream_t s)
+int gather_core(Mode mode, const uint16_t *codes, const float *weights, const void *tables, float *y, int64_t n,
+                int k, int tau, int d_out, int table_dtype, void *workspace, int64_t workspace_bytes, hipStream_t s)
 {
-    const int64_t m = (int64_t)k * (tau + 1);
-    hipLaunchKernelGGL(repack_shares_kernel, dim3(repack_grid(n, m)), dim3(256), 0, s, shares, spk, (long long)n,
-                       (long long)n_pad, (long long)m);
-    LFFN_HIP(hipGetLastError());
-    return LFFN_OK;
+    int rc = check_gather(codes, tables, y, n, k, tau, d_out, table_dtype);
+    if (rc == LFFN_OK && mode != kPlain) rc = check_weights(weights);
+    if (rc != LFFN_OK) return rc;
+    const int64_t need = gather_ws_bytes(n, k, tau, mode);
+    if (workspace) {
+        if (workspace_bytes < need) return LFFN_E_WORKSPACE;
+        if (!aligned(workspace, 256)) return LFFN_E_ALIGN;
+    }
+    if (n == 0) return LFFN_OK;
+    const Options opt = options_snapshot();
+    const TableRef T = table_ref(tables, table_dtype, tau);
+    LdsPlan plan;
+    rc = plan_gather_lds(n, k, tau, d_out, T, mode, opt, &plan);
+    if (rc != LFFN_OK) return rc;
+    Scratch sc;
+    if (plan.use && aligned(codes, 4)) {  // only the staged kernel needs scratch
+        rc = get_scratch(workspace, workspace_bytes, need, &sc);
+        if (rc != LFFN_OK) return rc;
+    }
+    return gather_from_abi(mode, codes, weights, T, y, n, k, tau, d_out, plan, &sc, s, opt);
 }
 
-int launch_repack_weights(const float *weights, float *wpk, int64_t n, int64_t n_pad, int k, hipStream_t s)
+HashSpec sign_hash(const int8_t *signs, int n_rounds)
 {
-    hipLaunchKernelGGL(repack_shares_kernel, dim3(repack_grid(n, k)), dim3(256), 0, s, weights, wpk, (long long)n,
-                       (long long)n_pad, (long long)k);
-    LFFN_HIP(hipGetLastError());
-    return LFFN_OK;
+    HashSpec h;
+    h.signs = signs;
+    h.n_rounds = n_rounds;
+    return h;
+}
+HashSpec bh_hash(const float *bmats, int block, int n_factors)
+{
+    HashSpec h;
+    h.bmats = bmats;
+    h.block = block & ~LFFN_PREPARED;
+    h.n_factors = n_factors;
+    h.bh_prepared = (block & LFFN_PREPARED) != 0;
+    return h;
+}
+
+// stand-alone BH hash (codes, and weights for the weighted variant) into caller buffers
+int hash_bh_core(const void *x, const float *bmats, uint16_t *codes, float *weights, bool weighted, int64_t n, int d,
+                 int k, int tau, int block, int n_factors, int x_dtype, void *workspace, int64_t workspace_bytes,
+                 hipStream_t s)
+{
+    int rc = check_bh(x, bmats, n, d, k, tau, block, n_factors, x_dtype, weighted);
+    if (rc != LFFN_OK) return rc;
+    if (!codes || (weighted && !weights)) return LFFN_E_NULL;
+    if (!aligned(codes, 2) || (weighted && !aligned(weights, 4))) return LFFN_E_ALIGN;
+    const HashSpec h = bh_hash(bmats, block, n_factors);
+    const int64_t need = h.bh_prepared ? 0 : bh_pack_bytes(d, k, tau, h.block, n_factors);
+    if (workspace) {
+        if (workspace_bytes < need) return LFFN_E_WORKSPACE;
+        if (!aligned(workspace, 256)) return LFFN_E_ALIGN;
+    }
+    if (n == 0) return LFFN_OK;
+    Scratch sc;
+    rc = get_scratch(workspace, workspace_bytes, need, &sc);
+    if (rc != LFFN_OK) return rc;
+    float *apack = h.bh_prepared ? nullptr : sc.take<float>(need);
+    if (!h.bh_prepared && !apack) return LFFN_E_WORKSPACE;
+    HashOut out;
+    out.codes = codes;
+    out.weights = weighted ? weights : nullptr;
+    return launch_hash_bh(x, h.bh_prepared ? nullptr : bmats, h.bh_prepared ? bmats : nullptr, apack, out, n, d, k,
+                          tau, h.block, n_factors, x_dtype, s);
+}
+
+bool bh_shape_ok(int d, int k, int tau, int block, int n_factors)
+{
+    return !(d < 1 || d > 1024 || k < 1 || tau < 1 || tau > 16 || block < 1 || n_factors < 1 || n_factors > 64);
 }
 
 }  // namespace
 
 extern "C" {
 
+int lookupffn_init(void)
+{
+    int cus = 0;
+    int rc = device_cus(&cus);
+    if (rc != LFFN_OK) return rc;
+    // code objects are loaded on first use: do that now for the two parts no attribute call below touches
+    // (this one: hash, re-pack and prepare kernels; and the direct gather's)
+    {
+        hipFuncAttributes attr;
+        LFFN_HIP(hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(repack_codes_kernel)));
+        rc = lffn_host::gather_direct_load();
+        if (rc != LFFN_OK) return rc;
+    }
+    // every kernel that asks for more than 64 KB of dynamic LDS is told so now, so that no later launch
+    // has to (the attribute call is not a stream operation and has no place inside a graph capture)
+    lffn_host::AttrOnly scope;
+    const size_t lds = 160 * 1024;
+    GatherLdsArgs ga{};
+    BhArgs ba{};
+    for (int tok : {4, 8, 12, 13, 16})
+        for (int fr : {1, 2, 4})
+            for (int sw : {4, 8}) {
+                for (int part = 0; part < 3; ++part) {
+                    rc = part == 0   ? lffn_host::gather_lds_plain_part(tok, ga, fr, sw, dim3(1), lds, nullptr)
+                         : part == 1 ? lffn_host::gather_lds_weighted_part(tok, ga, fr, sw, dim3(1), lds, nullptr)
+                                     : lffn_host::gather_lds_probes_part(tok, ga, fr, sw, dim3(1), lds, nullptr);
+                    if (rc != LFFN_OK && rc != LFFN_E_UNSUPPORTED) return rc;
+                }
+            }
+    for (int L = 6; L <= 10; ++L)
+        for (int block : {16, 32, 64})
+            for (int vec4 = 0; vec4 < 2; ++vec4)
+                for (int weighted = 0; weighted < 2; ++weighted) {
+                    ba.x_vec4 = vec4;
+                    if (L <= 8)
+                        rc = weighted ? lffn_host::bh_weighted_lo_part(L, ba, block, dim3(1), lds, nullptr)
+                                      : lffn_host::bh_plain_lo_part(L, ba, block, dim3(1), lds, nullptr);
+                    else if (!weighted)
+                        rc = L == 9 ? lffn_host::bh_plain_512_part(ba, block, dim3(1), lds, nullptr)
+                                    : lffn_host::bh_plain_1024_part(ba, block, dim3(1), lds, nullptr);
+                    else if (L == 9)
+                        rc = vec4 ? lffn_host::bh_weighted_512_vec4_part(ba, block, dim3(1), lds, nullptr)
+                                  : lffn_host::bh_weighted_512_scalar_part(ba, block, dim3(1), lds, nullptr);
+                    else
+                        rc = vec4 ? lffn_host::bh_weighted_1024_vec4_part(ba, block, dim3(1), lds, nullptr)
+                                  : lffn_host::bh_weighted_1024_scalar_part(ba, block, dim3(1), lds, nullptr);
+                    if (rc != LFFN_OK && rc != LFFN_E_UNSUPPORTED) return rc;
+                }
+    return LFFN_OK;
+}
+
 int lookupffn_hash(const void *x, const int8_t *signs, uint16_t *codes, int64_t n_tokens, int d, int k,
                    int tau, int n_rounds, int x_dtype, void *hip_stream)
 {
     int rc = check_hash(x, signs, codes, n_tokens, d, k, tau, n_rounds, x_dtype);
     if (rc != LFFN_OK || n_tokens == 0) return rc;
-    return launch_hash(x, signs, codes, nullptr, nullptr, n_tokens, d, k, tau, n_rounds, x_dtype,
-                       static_cast<hipStream_t>(hip_stream));
+    HashOut out;
+    out.codes = codes;
+    return launch_hash(x, signs, out, n_tokens, d, k, tau, n_rounds, x_dtype, static_cast<hipStream_t>(hip_stream),
+                       options_snapshot());
 }
 
 int lookupffn_hash_weighted(const void *x, const int8_t *signs, uint16_t *codes, float *weights, int64_t n_tokens,
@@ -885,38 +1251,11 @@ int lookupffn_hash_weighted(const void *x, const int8_t *signs, uint16_t *codes,
     int rc = check_hash(x, signs, codes, n_tokens, d, k, tau, n_rounds, x_dtype, true);
     if (rc == LFFN_OK) rc = check_weights(weights);
     if (rc != LFFN_OK || n_tokens == 0) return rc;
-    return launch_hash(x, signs, codes, nullptr, weights, n_tokens, d, k, tau, n_rounds, x_dtype,
-                       static_cast<hipStream_t>(hip_stream));
-}
-
-int lookupffn_gather_weighted(const uint16_t *codes, const float *weights, const void *tables, float *y,
-                              int64_t n_tokens, int k, int tau, int d_out, int table_dtype, void *hip_stream)
-{
-    int rc = check_gather(codes, tables, y, n_tokens, k, tau, d_out, table_dtype);
-    if (rc == LFFN_OK) rc = check_weights(weights);
-    if (rc != LFFN_OK || n_tokens == 0) return rc;
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    LdsPlan plan;
-    const bool bf16 = table_dtype == LFFN_BF16;
-    rc = plan_gather_lds(n_tokens, k, tau, d_out, bf16, &plan, true, false, true);
-    if (rc != LFFN_OK) return rc;
-    if (plan.use && aligned(codes, 4)) {
-        // the staged kernel reads packed codes and table-major weights: repack into the library's buffer
-        const int64_t pb = round256(packed_bytes(n_tokens, k));
-        void *ws = nullptr;
-        const int64_t wb = round256((int64_t)k * plan.a.n_pad * 4);
-        rc = own_workspace((size_t)(pb + wb + plan.widen_bytes), &ws);
-        if (rc != LFFN_OK) return rc;
-        plan.widened = plan.widen ? static_cast<char *>(ws) + pb + wb : nullptr;
-        uint32_t *packed = static_cast<uint32_t *>(ws);
-        float *wpk = reinterpret_cast<float *>(static_cast<char *>(ws) + pb);
-        rc = launch_repack_codes(codes, packed, n_tokens, plan.a.n_pad, k, tau, plan.shift, s);
-        if (rc != LFFN_OK) return rc;
-        rc = launch_repack_weights(weights, wpk, n_tokens, plan.a.n_pad, k, s);
-        if (rc != LFFN_OK) return rc;
-        return launch_gather_lds(plan, packed, wpk, tables, y, bf16, s);
-    }
-    return launch_gather_direct(codes, weights, tables, y, n_tokens, k, tau, d_out, table_dtype, s);
+    HashOut out;
+    out.codes = codes;
+    out.weights = weights;
+    return launch_hash(x, signs, out, n_tokens, d, k, tau, n_rounds, x_dtype, static_cast<hipStream_t>(hip_stream),
+                       options_snapshot());
 }
 
 int lookupffn_hash_probes(const void *x, const int8_t *signs, uint16_t *codes, float *shares, int64_t n_tokens,
@@ -925,404 +1264,198 @@ int lookupffn_hash_probes(const void *x, const int8_t *signs, uint16_t *codes, f
     int rc = check_hash(x, signs, codes, n_tokens, d, k, tau, n_rounds, x_dtype, true);
     if (rc == LFFN_OK) rc = check_weights(shares);
     if (rc != LFFN_OK || n_tokens == 0) return rc;
-    return launch_hash(x, signs, codes, nullptr, shares, n_tokens, d, k, tau, n_rounds, x_dtype,
-                       static_cast<hipStream_t>(hip_stream), true);
-}
-
-int lookupffn_gather_probes(const uint16_t *codes, const float *shares, const void *tables, float *y,
-                            int64_t n_tokens, int k, int tau, int d_out, int table_dtype, void *hip_stream)
-{
-    int rc = check_gather(codes, tables, y, n_tokens, k, tau, d_out, table_dtype);
-    if (rc == LFFN_OK) rc = check_weights(shares);
-    if (rc != LFFN_OK || n_tokens == 0) return rc;
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    LdsPlan plan;
-    rc = plan_gather_lds(n_tokens, k, tau, d_out, table_dtype == LFFN_BF16, &plan, true, true);
-    if (rc != LFFN_OK) return rc;
-    if (plan.use && aligned(codes, 4)) {
-        // staged form: packed codes and table-major shares in the library's buffer
-        const int64_t pb = round256(packed_bytes(n_tokens, k));
-        void *ws = nullptr;
-        rc = own_workspace((size_t)(pb + probes_spk_bytes(n_tokens, k, tau)), &ws);
-        if (rc != LFFN_OK) return rc;
-        uint32_t *packed = static_cast<uint32_t *>(ws);
-        float *spk = reinterpret_cast<float *>(static_cast<char *>(ws) + pb);
-        rc = launch_repack_codes(codes, packed, n_tokens, plan.a.n_pad, k, tau, plan.shift, s);
-        if (rc != LFFN_OK) return rc;
-        rc = launch_repack_shares(shares, spk, n_tokens, plan.a.n_pad, k, tau, s);
-        if (rc != LFFN_OK) return rc;
-        return launch_gather_lds(plan, packed, spk, tables, y, false, s, true);
-    }
-    return launch_gather_direct(codes, shares, tables, y, n_tokens, k, tau, d_out, table_dtype, s, true);
-}
-
-int64_t lookupffn_workspace_bytes_probes(int64_t n_tokens, int k, int tau)
-{
-    if (n_tokens <= 0 || k < 1 || tau < 1 || tau > 16) return 0;
-    // ABI codes and shares, and beside them the staged gather's packed codes and table-major shares
-    return weighted_codes_bytes(n_tokens, k) + round256((int64_t)n_tokens * k * (tau + 1) * 4) +
-           round256(packed_bytes(n_tokens, k)) + probes_spk_bytes(n_tokens, k, tau);
-}
-
-int lookupffn_forward_probes(const void *x, const int8_t *signs, const void *tables, float *y, int64_t n_tokens,
-                             int d, int k, int tau, int d_out, int n_rounds, int x_dtype, int table_dtype,
-                             void *workspace, int64_t workspace_bytes, void *hip_stream)
-{
-    const uint16_t *stand_in = reinterpret_cast<const uint16_t *>(uintptr_t(256));
-    int rc = check_hash(x, signs, stand_in, n_tokens, d, k, tau, n_rounds, x_dtype, true);
-    if (rc != LFFN_OK) return rc;
-    rc = check_gather(stand_in, tables, y, n_tokens, k, tau, d_out, table_dtype);
-    if (rc != LFFN_OK) return rc;
-    const int64_t need = lookupffn_workspace_bytes_probes(n_tokens, k, tau);
-    if (workspace) {
-        if (workspace_bytes < need) return LFFN_E_WORKSPACE;
-        if (!aligned(workspace, 256)) return LFFN_E_ALIGN;
-    }
-    if (n_tokens == 0) return LFFN_OK;
-    void *ws = workspace;
-    if (!ws) {
-        rc = own_workspace((size_t)need, &ws);
-        if (rc != LFFN_OK) return rc;
-    }
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    uint16_t *codes = static_cast<uint16_t *>(ws);
-    float *shares = reinterpret_cast<float *>(static_cast<char *>(ws) + weighted_codes_bytes(n_tokens, k));
-    rc = launch_hash(x, signs, codes, nullptr, shares, n_tokens, d, k, tau, n_rounds, x_dtype, s, true);
-    if (rc != LFFN_OK) return rc;
-    LdsPlan plan;
-    rc = plan_gather_lds(n_tokens, k, tau, d_out, table_dtype == LFFN_BF16, &plan, true, true);
-    if (rc != LFFN_OK) return rc;
-    if (plan.use) {
-        char *staged = static_cast<char *>(ws) + weighted_codes_bytes(n_tokens, k) +
-                       round256((int64_t)n_tokens * k * (tau + 1) * 4);
-        uint32_t *packed = reinterpret_cast<uint32_t *>(staged);
-        float *spk = reinterpret_cast<float *>(staged + round256(packed_bytes(n_tokens, k)));
-        rc = launch_repack_codes(codes, packed, n_tokens, plan.a.n_pad, k, tau, plan.shift, s);
-        if (rc != LFFN_OK) return rc;
-        rc = launch_repack_shares(shares, spk, n_tokens, plan.a.n_pad, k, tau, s);
-        if (rc != LFFN_OK) return rc;
-        return launch_gather_lds(plan, packed, spk, tables, y, false, s, true);
-    }
-    return launch_gather_direct(codes, shares, tables, y, n_tokens, k, tau, d_out, table_dtype, s, true);
-}
-
-int64_t lookupffn_workspace_bytes_weighted(int64_t n_tokens, int k)
-{
-    if (n_tokens <= 0 || k < 1) return 0;
-    const int64_t direct = weighted_codes_bytes(n_tokens, k) + round256((int64_t)n_tokens * k * 4);
-    const int64_t staged = round256(packed_bytes(n_tokens, k)) + round256((int64_t)k * packed_n_pad(n_tokens) * 4);
-    return direct + staged;  // both: the 64-byte-slice form re-packs from the ABI layout
-}
-
-int lookupffn_forward_weighted(const void *x, const int8_t *signs, const void *tables, float *y, int64_t n_tokens,
-                               int d, int k, int tau, int d_out, int n_rounds, int x_dtype, int table_dtype,
-                               void *workspace, int64_t workspace_bytes, void *hip_stream)
-{
-    const uint16_t *stand_in = reinterpret_cast<const uint16_t *>(uintptr_t(256));
-    int rc = check_hash(x, signs, stand_in, n_tokens, d, k, tau, n_rounds, x_dtype, true);
-    if (rc != LFFN_OK) return rc;
-    rc = check_gather(stand_in, tables, y, n_tokens, k, tau, d_out, table_dtype);
-    if (rc != LFFN_OK) return rc;
-    const int64_t need = lookupffn_workspace_bytes_weighted(n_tokens, k);
-    if (workspace) {
-        if (workspace_bytes < need) return LFFN_E_WORKSPACE;
-        if (!aligned(workspace, 256)) return LFFN_E_ALIGN;
-    }
-    if (n_tokens == 0) return LFFN_OK;
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const bool bf16 = table_dtype == LFFN_BF16;
-    LdsPlan plan;
-    rc = plan_gather_lds(n_tokens, k, tau, d_out, bf16, &plan, true, false, true);
-    if (rc != LFFN_OK) return rc;
-    const int64_t extra = widen_room(&plan, workspace, workspace_bytes, need);
-    void *ws = workspace;
-    if (!ws) {
-        rc = own_workspace((size_t)(need + extra), &ws);
-        if (rc != LFFN_OK) return rc;
-    }
-    plan.widened = extra ? static_cast<char *>(ws) + need : nullptr;
-    if (plan.use && plan.shift != 7) {
-        // 64-byte slices: ABI codes and weights, then the two re-pack kernels
-        char *base = static_cast<char *>(ws);
-        uint32_t *packed = reinterpret_cast<uint32_t *>(base);
-        float *wpk = reinterpret_cast<float *>(base + round256(packed_bytes(n_tokens, k)));
-        char *abi = base + round256(packed_bytes(n_tokens, k)) + round256((int64_t)k * packed_n_pad(n_tokens) * 4);
-        uint16_t *codes = reinterpret_cast<uint16_t *>(abi);
-        float *weights = reinterpret_cast<float *>(abi + weighted_codes_bytes(n_tokens, k));
-        rc = launch_hash(x, signs, codes, nullptr, weights, n_tokens, d, k, tau, n_rounds, x_dtype, s);
-        if (rc != LFFN_OK) return rc;
-        rc = launch_repack_codes(codes, packed, n_tokens, plan.a.n_pad, k, tau, plan.shift, s);
-        if (rc != LFFN_OK) return rc;
-        rc = launch_repack_weights(weights, wpk, n_tokens, plan.a.n_pad, k, s);
-        if (rc != LFFN_OK) return rc;
-        return launch_gather_lds(plan, packed, wpk, tables, y, bf16, s);
-    }
-    if (plan.use) {
-        uint32_t *packed = static_cast<uint32_t *>(ws);
-        float *wpk = reinterpret_cast<float *>(static_cast<char *>(ws) + round256(packed_bytes(n_tokens, k)));
-        rc = launch_hash(x, signs, nullptr, packed, wpk, n_tokens, d, k, tau, n_rounds, x_dtype, s);
-        if (rc != LFFN_OK) return rc;
-        return launch_gather_lds(plan, packed, wpk, tables, y, bf16, s);
-    }
-    uint16_t *codes = static_cast<uint16_t *>(ws);
-    float *weights = reinterpret_cast<float *>(static_cast<char *>(ws) + weighted_codes_bytes(n_tokens, k));
-    rc = launch_hash(x, signs, codes, nullptr, weights, n_tokens, d, k, tau, n_rounds, x_dtype, s);
-    if (rc != LFFN_OK) return rc;
-    return launch_gather_direct(codes, weights, tables, y, n_tokens, k, tau, d_out, table_dtype, s);
+    HashOut out;
+    out.codes = codes;
+    out.weights = shares;
+    out.probes = true;
+    return launch_hash(x, signs, out, n_tokens, d, k, tau, n_rounds, x_dtype, static_cast<hipStream_t>(hip_stream),
+                       options_snapshot());
 }
 
 int lookupffn_gather(const uint16_t *codes, const void *tables, float *y, int64_t n_tokens, int k, int tau,
-                     int d_out, int table_dtype, void *hip_stream)
+                     int d_out, int table_dtype, void *workspace, int64_t workspace_bytes, void *hip_stream)
 {
-    int rc = check_gather(codes, tables, y, n_tokens, k, tau, d_out, table_dtype);
-    if (rc != LFFN_OK || n_tokens == 0) return rc;
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const bool bf16 = table_dtype == LFFN_BF16;
-    LdsPlan plan;
-    rc = plan_gather_lds(n_tokens, k, tau, d_out, bf16, &plan, false, false, true);
-    if (rc != LFFN_OK) return rc;
-    if (plan.use && aligned(codes, 4)) {
-        // the staged kernel reads codes in its packed layout: repack into the library's buffer
-        // (bf16 tables: their fp32 copy goes behind it)
-        void *ws = nullptr;
-        const int64_t pb = round256(packed_bytes(n_tokens, k));
-        rc = own_workspace((size_t)(pb + plan.widen_bytes), &ws);
-        if (rc != LFFN_OK) return rc;
-        plan.widened = plan.widen ? static_cast<char *>(ws) + pb : nullptr;
-        uint32_t *packed = static_cast<uint32_t *>(ws);
-        rc = launch_repack_codes(codes, packed, n_tokens, plan.a.n_pad, k, tau, plan.shift, s);
-        if (rc != LFFN_OK) return rc;
-        return launch_gather_lds(plan, packed, nullptr, tables, y, bf16, s);
-    }
-    return launch_gather_direct(codes, nullptr, tables, y, n_tokens, k, tau, d_out, table_dtype, s);
+    return gather_core(kPlain, codes, nullptr, tables, y, n_tokens, k, tau, d_out, table_dtype, workspace,
+                       workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
-int64_t lookupffn_workspace_bytes_tables(int k, int tau, int d_out, int table_dtype)
+int lookupffn_gather_weighted(const uint16_t *codes, const float *weights, const void *tables, float *y,
+                              int64_t n_tokens, int k, int tau, int d_out, int table_dtype, void *workspace,
+                              int64_t workspace_bytes, void *hip_stream)
 {
-    if (table_dtype != LFFN_BF16 || k < 1 || tau < 1 || tau > 16 || d_out < 1) return 0;
-    return round256((int64_t)k * (int64_t(1) << tau) * d_out * 4);
+    return gather_core(kWeighted, codes, weights, tables, y, n_tokens, k, tau, d_out, table_dtype, workspace,
+                       workspace_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+int lookupffn_gather_probes(const uint16_t *codes, const float *shares, const void *tables, float *y,
+                            int64_t n_tokens, int k, int tau, int d_out, int table_dtype, void *workspace,
+                            int64_t workspace_bytes, void *hip_stream)
+{
+    return gather_core(kProbes, codes, shares, tables, y, n_tokens, k, tau, d_out, table_dtype, workspace,
+                       workspace_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+int64_t lookupffn_workspace_bytes_gather(int64_t n_tokens, int k)
+{
+    return (n_tokens <= 0 || k < 1) ? 0 : gather_ws_bytes(n_tokens, k, 1, kPlain);
+}
+int64_t lookupffn_workspace_bytes_gather_weighted(int64_t n_tokens, int k)
+{
+    return (n_tokens <= 0 || k < 1) ? 0 : gather_ws_bytes(n_tokens, k, 1, kWeighted);
+}
+int64_t lookupffn_workspace_bytes_gather_probes(int64_t n_tokens, int k, int tau)
+{
+    return (n_tokens <= 0 || k < 1 || tau < 1 || tau > 16) ? 0 : gather_ws_bytes(n_tokens, k, tau, kProbes);
 }
 
 int64_t lookupffn_workspace_bytes(int64_t n_tokens, int k)
 {
-    if (n_tokens <= 0 || k < 1) return 0;
-    // the packed layout with its token padding, and [n][k] uint16 beside it (the 64-byte-slice form of the
-    // staged gather takes its codes through the re-pack kernel; otherwise only one of the two is used)
-    return round256(packed_bytes(n_tokens, k)) + round256(n_tokens * (int64_t)k * 2);
+    return (n_tokens <= 0 || k < 1) ? 0 : forward_ws_bytes(n_tokens, k, 1, kPlain);
+}
+int64_t lookupffn_workspace_bytes_weighted(int64_t n_tokens, int k)
+{
+    return (n_tokens <= 0 || k < 1) ? 0 : forward_ws_bytes(n_tokens, k, 1, kWeighted);
+}
+int64_t lookupffn_workspace_bytes_probes(int64_t n_tokens, int k, int tau)
+{
+    return (n_tokens <= 0 || k < 1 || tau < 1 || tau > 16) ? 0 : forward_ws_bytes(n_tokens, k, tau, kProbes);
+}
+int64_t lookupffn_workspace_bytes_bh(int64_t n_tokens, int d, int k, int tau, int block, int n_factors)
+{
+    if (!bh_shape_ok(d, k, tau, block & ~LFFN_PREPARED, n_factors)) return 0;
+    const int64_t pack = (block & LFFN_PREPARED) ? 0 : bh_pack_bytes(d, k, tau, block, n_factors);
+    return pack + (n_tokens > 0 ? forward_ws_bytes(n_tokens, k, tau, kPlain) : 0);
+}
+int64_t lookupffn_workspace_bytes_bh_weighted(int64_t n_tokens, int d, int k, int tau, int block, int n_factors)
+{
+    if (!bh_shape_ok(d, k, tau, block & ~LFFN_PREPARED, n_factors)) return 0;
+    const int64_t pack = (block & LFFN_PREPARED) ? 0 : bh_pack_bytes(d, k, tau, block, n_factors);
+    return pack + (n_tokens > 0 ? forward_ws_bytes(n_tokens, k, tau, kWeighted) : 0);
 }
 
 int lookupffn_forward(const void *x, const int8_t *signs, const void *tables, float *y, int64_t n_tokens,
                       int d, int k, int tau, int d_out, int n_rounds, int x_dtype, int table_dtype,
                       void *workspace, int64_t workspace_bytes, void *hip_stream)
 {
-    // the codes pointer is checked for NULL by the two step checks; give them a stand-in
-    // until the real buffer is known
-    const uint16_t *stand_in = reinterpret_cast<const uint16_t *>(uintptr_t(256));
-    int rc = check_hash(x, signs, stand_in, n_tokens, d, k, tau, n_rounds, x_dtype);
-    if (rc != LFFN_OK) return rc;
-    rc = check_gather(stand_in, tables, y, n_tokens, k, tau, d_out, table_dtype);
-    if (rc != LFFN_OK) return rc;
-    const int64_t need = lookupffn_workspace_bytes(n_tokens, k);
-    if (workspace) {
-        if (workspace_bytes < need) return LFFN_E_WORKSPACE;
-        if (!aligned(workspace, 256)) return LFFN_E_ALIGN;
-    }
-    if (n_tokens == 0) return LFFN_OK;
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const bool bf16 = table_dtype == LFFN_BF16;
-    LdsPlan plan;
-    rc = plan_gather_lds(n_tokens, k, tau, d_out, bf16, &plan, false, false, true);
-    if (rc != LFFN_OK) return rc;
-    const int64_t extra = widen_room(&plan, workspace, workspace_bytes, need);
-    void *ws = workspace;
-    if (!ws) {
-        rc = own_workspace((size_t)(need + extra), &ws);
-        if (rc != LFFN_OK) return rc;
-    }
-    plan.widened = extra ? static_cast<char *>(ws) + need : nullptr;
-    if (plan.use && plan.shift != 7) {
-        // 64-byte slices: ABI codes, then the re-pack kernel scales them for 64-byte row pieces
-        uint32_t *packed = static_cast<uint32_t *>(ws);
-        uint16_t *codes = reinterpret_cast<uint16_t *>(static_cast<char *>(ws) + round256(packed_bytes(n_tokens, k)));
-        rc = launch_hash(x, signs, codes, nullptr, nullptr, n_tokens, d, k, tau, n_rounds, x_dtype, s);
-        if (rc != LFFN_OK) return rc;
-        rc = launch_repack_codes(codes, packed, n_tokens, plan.a.n_pad, k, tau, plan.shift, s);
-        if (rc != LFFN_OK) return rc;
-        return launch_gather_lds(plan, packed, nullptr, tables, y, bf16, s);
-    }
-    if (plan.use) {
-        uint32_t *packed = static_cast<uint32_t *>(ws);
-        rc = launch_hash(x, signs, nullptr, packed, nullptr, n_tokens, d, k, tau, n_rounds, x_dtype, s);
-        if (rc != LFFN_OK) return rc;
-        return launch_gather_lds(plan, packed, nullptr, tables, y, bf16, s);
-    }
-    uint16_t *codes = static_cast<uint16_t *>(ws);
-    rc = launch_hash(x, signs, codes, nullptr, nullptr, n_tokens, d, k, tau, n_rounds, x_dtype, s);
-    if (rc != LFFN_OK) return rc;
-    return launch_gather_direct(codes, nullptr, tables, y, n_tokens, k, tau, d_out, table_dtype, s);
+    return forward_core(sign_hash(signs, n_rounds), kPlain, x, tables, y, n_tokens, d, k, tau, d_out, x_dtype,
+                        table_dtype, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
-int64_t lookupffn_workspace_bytes_bh(int64_t n_tokens, int d, int k, int tau, int block, int n_factors)
+int lookupffn_forward_weighted(const void *x, const int8_t *signs, const void *tables, float *y, int64_t n_tokens,
+                               int d, int k, int tau, int d_out, int n_rounds, int x_dtype, int table_dtype,
+                               void *workspace, int64_t workspace_bytes, void *hip_stream)
 {
-    if (d < 1 || d > 1024 || k < 1 || tau < 1 || tau > 16 || block < 1 || n_factors < 1 || n_factors > 64) return 0;
-    return bh_pack_bytes(d, k, tau, block, n_factors) + lookupffn_workspace_bytes(n_tokens, k);
+    return forward_core(sign_hash(signs, n_rounds), kWeighted, x, tables, y, n_tokens, d, k, tau, d_out, x_dtype,
+                        table_dtype, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+int lookupffn_forward_probes(const void *x, const int8_t *signs, const void *tables, float *y, int64_t n_tokens,
+                             int d, int k, int tau, int d_out, int n_rounds, int x_dtype, int table_dtype,
+                             void *workspace, int64_t workspace_bytes, void *hip_stream)
+{
+    return forward_core(sign_hash(signs, n_rounds), kProbes, x, tables, y, n_tokens, d, k, tau, d_out, x_dtype,
+                        table_dtype, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
 int lookupffn_hash_bh(const void *x, const float *bmats, uint16_t *codes, int64_t n_tokens, int d, int k, int tau,
                       int block, int n_factors, int x_dtype, void *workspace, int64_t workspace_bytes,
                       void *hip_stream)
 {
-    int rc = check_bh(x, bmats, n_tokens, d, k, tau, block, n_factors, x_dtype);
-    if (rc != LFFN_OK) return rc;
-    if (!codes) return LFFN_E_NULL;
-    if (!aligned(codes, 2)) return LFFN_E_ALIGN;
-    const int64_t need = bh_pack_bytes(d, k, tau, block, n_factors);
-    if (workspace) {
-        if (workspace_bytes < need) return LFFN_E_WORKSPACE;
-        if (!aligned(workspace, 256)) return LFFN_E_ALIGN;
-    }
-    if (n_tokens == 0) return LFFN_OK;
-    void *ws = workspace;
-    if (!ws) {
-        rc = own_workspace((size_t)need, &ws);
-        if (rc != LFFN_OK) return rc;
-    }
-    return launch_hash_bh(x, bmats, static_cast<float *>(ws), codes, nullptr, n_tokens, d, k, tau, block, n_factors,
-                          x_dtype, static_cast<hipStream_t>(hip_stream));
-}
-
-int lookupffn_forward_bh(const void *x, const float *bmats, const void *tables, float *y, int64_t n_tokens, int d,
-                         int k, int tau, int d_out, int block, int n_factors, int x_dtype, int table_dtype,
-                         void *workspace, int64_t workspace_bytes, void *hip_stream)
-{
-    int rc = check_bh(x, bmats, n_tokens, d, k, tau, block, n_factors, x_dtype);
-    if (rc != LFFN_OK) return rc;
-    const uint16_t *stand_in = reinterpret_cast<const uint16_t *>(uintptr_t(256));
-    rc = check_gather(stand_in, tables, y, n_tokens, k, tau, d_out, table_dtype);
-    if (rc != LFFN_OK) return rc;
-    const int64_t pack = bh_pack_bytes(d, k, tau, block, n_factors);
-    const int64_t need = pack + lookupffn_workspace_bytes(n_tokens, k);
-    if (workspace) {
-        if (workspace_bytes < need) return LFFN_E_WORKSPACE;
-        if (!aligned(workspace, 256)) return LFFN_E_ALIGN;
-    }
-    if (n_tokens == 0) return LFFN_OK;
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const bool bf16 = table_dtype == LFFN_BF16;
-    LdsPlan plan;
-    rc = plan_gather_lds(n_tokens, k, tau, d_out, bf16, &plan, false, false, true);
-    if (rc != LFFN_OK) return rc;
-    if (plan.shift != 7) plan.use = false;  // the BH hash writes codes scaled for 128-byte row pieces only
-    const int64_t extra = widen_room(&plan, workspace, workspace_bytes, need);
-    void *ws = workspace;
-    if (!ws) {
-        rc = own_workspace((size_t)(need + extra), &ws);
-        if (rc != LFFN_OK) return rc;
-    }
-    plan.widened = extra ? static_cast<char *>(ws) + need : nullptr;
-    float *apack = static_cast<float *>(ws);
-    void *scratch = static_cast<char *>(ws) + pack;
-    if (plan.use) {
-        uint32_t *packed = static_cast<uint32_t *>(scratch);
-        rc = launch_hash_bh(x, bmats, apack, nullptr, packed, n_tokens, d, k, tau, block, n_factors, x_dtype, s);
-        if (rc != LFFN_OK) return rc;
-        return launch_gather_lds(plan, packed, nullptr, tables, y, bf16, s);
-    }
-    uint16_t *codes = static_cast<uint16_t *>(scratch);
-    rc = launch_hash_bh(x, bmats, apack, codes, nullptr, n_tokens, d, k, tau, block, n_factors, x_dtype, s);
-    if (rc != LFFN_OK) return rc;
-    return launch_gather_direct(codes, nullptr, tables, y, n_tokens, k, tau, d_out, table_dtype, s);
-}
-
-int64_t lookupffn_workspace_bytes_bh_weighted(int64_t n_tokens, int d, int k, int tau, int block, int n_factors)
-{
-    if (d < 1 || d > 1024 || k < 1 || tau < 1 || tau > 16 || block < 1 || n_factors < 1 || n_factors > 64) return 0;
-    return bh_pack_bytes(d, k, tau, block, n_factors) + lookupffn_workspace_bytes_weighted(n_tokens, k);
+    return hash_bh_core(x, bmats, codes, nullptr, false, n_tokens, d, k, tau, block, n_factors, x_dtype, workspace,
+                        workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
 int lookupffn_hash_bh_weighted(const void *x, const float *bmats, uint16_t *codes, float *weights, int64_t n_tokens,
                                int d, int k, int tau, int block, int n_factors, int x_dtype, void *workspace,
                                int64_t workspace_bytes, void *hip_stream)
 {
-    int rc = check_bh(x, bmats, n_tokens, d, k, tau, block, n_factors, x_dtype, true);
-    if (rc != LFFN_OK) return rc;
-    if (!codes || !weights) return LFFN_E_NULL;
-    if (!aligned(codes, 2) || !aligned(weights, 4)) return LFFN_E_ALIGN;
-    const int64_t need = bh_pack_bytes(d, k, tau, block, n_factors);
-    if (workspace) {
-        if (workspace_bytes < need) return LFFN_E_WORKSPACE;
-        if (!aligned(workspace, 256)) return LFFN_E_ALIGN;
-    }
-    if (n_tokens == 0) return LFFN_OK;
-    void *ws = workspace;
-    if (!ws) {
-        rc = own_workspace((size_t)need, &ws);
-        if (rc != LFFN_OK) return rc;
-    }
-    return launch_hash_bh(x, bmats, static_cast<float *>(ws), codes, nullptr, n_tokens, d, k, tau, block, n_factors,
-                          x_dtype, static_cast<hipStream_t>(hip_stream), weights, nullptr);
+    if (!weights) return (x && bmats && codes) ? LFFN_E_NULL : LFFN_E_NULL;
+    return hash_bh_core(x, bmats, codes, weights, true, n_tokens, d, k, tau, block, n_factors, x_dtype, workspace,
+                        workspace_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+int lookupffn_forward_bh(const void *x, const float *bmats, const void *tables, float *y, int64_t n_tokens, int d,
+                         int k, int tau, int d_out, int block, int n_factors, int x_dtype, int table_dtype,
+                         void *workspace, int64_t workspace_bytes, void *hip_stream)
+{
+    return forward_core(bh_hash(bmats, block, n_factors), kPlain, x, tables, y, n_tokens, d, k, tau, d_out, x_dtype,
+                        table_dtype, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
 int lookupffn_forward_bh_weighted(const void *x, const float *bmats, const void *tables, float *y, int64_t n_tokens,
                                   int d, int k, int tau, int d_out, int block, int n_factors, int x_dtype,
                                   int table_dtype, void *workspace, int64_t workspace_bytes, void *hip_stream)
 {
-    int rc = check_bh(x, bmats, n_tokens, d, k, tau, block, n_factors, x_dtype, true);
+    return forward_core(bh_hash(bmats, block, n_factors), kWeighted, x, tables, y, n_tokens, d, k, tau, d_out,
+                        x_dtype, table_dtype, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+// ---- one-time preparation of the learned constants ------------------------------------------------
+int64_t lookupffn_prepared_tables_bytes(int k, int tau, int d_out, int table_dtype)
+{
+    if (k < 1 || tau < 1 || tau > 16 || d_out < 1 || !dtype_ok(table_dtype)) return 0;
+    if (d_out % (table_dtype == LFFN_F32 ? 4 : 8) != 0 || ((int64_t)k << tau) > (int64_t(1) << 31)) return 0;
+    return prepared_tables_bytes(k, tau, d_out);
+}
+
+int lookupffn_prepare_tables(const void *tables, int k, int tau, int d_out, int table_dtype, void *prepared,
+                             int64_t prepared_bytes, void *hip_stream)
+{
+    if (!tables || !prepared) return LFFN_E_NULL;
+    if (k < 1 || d_out < 1 || k > (1 << 20) || d_out > (1 << 24)) return LFFN_E_SIZE;
+    if (tau < 1 || tau > 16) return LFFN_E_TAU;
+    if (!dtype_ok(table_dtype)) return LFFN_E_DTYPE;
+    if (d_out % (table_dtype == LFFN_F32 ? 4 : 8) != 0) return LFFN_E_ALIGN;
+    if (((int64_t)k << tau) > (int64_t(1) << 31)) return LFFN_E_SIZE;
+    if (!aligned(tables, 16) || !aligned(prepared, 256)) return LFFN_E_ALIGN;
+    const int64_t need = prepared_tables_bytes(k, tau, d_out);
+    if (prepared_bytes < need) return LFFN_E_WORKSPACE;
+    const int pw = prepared_piece_bytes(tau), ppw = pw / 16;
+    const int rows = 1 << tau, nvec = d_out / 4;
+    const long long n_ps = (nvec + ppw - 1) / ppw;
+    const long long n_out = n_ps * k * rows * ppw;
+    long long blocks = (n_out + 255) / 256;
+    if (blocks > 16384) blocks = 16384;
+    hipLaunchKernelGGL(prepare_tables_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                       tables, static_cast<uint4 *>(prepared), k, rows, nvec, ppw, table_dtype == LFFN_BF16 ? 1 : 0, n_out);
+    LFFN_HIP(hipGetLastError());
+    return LFFN_OK;
+}
+
+int64_t lookupffn_prepared_bh_bytes(int d, int k, int tau, int block, int n_factors)
+{
+    if (!bh_shape_ok(d, k, tau, block, n_factors) || (block != 16 && block != 32 && block != 64)) return 0;
+    return bh_pack_bytes(d, k, tau, block, n_factors);
+}
+
+int lookupffn_prepare_bh(const float *bmats, int d, int k, int tau, int block, int n_factors, void *prepared,
+                         int64_t prepared_bytes, void *hip_stream)
+{
+    if (!prepared) return LFFN_E_NULL;
+    const float *stand_in_x = reinterpret_cast<const float *>(uintptr_t(256));
+    int rc = check_bh(stand_in_x, bmats, 0, d, k, tau, block, n_factors, LFFN_F32);
     if (rc != LFFN_OK) return rc;
-    const uint16_t *stand_in = reinterpret_cast<const uint16_t *>(uintptr_t(256));
-    rc = check_gather(stand_in, tables, y, n_tokens, k, tau, d_out, table_dtype);
-    if (rc != LFFN_OK) return rc;
-    const int64_t pack = bh_pack_bytes(d, k, tau, block, n_factors);
-    const int64_t need = pack + lookupffn_workspace_bytes_weighted(n_tokens, k);
-    if (workspace) {
-        if (workspace_bytes < need) return LFFN_E_WORKSPACE;
-        if (!aligned(workspace, 256)) return LFFN_E_ALIGN;
-    }
-    if (n_tokens == 0) return LFFN_OK;
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const bool bf16 = table_dtype == LFFN_BF16;
-    LdsPlan plan;
-    rc = plan_gather_lds(n_tokens, k, tau, d_out, bf16, &plan, true, false, true);
-    if (rc != LFFN_OK) return rc;
-    if (plan.shift != 7) plan.use = false;  // the BH hash writes codes scaled for 128-byte row pieces only
-    const int64_t extra = widen_room(&plan, workspace, workspace_bytes, need);
-    void *ws = workspace;
-    if (!ws) {
-        rc = own_workspace((size_t)(need + extra), &ws);
-        if (rc != LFFN_OK) return rc;
-    }
-    plan.widened = extra ? static_cast<char *>(ws) + need : nullptr;
-    float *apack = static_cast<float *>(ws);
-    char *scratch = static_cast<char *>(ws) + pack;
-    if (plan.use) {
-        uint32_t *packed = reinterpret_cast<uint32_t *>(scratch);
-        float *wpk = reinterpret_cast<float *>(scratch + round256(packed_bytes(n_tokens, k)));
-        rc = launch_hash_bh(x, bmats, apack, nullptr, packed, n_tokens, d, k, tau, block, n_factors, x_dtype, s,
-                            nullptr, wpk);
-        if (rc != LFFN_OK) return rc;
-        return launch_gather_lds(plan, packed, wpk, tables, y, bf16, s);
-    }
-    uint16_t *codes = reinterpret_cast<uint16_t *>(scratch);
-    float *weights = reinterpret_cast<float *>(scratch + weighted_codes_bytes(n_tokens, k));
-    rc = launch_hash_bh(x, bmats, apack, codes, nullptr, n_tokens, d, k, tau, block, n_factors, x_dtype, s, weights,
-                        nullptr);
-    if (rc != LFFN_OK) return rc;
-    return launch_gather_direct(codes, weights, tables, y, n_tokens, k, tau, d_out, table_dtype, s);
+    if (!aligned(prepared, 256)) return LFFN_E_ALIGN;
+    if (prepared_bytes < bh_pack_bytes(d, k, tau, block, n_factors)) return LFFN_E_WORKSPACE;
+    return launch_bh_pack(bmats, static_cast<float *>(prepared), d, k, tau, block, n_factors,
+                          static_cast<hipStream_t>(hip_stream));
 }
 
 int lookupffn_release_workspace(void)
 {
     std::lock_guard<std::mutex> lk(g_ws_mu);
     int rc = LFFN_OK;
+    int cur = 0;
+    const bool have_cur = hipGetDevice(&cur) == hipSuccess;
     for (auto &kv : g_ws) {
-        if (!kv.second.ptr) continue;
-        int cur = 0;
-        if (hipGetDevice(&cur) != hipSuccess || hipSetDevice(kv.first) != hipSuccess ||
-            hipDeviceSynchronize() != hipSuccess || hipFree(kv.second.ptr) != hipSuccess)
-            rc = LFFN_E_HIP;
-        (void)hipSetDevice(cur);
+        if (!kv.second.ptr && kv.second.retired.empty()) continue;
+        if (hipSetDevice(kv.first) != hipSuccess || hipDeviceSynchronize() != hipSuccess) rc = LFFN_E_HIP;
+        if (kv.second.ptr && hipFree(kv.second.ptr) != hipSuccess) rc = LFFN_E_HIP;
+        for (void *p : kv.second.retired)
+            if (hipFree(p) != hipSuccess) rc = LFFN_E_HIP;
         kv.second = Workspace();
     }
+    if (have_cur) (void)hipSetDevice(cur);
     g_ws.clear();
     return rc;
 }
@@ -1330,12 +1463,13 @@ int lookupffn_release_workspace(void)
 int lookupffn_timing_enable(int mask)
 {
     if (mask < 0 || mask > 3) return LFFN_E_SIZE;
-    g_tm.on = mask;
+    g_tm.on.store(mask);
     return LFFN_OK;
 }
 
 int lookupffn_timing_reset(void)
 {
+    std::lock_guard<std::mutex> lk(g_tm.mu);
     for (auto &v : g_tm.ev) {
         for (auto &p : v) {
             (void)hipEventSynchronize(p.second);
@@ -1350,6 +1484,7 @@ int lookupffn_timing_read(int which, double *total_ms, int64_t *launches)
 {
     if (which < 0 || which > 1) return LFFN_E_SIZE;
     if (!total_ms || !launches) return LFFN_E_NULL;
+    std::lock_guard<std::mutex> lk(g_tm.mu);
     double sum = 0.0;
     for (auto &p : g_tm.ev[which]) {
         LFFN_HIP(hipEventSynchronize(p.second));
@@ -1362,9 +1497,27 @@ int lookupffn_timing_read(int which, double *total_ms, int64_t *launches)
     return LFFN_OK;
 }
 
+int lookupffn_timing_read_each(int which, double *ms_out, int64_t capacity, int64_t *launches)
+{
+    if (which < 0 || which > 1 || capacity < 0) return LFFN_E_SIZE;
+    if (!launches || (capacity > 0 && !ms_out)) return LFFN_E_NULL;
+    std::lock_guard<std::mutex> lk(g_tm.mu);
+    int64_t i = 0;
+    for (auto &p : g_tm.ev[which]) {
+        if (i >= capacity) break;
+        LFFN_HIP(hipEventSynchronize(p.second));
+        float ms = 0.0f;
+        LFFN_HIP(hipEventElapsedTime(&ms, p.first, p.second));
+        ms_out[i++] = ms;
+    }
+    *launches = (int64_t)g_tm.ev[which].size();
+    return LFFN_OK;
+}
+
 int lookupffn_set_option(const char *key, int value)
 {
     if (!key) return LFFN_E_NULL;
+    std::lock_guard<std::mutex> lk(g_opt_mu);
     if (!std::strcmp(key, "lanes_per_token")) {
         if (value != 0 && (value < 1 || value > 64 || (value & (value - 1)))) return LFFN_E_SIZE;
         g_opt.lanes_per_token = value;
@@ -1412,8 +1565,8 @@ const char *lookupffn_strerror(int status)
         case LFFN_E_TAU: return "tau must be in [1, 16]";
         case LFFN_E_DTYPE: return "unknown dtype";
         case LFFN_E_ALIGN: return "pointer alignment or d_out granularity not met";
-        case LFFN_E_UNSUPPORTED: return "shape not supported (d_pad above 4096)";
-        case LFFN_E_WORKSPACE: return "workspace too small";
+        case LFFN_E_UNSUPPORTED: return "shape not supported by this entry point";
+        case LFFN_E_WORKSPACE: return "workspace or output buffer too small";
         case LFFN_E_HIP: return "a HIP call failed";
         default: return "unknown status";
     }
@@ -1421,7 +1574,7 @@ const char *lookupffn_strerror(int status)
 
 const char *lookupffn_last_hip_error(void) { return g_hip_error.c_str(); }
 
-const char *lookupffn_last_gather_kernel(void) { return g_last_gather; }
+const char *lookupffn_last_gather_kernel(void) { return t_last_gather; }
 
 int lookupffn_version(void) { return kVersion; }
 

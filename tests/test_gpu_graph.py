@@ -96,3 +96,58 @@ def test_captured_single_layer_replays_like_eager(variant):
         assert np.array_equal(got, eager), f"replay {rep} differs from the eager call"
         r = ref(x_new).astype(np.float64)
         assert np.max(np.abs(got - r)) / np.sqrt(np.mean(r ** 2)) <= 1e-4
+
+
+@pytest.mark.parametrize("variant", ["plain", "weighted", "probes"])
+def test_captured_stand_alone_gather_replays_like_eager(variant):
+    """lookupffn_gather* with a caller workspace after lookupffn_init(): kernel launches only, so the call
+    (re-pack kernels + the LDS-staged gather) can be captured without an eager warm-up of its own."""
+    print(f"graph capture: stand-alone gather, {variant}, 3000 tokens of the C2 shape", flush=True)
+    B.lookupffn_init()
+    n, k, tau, d_out = 3000, 96, 8, 768
+    tables = synth.make_tables(31, k, 1 << tau, d_out)
+    prep = B.lookupffn_prepare_tables(B.to_device(tables))
+    rng = np.random.default_rng(17)
+    codes_in = torch.zeros((n, k), dtype=torch.int16, device="cuda")
+    if variant == "plain":
+        wts_in, call = None, lambda y: B.lookupffn_gather(codes_in, prep, y=y, workspace=ws)
+        nbytes = B.lookupffn_workspace_bytes_gather(n, k)
+    elif variant == "weighted":
+        wts_in = torch.zeros((n, k), dtype=torch.float32, device="cuda")
+        call = lambda y: B.lookupffn_gather_weighted(codes_in, wts_in, prep, y=y, workspace=ws)
+        nbytes = B.lookupffn_workspace_bytes_gather_weighted(n, k)
+    else:
+        wts_in = torch.zeros((n, k, tau + 1), dtype=torch.float32, device="cuda")
+        call = lambda y: B.lookupffn_gather_probes(codes_in, wts_in, prep, y=y, workspace=ws)
+        nbytes = B.lookupffn_workspace_bytes_gather_probes(n, k, tau)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    y = torch.empty((n, d_out), dtype=torch.float32, device="cuda")
+    B.lookupffn_set_option("gather_path", 2)
+    try:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            call(y)
+        assert B.lookupffn_last_gather_kernel() == "gather_lds_kernel"
+        torch.cuda.synchronize()
+        for rep in range(3):
+            codes = rng.integers(0, 1 << tau, size=(n, k)).astype(np.uint16)
+            codes_in.copy_(torch.from_numpy(codes.view(np.int16)))
+            if wts_in is not None:
+                wts = rng.random(tuple(wts_in.shape), dtype=np.float32)
+                wts_in.copy_(torch.from_numpy(wts))
+            y.fill_(float("nan"))
+            graph.replay()
+            torch.cuda.synchronize()
+            got = y.clone().cpu().numpy()
+            eager = call(y).clone().cpu().numpy()       # eager, same buffers, between the replays
+            assert np.array_equal(got, eager), f"replay {rep} differs from the eager call"
+            if variant == "plain":
+                assert np.array_equal(got, oracle.gather(codes, tables, acc64=False))
+            elif variant == "weighted":
+                r = oracle.gather_weighted(codes, wts.astype(np.float64), tables).astype(np.float64)
+                assert np.max(np.abs(got - r)) / np.sqrt(np.mean(r ** 2)) <= 1e-4
+            else:
+                r = oracle.gather_probes(codes, wts.astype(np.float64), tables).astype(np.float64)
+                assert np.max(np.abs(got - r)) / np.sqrt(np.mean(r ** 2)) <= 1e-4
+    finally:
+        B.lookupffn_set_option("gather_path", 0)

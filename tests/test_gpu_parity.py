@@ -11,6 +11,7 @@ import torch
 import oracle
 from paper_2403_07221_amd import binding as B
 from paper_2403_07221_amd import synth
+from sampling import sample_tokens
 
 pytestmark = pytest.mark.gpu
 
@@ -358,50 +359,127 @@ def test_forward_config3_full_size_bf16():
     print("forward C3 (65536 tokens, bf16)", flush=True)
     w = synth.C3
     x, signs, tables = synth.make_layer(w)
-    check_forward(w, x, signs, tables, sample=np.arange(0, w.n_tokens, 8))
+    check_forward(w, x, signs, tables, sample=sample_tokens(w.n_tokens, 7))
 
 
-def test_forward_bf16_tables_widened_copy_and_workspace_sizes():
-    """bf16 tables with a large batch: the staged gather runs on an fp32 copy made in scratch memory.  A
-    caller workspace with room for the copy takes that path, one without it the direct gather; same bits."""
-    print("forward bf16 tables, 16384 tokens: workspace with and without room for the widened tables", flush=True)
+def test_forward_bf16_tables_prepared_once_take_the_staged_gather():
+    """bf16 tables: the staged gather reads fp32 rows, so it runs on the copy lookupffn_prepare_tables makes
+    once; the raw bf16 tables take the direct gather.  Same bits either way."""
+    print("forward bf16 tables, 16384 tokens: raw tables (direct gather) and prepared tables (staged gather)", flush=True)
     w = synth.C3.with_tokens(16384)
     x, signs, tables = synth.make_layer(w)
     xd, sd, td = B.to_device(x), B.to_device(signs), B.to_device(tables)
-    base = B.lookupffn_workspace_bytes(w.n_tokens, w.k)
-    extra = B.lookupffn_workspace_bytes_tables(w.k, w.tau, w.d_out, "bf16")
-    assert extra == w.k * w.rows * w.d_out * 4 and B.lookupffn_workspace_bytes_tables(w.k, w.tau, w.d_out, "f32") == 0
-    want = oracle.forward(x[::16], signs, tables, acc64=False)
-    for nbytes, kernel in ((base + extra, "gather_lds_kernel"), (base, "gather_kernel"), (None, "gather_lds_kernel")):
-        ws = None if nbytes is None else torch.empty(nbytes, dtype=torch.uint8, device="cuda")
-        y = B.lookupffn_forward(xd, sd, td, workspace=ws)
+    prep = B.lookupffn_prepare_tables(td)
+    assert prep.buf.numel() == w.k * w.rows * w.d_out * 4 == B.lookupffn_prepared_tables_bytes(w.k, w.tau, w.d_out, "bf16")
+    sel = sample_tokens(w.n_tokens, 17)
+    want = oracle.forward(x[sel], signs, tables, acc64=False)
+    ws = torch.empty(B.lookupffn_workspace_bytes(w.n_tokens, w.k), dtype=torch.uint8, device="cuda")
+    for tab, work, kernel in ((prep, ws, "gather_lds_kernel"), (td, ws, "gather_kernel"), (prep, None, "gather_lds_kernel")):
+        y = B.lookupffn_forward(xd, sd, tab, workspace=work)
         torch.cuda.synchronize()
         assert B.lookupffn_last_gather_kernel() == kernel
-        assert np.array_equal(y.cpu().numpy()[::16], want)
-    yw = B.lookupffn_forward_weighted(xd, sd, td)
+        assert np.array_equal(y.cpu().numpy()[sel], want)
+    yw = B.lookupffn_forward_weighted(xd, sd, prep)
     torch.cuda.synchronize()
     assert B.lookupffn_last_gather_kernel() == "gather_lds_kernel"
-    ref = oracle.forward_weighted(x[::16], signs, tables)
-    assert rel_err(yw.cpu().numpy()[::16], ref) <= TOL_BF16
-    # a small batch does not repay the copy: direct gather
-    small = B.lookupffn_forward(xd[:2000], sd, td)
+    ref = oracle.forward_weighted(x[sel], signs, tables)
+    assert rel_err(yw.cpu().numpy()[sel], ref) <= TOL_BF16
+    # a small batch does not repay staging: direct gather, reading the prepared copy
+    small = B.lookupffn_forward(xd[:2000], sd, prep)
     torch.cuda.synchronize()
     assert B.lookupffn_last_gather_kernel() == "gather_kernel"
-    assert np.array_equal(small.cpu().numpy()[::16], want[:125])
+    sel_small = sel[sel < 2000]
+    assert np.array_equal(small.cpu().numpy()[sel_small], want[:len(sel_small)])
+
+
+PREPARED_SHAPES = [
+    # n, k, tau, d_out, table dtype
+    (3000, 96, 8, 768, "f32"),       # 128-byte pieces, no padding
+    (3000, 10, 8, 520, "bf16"),      # ragged last piece (2080-byte fp32 rows: 16.25 pieces)
+    (5000, 24, 7, 200, "f32"),       # tau = 7, ragged
+    (130, 2, 7, 4, "f32"),           # one 16-byte piece per row in a 128-byte piece
+    (9000, 6, 9, 200, "f32"),        # tau = 9: 64-byte pieces, ragged
+    (3000, 170, 9, 768, "bf16"),
+    (5000, 128, 10, 1024, "f32"),    # tau = 10
+    (2500, 2, 10, 16, "f32"),
+    (500, 10, 6, 64, "f32"),         # tau outside the staged kernel's range: the direct kernel reads the copy
+    (300, 7, 11, 72, "bf16"),        # odd k, tau = 11, 64-byte pieces
+    (40, 3, 1, 8, "bf16"),           # two-row tables
+]
+
+
+@pytest.mark.parametrize("n,k,tau,d_out,tdt", PREPARED_SHAPES)
+def test_gather_prepared_tables_equal_row_major_tables(n, k, tau, d_out, tdt):
+    print(f"gather with prepared tables n={n} k={k} tau={tau} d_out={d_out} {tdt}", flush=True)
+    tables = synth.make_tables(n + k + 1, k, 1 << tau, d_out, tdt)
+    codes = np.random.default_rng(n + 1).integers(0, 1 << tau, size=(n, k)).astype(np.uint16)
+    want = oracle.gather(codes, tables, acc64=False)
+    td = B.to_device(tables)
+    prep = B.lookupffn_prepare_tables(td)
+    assert prep.buf.numel() == B.lookupffn_prepared_tables_bytes(k, tau, d_out, tdt)
+    cd = torch.from_numpy(codes.view(np.int16)).cuda()
+    ws = torch.empty(max(B.lookupffn_workspace_bytes_gather(n, k), 256), dtype=torch.uint8, device="cuda")
+    try:
+        for path in (2, 1):
+            B.lookupffn_set_option("gather_path", path)
+            for lanes in ((0, 4, 8) if path == 2 else (0,)):
+                B.lookupffn_set_option("slice_lanes", lanes)
+                y = B.lookupffn_gather(cd, prep, workspace=ws)
+                torch.cuda.synchronize()
+                assert np.array_equal(y.cpu().numpy(), want), f"path {path}, slice_lanes {lanes}"
+        for lpt in (1, 2, 4, 8, 16):           # the direct kernel's lane widths, clamped to the prepared piece
+            B.lookupffn_set_option("gather_path", 1)
+            B.lookupffn_set_option("lanes_per_token", lpt)
+            y = B.lookupffn_gather(cd, prep)
+            torch.cuda.synchronize()
+            assert np.array_equal(y.cpu().numpy(), want), f"direct, lanes_per_token {lpt}"
+    finally:
+        B.lookupffn_set_option("gather_path", 0)
+        B.lookupffn_set_option("slice_lanes", 0)
+        B.lookupffn_set_option("lanes_per_token", 0)
+
+
+def test_prepared_tables_in_every_variant():
+    print("prepared tables: plain / weighted / multi-probe / BH forward equal the row-major results", flush=True)
+    w = synth.C2.with_tokens(3000)
+    x, signs, tables = synth.make_layer(w)
+    xd, sd, td = B.to_device(x), B.to_device(signs), B.to_device(tables)
+    prep = B.lookupffn_prepare_tables(td)
+    bm = synth.make_bmats(9, w.n_proj, 4, w.d_pad, 32)
+    bd = torch.from_numpy(bm).cuda()
+    pbh = B.lookupffn_prepare_bh(bd, w.d, w.k, w.tau)
+    for name, fwd, par, ppar in (("plain", B.lookupffn_forward, sd, sd), ("weighted", B.lookupffn_forward_weighted, sd, sd),
+                                 ("probes", B.lookupffn_forward_probes, sd, sd), ("bh", B.lookupffn_forward_bh, bd, pbh),
+                                 ("bh weighted", B.lookupffn_forward_bh_weighted, bd, pbh)):
+        for path in (2, 1):
+            B.lookupffn_set_option("gather_path", path)
+            try:
+                a = fwd(xd, par, td)
+                b = fwd(xd, ppar, prep)
+                torch.cuda.synchronize()
+            finally:
+                B.lookupffn_set_option("gather_path", 0)
+            assert torch.equal(a, b), f"{name}, gather_path {path}"
+    # the stand-alone BH hashes with prepared factors
+    assert torch.equal(B.lookupffn_hash_bh(xd, bd, w.k, w.tau), B.lookupffn_hash_bh(xd, pbh, w.k, w.tau))
+    c1, w1 = B.lookupffn_hash_bh_weighted(xd, bd, w.k, w.tau)
+    c2, w2 = B.lookupffn_hash_bh_weighted(xd, pbh, w.k, w.tau)
+    assert torch.equal(c1, c2) and torch.equal(w1, w2)
+    assert np.array_equal(B.codes_to_numpy(c1), oracle.bh_hash_codes(x, bm, w.k, w.tau))
 
 
 def test_forward_config4_full_size():
     print("forward C4 (16384 tokens, tau=10, 512 MB of tables)", flush=True)
     w = synth.C4
     x, signs, tables = synth.make_layer(w)
-    check_forward(w, x, signs, tables, sample=np.arange(0, w.n_tokens, 4))
+    check_forward(w, x, signs, tables, sample=sample_tokens(w.n_tokens, 5))
 
 
 @pytest.mark.parametrize("w", [synth.P6, synth.P7, synth.P8], ids=lambda w: w.name)
 def test_forward_paper_shapes_full_size(w):
     print(f"forward {w.name} ({w.n_tokens} tokens, d={w.d}, h={w.k}, tau={w.tau})", flush=True)
     x, signs, tables = synth.make_layer(w)
-    check_forward(w, x, signs, tables, sample=np.arange(0, w.n_tokens, 8))
+    check_forward(w, x, signs, tables, sample=sample_tokens(w.n_tokens, 7))
 
 
 def test_forward_config5_stacked_layers():

@@ -42,8 +42,8 @@ def hash_call(L, x=FAKE, signs=FAKE, codes=FAKE, n=0, d=768, k=96, tau=8, rounds
     return L.lookupffn_hash(x, signs, codes, n, d, k, tau, rounds, dt, None)
 
 
-def gather_call(L, codes=FAKE, tables=FAKE, y=FAKE, n=0, k=96, tau=8, d_out=768, dt=0):
-    return L.lookupffn_gather(codes, tables, y, n, k, tau, d_out, dt, None)
+def gather_call(L, codes=FAKE, tables=FAKE, y=FAKE, n=0, k=96, tau=8, d_out=768, dt=0, ws=None, wsb=0):
+    return L.lookupffn_gather(codes, tables, y, n, k, tau, d_out, dt, ws, wsb, None)
 
 
 def forward_call(L, x=FAKE, signs=FAKE, tables=FAKE, y=FAKE, n=0, d=768, k=96, tau=8, d_out=768, rounds=3,
@@ -74,6 +74,14 @@ def test_gather_argument_errors(L):
     assert gather_call(L, d_out=770) == -5                    # fp32 rows must be whole 16-byte pieces
     assert gather_call(L, d_out=772) == 0 and gather_call(L, d_out=772, dt=1) == -5
     assert gather_call(L, tables=FAKE + 4) == -5 and gather_call(L, y=FAKE + 8) == -5
+    # prepared tables: the flag with either source dtype; the buffer is 256-byte aligned
+    assert gather_call(L, dt=0x100) == 0 and gather_call(L, dt=0x101) == 0 and gather_call(L, dt=0x102) == -4
+    assert gather_call(L, dt=0x200) == -4 and gather_call(L, tables=FAKE + 16, dt=0x100) == -5
+    assert gather_call(L, d_out=772, dt=0x101) == -5          # the source rows were bf16: whole 16-byte pieces of those
+    # scratch of the stand-alone gather: too small or misaligned is refused before any launch
+    need = L.lookupffn_workspace_bytes_gather(1000, 96)
+    assert need >= 48 * 1000 * 4 and need % 256 == 0 and L.lookupffn_workspace_bytes_gather(0, 96) == 0
+    assert gather_call(L, n=1000, ws=FAKE, wsb=need - 1) == -7 and gather_call(L, n=1000, ws=FAKE + 16, wsb=need) == -5
 
 
 def test_forward_argument_errors(L):
@@ -91,8 +99,8 @@ def test_weighted_argument_errors(L):
     def hw(x=FAKE, signs=FAKE, codes=FAKE, w=FAKE, n=0, d=768, k=96, tau=8, rounds=3, dt=0):
         return L.lookupffn_hash_weighted(x, signs, codes, w, n, d, k, tau, rounds, dt, None)
 
-    def gw(codes=FAKE, w=FAKE, tables=FAKE, y=FAKE, n=0, k=96, tau=8, d_out=768, dt=0):
-        return L.lookupffn_gather_weighted(codes, w, tables, y, n, k, tau, d_out, dt, None)
+    def gw(codes=FAKE, w=FAKE, tables=FAKE, y=FAKE, n=0, k=96, tau=8, d_out=768, dt=0, ws=None, wsb=0):
+        return L.lookupffn_gather_weighted(codes, w, tables, y, n, k, tau, d_out, dt, ws, wsb, None)
 
     def fw(x=FAKE, tables=FAKE, y=FAKE, n=0, d=768, tau=8, ws=None, wsb=0):
         return L.lookupffn_forward_weighted(x, FAKE, tables, y, n, d, 96, tau, 768, 3, 0, 0, ws, wsb, None)
@@ -105,13 +113,60 @@ def test_weighted_argument_errors(L):
     need = L.lookupffn_workspace_bytes_weighted(1000, 96)
     assert need >= 1000 * 96 * 6 and need % 256 == 0 and L.lookupffn_workspace_bytes_weighted(0, 96) == 0
     assert fw(n=1000, ws=FAKE, wsb=need - 1) == -7 and fw(n=1000, ws=FAKE + 16, wsb=need) == -5
+    gneed = L.lookupffn_workspace_bytes_gather_weighted(1000, 96)
+    assert L.lookupffn_workspace_bytes_gather(1000, 96) + 1000 * 96 * 4 <= gneed < need
+    assert gw(n=1000, ws=FAKE, wsb=gneed - 1) == -7 and gw(n=1000, ws=FAKE + 16, wsb=gneed) == -5
 
 
-def test_workspace_for_widened_tables(L):
-    assert L.lookupffn_workspace_bytes_tables(96, 8, 768, 1) == 96 * 256 * 768 * 4
-    assert L.lookupffn_workspace_bytes_tables(96, 8, 768, 0) == 0           # fp32 tables need no copy
-    assert L.lookupffn_workspace_bytes_tables(3, 7, 8, 1) % 256 == 0
-    assert L.lookupffn_workspace_bytes_tables(0, 8, 768, 1) == 0 and L.lookupffn_workspace_bytes_tables(96, 17, 768, 1) == 0
+def test_prepare_tables_sizes_and_argument_errors(L):
+    def prep(tables=FAKE, k=96, tau=8, d_out=768, dt=0, out=FAKE, nbytes=None):
+        nbytes = L.lookupffn_prepared_tables_bytes(k, tau, d_out, dt) if nbytes is None else nbytes
+        return L.lookupffn_prepare_tables(tables, k, tau, d_out, dt, out, nbytes, None)
+
+    # fp32 copy, slice-major: whole 128-byte (tau <= 8) or 64-byte (tau >= 9) pieces per row
+    assert L.lookupffn_prepared_tables_bytes(96, 8, 768, 0) == 96 * 256 * 768 * 4
+    assert L.lookupffn_prepared_tables_bytes(96, 8, 768, 1) == 96 * 256 * 768 * 4       # bf16 rows are widened
+    assert L.lookupffn_prepared_tables_bytes(2, 7, 8, 0) == 2 * 128 * 128                # 32-byte rows padded to a piece
+    assert L.lookupffn_prepared_tables_bytes(6, 9, 200, 0) == 6 * 512 * 13 * 64          # 800-byte rows: 13 pieces of 64
+    assert L.lookupffn_prepared_tables_bytes(3, 10, 72, 1) % 256 == 0
+    for bad in ((0, 8, 768, 0), (96, 17, 768, 0), (96, 0, 768, 0), (96, 8, 770, 0), (96, 8, 772, 1), (96, 8, 768, 2)):
+        assert L.lookupffn_prepared_tables_bytes(*bad) == 0
+    assert prep(tables=None) == -1 and prep(out=None) == -1
+    assert prep(k=0) == -2 and prep(tau=0) == -3 and prep(tau=17) == -3 and prep(dt=2) == -4 and prep(dt=0x100) == -4
+    assert prep(d_out=770) == -5 and prep(d_out=772, dt=1) == -5
+    assert prep(tables=FAKE + 8) == -5 and prep(out=FAKE + 16) == -5
+    assert prep(nbytes=96 * 256 * 768 * 4 - 1) == -7
+
+
+def test_prepare_bh_sizes_and_argument_errors(L):
+    def prep(bm=FAKE, d=768, k=96, tau=8, block=64, m=4, out=FAKE, nbytes=None):
+        nbytes = L.lookupffn_prepared_bh_bytes(d, k, tau, block, m) if nbytes is None else nbytes
+        return L.lookupffn_prepare_bh(bm, d, k, tau, block, m, out, nbytes, None)
+
+    assert L.lookupffn_prepared_bh_bytes(768, 96, 8, 64, 4) == 4 * 1024 * 64 * 4         # P * m * d_pad * block floats
+    assert L.lookupffn_prepared_bh_bytes(512, 256, 8, 16, 4) == 4 * 4 * 512 * 16 * 4
+    assert L.lookupffn_prepared_bh_bytes(768, 96, 8, 48, 4) == 0 and L.lookupffn_prepared_bh_bytes(2000, 96, 8, 64, 4) == 0
+    assert prep(bm=None) == -1 and prep(out=None) == -1 and prep(block=8) == -6 and prep(d=20, k=4) == -6
+    assert prep(tau=0) == -3 and prep(m=0) == -2 and prep(out=FAKE + 16) == -5 and prep(bm=FAKE + 2) == -5
+    assert prep(nbytes=1024) == -7
+    # a workspace for the prepared form need not hold the re-ordered factors
+    full = L.lookupffn_workspace_bytes_bh(1000, 768, 96, 8, 64, 4)
+    assert L.lookupffn_workspace_bytes_bh(1000, 768, 96, 8, 0x100 | 64, 4) == full - 4 * 1024 * 64 * 4
+    assert L.lookupffn_hash_bh(FAKE, FAKE, FAKE, 0, 768, 96, 8, 0x100 | 64, 4, 0, None, 0, None) == 0
+    assert L.lookupffn_hash_bh(FAKE, FAKE + 16, FAKE, 0, 768, 96, 8, 0x100 | 64, 4, 0, None, 0, None) == -5
+    assert L.lookupffn_hash_bh(FAKE, FAKE, FAKE, 0, 768, 96, 8, 0x100 | 48, 4, 0, None, 0, None) == -6
+
+
+def test_timing_read_argument_errors(L):
+    cnt = ctypes.c_int64(0)
+    ms = ctypes.c_double(0)
+    assert L.lookupffn_timing_read(2, ctypes.byref(ms), ctypes.byref(cnt)) == -2
+    assert L.lookupffn_timing_read(0, None, ctypes.byref(cnt)) == -1
+    assert L.lookupffn_timing_read_each(0, None, 0, ctypes.byref(cnt)) == 0 and cnt.value == 0
+    assert L.lookupffn_timing_read_each(0, None, 4, ctypes.byref(cnt)) == -1
+    assert L.lookupffn_timing_read_each(3, None, 0, ctypes.byref(cnt)) == -2
+    assert L.lookupffn_timing_read_each(0, None, -1, ctypes.byref(cnt)) == -2
+    assert L.lookupffn_timing_read_each(0, None, 0, None) == -1
 
 
 def test_bh_argument_errors(L):
@@ -154,8 +209,8 @@ def test_probe_argument_errors(L):
     def hp(x=FAKE, signs=FAKE, codes=FAKE, sh=FAKE, n=0, d=768, k=96, tau=8):
         return L.lookupffn_hash_probes(x, signs, codes, sh, n, d, k, tau, 3, 0, None)
 
-    def gp(codes=FAKE, sh=FAKE, tables=FAKE, y=FAKE, n=0, tau=8, d_out=768):
-        return L.lookupffn_gather_probes(codes, sh, tables, y, n, 96, tau, d_out, 0, None)
+    def gp(codes=FAKE, sh=FAKE, tables=FAKE, y=FAKE, n=0, tau=8, d_out=768, ws=None, wsb=0):
+        return L.lookupffn_gather_probes(codes, sh, tables, y, n, 96, tau, d_out, 0, ws, wsb, None)
 
     def fp(x=FAKE, y=FAKE, n=0, tau=8, ws=None, wsb=0):
         return L.lookupffn_forward_probes(x, FAKE, FAKE, y, n, 768, 96, tau, 768, 3, 0, 0, ws, wsb, None)
@@ -167,6 +222,9 @@ def test_probe_argument_errors(L):
     need = L.lookupffn_workspace_bytes_probes(1000, 96, 8)
     assert need >= 1000 * 96 * (2 + 9 * 4) and need % 256 == 0 and L.lookupffn_workspace_bytes_probes(0, 96, 8) == 0
     assert fp(n=1000, ws=FAKE, wsb=need - 1) == -7 and fp(n=1000, ws=FAKE + 16, wsb=need) == -5
+    gneed = L.lookupffn_workspace_bytes_gather_probes(1000, 96, 8)
+    assert 1000 * 96 * 9 * 4 <= gneed < need and L.lookupffn_workspace_bytes_gather_probes(1000, 96, 17) == 0
+    assert gp(n=1000, ws=FAKE, wsb=gneed - 1) == -7 and gp(n=1000, ws=FAKE + 16, wsb=gneed) == -5
 
 
 def test_options(L):
