@@ -118,6 +118,22 @@ int lookupffn_forward(const void *x, const int8_t *signs, const void *tables, fl
 int64_t lookupffn_workspace_bytes(int64_t n_tokens, int k);
 
 /*
+ * lookupffn_forward for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * bit-identical y, but the intermediates live in a device array that is part of the library's code object
+ * (lookupffn_static_scratch_bytes() = 16 MiB per GPU, held from load until the process ends), so the call
+ * allocates nothing and frees nothing.  Batches whose intermediates (lookupffn_workspace_bytes(n_tokens, k))
+ * exceed that size return LFFN_E_WORKSPACE (k = 96: batches up to about 41000 tokens fit).  All calls on one GPU
+ * share the one array: calls that overlap in time on a GPU (two streams, two threads) race on it; order
+ * them on one stream.  Nothing in the array needs clearing between calls (every word a call reads, it
+ * wrote first).  The array's address is looked up on the first call on a device, or by lookupffn_init().
+ */
+int lookupffn_forward_static(const void *x, const int8_t *signs, const void *tables, float *y,
+                             int64_t n_tokens, int d, int k, int tau, int d_out,
+                             int n_rounds, int x_dtype, int table_dtype, void *hip_stream);
+int64_t lookupffn_static_scratch_bytes(void);
+
+/*
  * One-time preparation of the learned tables T_1 .. T_k of eq. "lookup" (Sec. 3.1): they are constants of
  * the model, so the layout the gather kernels stream best is written once, outside the forward pass.
  * lookupffn_prepare_tables copies tables[k][2^tau][d_out] (fp32 or bf16) into `prepared` as fp32 (bf16

@@ -20,6 +20,7 @@ PREPARED = 0x100   # OR-ed into table_dtype / block: the buffer is a prepared co
 EXPORTS = (
     "lookupffn_init",
     "lookupffn_hash", "lookupffn_gather", "lookupffn_forward", "lookupffn_workspace_bytes",
+    "lookupffn_forward_static", "lookupffn_static_scratch_bytes",
     "lookupffn_workspace_bytes_gather", "lookupffn_prepared_tables_bytes", "lookupffn_prepare_tables",
     "lookupffn_release_workspace", "lookupffn_timing_enable", "lookupffn_timing_reset",
     "lookupffn_timing_read", "lookupffn_timing_read_each", "lookupffn_set_option", "lookupffn_strerror",
@@ -53,6 +54,8 @@ def lib() -> ctypes.CDLL:
         L.lookupffn_hash.argtypes = [vp, vp, vp, i64, ci, ci, ci, ci, ci, vp]
         L.lookupffn_gather.argtypes = [vp, vp, vp, i64, ci, ci, ci, ci, vp, i64, vp]
         L.lookupffn_forward.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, ci, ci, vp, i64, vp]
+        L.lookupffn_forward_static.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, ci, ci, vp]
+        L.lookupffn_static_scratch_bytes.restype = i64
         L.lookupffn_hash_weighted.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, vp]
         L.lookupffn_gather_weighted.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, vp, i64, vp]
         L.lookupffn_forward_weighted.argtypes = L.lookupffn_forward.argtypes
@@ -330,6 +333,25 @@ def lookupffn_forward(x: torch.Tensor, signs: torch.Tensor, tables,
         _check(getattr(lib(), _entry)(_dev(x, "x"), _dev(signs, "signs"), tptr, _dev(y, "y"),
                                       n, d, k, tau, d_out, signs.shape[1], _dtype_code(x), tcode,
                                       ws_ptr, ws_bytes, _stream(x)))
+    return y
+
+
+def lookupffn_static_scratch_bytes() -> int:
+    return lib().lookupffn_static_scratch_bytes()
+
+
+def lookupffn_forward_static(x: torch.Tensor, signs: torch.Tensor, tables, y: torch.Tensor) -> torch.Tensor:
+    """lookupffn_forward with the intermediates in the library's static device array: no allocation at all
+    (y is the caller's).  Raises LookupFFNError(-7) when the batch needs more than that array holds."""
+    n, d = x.shape
+    tptr, k, tau, d_out, tcode, _ = _tables(tables)
+    _check_signs(signs, d, k, tau)
+    assert y.dtype == torch.float32 and tuple(y.shape) == (n, d_out)
+    if n == 0:
+        return y
+    with torch.cuda.device(x.device):
+        _check(lib().lookupffn_forward_static(_dev(x, "x"), _dev(signs, "signs"), tptr, _dev(y, "y"), n, d, k, tau,
+                                              d_out, signs.shape[1], _dtype_code(x), tcode, _stream(x)))
     return y
 
 

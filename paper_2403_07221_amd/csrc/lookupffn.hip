@@ -465,6 +465,33 @@ int get_scratch(void *workspace, int64_t workspace_bytes, int64_t need, Scratch 
     return LFFN_OK;
 }
 
+// ---------------------------------------------------------------- static scratch (lookupffn_forward_static)
+// Device memory that exists from the moment the code object is loaded: the workspace of the entry point
+// for callers that cannot allocate.  Every GPU the library runs on holds its own copy until the process
+// ends.  The name is a host-side stand-in, not a device address: host code uses the address
+// hipGetSymbolAddress returns for the current device (kept per device below), never the name.
+constexpr int64_t kStaticScratchBytes = int64_t(16) << 20;
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kStaticScratchBytes];
+
+std::mutex g_static_mu;
+std::map<int, void *> g_static_ptr;  // device -> address of that device's copy of `scratch`
+
+int static_scratch(void **out)
+{
+    int dev = 0;
+    LFFN_HIP(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lk(g_static_mu);
+    auto it = g_static_ptr.find(dev);
+    if (it == g_static_ptr.end()) {
+        void *p = nullptr;
+        LFFN_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || !aligned(p, 256)) return hip_fail(hipErrorInvalidSymbol, "hipGetSymbolAddress(scratch)");
+        it = g_static_ptr.emplace(dev, p).first;
+    }
+    *out = it->second;
+    return LFFN_OK;
+}
+
 // ---------------------------------------------------------------- tables: row-major or prepared
 // Bytes per row piece of the prepared (slice-major) layout: 128 up to tau = 8 (the staged gather's
 // 128-byte column slices; its 64-byte form reads half pieces), 64 from tau = 9 on.
@@ -1188,6 +1215,11 @@ int lookupffn_init(void)
     int cus = 0;
     int rc = device_cus(&cus);
     if (rc != LFFN_OK) return rc;
+    {
+        void *p = nullptr;  // the static scratch array's address on this device
+        rc = static_scratch(&p);
+        if (rc != LFFN_OK) return rc;
+    }
     // code objects are loaded on first use: do that now for the two parts no attribute call below touches
     // (this one: hash, re-pack and prepare kernels; and the direct gather's)
     {
@@ -1339,6 +1371,25 @@ int lookupffn_forward(const void *x, const int8_t *signs, const void *tables, fl
 {
     return forward_core(sign_hash(signs, n_rounds), kPlain, x, tables, y, n_tokens, d, k, tau, d_out, x_dtype,
                         table_dtype, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+int64_t lookupffn_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int lookupffn_forward_static(const void *x, const int8_t *signs, const void *tables, float *y, int64_t n_tokens,
+                             int d, int k, int tau, int d_out, int n_rounds, int x_dtype, int table_dtype,
+                             void *hip_stream)
+{
+    // sizes first (no HIP call yet): a batch whose intermediates do not fit the static array is refused
+    if (n_tokens > 0 && k >= 1 && tau >= 1 && tau <= 16 && n_tokens <= (int64_t(1) << 40) && k <= (1 << 20) &&
+        forward_ws_bytes(n_tokens, k, tau, kPlain) > kStaticScratchBytes)
+        return LFFN_E_WORKSPACE;
+    void *ws = reinterpret_cast<void *>(uintptr_t(256));  // stand-in until the arguments have been checked
+    if (n_tokens > 0 && x && signs && tables && y) {
+        int rc = static_scratch(&ws);
+        if (rc != LFFN_OK) return rc;
+    }
+    return forward_core(sign_hash(signs, n_rounds), kPlain, x, tables, y, n_tokens, d, k, tau, d_out, x_dtype,
+                        table_dtype, ws, kStaticScratchBytes, static_cast<hipStream_t>(hip_stream));
 }
 
 int lookupffn_forward_weighted(const void *x, const int8_t *signs, const void *tables, float *y, int64_t n_tokens,

@@ -95,6 +95,19 @@ def test_forward_argument_errors(L):
     assert forward_call(L, n=1000, ws=FAKE + 16, wsb=need) == -5
 
 
+def test_forward_static_argument_errors(L):
+    def fs(x=FAKE, signs=FAKE, tables=FAKE, y=FAKE, n=0, d=768, k=96, tau=8, d_out=768, xdt=0, tdt=0):
+        return L.lookupffn_forward_static(x, signs, tables, y, n, d, k, tau, d_out, 3, xdt, tdt, None)
+
+    assert L.lookupffn_static_scratch_bytes() == 16 << 20
+    assert fs() == 0                                                   # empty batch
+    assert fs(x=None) == -1 and fs(y=None) == -1 and fs(tau=0) == -3 and fs(tdt=9) == -4 and fs(d=5000) == -6
+    assert fs(n=5, x=None) == -1                                       # argument errors need no GPU
+    # the static array bounds the batch: refused before any HIP call
+    assert L.lookupffn_workspace_bytes(41000, 96) <= 16 << 20 < L.lookupffn_workspace_bytes(45000, 96)
+    assert fs(n=45000) == -7 and fs(n=1 << 30) == -7
+
+
 def test_weighted_argument_errors(L):
     def hw(x=FAKE, signs=FAKE, codes=FAKE, w=FAKE, n=0, d=768, k=96, tau=8, rounds=3, dt=0):
         return L.lookupffn_hash_weighted(x, signs, codes, w, n, d, k, tau, rounds, dt, None)
