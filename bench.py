@@ -256,7 +256,7 @@ def main():
     path_bytes += (w.k * (n_probe - 1) * w.d_out * tb + 2 * side_floats * 4) * w.n_tokens * w.n_layers
     gather_avg_ms = gather_ms / gather_n
     kernel = B.lookupffn_last_gather_kernel()
-    staged = kernel == "gather_lds_kernel"
+    staged = kernel in ("gather_lds_kernel", "gather_ring_kernel")
     # compulsory HBM traffic of one gather launch: every table byte once (as the kernel reads it: the prepared
     # copy is fp32), codes (+ weights) once, y once
     read_tb = 4 if (staged or not args.no_prepare) else tb

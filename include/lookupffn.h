@@ -123,7 +123,7 @@ int64_t lookupffn_workspace_bytes(int64_t n_tokens, int k);
  * bit-identical y, but the intermediates live in a device array that is part of the library's code object
  * (lookupffn_static_scratch_bytes() = 16 MiB per GPU, held from load until the process ends), so the call
  * allocates nothing and frees nothing.  Batches whose intermediates (lookupffn_workspace_bytes(n_tokens, k))
- * exceed that size return LFFN_E_WORKSPACE (k = 96: batches up to about 41000 tokens fit).  All calls on one GPU
+ * exceed that size return LFFN_E_WORKSPACE (k = 96: batches up to about 39000 tokens fit).  All calls on one GPU
  * share the one array: calls that overlap in time on a GPU (two streams, two threads) race on it; order
  * them on one stream.  Nothing in the array needs clearing between calls (every word a call reads, it
  * wrote first).  The array's address is looked up on the first call on a device, or by lookupffn_init().
@@ -258,12 +258,14 @@ int lookupffn_timing_read_each(int which, double *ms_out, int64_t capacity, int6
  * Launch-shape knobs of the gather kernel, for tuning sweeps (0 = library default):
  *   "lanes_per_token"  1,2,4,...,64   lanes (16 bytes each) that share one token's row slice
  *   "xcd_order"        1 / -1         force the XCD-sliced block order on / off
- *   "gather_path"      1 / 2          1: always the direct kernel; 2: the LDS-staged kernel
- *                                     whenever the shape allows it (tau 7 .. 10, k even)
+ *   "gather_path"      1 / 2 / 4      1: always the direct kernel; 2: the LDS-staged kernel whenever the shape
+ *                                     allows it (tau 7 .. 10, k even), whatever the batch size; 4: the lagged ring
+ *                                     kernel where it exists (prepared tables, tau 7 or 8, plain sum), else as 2
+ *   "ring_threads"     512 / 1024     workgroup size of the ring kernel
  *   "slice_lanes"      4 / 8          staged kernel: 64-byte column slices (4 lanes per token) where
  *                                     they exist (fp32 tables, tau 8 .. 10) / 128-byte ones (tau 7 .. 9);
  *                                     default: 128 bytes up to tau = 8, 64 bytes from tau = 9 on
- *   "token_slots"      4,8,13,16      staged kernel: at most this many tokens per lane group and chunk
+ *   "token_slots"      1 .. 32        staged kernels: at most this many tokens per lane group and chunk
  *   "hash_path"        1              always the generic hash kernel (default: the two-layout
  *                                     kernel when d_pad = 1024 and n_rounds <= 4)
  *   "hash_blocks"      1..65536       grid cap of the d_pad = 1024 hash kernel
@@ -276,7 +278,9 @@ const char *lookupffn_strerror(int status);
 /* Text of the last HIP error seen by this thread's most recent failing call ("" if none). */
 const char *lookupffn_last_hip_error(void);
 /* Which gather kernel the calling thread's most recent gather launch used: "gather_kernel" (direct, rows
- * fetched through L2) or "gather_lds_kernel" (table slices staged in LDS); "" before the first launch. */
+ * fetched through L2), "gather_lds_kernel" (table slices staged in LDS, double-buffered) or
+ * "gather_ring_kernel" (on request: prepared tables of up to 256 rows, plain sum; slices staged in an LDS ring,
+ * token groups lagged so that their reads never meet in a bank); "" before the first launch. */
 const char *lookupffn_last_gather_kernel(void);
 /* major*10000 + minor*100 + patch */
 int lookupffn_version(void);

@@ -12,7 +12,7 @@ SRC = PKG / "csrc" / "lookupffn.hip"
 LIB = PKG / "liblookupffn.so"
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
-N_PARTS = 12         # csrc/lookupffn.hip compiles as parts 0 .. 11 (-DLFFN_PART=i), linked together
+N_PARTS = 13         # csrc/lookupffn.hip compiles as parts 0 .. 12 (-DLFFN_PART=i), linked together
 SLOW_FIRST = [10, 11, 8, 9, 6, 5]   # the wide BH kernels take the longest: start them first
 OBJ_DIR = PKG / "_build"
 
@@ -30,15 +30,23 @@ def _quiet(stderr: str) -> str:
     return "\n".join(l for l in stderr.splitlines() if _NOISE not in l)
 
 
-def build_library(verbose: bool = False, jobs: int | None = None) -> Path:
-    """Compile the parts of csrc/lookupffn.hip side by side and link liblookupffn.so (always recompiles)."""
+def build_library(verbose: bool = False, jobs: int | None = None, only_parts=None) -> Path:
+    """Compile the parts of csrc/lookupffn.hip side by side and link liblookupffn.so (always recompiles).
+
+    `only_parts` (development aid; `python -m paper_2403_07221_amd.build 0 12`): recompile just these parts and
+    link them with the other parts' objects kept from the last such build in _build/ (a part whose object is
+    missing is compiled too).  The objects are then kept; a plain call compiles everything and keeps nothing."""
     jobs = jobs or max(1, min(os.cpu_count() or 1, int(os.environ.get("MAX_JOBS", "16"))))
     OBJ_DIR.mkdir(exist_ok=True)
-    objs = [OBJ_DIR / f"lookupffn_part{i}.{os.getpid()}.o" for i in range(N_PARTS)]
+    keep = only_parts is not None
+    tag = "dev" if keep else str(os.getpid())
+    objs = [OBJ_DIR / f"lookupffn_part{i}.{tag}.o" for i in range(N_PARTS)]
     cmds = [[HIPCC, *FLAGS, f"-DLFFN_PART={i}", "-c", "-o", str(objs[i]), str(SRC)] for i in range(N_PARTS)]
     tmp = LIB.with_suffix(f".so.tmp{os.getpid()}")
     try:
         order = SLOW_FIRST + [i for i in range(N_PARTS) if i not in SLOW_FIRST]
+        if keep:
+            order = [i for i in order if i in set(only_parts) or not objs[i].exists()]
         todo, running, errors = [(i, cmds[i]) for i in order], [], []
         while todo or running:
             while todo and len(running) < jobs:
@@ -62,11 +70,13 @@ def build_library(verbose: bool = False, jobs: int | None = None) -> Path:
             raise RuntimeError(f"link failed:\n{_quiet(r.stderr)}")
         os.replace(tmp, LIB)
     finally:
-        for o in objs:
-            o.unlink(missing_ok=True)
+        if not keep:
+            for o in objs:
+                o.unlink(missing_ok=True)
         tmp.unlink(missing_ok=True)
     return LIB
 
 
 if __name__ == "__main__":
-    print(build_library(verbose=True))
+    parts = [int(a) for a in sys.argv[1:]]
+    print(build_library(verbose=not parts, only_parts=parts or None))

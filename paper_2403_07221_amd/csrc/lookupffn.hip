@@ -16,6 +16,7 @@
 #include "bh_hash_kernel.hpp"
 #include "gather_kernel.hpp"
 #include "gather_lds_kernel.hpp"
+#include "gather_ring_kernel.hpp"
 #include "hash_kernel.hpp"
 
 // Build parts.  This file compiles whole (LFFN_PART undefined) or as parts that are linked together, so
@@ -46,6 +47,8 @@ int gather_direct_load();  // makes the runtime load part 1's code object now (l
 int gather_lds_plain_part(int tok, const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s);
 int gather_lds_weighted_part(int tok, const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s);
 int gather_lds_probes_part(int tok, const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s);
+// part 12: the lagged, bank-interleaved staged gather (prepared tables, tau <= 8)
+int gather_ring_part(int threads, int tok, const GatherRingArgs &a, dim3 grid, hipStream_t s);
 // parts 4 .. 11: the BH hash kernel.  Plain: d_pad = 64 .. 256, 512, 1024; weighted: d_pad = 64 .. 256, then
 // 512 and 1024 each split by the way the rows are read (four coordinates at a time or one by one): the
 // wide weighted kernels are the slowest to compile by far
@@ -231,6 +234,41 @@ int gather_lds_probes_part(int tok, const GatherLdsArgs &a, int fr, int sw, dim3
 }
 #endif
 
+#if LFFN_HAS(12)
+template <int THREADS, int TOK>
+int launch_gather_ring_t(const GatherRingArgs &a, dim3 grid, hipStream_t s)
+{
+    auto kern = gather_ring_kernel<THREADS, TOK>;
+    int rc = allow_lds(reinterpret_cast<const void *>(kern), kRingLdsBytes);
+    if (rc != LFFN_OK || attr_only()) return rc;
+    hipLaunchKernelGGL(kern, grid, dim3(THREADS), kRingLdsBytes, s, a);
+    return LFFN_OK;
+}
+
+int gather_ring_part(int threads, int tok, const GatherRingArgs &a, dim3 grid, hipStream_t s)
+{
+    if (threads == 1024) {
+        switch (tok) {
+            case 4: return launch_gather_ring_t<1024, 4>(a, grid, s);
+            case 8: return launch_gather_ring_t<1024, 8>(a, grid, s);
+            case 12: return launch_gather_ring_t<1024, 12>(a, grid, s);
+            case 13: return launch_gather_ring_t<1024, 13>(a, grid, s);
+            case 14: return launch_gather_ring_t<1024, 14>(a, grid, s);
+        }
+    } else if (threads == 512) {
+        switch (tok) {
+            case 8: return launch_gather_ring_t<512, 8>(a, grid, s);
+            case 16: return launch_gather_ring_t<512, 16>(a, grid, s);
+            case 20: return launch_gather_ring_t<512, 20>(a, grid, s);
+            case 24: return launch_gather_ring_t<512, 24>(a, grid, s);
+            case 28: return launch_gather_ring_t<512, 28>(a, grid, s);
+            case 32: return launch_gather_ring_t<512, 32>(a, grid, s);
+        }
+    }
+    return LFFN_E_UNSUPPORTED;
+}
+#endif
+
 #if LFFN_HAS(4)
 int bh_plain_lo_part(int L, const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s)
 {
@@ -348,11 +386,13 @@ int64_t round256(int64_t b) { return (b + 255) & ~int64_t(255); }
 struct Options {
     int lanes_per_token = 0;  // 0 = default
     int xcd_order = 0;        // 0 = default, 1 = on, -1 = off
-    int gather_path = 0;      // 0 = choose, 1 = direct kernel, 2 = LDS-staged kernel (if the shape allows)
+    int gather_path = 0;      // 0 = choose, 1 = direct kernel, 2 = the staged kernel whenever the shape allows,
+                              // 4 = the ring kernel whenever the shape allows (else as 2)
     int hash_path = 0;        // 0 = choose, 1 = generic kernel only
     int hash_blocks = 0;      // 0 = default grid cap of the d_pad = 1024 hash kernel
     int slice_lanes = 0;      // 0 = choose, 4 = 64-byte column slices in the staged gather where possible
     int token_slots = 0;      // 0 = choose, else the most token slots per lane of the staged gather
+    int ring_threads = 0;     // 0 = choose, 512 / 1024 = workgroup size of the ring gather
 };
 std::mutex g_opt_mu;
 Options g_opt;
@@ -777,7 +817,7 @@ int plan_gather_lds(int64_t n, int k, int tau, int d_out, const TableRef &T, Mod
     const int64_t nchunks = (tpb + (int64_t)groups * tok_max - 1) / ((int64_t)groups * tok_max);
     const int64_t chunk = (tpb + nchunks - 1) / nchunks;
     // Staging pays only when a chunk re-uses each staged row a few times.
-    if (opt.gather_path != 2 && chunk < 2 * (int64_t)rows) return LFFN_OK;
+    if (opt.gather_path < 2 && chunk < 2 * (int64_t)rows) return LFFN_OK;
     p->tok = (int)((chunk + groups - 1) / groups);
     if (mode == kProbes && sw == 8 && p->tok > 8) p->tok = 13;  // multi-probe form: 4, 8 or 13 slots
     if (sw == 4) p->tok = p->tok > 13 ? 16 : p->tok > 8 ? 13 : 8;  // the 64-byte form is built for 8, 13 and 16 token slots
@@ -791,7 +831,8 @@ int plan_gather_lds(int64_t n, int k, int tau, int d_out, const TableRef &T, Mod
     return LFFN_OK;
 }
 
-int64_t packed_bytes(int64_t n, int k) { return round256(((int64_t)(k + 1) / 2) * packed_n_pad(n) * 4); }
+// packed codes of either staged kernel: [k/2][n_pad] words, or the ring kernel's lagged [k/2 + 3][n_pad]
+int64_t packed_bytes(int64_t n, int k) { return round256(ring_code_words(k) * packed_n_pad(n) * 4); }
 int64_t wpk_bytes(int64_t n, int k) { return round256((int64_t)k * packed_n_pad(n) * 4); }
 int64_t spk_bytes(int64_t n, int k, int tau) { return round256((int64_t)k * (tau + 1) * packed_n_pad(n) * 4); }
 int64_t abi_codes_bytes(int64_t n, int k) { return round256(n * (int64_t)k * 2); }
@@ -934,11 +975,113 @@ int launch_repack_weights(const float *weights, float *wpk, int64_t n, int64_t n
     return LFFN_OK;
 }
 
+// Launch shape of the lagged, bank-interleaved staged gather (gather_ring_kernel): prepared tables of up
+// to 256 rows, plain sum.
+struct RingPlan {
+    bool use = false;
+    GatherRingArgs a{};
+    int threads = 0, tok = 0;
+    unsigned grid = 0;
+};
+
+int plan_gather_ring(int64_t n, int k, int tau, int d_out, const TableRef &T, Mode mode, const Options &opt,
+                     RingPlan *p)
+{
+    p->use = false;
+    // On request only (gather_path 4).  Measured on the RoBERTa-base shape it does not beat the double-buffered
+    // staged kernel: its reads are conflict-free, but both kernels are bound by the four vector adds per 16 bytes
+    // read, and this one pays a barrier and an LDS write per table.
+    if (opt.gather_path != 4 || mode != kPlain || !T.prepared || T.pw < 64) return LFFN_OK;
+    if (tau < 7 || tau > 8 || k > 480) return LFFN_OK;   // 256-row slices; the re-pack kernel's 64 x k tile fits LDS
+    if (n >= (int64_t(1) << 31) - 4096) return LFFN_OK;
+    int cus = 0;
+    int rc = device_cus(&cus);
+    if (rc != LFFN_OK) return rc;
+    if (cus < kXcds || cus % kXcds != 0) return LFFN_OK;
+    const int rows = 1 << tau;
+    GatherRingArgs &a = p->a;
+    a = GatherRingArgs{};
+    a.n = n;
+    a.n_pad = packed_n_pad(n);
+    a.k = k;
+    a.tau = tau;
+    a.d_out = d_out;
+    a.nvec = d_out / 4;
+    a.n_slices = (a.nvec + 3) / 4;
+    a.token_splits = kXcds / gcd(a.n_slices, kXcds);
+    a.n_units = a.n_slices * a.token_splits;
+    a.blocks_per_xcd = cus / kXcds;
+    a.row_stride = (uint32_t)T.pw;
+    a.spp = (uint32_t)(T.pw / 64);
+    a.table_stride = (uint32_t)(rows * T.pw);
+    a.slice_stride = (unsigned long long)k * rows * T.pw;
+    // tokens of the fullest workgroup, as the kernel splits them (in units of 16 tokens)
+    const int64_t tpb = 16 * lds_tokens_per_block((n + 15) / 16, a.n_units, a.token_splits, a.blocks_per_xcd);
+    // workgroup shapes that are built: (threads, token slots), a chunk holds threads / 4 * slots tokens
+    static const int shapes[][2] = {{1024, 4}, {1024, 8}, {1024, 12}, {1024, 13}, {1024, 14}, {512, 8}, {512, 16}, {512, 20}, {512, 24}, {512, 28}, {512, 32}};
+    int64_t cap_max = 0;
+    for (auto &sh : shapes) {
+        if (opt.ring_threads && sh[0] != opt.ring_threads) continue;
+        if (opt.token_slots && sh[1] > opt.token_slots) continue;
+        const int64_t cap = (int64_t)sh[0] / 4 * sh[1];
+        if (cap > cap_max) cap_max = cap;
+    }
+    if (cap_max == 0) return LFFN_OK;
+    const int64_t nchunks = (tpb + cap_max - 1) / cap_max;
+    const int64_t chunk = ((tpb / 16 + nchunks - 1) / nchunks) * 16;  // tokens of the longest chunk
+    // the shape with the fewest slots that holds a chunk; 1024 threads first (more waves to hide latency)
+    int best = -1;
+    for (int i = 0; i < (int)(sizeof(shapes) / sizeof(shapes[0])); ++i) {
+        if (opt.ring_threads && shapes[i][0] != opt.ring_threads) continue;
+        if (opt.token_slots && shapes[i][1] > opt.token_slots) continue;
+        const int64_t cap = (int64_t)shapes[i][0] / 4 * shapes[i][1];
+        if (cap < chunk) continue;
+        if (best < 0 || cap < (int64_t)shapes[best][0] / 4 * shapes[best][1]) best = i;
+    }
+    if (best < 0) return LFFN_OK;
+    p->threads = shapes[best][0];
+    p->tok = shapes[best][1];
+    p->grid = (unsigned)cus;
+    p->use = true;
+    return LFFN_OK;
+}
+
+int launch_gather_ring(const RingPlan &p, const uint16_t *codes, uint32_t *packed, const TableRef &T, float *y,
+                       hipStream_t s)
+{
+    GatherRingArgs a = p.a;
+    if (!packed || !T.prepared || a.n_pad < a.n + 16 * 256) return LFFN_E_UNSUPPORTED;
+    // codes in the ABI layout -> lagged packed layout (scaled by the 256-byte LDS row stride)
+    int64_t blocks = (a.n_pad + 63) / 64;
+    if (blocks > 8192) blocks = 8192;
+    const size_t tile = (size_t)64 * (a.k | 1) * sizeof(uint16_t);
+    TimedLaunch tl(1, s);
+    hipLaunchKernelGGL(repack_codes_lag_kernel, dim3((unsigned)blocks), dim3(256), tile, s, codes, packed,
+                       (long long)a.n, (long long)a.n_pad, a.k, a.tau, kRingShift);
+    LFFN_HIP(hipGetLastError());
+    a.packed = packed;
+    a.tables = T.p;
+    a.y = y;
+    int rc = lffn_host::gather_ring_part(p.threads, p.tok, a, dim3(p.grid), s);
+    if (rc != LFFN_OK) return rc;
+    LFFN_HIP(hipGetLastError());
+    tl.done();
+    t_last_gather = "gather_ring_kernel";
+    return LFFN_OK;
+}
+
 // Gather from ABI-layout codes (and weights / shares): the staged kernel through the re-pack kernels when
 // the plan says so and the scratch has room, else the direct kernel.
 int gather_from_abi(Mode mode, const uint16_t *codes, const float *weights, const TableRef &T, float *y, int64_t n,
                     int k, int tau, int d_out, const LdsPlan &plan, Scratch *sc, hipStream_t s, const Options &opt)
 {
+    RingPlan ring;
+    int rrc = plan_gather_ring(n, k, tau, d_out, T, mode, opt, &ring);
+    if (rrc != LFFN_OK) return rrc;
+    if (ring.use) {
+        uint32_t *packed = sc->take<uint32_t>(packed_bytes(n, k));
+        if (packed) return launch_gather_ring(ring, codes, packed, T, y, s);
+    }
     if (plan.use && aligned(codes, 4)) {
         uint32_t *packed = sc->take<uint32_t>(packed_bytes(n, k));
         float *wpk = mode == kWeighted ? sc->take<float>(wpk_bytes(n, k))
@@ -1108,7 +1251,10 @@ int forward_core(const HashSpec &h, Mode mode, const void *x, const void *tables
     };
     // the hash kernels write the staged gather's layout themselves when its codes are scaled for 128-byte
     // row pieces (and the variant is not the multi-probe one, whose shares exist in the ABI layout only)
-    if (plan.use && plan.shift == kPackedShift && mode != kProbes) {
+    RingPlan ring;
+    rc = plan_gather_ring(n, k, tau, d_out, T, mode, opt, &ring);
+    if (rc != LFFN_OK) return rc;
+    if (!ring.use && plan.use && plan.shift == kPackedShift && mode != kProbes) {
         HashOut out;
         const int64_t pb = packed_bytes(n, k), wb = mode == kWeighted ? wpk_bytes(n, k) : 0;
         out.packed = sc.take<uint32_t>(pb);
@@ -1148,8 +1294,11 @@ int gather_core(Mode mode, const uint16_t *codes, const float *weights, const vo
     LdsPlan plan;
     rc = plan_gather_lds(n, k, tau, d_out, T, mode, opt, &plan);
     if (rc != LFFN_OK) return rc;
+    RingPlan ring;
+    rc = plan_gather_ring(n, k, tau, d_out, T, mode, opt, &ring);
+    if (rc != LFFN_OK) return rc;
     Scratch sc;
-    if (plan.use && aligned(codes, 4)) {  // only the staged kernel needs scratch
+    if (ring.use || (plan.use && aligned(codes, 4))) {  // only the staged kernels need scratch
         rc = get_scratch(workspace, workspace_bytes, need, &sc);
         if (rc != LFFN_OK) return rc;
     }
@@ -1244,6 +1393,14 @@ int lookupffn_init(void)
                     if (rc != LFFN_OK && rc != LFFN_E_UNSUPPORTED) return rc;
                 }
             }
+    {
+        GatherRingArgs ra{};
+        for (int threads : {512, 1024})
+            for (int tok = 1; tok <= 32; ++tok) {
+                rc = lffn_host::gather_ring_part(threads, tok, ra, dim3(1), nullptr);
+                if (rc != LFFN_OK && rc != LFFN_E_UNSUPPORTED) return rc;
+            }
+    }
     for (int L = 6; L <= 10; ++L)
         for (int block : {16, 32, 64})
             for (int vec4 = 0; vec4 < 2; ++vec4)
@@ -1589,13 +1746,18 @@ int lookupffn_set_option(const char *key, int value)
         g_opt.slice_lanes = value;
         return LFFN_OK;
     }
+    if (!std::strcmp(key, "ring_threads")) {
+        if (value != 0 && value != 512 && value != 1024) return LFFN_E_SIZE;
+        g_opt.ring_threads = value;
+        return LFFN_OK;
+    }
     if (!std::strcmp(key, "token_slots")) {
-        if (value != 0 && value != 4 && value != 8 && value != 13 && value != 16) return LFFN_E_SIZE;
+        if (value < 0 || value > 32) return LFFN_E_SIZE;
         g_opt.token_slots = value;
         return LFFN_OK;
     }
     if (!std::strcmp(key, "gather_path")) {
-        if (value < 0 || value > 2) return LFFN_E_SIZE;
+        if (value < 0 || value > 4) return LFFN_E_SIZE;
         g_opt.gather_path = value;
         return LFFN_OK;
     }

@@ -420,7 +420,7 @@ def test_gather_prepared_tables_equal_row_major_tables(n, k, tau, d_out, tdt):
     cd = torch.from_numpy(codes.view(np.int16)).cuda()
     ws = torch.empty(max(B.lookupffn_workspace_bytes_gather(n, k), 256), dtype=torch.uint8, device="cuda")
     try:
-        for path in (2, 1):
+        for path in (2, 4, 1):
             B.lookupffn_set_option("gather_path", path)
             for lanes in ((0, 4, 8) if path == 2 else (0,)):
                 B.lookupffn_set_option("slice_lanes", lanes)
@@ -437,6 +437,52 @@ def test_gather_prepared_tables_equal_row_major_tables(n, k, tau, d_out, tdt):
         B.lookupffn_set_option("gather_path", 0)
         B.lookupffn_set_option("slice_lanes", 0)
         B.lookupffn_set_option("lanes_per_token", 0)
+
+
+RING_SHAPES = [
+    # n, k, tau, d_out, table dtype   (prepared tables, plain sum, tau 7 or 8: the lagged, bank-interleaved staged gather)
+    (16384, 96, 8, 768, "f32"),      # the benchmark's shape: 12 token slots, one chunk per workgroup
+    (6144, 96, 8, 768, "bf16"),
+    (1003, 96, 8, 768, "f32"),       # ragged token count, 4 slots
+    (1, 6, 8, 64, "f32"),            # one token
+    (777, 2, 8, 64, "f32"),          # fewer tables than the pipeline is deep
+    (777, 1, 8, 64, "f32"),
+    (777, 3, 8, 64, "bf16"),         # odd k
+    (2000, 5, 8, 72, "f32"),         # odd k, ragged last slice (18 pieces in slices of 4)
+    (3000, 13, 8, 520, "bf16"),
+    (5000, 24, 7, 200, "f32"),       # tau = 7: half-filled ring slices
+    (130, 2, 7, 4, "f32"),           # a single 16-byte piece per row
+    (120000, 4, 8, 128, "f32"),      # several chunks per workgroup
+    (300, 2, 8, 8192, "f32"),        # more slice-units than workgroups
+    (40000, 17, 8, 72, "f32"),       # 16 slots, odd k
+    (32768, 128, 8, 512, "f32"),     # the paper's small-model shape
+    (9000, 200, 8, 64, "f32"),       # many tables
+]
+
+
+@pytest.mark.parametrize("n,k,tau,d_out,tdt", RING_SHAPES)
+def test_gather_ring_kernel(n, k, tau, d_out, tdt):
+    print(f"gather (lagged ring) n={n} k={k} tau={tau} d_out={d_out} {tdt}", flush=True)
+    tables = synth.make_tables(n + 3 * k, k, 1 << tau, d_out, tdt)
+    codes = np.random.default_rng(n + k).integers(0, 1 << tau, size=(n, k)).astype(np.uint16)
+    want = oracle.gather(codes, tables, acc64=False)
+    prep = B.lookupffn_prepare_tables(B.to_device(tables))
+    cd = torch.from_numpy(codes.view(np.int16)).cuda()
+    try:
+        for slots, threads in ((0, 0), (4, 1024), (8, 0), (13, 1024), (14, 1024), (16, 512), (32, 512)):
+            B.lookupffn_set_option("gather_path", 4)
+            B.lookupffn_set_option("token_slots", slots)
+            B.lookupffn_set_option("ring_threads", threads)
+            y = torch.full((n, d_out), float("nan"), dtype=torch.float32, device="cuda")
+            B.lookupffn_gather(cd, prep, y=y)
+            torch.cuda.synchronize()
+            assert B.lookupffn_last_gather_kernel() == "gather_ring_kernel"
+            assert np.array_equal(y.cpu().numpy(), want), f"token_slots {slots}, ring_threads {threads}"
+    finally:
+        B.lookupffn_set_option("gather_path", 0)
+        B.lookupffn_set_option("token_slots", 0)
+        B.lookupffn_set_option("ring_threads", 0)
+    assert rel_err(want, oracle.gather(codes, tables, acc64=True)) <= (TOL_BF16 if tdt == "bf16" else TOL_F32)
 
 
 def test_prepared_tables_in_every_variant():

@@ -104,7 +104,7 @@ def test_forward_static_argument_errors(L):
     assert fs(x=None) == -1 and fs(y=None) == -1 and fs(tau=0) == -3 and fs(tdt=9) == -4 and fs(d=5000) == -6
     assert fs(n=5, x=None) == -1                                       # argument errors need no GPU
     # the static array bounds the batch: refused before any HIP call
-    assert L.lookupffn_workspace_bytes(41000, 96) <= 16 << 20 < L.lookupffn_workspace_bytes(45000, 96)
+    assert L.lookupffn_workspace_bytes(39000, 96) <= 16 << 20 < L.lookupffn_workspace_bytes(45000, 96)
     assert fs(n=45000) == -7 and fs(n=1 << 30) == -7
 
 
@@ -246,12 +246,15 @@ def test_options(L):
     assert L.lookupffn_set_option(b"lanes_per_token", 128) == -2
     assert L.lookupffn_set_option(b"lanes_per_token", 0) == 0
     assert L.lookupffn_set_option(b"xcd_order", 2) == -2 and L.lookupffn_set_option(b"xcd_order", 0) == 0
-    assert L.lookupffn_set_option(b"gather_path", 3) == -2 and L.lookupffn_set_option(b"gather_path", 0) == 0
+    assert L.lookupffn_set_option(b"gather_path", 5) == -2 and L.lookupffn_set_option(b"gather_path", 4) == 0
+    assert L.lookupffn_set_option(b"gather_path", 0) == 0
     assert L.lookupffn_set_option(b"hash_path", 2) == -2 and L.lookupffn_set_option(b"hash_path", 0) == 0
     assert L.lookupffn_set_option(b"hash_blocks", -1) == -2 and L.lookupffn_set_option(b"hash_blocks", 0) == 0
     assert L.lookupffn_set_option(b"slice_lanes", 4) == 0 and L.lookupffn_set_option(b"slice_lanes", 3) == -2
     assert L.lookupffn_set_option(b"slice_lanes", 0) == 0
-    assert L.lookupffn_set_option(b"token_slots", 8) == 0 and L.lookupffn_set_option(b"token_slots", 5) == -2
+    assert L.lookupffn_set_option(b"token_slots", 8) == 0 and L.lookupffn_set_option(b"token_slots", 33) == -2
+    assert L.lookupffn_set_option(b"ring_threads", 512) == 0 and L.lookupffn_set_option(b"ring_threads", 256) == -2
+    assert L.lookupffn_set_option(b"ring_threads", 0) == 0
     assert L.lookupffn_set_option(b"token_slots", 0) == 0
     assert L.lookupffn_set_option(b"no_such_key", 1) == -2
     assert L.lookupffn_set_option(None, 1) == -1
