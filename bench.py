@@ -62,6 +62,8 @@ def parse_args():
                          "never instead of, the hashed codes of the rotated Gaussian input)")
     ap.add_argument("--no-prepare", action="store_true",
                     help="pass the row-major tables / BH factors instead of their one-time prepared copies")
+    ap.add_argument("--layer-loop", action="store_true",
+                    help="config 5: time the loop of per-layer lookupffn_forward calls instead of the single launch")
     ap.add_argument("--parity-tokens", type=int, default=1024,
                     help="tokens of the timed y compared with the oracle after the timed region (0 = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -146,6 +148,72 @@ def parity_check(w, x, signs, tables, y_dev, n_check: int, weighted: bool, bh: b
     return out
 
 
+def launches_per_step_layers(w, args):
+    """Layers one launch of the timed kernel covers."""
+    return w.n_layers if (w.n_layers > 1 and not args.layer_loop) else 1
+
+
+def latency_report(w, args, xd, loop_step, stack_step, y_last):
+    """Latency of the layer chain, microseconds per pass and per layer: the single launch
+    (lookupffn_forward_stack), the loop of per-layer launches, and the loop replayed from a HIP graph; each
+    warm (the same batch again: the rows it touches stay in the caches) and cold (a different batch of a
+    rotation of 16 and a 1 GiB overwrite before every timed pass)."""
+    import torch
+    from paper_2403_07221_amd import synth
+
+    flush = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+    batches = [xd] + [torch.from_numpy(synth.make_x(synth.seed_for(w.index, 0, 5) + i, w.n_tokens, w.d, w.x_dtype)).cuda()
+                      for i in range(1, 16)]
+    x_run = torch.empty_like(xd)     # the launches (and the graph) read this buffer
+
+    def timed(fn, cold, reps):
+        total = []
+        for i in range(reps):
+            x_run.copy_(batches[i % 16] if cold else batches[0])
+            if cold:
+                flush.zero_()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            total.append(e0.elapsed_time(e1) * 1e3)
+        total.sort()
+        return total[len(total) // 2]
+
+    saved = xd.clone()
+    runs = {"single_launch": lambda: stack_step(x_run)}
+
+    def loop_on_x_run():
+        xd.copy_(x_run)          # the per-layer loop reads xd
+        loop_step()
+    runs["layer_loop"] = loop_on_x_run
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    loop_on_x_run()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            loop_on_x_run()
+    runs["layer_loop_graph"] = graph.replay
+    graph1 = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph1, stream=side):
+            stack_step(x_run)
+    runs["single_launch_graph"] = graph1.replay
+    rep = {"layers": w.n_layers, "unit": "us", "cold_means": "another batch of 16 and a 1 GiB overwrite before each timed pass"}
+    for name, fn in runs.items():
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        warm, cold = timed(fn, False, 21), timed(fn, True, 16)
+        rep[name] = {"warm_per_pass": warm, "warm_per_layer": warm / w.n_layers,
+                     "cold_per_pass": cold, "cold_per_layer": cold / w.n_layers}
+    xd.copy_(saved)
+    return rep
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -212,10 +280,20 @@ def main():
         dev = [(B.to_device(s_), prepared(B.to_device(t_))) for _, s_, t_ in layers]
         ys = [torch.empty((w.n_tokens, w.d_out), dtype=torch.float32, device="cuda") for _ in range(2)]
 
-        def step():
+        y_last = torch.empty((w.n_tokens, w.d_out), dtype=torch.float32, device="cuda")
+
+        def loop_step():
             h = xd
             for l in range(w.n_layers):
                 h = forward(h, dev[l][0], dev[l][1], y=ys[l & 1], workspace=ws)
+            return h
+
+        def stack_step(x_in=None):
+            B.lookupffn_forward_stack(xd if x_in is None else x_in, [s_ for s_, _ in dev], [t_ for _, t_ in dev], y=y_last)
+
+        # a step is one pass through all the layers: one launch (lookupffn_forward_stack) unless --layer-loop
+        step = loop_step if args.layer_loop else stack_step
+    launches_per_step = 1 if (w.n_layers > 1 and not args.layer_loop) else w.n_layers
 
     # untimed: the hash kernel's own duration (event pairs around it), outside the timed region so
     # that the timed steps carry only the one event pair the roofline entry needs
@@ -241,7 +319,9 @@ def main():
     gather_each = B.lookupffn_timing_read_each(1)
     B.lookupffn_timing_enable(0)
     B.lookupffn_timing_reset()
-    assert gather_n == args.steps * w.n_layers and hash_n == args.warmup * w.n_layers
+    kernel = B.lookupffn_last_gather_kernel()
+    fused = kernel == "forward_stack_kernel"          # hash and gather in one kernel: no hash launch of its own
+    assert gather_n == args.steps * launches_per_step and hash_n == (0 if fused else args.warmup * launches_per_step)
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tokens_per_s = w.n_tokens / (ms_per_step * 1e-3)
@@ -255,7 +335,6 @@ def main():
     gather_bytes = (w.k * n_probe * w.d_out * tb + w.d_out * 4 + w.k * 2 + side_floats * 4) * w.n_tokens
     path_bytes += (w.k * (n_probe - 1) * w.d_out * tb + 2 * side_floats * 4) * w.n_tokens * w.n_layers
     gather_avg_ms = gather_ms / gather_n
-    kernel = B.lookupffn_last_gather_kernel()
     staged = kernel in ("gather_lds_kernel", "gather_ring_kernel")
     # compulsory HBM traffic of one gather launch: every table byte once (as the kernel reads it: the prepared
     # copy is fp32), codes (+ weights) once, y once
@@ -264,6 +343,9 @@ def main():
     compulsory = table_bytes_read + (w.k * 2 + side_floats * 4 + w.d_out * 4) * w.n_tokens
     if w.n_tokens * w.k < w.k * w.rows:          # fewer lookups than rows: only the rows touched
         compulsory = (w.k * n_probe * w.d_out * read_tb + w.k * 2 + side_floats * 4 + w.d_out * 4) * w.n_tokens
+    if fused:                                    # one launch: x, the sign diagonals and the rows touched, per layer
+        compulsory = ((w.k * w.d_out * read_tb + w.d * xb + w.d_out * 4) * w.n_tokens
+                      + w.n_proj * w.n_rounds * w.d_pad) * launches_per_step_layers(w, args)
     each = sorted(gather_each)
     times = {"avg_kernel_ms": gather_avg_ms, "min_kernel_ms": each[0] if each else None,
              "median_kernel_ms": each[len(each) // 2] if each else None, "launches_timed": len(each)}
@@ -317,7 +399,7 @@ def main():
         # algorithmic bytes (one HBM row read per token and table, as if nothing were re-used) / kernel time /
         # 8 TB/s: a ratio, not a fraction -- above 1 it measures the re-use the kernel extracts on chip
         "hbm_effective_x_peak": gather_bytes / (gather_avg_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "kernels_ms": {"hash": hash_ms / max(hash_n, 1), "gather": gather_avg_ms},
+        "kernels_ms": {"hash": None if fused else hash_ms / max(hash_n, 1), "gather": gather_avg_ms},
         "whole_path": {"algorithmic_bytes_per_step": path_bytes,
                        "effective_GBps": path_bytes / (ms_per_step * 1e-3) / 1e9,
                        "compulsory_hbm_bytes_per_step": (compulsory + w.d * xb * w.n_tokens) * w.n_layers,
@@ -341,40 +423,7 @@ def main():
                                 "peak": 157.3, "unit": "TFLOP/s", "frac": flops / hash_s / 1e12 / 157.3,
                                 "flops_per_launch": flops, "avg_kernel_ms": hash_s * 1e3}
     if w.n_layers > 1:
-        # the same chain with every cache flushed before each pass (1 GiB overwrite, untimed):
-        # the configuration is meant to show latency with the tables cold
-        flush = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
-        cold_ms = 0.0
-        n_cold = 10
-        for _ in range(n_cold):
-            flush.zero_()
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            step()
-            e1.record()
-            torch.cuda.synchronize()
-            cold_ms += e0.elapsed_time(e1)
-        # the same chain captured once in a HIP graph (the entry points only launch kernels when given a
-        # workspace and y) and replayed: one submission per pass instead of 2 x layers launches
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            step()
-        torch.cuda.synchronize()
-        for _ in range(5):
-            graph.replay()
-        torch.cuda.synchronize()
-        n_graph = 200
-        g0 = time.perf_counter()
-        for _ in range(n_graph):
-            graph.replay()
-        torch.cuda.synchronize()
-        graph_us = (time.perf_counter() - g0) / n_graph * 1e6
-        out["latency"] = {"layers": w.n_layers, "warm_us_per_pass": ms_per_step * 1e3,
-                          "graph_us_per_pass": graph_us, "graph_us_per_layer": graph_us / w.n_layers,
-                          "warm_us_per_layer": ms_per_step * 1e3 / w.n_layers,
-                          "cold_us_per_pass": cold_ms / n_cold * 1e3,
-                          "cold_us_per_layer": cold_ms / n_cold * 1e3 / w.n_layers}
+        out["latency"] = latency_report(w, args, xd, loop_step, stack_step, y_last)
     if args.zipf > 0 and w.n_layers == 1:
         def time_gather(codes_np):
             cd = torch.from_numpy(codes_np.view(np.int16)).cuda()
@@ -413,6 +462,18 @@ def main():
             y_check = forward(xd, dev[0][0], dev[0][1], workspace=ws)
             torch.cuda.synchronize()
         pc = parity_check(w, x, signs, tables, y_check, args.parity_tokens, args.weighted, bh, args.probes)
+        if w.n_layers > 1:
+            # the whole chain: the timed step's final y against the oracle's fp32 sequential chain, bit for bit
+            import oracle
+            step()
+            torch.cuda.synchronize()
+            got = (y_last if not args.layer_loop else ys[(w.n_layers - 1) & 1]).cpu().numpy()
+            h = x
+            for _, s_, t_ in layers:
+                h = oracle.forward(h, s_, t_, acc64=False)
+            pc["chain_layers"] = w.n_layers
+            pc["chain_bits_equal"] = bool(np.array_equal(got, h))
+            pc["ok"] = bool(pc["ok"] and pc["chain_bits_equal"])
         out["parity_checked"] = pc["tokens"]
         out["parity"] = pc
         if not pc["ok"]:

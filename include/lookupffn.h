@@ -110,12 +110,33 @@ int64_t lookupffn_workspace_bytes_gather(int64_t n_tokens, int k);
 /*
  * Whole forward pass: Hash then Gather on the same stream (Sec. 3.1, eq. "lookup").
  * Scratch: lookupffn_workspace_bytes(n_tokens, k) bytes (0 if n_tokens == 0).
+ * Batches of up to 64 tokens ("small_tokens" below) whose shape lookupffn_forward_stack takes run as that
+ * call's single launch with n_layers = 1 (no scratch touched); y has the same bits either way.
  */
 int lookupffn_forward(const void *x, const int8_t *signs, const void *tables, float *y,
                       int64_t n_tokens, int d, int k, int tau, int d_out,
                       int n_rounds, int x_dtype, int table_dtype,
                       void *workspace, int64_t workspace_bytes, void *hip_stream);
 int64_t lookupffn_workspace_bytes(int64_t n_tokens, int k);
+
+/*
+ * Several chained layers of the forward pass in ONE kernel launch, for batches of a few tokens where the
+ * launches and the empty chip, not the arithmetic, set the time (Sec. 3.1; each layer is eq. "hadamard",
+ * the sign codes, eq. "lookup"): layer 0 reads x, layer l + 1 reads layer l's output as its input (so
+ * d_out == d when n_layers > 1; no residual and no normalisation in between), y receives the last layer's
+ * output.  `signs` and `tables` are HOST arrays of n_layers DEVICE pointers (read during the call, not kept):
+ * signs[l] as in lookupffn_hash, tables[l] as in lookupffn_gather, all layers with the same k, tau, dtypes
+ * and layout (LFFN_PREPARED in table_dtype: every tables[l] is a prepared copy).  One workgroup per token;
+ * the per-element sums are the same sequential fp32 sums as lookupffn_forward makes, so the result equals
+ * a loop of n_layers lookupffn_forward calls bit for bit.  No scratch memory, no allocation, no
+ * synchronisation: the call can be captured in a HIP graph.
+ * Shapes: 512 < d <= 1024, n_rounds <= 4, n_layers <= 32, one layer's tables below 2 GiB, signs 16-byte
+ * aligned, x rows 16-byte aligned when d % 4 == 0; anything else returns LFFN_E_UNSUPPORTED and the caller
+ * loops over lookupffn_forward instead.  n_layers > 1 with d_out != d returns LFFN_E_SIZE.
+ */
+int lookupffn_forward_stack(const void *x, const int8_t *const *signs, const void *const *tables, float *y,
+                            int64_t n_tokens, int d, int k, int tau, int d_out,
+                            int n_rounds, int n_layers, int x_dtype, int table_dtype, void *hip_stream);
 
 /*
  * lookupffn_forward for callers that cannot allocate device memory or pass a workspace: code under HIP
@@ -265,6 +286,9 @@ int lookupffn_timing_read_each(int which, double *ms_out, int64_t capacity, int6
  *   "slice_lanes"      4 / 8          staged kernel: 64-byte column slices (4 lanes per token) where
  *                                     they exist (fp32 tables, tau 8 .. 10) / 128-byte ones (tau 7 .. 9);
  *                                     default: 128 bytes up to tau = 8, 64 bytes from tau = 9 on
+ *   "small_tokens"     -1 / 1..2^20   lookupffn_forward: batches up to this many tokens take the single-launch
+ *                                     kernel of lookupffn_forward_stack when the shape is that kernel's and no
+ *                                     hash or gather path is forced (default 64; -1: never)
  *   "token_slots"      1 .. 32        staged kernels: at most this many tokens per lane group and chunk
  *   "hash_path"        1              always the generic hash kernel (default: the two-layout
  *                                     kernel when d_pad = 1024 and n_rounds <= 4)
@@ -279,7 +303,7 @@ const char *lookupffn_strerror(int status);
 const char *lookupffn_last_hip_error(void);
 /* Which gather kernel the calling thread's most recent gather launch used: "gather_kernel" (direct, rows
  * fetched through L2), "gather_lds_kernel" (table slices staged in LDS, double-buffered) or
- * "gather_ring_kernel" (on request: prepared tables of up to 256 rows, plain sum; slices staged in an LDS ring,
+ * "forward_stack_kernel" (hash and gather of a few tokens in one launch), "gather_ring_kernel" (on request: prepared tables of up to 256 rows, plain sum; slices staged in an LDS ring,
  * token groups lagged so that their reads never meet in a bank); "" before the first launch. */
 const char *lookupffn_last_gather_kernel(void);
 /* major*10000 + minor*100 + patch */

@@ -20,7 +20,7 @@ PREPARED = 0x100   # OR-ed into table_dtype / block: the buffer is a prepared co
 EXPORTS = (
     "lookupffn_init",
     "lookupffn_hash", "lookupffn_gather", "lookupffn_forward", "lookupffn_workspace_bytes",
-    "lookupffn_forward_static", "lookupffn_static_scratch_bytes",
+    "lookupffn_forward_static", "lookupffn_static_scratch_bytes", "lookupffn_forward_stack",
     "lookupffn_workspace_bytes_gather", "lookupffn_prepared_tables_bytes", "lookupffn_prepare_tables",
     "lookupffn_release_workspace", "lookupffn_timing_enable", "lookupffn_timing_reset",
     "lookupffn_timing_read", "lookupffn_timing_read_each", "lookupffn_set_option", "lookupffn_strerror",
@@ -56,6 +56,8 @@ def lib() -> ctypes.CDLL:
         L.lookupffn_forward.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, ci, ci, vp, i64, vp]
         L.lookupffn_forward_static.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, ci, ci, vp]
         L.lookupffn_static_scratch_bytes.restype = i64
+        L.lookupffn_forward_stack.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, i64,
+                                              ci, ci, ci, ci, ci, ci, ci, ci, vp]
         L.lookupffn_hash_weighted.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, ci, vp]
         L.lookupffn_gather_weighted.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, ci, vp, i64, vp]
         L.lookupffn_forward_weighted.argtypes = L.lookupffn_forward.argtypes
@@ -333,6 +335,33 @@ def lookupffn_forward(x: torch.Tensor, signs: torch.Tensor, tables,
         _check(getattr(lib(), _entry)(_dev(x, "x"), _dev(signs, "signs"), tptr, _dev(y, "y"),
                                       n, d, k, tau, d_out, signs.shape[1], _dtype_code(x), tcode,
                                       ws_ptr, ws_bytes, _stream(x)))
+    return y
+
+
+def lookupffn_forward_stack(x: torch.Tensor, signs, tables, y: torch.Tensor | None = None) -> torch.Tensor:
+    """Chained layers in one launch: `signs` and `tables` are sequences with one entry per layer (tables all
+    tensors or all PreparedTables, same shape and dtype); returns the last layer's y[n, d_out]."""
+    n, d = x.shape
+    n_layers = len(signs)
+    if n_layers != len(tables) or n_layers < 1:
+        raise ValueError("signs and tables need one entry per layer")
+    refs = [_tables(t) for t in tables]
+    tptr0, k, tau, d_out, tcode, _ = refs[0]
+    for (_, k_, tau_, d_out_, tcode_, _), sg in zip(refs, signs):
+        if (k_, tau_, d_out_, tcode_) != (k, tau, d_out, tcode) or tuple(sg.shape) != tuple(signs[0].shape):
+            raise ValueError("all layers must share one shape, dtype and layout")
+        _check_signs(sg, d, k, tau)
+    if y is None:
+        y = torch.empty((n, d_out), dtype=torch.float32, device=x.device)
+    assert y.dtype == torch.float32 and tuple(y.shape) == (n, d_out)
+    if n == 0:
+        return y
+    vp = ctypes.c_void_p
+    sp = (vp * n_layers)(*[_dev(sg, "signs") for sg in signs])
+    tp = (vp * n_layers)(*[r[0] for r in refs])
+    with torch.cuda.device(x.device):
+        _check(lib().lookupffn_forward_stack(_dev(x, "x"), sp, tp, _dev(y, "y"), n, d, k, tau, d_out,
+                                             signs[0].shape[1], n_layers, _dtype_code(x), tcode, _stream(x)))
     return y
 
 

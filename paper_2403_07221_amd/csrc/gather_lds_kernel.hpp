@@ -530,13 +530,20 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
                 }
             }
 
-            if (vec_ok) {
+            {
+                // The output addresses are formed here, from a lane index the compiler cannot see through: left
+                // alone it computes all TOK of them before the stage loop and keeps them in registers across it
+                // (the 12-, 13- and 16-slot forms then spill in their hot loop).
+                uint32_t lt = tid;
+                asm volatile("" : "+v"(lt));
+                const uint32_t sg = lt / SW, svec = slice * (uint32_t)SW + lt % SW;
                 typedef float f4 __attribute__((ext_vector_type(4)));
 #pragma unroll
                 for (int i = 0; i < TOK; ++i) {
-                    const uint32_t t = slot_token(i);
-                    if (t >= c1) continue;
-                    float *yp = a.y + (size_t)t * a.d_out + (size_t)vec * 4u;
+                    const uint32_t t = i < 4 * FQ ? c0 + (4u * G) * (uint32_t)(i >> 2) + 4u * sg + (uint32_t)(i & 3)
+                                                  : c0 + (uint32_t)G * (uint32_t)i + sg;
+                    if (t >= c1 || svec >= (uint32_t)a.nvec) continue;
+                    float *yp = a.y + (size_t)t * a.d_out + (size_t)svec * 4u;
                     f4 o0 = {acc[i].f[0], acc[i].f[1], acc[i].f[2], acc[i].f[3]};
                     __builtin_nontemporal_store(o0, reinterpret_cast<f4 *>(yp));
                 }

@@ -414,6 +414,139 @@ typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) u32x4_t lds_u32x4;
 typedef __attribute__((address_space(3))) uint16_t lds_u16;
 
+// ---- pieces of the d_pad = 1024 transform, shared by hash1024_kernel and the small-batch forward kernel ----
+
+// LDS byte addresses of a lane's pieces of the per-wave transpose area (at LDS byte address tp0) in both layouts
+struct H1024Lane {
+    uint32_t adrA[4];   // quarter m of the lane's 16 consecutive coordinates (16 bytes)
+    uint32_t adrB[16];  // register r of layout B
+};
+
+__device__ __forceinline__ void h1024_lane_setup(uint32_t tp0, unsigned lane, H1024Lane &L)
+{
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+        L.adrA[m] = tp0 + 4u * ((((lane & 0x3Cu) | ((lane ^ (lane >> 4)) & 3u)) << 4) | ((m ^ ((lane >> 2) & 3u)) << 2));
+    const uint32_t c = lane >> 4, l = lane & 15u;
+    const uint32_t base = (c << 8) | (c << 4) | l;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const uint32_t K = ((uint32_t)(r >> 2) << 6) | ((uint32_t)(r & 3) << 4) | ((uint32_t)(r >> 2) << 2);
+        L.adrB[r] = tp0 + 4u * (base ^ K);
+    }
+}
+
+// a1: coordinates lane*16 .. lane*16+15 of the row at `row` (d elements, fp32 or bf16), widened, zero-padded.
+// vec_ok: d % 4 == 0 and the row starts 16-byte (fp32) / 8-byte (bf16) aligned.
+__device__ __forceinline__ void h1024_load_row(const void *x, long long t, int d, bool x_bf16, bool vec_ok, unsigned lane,
+                                               float (&xv)[16])
+{
+    const int i0 = (int)lane * 16;
+    if (vec_ok) {
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (i0 + 4 * m < d) {
+                if (x_bf16) {
+                    const uint2 w = *reinterpret_cast<const uint2 *>((const uint16_t *)x + t * d + i0 + 4 * m);
+                    f = make_float4(__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xFFFF0000u),
+                                    __uint_as_float(w.y << 16), __uint_as_float(w.y & 0xFFFF0000u));
+                } else {
+                    f = *reinterpret_cast<const float4 *>((const float *)x + t * d + i0 + 4 * m);
+                }
+            }
+            xv[4 * m] = f.x;
+            xv[4 * m + 1] = f.y;
+            xv[4 * m + 2] = f.z;
+            xv[4 * m + 3] = f.w;
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            float f = 0.0f;
+            if (i0 + e < d) {
+                if (x_bf16)
+                    f = __uint_as_float((uint32_t)((const uint16_t *)x)[t * d + i0 + e] << 16);
+                else
+                    f = ((const float *)x)[t * d + i0 + e];
+            }
+            xv[e] = f;
+        }
+    }
+}
+
+// One round on v in layout A (lane = i[9:4], register = i[3:0]): sign diagonal (sw: the lane's 16 int8 as four
+// words), strides 1 .. 8, A -> B through LDS, strides 16 .. 128 in registers, 256 / 512 across lanes, scale;
+// unless LAST, back to layout A for the next round.  After a LAST round v is in layout B.
+template <bool LAST>
+__device__ __forceinline__ void h1024_round(float (&v)[16], const uint32_t (&sw)[4], const H1024Lane &L, unsigned lane,
+                                            float scale)
+{
+    constexpr int NREG = 16;
+#pragma unroll
+    for (int e = 0; e < NREG; ++e) v[e] = fxor(v[e], (sw[e >> 2] << (24 - 8 * (e & 3))) & 0x80000000u);
+    reg_stage<1, NREG>(v);
+    reg_stage<2, NREG>(v);
+    reg_stage<4, NREG>(v);
+    reg_stage<8, NREG>(v);
+    wave_lds_fence();
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        u32x4_t q = {__float_as_uint(v[4 * m]), __float_as_uint(v[4 * m + 1]), __float_as_uint(v[4 * m + 2]),
+                     __float_as_uint(v[4 * m + 3])};
+        *reinterpret_cast<lds_u32x4 *>((uintptr_t)L.adrA[m]) = q;
+    }
+    wave_lds_fence();
+#pragma unroll
+    for (int r = 0; r < NREG; ++r) v[r] = __uint_as_float(*reinterpret_cast<lds_u32 *>((uintptr_t)L.adrB[r]));
+    reg_stage<1, NREG>(v);
+    reg_stage<2, NREG>(v);
+    reg_stage<4, NREG>(v);
+    reg_stage<8, NREG>(v);
+    lane_stage<16, NREG>(v, lane);
+    lane_stage<32, NREG>(v, lane);
+#pragma unroll
+    for (int r = 0; r < NREG; ++r) v[r] = v[r] * scale;
+    if constexpr (!LAST) {
+        wave_lds_fence();
+#pragma unroll
+        for (int r = 0; r < NREG; ++r) *reinterpret_cast<lds_u32 *>((uintptr_t)L.adrB[r]) = __float_as_uint(v[r]);
+        wave_lds_fence();
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const u32x4_t q = *reinterpret_cast<lds_u32x4 *>((uintptr_t)L.adrA[m]);
+            v[4 * m] = __uint_as_float(q.x);
+            v[4 * m + 1] = __uint_as_float(q.y);
+            v[4 * m + 2] = __uint_as_float(q.z);
+            v[4 * m + 3] = __uint_as_float(q.w);
+        }
+    }
+}
+
+// a4: sign bits of projection p (v in layout B) into the wave's bit string.  Bit l of register r's lane mask is
+// coordinate i = (l[5:4] << 8) | (r << 4) | l[3:0]: each 16-bit quarter c of the mask is the run of bits
+// [c*256 + r*16, +16) of this projection; lane c stores quarter c of every register.
+__device__ __forceinline__ void h1024_sign_bits(const float (&v)[16], unsigned lane, uint32_t *bitw, int p)
+{
+    unsigned long long msk[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) msk[r] = __builtin_amdgcn_ballot_w64(v[r] >= 0.0f);
+    if (lane < 4) {
+        lds_u16 *dst = reinterpret_cast<lds_u16 *>((uintptr_t)((uint32_t)(uintptr_t)bitw + 2u * (p * 64 + lane * 16)));
+#pragma unroll
+        for (int r = 0; r < 16; ++r) dst[r] = (uint16_t)(msk[r] >> (16 * lane));
+    }
+}
+
+// code j = bits [j*tau, (j+1)*tau) of the bit string, little-endian
+__device__ __forceinline__ uint32_t hash_code_at(const uint32_t *bitw, unsigned j, int tau)
+{
+    const unsigned bit = j * (unsigned)tau;
+    const unsigned wi = bit >> 5, sh = bit & 31u;
+    const unsigned long long both = ((unsigned long long)bitw[wi + 1] << 32) | bitw[wi];
+    return (uint32_t)(both >> sh) & ((1u << tau) - 1u);
+}
+
 template <int R, int WMODE>
 __global__ __launch_bounds__(kHashThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void hash1024_kernel(HashArgs a)
 {
@@ -429,63 +562,14 @@ __global__ __launch_bounds__(kHashThreads) __attribute__((amdgpu_waves_per_eu(4,
     float *ztail = reinterpret_cast<float *>(bitw + n_bitw);
     for (int i = (int)lane; i < n_bitw; i += 64) bitw[i] = 0;
 
-    // LDS byte addresses (32-bit LDS pointers) of this lane's pieces in both layouts
-    const uint32_t tp0 = (uint32_t)(uintptr_t)tp;
-    uint32_t adrA[4];  // quarter m of the lane's 16 consecutive coordinates (16 bytes)
-#pragma unroll
-    for (int m = 0; m < 4; ++m)
-        adrA[m] = tp0 + 4u * ((((lane & 0x3Cu) | ((lane ^ (lane >> 4)) & 3u)) << 4) | ((m ^ ((lane >> 2) & 3u)) << 2));
-    uint32_t adrB[NREG];  // register r of layout B
-    {
-        const uint32_t c = lane >> 4, l = lane & 15u;
-        const uint32_t base = (c << 8) | (c << 4) | l;
-#pragma unroll
-        for (int r = 0; r < NREG; ++r) {
-            const uint32_t K = ((uint32_t)(r >> 2) << 6) | ((uint32_t)(r & 3) << 4) | ((uint32_t)(r >> 2) << 2);
-            adrB[r] = tp0 + 4u * (base ^ K);
-        }
-    }
+    H1024Lane L;
+    h1024_lane_setup((uint32_t)(uintptr_t)tp, lane, L);
 
     const long long gw = (long long)blockIdx.x * kHashWaves + wave;
     const long long n_waves = (long long)gridDim.x * kHashWaves;
     const float scale = a.scale;
     const bool vec_ok = (a.d % 4) == 0;  // rows start 16-byte (fp32) / 8-byte (bf16) aligned: checked by the host
 
-    // a1: coordinates lane*16 .. lane*16+15 of token t, widened, zero-padded
-    auto load_x = [&](long long t, float(&xv)[NREG]) {
-        const int i0 = (int)lane * 16;
-        if (vec_ok) {
-#pragma unroll
-            for (int m = 0; m < 4; ++m) {
-                float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (i0 + 4 * m < a.d) {
-                    if (a.x_bf16) {
-                        const uint2 w = *reinterpret_cast<const uint2 *>((const uint16_t *)a.x + t * a.d + i0 + 4 * m);
-                        f = make_float4(__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xFFFF0000u),
-                                        __uint_as_float(w.y << 16), __uint_as_float(w.y & 0xFFFF0000u));
-                    } else {
-                        f = *reinterpret_cast<const float4 *>((const float *)a.x + t * a.d + i0 + 4 * m);
-                    }
-                }
-                xv[4 * m] = f.x;
-                xv[4 * m + 1] = f.y;
-                xv[4 * m + 2] = f.z;
-                xv[4 * m + 3] = f.w;
-            }
-        } else {
-#pragma unroll
-            for (int e = 0; e < NREG; ++e) {
-                float f = 0.0f;
-                if (i0 + e < a.d) {
-                    if (a.x_bf16)
-                        f = __uint_as_float((uint32_t)((const uint16_t *)a.x)[t * a.d + i0 + e] << 16);
-                    else
-                        f = ((const float *)a.x)[t * a.d + i0 + e];
-                }
-                xv[e] = f;
-            }
-        }
-    };
     // a2: projection p's diagonals in layout A: 16 consecutive int8 per lane and round, kept as
     // four words; the XOR mask of coordinate e is the sign bit of byte e moved to bit 31
     // (signs are 16-byte aligned: host-checked)
@@ -503,12 +587,12 @@ __global__ __launch_bounds__(kHashThreads) __attribute__((amdgpu_waves_per_eu(4,
     if (P == 1 && gw < a.n) load_masks(0);
 
     float xn[NREG];
-    if (gw < a.n) load_x(gw, xn);
+    if (gw < a.n) h1024_load_row(a.x, gw, a.d, a.x_bf16, vec_ok, lane, xn);
     for (long long t = gw; t < a.n; t += n_waves) {
         float xv[NREG];
 #pragma unroll
         for (int e = 0; e < NREG; ++e) xv[e] = xn[e];
-        if (t + n_waves < a.n) load_x(t + n_waves, xn);
+        if (t + n_waves < a.n) h1024_load_row(a.x, t + n_waves, a.d, a.x_bf16, vec_ok, lane, xn);
 
         for (int p = 0; p < P; ++p) {
             if (P > 1) load_masks(p);
@@ -517,68 +601,19 @@ __global__ __launch_bounds__(kHashThreads) __attribute__((amdgpu_waves_per_eu(4,
             for (int e = 0; e < NREG; ++e) v[e] = xv[e];
 #pragma unroll
             for (int rd = 0; rd < R; ++rd) {
-                // ---- layout A: sign diagonal, strides 1, 2, 4, 8 ------------------------------
-#pragma unroll
-                for (int e = 0; e < NREG; ++e)
-                    v[e] = fxor(v[e], (sw[rd][e >> 2] << (24 - 8 * (e & 3))) & 0x80000000u);
-                reg_stage<1, NREG>(v);
-                reg_stage<2, NREG>(v);
-                reg_stage<4, NREG>(v);
-                reg_stage<8, NREG>(v);
-                // ---- A -> B through LDS ---------------------------------------------------------
-                wave_lds_fence();
-#pragma unroll
-                for (int m = 0; m < 4; ++m) {
-                    u32x4_t q = {__float_as_uint(v[4 * m]), __float_as_uint(v[4 * m + 1]),
-                                 __float_as_uint(v[4 * m + 2]), __float_as_uint(v[4 * m + 3])};
-                    *reinterpret_cast<lds_u32x4 *>((uintptr_t)adrA[m]) = q;
-                }
-                wave_lds_fence();
-#pragma unroll
-                for (int r = 0; r < NREG; ++r) v[r] = __uint_as_float(*reinterpret_cast<lds_u32 *>((uintptr_t)adrB[r]));
-                // ---- layout B: strides 16 .. 128 in registers, 256 / 512 across lanes, scale ----
-                reg_stage<1, NREG>(v);
-                reg_stage<2, NREG>(v);
-                reg_stage<4, NREG>(v);
-                reg_stage<8, NREG>(v);
-                lane_stage<16, NREG>(v, lane);
-                lane_stage<32, NREG>(v, lane);
-#pragma unroll
-                for (int r = 0; r < NREG; ++r) v[r] = v[r] * scale;
-                if (rd + 1 < R) {
-                    // ---- B -> A for the next round ------------------------------------------------
-                    wave_lds_fence();
-#pragma unroll
-                    for (int r = 0; r < NREG; ++r) *reinterpret_cast<lds_u32 *>((uintptr_t)adrB[r]) = __float_as_uint(v[r]);
-                    wave_lds_fence();
-#pragma unroll
-                    for (int m = 0; m < 4; ++m) {
-                        const u32x4_t q = *reinterpret_cast<lds_u32x4 *>((uintptr_t)adrA[m]);
-                        v[4 * m] = __uint_as_float(q.x);
-                        v[4 * m + 1] = __uint_as_float(q.y);
-                        v[4 * m + 2] = __uint_as_float(q.z);
-                        v[4 * m + 3] = __uint_as_float(q.w);
-                    }
-                }
+                if (rd + 1 < R)
+                    h1024_round<false>(v, sw[rd], L, lane, scale);
+                else
+                    h1024_round<true>(v, sw[rd], L, lane, scale);
             }
-            // ---- a4: sign bits.  In layout B, bit l of register r's lane mask is coordinate
-            // i = (l[5:4] << 8) | (r << 4) | l[3:0]: each 16-bit quarter c of the mask is the run of
-            // bits [c*256 + r*16, +16) of this projection; lane c stores quarter c of every register.
-            unsigned long long msk[NREG];
-#pragma unroll
-            for (int r = 0; r < NREG; ++r) msk[r] = __builtin_amdgcn_ballot_w64(v[r] >= 0.0f);
-            if (lane < 4) {
-                lds_u16 *dst = reinterpret_cast<lds_u16 *>((uintptr_t)((uint32_t)(uintptr_t)bitw + 2u * (p * 64 + lane * 16)));
-#pragma unroll
-                for (int r = 0; r < NREG; ++r) dst[r] = (uint16_t)(msk[r] >> (16 * lane));
-            }
+            h1024_sign_bits(v, lane, bitw, p);
 
             // ---- weighted variant: z of this projection into the transpose area (coordinate i at
             // word sigma(i)), then the weights of the tables that end in this projection.
             if constexpr (WEIGHTED) {
                 wave_lds_fence();
 #pragma unroll
-                for (int r = 0; r < NREG; ++r) *reinterpret_cast<lds_u32 *>((uintptr_t)adrB[r]) = __float_as_uint(v[r]);
+                for (int r = 0; r < NREG; ++r) *reinterpret_cast<lds_u32 *>((uintptr_t)L.adrB[r]) = __float_as_uint(v[r]);
                 wave_lds_fence();
                 auto z_at = [&](int c) -> float {
                     if (c < 0) return ztail[kZTail + c];
@@ -598,19 +633,12 @@ __global__ __launch_bounds__(kHashThreads) __attribute__((amdgpu_waves_per_eu(4,
         wave_lds_fence();
 
         // ---- a4: code j = bits [j*tau, (j+1)*tau), little-endian ---------------------------
-        const uint32_t cmask = (1u << a.tau) - 1u;
-        auto code_at = [&](unsigned j) -> uint32_t {
-            const unsigned bit = j * (unsigned)a.tau;
-            const unsigned wi = bit >> 5, sh = bit & 31u;
-            const unsigned long long both = ((unsigned long long)bitw[wi + 1] << 32) | bitw[wi];
-            return (uint32_t)(both >> sh) & cmask;
-        };
         if (a.packed) {
             for (int s = (int)lane; s < a.k / 2; s += 64)
-                a.packed[(long long)s * a.n_pad + t] =
-                    (code_at(2u * s) << kPackedShift) | (code_at(2u * s + 1u) << (16 + kPackedShift));
+                a.packed[(long long)s * a.n_pad + t] = (hash_code_at(bitw, 2u * s, a.tau) << kPackedShift) |
+                                                       (hash_code_at(bitw, 2u * s + 1u, a.tau) << (16 + kPackedShift));
         } else {
-            for (int j = (int)lane; j < a.k; j += 64) a.codes[t * a.k + j] = (uint16_t)code_at((unsigned)j);
+            for (int j = (int)lane; j < a.k; j += 64) a.codes[t * a.k + j] = (uint16_t)hash_code_at(bitw, (unsigned)j, a.tau);
         }
         wave_lds_fence();
     }

@@ -14,6 +14,7 @@
 #include <vector>
 
 #include "bh_hash_kernel.hpp"
+#include "forward_stack_kernel.hpp"
 #include "gather_kernel.hpp"
 #include "gather_lds_kernel.hpp"
 #include "gather_ring_kernel.hpp"
@@ -49,6 +50,9 @@ int gather_lds_weighted_part(int tok, const GatherLdsArgs &a, int fr, int sw, di
 int gather_lds_probes_part(int tok, const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s);
 // part 12: the lagged, bank-interleaved staged gather (prepared tables, tau <= 8)
 int gather_ring_part(int threads, int tok, const GatherRingArgs &a, dim3 grid, hipStream_t s);
+// part 13: hash and gather of a few tokens, one or several chained layers, in one launch
+int forward_stack_part(int n_rounds, bool bf16, const StackArgs &a, dim3 grid, int threads, size_t lds, hipStream_t s);
+int forward_stack_load();
 // parts 4 .. 11: the BH hash kernel.  Plain: d_pad = 64 .. 256, 512, 1024; weighted: d_pad = 64 .. 256, then
 // 512 and 1024 each split by the way the rows are read (four coordinates at a time or one by one): the
 // wide weighted kernels are the slowest to compile by far
@@ -269,6 +273,37 @@ int gather_ring_part(int threads, int tok, const GatherRingArgs &a, dim3 grid, h
 }
 #endif
 
+#if LFFN_HAS(13)
+template <int R>
+int launch_forward_stack_r(bool bf16, const StackArgs &a, dim3 grid, int threads, size_t lds, hipStream_t s)
+{
+    if (bf16)
+        hipLaunchKernelGGL((forward_stack_kernel<R, true>), grid, dim3(threads), lds, s, a);
+    else
+        hipLaunchKernelGGL((forward_stack_kernel<R, false>), grid, dim3(threads), lds, s, a);
+    return LFFN_OK;
+}
+
+int forward_stack_part(int n_rounds, bool bf16, const StackArgs &a, dim3 grid, int threads, size_t lds, hipStream_t s)
+{
+    if (threads < 64 || threads > 1024 || threads % 64) return LFFN_E_UNSUPPORTED;
+    switch (n_rounds) {
+        case 1: return launch_forward_stack_r<1>(bf16, a, grid, threads, lds, s);
+        case 2: return launch_forward_stack_r<2>(bf16, a, grid, threads, lds, s);
+        case 3: return launch_forward_stack_r<3>(bf16, a, grid, threads, lds, s);
+        case 4: return launch_forward_stack_r<4>(bf16, a, grid, threads, lds, s);
+    }
+    return LFFN_E_UNSUPPORTED;
+}
+
+int forward_stack_load()
+{
+    hipFuncAttributes attr;
+    hipError_t e = hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(forward_stack_kernel<3, false>));
+    return e == hipSuccess ? LFFN_OK : hip_fail(e, "hipFuncGetAttributes(forward_stack_kernel)");
+}
+#endif
+
 #if LFFN_HAS(4)
 int bh_plain_lo_part(int L, const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s)
 {
@@ -393,7 +428,10 @@ struct Options {
     int slice_lanes = 0;      // 0 = choose, 4 = 64-byte column slices in the staged gather where possible
     int token_slots = 0;      // 0 = choose, else the most token slots per lane of the staged gather
     int ring_threads = 0;     // 0 = choose, 512 / 1024 = workgroup size of the ring gather
+    int small_tokens = 0;     // 0 = default, -1 = never: up to this many tokens lookupffn_forward runs as one
+                              // hash-and-gather launch (when the shape is that kernel's)
 };
+constexpr int kSmallTokensDefault = 64;
 std::mutex g_opt_mu;
 Options g_opt;
 Options options_snapshot()
@@ -1198,6 +1236,75 @@ int launch_hash_bh(const void *x, const float *pack_from, const float *apack_in,
 }
 
 // ---------------------------------------------------------------- the forward pass, all variants
+// ---------------------------------------------------------------- the one-launch path for a few tokens
+// Whether forward_stack_kernel takes this shape (checked without a HIP call).
+bool stack_shape_ok(const void *x, const int8_t *const *signs, const void *const *tables, int n_layers, int64_t n,
+                    int d, int k, int tau, int d_out, int n_rounds, int x_dtype, int table_dtype)
+{
+    if (log2_pad(d) != 10 || n_rounds > 4 || n_layers < 1 || n_layers > kStackMaxLayers) return false;
+    if (n_layers > 1 && d_out != d) return false;
+    if (n > 0x7FFFFFFF) return false;
+    const bool xb = x_dtype == LFFN_BF16;
+    const size_t xrow = (size_t)d * (xb ? 2 : 4);
+    if (d % 4 == 0 && !(aligned(x, 16) && xrow % (xb ? 8 : 16) == 0)) return false;
+    for (int l = 0; l < n_layers; ++l)
+        if (!aligned(signs[l], 16)) return false;
+    const int P = (int)(((int64_t)k * tau + 1023) / 1024);
+    if (stack_lds_bytes(P, k) > 64 * 1024) return false;
+    const TableRef T = table_ref(tables[0], table_dtype, tau);
+    const int64_t bytes = T.prepared ? prepared_tables_bytes(k, tau, d_out)
+                                     : ((int64_t)k << tau) * d_out * (T.bf16 ? 2 : 4);
+    return bytes < (int64_t(1) << 31);
+}
+
+// Call only with stack_shape_ok(...) true and every argument validated.
+int launch_forward_stack(const void *x, const int8_t *const *signs, const void *const *tables, float *y, int64_t n,
+                         int d, int k, int tau, int d_out, int n_rounds, int n_layers, int x_dtype, int table_dtype,
+                         hipStream_t s)
+{
+    const TableRef T = table_ref(tables[0], table_dtype, tau);
+    StackArgs a{};
+    a.x = x;
+    a.y = y;
+    for (int l = 0; l < n_layers; ++l) {
+        a.signs[l] = signs[l];
+        a.tables[l] = static_cast<const char *>(tables[l]);
+    }
+    a.n = n;
+    a.d = d;
+    a.d_out = d_out;
+    a.k = k;
+    a.tau = tau;
+    a.P = (int)(((int64_t)k * tau + 1023) / 1024);
+    a.n_layers = n_layers;
+    a.x_bf16 = x_dtype == LFFN_BF16;
+    a.scale = (float)(1.0 / std::sqrt(1024.0));
+    const int64_t rows = int64_t(1) << tau;
+    if (T.prepared) {
+        a.row_dwords = (uint32_t)d_out;
+        a.piece_shift = T.pw == 128 ? 7 : 6;
+        a.row_stride = (uint32_t)T.pw;
+        a.slice_stride = (uint32_t)((int64_t)k * rows * T.pw);
+        a.table_bytes = (uint32_t)prepared_tables_bytes(k, tau, d_out);
+    } else {
+        const int64_t row_bytes = (int64_t)d_out * (T.bf16 ? 2 : 4);
+        a.row_dwords = (uint32_t)(row_bytes / 4);
+        a.piece_shift = 31;
+        a.row_stride = (uint32_t)row_bytes;
+        a.slice_stride = 0;
+        a.table_bytes = (uint32_t)((int64_t)k * rows * row_bytes);
+    }
+    int threads = (int)((a.row_dwords + 63) / 64 * 64);
+    if (threads > 1024) threads = 1024;
+    TimedLaunch tl(1, s);
+    int rc = lffn_host::forward_stack_part(n_rounds, T.bf16, a, dim3((unsigned)n), threads, stack_lds_bytes(a.P, k), s);
+    if (rc != LFFN_OK) return rc;
+    LFFN_HIP(hipGetLastError());
+    tl.done();
+    t_last_gather = "forward_stack_kernel";
+    return LFFN_OK;
+}
+
 // Hash: the sign-diagonal rounds (`signs`, n_rounds) or the BH factors (`bmats`, block, n_factors).
 struct HashSpec {
     const int8_t *signs = nullptr;
@@ -1234,9 +1341,13 @@ int forward_core(const HashSpec &h, Mode mode, const void *x, const void *tables
         if (!aligned(workspace, 256)) return LFFN_E_ALIGN;
     }
     if (n == 0) return LFFN_OK;
+    const Options opt = options_snapshot();
+    if (!h.bh() && mode == kPlain && opt.gather_path == 0 && opt.hash_path == 0 && opt.small_tokens >= 0 &&
+        n <= (opt.small_tokens ? opt.small_tokens : kSmallTokensDefault) &&
+        stack_shape_ok(x, &h.signs, &tables, 1, n, d, k, tau, d_out, h.n_rounds, x_dtype, table_dtype))
+        return launch_forward_stack(x, &h.signs, &tables, y, n, d, k, tau, d_out, h.n_rounds, 1, x_dtype, table_dtype, s);
     rc = get_scratch(workspace, workspace_bytes, need, &sc);
     if (rc != LFFN_OK) return rc;
-    const Options opt = options_snapshot();
     const TableRef T = table_ref(tables, table_dtype, tau);
     LdsPlan plan;
     rc = plan_gather_lds(n, k, tau, d_out, T, mode, opt, &plan);
@@ -1393,6 +1504,8 @@ int lookupffn_init(void)
                     if (rc != LFFN_OK && rc != LFFN_E_UNSUPPORTED) return rc;
                 }
             }
+    rc = lffn_host::forward_stack_load();
+    if (rc != LFFN_OK) return rc;
     {
         GatherRingArgs ra{};
         for (int threads : {512, 1024})
@@ -1528,6 +1641,26 @@ int lookupffn_forward(const void *x, const int8_t *signs, const void *tables, fl
 {
     return forward_core(sign_hash(signs, n_rounds), kPlain, x, tables, y, n_tokens, d, k, tau, d_out, x_dtype,
                         table_dtype, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+int lookupffn_forward_stack(const void *x, const int8_t *const *signs, const void *const *tables, float *y,
+                            int64_t n_tokens, int d, int k, int tau, int d_out, int n_rounds, int n_layers,
+                            int x_dtype, int table_dtype, void *hip_stream)
+{
+    if (!signs || !tables) return LFFN_E_NULL;
+    if (n_layers < 1 || n_layers > kStackMaxLayers) return LFFN_E_SIZE;
+    const uint16_t *stand_in = reinterpret_cast<const uint16_t *>(uintptr_t(256));  // no codes leave the kernel
+    for (int l = 0; l < n_layers; ++l) {
+        int rc = check_hash(x, signs[l], stand_in, n_tokens, d, k, tau, n_rounds, x_dtype);
+        if (rc == LFFN_OK) rc = check_gather(stand_in, tables[l], y, n_tokens, k, tau, d_out, table_dtype);
+        if (rc != LFFN_OK) return rc;
+    }
+    if (n_layers > 1 && d_out != d) return LFFN_E_SIZE;
+    if (!stack_shape_ok(x, signs, tables, n_layers, n_tokens, d, k, tau, d_out, n_rounds, x_dtype, table_dtype))
+        return LFFN_E_UNSUPPORTED;
+    if (n_tokens == 0) return LFFN_OK;
+    return launch_forward_stack(x, signs, tables, y, n_tokens, d, k, tau, d_out, n_rounds, n_layers, x_dtype,
+                                table_dtype, static_cast<hipStream_t>(hip_stream));
 }
 
 int64_t lookupffn_static_scratch_bytes(void) { return kStaticScratchBytes; }
@@ -1749,6 +1882,11 @@ int lookupffn_set_option(const char *key, int value)
     if (!std::strcmp(key, "ring_threads")) {
         if (value != 0 && value != 512 && value != 1024) return LFFN_E_SIZE;
         g_opt.ring_threads = value;
+        return LFFN_OK;
+    }
+    if (!std::strcmp(key, "small_tokens")) {
+        if (value < -1 || value > (1 << 20)) return LFFN_E_SIZE;
+        g_opt.small_tokens = value;
         return LFFN_OK;
     }
     if (!std::strcmp(key, "token_slots")) {

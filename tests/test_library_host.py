@@ -108,6 +108,28 @@ def test_forward_static_argument_errors(L):
     assert fs(n=45000) == -7 and fs(n=1 << 30) == -7
 
 
+def test_forward_stack_argument_errors(L):
+    vp = ctypes.c_void_p
+
+    def st(x=FAKE, signs=(FAKE,), tables=(FAKE,), y=FAKE, n=0, d=768, k=96, tau=8, d_out=768, rounds=3, xdt=0, tdt=0):
+        sp = (vp * len(signs))(*signs) if signs is not None else None
+        tp = (vp * len(tables))(*tables) if tables is not None else None
+        return L.lookupffn_forward_stack(x, sp, tp, y, n, d, k, tau, d_out, rounds, len(signs or ()), xdt, tdt, None)
+
+    assert st() == 0 and st(signs=(FAKE,) * 12, tables=(FAKE,) * 12) == 0          # empty batch
+    assert st(signs=None) == -1 and st(x=None) == -1 and st(y=None) == -1
+    assert st(signs=(FAKE, None), tables=(FAKE, FAKE)) == -1 and st(signs=(FAKE, FAKE), tables=(FAKE, None)) == -1
+    assert st(signs=(FAKE,) * 33, tables=(FAKE,) * 33) == -2                       # at most 32 layers
+    assert st(tau=0) == -3 and st(tdt=7) == -4 and st(d_out=770) == -5
+    assert st(signs=(FAKE,) * 2, tables=(FAKE,) * 2, d_out=512) == -2              # chained layers: d_out == d
+    assert st(d_out=512) == 0                                                     # a single layer may differ
+    # shapes the single-launch kernel does not take: other transform widths, more than four rounds,
+    # a table set of 2 GiB or more, signs off the 16-byte grid
+    assert st(d=64) == -6 and st(d=512) == -6 and st(d=2048) == -6 and st(rounds=5) == -6
+    assert st(k=128, tau=12, d_out=1024) == -6 and st(k=128, tau=11, d_out=1024) == 0
+    assert st(signs=(FAKE + 4,)) == -6
+
+
 def test_weighted_argument_errors(L):
     def hw(x=FAKE, signs=FAKE, codes=FAKE, w=FAKE, n=0, d=768, k=96, tau=8, rounds=3, dt=0):
         return L.lookupffn_hash_weighted(x, signs, codes, w, n, d, k, tau, rounds, dt, None)
@@ -256,6 +278,8 @@ def test_options(L):
     assert L.lookupffn_set_option(b"ring_threads", 512) == 0 and L.lookupffn_set_option(b"ring_threads", 256) == -2
     assert L.lookupffn_set_option(b"ring_threads", 0) == 0
     assert L.lookupffn_set_option(b"token_slots", 0) == 0
+    assert L.lookupffn_set_option(b"small_tokens", -1) == 0 and L.lookupffn_set_option(b"small_tokens", -2) == -2
+    assert L.lookupffn_set_option(b"small_tokens", 256) == 0 and L.lookupffn_set_option(b"small_tokens", 0) == 0
     assert L.lookupffn_set_option(b"no_such_key", 1) == -2
     assert L.lookupffn_set_option(None, 1) == -1
 
