@@ -40,7 +40,9 @@
  *     convenience for simple callers: the library then uses a per-device buffer of its own, which it grows
  *     with hipMalloc when a call needs more (old buffers are kept until lookupffn_release_workspace(), so
  *     enqueued work stays valid; a growing call cannot be captured, and all NULL-workspace calls on a
- *     device must be ordered on one stream because they share that buffer).
+ *     device must be ordered on one stream because they share that buffer).  The size queries take any
+ *     arguments: a count that no buffer can have (beyond 2^63 bytes) comes back as INT64_MAX rounded down
+ *     to a multiple of 256, which every workspace is smaller than.
  *   - Return value: 0 on success, a negative lffn_status otherwise.  Arguments are
  *     validated before the first HIP call, so error paths need no GPU.
  *     n_tokens == 0 is a successful no-op.  Nothing is printed, nothing aborts.

@@ -869,26 +869,38 @@ int plan_gather_lds(int64_t n, int k, int tau, int d_out, const TableRef &T, Mod
     return LFFN_OK;
 }
 
+// Byte counts of the scratch regions.  The arguments may be anything a caller passes to a size query, so
+// the products are formed in 128 bits and a count that no buffer can have saturates at kBytesMax (every
+// workspace is then too small, and nothing overflows).
+constexpr int64_t kBytesMax = INT64_MAX & ~int64_t(255);
+typedef unsigned __int128 u128;
+int64_t sat_bytes(u128 b)
+{
+    b = (b + 255) & ~u128(255);
+    return b > (u128)kBytesMax ? kBytesMax : (int64_t)b;
+}
+int64_t sat_add(int64_t a, int64_t b) { return a > kBytesMax - b ? kBytesMax : a + b; }
+u128 n_pad_of(int64_t n) { return n > (int64_t(1) << 60) ? (u128)1 << 61 : (u128)packed_n_pad(n); }
 // packed codes of either staged kernel: [k/2][n_pad] words, or the ring kernel's lagged [k/2 + 3][n_pad]
-int64_t packed_bytes(int64_t n, int k) { return round256(ring_code_words(k) * packed_n_pad(n) * 4); }
-int64_t wpk_bytes(int64_t n, int k) { return round256((int64_t)k * packed_n_pad(n) * 4); }
-int64_t spk_bytes(int64_t n, int k, int tau) { return round256((int64_t)k * (tau + 1) * packed_n_pad(n) * 4); }
-int64_t abi_codes_bytes(int64_t n, int k) { return round256(n * (int64_t)k * 2); }
+int64_t packed_bytes(int64_t n, int k) { return sat_bytes((u128)ring_code_words(k) * n_pad_of(n) * 4); }
+int64_t wpk_bytes(int64_t n, int k) { return sat_bytes((u128)k * n_pad_of(n) * 4); }
+int64_t spk_bytes(int64_t n, int k, int tau) { return sat_bytes((u128)k * (u128)(tau + 1) * n_pad_of(n) * 4); }
+int64_t abi_codes_bytes(int64_t n, int k) { return sat_bytes((u128)n * (u128)k * 2); }
 int64_t abi_weights_bytes(int64_t n, int k, int tau, Mode m)
 {
-    return m == kPlain ? 0 : round256(n * (int64_t)k * (m == kProbes ? tau + 1 : 1) * 4);
+    return m == kPlain ? 0 : sat_bytes((u128)n * (u128)k * (u128)(m == kProbes ? tau + 1 : 1) * 4);
 }
 // scratch of a stand-alone gather: the staged kernel's packed codes and table-major weights / shares
 int64_t gather_ws_bytes(int64_t n, int k, int tau, Mode m)
 {
-    if (n <= 0) return 0;
-    return packed_bytes(n, k) + (m == kWeighted ? wpk_bytes(n, k) : m == kProbes ? spk_bytes(n, k, tau) : 0);
+    if (n <= 0 || k < 1) return 0;
+    return sat_add(packed_bytes(n, k), m == kWeighted ? wpk_bytes(n, k) : m == kProbes ? spk_bytes(n, k, tau) : 0);
 }
 // scratch of a forward pass: the hash's ABI-layout outputs and the gather's scratch
 int64_t forward_ws_bytes(int64_t n, int k, int tau, Mode m)
 {
-    if (n <= 0) return 0;
-    return abi_codes_bytes(n, k) + abi_weights_bytes(n, k, tau, m) + gather_ws_bytes(n, k, tau, m);
+    if (n <= 0 || k < 1) return 0;
+    return sat_add(sat_add(abi_codes_bytes(n, k), abi_weights_bytes(n, k, tau, m)), gather_ws_bytes(n, k, tau, m));
 }
 
 int launch_gather_lds(const LdsPlan &p, const uint32_t *packed, const float *wpk, const TableRef &T, float *y,
@@ -1319,7 +1331,7 @@ int64_t forward_need(const HashSpec &h, Mode mode, int64_t n, int d, int k, int 
 {
     if (n <= 0) return 0;
     const int64_t pack = (h.bh() && !h.bh_prepared) ? bh_pack_bytes(d, k, tau, h.block, h.n_factors) : 0;
-    return pack + forward_ws_bytes(n, k, tau, mode);
+    return sat_add(pack, forward_ws_bytes(n, k, tau, mode));
 }
 
 int forward_core(const HashSpec &h, Mode mode, const void *x, const void *tables, float *y, int64_t n, int d,
@@ -1626,13 +1638,13 @@ int64_t lookupffn_workspace_bytes_bh(int64_t n_tokens, int d, int k, int tau, in
 {
     if (!bh_shape_ok(d, k, tau, block & ~LFFN_PREPARED, n_factors)) return 0;
     const int64_t pack = (block & LFFN_PREPARED) ? 0 : bh_pack_bytes(d, k, tau, block, n_factors);
-    return pack + (n_tokens > 0 ? forward_ws_bytes(n_tokens, k, tau, kPlain) : 0);
+    return sat_add(pack, n_tokens > 0 ? forward_ws_bytes(n_tokens, k, tau, kPlain) : 0);
 }
 int64_t lookupffn_workspace_bytes_bh_weighted(int64_t n_tokens, int d, int k, int tau, int block, int n_factors)
 {
     if (!bh_shape_ok(d, k, tau, block & ~LFFN_PREPARED, n_factors)) return 0;
     const int64_t pack = (block & LFFN_PREPARED) ? 0 : bh_pack_bytes(d, k, tau, block, n_factors);
-    return pack + (n_tokens > 0 ? forward_ws_bytes(n_tokens, k, tau, kWeighted) : 0);
+    return sat_add(pack, n_tokens > 0 ? forward_ws_bytes(n_tokens, k, tau, kWeighted) : 0);
 }
 
 int lookupffn_forward(const void *x, const int8_t *signs, const void *tables, float *y, int64_t n_tokens,

@@ -290,3 +290,19 @@ def test_binding_refuses_cpu_tensors():
     signs = torch.ones(1, 2, 64, dtype=torch.int8)
     with pytest.raises(ValueError):
         binding.lookupffn_hash(x, signs, 8, 8, codes=torch.zeros(4, 8, dtype=torch.int16))
+
+
+def test_kernel_argument_structs_are_value_initialised():
+    """Every kernel-argument struct the host code fills starts zeroed: a field that one call path forgets
+    is then 0 / NULL in the kernel, never stack garbage (a run-time mode flag left unset once sent a
+    weighted gather down the multi-probe branch, which reads 1 + tau floats per table from a one-float
+    buffer)."""
+    src = (ROOT / "paper_2403_07221_amd" / "csrc" / "lookupffn.hip").read_text()
+    names = set(re.findall(r"\bstruct (\w+Args)\b", "".join(
+        (ROOT / "paper_2403_07221_amd" / "csrc" / f).read_text()
+        for f in ("hash_kernel.hpp", "bh_hash_kernel.hpp", "gather_kernel.hpp", "gather_lds_kernel.hpp",
+                  "gather_ring_kernel.hpp", "forward_stack_kernel.hpp"))))
+    assert {"HashArgs", "BhArgs", "GatherArgs", "GatherLdsArgs", "GatherRingArgs", "StackArgs"} <= names
+    decl = re.compile(r"^\s*(?:%s)\s+\w+\s*;" % "|".join(sorted(names)), re.M)
+    assert decl.findall(src) == []
+    assert len(re.findall(r"^\s*(?:%s)\s+\w+\{\};" % "|".join(sorted(names)), src, re.M)) >= 8
