@@ -6,7 +6,7 @@ the smoke check and the bench's ``cpu_baseline`` leg may import this package;
 the GPU library never does and shares no code with it.
 
 numpy conventions: fp32 data are ``float32`` arrays; bf16 data are ``uint16``
-arrays holding the raw bf16 bit patterns.
+arrays holding the raw bf16 bit patterns; IEEE half data are ``float16`` arrays.
 """
 from __future__ import annotations
 
@@ -30,7 +30,7 @@ try:
 except OSError:
     pass
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 _lib = None
 
 
@@ -68,6 +68,9 @@ def lib() -> ctypes.CDLL:
         L.oracle_weights.argtypes = [vp, ci, vp, vp, i64, ci, ci, ci, ci]
         L.oracle_gather_weighted.argtypes = [vp, vp, vp, ci, vp, i64, ci, ci, ci]
         L.oracle_forward_weighted.argtypes = [vp, ci, vp, vp, ci, vp, vp, vp, i64, ci, ci, ci, ci, ci]
+        for name in ("oracle_half_to_float", "oracle_float_to_bf16", "oracle_float_to_half"):
+            getattr(L, name).argtypes = [vp, vp, i64]
+            getattr(L, name).restype = None
         _lib = L
     return _lib
 
@@ -77,7 +80,9 @@ def _dtype_code(a: np.ndarray) -> int:
         return F32
     if a.dtype == np.uint16:
         return BF16
-    raise TypeError(f"oracle takes float32 or uint16 (raw bf16) arrays, got {a.dtype}")
+    if a.dtype == np.float16:
+        return F16
+    raise TypeError(f"oracle takes float32, uint16 (raw bf16) or float16 arrays, got {a.dtype}")
 
 
 def _ptr(a: np.ndarray):
@@ -104,6 +109,30 @@ def max_threads() -> int:
 
 def set_threads(n: int) -> None:
     lib().oracle_set_threads(n)
+
+
+def half_to_float(bits: np.ndarray) -> np.ndarray:
+    """Values of IEEE binary16 bit patterns (uint16), as float32."""
+    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    out = np.empty(bits.shape, dtype=np.float32)
+    lib().oracle_half_to_float(_ptr(bits), _ptr(out), bits.size)
+    return out
+
+
+def float_to_bf16(f: np.ndarray) -> np.ndarray:
+    """fp32 -> raw bf16 bit patterns (uint16), round to nearest even."""
+    f = np.ascontiguousarray(f, dtype=np.float32)
+    out = np.empty(f.shape, dtype=np.uint16)
+    lib().oracle_float_to_bf16(_ptr(f), _ptr(out), f.size)
+    return out
+
+
+def float_to_half(f: np.ndarray) -> np.ndarray:
+    """fp32 -> IEEE binary16 bit patterns (uint16), round to nearest even."""
+    f = np.ascontiguousarray(f, dtype=np.float32)
+    out = np.empty(f.shape, dtype=np.uint16)
+    lib().oracle_float_to_half(_ptr(f), _ptr(out), f.size)
+    return out
 
 
 def fwht(v: np.ndarray) -> np.ndarray:

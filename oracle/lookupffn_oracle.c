@@ -59,7 +59,7 @@
 #include <omp.h>
 #endif
 
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2 };
 enum { ORACLE_OK = 0, ORACLE_E_ARG = -1, ORACLE_E_NOMEM = -2 };
 
 /* host threads the token loops may use (tokens are independent, Sec. 2.1 "point-wise") */
@@ -96,10 +96,90 @@ int oracle_n_proj(int d, int k, int tau)
     return (int)(((int64_t)k * tau + d_pad - 1) / d_pad);
 }
 
-/* element `i` of a row stored as fp32 or bf16, widened exactly to fp32 */
+/*
+ * Value of an IEEE 754 binary16 bit pattern (1 sign, 5 exponent, 10 fraction bits), exact in fp32:
+ *   exponent 0:      (-1)^s * fraction * 2^-24          (zero and subnormals)
+ *   exponent 1..30:  (-1)^s * (1024 + fraction) * 2^(exponent - 25)
+ *   exponent 31:     infinity (fraction 0) or NaN
+ */
+static float half_value(uint16_t h)
+{
+    const int s = h >> 15, e = (h >> 10) & 31, m = h & 1023;
+    float v;
+    if (e == 0)
+        v = ldexpf((float)m, -24);
+    else if (e == 31)
+        v = m ? NAN : INFINITY;
+    else
+        v = ldexpf((float)(1024 + m), e - 25);
+    return s ? -v : v;
+}
+
+void oracle_half_to_float(const uint16_t *h, float *out, int64_t n)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = half_value(h[i]);
+}
+
+/*
+ * fp32 -> 16-bit storage, round to nearest, ties to even (for outputs kept in 16 bits).
+ * bf16 keeps the top 16 bits of the fp32 pattern: add half an ulp of the kept part, plus the
+ * kept part's last bit on a tie, and cut; NaN stays NaN (quiet bit set).
+ */
+void oracle_float_to_bf16(const float *f, uint16_t *out, int64_t n)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        uint32_t u;
+        memcpy(&u, &f[i], 4);
+        if ((u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu))
+            out[i] = (uint16_t)((u >> 16) | 0x0040u);
+        else
+            out[i] = (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+    }
+}
+
+/*
+ * fp32 -> binary16, round to nearest even, by search: among the 2 * 0x7C01 finite-or-infinite
+ * patterns of the value's sign, the one whose value is nearest (ties: even fraction bit).  Written as
+ * the definition, not as bit tricks: the candidates are found by bisection on the magnitude
+ * (half_value is monotone in the pattern for a fixed sign).
+ */
+void oracle_float_to_half(const float *f, uint16_t *out, int64_t n)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        const float v = f[i];
+        if (v != v) {
+            out[i] = 0x7E00;
+            continue;
+        }
+        const uint16_t sign = signbit(v) ? 0x8000 : 0;
+        const double a = fabs((double)v);
+        /* largest pattern lo in [0, 0x7C00] with value <= a (0x7C00 = infinity) */
+        int lo = 0, hi = 0x7C00;
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) / 2;
+            if ((double)half_value((uint16_t)mid) <= a)
+                lo = mid;
+            else
+                hi = mid - 1;
+        }
+        int pick = lo;
+        if (lo < 0x7C00) {
+            /* beyond the largest finite value the upper neighbour counts as 2^16 (the next power of
+             * two), as IEEE rounding to an unbounded exponent range prescribes */
+            const double below = (double)half_value((uint16_t)lo);
+            const double above = lo + 1 == 0x7C00 ? 65536.0 : (double)half_value((uint16_t)(lo + 1));
+            const double dl = a - below, du = above - a;
+            if (du < dl || (du == dl && (lo & 1))) pick = lo + 1;
+        }
+        out[i] = (uint16_t)(sign | pick);
+    }
+}
+
+/* element `i` of a row stored as fp32, bf16 or binary16, widened exactly to fp32 */
 static float load_elt(const void *base, int dtype, int64_t i)
 {
     if (dtype == ORACLE_F32) return ((const float *)base)[i];
+    if (dtype == ORACLE_F16) return half_value(((const uint16_t *)base)[i]);
     uint32_t w = (uint32_t)((const uint16_t *)base)[i] << 16; /* bf16 = top half of fp32 */
     float f;
     memcpy(&f, &w, sizeof f);
