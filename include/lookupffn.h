@@ -23,11 +23,11 @@
  *   - Every data pointer is a DEVICE pointer owned by the caller and valid on the
  *     current HIP device; the library never frees or retains them.
  *   - Arrays are dense and row-major:
- *       x      [n_tokens][d]                 fp32 or bf16 (raw 16-bit patterns)
+ *       x      [n_tokens][d]                 fp32, bf16 or IEEE half (16-bit patterns)
  *       signs  [P][n_rounds][d_pad]          int8, a negative entry means "flip"
  *       codes  [n_tokens][k]                 uint16
  *       weights[n_tokens][k]                 fp32 (weighted variant only)
- *       tables [k][2^tau][d_out]             fp32 or bf16, or the prepared copy (lookupffn_prepare_tables)
+ *       tables [k][2^tau][d_out]             fp32, bf16 or IEEE half, or the prepared copy (lookupffn_prepare_tables)
  *       y      [n_tokens][d_out]             fp32
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Work is enqueued on it and the call returns without synchronising.
@@ -47,7 +47,7 @@
  *     validated before the first HIP call, so error paths need no GPU.
  *     n_tokens == 0 is a successful no-op.  Nothing is printed, nothing aborts.
  *   - Arithmetic: the hash runs in fp32 (round to nearest, no fused multiply-add,
- *     butterflies in ascending stride order), bf16 inputs are widened exactly; the
+ *     butterflies in ascending stride order), bf16 and half inputs are widened exactly; the
  *     gather accumulates in fp32 in table order j = 0..k-1.  The weights are evaluated in
  *     fp32 as |z_j|_1 / prod_b (1 + exp(-2|z_jb|)) (the same quotient with exp(|z_j|_1) divided
  *     out, so nothing overflows) with the hardware exp2 and reciprocal; the weighted gather
@@ -62,7 +62,7 @@
 extern "C" {
 #endif
 
-typedef enum { LFFN_F32 = 0, LFFN_BF16 = 1 } lffn_dtype;
+typedef enum { LFFN_F32 = 0, LFFN_BF16 = 1, LFFN_F16 = 2 /* IEEE binary16 */ } lffn_dtype;
 /* OR-ed into a `table_dtype` argument: `tables` is the buffer lookupffn_prepare_tables() wrote (from
  * tables of the dtype in the low bits).  OR-ed into a `block` argument of the BH entry points: `bmats`
  * is the buffer lookupffn_prepare_bh() wrote. */
@@ -73,9 +73,9 @@ typedef enum {
     LFFN_E_NULL = -1,         /* a required pointer is NULL */
     LFFN_E_SIZE = -2,         /* n_tokens < 0, d/k/d_out/n_rounds < 1, or a size product overflows */
     LFFN_E_TAU = -3,          /* tau outside [1, 16] */
-    LFFN_E_DTYPE = -4,        /* dtype is neither LFFN_F32 nor LFFN_BF16 */
+    LFFN_E_DTYPE = -4,        /* dtype is none of LFFN_F32, LFFN_BF16, LFFN_F16 */
     LFFN_E_ALIGN = -5,        /* tables or y not 16-byte aligned, x/codes not element aligned,
-                                 or d_out not a multiple of 4 (fp32 tables) / 8 (bf16 tables) */
+                                 or d_out not a multiple of 4 (fp32 tables) / 8 (16-bit tables) */
     LFFN_E_UNSUPPORTED = -6,  /* a shape the kernels are not built for: d_pad above 4096; the BH
                                  entry points state their own limits */
     LFFN_E_WORKSPACE = -7,    /* caller workspace (or a prepare call's output buffer) smaller than the matching
@@ -112,7 +112,7 @@ int64_t lookupffn_workspace_bytes_gather(int64_t n_tokens, int k);
 /*
  * Whole forward pass: Hash then Gather on the same stream (Sec. 3.1, eq. "lookup").
  * Scratch: lookupffn_workspace_bytes(n_tokens, k) bytes (0 if n_tokens == 0).
- * Batches of up to 64 tokens ("small_tokens" below) whose shape lookupffn_forward_stack takes run as that
+ * Batches of up to 512 tokens ("small_tokens" below) whose shape lookupffn_forward_stack takes run as that
  * call's single launch with n_layers = 1 (no scratch touched); y has the same bits either way.
  */
 int lookupffn_forward(const void *x, const int8_t *signs, const void *tables, float *y,
@@ -159,13 +159,13 @@ int64_t lookupffn_static_scratch_bytes(void);
 /*
  * One-time preparation of the learned tables T_1 .. T_k of eq. "lookup" (Sec. 3.1): they are constants of
  * the model, so the layout the gather kernels stream best is written once, outside the forward pass.
- * lookupffn_prepare_tables copies tables[k][2^tau][d_out] (fp32 or bf16) into `prepared` as fp32 (bf16
+ * lookupffn_prepare_tables copies tables[k][2^tau][d_out] (fp32, bf16 or half) into `prepared` as fp32 (16-bit rows
  * widened exactly), slice-major: the 128-byte (tau <= 8) or 64-byte (tau >= 9) column slice of all rows of
  * all tables is one contiguous run, ragged last slice zero-filled.  `prepared`: device memory, 256-byte
  * aligned, lookupffn_prepared_tables_bytes() bytes (0 for arguments the call would reject), owned by the
  * caller.  Every gather / forward entry point takes it in place of `tables` with
  * table_dtype = LFFN_PREPARED | <dtype of the source tables>; results are bit-identical to those with
- * the row-major tables.  bf16 tables take the LDS-staged gather only in this form (it reads fp32 rows).
+ * the row-major tables.  16-bit tables take the LDS-staged gather only in this form (it reads fp32 rows).
  */
 int64_t lookupffn_prepared_tables_bytes(int k, int tau, int d_out, int table_dtype);
 int lookupffn_prepare_tables(const void *tables, int k, int tau, int d_out, int table_dtype,
@@ -290,7 +290,7 @@ int lookupffn_timing_read_each(int which, double *ms_out, int64_t capacity, int6
  *                                     default: 128 bytes up to tau = 8, 64 bytes from tau = 9 on
  *   "small_tokens"     -1 / 1..2^20   lookupffn_forward: batches up to this many tokens take the single-launch
  *                                     kernel of lookupffn_forward_stack when the shape is that kernel's and no
- *                                     hash or gather path is forced (default 64; -1: never)
+ *                                     hash or gather path is forced (default 512; -1: never)
  *   "token_slots"      1 .. 32        staged kernels: at most this many tokens per lane group and chunk
  *   "hash_path"        1              always the generic hash kernel (default: the two-layout
  *                                     kernel when d_pad = 1024 and n_rounds <= 4)

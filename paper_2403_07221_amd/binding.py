@@ -15,7 +15,7 @@ import torch
 _LIB_PATH = Path(__file__).resolve().parent / "liblookupffn.so"
 _lib = None
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 PREPARED = 0x100   # OR-ed into table_dtype / block: the buffer is a prepared copy (see include/lookupffn.h)
 EXPORTS = (
     "lookupffn_init",
@@ -107,7 +107,9 @@ def _dtype_code(t: torch.Tensor) -> int:
         return F32
     if t.dtype == torch.bfloat16:
         return BF16
-    raise TypeError(f"expected float32 or bfloat16, got {t.dtype}")
+    if t.dtype == torch.float16:
+        return F16
+    raise TypeError(f"expected float32, bfloat16 or float16, got {t.dtype}")
 
 
 def _dev(t: torch.Tensor, name: str) -> int:
@@ -174,7 +176,8 @@ def lookupffn_init() -> None:
 
 
 def lookupffn_prepared_tables_bytes(k: int, tau: int, d_out: int, table_dtype) -> int:
-    code = table_dtype if isinstance(table_dtype, int) else (BF16 if table_dtype in ("bf16", torch.bfloat16) else F32)
+    code = table_dtype if isinstance(table_dtype, int) else (
+        BF16 if table_dtype in ("bf16", torch.bfloat16) else F16 if table_dtype in ("f16", torch.float16) else F32)
     return lib().lookupffn_prepared_tables_bytes(k, tau, d_out, code)
 
 

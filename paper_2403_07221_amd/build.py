@@ -35,7 +35,8 @@ def build_library(verbose: bool = False, jobs: int | None = None, only_parts=Non
 
     `only_parts` (development aid; `python -m paper_2403_07221_amd.build 0 12`): recompile just these parts and
     link them with the other parts' objects kept from the last such build in _build/ (a part whose object is
-    missing is compiled too).  The objects are then kept; a plain call compiles everything and keeps nothing."""
+    missing is compiled too).  The objects are then kept -- a part whose sources changed since must be named again, or
+    the link takes its stale object; a plain call compiles everything, keeps nothing and drops the kept objects."""
     jobs = jobs or max(1, min(os.cpu_count() or 1, int(os.environ.get("MAX_JOBS", "16"))))
     OBJ_DIR.mkdir(exist_ok=True)
     keep = only_parts is not None
@@ -71,7 +72,8 @@ def build_library(verbose: bool = False, jobs: int | None = None, only_parts=Non
         os.replace(tmp, LIB)
     finally:
         if not keep:
-            for o in objs:
+            # a full build also drops the objects a partial build kept: they no longer match the sources
+            for o in [*objs, *OBJ_DIR.glob("lookupffn_part*.dev.o")]:
                 o.unlink(missing_ok=True)
         tmp.unlink(missing_ok=True)
     return LIB

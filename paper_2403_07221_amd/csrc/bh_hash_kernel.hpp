@@ -41,7 +41,7 @@ struct BhArgs {
     long long n_pad;
     long long n;
     int d, k, tau, n_factors, P;
-    int x_bf16;
+    int x_kind;  // element type of x: 0 fp32, 1 bf16, 2 IEEE half
     int x_vec4;           // rows may be read four coordinates at a time (alignment checked by the host)
     float scale;
 };
@@ -192,12 +192,12 @@ __global__ __launch_bounds__(kBhThreads) void bh_hash_kernel(BhArgs a)
                 // immediate offset; tiles wholly inside or outside the row are told apart by uniform
                 // branches), then a 4 x 4 transpose between lane groups and registers (two rounds of
                 // lane-row swaps) gives the layout above
-                const char *xrow = reinterpret_cast<const char *>(a.x) + (tc * a.d + 4 * (long long)g) * (a.x_bf16 ? 2 : 4);
+                const char *xrow = reinterpret_cast<const char *>(a.x) + (tc * a.d + 4 * (long long)g) * (a.x_kind ? 2 : 4);
                 auto piece = [&](int beta) -> float4 {
-                    if (a.x_bf16) {
+                    if (a.x_kind) {
                         const uint2 w = *reinterpret_cast<const uint2 *>(xrow + beta * 32);
-                        return make_float4(__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xFFFF0000u),
-                                           __uint_as_float(w.y << 16), __uint_as_float(w.y & 0xFFFF0000u));
+                        const float2 lo = widen16x2(w.x, a.x_kind), hi = widen16x2(w.y, a.x_kind);
+                        return make_float4(lo.x, lo.y, hi.x, hi.y);
                     }
                     return *reinterpret_cast<const float4 *>(xrow + beta * 64);
                 };
@@ -230,8 +230,8 @@ __global__ __launch_bounds__(kBhThreads) void bh_hash_kernel(BhArgs a)
                         const int c = 16 * beta + (int)g + 4 * r;
                         float f = 0.0f;
                         if (t_ok && c < a.d) {
-                            if (a.x_bf16)
-                                f = __uint_as_float((uint32_t)((const uint16_t *)a.x)[t * a.d + c] << 16);
+                            if (a.x_kind)
+                                f = widen16(((const uint16_t *)a.x)[t * a.d + c], a.x_kind);
                             else
                                 f = ((const float *)a.x)[t * a.d + c];
                         }

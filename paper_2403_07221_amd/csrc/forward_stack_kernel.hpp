@@ -7,7 +7,7 @@
 // the hash and the gather, nor between layers:
 //   * wave 0 transforms the row (the same round function as hash1024_kernel, so the same bits), forms the
 //     sign-bit string and turns each code into the byte offset of the selected row, in LDS;
-//   * every lane then owns one dword of the output row (one fp32 column, or two bf16 columns) and walks the
+//   * every lane then owns one dword of the output row (one fp32 column, or two 16-bit columns) and walks the
 //     k tables IN ORDER: the row offset is wave-uniform, so the fetch is a buffer load with the lane's
 //     column offset in a VGPR and the row offset in an SGPR; 32 fetches are issued back to back into one
 //     register set while the previous 32 are added;
@@ -23,8 +23,8 @@
 // four waves that exchange through LDS they take as long: the butterflies of a round depend on one
 // another).
 //
-// Shapes: d_pad = 1024 (512 < d <= 1024); table set below 2 GiB (32-bit buffer offsets); row-major fp32 or
-// bf16 tables, or the prepared (slice-major, fp32) layout.
+// Shapes: d_pad = 1024 (512 < d <= 1024); table set below 2 GiB (32-bit buffer offsets); row-major fp32, bf16
+// or IEEE half tables, or the prepared (slice-major, fp32) layout.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -43,7 +43,7 @@ struct StackArgs {
     const char *tables[kStackMaxLayers];   // per layer, all in the same layout
     long long n;
     int d, d_out, k, tau, P, n_layers;
-    int x_bf16;
+    int x_kind;  // element type of x: 0 fp32, 1 bf16, 2 IEEE half
     float scale;
     uint32_t row_dwords;  // dwords of one table row
     // byte offset of dword q of row r (r = (j << tau) + code), with b = 4q:
@@ -63,11 +63,12 @@ __host__ __device__ inline size_t stack_lds_bytes(int P, int k)
     return ((size_t)kH1024TransposeWords + stack_bit_words(P) + stack_code_words(k) + 2 * 1024) * 4;
 }
 
-template <int R, bool BF16>
+template <int R, int KIND>
 __global__ __launch_bounds__(1024) void forward_stack_kernel(StackArgs a)
 {
     constexpr int N = 1024, NREG = 16;
-    constexpr int CH = BF16 ? kStackChunk / 2 : kStackChunk;  // two accumulators and the unpacking need registers too
+    constexpr bool HALF16 = KIND != 0;  // two 16-bit columns per dword
+    constexpr int CH = HALF16 ? kStackChunk / 2 : kStackChunk;  // two accumulators and the unpacking need registers too
     extern __shared__ uint32_t lds[];
     const unsigned tid = threadIdx.x;
     const unsigned lane = tid & 63u;
@@ -94,7 +95,7 @@ __global__ __launch_bounds__(1024) void forward_stack_kernel(StackArgs a)
             // ---- a1: the row in layout A (lane = i[9:4], register = i[3:0]) -------------------------
             float xv[NREG];
             if (l == 0) {
-                h1024_load_row(a.x, t, a.d, a.x_bf16, vec_ok, lane, xv);
+                h1024_load_row(a.x, t, a.d, a.x_kind, vec_ok, lane, xv);
             } else {
 #pragma unroll
                 for (int m = 0; m < 4; ++m) {
@@ -159,9 +160,10 @@ __global__ __launch_bounds__(1024) void forward_stack_kernel(StackArgs a)
 #pragma unroll
                 for (int u = 0; u < CH; ++u) {
                     if (u < n_add) {
-                        if constexpr (BF16) {
-                            acc0 += __uint_as_float(r[u] << 16);
-                            acc1 += __uint_as_float(r[u] & 0xFFFF0000u);
+                        if constexpr (HALF16) {
+                            const float2 e = widen16x2<KIND == 0 ? 1 : KIND>(r[u]);
+                            acc0 += e.x;
+                            acc1 += e.y;
                         } else {
                             acc0 += __uint_as_float(r[u]);
                         }
@@ -182,13 +184,13 @@ __global__ __launch_bounds__(1024) void forward_stack_kernel(StackArgs a)
                 if (c + 2 < n_ch) issue(ra, (c + 2) * CH);
                 if (c + 1 < n_ch) add(rb, (c + 1) * CH);
             }
-            const uint32_t col = q * (BF16 ? 2 : 1);
+            const uint32_t col = q * (HALF16 ? 2 : 1);
             if (!last) {
                 nxt[col] = acc0;
-                if constexpr (BF16) nxt[col + 1] = acc1;
+                if constexpr (HALF16) nxt[col + 1] = acc1;
             } else {
                 a.y[t * a.d_out + col] = acc0;
-                if constexpr (BF16) a.y[t * a.d_out + col + 1] = acc1;
+                if constexpr (HALF16) a.y[t * a.d_out + col + 1] = acc1;
             }
         }
         __syncthreads();

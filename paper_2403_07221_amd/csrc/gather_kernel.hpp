@@ -22,6 +22,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "elem16.hpp"
+
 namespace lffn {
 
 constexpr int kGatherThreads = 256;
@@ -31,7 +33,7 @@ constexpr int kXcds = 8;
 struct GatherArgs {
     const uint16_t *codes;  // [n][k]
     const float *weights;   // [n][k] for the weighted form, [n][k][1+tau] for the multi-probe form, else NULL
-    const char *tables;     // [k][rows][d_out] fp32 or bf16
+    const char *tables;     // [k][rows][d_out] fp32, bf16 or IEEE half
     float *y;               // [n][d_out]
     long long n;
     int k, tau, d_out;
@@ -51,9 +53,10 @@ struct GatherArgs {
     unsigned long long slice_stride;
 };
 
-template <bool BF16>
+// KIND: element type of the rows (0 fp32, 1 bf16, 2 IEEE half)
+template <int KIND>
 struct Acc {
-    static constexpr int W = BF16 ? 8 : 4;  // elements in 16 bytes
+    static constexpr int W = KIND ? 8 : 4;  // elements in 16 bytes
     float f[W];
     __device__ __forceinline__ void zero()
     {
@@ -66,45 +69,43 @@ struct Acc {
     __device__ __forceinline__ void pin()
     {
         asm volatile("" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]));
-        if constexpr (BF16) asm volatile("" : "+v"(f[4]), "+v"(f[5]), "+v"(f[6]), "+v"(f[7]));
+        if constexpr (KIND != 0) asm volatile("" : "+v"(f[4]), "+v"(f[5]), "+v"(f[6]), "+v"(f[7]));
+    }
+    // the W elements of 16 bytes of a row, widened exactly
+    __device__ __forceinline__ void unpack(const uint4 &r, float (&e)[W]) const
+    {
+        if constexpr (KIND != 0) {
+            const float2 a = widen16x2<KIND == 0 ? 1 : KIND>(r.x), b = widen16x2<KIND == 0 ? 1 : KIND>(r.y),
+                         c = widen16x2<KIND == 0 ? 1 : KIND>(r.z), d = widen16x2<KIND == 0 ? 1 : KIND>(r.w);
+            e[0] = a.x;
+            e[1] = a.y;
+            e[2] = b.x;
+            e[3] = b.y;
+            e[4] = c.x;
+            e[5] = c.y;
+            e[6] = d.x;
+            e[7] = d.y;
+        } else {
+            e[0] = __uint_as_float(r.x);
+            e[1] = __uint_as_float(r.y);
+            e[2] = __uint_as_float(r.z);
+            e[3] = __uint_as_float(r.w);
+        }
     }
     __device__ __forceinline__ void add(const uint4 &r)
     {
-        if constexpr (BF16) {
-            // a bf16 is the top half of an fp32: widening is a shift / mask, exact
-            f[0] += __uint_as_float(r.x << 16);
-            f[1] += __uint_as_float(r.x & 0xFFFF0000u);
-            f[2] += __uint_as_float(r.y << 16);
-            f[3] += __uint_as_float(r.y & 0xFFFF0000u);
-            f[4] += __uint_as_float(r.z << 16);
-            f[5] += __uint_as_float(r.z & 0xFFFF0000u);
-            f[6] += __uint_as_float(r.w << 16);
-            f[7] += __uint_as_float(r.w & 0xFFFF0000u);
-        } else {
-            f[0] += __uint_as_float(r.x);
-            f[1] += __uint_as_float(r.y);
-            f[2] += __uint_as_float(r.z);
-            f[3] += __uint_as_float(r.w);
-        }
+        float e[W];
+        unpack(r, e);
+#pragma unroll
+        for (int i = 0; i < W; ++i) f[i] += e[i];
     }
     // acc += w * row, one rounding per element
     __device__ __forceinline__ void fma(const uint4 &r, float w)
     {
-        if constexpr (BF16) {
-            f[0] = __builtin_fmaf(w, __uint_as_float(r.x << 16), f[0]);
-            f[1] = __builtin_fmaf(w, __uint_as_float(r.x & 0xFFFF0000u), f[1]);
-            f[2] = __builtin_fmaf(w, __uint_as_float(r.y << 16), f[2]);
-            f[3] = __builtin_fmaf(w, __uint_as_float(r.y & 0xFFFF0000u), f[3]);
-            f[4] = __builtin_fmaf(w, __uint_as_float(r.z << 16), f[4]);
-            f[5] = __builtin_fmaf(w, __uint_as_float(r.z & 0xFFFF0000u), f[5]);
-            f[6] = __builtin_fmaf(w, __uint_as_float(r.w << 16), f[6]);
-            f[7] = __builtin_fmaf(w, __uint_as_float(r.w & 0xFFFF0000u), f[7]);
-        } else {
-            f[0] = __builtin_fmaf(w, __uint_as_float(r.x), f[0]);
-            f[1] = __builtin_fmaf(w, __uint_as_float(r.y), f[1]);
-            f[2] = __builtin_fmaf(w, __uint_as_float(r.z), f[2]);
-            f[3] = __builtin_fmaf(w, __uint_as_float(r.w), f[3]);
-        }
+        float e[W];
+        unpack(r, e);
+#pragma unroll
+        for (int i = 0; i < W; ++i) f[i] = __builtin_fmaf(w, e[i], f[i]);
     }
 };
 
@@ -115,7 +116,7 @@ __device__ __forceinline__ uint32_t code_of(const uint4 &c, int u)
 }
 
 // WMODE: 0 = plain sum, 1 = weighted form, 2 = multi-probe form
-template <bool BF16, int LPT, int WMODE>
+template <int KIND, int LPT, int WMODE>
 __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a)
 {
     constexpr int TPW = 64 / LPT;  // tokens per wave
@@ -154,7 +155,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a)
         return *reinterpret_cast<const uint4 *>(tcol + (unsigned long long)r * row_bytes);
     };
 
-    Acc<BF16> acc;
+    Acc<KIND> acc;
     acc.zero();
 
     int j0 = 0;
@@ -251,11 +252,11 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a)
     for (; j0 < k; ++j0) acc.add(row(j0, crow[j0]));
 
     // ---- a6: store, streaming (y is written once and not read again here) -------------
-    float *yp = a.y + t * a.d_out + (size_t)vec * Acc<BF16>::W;
+    float *yp = a.y + t * a.d_out + (size_t)vec * Acc<KIND>::W;
     typedef float f4 __attribute__((ext_vector_type(4)));
     f4 o0 = {acc.f[0], acc.f[1], acc.f[2], acc.f[3]};
     __builtin_nontemporal_store(o0, reinterpret_cast<f4 *>(yp));
-    if constexpr (BF16) {
+    if constexpr (KIND != 0) {
         f4 o1 = {acc.f[4], acc.f[5], acc.f[6], acc.f[7]};
         __builtin_nontemporal_store(o1, reinterpret_cast<f4 *>(yp) + 1);
     }

@@ -44,6 +44,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "elem16.hpp"
+
 #include <type_traits>
 
 #include "gather_kernel.hpp"
@@ -554,13 +556,13 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
 
 #if !defined(LFFN_PART) || LFFN_PART == 0  // a plain function: defined by part 0 only of a build in parts
 // One-time re-layout of the learned tables T_j (Sec. 3.1, eq. "lookup") for the gather kernels: fp32
-// elements (bf16 rows widened exactly: a bf16 is the upper half of an fp32), slice-major,
+// elements (bf16 and IEEE half rows widened exactly), slice-major,
 //   dst[ps][j][row][PW bytes],  ps < ceil(d_out*4 / PW),
 // so that the column slice of ALL tables a workgroup streams is one contiguous run.  Pieces past the end
 // of a row (ragged last slice) are zero.  One 16-byte output piece per thread and step.
 //   nvec = d_out / 4 (pieces per fp32 row), ppw = PW / 16, n_out = output pieces in total
 __global__ __launch_bounds__(256) void prepare_tables_kernel(const void *src, uint4 *dst, int k, int rows, int nvec,
-                                                             int ppw, int bf16, long long n_out)
+                                                             int ppw, int kind, long long n_out)
 {
     for (long long o = (long long)blockIdx.x * blockDim.x + threadIdx.x; o < n_out;
          o += (long long)gridDim.x * blockDim.x) {
@@ -574,9 +576,10 @@ __global__ __launch_bounds__(256) void prepare_tables_kernel(const void *src, ui
         uint4 v = make_uint4(0u, 0u, 0u, 0u);
         if (vec < nvec) {
             const long long piece = ((long long)j * rows + row) * nvec + vec;
-            if (bf16) {
+            if (kind) {
                 const uint2 w = static_cast<const uint2 *>(src)[piece];
-                v = make_uint4(w.x << 16, w.x & 0xFFFF0000u, w.y << 16, w.y & 0xFFFF0000u);
+                const float2 lo = widen16x2(w.x, kind), hi = widen16x2(w.y, kind);
+                v = make_uint4(__float_as_uint(lo.x), __float_as_uint(lo.y), __float_as_uint(hi.x), __float_as_uint(hi.y));
             } else {
                 v = static_cast<const uint4 *>(src)[piece];
             }

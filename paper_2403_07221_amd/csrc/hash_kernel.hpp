@@ -17,6 +17,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "elem16.hpp"
+
 namespace lffn {
 
 // Layout of the gather kernels' internal "packed" codes (the scratch buffer of the forward
@@ -42,7 +44,7 @@ struct HashArgs {
     long long n_pad;      // token stride of `packed`
     long long n;
     int d, k, tau, n_rounds, P;
-    int x_bf16;
+    int x_kind;           // element type of x: 0 fp32, 1 bf16, 2 IEEE half
     float scale;          // (float)(1 / sqrt(N))
 };
 
@@ -281,8 +283,8 @@ __global__ __launch_bounds__(kHashThreads) void hash_kernel(HashArgs a)
             const int i = (int)lane + 64 * r;
             float f = 0.0f;
             if (i < a.d) {
-                if (a.x_bf16)
-                    f = __uint_as_float((uint32_t)((const uint16_t *)a.x)[t * a.d + i] << 16);
+                if (a.x_kind)
+                    f = widen16(((const uint16_t *)a.x)[t * a.d + i], a.x_kind);
                 else
                     f = ((const float *)a.x)[t * a.d + i];
             }
@@ -436,9 +438,9 @@ __device__ __forceinline__ void h1024_lane_setup(uint32_t tp0, unsigned lane, H1
     }
 }
 
-// a1: coordinates lane*16 .. lane*16+15 of the row at `row` (d elements, fp32 or bf16), widened, zero-padded.
-// vec_ok: d % 4 == 0 and the row starts 16-byte (fp32) / 8-byte (bf16) aligned.
-__device__ __forceinline__ void h1024_load_row(const void *x, long long t, int d, bool x_bf16, bool vec_ok, unsigned lane,
+// a1: coordinates lane*16 .. lane*16+15 of row t (d elements of kind x_kind), widened, zero-padded.
+// vec_ok: d % 4 == 0 and the rows start 16-byte (fp32) / 8-byte (16-bit kinds) aligned.
+__device__ __forceinline__ void h1024_load_row(const void *x, long long t, int d, int x_kind, bool vec_ok, unsigned lane,
                                                float (&xv)[16])
 {
     const int i0 = (int)lane * 16;
@@ -447,10 +449,10 @@ __device__ __forceinline__ void h1024_load_row(const void *x, long long t, int d
         for (int m = 0; m < 4; ++m) {
             float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
             if (i0 + 4 * m < d) {
-                if (x_bf16) {
+                if (x_kind) {
                     const uint2 w = *reinterpret_cast<const uint2 *>((const uint16_t *)x + t * d + i0 + 4 * m);
-                    f = make_float4(__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xFFFF0000u),
-                                    __uint_as_float(w.y << 16), __uint_as_float(w.y & 0xFFFF0000u));
+                    const float2 lo = widen16x2(w.x, x_kind), hi = widen16x2(w.y, x_kind);
+                    f = make_float4(lo.x, lo.y, hi.x, hi.y);
                 } else {
                     f = *reinterpret_cast<const float4 *>((const float *)x + t * d + i0 + 4 * m);
                 }
@@ -465,8 +467,8 @@ __device__ __forceinline__ void h1024_load_row(const void *x, long long t, int d
         for (int e = 0; e < 16; ++e) {
             float f = 0.0f;
             if (i0 + e < d) {
-                if (x_bf16)
-                    f = __uint_as_float((uint32_t)((const uint16_t *)x)[t * d + i0 + e] << 16);
+                if (x_kind)
+                    f = widen16(((const uint16_t *)x)[t * d + i0 + e], x_kind);
                 else
                     f = ((const float *)x)[t * d + i0 + e];
             }
@@ -587,12 +589,12 @@ __global__ __launch_bounds__(kHashThreads) __attribute__((amdgpu_waves_per_eu(4,
     if (P == 1 && gw < a.n) load_masks(0);
 
     float xn[NREG];
-    if (gw < a.n) h1024_load_row(a.x, gw, a.d, a.x_bf16, vec_ok, lane, xn);
+    if (gw < a.n) h1024_load_row(a.x, gw, a.d, a.x_kind, vec_ok, lane, xn);
     for (long long t = gw; t < a.n; t += n_waves) {
         float xv[NREG];
 #pragma unroll
         for (int e = 0; e < NREG; ++e) xv[e] = xn[e];
-        if (t + n_waves < a.n) h1024_load_row(a.x, t + n_waves, a.d, a.x_bf16, vec_ok, lane, xn);
+        if (t + n_waves < a.n) h1024_load_row(a.x, t + n_waves, a.d, a.x_kind, vec_ok, lane, xn);
 
         for (int p = 0; p < P; ++p) {
             if (P > 1) load_masks(p);

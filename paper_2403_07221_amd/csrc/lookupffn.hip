@@ -42,7 +42,7 @@ struct AttrOnly {
     ~AttrOnly();
 };
 // part 1: the direct gather kernel
-int gather_direct_part(bool bf16, int lpt, const GatherArgs &a, bool probes, dim3 grid, hipStream_t s);
+int gather_direct_part(int kind, int lpt, const GatherArgs &a, bool probes, dim3 grid, hipStream_t s);
 int gather_direct_load();  // makes the runtime load part 1's code object now (lookupffn_init)
 // parts 2, 3: the LDS-staged gather kernel (plain sum; weighted and multi-probe)
 int gather_lds_plain_part(int tok, const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s);
@@ -51,7 +51,7 @@ int gather_lds_probes_part(int tok, const GatherLdsArgs &a, int fr, int sw, dim3
 // part 12: the lagged, bank-interleaved staged gather (prepared tables, tau <= 8)
 int gather_ring_part(int threads, int tok, const GatherRingArgs &a, dim3 grid, hipStream_t s);
 // part 13: hash and gather of a few tokens, one or several chained layers, in one launch
-int forward_stack_part(int n_rounds, bool bf16, const StackArgs &a, dim3 grid, int threads, size_t lds, hipStream_t s);
+int forward_stack_part(int n_rounds, int kind, const StackArgs &a, dim3 grid, int threads, size_t lds, hipStream_t s);
 int forward_stack_load();
 // parts 4 .. 11: the BH hash kernel.  Plain: d_pad = 64 .. 256, 512, 1024; weighted: d_pad = 64 .. 256, then
 // 512 and 1024 each split by the way the rows are read (four coordinates at a time or one by one): the
@@ -87,28 +87,28 @@ thread_local int t_attr_only = 0;
 #endif
 
 // ---------------------------------------------------------------- kernel launchers (templates: every part may use them)
-template <bool BF16, int LPT>
+template <int KIND, int LPT>
 void launch_gather_t(const GatherArgs &a, bool probes, dim3 grid, hipStream_t s)
 {
     if (probes)
-        hipLaunchKernelGGL((gather_kernel<BF16, LPT, 2>), grid, dim3(kGatherThreads), 0, s, a);
+        hipLaunchKernelGGL((gather_kernel<KIND, LPT, 2>), grid, dim3(kGatherThreads), 0, s, a);
     else if (a.weights)
-        hipLaunchKernelGGL((gather_kernel<BF16, LPT, 1>), grid, dim3(kGatherThreads), 0, s, a);
+        hipLaunchKernelGGL((gather_kernel<KIND, LPT, 1>), grid, dim3(kGatherThreads), 0, s, a);
     else
-        hipLaunchKernelGGL((gather_kernel<BF16, LPT, 0>), grid, dim3(kGatherThreads), 0, s, a);
+        hipLaunchKernelGGL((gather_kernel<KIND, LPT, 0>), grid, dim3(kGatherThreads), 0, s, a);
 }
 
-template <bool BF16>
+template <int KIND>
 int launch_gather_lpt(int lpt, const GatherArgs &a, bool probes, dim3 grid, hipStream_t s)
 {
     switch (lpt) {
-        case 1: launch_gather_t<BF16, 1>(a, probes, grid, s); break;
-        case 2: launch_gather_t<BF16, 2>(a, probes, grid, s); break;
-        case 4: launch_gather_t<BF16, 4>(a, probes, grid, s); break;
-        case 8: launch_gather_t<BF16, 8>(a, probes, grid, s); break;
-        case 16: launch_gather_t<BF16, 16>(a, probes, grid, s); break;
-        case 32: launch_gather_t<BF16, 32>(a, probes, grid, s); break;
-        case 64: launch_gather_t<BF16, 64>(a, probes, grid, s); break;
+        case 1: launch_gather_t<KIND, 1>(a, probes, grid, s); break;
+        case 2: launch_gather_t<KIND, 2>(a, probes, grid, s); break;
+        case 4: launch_gather_t<KIND, 4>(a, probes, grid, s); break;
+        case 8: launch_gather_t<KIND, 8>(a, probes, grid, s); break;
+        case 16: launch_gather_t<KIND, 16>(a, probes, grid, s); break;
+        case 32: launch_gather_t<KIND, 32>(a, probes, grid, s); break;
+        case 64: launch_gather_t<KIND, 64>(a, probes, grid, s); break;
         default: return LFFN_E_UNSUPPORTED;
     }
     return LFFN_OK;
@@ -192,15 +192,20 @@ int launch_bh_w(const BhArgs &a, int block, dim3 grid, size_t lds, hipStream_t s
 namespace lffn_host {
 
 #if LFFN_HAS(1)
-int gather_direct_part(bool bf16, int lpt, const GatherArgs &a, bool probes, dim3 grid, hipStream_t s)
+int gather_direct_part(int kind, int lpt, const GatherArgs &a, bool probes, dim3 grid, hipStream_t s)
 {
-    return bf16 ? launch_gather_lpt<true>(lpt, a, probes, grid, s) : launch_gather_lpt<false>(lpt, a, probes, grid, s);
+    switch (kind) {
+        case kElemF32: return launch_gather_lpt<kElemF32>(lpt, a, probes, grid, s);
+        case kElemBF16: return launch_gather_lpt<kElemBF16>(lpt, a, probes, grid, s);
+        case kElemF16: return launch_gather_lpt<kElemF16>(lpt, a, probes, grid, s);
+    }
+    return LFFN_E_DTYPE;
 }
 
 int gather_direct_load()
 {
     hipFuncAttributes attr;
-    hipError_t e = hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(gather_kernel<false, 8, 0>));
+    hipError_t e = hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(gather_kernel<kElemF32, 8, 0>));
     return e == hipSuccess ? LFFN_OK : hip_fail(e, "hipFuncGetAttributes(gather_kernel)");
 }
 #endif
@@ -275,23 +280,25 @@ int gather_ring_part(int threads, int tok, const GatherRingArgs &a, dim3 grid, h
 
 #if LFFN_HAS(13)
 template <int R>
-int launch_forward_stack_r(bool bf16, const StackArgs &a, dim3 grid, int threads, size_t lds, hipStream_t s)
+int launch_forward_stack_r(int kind, const StackArgs &a, dim3 grid, int threads, size_t lds, hipStream_t s)
 {
-    if (bf16)
-        hipLaunchKernelGGL((forward_stack_kernel<R, true>), grid, dim3(threads), lds, s, a);
-    else
-        hipLaunchKernelGGL((forward_stack_kernel<R, false>), grid, dim3(threads), lds, s, a);
+    switch (kind) {
+        case kElemF32: hipLaunchKernelGGL((forward_stack_kernel<R, kElemF32>), grid, dim3(threads), lds, s, a); break;
+        case kElemBF16: hipLaunchKernelGGL((forward_stack_kernel<R, kElemBF16>), grid, dim3(threads), lds, s, a); break;
+        case kElemF16: hipLaunchKernelGGL((forward_stack_kernel<R, kElemF16>), grid, dim3(threads), lds, s, a); break;
+        default: return LFFN_E_DTYPE;
+    }
     return LFFN_OK;
 }
 
-int forward_stack_part(int n_rounds, bool bf16, const StackArgs &a, dim3 grid, int threads, size_t lds, hipStream_t s)
+int forward_stack_part(int n_rounds, int kind, const StackArgs &a, dim3 grid, int threads, size_t lds, hipStream_t s)
 {
     if (threads < 64 || threads > 1024 || threads % 64) return LFFN_E_UNSUPPORTED;
     switch (n_rounds) {
-        case 1: return launch_forward_stack_r<1>(bf16, a, grid, threads, lds, s);
-        case 2: return launch_forward_stack_r<2>(bf16, a, grid, threads, lds, s);
-        case 3: return launch_forward_stack_r<3>(bf16, a, grid, threads, lds, s);
-        case 4: return launch_forward_stack_r<4>(bf16, a, grid, threads, lds, s);
+        case 1: return launch_forward_stack_r<1>(kind, a, grid, threads, lds, s);
+        case 2: return launch_forward_stack_r<2>(kind, a, grid, threads, lds, s);
+        case 3: return launch_forward_stack_r<3>(kind, a, grid, threads, lds, s);
+        case 4: return launch_forward_stack_r<4>(kind, a, grid, threads, lds, s);
     }
     return LFFN_E_UNSUPPORTED;
 }
@@ -299,7 +306,7 @@ int forward_stack_part(int n_rounds, bool bf16, const StackArgs &a, dim3 grid, i
 int forward_stack_load()
 {
     hipFuncAttributes attr;
-    hipError_t e = hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(forward_stack_kernel<3, false>));
+    hipError_t e = hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(forward_stack_kernel<3, kElemF32>));
     return e == hipSuccess ? LFFN_OK : hip_fail(e, "hipFuncGetAttributes(forward_stack_kernel)");
 }
 #endif
@@ -410,7 +417,8 @@ int log2_pad(int d)
     return l;
 }
 
-bool dtype_ok(int t) { return t == LFFN_F32 || t == LFFN_BF16; }
+bool dtype_ok(int t) { return t == LFFN_F32 || t == LFFN_BF16 || t == LFFN_F16; }
+static_assert(LFFN_F32 == kElemF32 && LFFN_BF16 == kElemBF16 && LFFN_F16 == kElemF16, "the ABI's dtype codes are the kernels' element kinds");
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 int gcd(int a, int b) { return b ? gcd(b, a % b) : a; }
 int64_t round256(int64_t b) { return (b + 255) & ~int64_t(255); }
@@ -431,7 +439,7 @@ struct Options {
     int small_tokens = 0;     // 0 = default, -1 = never: up to this many tokens lookupffn_forward runs as one
                               // hash-and-gather launch (when the shape is that kernel's)
 };
-constexpr int kSmallTokensDefault = 64;
+constexpr int kSmallTokensDefault = 512;  // k = 96, d_out = 768: 23 us against 33 us at 512 tokens, even at about 900
 std::mutex g_opt_mu;
 Options g_opt;
 Options options_snapshot()
@@ -577,7 +585,7 @@ int prepared_piece_bytes(int tau) { return tau <= 8 ? 128 : 64; }
 
 struct TableRef {
     const char *p = nullptr;
-    bool bf16 = false;      // element type of the buffer the kernels read (prepared tables are always fp32)
+    int kind = kElemF32;    // element type of the buffer the kernels read (prepared tables are always fp32)
     bool prepared = false;
     int pw = 0;             // prepared: bytes per row piece
 };
@@ -587,7 +595,7 @@ TableRef table_ref(const void *tables, int table_dtype, int tau)
     TableRef t;
     t.p = static_cast<const char *>(tables);
     t.prepared = (table_dtype & LFFN_PREPARED) != 0;
-    t.bf16 = !t.prepared && (table_dtype & 0xFF) == LFFN_BF16;
+    t.kind = t.prepared ? kElemF32 : (table_dtype & 0xFF);  // LFFN_F32 / BF16 / F16 are the kernels' kinds 0 / 1 / 2
     t.pw = t.prepared ? prepared_piece_bytes(tau) : 0;
     return t;
 }
@@ -711,18 +719,18 @@ int launch_hash(const void *x, const int8_t *signs, const HashOut &out, int64_t 
     a.tau = tau;
     a.n_rounds = n_rounds;
     a.P = (int)(((int64_t)k * tau + N - 1) / N);
-    a.x_bf16 = x_dtype == LFFN_BF16;
+    a.x_kind = x_dtype;  // LFFN_F32 / BF16 / F16 are the kernels' kinds 0 / 1 / 2
     a.scale = (float)(1.0 / std::sqrt((double)N));
     if (!a.codes && !a.packed) return LFFN_E_NULL;
     if (out.probes && (!a.codes || !a.weights)) return LFFN_E_UNSUPPORTED;  // shares exist in the ABI layout only
     TimedLaunch tl(0, s);
     // d_pad = 1024 with up to four rounds: the two-layout kernel (needs 16-byte aligned signs, and
     // rows that start on 16-byte boundaries when it loads them as vectors)
-    const size_t xrow = (size_t)d * (a.x_bf16 ? 2 : 4);
+    const size_t xrow = (size_t)d * (a.x_kind ? 2 : 4);
     const bool weighted = out.weights != nullptr;
     if (opt.hash_path != 1 && L == 10 && n_rounds <= 4 && aligned(signs, 16) &&
         h1024_lds_bytes(a.P, weighted) <= 64 * 1024 &&
-        (d % 4 != 0 || (aligned(x, 16) && xrow % (a.x_bf16 ? 8 : 16) == 0))) {
+        (d % 4 != 0 || (aligned(x, 16) && xrow % (a.x_kind ? 8 : 16) == 0))) {
         int64_t blocks = (n + kHashWaves - 1) / kHashWaves;
         const int64_t cap = opt.hash_blocks ? opt.hash_blocks : 4096;
         if (blocks > cap) blocks = cap;
@@ -803,7 +811,7 @@ int plan_gather_lds(int64_t n, int k, int tau, int d_out, const TableRef &T, Mod
 {
     p->use = false;
     if (opt.gather_path == 1) return LFFN_OK;
-    if (T.bf16) return LFFN_OK;  // the staged kernel reads fp32 rows: bf16 tables take it once prepared
+    if (T.kind) return LFFN_OK;  // the staged kernel reads fp32 rows: 16-bit tables take it once prepared
     const int rows = 1 << tau;
     if (tau < 7 || tau > 10 || k % 2 != 0) return LFFN_OK;
     // column slices: 128 bytes (8 lanes per token) up to tau = 8; 64 bytes from tau = 9 on (two 512-row
@@ -913,7 +921,7 @@ int launch_gather_lds(const LdsPlan &p, const uint32_t *packed, const float *wpk
     a.y = y;
     // extents the kernel assumes: rows * copy rounds cover a table exactly, the stage fits its buffer,
     // token windows of 16 x 256 tokens past any token stay inside the padded code arrays
-    if ((kLdsThreads / p.sw) * p.fr != (1 << a.tau) || a.n_pad < a.n + 16 * 256 || (a.k & 1) || T.bf16 ||
+    if ((kLdsThreads / p.sw) * p.fr != (1 << a.tau) || a.n_pad < a.n + 16 * 256 || (a.k & 1) || T.kind ||
         (mode != kPlain) != (wpk != nullptr) || !packed)
         return LFFN_E_UNSUPPORTED;
     const dim3 grid(p.grid);
@@ -935,7 +943,7 @@ int launch_gather_lds(const LdsPlan &p, const uint32_t *packed, const float *wpk
 int launch_gather_direct(const uint16_t *codes, const float *weights, const TableRef &T, float *y, int64_t n,
                          int k, int tau, int d_out, Mode mode, hipStream_t s, const Options &opt)
 {
-    const int esz = T.bf16 ? 2 : 4;
+    const int esz = T.kind ? 2 : 4;
     GatherArgs a{};
     a.codes = codes;
     a.weights = weights;
@@ -991,7 +999,7 @@ int launch_gather_direct(const uint16_t *codes, const float *weights, const Tabl
     if (blocks > 0x7FFFFFFFLL) return LFFN_E_SIZE;
     const dim3 grid((unsigned)blocks);
     TimedLaunch tl(1, s);
-    int rc = lffn_host::gather_direct_part(T.bf16, lpt, a, mode == kProbes, grid, s);
+    int rc = lffn_host::gather_direct_part(T.kind, lpt, a, mode == kProbes, grid, s);
     if (rc != LFFN_OK) return rc;
     LFFN_HIP(hipGetLastError());
     tl.done();
@@ -1214,8 +1222,8 @@ int launch_hash_bh(const void *x, const float *pack_from, const float *apack_in,
     a.tau = tau;
     a.n_factors = n_factors;
     a.P = (int)(((int64_t)k * tau + N - 1) / N);
-    a.x_bf16 = x_dtype == LFFN_BF16;
-    a.x_vec4 = d % 4 == 0 && aligned(x, a.x_bf16 ? 8 : 16);
+    a.x_kind = x_dtype;  // LFFN_F32 / BF16 / F16 are the kernels' kinds 0 / 1 / 2
+    a.x_vec4 = d % 4 == 0 && aligned(x, a.x_kind ? 8 : 16);
     a.scale = (float)(1.0 / std::sqrt((double)N));
     if (!a.apack || (!a.codes && !a.packed) || out.probes) return LFFN_E_NULL;
     TimedLaunch tl(0, s);
@@ -1256,7 +1264,7 @@ bool stack_shape_ok(const void *x, const int8_t *const *signs, const void *const
     if (log2_pad(d) != 10 || n_rounds > 4 || n_layers < 1 || n_layers > kStackMaxLayers) return false;
     if (n_layers > 1 && d_out != d) return false;
     if (n > 0x7FFFFFFF) return false;
-    const bool xb = x_dtype == LFFN_BF16;
+    const bool xb = x_dtype != LFFN_F32;
     const size_t xrow = (size_t)d * (xb ? 2 : 4);
     if (d % 4 == 0 && !(aligned(x, 16) && xrow % (xb ? 8 : 16) == 0)) return false;
     for (int l = 0; l < n_layers; ++l)
@@ -1265,7 +1273,7 @@ bool stack_shape_ok(const void *x, const int8_t *const *signs, const void *const
     if (stack_lds_bytes(P, k) > 64 * 1024) return false;
     const TableRef T = table_ref(tables[0], table_dtype, tau);
     const int64_t bytes = T.prepared ? prepared_tables_bytes(k, tau, d_out)
-                                     : ((int64_t)k << tau) * d_out * (T.bf16 ? 2 : 4);
+                                     : ((int64_t)k << tau) * d_out * (T.kind ? 2 : 4);
     return bytes < (int64_t(1) << 31);
 }
 
@@ -1289,7 +1297,7 @@ int launch_forward_stack(const void *x, const int8_t *const *signs, const void *
     a.tau = tau;
     a.P = (int)(((int64_t)k * tau + 1023) / 1024);
     a.n_layers = n_layers;
-    a.x_bf16 = x_dtype == LFFN_BF16;
+    a.x_kind = x_dtype;  // LFFN_F32 / BF16 / F16 are the kernels' kinds 0 / 1 / 2
     a.scale = (float)(1.0 / std::sqrt(1024.0));
     const int64_t rows = int64_t(1) << tau;
     if (T.prepared) {
@@ -1299,7 +1307,7 @@ int launch_forward_stack(const void *x, const int8_t *const *signs, const void *
         a.slice_stride = (uint32_t)((int64_t)k * rows * T.pw);
         a.table_bytes = (uint32_t)prepared_tables_bytes(k, tau, d_out);
     } else {
-        const int64_t row_bytes = (int64_t)d_out * (T.bf16 ? 2 : 4);
+        const int64_t row_bytes = (int64_t)d_out * (T.kind ? 2 : 4);
         a.row_dwords = (uint32_t)(row_bytes / 4);
         a.piece_shift = 31;
         a.row_stride = (uint32_t)row_bytes;
@@ -1309,7 +1317,7 @@ int launch_forward_stack(const void *x, const int8_t *const *signs, const void *
     int threads = (int)((a.row_dwords + 63) / 64 * 64);
     if (threads > 1024) threads = 1024;
     TimedLaunch tl(1, s);
-    int rc = lffn_host::forward_stack_part(n_rounds, T.bf16, a, dim3((unsigned)n), threads, stack_lds_bytes(a.P, k), s);
+    int rc = lffn_host::forward_stack_part(n_rounds, T.kind, a, dim3((unsigned)n), threads, stack_lds_bytes(a.P, k), s);
     if (rc != LFFN_OK) return rc;
     LFFN_HIP(hipGetLastError());
     tl.done();
@@ -1770,7 +1778,7 @@ int lookupffn_prepare_tables(const void *tables, int k, int tau, int d_out, int 
     long long blocks = (n_out + 255) / 256;
     if (blocks > 16384) blocks = 16384;
     hipLaunchKernelGGL(prepare_tables_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
-                       tables, static_cast<uint4 *>(prepared), k, rows, nvec, ppw, table_dtype == LFFN_BF16 ? 1 : 0, n_out);
+                       tables, static_cast<uint4 *>(prepared), k, rows, nvec, ppw, table_dtype, n_out);
     LFFN_HIP(hipGetLastError());
     return LFFN_OK;
 }

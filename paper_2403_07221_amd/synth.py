@@ -34,8 +34,8 @@ class Workload:
     k: int
     tau: int
     d_out: int
-    x_dtype: str = "f32"       # "f32" | "bf16"
-    table_dtype: str = "f32"   # "f32" | "bf16"
+    x_dtype: str = "f32"       # "f32" | "bf16" | "f16"
+    table_dtype: str = "f32"   # "f32" | "bf16" | "f16"
     n_layers: int = 1
     seed_index: int | None = None  # reuse another configuration's signs/tables seeds
 
@@ -112,14 +112,14 @@ def make_bmats(seed: int, n_proj: int, n_factors: int, d_pad: int, block: int) -
 
 def make_x(seed: int, n: int, d: int, dtype: str = "f32") -> np.ndarray:
     x = _rng(seed).standard_normal((n, d), dtype=np.float32)
-    return to_bf16_bits(x) if dtype == "bf16" else x
+    return to_bf16_bits(x) if dtype == "bf16" else x.astype(np.float16) if dtype == "f16" else x
 
 
 def make_tables(seed: int, k: int, rows: int, d_out: int, dtype: str = "f32",
                 sigma: float = 0.02) -> np.ndarray:
     t = _rng(seed).standard_normal((k, rows, d_out), dtype=np.float32)
     t *= np.float32(sigma)
-    return to_bf16_bits(t) if dtype == "bf16" else t
+    return to_bf16_bits(t) if dtype == "bf16" else t.astype(np.float16) if dtype == "f16" else t
 
 
 def make_zipf_codes(seed: int, n: int, k: int, tau: int, s: float = 1.0) -> np.ndarray:

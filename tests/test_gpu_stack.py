@@ -119,11 +119,11 @@ def test_forward_stack_equals_the_layer_loop(prepared):
 
 def test_forward_takes_the_single_launch_up_to_its_token_limit():
     w = synth.C2
-    x, signs, tables = synth.make_layer(w, n_tokens=200)
+    x, signs, tables = synth.make_layer(w, n_tokens=600)
     sd, td = B.to_device(signs), B.to_device(tables)
     want = oracle.forward(x, signs, tables, acc64=False)
     try:
-        for n, limit, single in ((64, 0, True), (65, 0, False), (200, 200, True), (3, -1, False),
+        for n, limit, single in ((512, 0, True), (513, 0, False), (600, 600, True), (3, -1, False),
                                  (3, 2, False), (2, 2, True)):
             print(f"forward n={n} small_tokens={limit}", flush=True)
             B.lookupffn_set_option("small_tokens", limit)

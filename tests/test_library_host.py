@@ -60,7 +60,7 @@ def test_hash_argument_errors(L):
     assert hash_call(L, n=-1) == -2 and hash_call(L, d=0) == -2 and hash_call(L, k=0) == -2
     assert hash_call(L, rounds=0) == -2
     assert hash_call(L, tau=0) == -3 and hash_call(L, tau=17) == -3
-    assert hash_call(L, dt=2) == -4
+    assert hash_call(L, dt=2) == 0 and hash_call(L, dt=3) == -4                # 2 = IEEE half
     assert hash_call(L, x=FAKE + 2) == -5 and hash_call(L, x=FAKE + 2, dt=1) == 0
     assert hash_call(L, codes=FAKE + 1) == -5
     assert hash_call(L, d=4097) == -6 and hash_call(L, d=4096, k=512) == 0
@@ -75,7 +75,7 @@ def test_gather_argument_errors(L):
     assert gather_call(L, d_out=772) == 0 and gather_call(L, d_out=772, dt=1) == -5
     assert gather_call(L, tables=FAKE + 4) == -5 and gather_call(L, y=FAKE + 8) == -5
     # prepared tables: the flag with either source dtype; the buffer is 256-byte aligned
-    assert gather_call(L, dt=0x100) == 0 and gather_call(L, dt=0x101) == 0 and gather_call(L, dt=0x102) == -4
+    assert gather_call(L, dt=0x100) == 0 and gather_call(L, dt=0x101) == 0 and gather_call(L, dt=0x102) == 0 and gather_call(L, dt=0x103) == -4
     assert gather_call(L, dt=0x200) == -4 and gather_call(L, tables=FAKE + 16, dt=0x100) == -5
     assert gather_call(L, d_out=772, dt=0x101) == -5          # the source rows were bf16: whole 16-byte pieces of those
     # scratch of the stand-alone gather: too small or misaligned is refused before any launch
@@ -164,10 +164,10 @@ def test_prepare_tables_sizes_and_argument_errors(L):
     assert L.lookupffn_prepared_tables_bytes(2, 7, 8, 0) == 2 * 128 * 128                # 32-byte rows padded to a piece
     assert L.lookupffn_prepared_tables_bytes(6, 9, 200, 0) == 6 * 512 * 13 * 64          # 800-byte rows: 13 pieces of 64
     assert L.lookupffn_prepared_tables_bytes(3, 10, 72, 1) % 256 == 0
-    for bad in ((0, 8, 768, 0), (96, 17, 768, 0), (96, 0, 768, 0), (96, 8, 770, 0), (96, 8, 772, 1), (96, 8, 768, 2)):
+    for bad in ((0, 8, 768, 0), (96, 17, 768, 0), (96, 0, 768, 0), (96, 8, 770, 0), (96, 8, 772, 1), (96, 8, 772, 2), (96, 8, 768, 3)):
         assert L.lookupffn_prepared_tables_bytes(*bad) == 0
     assert prep(tables=None) == -1 and prep(out=None) == -1
-    assert prep(k=0) == -2 and prep(tau=0) == -3 and prep(tau=17) == -3 and prep(dt=2) == -4 and prep(dt=0x100) == -4
+    assert prep(k=0) == -2 and prep(tau=0) == -3 and prep(tau=17) == -3 and prep(dt=3) == -4 and prep(dt=0x100) == -4
     assert prep(d_out=770) == -5 and prep(d_out=772, dt=1) == -5
     assert prep(tables=FAKE + 8) == -5 and prep(out=FAKE + 16) == -5
     assert prep(nbytes=96 * 256 * 768 * 4 - 1) == -7

@@ -11,6 +11,7 @@ import pytest
 ROOT = Path(__file__).resolve().parent.parent
 SAN = ROOT / "tests" / "sanitize"
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+CLANG = "/opt/rocm/lib/llvm/bin/clang"      # the host compiler hipcc drives: links the host-only objects
 ENV = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="halt_on_error=1:print_stacktrace=1")
 
 
@@ -29,7 +30,7 @@ def test_oracle_under_asan_and_ubsan(tmp_path):
     assert "oracle ran clean" in out and "runtime error" not in out and "AddressSanitizer" not in out
 
 
-@pytest.mark.skipif(not shutil.which(HIPCC), reason="hipcc not found")
+@pytest.mark.skipif(not (shutil.which(HIPCC) and shutil.which(CLANG)), reason="hipcc / clang not found")
 def test_library_host_code_under_asan_and_ubsan(tmp_path):
     """Host pass only (--cuda-host-only: the kernels get their launch stubs, no device code is generated);
     the sanitizer flags go to the host compiler.  The host object refers to the device-code bundle that a
@@ -49,11 +50,11 @@ def test_library_host_code_under_asan_and_ubsan(tmp_path):
         f"const unsigned char {undefined[0]}[4096] __attribute__((section(\".hip_fatbin\"), aligned(4096))) =\n"
         "    \"__CLANG_OFFLOAD_BUNDLE__\";\n")
     lib = tmp_path / "liblookupffn_san.so"
-    run([HIPCC, "-shared", "-fPIC", "-fsanitize=address", "-fsanitize=undefined", "-o", str(lib), str(obj),
-         "-x", "c", str(stub)], timeout=300)
+    host_san = ["-fsanitize=address,undefined", "-fno-sanitize-recover=undefined"]
+    run([CLANG + "++", "-shared", "-fPIC", *host_san, "-o", str(lib), str(obj), "-x", "c", str(stub),
+         "-L/opt/rocm/lib", "-lamdhip64", "-Wl,-rpath,/opt/rocm/lib"], timeout=300)
     exe = tmp_path / "host_san"
-    run([HIPCC, "-O1", "-g", "-x", "c", "-fsanitize=address", "-fsanitize=undefined", "-fno-sanitize-recover=undefined",
-         *inc, "-o", str(exe), str(SAN / "host_driver.c"), "-x", "none", str(lib), "-Wl,-rpath," + str(tmp_path)],
-        timeout=300)
+    run([CLANG, "-O1", "-g", *host_san, *inc, "-o", str(exe), str(SAN / "host_driver.c"), str(lib),
+         "-Wl,-rpath," + str(tmp_path)], timeout=300)
     out = run([str(exe)], env=ENV, timeout=300)
     assert "host code ran clean" in out and "runtime error" not in out and "AddressSanitizer" not in out
