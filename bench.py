@@ -64,6 +64,9 @@ def parse_args():
                     help="pass the row-major tables / BH factors instead of their one-time prepared copies")
     ap.add_argument("--layer-loop", action="store_true",
                     help="config 5: time the loop of per-layer lookupffn_forward calls instead of the single launch")
+    ap.add_argument("--latency-passes", choices=["both", "warm", "cold"], default="both",
+                    help="config 5: which passes the latency report times (one kind only: for counter runs, so that "
+                         "every dispatch after the timed steps is of that kind)")
     ap.add_argument("--parity-tokens", type=int, default=1024,
                     help="tokens of the timed y compared with the oracle after the timed region (0 = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -204,12 +207,17 @@ def latency_report(w, args, xd, loop_step, stack_step, y_last):
     runs["single_launch_graph"] = graph1.replay
     rep = {"layers": w.n_layers, "unit": "us", "cold_means": "another batch of 16 and a 1 GiB overwrite before each timed pass"}
     for name, fn in runs.items():
-        for _ in range(3):
-            fn()
+        if args.latency_passes != "cold":     # (a cold-only run warms nothing up)
+            for _ in range(3):
+                fn()
         torch.cuda.synchronize()
-        warm, cold = timed(fn, False, 21), timed(fn, True, 16)
-        rep[name] = {"warm_per_pass": warm, "warm_per_layer": warm / w.n_layers,
-                     "cold_per_pass": cold, "cold_per_layer": cold / w.n_layers}
+        rep[name] = {}
+        if args.latency_passes != "cold":
+            warm = timed(fn, False, 21)
+            rep[name].update({"warm_per_pass": warm, "warm_per_layer": warm / w.n_layers})
+        if args.latency_passes != "warm":
+            cold = timed(fn, True, 16)
+            rep[name].update({"cold_per_pass": cold, "cold_per_layer": cold / w.n_layers})
     xd.copy_(saved)
     return rep
 
