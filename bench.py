@@ -62,6 +62,8 @@ def parse_args():
                          "never instead of, the hashed codes of the rotated Gaussian input)")
     ap.add_argument("--no-prepare", action="store_true",
                     help="pass the row-major tables / BH factors instead of their one-time prepared copies")
+    ap.add_argument("--y-dtype", choices=["f32", "bf16", "f16"], default="f32",
+                    help="storage type of y (the sums are fp32 either way; 16-bit y is rounded once when stored)")
     ap.add_argument("--layer-loop", action="store_true",
                     help="config 5: time the loop of per-layer lookupffn_forward calls instead of the single launch")
     ap.add_argument("--latency-passes", choices=["both", "warm", "cold"], default="both",
@@ -131,7 +133,8 @@ def parity_check(w, x, signs, tables, y_dev, n_check: int, weighted: bool, bh: b
     n = x.shape[0]
     step = max(1, n // max(n_check, 1)) | 1
     idx = np.unique(np.concatenate([np.arange(0, n, step), np.arange(0, min(64, n)), np.arange(max(0, n - 64), n)]))
-    got = y_dev[idx].cpu().numpy() if hasattr(y_dev, "cpu") else y_dev[idx]
+    y16 = hasattr(y_dev, "dtype") and str(y_dev.dtype) in ("torch.bfloat16", "torch.float16")
+    got = y_dev[idx].float().cpu().numpy() if hasattr(y_dev, "cpu") else y_dev[idx]
     xs = x[idx]
     if bh:
         ref = (oracle.bh_forward_weighted if weighted else oracle.bh_forward)(xs, signs, tables)
@@ -145,9 +148,19 @@ def parity_check(w, x, signs, tables, y_dev, n_check: int, weighted: bool, bh: b
     err = float(np.max(np.abs(got.astype(np.float64) - r)) / np.sqrt(np.mean(r ** 2)))
     tol = 1e-2 if w.table_dtype == "bf16" else 1e-4
     out = {"tokens": int(len(idx)), "max_abs_err_over_rms": err, "tolerance": tol, "ok": bool(err <= tol)}
+    if y16:
+        # y stored in 16 bits: the tolerance plus one rounding to y's type per element (twice half an ulp allowed)
+        rel = 2.0 ** -8 if "bfloat16" in str(y_dev.dtype) else 2.0 ** -11
+        out["ok"] = bool(np.all(np.abs(got.astype(np.float64) - r) <= rel * np.abs(r) + tol * np.sqrt(np.mean(r ** 2))))
+        out["tolerance"] = f"{tol} of rms + {rel} relative per element (16-bit y)"
     if not (weighted or probes):
         seq = (oracle.bh_forward if bh else oracle.forward)(xs, signs, tables, acc64=False)
-        out["bit_equal_to_fp32_sequential_sum"] = bool(np.array_equal(got, seq))
+        if y16:
+            narrow = oracle.float_to_bf16 if "bfloat16" in str(y_dev.dtype) else oracle.float_to_half
+            bits = y_dev[idx].view(__import__("torch").int16).cpu().numpy().view(np.uint16)
+            out["bit_equal_to_rounded_fp32_sequential_sum"] = bool(np.array_equal(bits, narrow(seq)))
+        else:
+            out["bit_equal_to_fp32_sequential_sum"] = bool(np.array_equal(got, seq))
     return out
 
 
@@ -263,6 +276,11 @@ def main():
                else B.lookupffn_forward_probes if args.probes
                else B.lookupffn_forward_weighted if args.weighted else B.lookupffn_forward)
 
+    y_torch = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[args.y_dtype]
+    if args.y_dtype != "f32" and w.n_layers > 1 and args.layer_loop:
+        print("--layer-loop hands y from layer to layer in fp32: use --y-dtype f32 with it", file=sys.stderr)
+        sys.exit(2)
+
     def prepared(td):
         return td if args.no_prepare else B.lookupffn_prepare_tables(td)
 
@@ -276,7 +294,7 @@ def main():
         td = prepared(td_rows)
         if bh and not args.no_prepare:
             sd = B.lookupffn_prepare_bh(sd, w.d, w.k, w.tau)
-        y = torch.empty((w.n_tokens, w.d_out), dtype=torch.float32, device="cuda")
+        y = torch.empty((w.n_tokens, w.d_out), dtype=y_torch, device="cuda")
 
         def step():
             forward(xd, sd, td, y=y, workspace=ws)
@@ -288,7 +306,7 @@ def main():
         dev = [(B.to_device(s_), prepared(B.to_device(t_))) for _, s_, t_ in layers]
         ys = [torch.empty((w.n_tokens, w.d_out), dtype=torch.float32, device="cuda") for _ in range(2)]
 
-        y_last = torch.empty((w.n_tokens, w.d_out), dtype=torch.float32, device="cuda")
+        y_last = torch.empty((w.n_tokens, w.d_out), dtype=y_torch, device="cuda")
 
         def loop_step():
             h = xd
@@ -336,11 +354,12 @@ def main():
 
     xb = 2 if w.x_dtype == "bf16" else 4
     tb = 2 if w.table_dtype == "bf16" else 4
+    yb = 4 if args.y_dtype == "f32" else 2
     path_bytes = cost.bytes_per_token(w.d, w.k, w.d_out, xb, tb) * w.n_tokens * w.n_layers
     n_probe = (w.tau + 1) if args.probes else 1
     side_floats = w.k * n_probe if (args.weighted or args.probes) else 0      # weights / shares per token
     # the gather kernel alone: k table rows (x probes) + the y row + the k uint16 codes (+ weights) it reads, per token
-    gather_bytes = (w.k * n_probe * w.d_out * tb + w.d_out * 4 + w.k * 2 + side_floats * 4) * w.n_tokens
+    gather_bytes = (w.k * n_probe * w.d_out * tb + w.d_out * yb + w.k * 2 + side_floats * 4) * w.n_tokens
     path_bytes += (w.k * (n_probe - 1) * w.d_out * tb + 2 * side_floats * 4) * w.n_tokens * w.n_layers
     gather_avg_ms = gather_ms / gather_n
     staged = kernel in ("gather_lds_kernel", "gather_ring_kernel")
@@ -348,11 +367,11 @@ def main():
     # copy is fp32), codes (+ weights) once, y once
     read_tb = 4 if (staged or not args.no_prepare) else tb
     table_bytes_read = w.k * w.rows * w.d_out * read_tb
-    compulsory = table_bytes_read + (w.k * 2 + side_floats * 4 + w.d_out * 4) * w.n_tokens
+    compulsory = table_bytes_read + (w.k * 2 + side_floats * 4 + w.d_out * yb) * w.n_tokens
     if w.n_tokens * w.k < w.k * w.rows:          # fewer lookups than rows: only the rows touched
-        compulsory = (w.k * n_probe * w.d_out * read_tb + w.k * 2 + side_floats * 4 + w.d_out * 4) * w.n_tokens
+        compulsory = (w.k * n_probe * w.d_out * read_tb + w.k * 2 + side_floats * 4 + w.d_out * yb) * w.n_tokens
     if fused:                                    # one launch: x, the sign diagonals and the rows touched, per layer
-        compulsory = ((w.k * w.d_out * read_tb + w.d * xb + w.d_out * 4) * w.n_tokens
+        compulsory = ((w.k * w.d_out * read_tb + w.d * xb + w.d_out * yb) * w.n_tokens
                       + w.n_proj * w.n_rounds * w.d_pad) * launches_per_step_layers(w, args)
     each = sorted(gather_each)
     times = {"avg_kernel_ms": gather_avg_ms, "min_kernel_ms": each[0] if each else None,
@@ -394,7 +413,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "n_tokens": w.n_tokens, "d": w.d, "d_pad": w.d_pad,
                    "hash_rounds": w.n_rounds, "k_tables": w.k, "tau": w.tau, "d_out": w.d_out,
-                   "x_dtype": w.x_dtype, "table_dtype": w.table_dtype,
+                   "x_dtype": w.x_dtype, "table_dtype": w.table_dtype, "y_dtype": args.y_dtype,
                    "table_bytes": w.k * w.rows * w.d_out * tb,
                    "tables_prepared_once": not args.no_prepare,
                    "variant": "weighted" if args.weighted else "multi-probe" if args.probes else "plain-sum",
@@ -475,10 +494,15 @@ def main():
             import oracle
             step()
             torch.cuda.synchronize()
-            got = (y_last if not args.layer_loop else ys[(w.n_layers - 1) & 1]).cpu().numpy()
+            y_end = y_last if not args.layer_loop else ys[(w.n_layers - 1) & 1]
             h = x
             for _, s_, t_ in layers:
                 h = oracle.forward(h, s_, t_, acc64=False)
+            if args.y_dtype == "f32":
+                got = y_end.cpu().numpy()
+            else:   # the last layer's output rounded once
+                got = y_end.view(torch.int16).cpu().numpy().view(np.uint16)
+                h = (oracle.float_to_bf16 if args.y_dtype == "bf16" else oracle.float_to_half)(h)
             pc["chain_layers"] = w.n_layers
             pc["chain_bits_equal"] = bool(np.array_equal(got, h))
             pc["ok"] = bool(pc["ok"] and pc["chain_bits_equal"])

@@ -67,6 +67,12 @@ typedef enum { LFFN_F32 = 0, LFFN_BF16 = 1, LFFN_F16 = 2 /* IEEE binary16 */ } l
  * tables of the dtype in the low bits).  OR-ed into a `block` argument of the BH entry points: `bmats`
  * is the buffer lookupffn_prepare_bh() wrote. */
 #define LFFN_PREPARED 0x100
+/* OR-ed into a `table_dtype` argument of a gather / forward entry point: y is stored as bf16 / IEEE half
+ * instead of fp32 (the fp32 sums rounded once, to nearest even, when they are stored; y then 8-byte aligned).
+ * At most one of the two.  lookupffn_forward_stack rounds only the last layer's output: the values handed from
+ * layer to layer stay fp32. */
+#define LFFN_Y_BF16 0x200
+#define LFFN_Y_F16 0x400
 
 typedef enum {
     LFFN_OK = 0,
@@ -104,7 +110,7 @@ int lookupffn_hash(const void *x, const int8_t *signs, uint16_t *codes,
  * value of `codes` can make the kernel read outside `tables`.  Scratch:
  * lookupffn_workspace_bytes_gather(n_tokens, k) bytes (the LDS-staged kernel reads the codes re-packed).
  */
-int lookupffn_gather(const uint16_t *codes, const void *tables, float *y,
+int lookupffn_gather(const uint16_t *codes, const void *tables, void *y,
                      int64_t n_tokens, int k, int tau, int d_out,
                      int table_dtype, void *workspace, int64_t workspace_bytes, void *hip_stream);
 int64_t lookupffn_workspace_bytes_gather(int64_t n_tokens, int k);
@@ -115,7 +121,7 @@ int64_t lookupffn_workspace_bytes_gather(int64_t n_tokens, int k);
  * Batches of up to 512 tokens ("small_tokens" below) whose shape lookupffn_forward_stack takes run as that
  * call's single launch with n_layers = 1 (no scratch touched); y has the same bits either way.
  */
-int lookupffn_forward(const void *x, const int8_t *signs, const void *tables, float *y,
+int lookupffn_forward(const void *x, const int8_t *signs, const void *tables, void *y,
                       int64_t n_tokens, int d, int k, int tau, int d_out,
                       int n_rounds, int x_dtype, int table_dtype,
                       void *workspace, int64_t workspace_bytes, void *hip_stream);
@@ -136,7 +142,7 @@ int64_t lookupffn_workspace_bytes(int64_t n_tokens, int k);
  * aligned, x rows 16-byte aligned when d % 4 == 0; anything else returns LFFN_E_UNSUPPORTED and the caller
  * loops over lookupffn_forward instead.  n_layers > 1 with d_out != d returns LFFN_E_SIZE.
  */
-int lookupffn_forward_stack(const void *x, const int8_t *const *signs, const void *const *tables, float *y,
+int lookupffn_forward_stack(const void *x, const int8_t *const *signs, const void *const *tables, void *y,
                             int64_t n_tokens, int d, int k, int tau, int d_out,
                             int n_rounds, int n_layers, int x_dtype, int table_dtype, void *hip_stream);
 
@@ -151,7 +157,7 @@ int lookupffn_forward_stack(const void *x, const int8_t *const *signs, const voi
  * them on one stream.  Nothing in the array needs clearing between calls (every word a call reads, it
  * wrote first).  The array's address is looked up on the first call on a device, or by lookupffn_init().
  */
-int lookupffn_forward_static(const void *x, const int8_t *signs, const void *tables, float *y,
+int lookupffn_forward_static(const void *x, const int8_t *signs, const void *tables, void *y,
                              int64_t n_tokens, int d, int k, int tau, int d_out,
                              int n_rounds, int x_dtype, int table_dtype, void *hip_stream);
 int64_t lookupffn_static_scratch_bytes(void);
@@ -181,11 +187,11 @@ int lookupffn_prepare_tables(const void *tables, int k, int tau, int d_out, int 
 int lookupffn_hash_weighted(const void *x, const int8_t *signs, uint16_t *codes, float *weights,
                             int64_t n_tokens, int d, int k, int tau,
                             int n_rounds, int x_dtype, void *hip_stream);
-int lookupffn_gather_weighted(const uint16_t *codes, const float *weights, const void *tables, float *y,
+int lookupffn_gather_weighted(const uint16_t *codes, const float *weights, const void *tables, void *y,
                               int64_t n_tokens, int k, int tau, int d_out,
                               int table_dtype, void *workspace, int64_t workspace_bytes, void *hip_stream);
 int64_t lookupffn_workspace_bytes_gather_weighted(int64_t n_tokens, int k);
-int lookupffn_forward_weighted(const void *x, const int8_t *signs, const void *tables, float *y,
+int lookupffn_forward_weighted(const void *x, const int8_t *signs, const void *tables, void *y,
                                int64_t n_tokens, int d, int k, int tau, int d_out,
                                int n_rounds, int x_dtype, int table_dtype,
                                void *workspace, int64_t workspace_bytes, void *hip_stream);
@@ -204,11 +210,11 @@ int64_t lookupffn_workspace_bytes_weighted(int64_t n_tokens, int k);
 int lookupffn_hash_probes(const void *x, const int8_t *signs, uint16_t *codes, float *shares,
                           int64_t n_tokens, int d, int k, int tau,
                           int n_rounds, int x_dtype, void *hip_stream);
-int lookupffn_gather_probes(const uint16_t *codes, const float *shares, const void *tables, float *y,
+int lookupffn_gather_probes(const uint16_t *codes, const float *shares, const void *tables, void *y,
                             int64_t n_tokens, int k, int tau, int d_out,
                             int table_dtype, void *workspace, int64_t workspace_bytes, void *hip_stream);
 int64_t lookupffn_workspace_bytes_gather_probes(int64_t n_tokens, int k, int tau);
-int lookupffn_forward_probes(const void *x, const int8_t *signs, const void *tables, float *y,
+int lookupffn_forward_probes(const void *x, const int8_t *signs, const void *tables, void *y,
                              int64_t n_tokens, int d, int k, int tau, int d_out,
                              int n_rounds, int x_dtype, int table_dtype,
                              void *workspace, int64_t workspace_bytes, void *hip_stream);
@@ -234,7 +240,7 @@ int lookupffn_prepare_bh(const float *bmats, int d, int k, int tau, int block, i
 int lookupffn_hash_bh(const void *x, const float *bmats, uint16_t *codes,
                       int64_t n_tokens, int d, int k, int tau, int block, int n_factors, int x_dtype,
                       void *workspace, int64_t workspace_bytes, void *hip_stream);
-int lookupffn_forward_bh(const void *x, const float *bmats, const void *tables, float *y,
+int lookupffn_forward_bh(const void *x, const float *bmats, const void *tables, void *y,
                          int64_t n_tokens, int d, int k, int tau, int d_out, int block, int n_factors,
                          int x_dtype, int table_dtype,
                          void *workspace, int64_t workspace_bytes, void *hip_stream);
@@ -252,7 +258,7 @@ int64_t lookupffn_workspace_bytes_bh(int64_t n_tokens, int d, int k, int tau, in
 int lookupffn_hash_bh_weighted(const void *x, const float *bmats, uint16_t *codes, float *weights,
                                int64_t n_tokens, int d, int k, int tau, int block, int n_factors, int x_dtype,
                                void *workspace, int64_t workspace_bytes, void *hip_stream);
-int lookupffn_forward_bh_weighted(const void *x, const float *bmats, const void *tables, float *y,
+int lookupffn_forward_bh_weighted(const void *x, const float *bmats, const void *tables, void *y,
                                   int64_t n_tokens, int d, int k, int tau, int d_out, int block, int n_factors,
                                   int x_dtype, int table_dtype,
                                   void *workspace, int64_t workspace_bytes, void *hip_stream);

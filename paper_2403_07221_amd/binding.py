@@ -16,6 +16,7 @@ _LIB_PATH = Path(__file__).resolve().parent / "liblookupffn.so"
 _lib = None
 
 F32, BF16, F16 = 0, 1, 2
+Y_BF16, Y_F16 = 0x200, 0x400   # OR-ed into table_dtype: y is stored in 16 bits
 PREPARED = 0x100   # OR-ed into table_dtype / block: the buffer is a prepared copy (see include/lookupffn.h)
 EXPORTS = (
     "lookupffn_init",
@@ -110,6 +111,17 @@ def _dtype_code(t: torch.Tensor) -> int:
     if t.dtype == torch.float16:
         return F16
     raise TypeError(f"expected float32, bfloat16 or float16, got {t.dtype}")
+
+
+def _y_flag(y: torch.Tensor) -> int:
+    """table_dtype flag for the storage type of an output tensor."""
+    if y.dtype == torch.float32:
+        return 0
+    if y.dtype == torch.bfloat16:
+        return Y_BF16
+    if y.dtype == torch.float16:
+        return Y_F16
+    raise TypeError(f"y must be float32, bfloat16 or float16, got {y.dtype}")
 
 
 def _dev(t: torch.Tensor, name: str) -> int:
@@ -219,7 +231,8 @@ def _gather(entry: str, codes, weights, tables, y, workspace, wshape):
         assert weights.dtype == torch.float32 and tuple(weights.shape) == wshape(n, k, tau)
     if y is None:
         y = torch.empty((n, d_out), dtype=torch.float32, device=dev)
-    assert y.dtype == torch.float32 and tuple(y.shape) == (n, d_out)
+    assert tuple(y.shape) == (n, d_out)
+    tcode |= _y_flag(y)      # a bfloat16 / float16 y is stored in that type
     if n == 0:
         return y
     ws_ptr, ws_bytes = _ws(workspace)
@@ -330,7 +343,8 @@ def lookupffn_forward(x: torch.Tensor, signs: torch.Tensor, tables,
     _check_signs(signs, d, k, tau)
     if y is None:
         y = torch.empty((n, d_out), dtype=torch.float32, device=x.device)
-    assert y.dtype == torch.float32 and tuple(y.shape) == (n, d_out)
+    assert tuple(y.shape) == (n, d_out)
+    tcode |= _y_flag(y)      # a bfloat16 / float16 y is stored in that type
     if n == 0:
         return y
     ws_ptr, ws_bytes = _ws(workspace)
@@ -356,7 +370,8 @@ def lookupffn_forward_stack(x: torch.Tensor, signs, tables, y: torch.Tensor | No
         _check_signs(sg, d, k, tau)
     if y is None:
         y = torch.empty((n, d_out), dtype=torch.float32, device=x.device)
-    assert y.dtype == torch.float32 and tuple(y.shape) == (n, d_out)
+    assert tuple(y.shape) == (n, d_out)
+    tcode |= _y_flag(y)      # a bfloat16 / float16 y is stored in that type
     if n == 0:
         return y
     vp = ctypes.c_void_p
@@ -378,7 +393,8 @@ def lookupffn_forward_static(x: torch.Tensor, signs: torch.Tensor, tables, y: to
     n, d = x.shape
     tptr, k, tau, d_out, tcode, _ = _tables(tables)
     _check_signs(signs, d, k, tau)
-    assert y.dtype == torch.float32 and tuple(y.shape) == (n, d_out)
+    assert tuple(y.shape) == (n, d_out)
+    tcode |= _y_flag(y)      # a bfloat16 / float16 y is stored in that type
     if n == 0:
         return y
     with torch.cuda.device(x.device):
@@ -453,7 +469,8 @@ def lookupffn_forward_bh(x: torch.Tensor, bmats, tables, y: torch.Tensor | None 
     bptr, block, m = _bh(bmats, d, k, tau)
     if y is None:
         y = torch.empty((n, d_out), dtype=torch.float32, device=x.device)
-    assert y.dtype == torch.float32 and tuple(y.shape) == (n, d_out)
+    assert tuple(y.shape) == (n, d_out)
+    tcode |= _y_flag(y)      # a bfloat16 / float16 y is stored in that type
     if n == 0:
         return y
     ws_ptr, ws_bytes = _ws(workspace)

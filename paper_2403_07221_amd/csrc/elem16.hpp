@@ -35,4 +35,30 @@ __device__ __forceinline__ float2 widen16x2(uint32_t w, int kind)
     return kind == kElemF16 ? widen16x2<kElemF16>(w) : widen16x2<kElemBF16>(w);
 }
 
+// fp32 -> 16-bit storage for outputs kept in 16 bits, round to nearest even.  bf16: half an ulp of the kept
+// part plus its last bit on a tie is added to the pattern, then the low half is cut (NaN keeps a quiet
+// payload); IEEE half: the hardware conversion (round to nearest even is the default mode, never changed).
+__device__ __forceinline__ uint32_t narrow16(float f, int kind)
+{
+    if (kind == kElemF16) return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)f);
+    const uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+// Stores four consecutive outputs, elements e .. e + 3 of y (e % 4 == 0), in y's storage type, streaming
+// (y is written once and not read again by the kernel).
+__device__ __forceinline__ void store_y4(void *y, size_t e, float a, float b, float c, float d, int y_kind)
+{
+    if (y_kind == kElemF32) {
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        const f4 o = {a, b, c, d};
+        __builtin_nontemporal_store(o, reinterpret_cast<f4 *>(static_cast<float *>(y) + e));
+    } else {
+        typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+        const u2 o = {narrow16(a, y_kind) | (narrow16(b, y_kind) << 16), narrow16(c, y_kind) | (narrow16(d, y_kind) << 16)};
+        __builtin_nontemporal_store(o, reinterpret_cast<u2 *>(static_cast<uint16_t *>(y) + e));
+    }
+}
+
 }  // namespace lffn

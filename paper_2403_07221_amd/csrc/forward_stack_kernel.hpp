@@ -38,7 +38,8 @@ constexpr int kStackChunk = 32;  // fetches issued back to back into one registe
 
 struct StackArgs {
     const void *x;  // [n][d], input of the first layer
-    float *y;       // [n][d_out], output of the last layer
+    void *y;        // [n][d_out], output of the last layer: fp32, or bf16 / IEEE half when y_kind says so
+    int y_kind;
     const int8_t *signs[kStackMaxLayers];  // per layer [P][R][1024]
     const char *tables[kStackMaxLayers];   // per layer, all in the same layout
     long long n;
@@ -189,8 +190,14 @@ __global__ __launch_bounds__(1024) void forward_stack_kernel(StackArgs a)
                 nxt[col] = acc0;
                 if constexpr (HALF16) nxt[col + 1] = acc1;
             } else {
-                a.y[t * a.d_out + col] = acc0;
-                if constexpr (HALF16) a.y[t * a.d_out + col + 1] = acc1;
+                const size_t e = (size_t)t * a.d_out + col;
+                if (a.y_kind == kElemF32) {
+                    static_cast<float *>(a.y)[e] = acc0;
+                    if constexpr (HALF16) static_cast<float *>(a.y)[e + 1] = acc1;
+                } else {
+                    static_cast<uint16_t *>(a.y)[e] = (uint16_t)narrow16(acc0, a.y_kind);
+                    if constexpr (HALF16) static_cast<uint16_t *>(a.y)[e + 1] = (uint16_t)narrow16(acc1, a.y_kind);
+                }
             }
         }
         __syncthreads();

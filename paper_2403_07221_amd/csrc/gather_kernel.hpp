@@ -34,7 +34,8 @@ struct GatherArgs {
     const uint16_t *codes;  // [n][k]
     const float *weights;   // [n][k] for the weighted form, [n][k][1+tau] for the multi-probe form, else NULL
     const char *tables;     // [k][rows][d_out] fp32, bf16 or IEEE half
-    float *y;               // [n][d_out]
+    void *y;                // [n][d_out] fp32, or bf16 / IEEE half when y_kind says so
+    int y_kind;             // 0 fp32, 1 bf16, 2 IEEE half
     long long n;
     int k, tau, d_out;
     int nvec;          // 16-byte pieces per row
@@ -252,14 +253,9 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a)
     for (; j0 < k; ++j0) acc.add(row(j0, crow[j0]));
 
     // ---- a6: store, streaming (y is written once and not read again here) -------------
-    float *yp = a.y + t * a.d_out + (size_t)vec * Acc<KIND>::W;
-    typedef float f4 __attribute__((ext_vector_type(4)));
-    f4 o0 = {acc.f[0], acc.f[1], acc.f[2], acc.f[3]};
-    __builtin_nontemporal_store(o0, reinterpret_cast<f4 *>(yp));
-    if constexpr (KIND != 0) {
-        f4 o1 = {acc.f[4], acc.f[5], acc.f[6], acc.f[7]};
-        __builtin_nontemporal_store(o1, reinterpret_cast<f4 *>(yp) + 1);
-    }
+    const size_t e = (size_t)t * a.d_out + (size_t)vec * Acc<KIND>::W;
+    store_y4(a.y, e, acc.f[0], acc.f[1], acc.f[2], acc.f[3], a.y_kind);
+    if constexpr (KIND != 0) store_y4(a.y, e + 4, acc.f[4], acc.f[5], acc.f[6], acc.f[7], a.y_kind);
 }
 
 }  // namespace lffn

@@ -75,7 +75,8 @@ struct GatherLdsArgs {
                              // slots past a chunk's end multiply it into accumulators that are never stored.
     long long n_pad;
     const char *tables;      // fp32 rows, row-major [k][rows][d_out] or the slice-major prepared layout
-    float *y;
+    void *y;            // [n][d_out] fp32, or bf16 / IEEE half when y_kind says so
+    int y_kind;         // 0 fp32, 1 bf16, 2 IEEE half
     long long n;
     int k, tau, d_out;
     int nvec;           // 16-byte pieces per row
@@ -540,15 +541,13 @@ __global__ __launch_bounds__(kLdsThreads) void gather_lds_kernel(GatherLdsArgs a
                 uint32_t lt = tid;
                 asm volatile("" : "+v"(lt));
                 const uint32_t sg = lt / SW, svec = slice * (uint32_t)SW + lt % SW;
-                typedef float f4 __attribute__((ext_vector_type(4)));
 #pragma unroll
                 for (int i = 0; i < TOK; ++i) {
                     const uint32_t t = i < 4 * FQ ? c0 + (4u * G) * (uint32_t)(i >> 2) + 4u * sg + (uint32_t)(i & 3)
                                                   : c0 + (uint32_t)G * (uint32_t)i + sg;
                     if (t >= c1 || svec >= (uint32_t)a.nvec) continue;
-                    float *yp = a.y + (size_t)t * a.d_out + (size_t)svec * 4u;
-                    f4 o0 = {acc[i].f[0], acc[i].f[1], acc[i].f[2], acc[i].f[3]};
-                    __builtin_nontemporal_store(o0, reinterpret_cast<f4 *>(yp));
+                    store_y4(a.y, (size_t)t * a.d_out + (size_t)svec * 4u, acc[i].f[0], acc[i].f[1], acc[i].f[2],
+                             acc[i].f[3], a.y_kind);
                 }
             }
         }

@@ -44,6 +44,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "elem16.hpp"
+
 #include "gather_kernel.hpp"
 #include "gather_lds_kernel.hpp"
 #include "hash_kernel.hpp"
@@ -63,7 +65,8 @@ struct GatherRingArgs {
     const uint32_t *packed;  // lagged packed codes [ring_code_words(k)][n_pad]
     long long n_pad;
     const char *tables;      // prepared tables: [slice of pw bytes][k][rows][pw], fp32
-    float *y;
+    void *y;   // [n][d_out] fp32, or bf16 / IEEE half when y_kind says so
+    int y_kind;
     long long n;
     int k, tau, d_out;
     int nvec;            // 16-byte pieces per row
@@ -256,15 +259,13 @@ __global__ __launch_bounds__(THREADS) void gather_ring_kernel(GatherRingArgs a)
                 const uint32_t sg = lt >> 2, sq = lt & 3u, svec = slice * 4u + sq;
                 const uint32_t so = 16u * (sg >> 4) + 4u * (sg & 3u) + ((sg >> 2) & 3u);
                 if (svec < (uint32_t)a.nvec) {
-                    typedef float f4 __attribute__((ext_vector_type(4)));
 #pragma unroll
                     for (int i = 0; i < TOK; ++i) {
                         const uint32_t t = i < 4 * NQ ? c0 + (4u * G) * (uint32_t)(i >> 2) + 4u * sg + (uint32_t)(i & 3)
                                                       : c0 + (4u * G) * NQ + (uint32_t)G * (uint32_t)(i - 4 * NQ) + so;
                         if (t >= c1) continue;
-                        float *yp = a.y + (size_t)t * a.d_out + (size_t)svec * 4u;
-                        f4 o0 = {acc[i].f[0], acc[i].f[1], acc[i].f[2], acc[i].f[3]};
-                        __builtin_nontemporal_store(o0, reinterpret_cast<f4 *>(yp));
+                        store_y4(a.y, (size_t)t * a.d_out + (size_t)svec * 4u, acc[i].f[0], acc[i].f[1], acc[i].f[2],
+                                 acc[i].f[3], a.y_kind);
                     }
                 }
             };

@@ -588,6 +588,7 @@ struct TableRef {
     int kind = kElemF32;    // element type of the buffer the kernels read (prepared tables are always fp32)
     bool prepared = false;
     int pw = 0;             // prepared: bytes per row piece
+    int y_kind = kElemF32;  // storage type of the output rows (LFFN_Y_BF16 / LFFN_Y_F16 in table_dtype)
 };
 
 TableRef table_ref(const void *tables, int table_dtype, int tau)
@@ -597,6 +598,7 @@ TableRef table_ref(const void *tables, int table_dtype, int tau)
     t.prepared = (table_dtype & LFFN_PREPARED) != 0;
     t.kind = t.prepared ? kElemF32 : (table_dtype & 0xFF);  // LFFN_F32 / BF16 / F16 are the kernels' kinds 0 / 1 / 2
     t.pw = t.prepared ? prepared_piece_bytes(tau) : 0;
+    t.y_kind = (table_dtype & LFFN_Y_BF16) ? kElemBF16 : (table_dtype & LFFN_Y_F16) ? kElemF16 : kElemF32;
     return t;
 }
 
@@ -632,18 +634,21 @@ int check_weights(const float *weights)
     return LFFN_OK;
 }
 
-int check_gather(const uint16_t *codes, const void *tables, const float *y, int64_t n, int k, int tau,
+int check_gather(const uint16_t *codes, const void *tables, const void *y, int64_t n, int k, int tau,
                  int d_out, int table_dtype)
 {
     if (!codes || !tables || !y) return LFFN_E_NULL;
     if (n < 0 || k < 1 || d_out < 1) return LFFN_E_SIZE;
     if (tau < 1 || tau > 16) return LFFN_E_TAU;
-    if ((table_dtype & ~(0xFF | LFFN_PREPARED)) != 0 || !dtype_ok(table_dtype & 0xFF)) return LFFN_E_DTYPE;
+    if ((table_dtype & ~(0xFF | LFFN_PREPARED | LFFN_Y_BF16 | LFFN_Y_F16)) != 0 || !dtype_ok(table_dtype & 0xFF))
+        return LFFN_E_DTYPE;
+    if ((table_dtype & LFFN_Y_BF16) && (table_dtype & LFFN_Y_F16)) return LFFN_E_DTYPE;
     if (k > (1 << 20) || n > (int64_t(1) << 40) || d_out > (1 << 24)) return LFFN_E_SIZE;
     const int w = (table_dtype & 0xFF) == LFFN_F32 ? 4 : 8;
     if (d_out % w != 0) return LFFN_E_ALIGN;
     const size_t ta = (table_dtype & LFFN_PREPARED) ? 256 : 16;
-    if (!aligned(tables, ta) || !aligned(y, 16) || !aligned(codes, 2)) return LFFN_E_ALIGN;
+    const size_t ya = (table_dtype & (LFFN_Y_BF16 | LFFN_Y_F16)) ? 8 : 16;  // four outputs are stored at a time
+    if (!aligned(tables, ta) || !aligned(y, ya) || !aligned(codes, 2)) return LFFN_E_ALIGN;
     // row index (j << tau) + code must fit 32 bits
     if (((int64_t)k << tau) > (int64_t(1) << 31)) return LFFN_E_SIZE;
     return LFFN_OK;
@@ -911,7 +916,7 @@ int64_t forward_ws_bytes(int64_t n, int k, int tau, Mode m)
     return sat_add(sat_add(abi_codes_bytes(n, k), abi_weights_bytes(n, k, tau, m)), gather_ws_bytes(n, k, tau, m));
 }
 
-int launch_gather_lds(const LdsPlan &p, const uint32_t *packed, const float *wpk, const TableRef &T, float *y,
+int launch_gather_lds(const LdsPlan &p, const uint32_t *packed, const float *wpk, const TableRef &T, void *y,
                       Mode mode, hipStream_t s)
 {
     GatherLdsArgs a = p.a;
@@ -919,6 +924,7 @@ int launch_gather_lds(const LdsPlan &p, const uint32_t *packed, const float *wpk
     a.wpk = wpk;
     a.tables = T.p;
     a.y = y;
+    a.y_kind = T.y_kind;
     // extents the kernel assumes: rows * copy rounds cover a table exactly, the stage fits its buffer,
     // token windows of 16 x 256 tokens past any token stay inside the padded code arrays
     if ((kLdsThreads / p.sw) * p.fr != (1 << a.tau) || a.n_pad < a.n + 16 * 256 || (a.k & 1) || T.kind ||
@@ -940,7 +946,7 @@ int launch_gather_lds(const LdsPlan &p, const uint32_t *packed, const float *wpk
     return LFFN_OK;
 }
 
-int launch_gather_direct(const uint16_t *codes, const float *weights, const TableRef &T, float *y, int64_t n,
+int launch_gather_direct(const uint16_t *codes, const float *weights, const TableRef &T, void *y, int64_t n,
                          int k, int tau, int d_out, Mode mode, hipStream_t s, const Options &opt)
 {
     const int esz = T.kind ? 2 : 4;
@@ -949,6 +955,7 @@ int launch_gather_direct(const uint16_t *codes, const float *weights, const Tabl
     a.weights = weights;
     a.tables = T.p;
     a.y = y;
+    a.y_kind = T.y_kind;
     a.n = n;
     a.k = k;
     a.tau = tau;
@@ -1104,7 +1111,7 @@ int plan_gather_ring(int64_t n, int k, int tau, int d_out, const TableRef &T, Mo
     return LFFN_OK;
 }
 
-int launch_gather_ring(const RingPlan &p, const uint16_t *codes, uint32_t *packed, const TableRef &T, float *y,
+int launch_gather_ring(const RingPlan &p, const uint16_t *codes, uint32_t *packed, const TableRef &T, void *y,
                        hipStream_t s)
 {
     GatherRingArgs a = p.a;
@@ -1120,6 +1127,7 @@ int launch_gather_ring(const RingPlan &p, const uint16_t *codes, uint32_t *packe
     a.packed = packed;
     a.tables = T.p;
     a.y = y;
+    a.y_kind = T.y_kind;
     int rc = lffn_host::gather_ring_part(p.threads, p.tok, a, dim3(p.grid), s);
     if (rc != LFFN_OK) return rc;
     LFFN_HIP(hipGetLastError());
@@ -1130,7 +1138,7 @@ int launch_gather_ring(const RingPlan &p, const uint16_t *codes, uint32_t *packe
 
 // Gather from ABI-layout codes (and weights / shares): the staged kernel through the re-pack kernels when
 // the plan says so and the scratch has room, else the direct kernel.
-int gather_from_abi(Mode mode, const uint16_t *codes, const float *weights, const TableRef &T, float *y, int64_t n,
+int gather_from_abi(Mode mode, const uint16_t *codes, const float *weights, const TableRef &T, void *y, int64_t n,
                     int k, int tau, int d_out, const LdsPlan &plan, Scratch *sc, hipStream_t s, const Options &opt)
 {
     RingPlan ring;
@@ -1278,7 +1286,7 @@ bool stack_shape_ok(const void *x, const int8_t *const *signs, const void *const
 }
 
 // Call only with stack_shape_ok(...) true and every argument validated.
-int launch_forward_stack(const void *x, const int8_t *const *signs, const void *const *tables, float *y, int64_t n,
+int launch_forward_stack(const void *x, const int8_t *const *signs, const void *const *tables, void *y, int64_t n,
                          int d, int k, int tau, int d_out, int n_rounds, int n_layers, int x_dtype, int table_dtype,
                          hipStream_t s)
 {
@@ -1286,6 +1294,7 @@ int launch_forward_stack(const void *x, const int8_t *const *signs, const void *
     StackArgs a{};
     a.x = x;
     a.y = y;
+    a.y_kind = T.y_kind;
     for (int l = 0; l < n_layers; ++l) {
         a.signs[l] = signs[l];
         a.tables[l] = static_cast<const char *>(tables[l]);
@@ -1342,7 +1351,7 @@ int64_t forward_need(const HashSpec &h, Mode mode, int64_t n, int d, int k, int 
     return sat_add(pack, forward_ws_bytes(n, k, tau, mode));
 }
 
-int forward_core(const HashSpec &h, Mode mode, const void *x, const void *tables, float *y, int64_t n, int d,
+int forward_core(const HashSpec &h, Mode mode, const void *x, const void *tables, void *y, int64_t n, int d,
                  int k, int tau, int d_out, int x_dtype, int table_dtype, void *workspace,
                  int64_t workspace_bytes, hipStream_t s)
 {
@@ -1408,7 +1417,7 @@ int forward_core(const HashSpec &h, Mode mode, const void *x, const void *tables
     return gather_from_abi(mode, out.codes, out.weights, T, y, n, k, tau, d_out, plan, &sc, s, opt);
 }
 
-int gather_core(Mode mode, const uint16_t *codes, const float *weights, const void *tables, float *y, int64_t n,
+int gather_core(Mode mode, const uint16_t *codes, const float *weights, const void *tables, void *y, int64_t n,
                 int k, int tau, int d_out, int table_dtype, void *workspace, int64_t workspace_bytes, hipStream_t s)
 {
     int rc = check_gather(codes, tables, y, n, k, tau, d_out, table_dtype);
@@ -1594,14 +1603,14 @@ int lookupffn_hash_probes(const void *x, const int8_t *signs, uint16_t *codes, f
                        options_snapshot());
 }
 
-int lookupffn_gather(const uint16_t *codes, const void *tables, float *y, int64_t n_tokens, int k, int tau,
+int lookupffn_gather(const uint16_t *codes, const void *tables, void *y, int64_t n_tokens, int k, int tau,
                      int d_out, int table_dtype, void *workspace, int64_t workspace_bytes, void *hip_stream)
 {
     return gather_core(kPlain, codes, nullptr, tables, y, n_tokens, k, tau, d_out, table_dtype, workspace,
                        workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
-int lookupffn_gather_weighted(const uint16_t *codes, const float *weights, const void *tables, float *y,
+int lookupffn_gather_weighted(const uint16_t *codes, const float *weights, const void *tables, void *y,
                               int64_t n_tokens, int k, int tau, int d_out, int table_dtype, void *workspace,
                               int64_t workspace_bytes, void *hip_stream)
 {
@@ -1609,7 +1618,7 @@ int lookupffn_gather_weighted(const uint16_t *codes, const float *weights, const
                        workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
-int lookupffn_gather_probes(const uint16_t *codes, const float *shares, const void *tables, float *y,
+int lookupffn_gather_probes(const uint16_t *codes, const float *shares, const void *tables, void *y,
                             int64_t n_tokens, int k, int tau, int d_out, int table_dtype, void *workspace,
                             int64_t workspace_bytes, void *hip_stream)
 {
@@ -1655,7 +1664,7 @@ int64_t lookupffn_workspace_bytes_bh_weighted(int64_t n_tokens, int d, int k, in
     return sat_add(pack, n_tokens > 0 ? forward_ws_bytes(n_tokens, k, tau, kWeighted) : 0);
 }
 
-int lookupffn_forward(const void *x, const int8_t *signs, const void *tables, float *y, int64_t n_tokens,
+int lookupffn_forward(const void *x, const int8_t *signs, const void *tables, void *y, int64_t n_tokens,
                       int d, int k, int tau, int d_out, int n_rounds, int x_dtype, int table_dtype,
                       void *workspace, int64_t workspace_bytes, void *hip_stream)
 {
@@ -1663,7 +1672,7 @@ int lookupffn_forward(const void *x, const int8_t *signs, const void *tables, fl
                         table_dtype, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
-int lookupffn_forward_stack(const void *x, const int8_t *const *signs, const void *const *tables, float *y,
+int lookupffn_forward_stack(const void *x, const int8_t *const *signs, const void *const *tables, void *y,
                             int64_t n_tokens, int d, int k, int tau, int d_out, int n_rounds, int n_layers,
                             int x_dtype, int table_dtype, void *hip_stream)
 {
@@ -1685,7 +1694,7 @@ int lookupffn_forward_stack(const void *x, const int8_t *const *signs, const voi
 
 int64_t lookupffn_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
-int lookupffn_forward_static(const void *x, const int8_t *signs, const void *tables, float *y, int64_t n_tokens,
+int lookupffn_forward_static(const void *x, const int8_t *signs, const void *tables, void *y, int64_t n_tokens,
                              int d, int k, int tau, int d_out, int n_rounds, int x_dtype, int table_dtype,
                              void *hip_stream)
 {
@@ -1702,7 +1711,7 @@ int lookupffn_forward_static(const void *x, const int8_t *signs, const void *tab
                         table_dtype, ws, kStaticScratchBytes, static_cast<hipStream_t>(hip_stream));
 }
 
-int lookupffn_forward_weighted(const void *x, const int8_t *signs, const void *tables, float *y, int64_t n_tokens,
+int lookupffn_forward_weighted(const void *x, const int8_t *signs, const void *tables, void *y, int64_t n_tokens,
                                int d, int k, int tau, int d_out, int n_rounds, int x_dtype, int table_dtype,
                                void *workspace, int64_t workspace_bytes, void *hip_stream)
 {
@@ -1710,7 +1719,7 @@ int lookupffn_forward_weighted(const void *x, const int8_t *signs, const void *t
                         table_dtype, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
-int lookupffn_forward_probes(const void *x, const int8_t *signs, const void *tables, float *y, int64_t n_tokens,
+int lookupffn_forward_probes(const void *x, const int8_t *signs, const void *tables, void *y, int64_t n_tokens,
                              int d, int k, int tau, int d_out, int n_rounds, int x_dtype, int table_dtype,
                              void *workspace, int64_t workspace_bytes, void *hip_stream)
 {
@@ -1735,7 +1744,7 @@ int lookupffn_hash_bh_weighted(const void *x, const float *bmats, uint16_t *code
                         workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
-int lookupffn_forward_bh(const void *x, const float *bmats, const void *tables, float *y, int64_t n_tokens, int d,
+int lookupffn_forward_bh(const void *x, const float *bmats, const void *tables, void *y, int64_t n_tokens, int d,
                          int k, int tau, int d_out, int block, int n_factors, int x_dtype, int table_dtype,
                          void *workspace, int64_t workspace_bytes, void *hip_stream)
 {
@@ -1743,7 +1752,7 @@ int lookupffn_forward_bh(const void *x, const float *bmats, const void *tables, 
                         table_dtype, workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
-int lookupffn_forward_bh_weighted(const void *x, const float *bmats, const void *tables, float *y, int64_t n_tokens,
+int lookupffn_forward_bh_weighted(const void *x, const float *bmats, const void *tables, void *y, int64_t n_tokens,
                                   int d, int k, int tau, int d_out, int block, int n_factors, int x_dtype,
                                   int table_dtype, void *workspace, int64_t workspace_bytes, void *hip_stream)
 {

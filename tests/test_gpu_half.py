@@ -137,3 +137,73 @@ def test_single_launch_path_with_half_storage():
     y1 = B.lookupffn_forward(B.to_device(x), B.to_device(signs[0]), B.to_device(tables[0]))   # 9 tokens: the same kernel
     assert B.lookupffn_last_gather_kernel() == "forward_stack_kernel"
     assert np.array_equal(y1.cpu().numpy(), oracle.forward(x, signs[0], tables[0], acc64=False))
+
+
+# ------------------------------------------------------------------ outputs stored in 16 bits
+
+def y16_bits(y: torch.Tensor) -> np.ndarray:
+    return y.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def close16(y: torch.Tensor, ref: np.ndarray, tol32: float) -> bool:
+    """y (16-bit storage) against a reference: the fp32 tolerance (relative to the rms) plus one rounding to
+    y's type per element (half an ulp: 2^-9 relative for bf16, 2^-12 for half; twice that is allowed)."""
+    rel = 2.0 ** -8 if y.dtype == torch.bfloat16 else 2.0 ** -11
+    got = y.float().cpu().numpy().astype(np.float64)
+    r = ref.astype(np.float64)
+    return bool(np.all(np.abs(got - r) <= rel * np.abs(r) + tol32 * np.sqrt(np.mean(r ** 2))))
+
+
+def expect16(y32: np.ndarray, dtype) -> np.ndarray:
+    return oracle.float_to_bf16(y32) if dtype == torch.bfloat16 else oracle.float_to_half(y32)
+
+
+@pytest.mark.parametrize("ydt", [torch.bfloat16, torch.float16])
+def test_outputs_stored_in_16_bits_are_the_rounded_fp32_sums(ydt):
+    """Every gather kernel and entry point: y in bf16 / half holds exactly the oracle's fp32 sequential sums
+    rounded once to nearest even; against the fp64 sums that is the fp32 tolerance plus one rounding to y's type."""
+    print(f"y stored as {ydt}", flush=True)
+    w = synth.C2.with_tokens(3000)
+    x, signs, tables = synth.make_layer(w)
+    xd, sd, td = B.to_device(x), B.to_device(signs), B.to_device(tables)
+    prep = B.lookupffn_prepare_tables(td)
+    y32, codes = oracle.forward(x, signs, tables, acc64=False, return_codes=True)
+    want = expect16(y32, ydt)
+    cd = torch.from_numpy(codes.view(np.int16)).cuda()
+    try:
+        for path, tabs, kernel in ((1, td, "gather_kernel"), (2, prep, "gather_lds_kernel"), (4, prep, "gather_ring_kernel")):
+            B.lookupffn_set_option("gather_path", path)
+            y = torch.empty((w.n_tokens, w.d_out), dtype=ydt, device="cuda")
+            B.lookupffn_gather(cd, tabs, y=y)
+            assert B.lookupffn_last_gather_kernel() == kernel
+            assert np.array_equal(y16_bits(y), want), kernel
+            y.zero_()
+            B.lookupffn_forward(xd, sd, tabs, y=y)
+            assert np.array_equal(y16_bits(y), want), ("forward", kernel)
+    finally:
+        B.lookupffn_set_option("gather_path", 0)
+    ref64 = oracle.forward(x, signs, tables, acc64=True)
+    assert close16(y, ref64, 1e-4)
+    # weighted and multi-probe: within tolerance of the fp64 oracle (their fp32 values are not pinned bit for bit)
+    yw = torch.empty((w.n_tokens, w.d_out), dtype=ydt, device="cuda")
+    B.lookupffn_forward_weighted(xd, sd, prep, y=yw)
+    assert close16(yw, oracle.forward_weighted(x, signs, tables), 1e-4)
+    B.lookupffn_forward_probes(xd, sd, prep, y=yw)
+    assert close16(yw, oracle.forward_probes(x, signs, tables), 1e-4)
+    # bf16 rows in, 16-bit rows out, through the direct kernel's 8-element pieces
+    t16 = synth.make_tables(5, w.k, w.rows, w.d_out, "bf16")
+    y = torch.empty((200, w.d_out), dtype=ydt, device="cuda")
+    B.lookupffn_gather(cd[:200].contiguous(), B.to_device(t16), y=y)
+    assert np.array_equal(y16_bits(y), expect16(oracle.gather(codes[:200], t16, acc64=False), ydt))
+    # the single launch: a few tokens, and a chain (only the last layer's output is rounded)
+    y8 = torch.empty((8, w.d_out), dtype=ydt, device="cuda")
+    B.lookupffn_forward(xd[:8].contiguous(), sd, td, y=y8)
+    assert B.lookupffn_last_gather_kernel() == "forward_stack_kernel"
+    assert np.array_equal(y16_bits(y8), want[:8])
+    chain = [synth.make_layer(synth.C5, layer=l, with_x=False) for l in range(3)]
+    h = x[:8]
+    for _, s_, t_ in chain:
+        h = oracle.forward(h, s_, t_, acc64=False)
+    B.lookupffn_forward_stack(xd[:8].contiguous(), [B.to_device(s_) for _, s_, _ in chain],
+                              [B.to_device(t_) for _, _, t_ in chain], y=y8)
+    assert np.array_equal(y16_bits(y8), expect16(h, ydt))

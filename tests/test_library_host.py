@@ -76,7 +76,10 @@ def test_gather_argument_errors(L):
     assert gather_call(L, tables=FAKE + 4) == -5 and gather_call(L, y=FAKE + 8) == -5
     # prepared tables: the flag with either source dtype; the buffer is 256-byte aligned
     assert gather_call(L, dt=0x100) == 0 and gather_call(L, dt=0x101) == 0 and gather_call(L, dt=0x102) == 0 and gather_call(L, dt=0x103) == -4
-    assert gather_call(L, dt=0x200) == -4 and gather_call(L, tables=FAKE + 16, dt=0x100) == -5
+    assert gather_call(L, dt=0x800) == -4 and gather_call(L, tables=FAKE + 16, dt=0x100) == -5
+    # 16-bit outputs: one of the two flags, y then 8-byte aligned
+    assert gather_call(L, dt=0x200) == 0 and gather_call(L, dt=0x401) == 0 and gather_call(L, dt=0x600) == -4
+    assert gather_call(L, y=FAKE + 8, dt=0x200) == 0 and gather_call(L, y=FAKE + 4, dt=0x200) == -5
     assert gather_call(L, d_out=772, dt=0x101) == -5          # the source rows were bf16: whole 16-byte pieces of those
     # scratch of the stand-alone gather: too small or misaligned is refused before any launch
     need = L.lookupffn_workspace_bytes_gather(1000, 96)
