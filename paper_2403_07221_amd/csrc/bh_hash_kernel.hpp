@@ -38,6 +38,8 @@ struct BhArgs {
     uint32_t *packed;     // packed codes of the staged gather, or NULL
     float *weights;       // weighted variant: gather weights [n][k] (beside `codes`), or NULL
     float *wpk;           // weighted variant: the same table-major, [k][n_pad] (beside `packed`), or NULL
+    float *zout;          // plain variant: z of every token, [n][P*N] fp32, for weights of tables that straddle
+                          // tiles (any tau), or NULL
     long long n_pad;
     long long n;
     int d, k, tau, n_factors, P;
@@ -395,6 +397,17 @@ __global__ __launch_bounds__(kBhThreads) void bh_hash_kernel(BhArgs a)
                     emit(std::integral_constant<int, 16>{});
                 else
                     emit(std::integral_constant<int, 4>{});
+            }
+
+            // z itself, on request: register r of tile beta is coordinate 16*beta + g + 4r
+            if constexpr (!WEIGHTED) {
+                if (a.zout && t_ok) {
+                    float *zr = a.zout + (t * P + p) * N + g;
+#pragma unroll
+                    for (int beta = 0; beta < NT; ++beta)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) zr[16 * beta + 4 * r] = v[beta][r];
+                }
             }
 
             // ---- a4: sign bits into the tokens' bit strings: word w covers tiles 2w, 2w+1 --------

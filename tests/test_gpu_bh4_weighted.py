@@ -52,6 +52,12 @@ SHAPES = [
     (50, 600, 100, 8, 16, 6, "bf16"),    # six factors
     (2100, 768, 96, 8, 32, 4, "f32"),    # several token groups per wave
     (515, 130, 75, 4, 16, 4, "f32"),     # odd width: rows read one coordinate at a time; two projections
+    # tau other than 4, 8, 16: tables straddle the kernel's 16-coordinate tiles, the weights are formed from z
+    (300, 768, 170, 9, 64, 4, "f32"),    # the paper's RoBERTa-base row: two projections, a table straddles them
+    (129, 768, 100, 9, 16, 4, "bf16"),
+    (77, 64, 20, 3, 16, 4, "f32"),
+    (200, 512, 40, 13, 32, 4, "f32"),    # tau = 13 (the paper's ablation), two projections
+    (50, 1000, 1000, 1, 64, 2, "f32"),   # tau = 1
 ]
 
 
@@ -70,8 +76,8 @@ def test_bh_weighted_codes_exact_weights_close(n, d, k, tau, b, m, xdt):
     assert float(err.max()) <= TOL_W
 
 
-def test_bh_weighted_hash_leaves_plain_codes_unchanged_and_rejects_other_tau():
-    print("bh weighted hash: same codes as the plain BH hash; tau = 9 is refused", flush=True)
+def test_bh_weighted_hash_leaves_plain_codes_unchanged():
+    print("bh weighted hash: same codes as the plain BH hash", flush=True)
     n, d, k, tau, b = 333, 768, 96, 8, 32
     bm = synth.make_bmats(5, 1, 4, 1024, b)
     x = synth.make_x(6, n, d)
@@ -80,10 +86,8 @@ def test_bh_weighted_hash_leaves_plain_codes_unchanged_and_rejects_other_tau():
     plain = B.lookupffn_hash_bh(xd, bd, k, tau)
     torch.cuda.synchronize()
     assert torch.equal(codes, plain)
-    bm9 = synth.make_bmats(5, 1, 4, 1024, b)
-    with pytest.raises(B.LookupFFNError) as e:
-        B.lookupffn_hash_bh_weighted(xd, torch.from_numpy(bm9).cuda(), 100, 9)
-    assert e.value.status == -6
+    codes9, _ = B.lookupffn_hash_bh_weighted(xd, bd, 100, 9)      # weights through z in scratch memory
+    assert torch.equal(codes9, B.lookupffn_hash_bh(xd, bd, 100, 9))
 
 
 def check_forward(w, b, sample=None, m=4):
@@ -137,7 +141,8 @@ def test_forward_bh_weighted_equals_hash_then_gather():
     assert torch.equal(y, y_parts)
 
 
-@pytest.mark.parametrize("w,b,step", [(synth.C2, 64, 5), (synth.C2, 16, 7), (synth.C3, 32, 17), (synth.P7, 32, 13)],
+@pytest.mark.parametrize("w,b,step", [(synth.C2, 64, 5), (synth.C2, 16, 7), (synth.C3, 32, 17), (synth.P7, 32, 13),
+                                      (synth.P8, 64, 21)],     # P8: the paper's RoBERTa-base row, tau = 9
                          ids=lambda v: getattr(v, "name", str(v)))
 def test_forward_bh_weighted_full_size(w, b, step):
     print(f"bh weighted forward {w.name} block {b} ({w.n_tokens} tokens)", flush=True)
