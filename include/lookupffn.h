@@ -291,7 +291,7 @@ int lookupffn_timing_read_each(int which, double *ms_out, int64_t capacity, int6
  *   "lanes_per_token"  1,2,4,...,64   lanes (16 bytes each) that share one token's row slice
  *   "xcd_order"        1 / -1         force the XCD-sliced block order on / off
  *   "gather_path"      1 / 2 / 4      1: always the direct kernel; 2: the LDS-staged kernel whenever the shape
- *                                     allows it (tau 7 .. 10, k even), whatever the batch size; 4: the lagged ring
+ *                                     allows it (tau 7 .. 10, fp32 or prepared rows), whatever the batch size; 4: the lagged ring
  *                                     kernel where it exists (prepared tables, tau 7 or 8, plain sum), else as 2
  *   "ring_threads"     512 / 1024     workgroup size of the ring kernel
  *   "slice_lanes"      4 / 8          staged kernel: 64-byte column slices (4 lanes per token) where

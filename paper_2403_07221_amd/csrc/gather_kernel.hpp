@@ -45,6 +45,9 @@ struct GatherArgs {
     int ntb;           // token blocks in total; a token block = kGatherWaves * (64/LPT) tokens
     int xcd_mode;      // 1: block order is XCD-sliced (see above); 0: plain
     int codes_vec8;    // 1: k % 8 == 0 and codes (and weights) 16-byte aligned -> read 8 at a time
+    int code_stride;   // codes (and weights, and groups of 1 + tau shares) per token in the arrays; k unless
+                       // the launch covers only some of the tables
+    int accumulate;    // 1: the sums start from what y holds (fp32 y, fp32 rows) instead of zero
     // The 16-byte piece q of row r = (j << tau) + code in slice s sits at
     //   tables + (s / spp) * slice_stride + (s % spp) * LPT*16 + r * row_stride + q*16
     // row-major tables: spp = 1, slice_stride = LPT*16, row_stride = bytes of a row; prepared tables
@@ -144,7 +147,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a)
     const int vec = slice * LPT + (int)(lane % LPT);
     if (t >= a.n || vec >= a.nvec) return;  // no barrier below: early exit is safe
 
-    const uint16_t *crow = a.codes + t * a.k;
+    const uint16_t *crow = a.codes + t * a.code_stride;
     const char *tcol = a.tables + (size_t)((unsigned)slice / a.spp) * (size_t)a.slice_stride +
                        (size_t)((unsigned)slice % a.spp) * (LPT * 16u) + (size_t)(lane % LPT) * 16u;
     const uint32_t rmask = (1u << a.tau) - 1u;
@@ -158,10 +161,17 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a)
 
     Acc<KIND> acc;
     acc.zero();
+    if constexpr (KIND == 0) {
+        if (a.accumulate) {
+            const float4 y0 = *reinterpret_cast<const float4 *>(static_cast<const float *>(a.y) +
+                                                                 (size_t)t * a.d_out + (size_t)vec * 4);
+            acc.f[0] = y0.x, acc.f[1] = y0.y, acc.f[2] = y0.z, acc.f[3] = y0.w;
+        }
+    }
 
     int j0 = 0;
     if constexpr (WMODE == 2) {
-        const float *wp = a.weights + t * a.k * (tau + 1);
+        const float *wp = a.weights + t * a.code_stride * (tau + 1);
         const int np = tau + 1;
         for (int j = 0; j < k; ++j, wp += np) {
             const uint32_t g = crow[j] & rmask;
@@ -182,7 +192,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(GatherArgs a)
         }
         j0 = k;
     } else if constexpr (WMODE == 1) {
-        const float *wrow = a.weights + t * a.k;
+        const float *wrow = a.weights + t * a.code_stride;
         if (a.codes_vec8) {
             const uint4 *c8 = reinterpret_cast<const uint4 *>(crow);
             const float4 *w4 = reinterpret_cast<const float4 *>(wrow);

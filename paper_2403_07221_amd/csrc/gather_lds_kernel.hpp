@@ -1,4 +1,5 @@
-// LDS-staged gather for tables of 2^7 .. 2^10 rows (k even, fp32 rows):
+// LDS-staged gather for tables of 2^7 .. 2^10 rows (k even, fp32 rows; for an odd k the host gives this
+// kernel the first k - 1 tables and lets the direct kernel add the last one onto its sums):
 //   y[t][:] = sum_{j<k} tables[j][code[t][j]][:]        (Sec. 3.1, eq. "lookup")
 //
 // With tau = 8 a table has only 256 rows, so a batch of thousands of tokens

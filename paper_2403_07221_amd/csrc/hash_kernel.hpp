@@ -680,8 +680,7 @@ __global__ __launch_bounds__(256) void weights_from_z_kernel(const float *z, lon
 // n) are contiguous; grid-stride over tiles.
 //   ZERO_PAD: also write zeros to the token padding [n, n_pad) (the packed codes need valid rows there).
 template <bool ZERO_PAD, class F>
-__device__ __forceinline__ void transpose_tiles(const uint32_t *src, uint32_t *dst, long long n, long long n_pad,
-                                                long long m, F f)
+__device__ __forceinline__ void transpose_tiles(uint32_t *dst, long long n, long long n_pad, long long m, F word)
 {
     __shared__ uint32_t tile[64][65];
     const long long n_out = ZERO_PAD ? n_pad : n;
@@ -691,8 +690,7 @@ __device__ __forceinline__ void transpose_tiles(const uint32_t *src, uint32_t *d
         const long long t0 = (tl / tiles_m) * 64, j0 = (tl % tiles_m) * 64;
         __syncthreads();
 #pragma unroll
-        for (int r = r0; r < 64; r += 4)
-            tile[r][c] = (t0 + r < n && j0 + c < m) ? f(src[(t0 + r) * m + j0 + c]) : 0u;
+        for (int r = r0; r < 64; r += 4) tile[r][c] = (t0 + r < n && j0 + c < m) ? word(t0 + r, j0 + c) : 0u;
         __syncthreads();
 #pragma unroll
         for (int r = r0; r < 64; r += 4)
@@ -705,21 +703,33 @@ __device__ __forceinline__ void transpose_tiles(const uint32_t *src, uint32_t *d
 __global__ __launch_bounds__(256) void repack_shares_kernel(const float *shares, float *spk, long long n,
                                                             long long n_pad, long long m)
 {
-    transpose_tiles<false>(reinterpret_cast<const uint32_t *>(shares), reinterpret_cast<uint32_t *>(spk), n, n_pad, m,
-                           [](uint32_t w) { return w; });
+    const uint32_t *src = reinterpret_cast<const uint32_t *>(shares);
+    transpose_tiles<false>(reinterpret_cast<uint32_t *>(spk), n, n_pad, m,
+                           [=](long long t, long long c) { return src[t * m + c]; });
 }
 
-// ABI codes [n][k] (k even, rows 4-byte aligned) -> packed[k/2][n_pad]: two codes per word, reduced modulo
-// 2^tau and scaled by 2^shift (for a stand-alone gather call that takes the LDS-staged kernel, and for the
-// staged kernel's 64-byte-slice form, which needs shift 6); zeros in the token padding
+// ABI codes [n][k] -> packed[k/2][n_pad]: two codes per word, reduced modulo 2^tau and scaled by 2^shift (for
+// a stand-alone gather call that takes the LDS-staged kernel, and for the staged kernel's 64-byte-slice
+// form, which needs shift 6); zeros in the token padding.  Even k with 4-byte aligned codes is read a pair
+// at a time; an odd k is read code by code and its last table is left out (the caller adds it otherwise).
 __global__ __launch_bounds__(256) void repack_codes_kernel(const uint16_t *codes, uint32_t *packed, long long n,
                                                            long long n_pad, int k, int tau, int shift)
 {
     const uint32_t cmask = (1u << tau) - 1u;
-    transpose_tiles<true>(reinterpret_cast<const uint32_t *>(codes), packed, n, n_pad, (long long)(k / 2),
-                          [=](uint32_t pair) {
-                              return ((pair & cmask) << shift) | (((pair >> 16) & cmask) << (16 + shift));
-                          });
+    auto scale = [=](uint32_t lo, uint32_t hi) { return ((lo & cmask) << shift) | ((hi & cmask) << (16 + shift)); };
+    const long long m = k / 2;
+    if (k & 1) {
+        transpose_tiles<true>(packed, n, n_pad, m, [=](long long t, long long c) {
+            const uint16_t *p = codes + t * k + 2 * c;
+            return scale(p[0], p[1]);
+        });
+    } else {
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(codes);
+        transpose_tiles<true>(packed, n, n_pad, m, [=](long long t, long long c) {
+            const uint32_t pair = src[t * m + c];
+            return scale(pair, pair >> 16);
+        });
+    }
 }
 #endif
 

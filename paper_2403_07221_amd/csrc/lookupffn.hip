@@ -418,7 +418,7 @@ int log2_pad(int d)
 }
 
 bool dtype_ok(int t) { return t == LFFN_F32 || t == LFFN_BF16 || t == LFFN_F16; }
-static_assert(LFFN_F32 == kElemF32 && LFFN_BF16 == kElemBF16 && LFFN_F16 == kElemF16, "the ABI's dtype codes are the kernels' element kinds");
+static_assert((int)LFFN_F32 == (int)kElemF32 && (int)LFFN_BF16 == (int)kElemBF16 && (int)LFFN_F16 == (int)kElemF16, "the ABI's dtype codes are the kernels' element kinds");
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 int gcd(int a, int b) { return b ? gcd(b, a % b) : a; }
 int64_t round256(int64_t b) { return (b + 255) & ~int64_t(255); }
@@ -809,6 +809,8 @@ struct LdsPlan {
                     // write shift 7; a plan with shift 6 takes its codes through the re-pack kernel.
     unsigned grid = 0;
     size_t lds = 0;
+    int tail = 0;   // tables left to the direct kernel, which adds them onto the staged kernel's y: 1 when
+                    // k is odd (the staged kernel takes its tables in pairs), else 0
 };
 
 int plan_gather_lds(int64_t n, int k, int tau, int d_out, const TableRef &T, Mode mode, const Options &opt,
@@ -818,7 +820,11 @@ int plan_gather_lds(int64_t n, int k, int tau, int d_out, const TableRef &T, Mod
     if (opt.gather_path == 1) return LFFN_OK;
     if (T.kind) return LFFN_OK;  // the staged kernel reads fp32 rows: 16-bit tables take it once prepared
     const int rows = 1 << tau;
-    if (tau < 7 || tau > 10 || k % 2 != 0) return LFFN_OK;
+    if (tau < 7 || tau > 10) return LFFN_OK;
+    // an odd k: the first k - 1 tables staged, the last one added by the direct kernel, which re-reads the
+    // fp32 sums (so not with 16-bit outputs, which are rounded once from the complete sum)
+    const int tail = k & 1;
+    if (tail && (k < 3 || T.y_kind != 0)) return LFFN_OK;
     // column slices: 128 bytes (8 lanes per token) up to tau = 8; 64 bytes from tau = 9 on (two 512-row
     // tables per stage and half the copy volume per token measured faster than one per stage; tau = 10
     // fits a 64 KB buffer only this way).  The 64-byte form exists for tau >= 8.
@@ -839,7 +845,7 @@ int plan_gather_lds(int64_t n, int k, int tau, int d_out, const TableRef &T, Mod
     a = GatherLdsArgs{};
     a.n = n;
     a.n_pad = packed_n_pad(n);
-    a.k = k;
+    a.k = k - tail;
     a.tau = tau;
     a.d_out = d_out;
     const uint32_t row_bytes = (uint32_t)d_out * 4;  // of the fp32 rows the kernel reads
@@ -878,6 +884,7 @@ int plan_gather_lds(int64_t n, int k, int tau, int d_out, const TableRef &T, Mod
     p->lds = gather_lds_bytes(tau, sw);
     if (p->lds < (size_t)kLdsMinBytes) p->lds = kLdsMinBytes;
     p->grid = (unsigned)cus;
+    p->tail = tail;
     p->use = true;
     return LFFN_OK;
 }
@@ -946,24 +953,27 @@ int launch_gather_lds(const LdsPlan &p, const uint32_t *packed, const float *wpk
     return LFFN_OK;
 }
 
+// j_first > 0: only the tables [j_first, k) are summed, onto what y already holds (fp32 y and fp32 rows).
 int launch_gather_direct(const uint16_t *codes, const float *weights, const TableRef &T, void *y, int64_t n,
-                         int k, int tau, int d_out, Mode mode, hipStream_t s, const Options &opt)
+                         int k, int tau, int d_out, Mode mode, hipStream_t s, const Options &opt, int j_first = 0)
 {
     const int esz = T.kind ? 2 : 4;
+    if (j_first < 0 || j_first >= k || (j_first && (T.kind || T.y_kind))) return LFFN_E_UNSUPPORTED;
+    if ((mode != kPlain) != (weights != nullptr)) return LFFN_E_NULL;
     GatherArgs a{};
-    a.codes = codes;
-    a.weights = weights;
-    a.tables = T.p;
+    a.codes = codes + j_first;
+    a.weights = weights ? weights + (size_t)j_first * (mode == kProbes ? tau + 1 : 1) : nullptr;
     a.y = y;
     a.y_kind = T.y_kind;
     a.n = n;
-    a.k = k;
+    a.k = k - j_first;
+    a.code_stride = k;
+    a.accumulate = j_first > 0;
     a.tau = tau;
     a.d_out = d_out;
     const uint32_t row_bytes = (uint32_t)d_out * esz;
     a.nvec = (int)(row_bytes / 16);
-    a.codes_vec8 = (k % 8 == 0) && aligned(codes, 16) && (!weights || aligned(weights, 16));
-    if ((mode != kPlain) != (weights != nullptr)) return LFFN_E_NULL;
+    a.codes_vec8 = j_first == 0 && (k % 8 == 0) && aligned(codes, 16) && (!weights || aligned(weights, 16));
 
     int lpt = opt.lanes_per_token;
     if (lpt == 0) {
@@ -982,6 +992,7 @@ int launch_gather_direct(const uint16_t *codes, const float *weights, const Tabl
         a.row_stride = row_bytes;
         a.slice_stride = (unsigned long long)lpt * 16;
     }
+    a.tables = T.p + ((size_t)j_first << tau) * a.row_stride;  // row (j << tau) + code of either layout
     const int64_t ntb = (n + (int64_t)kGatherWaves * tpw - 1) / ((int64_t)kGatherWaves * tpw);
     if (ntb > (int64_t(1) << 30)) return LFFN_E_SIZE;
     a.ntb = (int)ntb;
@@ -1159,7 +1170,11 @@ int gather_from_abi(Mode mode, const uint16_t *codes, const float *weights, cons
                 rc = launch_repack_weights(weights, wpk, n, plan.a.n_pad, (int64_t)k * (mode == kProbes ? tau + 1 : 1), s);
                 if (rc != LFFN_OK) return rc;
             }
-            return launch_gather_lds(plan, packed, wpk, T, y, mode, s);
+            rc = launch_gather_lds(plan, packed, wpk, T, y, mode, s);
+            if (rc != LFFN_OK || !plan.tail) return rc;
+            rc = launch_gather_direct(codes, weights, T, y, n, k, tau, d_out, mode, s, opt, k - plan.tail);
+            t_last_gather = "gather_lds_kernel";  // the one that did all tables but the last
+            return rc;
         }
     }
     return launch_gather_direct(codes, weights, T, y, n, k, tau, d_out, mode, s, opt);
@@ -1421,7 +1436,7 @@ int forward_core(const HashSpec &h, Mode mode, const void *x, const void *tables
     RingPlan ring;
     rc = plan_gather_ring(n, k, tau, d_out, T, mode, opt, &ring);
     if (rc != LFFN_OK) return rc;
-    if (!ring.use && plan.use && plan.shift == kPackedShift && mode != kProbes && !zb) {
+    if (!ring.use && plan.use && !plan.tail && plan.shift == kPackedShift && mode != kProbes && !zb) {
         HashOut out;
         const int64_t pb = packed_bytes(n, k), wb = mode == kWeighted ? wpk_bytes(n, k) : 0;
         out.packed = sc.take<uint32_t>(pb);

@@ -198,7 +198,7 @@ def test_gather_every_launch_shape(lpt, xcd):
 
 
 LDS_SHAPES = [
-    # n, k, tau, d_out, table dtype     (gather_path = 2 forces the LDS-staged kernel: tau 7 .. 10, k even)
+    # n, k, tau, d_out, table dtype     (gather_path = 2 forces the LDS-staged kernel: tau 7 .. 10; odd k has a file of its own)
     (1003, 96, 8, 768, "f32"),       # three slices per XCD, ragged chunks
     (1003, 96, 8, 768, "bf16"),
     (16384, 32, 8, 768, "f32"),      # the benchmark's split: 11/11/10 workgroups per slice, 13 tokens per lane

@@ -110,7 +110,7 @@ def test_gather_probes_first_probe_only_equals_the_plain_gather(lpt):
 
 
 LDS_SHAPES = [
-    # n, k, tau, d_out      (gather_path = 2 forces the LDS-staged kernel: fp32 tables, tau 7 .. 10, k even)
+    # n, k, tau, d_out      (gather_path = 2 forces the LDS-staged kernel: fp32 tables, tau 7 .. 10; odd k has a file of its own)
     (1003, 96, 8, 768),      # 128-byte slices, two tables per stage
     (16384, 8, 8, 768),      # 13 token slots per lane
     (5000, 24, 7, 200),      # 128-row tables, ragged last slice

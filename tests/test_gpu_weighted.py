@@ -160,7 +160,7 @@ def test_gather_weighted_unit_weights_equal_the_plain_gather(lpt):
 
 
 LDS_SHAPES = [
-    # n, k, tau, d_out      (gather_path = 2 forces the LDS-staged kernel: fp32 tables, tau 7 .. 10, k even)
+    # n, k, tau, d_out      (gather_path = 2 forces the LDS-staged kernel: fp32 tables, tau 7 .. 10; odd k has a file of its own)
     (1003, 96, 8, 768),      # three slices per XCD, ragged chunks
     (16384, 32, 8, 768),     # the benchmark's split, two chunks of 6 tokens per lane
     (5000, 24, 7, 200),      # ragged last slice, 128-row tables
