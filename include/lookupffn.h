@@ -301,9 +301,11 @@ int lookupffn_timing_read_each(int which, double *ms_out, int64_t capacity, int6
  *                                     kernel of lookupffn_forward_stack when the shape is that kernel's and no
  *                                     hash or gather path is forced (default 512; -1: never)
  *   "token_slots"      1 .. 32        staged kernels: at most this many tokens per lane group and chunk
- *   "hash_path"        1              always the generic hash kernel (default: the two-layout
- *                                     kernel when d_pad = 1024 and n_rounds <= 4)
- *   "hash_blocks"      1..65536       grid cap of the d_pad = 1024 hash kernel
+ *   "hash_path"        1 / 2          1: always the generic hash kernel; 2: never the four-tokens-per-wavefront
+ *                                     kernel (default for d_pad = 1024 and n_rounds <= 4: that kernel when d is
+ *                                     a multiple of 16 and only codes are asked for, else the two-layout
+ *                                     one-token-per-wavefront kernel)
+ *   "hash_blocks"      1..65536       grid cap of the d_pad = 1024 hash kernels
  * Returns LFFN_E_SIZE for an unknown key or a value outside the documented set.  Process-wide; a call
  * reads the knobs once when it starts.
  */

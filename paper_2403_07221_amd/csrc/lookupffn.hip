@@ -19,10 +19,11 @@
 #include "gather_lds_kernel.hpp"
 #include "gather_ring_kernel.hpp"
 #include "hash_kernel.hpp"
+#include "hash_x4_kernel.hpp"
 
 // Build parts.  This file compiles whole (LFFN_PART undefined) or as parts that are linked together, so
 // that the kernel families compile side by side: part 0 holds the C ABI, the host logic and the hash and
-// re-pack kernels; parts 1 .. 11 hold one family of kernel launchers each (declared just below).  No
+// re-pack kernels; parts 1 .. 14 hold one family of kernel launchers each (declared just below).  No
 // kernel is instantiated in two parts.
 #ifdef LFFN_PART
 #define LFFN_HAS(p) (LFFN_PART == (p))
@@ -53,6 +54,9 @@ int gather_ring_part(int threads, int tok, const GatherRingArgs &a, dim3 grid, h
 // part 13: hash and gather of a few tokens, one or several chained layers, in one launch
 int forward_stack_part(int n_rounds, int kind, const StackArgs &a, dim3 grid, int threads, size_t lds, hipStream_t s);
 int forward_stack_load();
+// part 14: the d_pad = 1024 hash with four tokens per wavefront (codes only)
+int hash_x4_part(int n_rounds, const HashArgs &a, dim3 grid, size_t lds, hipStream_t s);
+int hash_x4_load();
 // parts 4 .. 11: the BH hash kernel.  Plain: d_pad = 64 .. 256, 512, 1024; weighted: d_pad = 64 .. 256, then
 // 512 and 1024 each split by the way the rows are read (four coordinates at a time or one by one): the
 // wide weighted kernels are the slowest to compile by far
@@ -283,9 +287,9 @@ template <int R>
 int launch_forward_stack_r(int kind, const StackArgs &a, dim3 grid, int threads, size_t lds, hipStream_t s)
 {
     switch (kind) {
-        case kElemF32: hipLaunchKernelGGL((forward_stack_kernel<R, kElemF32>), grid, dim3(threads), lds, s, a); break;
-        case kElemBF16: hipLaunchKernelGGL((forward_stack_kernel<R, kElemBF16>), grid, dim3(threads), lds, s, a); break;
-        case kElemF16: hipLaunchKernelGGL((forward_stack_kernel<R, kElemF16>), grid, dim3(threads), lds, s, a); break;
+        case kElemF32: hipLaunchKernelGGL((forward_stack_kernel<R, kElemF32>), grid, dim3(kX4Threads), lds, s, a); break;
+        case kElemBF16: hipLaunchKernelGGL((forward_stack_kernel<R, kElemBF16>), grid, dim3(kX4Threads), lds, s, a); break;
+        case kElemF16: hipLaunchKernelGGL((forward_stack_kernel<R, kElemF16>), grid, dim3(kX4Threads), lds, s, a); break;
         default: return LFFN_E_DTYPE;
     }
     return LFFN_OK;
@@ -308,6 +312,43 @@ int forward_stack_load()
     hipFuncAttributes attr;
     hipError_t e = hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(forward_stack_kernel<3, kElemF32>));
     return e == hipSuccess ? LFFN_OK : hip_fail(e, "hipFuncGetAttributes(forward_stack_kernel)");
+}
+#endif
+
+#if LFFN_HAS(14)
+template <int MFULL>
+int launch_hash_x4_r(int n_rounds, const HashArgs &a, dim3 grid, size_t lds, hipStream_t s)
+{
+    switch (n_rounds) {
+        case 1: hipLaunchKernelGGL((hash1024x4_kernel<1, MFULL>), grid, dim3(kX4Threads), lds, s, a); break;
+        case 2: hipLaunchKernelGGL((hash1024x4_kernel<2, MFULL>), grid, dim3(kX4Threads), lds, s, a); break;
+        case 3: hipLaunchKernelGGL((hash1024x4_kernel<3, MFULL>), grid, dim3(kX4Threads), lds, s, a); break;
+        case 4: hipLaunchKernelGGL((hash1024x4_kernel<4, MFULL>), grid, dim3(kX4Threads), lds, s, a); break;
+        default: return LFFN_E_UNSUPPORTED;
+    }
+    return LFFN_OK;
+}
+
+int hash_x4_part(int n_rounds, const HashArgs &a, dim3 grid, size_t lds, hipStream_t s)
+{
+    // built for the row lengths of the paper's models (d = 768 and 1024, three rounds); any other multiple of
+    // 16 in range takes the form with run-time bounds
+    if (a.d == 768 && n_rounds == 3) {
+        hipLaunchKernelGGL((hash1024x4_kernel<3, 48>), grid, dim3(kX4Threads), lds, s, a);
+        return LFFN_OK;
+    }
+    if (a.d == 1024 && n_rounds == 3) {
+        hipLaunchKernelGGL((hash1024x4_kernel<3, 64>), grid, dim3(kX4Threads), lds, s, a);
+        return LFFN_OK;
+    }
+    return launch_hash_x4_r<0>(n_rounds, a, grid, lds, s);
+}
+
+int hash_x4_load()
+{
+    hipFuncAttributes attr;
+    hipError_t e = hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(hash1024x4_kernel<3, 0>));
+    return e == hipSuccess ? LFFN_OK : hip_fail(e, "hipFuncGetAttributes(hash1024x4_kernel)");
 }
 #endif
 
@@ -431,7 +472,7 @@ struct Options {
     int xcd_order = 0;        // 0 = default, 1 = on, -1 = off
     int gather_path = 0;      // 0 = choose, 1 = direct kernel, 2 = the staged kernel whenever the shape allows,
                               // 4 = the ring kernel whenever the shape allows (else as 2)
-    int hash_path = 0;        // 0 = choose, 1 = generic kernel only
+    int hash_path = 0;        // 0 = choose, 1 = generic kernel only, 2 = no four-tokens-per-wave kernel
     int hash_blocks = 0;      // 0 = default grid cap of the d_pad = 1024 hash kernel
     int slice_lanes = 0;      // 0 = choose, 4 = 64-byte column slices in the staged gather where possible
     int token_slots = 0;      // 0 = choose, else the most token slots per lane of the staged gather
@@ -705,6 +746,23 @@ bool hash_extents_ok(const HashOut &o, int64_t n, int k, int tau, int64_t n_pad,
     return true;
 }
 
+int device_cus(int *cus)
+{
+    static std::mutex mu;
+    static std::map<int, int> cache;
+    int dev = 0;
+    LFFN_HIP(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lk(mu);
+    auto it = cache.find(dev);
+    if (it == cache.end()) {
+        int n = 0;
+        LFFN_HIP(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev));
+        it = cache.emplace(dev, n).first;
+    }
+    *cus = it->second;
+    return LFFN_OK;
+}
+
 int launch_hash(const void *x, const int8_t *signs, const HashOut &out, int64_t n, int d, int k, int tau,
                 int n_rounds, int x_dtype, hipStream_t s, const Options &opt)
 {
@@ -729,6 +787,25 @@ int launch_hash(const void *x, const int8_t *signs, const HashOut &out, int64_t 
     if (!a.codes && !a.packed) return LFFN_E_NULL;
     if (out.probes && (!a.codes || !a.weights)) return LFFN_E_UNSUPPORTED;  // shares exist in the ABI layout only
     TimedLaunch tl(0, s);
+    // d_pad = 1024, codes only, up to four rounds: four tokens per wavefront, no LDS transposes
+    // (a lane holds every 16th coordinate: d a multiple of 16 makes "in range" a per-register question)
+    if (opt.hash_path == 0 && L == 10 && d % 16 == 0 && n_rounds >= 1 && n_rounds <= 4 && !out.weights &&
+        aligned(signs, 16) && hx4_lds_bytes(a.P, n_rounds) <= 64 * 1024) {
+        // two workgroups per compute unit fill it (two waves per SIMD); a larger batch is worked through in
+        // several groups of four tokens per wave, the next group's rows in flight during a transform
+        int cus = 0;
+        int rc = device_cus(&cus);
+        if (rc != LFFN_OK) return rc;
+        const int64_t groups = (n + kX4Tokens - 1) / kX4Tokens;
+        int64_t blocks = (groups + kX4Waves - 1) / kX4Waves;
+        const int64_t cap = opt.hash_blocks ? opt.hash_blocks : 2 * (int64_t)cus;
+        if (blocks > cap) blocks = cap;
+        rc = lffn_host::hash_x4_part(n_rounds, a, dim3((unsigned)blocks), hx4_lds_bytes(a.P, n_rounds), s);
+        if (rc != LFFN_OK) return rc;
+        LFFN_HIP(hipGetLastError());
+        tl.done();
+        return LFFN_OK;
+    }
     // d_pad = 1024 with up to four rounds: the two-layout kernel (needs 16-byte aligned signs, and
     // rows that start on 16-byte boundaries when it loads them as vectors)
     const size_t xrow = (size_t)d * (a.x_kind ? 2 : 4);
@@ -768,23 +845,6 @@ int launch_hash(const void *x, const int8_t *signs, const HashOut &out, int64_t 
 }
 
 constexpr int kLdsMinBytes = 84 * 1024;  // more than half of the 160 KB LDS: one workgroup per CU
-
-int device_cus(int *cus)
-{
-    static std::mutex mu;
-    static std::map<int, int> cache;
-    int dev = 0;
-    LFFN_HIP(hipGetDevice(&dev));
-    std::lock_guard<std::mutex> lk(mu);
-    auto it = cache.find(dev);
-    if (it == cache.end()) {
-        int n = 0;
-        LFFN_HIP(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev));
-        it = cache.emplace(dev, n).first;
-    }
-    *cus = it->second;
-    return LFFN_OK;
-}
 
 // Largest number of tokens a workgroup gets in one piece, mirroring the kernel's split.
 int64_t lds_tokens_per_block(int64_t n, int n_units, int token_splits, int Bx)
@@ -1579,6 +1639,8 @@ int lookupffn_init(void)
                     if (rc != LFFN_OK && rc != LFFN_E_UNSUPPORTED) return rc;
                 }
             }
+    rc = lffn_host::hash_x4_load();
+    if (rc != LFFN_OK) return rc;
     rc = lffn_host::forward_stack_load();
     if (rc != LFFN_OK) return rc;
     {
@@ -1941,7 +2003,7 @@ int lookupffn_set_option(const char *key, int value)
         return LFFN_OK;
     }
     if (!std::strcmp(key, "hash_path")) {
-        if (value < 0 || value > 1) return LFFN_E_SIZE;
+        if (value < 0 || value > 2) return LFFN_E_SIZE;
         g_opt.hash_path = value;
         return LFFN_OK;
     }
