@@ -82,6 +82,71 @@ __device__ __forceinline__ void x4_exchange(float (&v)[kX4Regs], float s)
     for (int g = 0; g < LIVE; g += 16) x4_exchange16<BIT>(&v[g], s);
 }
 
+// value of x in the lane whose c differs in bit BIT
+template <int BIT>
+__device__ __forceinline__ float x4_partner(float x)
+{
+    constexpr int ctrl = BIT == 0 ? 0xB1 : BIT == 1 ? 0x4E : BIT == 2 ? 0x141 : 0x128;  // the exchanges' controls
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), ctrl, 0xF, 0xF, true));
+}
+
+// Gather weights of the tables in projection p for tau = 2^SH (see the call).  Register m holds 16 >> SH tables
+// per token; table j's weight goes to weights[t][j] or, table-major, to wpk[j][t].  After the all-reduce every
+// lane of a table's run holds its weight, so for tau >= 4 lane x of the run picks the weight of register
+// m0 + x of a block of S = min(8, tau) registers: one store per block, every lane a different (table, token),
+// instead of one store per register from one lane in tau.
+template <int SH>
+__device__ __forceinline__ void x4_weights(const HashArgs &a, const float (&v)[kX4Regs], int p, int n_reg, unsigned c,
+                                           long long t, bool t_ok)
+{
+    constexpr int PER_REG = 16 >> SH;                       // tables per register
+    constexpr int TAU = 1 << SH;
+    constexpr int S = TAU >= 8 ? 8 : TAU >= 4 ? 4 : 1;      // registers per store
+    const unsigned x = c & (unsigned)(TAU - 1);             // position in the table's run of lanes
+    const int jl = p * (1024 >> SH) + (int)(c >> SH) + (S > 1 ? (int)x * PER_REG : 0);  // this lane's table in block 0
+    const bool writer = t_ok && x < (unsigned)S;
+    float *dst = a.wpk ? a.wpk + wpk_index(jl, t, a.n_pad) : a.weights + t * a.k + jl;
+    const long long step = a.wpk ? (long long)PER_REG * a.n_pad : PER_REG;   // elements from one register's table to the next's
+    // eight registers at a time: their reduction chains are independent and interleave
+#pragma unroll
+    for (int m0 = 0; m0 < kX4Regs; m0 += 8) {
+        if (m0 < n_reg) {
+            float sum[8], q[8], w[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                sum[u] = __builtin_fabsf(v[m0 + u]);
+                q[u] = 1.0f + __builtin_amdgcn_exp2f(sum[u] * -2.885390082f);  // exp(-2 |z|) = 2^(-2 |z| log2 e)
+            }
+            if constexpr (SH > 0) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u) { sum[u] += x4_partner<0>(sum[u]); q[u] *= x4_partner<0>(q[u]); }
+            }
+            if constexpr (SH > 1) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u) { sum[u] += x4_partner<1>(sum[u]); q[u] *= x4_partner<1>(q[u]); }
+            }
+            if constexpr (SH > 2) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u) { sum[u] += x4_partner<2>(sum[u]); q[u] *= x4_partner<2>(q[u]); }
+            }
+            if constexpr (SH > 3) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u) { sum[u] += x4_partner<3>(sum[u]); q[u] *= x4_partner<3>(q[u]); }
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) w[u] = sum[u] * __builtin_amdgcn_rcpf(q[u]);  // q >= 1: no overflow; reciprocal good to 1 ulp
+#pragma unroll
+            for (int b0 = 0; b0 < 8; b0 += S) {
+                float ws = w[b0];
+#pragma unroll
+                for (int u = 1; u < S; ++u) ws = x == (unsigned)u ? w[b0 + u] : ws;
+                const int mb = m0 + b0;                                      // first register of the block
+                if (writer && jl + mb * PER_REG < a.k) dst[mb * step] = ws;
+            }
+        }
+    }
+}
+
 // lane order -> c order inside every 16-bit group of w: the four bits of the odd nibbles reversed
 __device__ __forceinline__ uint32_t x4_c_order(uint32_t w)
 {
@@ -133,7 +198,7 @@ __device__ __forceinline__ void x4_reg_stage(float (&v)[kX4Regs])
 // The kernel keeps two sets of rows in registers (the one being transformed and the next one, in flight), about
 // 230 registers per lane: two waves per SIMD, which is enough because a wave's instructions are independent
 // for 64 registers at a stretch; the grid is sized so that a wave works through several groups of tokens.
-template <int R, int MFULL>
+template <int R, int MFULL, bool WEIGHTED>
 __global__ __launch_bounds__(kX4Threads) void hash1024x4_kernel(HashArgs a)
 {
     constexpr int N = 1024;
@@ -279,6 +344,21 @@ __global__ __launch_bounds__(kX4Threads) void hash1024x4_kernel(HashArgs a)
             // ---- a4: sign bits.  Mask m = bits [16 m, 16 m + 16) of each token's string, lane order ----
             uint32_t lo = 0, hi = 0;
             x4_collect_masks<0>(v, lo, hi);
+            // ---- weighted variant (Sec. 4): w_j = |z_j|_1 / prod_b (1 + exp(-2 |z_jb|)).  tau divides 16
+            // (host-checked), so a table's coordinates are tau neighbouring c of one register: sum and product
+            // are all-reduced over those lanes with the exchanges' DPP controls, and the lane with the
+            // table's first coordinate stores sum * (1 / product).
+            if constexpr (WEIGHTED) {
+                const long long bits_left = (long long)a.k * a.tau - (long long)p * N;
+                const int n_reg = bits_left >= N ? kX4Regs : (int)((bits_left + 15) >> 4);  // registers that hold table coordinates
+                switch (a.tau) {
+                    case 1: x4_weights<0>(a, v, p, n_reg, c, t, t_ok); break;
+                    case 2: x4_weights<1>(a, v, p, n_reg, c, t, t_ok); break;
+                    case 4: x4_weights<2>(a, v, p, n_reg, c, t, t_ok); break;
+                    case 8: x4_weights<3>(a, v, p, n_reg, c, t, t_ok); break;
+                    default: x4_weights<4>(a, v, p, n_reg, c, t, t_ok); break;
+                }
+            }
             lo = x4_c_order(lo);
             hi = x4_c_order(hi);
             // lane m: halfword m of projection p of tokens 0, 1 (lo) and 2, 3 (hi)

@@ -316,14 +316,14 @@ int forward_stack_load()
 #endif
 
 #if LFFN_HAS(14)
-template <int MFULL>
+template <int MFULL, bool WEIGHTED>
 int launch_hash_x4_r(int n_rounds, const HashArgs &a, dim3 grid, size_t lds, hipStream_t s)
 {
     switch (n_rounds) {
-        case 1: hipLaunchKernelGGL((hash1024x4_kernel<1, MFULL>), grid, dim3(kX4Threads), lds, s, a); break;
-        case 2: hipLaunchKernelGGL((hash1024x4_kernel<2, MFULL>), grid, dim3(kX4Threads), lds, s, a); break;
-        case 3: hipLaunchKernelGGL((hash1024x4_kernel<3, MFULL>), grid, dim3(kX4Threads), lds, s, a); break;
-        case 4: hipLaunchKernelGGL((hash1024x4_kernel<4, MFULL>), grid, dim3(kX4Threads), lds, s, a); break;
+        case 1: hipLaunchKernelGGL((hash1024x4_kernel<1, MFULL, WEIGHTED>), grid, dim3(kX4Threads), lds, s, a); break;
+        case 2: hipLaunchKernelGGL((hash1024x4_kernel<2, MFULL, WEIGHTED>), grid, dim3(kX4Threads), lds, s, a); break;
+        case 3: hipLaunchKernelGGL((hash1024x4_kernel<3, MFULL, WEIGHTED>), grid, dim3(kX4Threads), lds, s, a); break;
+        case 4: hipLaunchKernelGGL((hash1024x4_kernel<4, MFULL, WEIGHTED>), grid, dim3(kX4Threads), lds, s, a); break;
         default: return LFFN_E_UNSUPPORTED;
     }
     return LFFN_OK;
@@ -331,23 +331,23 @@ int launch_hash_x4_r(int n_rounds, const HashArgs &a, dim3 grid, size_t lds, hip
 
 int hash_x4_part(int n_rounds, const HashArgs &a, dim3 grid, size_t lds, hipStream_t s)
 {
+    const bool weighted = a.weights || a.wpk;
     // built for the row lengths of the paper's models (d = 768 and 1024, three rounds); any other multiple of
     // 16 in range takes the form with run-time bounds
-    if (a.d == 768 && n_rounds == 3) {
-        hipLaunchKernelGGL((hash1024x4_kernel<3, 48>), grid, dim3(kX4Threads), lds, s, a);
+    if (n_rounds == 3 && (a.d == 768 || a.d == 1024)) {
+        if (a.d == 768 && weighted) hipLaunchKernelGGL((hash1024x4_kernel<3, 48, true>), grid, dim3(kX4Threads), lds, s, a);
+        else if (a.d == 768) hipLaunchKernelGGL((hash1024x4_kernel<3, 48, false>), grid, dim3(kX4Threads), lds, s, a);
+        else if (weighted) hipLaunchKernelGGL((hash1024x4_kernel<3, 64, true>), grid, dim3(kX4Threads), lds, s, a);
+        else hipLaunchKernelGGL((hash1024x4_kernel<3, 64, false>), grid, dim3(kX4Threads), lds, s, a);
         return LFFN_OK;
     }
-    if (a.d == 1024 && n_rounds == 3) {
-        hipLaunchKernelGGL((hash1024x4_kernel<3, 64>), grid, dim3(kX4Threads), lds, s, a);
-        return LFFN_OK;
-    }
-    return launch_hash_x4_r<0>(n_rounds, a, grid, lds, s);
+    return weighted ? launch_hash_x4_r<0, true>(n_rounds, a, grid, lds, s) : launch_hash_x4_r<0, false>(n_rounds, a, grid, lds, s);
 }
 
 int hash_x4_load()
 {
     hipFuncAttributes attr;
-    hipError_t e = hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(hash1024x4_kernel<3, 0>));
+    hipError_t e = hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(hash1024x4_kernel<3, 0, false>));
     return e == hipSuccess ? LFFN_OK : hip_fail(e, "hipFuncGetAttributes(hash1024x4_kernel)");
 }
 #endif
@@ -787,9 +787,11 @@ int launch_hash(const void *x, const int8_t *signs, const HashOut &out, int64_t 
     if (!a.codes && !a.packed) return LFFN_E_NULL;
     if (out.probes && (!a.codes || !a.weights)) return LFFN_E_UNSUPPORTED;  // shares exist in the ABI layout only
     TimedLaunch tl(0, s);
-    // d_pad = 1024, codes only, up to four rounds: four tokens per wavefront, no LDS transposes
+    // d_pad = 1024, up to four rounds, codes alone or with the gather weights of a tau that divides 16 (a table is
+    // then a run of lanes of one register): four tokens per wavefront, no LDS transposes
     // (a lane holds every 16th coordinate: d a multiple of 16 makes "in range" a per-register question)
-    if (opt.hash_path == 0 && L == 10 && d % 16 == 0 && n_rounds >= 1 && n_rounds <= 4 && !out.weights &&
+    const bool x4_weights_ok = !out.weights || (!out.probes && 16 % tau == 0);
+    if (opt.hash_path == 0 && L == 10 && d % 16 == 0 && n_rounds >= 1 && n_rounds <= 4 && x4_weights_ok &&
         aligned(signs, 16) && hx4_lds_bytes(a.P, n_rounds) <= 64 * 1024) {
         // two workgroups per compute unit fill it (two waves per SIMD); a larger batch is worked through in
         // several groups of four tokens per wave, the next group's rows in flight during a transform

@@ -102,3 +102,64 @@ def test_hash_four_tokens_per_wave_special_values():
         signs = (np.full((1, R, d), s, np.int8) if s else synth.make_signs(6, 1, R, d))
         got = gpu_hash(x768, signs, 96, tau)
         assert np.array_equal(got, oracle.hash_codes(x768, signs, 96, tau)), f"diagonal {s}, d = 768"
+
+
+TOL_W = 2e-5   # relative, per weight: fp32 sum and product of at most 16 terms, exp2 and the fast quotient
+
+
+X4_WEIGHTED_SHAPES = [
+    # n, d, k, tau, R, x dtype      (weights come from this kernel when tau divides 16)
+    (1003, 768, 96, 8, 3, "f32"),       # the benchmark's layer: two tables per register
+    (4099, 768, 96, 8, 3, "bf16"),
+    (20011, 768, 96, 8, 3, "f32"),      # several groups per wave
+    (777, 1024, 64, 16, 3, "f32"),      # a table per register
+    (777, 1024, 200, 16, 3, "f16"),     # four projections (3200 bits), the last one partly used
+    (777, 768, 250, 4, 3, "f32"),       # four tables per register
+    (333, 1024, 500, 2, 2, "f32"),      # tau = 2
+    (333, 768, 700, 1, 3, "f32"),       # tau = 1: the sigmoid unit
+    (333, 528, 37, 8, 4, "f32"),        # run-time bounds, an odd number of tables
+    (5, 768, 96, 8, 3, "f32"),
+]
+
+
+@pytest.mark.parametrize("n,d,k,tau,R,xdt", X4_WEIGHTED_SHAPES)
+def test_hash_weighted_four_tokens_per_wave(n, d, k, tau, R, xdt):
+    print(f"weighted hash (four tokens per wave) n={n} d={d} k={k} tau={tau} R={R} {xdt}", flush=True)
+    w = synth.Workload("t", 7, n, d, R, k, tau, 8, x_dtype=xdt)
+    signs = synth.make_signs(1000 * d + k + R, w.n_proj, R, w.d_pad)
+    x = synth.make_x(n + d + 2, n, d, xdt)
+    want_codes = oracle.hash_codes(x, signs, k, tau)
+    want_w = oracle.weights(x, signs, k, tau)
+    out = {}
+    try:
+        for path in (0, 2):                    # 2: the one-token-per-wave kernel on the same inputs
+            B.lookupffn_set_option("hash_path", path)
+            codes, wts = B.lookupffn_hash_weighted(B.to_device(x), B.to_device(signs), k, tau)
+            torch.cuda.synchronize()
+            out[path] = (B.codes_to_numpy(codes), wts.cpu().numpy())
+    finally:
+        B.lookupffn_set_option("hash_path", 0)
+    for path, (codes, wts) in out.items():
+        assert np.array_equal(codes, want_codes), f"hash_path {path}"
+        err = np.abs(wts.astype(np.float64) - want_w) / np.maximum(np.abs(want_w), 1e-30)
+        assert err.max() <= TOL_W, f"hash_path {path}: weights off by {err.max():.2e}"
+
+
+def test_forward_weighted_with_the_four_token_hash():
+    print("weighted forward, 16384 tokens: hash writes packed codes and table-major weights for the staged gather", flush=True)
+    w = synth.C2
+    x, signs, tables = synth.make_layer(w)
+    xd, sd, td = B.to_device(x), B.to_device(signs), B.to_device(tables)
+    ys = {}
+    try:
+        for path in (0, 2):
+            B.lookupffn_set_option("hash_path", path)
+            ys[path] = B.lookupffn_forward_weighted(xd, sd, td).cpu().numpy()
+            assert B.lookupffn_last_gather_kernel() == "gather_lds_kernel"
+    finally:
+        B.lookupffn_set_option("hash_path", 0)
+    rms = np.sqrt(np.mean(ys[2].astype(np.float64) ** 2))
+    assert np.max(np.abs(ys[0].astype(np.float64) - ys[2])) / rms <= 1e-5   # weights differ in the last bits only
+    idx = np.r_[0:64, 8000:8064, 16320:16384]
+    ref = oracle.forward_weighted(x[idx], signs, tables)
+    assert np.max(np.abs(ys[0][idx].astype(np.float64) - ref)) / np.sqrt(np.mean(ref.astype(np.float64) ** 2)) <= 1e-4
