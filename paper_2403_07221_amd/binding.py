@@ -25,7 +25,7 @@ EXPORTS = (
     "lookupffn_workspace_bytes_gather", "lookupffn_prepared_tables_bytes", "lookupffn_prepare_tables",
     "lookupffn_release_workspace", "lookupffn_timing_enable", "lookupffn_timing_reset",
     "lookupffn_timing_read", "lookupffn_timing_read_each", "lookupffn_set_option", "lookupffn_strerror",
-    "lookupffn_last_hip_error", "lookupffn_last_gather_kernel", "lookupffn_version",
+    "lookupffn_last_hip_error", "lookupffn_last_gather_kernel", "lookupffn_last_hash_kernel", "lookupffn_version",
     "lookupffn_hash_weighted", "lookupffn_gather_weighted", "lookupffn_forward_weighted",
     "lookupffn_workspace_bytes_weighted", "lookupffn_workspace_bytes_gather_weighted",
     "lookupffn_prepared_bh_bytes", "lookupffn_prepare_bh",
@@ -90,6 +90,7 @@ def lib() -> ctypes.CDLL:
         L.lookupffn_strerror.restype = ctypes.c_char_p
         L.lookupffn_last_hip_error.restype = ctypes.c_char_p
         L.lookupffn_last_gather_kernel.restype = ctypes.c_char_p
+        L.lookupffn_last_hash_kernel.restype = ctypes.c_char_p
         _lib = L
     return _lib
 
@@ -551,6 +552,10 @@ def lookupffn_set_option(key: str, value: int) -> None:
 
 def lookupffn_last_gather_kernel() -> str:
     return lib().lookupffn_last_gather_kernel().decode()
+
+
+def lookupffn_last_hash_kernel() -> str:
+    return lib().lookupffn_last_hash_kernel().decode()
 
 
 def lookupffn_version() -> int:

@@ -87,6 +87,7 @@ constexpr int kVersion = 100;  // 0.1.0
 constexpr int kMaxLog2N = 12;  // d_pad <= 4096
 thread_local std::string g_hip_error;
 thread_local const char *t_last_gather = "";  // name of the gather kernel this thread's most recent launch used
+thread_local const char *t_last_hash = "";    // the same for the hash kernel
 thread_local int t_attr_only = 0;
 #endif
 
@@ -472,7 +473,7 @@ struct Options {
     int xcd_order = 0;        // 0 = default, 1 = on, -1 = off
     int gather_path = 0;      // 0 = choose, 1 = direct kernel, 2 = the staged kernel whenever the shape allows,
                               // 4 = the ring kernel whenever the shape allows (else as 2)
-    int hash_path = 0;        // 0 = choose, 1 = generic kernel only, 2 = no four-tokens-per-wave kernel
+    int hash_path = 0;        // 0 = choose, 1 = generic kernel only, 2 = no four-tokens-per-wave kernel, 3 = that kernel for every batch size
     int hash_blocks = 0;      // 0 = default grid cap of the d_pad = 1024 hash kernel
     int slice_lanes = 0;      // 0 = choose, 4 = 64-byte column slices in the staged gather where possible
     int token_slots = 0;      // 0 = choose, else the most token slots per lane of the staged gather
@@ -790,8 +791,11 @@ int launch_hash(const void *x, const int8_t *signs, const HashOut &out, int64_t 
     // d_pad = 1024, up to four rounds, codes alone or with the gather weights of a tau that divides 16 (a table is
     // then a run of lanes of one register): four tokens per wavefront, no LDS transposes
     // (a lane holds every 16th coordinate: d a multiple of 16 makes "in range" a per-register question)
+    // It needs a batch that gives every SIMD two waves of four tokens to pull ahead: below about 2048 tokens
+    // (4096 with weights) one group's latency decides and the one-token kernel is 2 - 4 us faster (measured)
     const bool x4_weights_ok = !out.weights || (!out.probes && 16 % tau == 0);
-    if (opt.hash_path == 0 && L == 10 && d % 16 == 0 && n_rounds >= 1 && n_rounds <= 4 && x4_weights_ok &&
+    const bool x4_wanted = opt.hash_path == 3 || (opt.hash_path == 0 && n >= (out.weights ? 4096 : 2048));
+    if (x4_wanted && L == 10 && d % 16 == 0 && n_rounds >= 1 && n_rounds <= 4 && x4_weights_ok &&
         aligned(signs, 16) && hx4_lds_bytes(a.P, n_rounds) <= 64 * 1024) {
         // two workgroups per compute unit fill it (two waves per SIMD); a larger batch is worked through in
         // several groups of four tokens per wave, the next group's rows in flight during a transform
@@ -806,6 +810,7 @@ int launch_hash(const void *x, const int8_t *signs, const HashOut &out, int64_t 
         if (rc != LFFN_OK) return rc;
         LFFN_HIP(hipGetLastError());
         tl.done();
+        t_last_hash = "hash1024x4_kernel";
         return LFFN_OK;
     }
     // d_pad = 1024 with up to four rounds: the two-layout kernel (needs 16-byte aligned signs, and
@@ -828,6 +833,7 @@ int launch_hash(const void *x, const int8_t *signs, const HashOut &out, int64_t 
         }
         LFFN_HIP(hipGetLastError());
         tl.done();
+        t_last_hash = "hash1024_kernel";
         return LFFN_OK;
     }
     const size_t lds = hash_lds_bytes(a.P, n_rounds, N, weighted);
@@ -843,6 +849,7 @@ int launch_hash(const void *x, const int8_t *signs, const HashOut &out, int64_t 
     }
     LFFN_HIP(hipGetLastError());
     tl.done();
+    t_last_hash = "hash_kernel";
     return LFFN_OK;
 }
 
@@ -1431,6 +1438,7 @@ int launch_forward_stack(const void *x, const int8_t *const *signs, const void *
     LFFN_HIP(hipGetLastError());
     tl.done();
     t_last_gather = "forward_stack_kernel";
+    t_last_hash = "forward_stack_kernel";
     return LFFN_OK;
 }
 
@@ -2005,7 +2013,7 @@ int lookupffn_set_option(const char *key, int value)
         return LFFN_OK;
     }
     if (!std::strcmp(key, "hash_path")) {
-        if (value < 0 || value > 2) return LFFN_E_SIZE;
+        if (value < 0 || value > 3) return LFFN_E_SIZE;
         g_opt.hash_path = value;
         return LFFN_OK;
     }
@@ -2066,6 +2074,7 @@ const char *lookupffn_strerror(int status)
 const char *lookupffn_last_hip_error(void) { return g_hip_error.c_str(); }
 
 const char *lookupffn_last_gather_kernel(void) { return t_last_gather; }
+const char *lookupffn_last_hash_kernel(void) { return t_last_hash; }
 
 int lookupffn_version(void) { return kVersion; }
 

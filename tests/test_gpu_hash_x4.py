@@ -16,6 +16,7 @@ pytestmark = pytest.mark.gpu
 def _gpu():
     assert torch.cuda.is_available(), "these tests need the MI355X"
     B.lib()
+    B.lookupffn_set_option("hash_path", 3)      # the four-token kernel at every batch size (by default: from 2048 tokens)
     yield
     B.lookupffn_set_option("hash_path", 0)
     B.lookupffn_set_option("hash_blocks", 0)
@@ -56,12 +57,14 @@ def test_hash_four_tokens_per_wave_bit_exact(n, d, k, tau, R, xdt):
     x = synth.make_x(n + d + 1, n, d, xdt)
     want = oracle.hash_codes(x, signs, k, tau)
     got = gpu_hash(x, signs, k, tau)
+    assert B.lookupffn_last_hash_kernel() == "hash1024x4_kernel"
     assert np.array_equal(got, want), f"{np.count_nonzero(got != want)} codes differ"
     B.lookupffn_set_option("hash_path", 2)      # the one-token-per-wave kernel on the same inputs
     try:
         assert np.array_equal(gpu_hash(x, signs, k, tau), want)
+        assert B.lookupffn_last_hash_kernel() == "hash1024_kernel"
     finally:
-        B.lookupffn_set_option("hash_path", 0)
+        B.lookupffn_set_option("hash_path", 3)
 
 
 @pytest.mark.parametrize("blocks", [1, 3, 64])
@@ -113,7 +116,7 @@ X4_WEIGHTED_SHAPES = [
     (4099, 768, 96, 8, 3, "bf16"),
     (20011, 768, 96, 8, 3, "f32"),      # several groups per wave
     (777, 1024, 64, 16, 3, "f32"),      # a table per register
-    (777, 1024, 200, 16, 3, "f16"),     # four projections (3200 bits), the last one partly used
+    (777, 1024, 190, 16, 3, "f16"),     # three projections (3040 bits), the last one partly used
     (777, 768, 250, 4, 3, "f32"),       # four tables per register
     (333, 1024, 500, 2, 2, "f32"),      # tau = 2
     (333, 768, 700, 1, 3, "f32"),       # tau = 1: the sigmoid unit
@@ -132,13 +135,14 @@ def test_hash_weighted_four_tokens_per_wave(n, d, k, tau, R, xdt):
     want_w = oracle.weights(x, signs, k, tau)
     out = {}
     try:
-        for path in (0, 2):                    # 2: the one-token-per-wave kernel on the same inputs
+        for path in (3, 2):                    # 2: the one-token-per-wave kernel on the same inputs
             B.lookupffn_set_option("hash_path", path)
             codes, wts = B.lookupffn_hash_weighted(B.to_device(x), B.to_device(signs), k, tau)
             torch.cuda.synchronize()
+            assert B.lookupffn_last_hash_kernel() == ("hash1024x4_kernel" if path == 3 else "hash1024_kernel")
             out[path] = (B.codes_to_numpy(codes), wts.cpu().numpy())
     finally:
-        B.lookupffn_set_option("hash_path", 0)
+        B.lookupffn_set_option("hash_path", 3)
     for path, (codes, wts) in out.items():
         assert np.array_equal(codes, want_codes), f"hash_path {path}"
         err = np.abs(wts.astype(np.float64) - want_w) / np.maximum(np.abs(want_w), 1e-30)
@@ -152,14 +156,38 @@ def test_forward_weighted_with_the_four_token_hash():
     xd, sd, td = B.to_device(x), B.to_device(signs), B.to_device(tables)
     ys = {}
     try:
-        for path in (0, 2):
+        for path in (3, 2):
             B.lookupffn_set_option("hash_path", path)
             ys[path] = B.lookupffn_forward_weighted(xd, sd, td).cpu().numpy()
             assert B.lookupffn_last_gather_kernel() == "gather_lds_kernel"
     finally:
-        B.lookupffn_set_option("hash_path", 0)
+        B.lookupffn_set_option("hash_path", 3)
     rms = np.sqrt(np.mean(ys[2].astype(np.float64) ** 2))
-    assert np.max(np.abs(ys[0].astype(np.float64) - ys[2])) / rms <= 1e-5   # weights differ in the last bits only
+    assert np.max(np.abs(ys[3].astype(np.float64) - ys[2])) / rms <= 1e-5   # weights differ in the last bits only
     idx = np.r_[0:64, 8000:8064, 16320:16384]
     ref = oracle.forward_weighted(x[idx], signs, tables)
-    assert np.max(np.abs(ys[0][idx].astype(np.float64) - ref)) / np.sqrt(np.mean(ref.astype(np.float64) ** 2)) <= 1e-4
+    assert np.max(np.abs(ys[3][idx].astype(np.float64) - ref)) / np.sqrt(np.mean(ref.astype(np.float64) ** 2)) <= 1e-4
+
+
+def test_hash_kernel_choice_by_batch_size_and_shape():
+    print("hash: which kernel the library picks by default", flush=True)
+    B.lookupffn_set_option("hash_path", 0)
+    try:
+        def kernel(n, d, k, tau, weighted=False, R=3):
+            w = synth.Workload("t", 7, n, d, R, k, tau, 8)
+            signs = B.to_device(synth.make_signs(3, w.n_proj, R, w.d_pad))
+            x = B.to_device(synth.make_x(4, n, d))
+            (B.lookupffn_hash_weighted if weighted else B.lookupffn_hash)(x, signs, k, tau)
+            torch.cuda.synchronize()
+            return B.lookupffn_last_hash_kernel()
+        assert kernel(2048, 768, 96, 8) == "hash1024x4_kernel"
+        assert kernel(2047, 768, 96, 8) == "hash1024_kernel"          # small batches: one group's latency decides
+        assert kernel(4096, 768, 96, 8, weighted=True) == "hash1024x4_kernel"
+        assert kernel(4095, 768, 96, 8, weighted=True) == "hash1024_kernel"
+        assert kernel(4096, 768, 80, 10, weighted=True) == "hash1024_kernel"   # tau does not divide 16
+        assert kernel(4096, 1000, 96, 8) == "hash1024_kernel"         # d not a multiple of 16
+        assert kernel(4096, 768, 96, 8, R=5) == "hash_kernel"         # five rounds
+        assert kernel(4096, 512, 64, 8) == "hash_kernel"              # d_pad = 512
+        assert kernel(4096, 1024, 200, 16) == "hash1024_kernel"       # four projections: the constants outgrow 64 KB of LDS
+    finally:
+        B.lookupffn_set_option("hash_path", 3)

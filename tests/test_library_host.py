@@ -276,7 +276,7 @@ def test_options(L):
     assert L.lookupffn_set_option(b"xcd_order", 2) == -2 and L.lookupffn_set_option(b"xcd_order", 0) == 0
     assert L.lookupffn_set_option(b"gather_path", 5) == -2 and L.lookupffn_set_option(b"gather_path", 4) == 0
     assert L.lookupffn_set_option(b"gather_path", 0) == 0
-    assert L.lookupffn_set_option(b"hash_path", 3) == -2 and L.lookupffn_set_option(b"hash_path", 0) == 0
+    assert L.lookupffn_set_option(b"hash_path", 4) == -2 and L.lookupffn_set_option(b"hash_path", 0) == 0
     assert L.lookupffn_set_option(b"hash_blocks", -1) == -2 and L.lookupffn_set_option(b"hash_blocks", 0) == 0
     assert L.lookupffn_set_option(b"slice_lanes", 4) == 0 and L.lookupffn_set_option(b"slice_lanes", 3) == -2
     assert L.lookupffn_set_option(b"slice_lanes", 0) == 0
