@@ -288,9 +288,9 @@ template <int R>
 int launch_forward_stack_r(int kind, const StackArgs &a, dim3 grid, int threads, size_t lds, hipStream_t s)
 {
     switch (kind) {
-        case kElemF32: hipLaunchKernelGGL((forward_stack_kernel<R, kElemF32>), grid, dim3(kX4Threads), lds, s, a); break;
-        case kElemBF16: hipLaunchKernelGGL((forward_stack_kernel<R, kElemBF16>), grid, dim3(kX4Threads), lds, s, a); break;
-        case kElemF16: hipLaunchKernelGGL((forward_stack_kernel<R, kElemF16>), grid, dim3(kX4Threads), lds, s, a); break;
+        case kElemF32: hipLaunchKernelGGL((forward_stack_kernel<R, kElemF32>), grid, dim3(threads), lds, s, a); break;
+        case kElemBF16: hipLaunchKernelGGL((forward_stack_kernel<R, kElemBF16>), grid, dim3(threads), lds, s, a); break;
+        case kElemF16: hipLaunchKernelGGL((forward_stack_kernel<R, kElemF16>), grid, dim3(threads), lds, s, a); break;
         default: return LFFN_E_DTYPE;
     }
     return LFFN_OK;
