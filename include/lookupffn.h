@@ -301,13 +301,15 @@ int lookupffn_timing_read_each(int which, double *ms_out, int64_t capacity, int6
  *                                     kernel of lookupffn_forward_stack when the shape is that kernel's and no
  *                                     hash or gather path is forced (default 512; -1: never)
  *   "token_slots"      1 .. 32        staged kernels: at most this many tokens per lane group and chunk
- *   "hash_path"        1 / 2 / 3      1: always the generic hash kernel; 2: never the four-tokens-per-wavefront
- *                                     kernel; 3: that kernel for every batch size.  Default for d_pad = 1024 and
- *                                     n_rounds <= 4: the four-token kernel when d is a multiple of 16, the batch
- *                                     has at least 2048 tokens (4096 with weights) and codes alone or codes with
- *                                     the weights of a tau that divides 16 are asked for; else the two-layout
- *                                     one-token-per-wavefront kernel
- *   "hash_blocks"      1..65536       grid cap of the d_pad = 1024 hash kernels
+ *   "hash_path"        1 / 2 / 3      1: always the generic hash kernel; 2: never the token-per-lane-row kernel
+ *                                     (four tokens per wavefront at d_pad = 1024, eight at 512); 3: that kernel
+ *                                     for every batch size.  Default for n_rounds <= 4: the lane-row kernel when
+ *                                     d_pad is 1024 or 512, d is a multiple of 16, the batch has at least 2048
+ *                                     tokens (4096 with weights; at d_pad = 512: 6144 and 12288) and codes
+ *                                     alone, or codes with the weights of a tau that divides 16 (8 at d_pad =
+ *                                     512), are asked for; else, at d_pad = 1024, the two-layout
+ *                                     one-token-per-wavefront kernel; else the generic one
+ *   "hash_blocks"      1..65536       grid cap of the lane-row and two-layout hash kernels
  * Returns LFFN_E_SIZE for an unknown key or a value outside the documented set.  Process-wide; a call
  * reads the knobs once when it starts.
  */
@@ -321,8 +323,8 @@ const char *lookupffn_last_hip_error(void);
  * "forward_stack_kernel" (hash and gather of a few tokens in one launch), "gather_ring_kernel" (on request: prepared tables of up to 256 rows, plain sum; slices staged in an LDS ring,
  * token groups lagged so that their reads never meet in a bank); "" before the first launch. */
 const char *lookupffn_last_gather_kernel(void);
-/* The same for the sign-diagonal hash: "hash1024x4_kernel" (d_pad = 1024, four tokens per wavefront),
- * "hash1024_kernel" (d_pad = 1024, one token per wavefront), "hash_kernel" (any width) or
+/* The same for the sign-diagonal hash: "hash_row_kernel" (d_pad = 1024 or 512, a token per row of 16 or 8
+ * lanes), "hash1024_kernel" (d_pad = 1024, one token per wavefront), "hash_kernel" (any width) or
  * "forward_stack_kernel"; "" before the first launch (the BH hash has one kernel and is not reported). */
 const char *lookupffn_last_hash_kernel(void);
 /* major*10000 + minor*100 + patch */

@@ -12,7 +12,7 @@ SRC = PKG / "csrc" / "lookupffn.hip"
 LIB = PKG / "liblookupffn.so"
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
-N_PARTS = 15         # csrc/lookupffn.hip compiles as parts 0 .. 14 (-DLFFN_PART=i), linked together
+N_PARTS = 16         # csrc/lookupffn.hip compiles as parts 0 .. 15 (-DLFFN_PART=i), linked together
 SLOW_FIRST = [10, 11, 8, 9, 6, 5]   # the wide BH kernels take the longest: start them first
 OBJ_DIR = PKG / "_build"
 

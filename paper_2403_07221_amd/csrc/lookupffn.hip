@@ -19,11 +19,11 @@
 #include "gather_lds_kernel.hpp"
 #include "gather_ring_kernel.hpp"
 #include "hash_kernel.hpp"
-#include "hash_x4_kernel.hpp"
+#include "hash_row_kernel.hpp"
 
 // Build parts.  This file compiles whole (LFFN_PART undefined) or as parts that are linked together, so
 // that the kernel families compile side by side: part 0 holds the C ABI, the host logic and the hash and
-// re-pack kernels; parts 1 .. 14 hold one family of kernel launchers each (declared just below).  No
+// re-pack kernels; parts 1 .. 15 hold one family of kernel launchers each (declared just below).  No
 // kernel is instantiated in two parts.
 #ifdef LFFN_PART
 #define LFFN_HAS(p) (LFFN_PART == (p))
@@ -54,9 +54,11 @@ int gather_ring_part(int threads, int tok, const GatherRingArgs &a, dim3 grid, h
 // part 13: hash and gather of a few tokens, one or several chained layers, in one launch
 int forward_stack_part(int n_rounds, int kind, const StackArgs &a, dim3 grid, int threads, size_t lds, hipStream_t s);
 int forward_stack_load();
-// part 14: the d_pad = 1024 hash with four tokens per wavefront (codes only)
-int hash_x4_part(int n_rounds, const HashArgs &a, dim3 grid, size_t lds, hipStream_t s);
-int hash_x4_load();
+// parts 14, 15: the hash with a token per row of lanes, d_pad = 1024 (four tokens per wavefront) and 512 (eight)
+int hash_row16_part(int n_rounds, const HashArgs &a, dim3 grid, size_t lds, hipStream_t s);
+int hash_row8_part(int n_rounds, const HashArgs &a, dim3 grid, size_t lds, hipStream_t s);
+int hash_row16_load();
+int hash_row8_load();
 // parts 4 .. 11: the BH hash kernel.  Plain: d_pad = 64 .. 256, 512, 1024; weighted: d_pad = 64 .. 256, then
 // 512 and 1024 each split by the way the rows are read (four coordinates at a time or one by one): the
 // wide weighted kernels are the slowest to compile by far
@@ -316,40 +318,64 @@ int forward_stack_load()
 }
 #endif
 
-#if LFFN_HAS(14)
-template <int MFULL, bool WEIGHTED>
-int launch_hash_x4_r(int n_rounds, const HashArgs &a, dim3 grid, size_t lds, hipStream_t s)
+#if LFFN_HAS(14) || LFFN_HAS(15)
+template <int MFULL, bool WEIGHTED, int LPT>
+int launch_hash_row_r(int n_rounds, const HashArgs &a, dim3 grid, size_t lds, hipStream_t s)
 {
     switch (n_rounds) {
-        case 1: hipLaunchKernelGGL((hash1024x4_kernel<1, MFULL, WEIGHTED>), grid, dim3(kX4Threads), lds, s, a); break;
-        case 2: hipLaunchKernelGGL((hash1024x4_kernel<2, MFULL, WEIGHTED>), grid, dim3(kX4Threads), lds, s, a); break;
-        case 3: hipLaunchKernelGGL((hash1024x4_kernel<3, MFULL, WEIGHTED>), grid, dim3(kX4Threads), lds, s, a); break;
-        case 4: hipLaunchKernelGGL((hash1024x4_kernel<4, MFULL, WEIGHTED>), grid, dim3(kX4Threads), lds, s, a); break;
+        case 1: hipLaunchKernelGGL((hash_row_kernel<1, MFULL, WEIGHTED, LPT>), grid, dim3(kRowThreads), lds, s, a); break;
+        case 2: hipLaunchKernelGGL((hash_row_kernel<2, MFULL, WEIGHTED, LPT>), grid, dim3(kRowThreads), lds, s, a); break;
+        case 3: hipLaunchKernelGGL((hash_row_kernel<3, MFULL, WEIGHTED, LPT>), grid, dim3(kRowThreads), lds, s, a); break;
+        case 4: hipLaunchKernelGGL((hash_row_kernel<4, MFULL, WEIGHTED, LPT>), grid, dim3(kRowThreads), lds, s, a); break;
         default: return LFFN_E_UNSUPPORTED;
     }
     return LFFN_OK;
 }
+#endif
 
-int hash_x4_part(int n_rounds, const HashArgs &a, dim3 grid, size_t lds, hipStream_t s)
+#if LFFN_HAS(14)
+int hash_row16_part(int n_rounds, const HashArgs &a, dim3 grid, size_t lds, hipStream_t s)
 {
     const bool weighted = a.weights || a.wpk;
     // built for the row lengths of the paper's models (d = 768 and 1024, three rounds); any other multiple of
     // 16 in range takes the form with run-time bounds
     if (n_rounds == 3 && (a.d == 768 || a.d == 1024)) {
-        if (a.d == 768 && weighted) hipLaunchKernelGGL((hash1024x4_kernel<3, 48, true>), grid, dim3(kX4Threads), lds, s, a);
-        else if (a.d == 768) hipLaunchKernelGGL((hash1024x4_kernel<3, 48, false>), grid, dim3(kX4Threads), lds, s, a);
-        else if (weighted) hipLaunchKernelGGL((hash1024x4_kernel<3, 64, true>), grid, dim3(kX4Threads), lds, s, a);
-        else hipLaunchKernelGGL((hash1024x4_kernel<3, 64, false>), grid, dim3(kX4Threads), lds, s, a);
+        if (a.d == 768 && weighted) hipLaunchKernelGGL((hash_row_kernel<3, 48, true, 16>), grid, dim3(kRowThreads), lds, s, a);
+        else if (a.d == 768) hipLaunchKernelGGL((hash_row_kernel<3, 48, false, 16>), grid, dim3(kRowThreads), lds, s, a);
+        else if (weighted) hipLaunchKernelGGL((hash_row_kernel<3, 64, true, 16>), grid, dim3(kRowThreads), lds, s, a);
+        else hipLaunchKernelGGL((hash_row_kernel<3, 64, false, 16>), grid, dim3(kRowThreads), lds, s, a);
         return LFFN_OK;
     }
-    return weighted ? launch_hash_x4_r<0, true>(n_rounds, a, grid, lds, s) : launch_hash_x4_r<0, false>(n_rounds, a, grid, lds, s);
+    return weighted ? launch_hash_row_r<0, true, 16>(n_rounds, a, grid, lds, s)
+                    : launch_hash_row_r<0, false, 16>(n_rounds, a, grid, lds, s);
 }
 
-int hash_x4_load()
+int hash_row16_load()
 {
     hipFuncAttributes attr;
-    hipError_t e = hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(hash1024x4_kernel<3, 0, false>));
-    return e == hipSuccess ? LFFN_OK : hip_fail(e, "hipFuncGetAttributes(hash1024x4_kernel)");
+    hipError_t e = hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(hash_row_kernel<3, 0, false, 16>));
+    return e == hipSuccess ? LFFN_OK : hip_fail(e, "hipFuncGetAttributes(hash_row_kernel, 16 lanes per token)");
+}
+#endif
+
+#if LFFN_HAS(15)
+int hash_row8_part(int n_rounds, const HashArgs &a, dim3 grid, size_t lds, hipStream_t s)
+{
+    const bool weighted = a.weights || a.wpk;
+    if (n_rounds == 3 && a.d == 512) {  // the paper's small models
+        if (weighted) hipLaunchKernelGGL((hash_row_kernel<3, 64, true, 8>), grid, dim3(kRowThreads), lds, s, a);
+        else hipLaunchKernelGGL((hash_row_kernel<3, 64, false, 8>), grid, dim3(kRowThreads), lds, s, a);
+        return LFFN_OK;
+    }
+    return weighted ? launch_hash_row_r<0, true, 8>(n_rounds, a, grid, lds, s)
+                    : launch_hash_row_r<0, false, 8>(n_rounds, a, grid, lds, s);
+}
+
+int hash_row8_load()
+{
+    hipFuncAttributes attr;
+    hipError_t e = hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(hash_row_kernel<3, 0, false, 8>));
+    return e == hipSuccess ? LFFN_OK : hip_fail(e, "hipFuncGetAttributes(hash_row_kernel, 8 lanes per token)");
 }
 #endif
 
@@ -473,7 +499,7 @@ struct Options {
     int xcd_order = 0;        // 0 = default, 1 = on, -1 = off
     int gather_path = 0;      // 0 = choose, 1 = direct kernel, 2 = the staged kernel whenever the shape allows,
                               // 4 = the ring kernel whenever the shape allows (else as 2)
-    int hash_path = 0;        // 0 = choose, 1 = generic kernel only, 2 = no four-tokens-per-wave kernel, 3 = that kernel for every batch size
+    int hash_path = 0;        // 0 = choose, 1 = generic kernel only, 2 = no token-per-lane-row kernel, 3 = that kernel for every batch size
     int hash_blocks = 0;      // 0 = default grid cap of the d_pad = 1024 hash kernel
     int slice_lanes = 0;      // 0 = choose, 4 = 64-byte column slices in the staged gather where possible
     int token_slots = 0;      // 0 = choose, else the most token slots per lane of the staged gather
@@ -788,29 +814,35 @@ int launch_hash(const void *x, const int8_t *signs, const HashOut &out, int64_t 
     if (!a.codes && !a.packed) return LFFN_E_NULL;
     if (out.probes && (!a.codes || !a.weights)) return LFFN_E_UNSUPPORTED;  // shares exist in the ABI layout only
     TimedLaunch tl(0, s);
-    // d_pad = 1024, up to four rounds, codes alone or with the gather weights of a tau that divides 16 (a table is
-    // then a run of lanes of one register): four tokens per wavefront, no LDS transposes
-    // (a lane holds every 16th coordinate: d a multiple of 16 makes "in range" a per-register question)
-    // It needs a batch that gives every SIMD two waves of four tokens to pull ahead: below about 2048 tokens
-    // (4096 with weights) one group's latency decides and the one-token kernel is 2 - 4 us faster (measured)
-    const bool x4_weights_ok = !out.weights || (!out.probes && 16 % tau == 0);
-    const bool x4_wanted = opt.hash_path == 3 || (opt.hash_path == 0 && n >= (out.weights ? 4096 : 2048));
-    if (x4_wanted && L == 10 && d % 16 == 0 && n_rounds >= 1 && n_rounds <= 4 && x4_weights_ok &&
-        aligned(signs, 16) && hx4_lds_bytes(a.P, n_rounds) <= 64 * 1024) {
+    // d_pad = 1024 or 512, up to four rounds, codes alone or with the gather weights of a tau that divides the
+    // lanes of a token (a table is then a run of lanes of one register): a token per row of 16 (8) lanes, four
+    // (eight) tokens per wavefront, no LDS transposes.  A lane holds every 16th (8th) coordinate: d a multiple
+    // of 16 makes "in range" a per-register question.
+    // It needs a batch that gives most SIMDs two waves of tokens to pull ahead; below that one group's latency
+    // decides and the one-token kernels are faster.  Measured crossovers: d_pad = 1024 about 2048 tokens (4096
+    // with weights), d_pad = 512 (twice the tokens per wave) about 6000 (10000 with weights).
+    const int lpt = L == 10 ? 16 : 8;
+    const bool row_weights_ok = !out.weights || (!out.probes && lpt % tau == 0);
+    const int64_t row_from = lpt == 16 ? (out.weights ? 4096 : 2048) : (out.weights ? 12288 : 6144);
+    const bool row_wanted = opt.hash_path == 3 || (opt.hash_path == 0 && n >= row_from);
+    if (row_wanted && (L == 10 || L == 9) && d % 16 == 0 && n_rounds >= 1 && n_rounds <= 4 && row_weights_ok &&
+        aligned(signs, 16) && hrow_lds_bytes(a.P, n_rounds, lpt) <= 64 * 1024) {
         // two workgroups per compute unit fill it (two waves per SIMD); a larger batch is worked through in
-        // several groups of four tokens per wave, the next group's rows in flight during a transform
+        // several groups of tokens per wave, the next group's rows in flight during a transform
         int cus = 0;
         int rc = device_cus(&cus);
         if (rc != LFFN_OK) return rc;
-        const int64_t groups = (n + kX4Tokens - 1) / kX4Tokens;
-        int64_t blocks = (groups + kX4Waves - 1) / kX4Waves;
+        const int64_t groups = (n + 64 / lpt - 1) / (64 / lpt);
+        int64_t blocks = (groups + kRowWaves - 1) / kRowWaves;
         const int64_t cap = opt.hash_blocks ? opt.hash_blocks : 2 * (int64_t)cus;
         if (blocks > cap) blocks = cap;
-        rc = lffn_host::hash_x4_part(n_rounds, a, dim3((unsigned)blocks), hx4_lds_bytes(a.P, n_rounds), s);
+        const size_t lds = hrow_lds_bytes(a.P, n_rounds, lpt);
+        rc = lpt == 16 ? lffn_host::hash_row16_part(n_rounds, a, dim3((unsigned)blocks), lds, s)
+                       : lffn_host::hash_row8_part(n_rounds, a, dim3((unsigned)blocks), lds, s);
         if (rc != LFFN_OK) return rc;
         LFFN_HIP(hipGetLastError());
         tl.done();
-        t_last_hash = "hash1024x4_kernel";
+        t_last_hash = "hash_row_kernel";
         return LFFN_OK;
     }
     // d_pad = 1024 with up to four rounds: the two-layout kernel (needs 16-byte aligned signs, and
@@ -1649,7 +1681,9 @@ int lookupffn_init(void)
                     if (rc != LFFN_OK && rc != LFFN_E_UNSUPPORTED) return rc;
                 }
             }
-    rc = lffn_host::hash_x4_load();
+    rc = lffn_host::hash_row16_load();
+    if (rc != LFFN_OK) return rc;
+    rc = lffn_host::hash_row8_load();
     if (rc != LFFN_OK) return rc;
     rc = lffn_host::forward_stack_load();
     if (rc != LFFN_OK) return rc;

@@ -1,6 +1,6 @@
-"""GPU parity of the d_pad = 1024 hash kernel that keeps four tokens per wavefront (Sec. 3.2, eq. hadamard;
-Sec. 3.1 codes): codes bit-exact against the oracle, and the one-token-per-wavefront kernel (hash_path = 2)
-on the same inputs, over the shapes that select each of its forms."""
+"""GPU parity of the hash kernel that keeps a token per row of lanes (d_pad = 1024: four tokens per wavefront,
+d_pad = 512: eight; Sec. 3.2, eq. hadamard; Sec. 3.1 codes): codes bit-exact against the oracle, and the
+one-token-per-wavefront kernels (hash_path = 2) on the same inputs, over the shapes that select each of its forms."""
 import numpy as np
 import pytest
 import torch
@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 def _gpu():
     assert torch.cuda.is_available(), "these tests need the MI355X"
     B.lib()
-    B.lookupffn_set_option("hash_path", 3)      # the four-token kernel at every batch size (by default: from 2048 tokens)
+    B.lookupffn_set_option("hash_path", 3)      # the lane-row kernel at every batch size (by default: large batches only)
     yield
     B.lookupffn_set_option("hash_path", 0)
     B.lookupffn_set_option("hash_blocks", 0)
@@ -46,6 +46,17 @@ X4_SHAPES = [
     (333, 768, 96, 8, 2, "bf16"),       # two rounds
     (333, 1024, 250, 4, 4, "f32"),      # four rounds
     (333, 768, 7, 1, 3, "f32"),         # tau = 1
+    # d_pad = 512: eight tokens per wavefront, eight lanes per token
+    (1, 512, 64, 8, 3, "f32"),
+    (7, 512, 64, 8, 3, "bf16"),         # one group, one row short
+    (9, 512, 64, 8, 3, "f32"),          # one full group and one token
+    (4099, 512, 64, 8, 3, "f32"),
+    (40003, 512, 128, 8, 3, "f32"),     # the paper's small-model shape: two projections, several groups per wave
+    (9001, 512, 20, 13, 3, "f16"),      # the paper's tau = 13 ablation shape
+    (333, 272, 30, 9, 3, "f32"),        # run-time bounds: 34 registers in range
+    (333, 496, 61, 8, 1, "f32"),        # one round
+    (333, 512, 64, 8, 2, "f32"),
+    (333, 384, 100, 16, 4, "bf16"),     # four rounds, four projections
 ]
 
 
@@ -57,12 +68,12 @@ def test_hash_four_tokens_per_wave_bit_exact(n, d, k, tau, R, xdt):
     x = synth.make_x(n + d + 1, n, d, xdt)
     want = oracle.hash_codes(x, signs, k, tau)
     got = gpu_hash(x, signs, k, tau)
-    assert B.lookupffn_last_hash_kernel() == "hash1024x4_kernel"
+    assert B.lookupffn_last_hash_kernel() == "hash_row_kernel"
     assert np.array_equal(got, want), f"{np.count_nonzero(got != want)} codes differ"
     B.lookupffn_set_option("hash_path", 2)      # the one-token-per-wave kernel on the same inputs
     try:
         assert np.array_equal(gpu_hash(x, signs, k, tau), want)
-        assert B.lookupffn_last_hash_kernel() == "hash1024_kernel"
+        assert B.lookupffn_last_hash_kernel() == ("hash1024_kernel" if d > 512 else "hash_kernel")
     finally:
         B.lookupffn_set_option("hash_path", 3)
 
@@ -122,6 +133,12 @@ X4_WEIGHTED_SHAPES = [
     (333, 768, 700, 1, 3, "f32"),       # tau = 1: the sigmoid unit
     (333, 528, 37, 8, 4, "f32"),        # run-time bounds, an odd number of tables
     (5, 768, 96, 8, 3, "f32"),
+    # d_pad = 512: tau divides 8
+    (4099, 512, 64, 8, 3, "f32"),       # a table per register
+    (20011, 512, 128, 8, 3, "bf16"),    # two projections
+    (777, 512, 200, 4, 3, "f32"),       # two tables per register
+    (333, 496, 300, 2, 2, "f32"),
+    (333, 272, 400, 1, 4, "f16"),
 ]
 
 
@@ -139,7 +156,7 @@ def test_hash_weighted_four_tokens_per_wave(n, d, k, tau, R, xdt):
             B.lookupffn_set_option("hash_path", path)
             codes, wts = B.lookupffn_hash_weighted(B.to_device(x), B.to_device(signs), k, tau)
             torch.cuda.synchronize()
-            assert B.lookupffn_last_hash_kernel() == ("hash1024x4_kernel" if path == 3 else "hash1024_kernel")
+            assert B.lookupffn_last_hash_kernel() == ("hash_row_kernel" if path == 3 else "hash1024_kernel" if d > 512 else "hash_kernel")
             out[path] = (B.codes_to_numpy(codes), wts.cpu().numpy())
     finally:
         B.lookupffn_set_option("hash_path", 3)
@@ -180,14 +197,19 @@ def test_hash_kernel_choice_by_batch_size_and_shape():
             (B.lookupffn_hash_weighted if weighted else B.lookupffn_hash)(x, signs, k, tau)
             torch.cuda.synchronize()
             return B.lookupffn_last_hash_kernel()
-        assert kernel(2048, 768, 96, 8) == "hash1024x4_kernel"
+        assert kernel(2048, 768, 96, 8) == "hash_row_kernel"
         assert kernel(2047, 768, 96, 8) == "hash1024_kernel"          # small batches: one group's latency decides
-        assert kernel(4096, 768, 96, 8, weighted=True) == "hash1024x4_kernel"
+        assert kernel(4096, 768, 96, 8, weighted=True) == "hash_row_kernel"
         assert kernel(4095, 768, 96, 8, weighted=True) == "hash1024_kernel"
         assert kernel(4096, 768, 80, 10, weighted=True) == "hash1024_kernel"   # tau does not divide 16
         assert kernel(4096, 1000, 96, 8) == "hash1024_kernel"         # d not a multiple of 16
         assert kernel(4096, 768, 96, 8, R=5) == "hash_kernel"         # five rounds
-        assert kernel(4096, 512, 64, 8) == "hash_kernel"              # d_pad = 512
+        assert kernel(6144, 512, 64, 8) == "hash_row_kernel"          # d_pad = 512: eight tokens per wavefront
+        assert kernel(6143, 512, 64, 8) == "hash_kernel"
+        assert kernel(12288, 512, 64, 8, weighted=True) == "hash_row_kernel"
+        assert kernel(12287, 512, 64, 8, weighted=True) == "hash_kernel"
+        assert kernel(12288, 512, 32, 16, weighted=True) == "hash_kernel"     # tau = 16 spans two registers there
+        assert kernel(4096, 256, 32, 8) == "hash_kernel"              # d_pad = 256
         assert kernel(4096, 1024, 200, 16) == "hash1024_kernel"       # four projections: the constants outgrow 64 KB of LDS
     finally:
         B.lookupffn_set_option("hash_path", 3)
