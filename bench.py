@@ -449,6 +449,18 @@ def main():
         out["hash_roofline"] = {"kernel": "bh_pack_kernel + bh_hash_kernel", "bound": "mfma", "achieved": flops / hash_s / 1e12,
                                 "peak": 157.3, "unit": "TFLOP/s", "frac": flops / hash_s / 1e12 / 157.3,
                                 "flops_per_launch": flops, "avg_kernel_ms": hash_s * 1e3}
+    elif not fused and hash_n:
+        # the sign-diagonal hash is bound by vector-ALU issue: the butterflies alone are d_pad * log2(d_pad)
+        # fp32 adds per round, projection and token, against one 64-lane add per SIMD every four clocks
+        # (256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 T adds/s: packed fp32 is not used and an add is
+        # not a fused multiply-add, so this is a quarter of the 157.3 TFLOP/s vector figure).  The time is
+        # the hash step's event pair, which includes a few microseconds of launch and queue time.
+        adds = w.n_proj * w.n_rounds * w.d_pad * (w.d_pad.bit_length() - 1) * w.n_tokens
+        hash_s = hash_ms / hash_n * 1e-3
+        alu_peak = 256 * 4 * 16 * 2.4e9 / 1e12
+        out["hash_roofline"] = {"kernel": B.lookupffn_last_hash_kernel(), "bound": "alu", "achieved": adds / hash_s / 1e12,
+                                "peak": alu_peak, "unit": "T fp32 adds/s", "frac": adds / hash_s / 1e12 / alu_peak,
+                                "adds_per_launch": adds, "avg_kernel_ms": hash_s * 1e3}
     if w.n_layers > 1:
         out["latency"] = latency_report(w, args, xd, loop_step, stack_step, y_last)
     if args.zipf > 0 and w.n_layers == 1:
