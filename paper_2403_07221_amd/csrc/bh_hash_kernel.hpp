@@ -41,6 +41,7 @@ struct BhArgs {
     float *zout;          // plain variant: z of every token, [n][P*N] fp32, for weights of tables that straddle
                           // tiles (any tau), or NULL
     long long n_pad;
+    int packed_shift;     // log2 of the row-piece bytes the packed codes are scaled by
     long long n;
     int d, k, tau, n_factors, P;
     int x_kind;  // element type of x: 0 fp32, 1 bf16, 2 IEEE half
@@ -439,7 +440,7 @@ __global__ __launch_bounds__(kBhThreads) void bh_hash_kernel(BhArgs a)
             if (a.packed) {
                 for (int s = (int)lane; s < a.k / 2; s += 64)
                     a.packed[(long long)s * a.n_pad + tok] =
-                        (code_at(2u * s) << kPackedShift) | (code_at(2u * s + 1u) << (16 + kPackedShift));
+                        (code_at(2u * s) << a.packed_shift) | (code_at(2u * s + 1u) << (16 + a.packed_shift));
             } else {
                 for (int j = (int)lane; j < a.k; j += 64) a.codes[tok * a.k + j] = (uint16_t)code_at((unsigned)j);
             }

@@ -42,6 +42,7 @@ struct HashArgs {
     float *weights;       // [n][k] gather weights of the weighted variant (Sec. 4), or NULL
     float *wpk;           // the same weights table-major, [k][n_pad], for the LDS-staged gather, or NULL
     long long n_pad;      // token stride of `packed`
+    int packed_shift;     // log2 of the row-piece bytes the packed codes are scaled by (7: 128-byte pieces, 6: 64-byte)
     long long n;
     int d, k, tau, n_rounds, P;
     int x_kind;           // element type of x: 0 fp32, 1 bf16, 2 IEEE half
@@ -369,7 +370,7 @@ __global__ __launch_bounds__(kHashThreads) void hash_kernel(HashArgs a)
         if (a.packed) {
             for (int s = (int)lane; s < a.k / 2; s += 64)
                 a.packed[(long long)s * a.n_pad + t] =
-                    (code_at(2u * s) << kPackedShift) | (code_at(2u * s + 1u) << (16 + kPackedShift));
+                    (code_at(2u * s) << a.packed_shift) | (code_at(2u * s + 1u) << (16 + a.packed_shift));
         } else {
             for (int j = (int)lane; j < a.k; j += 64) a.codes[t * a.k + j] = (uint16_t)code_at((unsigned)j);
         }
@@ -637,8 +638,8 @@ __global__ __launch_bounds__(kHashThreads) __attribute__((amdgpu_waves_per_eu(4,
         // ---- a4: code j = bits [j*tau, (j+1)*tau), little-endian ---------------------------
         if (a.packed) {
             for (int s = (int)lane; s < a.k / 2; s += 64)
-                a.packed[(long long)s * a.n_pad + t] = (hash_code_at(bitw, 2u * s, a.tau) << kPackedShift) |
-                                                       (hash_code_at(bitw, 2u * s + 1u, a.tau) << (16 + kPackedShift));
+                a.packed[(long long)s * a.n_pad + t] = (hash_code_at(bitw, 2u * s, a.tau) << a.packed_shift) |
+                                                       (hash_code_at(bitw, 2u * s + 1u, a.tau) << (16 + a.packed_shift));
         } else {
             for (int j = (int)lane; j < a.k; j += 64) a.codes[t * a.k + j] = (uint16_t)hash_code_at(bitw, (unsigned)j, a.tau);
         }

@@ -394,8 +394,8 @@ __global__ __launch_bounds__(kRowThreads) void hash_row_kernel(HashArgs a)
             const unsigned q = lane & (LPT - 1u);
             if (a.packed) {
                 for (int s = (int)q; s < a.k / 2; s += LPT)
-                    a.packed[(long long)s * a.n_pad + t] = (hash_code_at(bits_row, 2u * s, a.tau) << kPackedShift) |
-                                                           (hash_code_at(bits_row, 2u * s + 1u, a.tau) << (16 + kPackedShift));
+                    a.packed[(long long)s * a.n_pad + t] = (hash_code_at(bits_row, 2u * s, a.tau) << a.packed_shift) |
+                                                           (hash_code_at(bits_row, 2u * s + 1u, a.tau) << (16 + a.packed_shift));
             } else {
                 for (int j = (int)q; j < a.k; j += LPT)
                     a.codes[t * a.k + j] = (uint16_t)hash_code_at(bits_row, (unsigned)j, a.tau);

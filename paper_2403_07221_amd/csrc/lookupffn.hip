@@ -752,6 +752,7 @@ struct HashOut {
     uint32_t *packed = nullptr;
     float *weights = nullptr;  // beside `codes`: [n][k] or [n][k][1+tau]; beside `packed`: wpk[k][n_pad]
     bool probes = false;
+    int shift = kPackedShift;  // what the packed codes are scaled by: log2 of the staged gather's row-piece bytes
 };
 
 // Host-side extent check of one hash launch: every index the kernels form from (n, k, tau, n_pad)
@@ -803,6 +804,7 @@ int launch_hash(const void *x, const int8_t *signs, const HashOut &out, int64_t 
     a.weights = out.codes ? out.weights : nullptr;
     a.wpk = out.codes ? nullptr : out.weights;
     a.n_pad = packed_n_pad(n);
+    a.packed_shift = out.shift;
     a.n = n;
     a.d = d;
     a.k = k;
@@ -906,8 +908,8 @@ struct LdsPlan {
     int tok = 0;
     int sw = 8;     // lanes per token: 8 = 128-byte column slices, 4 = 64-byte ones
     int fr = 1;     // 16 KB copy rounds per table slice
-    int shift = 7;  // log2 of the row-piece bytes: what the packed codes are scaled by.  The hash kernels
-                    // write shift 7; a plan with shift 6 takes its codes through the re-pack kernel.
+    int shift = 7;  // log2 of the row-piece bytes: what the packed codes are scaled by (the hash kernels and the
+                    // re-pack kernel scale by whatever the plan says)
     unsigned grid = 0;
     size_t lds = 0;
     int tail = 0;   // tables left to the direct kernel, which adds them onto the staged kernel's y: 1 when
@@ -1350,6 +1352,7 @@ int launch_hash_bh(const void *x, const float *pack_from, const float *apack_in,
     a.weights = out.codes ? out.weights : nullptr;
     a.wpk = out.codes ? nullptr : out.weights;
     a.n_pad = packed_n_pad(n);
+    a.packed_shift = out.shift;
     a.n = n;
     a.d = d;
     a.k = k;
@@ -1533,13 +1536,14 @@ int forward_core(const HashSpec &h, Mode mode, const void *x, const void *tables
                                   d, k, tau, h.block, h.n_factors, x_dtype, s, zscratch);
         return launch_hash(x, h.signs, out, n, d, k, tau, h.n_rounds, x_dtype, s, opt);
     };
-    // the hash kernels write the staged gather's layout themselves when its codes are scaled for 128-byte
-    // row pieces (and the variant is not the multi-probe one, whose shares exist in the ABI layout only)
+    // the hash kernels write the staged gather's layout themselves, scaled for its row pieces (unless the
+    // variant is the multi-probe one, whose shares exist in the ABI layout only)
     RingPlan ring;
     rc = plan_gather_ring(n, k, tau, d_out, T, mode, opt, &ring);
     if (rc != LFFN_OK) return rc;
-    if (!ring.use && plan.use && !plan.tail && plan.shift == kPackedShift && mode != kProbes && !zb) {
+    if (!ring.use && plan.use && !plan.tail && mode != kProbes && !zb) {
         HashOut out;
+        out.shift = plan.shift;
         const int64_t pb = packed_bytes(n, k), wb = mode == kWeighted ? wpk_bytes(n, k) : 0;
         out.packed = sc.take<uint32_t>(pb);
         out.weights = mode == kWeighted ? sc.take<float>(wb) : nullptr;
