@@ -305,9 +305,9 @@ int lookupffn_timing_read_each(int which, double *ms_out, int64_t capacity, int6
  *                                     (four tokens per wavefront at d_pad = 1024, eight at 512); 3: that kernel
  *                                     for every batch size.  Default for n_rounds <= 4: the lane-row kernel when
  *                                     d_pad is 1024 or 512, d is a multiple of 16, the batch has at least 2048
- *                                     tokens (4096 with weights; at d_pad = 512: 6144 and 12288) and codes
- *                                     alone, or codes with the weights of a tau that divides 16 (8 at d_pad =
- *                                     512), are asked for; else, at d_pad = 1024, the two-layout
+ *                                     tokens (4096 with weights; at d_pad = 512: 6144 and 12288), codes alone or
+ *                                     codes and gather weights are asked for (not the multi-probe shares) and
+ *                                     its constants fit 64 KB of LDS; else, at d_pad = 1024, the two-layout
  *                                     one-token-per-wavefront kernel; else the generic one
  *   "hash_blocks"      1..65536       grid cap of the lane-row and two-layout hash kernels
  * Returns LFFN_E_SIZE for an unknown key or a value outside the documented set.  Process-wide; a call

@@ -43,9 +43,16 @@ constexpr int kRowLaneWords = 68;    // words between the constants of two lanes
 // constants: [P][1 + R][LPT lanes][kRowLaneWords]; slot 0 the first round's XOR words, slot 1 + r the
 // multipliers at the end of round r
 __host__ __device__ inline size_t hrow_const_words(int P, int R, int lpt) { return (size_t)P * (R + 1) * lpt * kRowLaneWords; }
-__host__ __device__ inline size_t hrow_lds_bytes(int P, int R, int lpt)
+// z window of the weights of a tau that does not divide LPT: per wave one token's z of the current projection
+// and, per token of the wave, the last kZTail coordinates of the projections before it
+__host__ __device__ inline size_t hrow_window_words(int lpt, bool window)
 {
-    return 4 * (hrow_const_words(P, R, lpt) + (size_t)kRowWaves * (64 / lpt) * hash_bit_words(P, 64 * lpt));
+    return window ? (size_t)kRowWaves * (64 * lpt + (64 / lpt) * kZTail) : 0;
+}
+__host__ __device__ inline size_t hrow_lds_bytes(int P, int R, int lpt, bool window = false)
+{
+    return 4 * (hrow_const_words(P, R, lpt) + (size_t)kRowWaves * (64 / lpt) * hash_bit_words(P, 64 * lpt) +
+                hrow_window_words(lpt, window));
 }
 
 typedef __attribute__((address_space(3))) uint8_t lds_u8;
@@ -199,7 +206,9 @@ __device__ __forceinline__ void row_reg_stage(float (&v)[kRowRegs])
 // The kernel keeps two sets of rows in registers (the one being transformed and the next one, in flight), about
 // 230 registers per lane: two waves per SIMD, which is enough because a wave's instructions are independent
 // for 64 registers at a stretch; the grid is sized so that a wave works through several groups of tokens.
-template <int R, int MFULL, bool WEIGHTED, int LPT>
+// WMODE: 0 codes only; 1 codes and gather weights, tau divides LPT (reduced in registers); 2 codes and gather
+// weights of any tau <= 16, through a z window in LDS (one token at a time, a lane per table)
+template <int R, int MFULL, int WMODE, int LPT>
 __global__ __launch_bounds__(kRowThreads) void hash_row_kernel(HashArgs a)
 {
     static_assert(LPT == 16 || LPT == 8, "a token is a row of 16 lanes or half of one");
@@ -216,6 +225,10 @@ __global__ __launch_bounds__(kRowThreads) void hash_row_kernel(HashArgs a)
     const int W = hash_bit_words(P, N);
     uint32_t *consts = lds;
     uint32_t *bits_wave = lds + hrow_const_words(P, R, LPT) + (size_t)wave * TOK * W;
+    // window mode: [N] z of one token, then [TOK][kZTail] tails (see hrow_window_words)
+    float *zwin = reinterpret_cast<float *>(lds + hrow_const_words(P, R, LPT) + (size_t)kRowWaves * TOK * W) +
+                  (size_t)wave * (N + TOK * kZTail);
+    float *ztail = zwin + N;
 
     const int m_full = MFULL ? MFULL : __builtin_amdgcn_readfirstlane(a.d / LPT);
     const long long n_groups = (a.n + TOK - 1) / TOK;
@@ -355,7 +368,7 @@ __global__ __launch_bounds__(kRowThreads) void hash_row_kernel(HashArgs a)
             // (host-checked), so a table's coordinates are tau neighbouring c of one register: sum and product
             // are all-reduced over those lanes with the exchanges' DPP controls, and the weight is
             // sum * (1 / product).
-            if constexpr (WEIGHTED) {
+            if constexpr (WMODE == 1) {
                 const long long bits_left = (long long)a.k * a.tau - (long long)p * N;
                 const int n_reg = bits_left >= N ? kRowRegs : (int)((bits_left + LPT - 1) / LPT);  // registers that hold table coordinates
                 switch (a.tau) {
@@ -367,6 +380,51 @@ __global__ __launch_bounds__(kRowThreads) void hash_row_kernel(HashArgs a)
                         if constexpr (LPT == 16) row_weights<4, LPT>(a, v, p, n_reg, c, t, t_ok);
                         break;
                 }
+            }
+            // Any other tau (a table then crosses registers, and may cross from one projection into the next): z
+            // goes through LDS, one token at a time; the wave's lanes take a table each and form the same sum and
+            // product coordinate by coordinate.  Tables are handled in the projection that holds their last
+            // coordinate; the 16 coordinates before a projection's start are kept per token.
+            if constexpr (WMODE == 2) {
+                const int tau = a.tau;
+                const long long lo_bit = (long long)p * N;
+                const int jlo = (int)(lo_bit / tau);
+                long long jhi = (lo_bit + N) / tau;
+                if (jhi > a.k) jhi = a.k;
+#pragma unroll 1
+                for (int tr = 0; tr < TOK; ++tr) {  // the wave's tokens in turn
+                    wave_lds_fence();
+                    if (row == (unsigned)tr) {
+#pragma unroll
+                        for (int m = 0; m < kRowRegs; ++m) zwin[LPT * m + (int)c] = v[m];
+                    }
+                    wave_lds_fence();
+                    const long long tw = g * TOK + tr;
+                    const float *tail = ztail + tr * kZTail;
+                    if (tw < a.n) {
+                        for (int j = jlo + (int)lane; j < (int)jhi; j += 64) {
+                            const int c0 = (int)((long long)j * tau - lo_bit);  // may be negative: the table began before
+                            float sum = 0.0f, q = 1.0f;
+                            for (int b = 0; b < tau; ++b) {
+                                const int cc = c0 + b;
+                                const float az = __builtin_fabsf(cc < 0 ? tail[kZTail + cc] : zwin[cc]);
+                                sum += az;
+                                q *= 1.0f + __builtin_amdgcn_exp2f(az * -2.885390082f);  // exp(-2 az) = 2^(-2 az log2 e)
+                            }
+                            const float w = sum * __builtin_amdgcn_rcpf(q);  // q >= 1
+                            if (a.wpk) a.wpk[wpk_index(j, tw, a.n_pad)] = w;
+                            else a.weights[tw * a.k + j] = w;
+                        }
+                    }
+                    if (p + 1 < P) {  // the last 16 coordinates of this projection become the token's tail
+                        wave_lds_fence();
+                        float keep = 0.0f;
+                        if (lane < (unsigned)kZTail) keep = zwin[N - kZTail + (int)lane];
+                        wave_lds_fence();
+                        if (lane < (unsigned)kZTail) ztail[tr * kZTail + (int)lane] = keep;
+                    }
+                }
+                wave_lds_fence();
             }
             lo = row_c_order(lo);
             hi = row_c_order(hi);

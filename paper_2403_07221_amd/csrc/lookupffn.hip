@@ -319,41 +319,54 @@ int forward_stack_load()
 #endif
 
 #if LFFN_HAS(14) || LFFN_HAS(15)
-template <int MFULL, bool WEIGHTED, int LPT>
+// WMODE of the lane-row kernel: 0 codes only, 1 weights reduced in registers (tau divides the lanes of a token),
+// 2 weights of any tau through the z window
+inline int row_wmode(const HashArgs &a, int lpt) { return !(a.weights || a.wpk) ? 0 : lpt % a.tau == 0 ? 1 : 2; }
+
+template <int MFULL, int WMODE, int LPT>
 int launch_hash_row_r(int n_rounds, const HashArgs &a, dim3 grid, size_t lds, hipStream_t s)
 {
     switch (n_rounds) {
-        case 1: hipLaunchKernelGGL((hash_row_kernel<1, MFULL, WEIGHTED, LPT>), grid, dim3(kRowThreads), lds, s, a); break;
-        case 2: hipLaunchKernelGGL((hash_row_kernel<2, MFULL, WEIGHTED, LPT>), grid, dim3(kRowThreads), lds, s, a); break;
-        case 3: hipLaunchKernelGGL((hash_row_kernel<3, MFULL, WEIGHTED, LPT>), grid, dim3(kRowThreads), lds, s, a); break;
-        case 4: hipLaunchKernelGGL((hash_row_kernel<4, MFULL, WEIGHTED, LPT>), grid, dim3(kRowThreads), lds, s, a); break;
+        case 1: hipLaunchKernelGGL((hash_row_kernel<1, MFULL, WMODE, LPT>), grid, dim3(kRowThreads), lds, s, a); break;
+        case 2: hipLaunchKernelGGL((hash_row_kernel<2, MFULL, WMODE, LPT>), grid, dim3(kRowThreads), lds, s, a); break;
+        case 3: hipLaunchKernelGGL((hash_row_kernel<3, MFULL, WMODE, LPT>), grid, dim3(kRowThreads), lds, s, a); break;
+        case 4: hipLaunchKernelGGL((hash_row_kernel<4, MFULL, WMODE, LPT>), grid, dim3(kRowThreads), lds, s, a); break;
         default: return LFFN_E_UNSUPPORTED;
     }
     return LFFN_OK;
+}
+
+// MFULL: the kernel built for one row length, three rounds; else the form with run-time bounds
+template <int MFULL, int LPT>
+int launch_hash_row_m(int n_rounds, const HashArgs &a, dim3 grid, size_t lds, hipStream_t s)
+{
+    const int wmode = row_wmode(a, LPT);
+    if (MFULL != 0) {
+        if (wmode == 0) hipLaunchKernelGGL((hash_row_kernel<3, MFULL, 0, LPT>), grid, dim3(kRowThreads), lds, s, a);
+        else if (wmode == 1) hipLaunchKernelGGL((hash_row_kernel<3, MFULL, 1, LPT>), grid, dim3(kRowThreads), lds, s, a);
+        else hipLaunchKernelGGL((hash_row_kernel<3, MFULL, 2, LPT>), grid, dim3(kRowThreads), lds, s, a);
+        return LFFN_OK;
+    }
+    return wmode == 0   ? launch_hash_row_r<0, 0, LPT>(n_rounds, a, grid, lds, s)
+           : wmode == 1 ? launch_hash_row_r<0, 1, LPT>(n_rounds, a, grid, lds, s)
+                        : launch_hash_row_r<0, 2, LPT>(n_rounds, a, grid, lds, s);
 }
 #endif
 
 #if LFFN_HAS(14)
 int hash_row16_part(int n_rounds, const HashArgs &a, dim3 grid, size_t lds, hipStream_t s)
 {
-    const bool weighted = a.weights || a.wpk;
     // built for the row lengths of the paper's models (d = 768 and 1024, three rounds); any other multiple of
     // 16 in range takes the form with run-time bounds
-    if (n_rounds == 3 && (a.d == 768 || a.d == 1024)) {
-        if (a.d == 768 && weighted) hipLaunchKernelGGL((hash_row_kernel<3, 48, true, 16>), grid, dim3(kRowThreads), lds, s, a);
-        else if (a.d == 768) hipLaunchKernelGGL((hash_row_kernel<3, 48, false, 16>), grid, dim3(kRowThreads), lds, s, a);
-        else if (weighted) hipLaunchKernelGGL((hash_row_kernel<3, 64, true, 16>), grid, dim3(kRowThreads), lds, s, a);
-        else hipLaunchKernelGGL((hash_row_kernel<3, 64, false, 16>), grid, dim3(kRowThreads), lds, s, a);
-        return LFFN_OK;
-    }
-    return weighted ? launch_hash_row_r<0, true, 16>(n_rounds, a, grid, lds, s)
-                    : launch_hash_row_r<0, false, 16>(n_rounds, a, grid, lds, s);
+    if (n_rounds == 3 && a.d == 768) return launch_hash_row_m<48, 16>(3, a, grid, lds, s);
+    if (n_rounds == 3 && a.d == 1024) return launch_hash_row_m<64, 16>(3, a, grid, lds, s);
+    return launch_hash_row_m<0, 16>(n_rounds, a, grid, lds, s);
 }
 
 int hash_row16_load()
 {
     hipFuncAttributes attr;
-    hipError_t e = hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(hash_row_kernel<3, 0, false, 16>));
+    hipError_t e = hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(hash_row_kernel<3, 0, 0, 16>));
     return e == hipSuccess ? LFFN_OK : hip_fail(e, "hipFuncGetAttributes(hash_row_kernel, 16 lanes per token)");
 }
 #endif
@@ -361,20 +374,14 @@ int hash_row16_load()
 #if LFFN_HAS(15)
 int hash_row8_part(int n_rounds, const HashArgs &a, dim3 grid, size_t lds, hipStream_t s)
 {
-    const bool weighted = a.weights || a.wpk;
-    if (n_rounds == 3 && a.d == 512) {  // the paper's small models
-        if (weighted) hipLaunchKernelGGL((hash_row_kernel<3, 64, true, 8>), grid, dim3(kRowThreads), lds, s, a);
-        else hipLaunchKernelGGL((hash_row_kernel<3, 64, false, 8>), grid, dim3(kRowThreads), lds, s, a);
-        return LFFN_OK;
-    }
-    return weighted ? launch_hash_row_r<0, true, 8>(n_rounds, a, grid, lds, s)
-                    : launch_hash_row_r<0, false, 8>(n_rounds, a, grid, lds, s);
+    if (n_rounds == 3 && a.d == 512) return launch_hash_row_m<64, 8>(3, a, grid, lds, s);  // the paper's small models
+    return launch_hash_row_m<0, 8>(n_rounds, a, grid, lds, s);
 }
 
 int hash_row8_load()
 {
     hipFuncAttributes attr;
-    hipError_t e = hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(hash_row_kernel<3, 0, false, 8>));
+    hipError_t e = hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(hash_row_kernel<3, 0, 0, 8>));
     return e == hipSuccess ? LFFN_OK : hip_fail(e, "hipFuncGetAttributes(hash_row_kernel, 8 lanes per token)");
 }
 #endif
@@ -816,19 +823,20 @@ int launch_hash(const void *x, const int8_t *signs, const HashOut &out, int64_t 
     if (!a.codes && !a.packed) return LFFN_E_NULL;
     if (out.probes && (!a.codes || !a.weights)) return LFFN_E_UNSUPPORTED;  // shares exist in the ABI layout only
     TimedLaunch tl(0, s);
-    // d_pad = 1024 or 512, up to four rounds, codes alone or with the gather weights of a tau that divides the
-    // lanes of a token (a table is then a run of lanes of one register): a token per row of 16 (8) lanes, four
-    // (eight) tokens per wavefront, no LDS transposes.  A lane holds every 16th (8th) coordinate: d a multiple
+    // d_pad = 1024 or 512, up to four rounds, codes alone or with the gather weights (reduced in registers when
+    // tau divides the lanes of a token: a table is then a run of lanes of one register; else through a z window
+    // in LDS): a token per row of 16 (8) lanes, four (eight) tokens per wavefront, no LDS transposes.  A lane holds every 16th (8th) coordinate: d a multiple
     // of 16 makes "in range" a per-register question.
     // It needs a batch that gives most SIMDs two waves of tokens to pull ahead; below that one group's latency
     // decides and the one-token kernels are faster.  Measured crossovers: d_pad = 1024 about 2048 tokens (4096
     // with weights), d_pad = 512 (twice the tokens per wave) about 6000 (10000 with weights).
     const int lpt = L == 10 ? 16 : 8;
-    const bool row_weights_ok = !out.weights || (!out.probes && lpt % tau == 0);
+    const bool row_weights_ok = !out.weights || !out.probes;
+    const bool row_window = out.weights && lpt % tau != 0;  // weights through the z window in LDS
     const int64_t row_from = lpt == 16 ? (out.weights ? 4096 : 2048) : (out.weights ? 12288 : 6144);
     const bool row_wanted = opt.hash_path == 3 || (opt.hash_path == 0 && n >= row_from);
     if (row_wanted && (L == 10 || L == 9) && d % 16 == 0 && n_rounds >= 1 && n_rounds <= 4 && row_weights_ok &&
-        aligned(signs, 16) && hrow_lds_bytes(a.P, n_rounds, lpt) <= 64 * 1024) {
+        aligned(signs, 16) && hrow_lds_bytes(a.P, n_rounds, lpt, row_window) <= 64 * 1024) {
         // two workgroups per compute unit fill it (two waves per SIMD); a larger batch is worked through in
         // several groups of tokens per wave, the next group's rows in flight during a transform
         int cus = 0;
@@ -838,7 +846,7 @@ int launch_hash(const void *x, const int8_t *signs, const HashOut &out, int64_t 
         int64_t blocks = (groups + kRowWaves - 1) / kRowWaves;
         const int64_t cap = opt.hash_blocks ? opt.hash_blocks : 2 * (int64_t)cus;
         if (blocks > cap) blocks = cap;
-        const size_t lds = hrow_lds_bytes(a.P, n_rounds, lpt);
+        const size_t lds = hrow_lds_bytes(a.P, n_rounds, lpt, row_window);
         rc = lpt == 16 ? lffn_host::hash_row16_part(n_rounds, a, dim3((unsigned)blocks), lds, s)
                        : lffn_host::hash_row8_part(n_rounds, a, dim3((unsigned)blocks), lds, s);
         if (rc != LFFN_OK) return rc;

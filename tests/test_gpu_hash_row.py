@@ -201,15 +201,45 @@ def test_hash_kernel_choice_by_batch_size_and_shape():
         assert kernel(2047, 768, 96, 8) == "hash1024_kernel"          # small batches: one group's latency decides
         assert kernel(4096, 768, 96, 8, weighted=True) == "hash_row_kernel"
         assert kernel(4095, 768, 96, 8, weighted=True) == "hash1024_kernel"
-        assert kernel(4096, 768, 80, 10, weighted=True) == "hash1024_kernel"   # tau does not divide 16
+        assert kernel(4096, 768, 80, 10, weighted=True) == "hash_row_kernel"   # tau does not divide 16: z window
         assert kernel(4096, 1000, 96, 8) == "hash1024_kernel"         # d not a multiple of 16
         assert kernel(4096, 768, 96, 8, R=5) == "hash_kernel"         # five rounds
         assert kernel(6144, 512, 64, 8) == "hash_row_kernel"          # d_pad = 512: eight tokens per wavefront
         assert kernel(6143, 512, 64, 8) == "hash_kernel"
         assert kernel(12288, 512, 64, 8, weighted=True) == "hash_row_kernel"
         assert kernel(12287, 512, 64, 8, weighted=True) == "hash_kernel"
-        assert kernel(12288, 512, 32, 16, weighted=True) == "hash_kernel"     # tau = 16 spans two registers there
+        assert kernel(12288, 512, 32, 16, weighted=True) == "hash_row_kernel"  # tau = 16 spans two registers there: z window
         assert kernel(4096, 256, 32, 8) == "hash_kernel"              # d_pad = 256
         assert kernel(4096, 1024, 200, 16) == "hash1024_kernel"       # four projections: the constants outgrow 64 KB of LDS
     finally:
         B.lookupffn_set_option("hash_path", 3)
+
+
+X_WINDOW_SHAPES = [
+    # n, d, k, tau, R, x dtype      (weights of a tau that does not divide the lanes of a token: z window in LDS)
+    (4099, 768, 170, 9, 3, "f32"),      # the paper's RoBERTa-base shape: table 113 straddles the two projections
+    (20011, 1024, 128, 10, 3, "f32"),   # the benchmark's tau = 10 layer: table 102 straddles
+    (777, 1024, 78, 13, 3, "bf16"),     # one projection, last table ends at bit 1014
+    (777, 768, 130, 15, 3, "f32"),      # two projections, table 68 straddles them
+    (777, 768, 300, 3, 2, "f16"),       # tau = 3
+    (5, 768, 170, 9, 3, "f32"),
+    (4099, 512, 100, 9, 3, "f32"),      # d_pad = 512: eight tokens per wave, two projections
+    (777, 512, 30, 16, 3, "f32"),       # tau = 16 spans two registers of the 8-lane form
+    (777, 384, 61, 7, 4, "bf16"),
+]
+
+
+@pytest.mark.parametrize("n,d,k,tau,R,xdt", X_WINDOW_SHAPES)
+def test_hash_weighted_lane_rows_any_tau(n, d, k, tau, R, xdt):
+    print(f"weighted hash (token per lane row, z window) n={n} d={d} k={k} tau={tau} R={R} {xdt}", flush=True)
+    w = synth.Workload("t", 7, n, d, R, k, tau, 8, x_dtype=xdt)
+    signs = synth.make_signs(1000 * d + k + R + 1, w.n_proj, R, w.d_pad)
+    x = synth.make_x(n + d + 3, n, d, xdt)
+    want_codes = oracle.hash_codes(x, signs, k, tau)
+    want_w = oracle.weights(x, signs, k, tau)
+    codes, wts = B.lookupffn_hash_weighted(B.to_device(x), B.to_device(signs), k, tau)
+    torch.cuda.synchronize()
+    assert B.lookupffn_last_hash_kernel() == "hash_row_kernel"
+    assert np.array_equal(B.codes_to_numpy(codes), want_codes)
+    err = np.abs(wts.cpu().numpy().astype(np.float64) - want_w) / np.maximum(np.abs(want_w), 1e-30)
+    assert err.max() <= TOL_W, f"weights off by {err.max():.2e}"
