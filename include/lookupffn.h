@@ -252,11 +252,9 @@ int64_t lookupffn_workspace_bytes_bh(int64_t n_tokens, int d, int k, int tau, in
  * (fp32, 4-byte aligned) with w_j as in lookupffn_hash_weighted, computed from the z of the BH hash;
  * lookupffn_forward_bh_weighted = that + lookupffn_gather_weighted, with
  * lookupffn_workspace_bytes_bh_weighted() bytes of scratch.
- * Supported: the shapes of lookupffn_hash_bh.  With tau = 4, 8 or 16 the hash kernel reduces a table's weight
- * itself (a table lies inside one 16-coordinate tile of z); with any other tau (the paper's RoBERTa-base row is
- * tau = 9) it writes z to the workspace -- n_tokens * P * d_pad fp32, counted by
- * lookupffn_workspace_bytes_bh_weighted(), which lookupffn_hash_bh_weighted then needs as well -- and a second
- * kernel forms the weights from it.
+ * Supported: the shapes of lookupffn_hash_bh, every tau (with tau = 4, 8 or 16 a table lies inside one
+ * 16-coordinate tile of z and is reduced in registers; with any other tau -- the paper's RoBERTa-base row is
+ * tau = 9 -- the kernel forms the weights from z through a window in LDS).
  */
 int lookupffn_hash_bh_weighted(const void *x, const float *bmats, uint16_t *codes, float *weights,
                                int64_t n_tokens, int d, int k, int tau, int block, int n_factors, int x_dtype,

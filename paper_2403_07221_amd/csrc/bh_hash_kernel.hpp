@@ -38,8 +38,8 @@ struct BhArgs {
     uint32_t *packed;     // packed codes of the staged gather, or NULL
     float *weights;       // weighted variant: gather weights [n][k] (beside `codes`), or NULL
     float *wpk;           // weighted variant: the same table-major, [k][n_pad] (beside `packed`), or NULL
-    float *zout;          // plain variant: z of every token, [n][P*N] fp32, for weights of tables that straddle
-                          // tiles (any tau), or NULL
+    int window;           // plain instantiation with `weights` / `wpk` set: the weights of a tau whose tables
+                          // straddle tiles, formed from z through a window in LDS (see the kernel)
     long long n_pad;
     int packed_shift;     // log2 of the row-piece bytes the packed codes are scaled by
     long long n;
@@ -62,9 +62,16 @@ __host__ __device__ constexpr int bh_chunk_tiles(int N, int TB)
 }
 // words of LDS per wave: one bit string of P*N bits per token
 __host__ __device__ inline int bh_bit_words(int P, int N) { return hash_bit_words(P, N); }
-__host__ inline size_t bh_lds_bytes(int P, int N)
+// z window of the weights of a tau other than 4, 8, 16: per wave, for each of its 16 tokens, kBhWinTail
+// coordinates before the current run of kBhWin(N) coordinates and the run itself; an odd number of words per
+// token spreads the tokens over the banks
+constexpr int kBhWinTail = 16;
+__host__ __device__ constexpr int kBhWin(int N) { return N < 128 ? N : 128; }
+__host__ __device__ constexpr int bh_win_stride(int N) { return kBhWin(N) + kBhWinTail + 1; }
+__host__ inline size_t bh_lds_bytes(int P, int N, bool window = false)
 {
-    return kBhRing * (size_t)kBhChunkBytes + sizeof(uint32_t) * (size_t)kBhWaves * kBhTok * bh_bit_words(P, N);
+    return kBhRing * (size_t)kBhChunkBytes + sizeof(uint32_t) * (size_t)kBhWaves * kBhTok * bh_bit_words(P, N) +
+           (window ? sizeof(float) * (size_t)kBhWaves * kBhTok * bh_win_stride(N) : 0);
 }
 
 // Packed factor layout: apack[p][f][o][ii][l][kk], o < N/16 output tiles, ii < b/16 input tiles of
@@ -400,14 +407,68 @@ __global__ __launch_bounds__(kBhThreads) void bh_hash_kernel(BhArgs a)
                     emit(std::integral_constant<int, 4>{});
             }
 
-            // z itself, on request: register r of tile beta is coordinate 16*beta + g + 4r
+            // ---- weighted variant for any other tau: a table then straddles tiles (and may run from one
+            // projection into the next), so z goes through a window in LDS, kBhWin coordinates of all 16 tokens at
+            // a time; the lanes take a (token, table) pair each and form the same sum and product coordinate
+            // by coordinate.  A table is handled in the run that holds its last coordinate; the 16 coordinates
+            // before a run are kept (across projections too).  Register r of tile beta is coordinate
+            // 16*beta + g + 4r.
             if constexpr (!WEIGHTED) {
-                if (a.zout && t_ok) {
-                    float *zr = a.zout + (t * P + p) * N + g;
+                if (a.window) {
+                    constexpr int QW = kBhWin(N), QT = QW / 16, ZS = bh_win_stride(N);
+                    float *zw = reinterpret_cast<float *>(lds + kBhRing * (kBhChunkBytes / 4) + kBhWaves * (kBhTok * n_bitw)) +
+                                wave * (kBhTok * ZS);
+                    const int tau = a.tau;
 #pragma unroll
-                    for (int beta = 0; beta < NT; ++beta)
+                    for (int q0 = 0; q0 < NT; q0 += QT) {
+                        wave_lds_fence();
+                        {
+                            float *zt = zw + tl * ZS + kBhWinTail + g;
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) zr[16 * beta + 4 * r] = v[beta][r];
+                            for (int b = 0; b < QT; ++b)
+#pragma unroll
+                                for (int r = 0; r < 4; ++r) zt[16 * b + 4 * r] = v[q0 + b][r];
+                        }
+                        wave_lds_fence();
+                        const long long lo = (long long)p * N + 16 * q0;  // first coordinate of the run in the bit string
+                        const int jlo = (int)(lo / tau);
+                        long long jhi = (lo + QW) / tau;
+                        if (jhi > a.k) jhi = a.k;
+                        const int ntab = (int)jhi - jlo;
+                        for (int idx = (int)lane; idx < kBhTok * ntab; idx += 64) {
+                            // table-major output: the 16 tokens of a table are neighbours; else a token's tables are
+                            const int tt = a.wpk ? (idx & 15) : idx / ntab;
+                            const int j = jlo + (a.wpk ? (idx >> 4) : idx - tt * ntab);
+                            const long long tok = grp * kBhTok + tt;
+                            const float *zz = zw + tt * ZS + kBhWinTail + (int)((long long)j * tau - lo);  // may start in the tail
+                            float sum = 0.0f, q = 1.0f;
+                            for (int b = 0; b < tau; ++b) {
+                                const float az = __builtin_fabsf(zz[b]);
+                                sum += az;
+                                q *= 1.0f + __builtin_amdgcn_exp2f(az * -2.885390082f);  // exp(-2 az) = 2^(-2 az log2 e)
+                            }
+                            const float w = sum * __builtin_amdgcn_rcpf(q);  // q >= 1
+                            if (tok < a.n) {
+                                if (a.wpk) a.wpk[wpk_index(j, tok, a.n_pad)] = w;
+                                else a.weights[tok * a.k + j] = w;
+                            }
+                        }
+                        // the run's last 16 coordinates become the tail of the next run: 16 tokens x 16 words
+                        wave_lds_fence();
+                        float keep[4];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int e = (int)lane + 64 * i;  // token e / 16, word e % 16
+                            keep[i] = zw[(e >> 4) * ZS + kBhWinTail + QW - kBhWinTail + (e & 15)];
+                        }
+                        wave_lds_fence();
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int e = (int)lane + 64 * i;
+                            zw[(e >> 4) * ZS + (e & 15)] = keep[i];
+                        }
+                    }
+                    wave_lds_fence();
                 }
             }
 

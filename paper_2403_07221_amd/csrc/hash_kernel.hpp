@@ -655,27 +655,6 @@ __global__ __launch_bounds__(kHashThreads) __attribute__((amdgpu_waves_per_eu(4,
 
 // The re-pack kernels are plain functions: when the library is built in parts only part 0 defines them.
 #if !defined(LFFN_PART) || LFFN_PART == 0
-// Gather weights (Sec. 4) from soft codes kept in memory: z[n][zs], table j's coordinates are
-// z[t][j*tau .. (j+1)*tau).  One thread per (token, table); the same fp32 formula as emit_weights.  Used where
-// the hash kernel cannot reduce the weights itself (the BH kernel for tau other than 4, 8, 16).
-__global__ __launch_bounds__(256) void weights_from_z_kernel(const float *z, long long zs, float *weights, long long n,
-                                                             int k, int tau)
-{
-    const long long total = n * k;
-    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
-        const long long t = i / k;
-        const int j = (int)(i - t * k);
-        const float *zj = z + t * zs + (long long)j * tau;
-        float sum = 0.0f, q = 1.0f;
-        for (int b = 0; b < tau; ++b) {
-            const float az = __builtin_fabsf(zj[b]);
-            sum += az;
-            q *= 1.0f + __builtin_amdgcn_exp2f(az * -2.885390082f);  // exp(-2 az) = 2^(-2 az log2 e)
-        }
-        weights[i] = __fdividef(sum, q);
-    }
-}
-
 // The re-pack kernels transpose a token-major matrix src[n][m] into the table-major dst[m][n_pad] the
 // staged gather reads, through 64 x 64 LDS tiles so that both the reads (along m) and the writes (along
 // n) are contiguous; grid-stride over tiles.

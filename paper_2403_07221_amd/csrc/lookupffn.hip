@@ -1308,22 +1308,14 @@ int check_bh(const void *x, const float *bmats, int64_t n, int d, int k, int tau
     if (b != 16 && b != 32 && b != 64) return LFFN_E_UNSUPPORTED;
     if (b > N) return LFFN_E_SIZE;
     const int64_t P = ((int64_t)k * tau + N - 1) / N;
-    if (P > 64 || bh_lds_bytes((int)P, N) > 150 * 1024) return LFFN_E_UNSUPPORTED;
+    if (P > 64 || bh_lds_bytes((int)P, N, weighted && !(tau == 4 || tau == 8 || tau == 16)) > 150 * 1024) return LFFN_E_UNSUPPORTED;
     if (!aligned(x, x_dtype == LFFN_F32 ? 4 : 2) || !aligned(bmats, (block & LFFN_PREPARED) ? 256 : 4)) return LFFN_E_ALIGN;
     return LFFN_OK;
 }
 
-// The BH kernel reduces a table's weight inside one 16-coordinate tile of z (tau = 4, 8, 16).  For any other
-// tau it writes z to scratch memory and a second kernel forms the weights (codes and weights then come in the
-// ABI layout only).
+// The BH kernel reduces a table's weight inside one 16-coordinate tile of z (tau = 4, 8, 16: the weighted
+// instantiations).  For any other tau the plain instantiation forms the weights from z through a window in LDS.
 bool bh_weights_in_kernel(int tau) { return tau == 4 || tau == 8 || tau == 16; }
-int64_t bh_z_bytes(int64_t n, int d, int k, int tau, bool weighted)
-{
-    if (!weighted || bh_weights_in_kernel(tau) || n <= 0) return 0;
-    const int N = 1 << log2_pad(d);
-    const int64_t P = ((int64_t)k * tau + N - 1) / N;
-    return sat_bytes((u128)n * (u128)P * (u128)N * 4);
-}
 
 int64_t bh_pack_bytes(int d, int k, int tau, int block, int n_factors)
 {
@@ -1348,7 +1340,7 @@ int launch_bh_pack(const float *bmats, float *apack, int d, int k, int tau, int 
 // Hashes with the packed factors `apack`; `pack_from` != NULL: re-order them from there first.
 int launch_hash_bh(const void *x, const float *pack_from, const float *apack_in, float *apack_scratch,
                    const HashOut &out, int64_t n, int d, int k, int tau, int block, int n_factors, int x_dtype,
-                   hipStream_t s, float *zscratch = nullptr)
+                   hipStream_t s)
 {
     const int L = log2_pad(d);
     const int N = 1 << L;
@@ -1371,12 +1363,7 @@ int launch_hash_bh(const void *x, const float *pack_from, const float *apack_in,
     a.x_vec4 = d % 4 == 0 && aligned(x, a.x_kind ? 8 : 16);
     a.scale = (float)(1.0 / std::sqrt((double)N));
     if (!a.apack || (!a.codes && !a.packed) || out.probes) return LFFN_E_NULL;
-    const bool z_route = out.weights && !bh_weights_in_kernel(tau);  // weights from z in scratch memory
-    if (z_route) {
-        if (!zscratch || !a.codes) return LFFN_E_WORKSPACE;
-        a.weights = nullptr;
-        a.zout = zscratch;
-    }
+    a.window = out.weights && !bh_weights_in_kernel(tau);  // weights through the z window of the plain kernels
     TimedLaunch tl(0, s);
     if (pack_from) {
         int rc = launch_bh_pack(pack_from, apack_scratch, d, k, tau, block, n_factors, s);
@@ -1385,8 +1372,8 @@ int launch_hash_bh(const void *x, const float *pack_from, const float *apack_in,
     int64_t blocks = ((n + kBhTok - 1) / kBhTok + kBhWaves - 1) / kBhWaves;
     if (blocks > 4096) blocks = 4096;
     const dim3 grid((unsigned)blocks);
-    const size_t lds = bh_lds_bytes(a.P, N);
-    const bool weighted = a.weights || a.wpk;
+    const size_t lds = bh_lds_bytes(a.P, N, a.window != 0);
+    const bool weighted = (a.weights || a.wpk) && !a.window;  // the instantiations that reduce weights in registers
     int rc;
     if (L <= 8)
         rc = weighted ? lffn_host::bh_weighted_lo_part(L, a, block, grid, lds, s)
@@ -1402,13 +1389,6 @@ int launch_hash_bh(const void *x, const float *pack_from, const float *apack_in,
                       : lffn_host::bh_weighted_1024_scalar_part(a, block, grid, lds, s);
     if (rc != LFFN_OK) return rc;
     LFFN_HIP(hipGetLastError());
-    if (z_route) {
-        int64_t wb = (n * k + 255) / 256;
-        if (wb > 16384) wb = 16384;
-        hipLaunchKernelGGL(weights_from_z_kernel, dim3((unsigned)wb), dim3(256), 0, s, zscratch, (long long)a.P * N,
-                           out.weights, (long long)n, k, tau);
-        LFFN_HIP(hipGetLastError());
-    }
     tl.done();
     return LFFN_OK;
 }
@@ -1499,8 +1479,7 @@ int64_t forward_need(const HashSpec &h, Mode mode, int64_t n, int d, int k, int 
 {
     if (n <= 0) return 0;
     const int64_t pack = (h.bh() && !h.bh_prepared) ? bh_pack_bytes(d, k, tau, h.block, h.n_factors) : 0;
-    const int64_t zb = h.bh() ? bh_z_bytes(n, d, k, tau, mode == kWeighted) : 0;
-    return sat_add(sat_add(pack, zb), forward_ws_bytes(n, k, tau, mode));
+    return sat_add(pack, forward_ws_bytes(n, k, tau, mode));
 }
 
 int forward_core(const HashSpec &h, Mode mode, const void *x, const void *tables, void *y, int64_t n, int d,
@@ -1535,13 +1514,10 @@ int forward_core(const HashSpec &h, Mode mode, const void *x, const void *tables
     if (rc != LFFN_OK) return rc;
     float *apack = (h.bh() && !h.bh_prepared) ? sc.take<float>(bh_pack_bytes(d, k, tau, h.block, h.n_factors)) : nullptr;
     if (h.bh() && !h.bh_prepared && !apack) return LFFN_E_WORKSPACE;
-    const int64_t zb = h.bh() ? bh_z_bytes(n, d, k, tau, mode == kWeighted) : 0;
-    float *zscratch = zb ? sc.take<float>(zb) : nullptr;
-    if (zb && !zscratch) return LFFN_E_WORKSPACE;
     auto run_hash = [&](const HashOut &out) -> int {
         if (h.bh())
             return launch_hash_bh(x, h.bh_prepared ? nullptr : h.bmats, h.bh_prepared ? h.bmats : nullptr, apack, out, n,
-                                  d, k, tau, h.block, h.n_factors, x_dtype, s, zscratch);
+                                  d, k, tau, h.block, h.n_factors, x_dtype, s);
         return launch_hash(x, h.signs, out, n, d, k, tau, h.n_rounds, x_dtype, s, opt);
     };
     // the hash kernels write the staged gather's layout themselves, scaled for its row pieces (unless the
@@ -1549,7 +1525,7 @@ int forward_core(const HashSpec &h, Mode mode, const void *x, const void *tables
     RingPlan ring;
     rc = plan_gather_ring(n, k, tau, d_out, T, mode, opt, &ring);
     if (rc != LFFN_OK) return rc;
-    if (!ring.use && plan.use && !plan.tail && mode != kProbes && !zb) {
+    if (!ring.use && plan.use && !plan.tail && mode != kProbes) {
         HashOut out;
         out.shift = plan.shift;
         const int64_t pb = packed_bytes(n, k), wb = mode == kWeighted ? wpk_bytes(n, k) : 0;
@@ -1629,8 +1605,7 @@ int hash_bh_core(const void *x, const float *bmats, uint16_t *codes, float *weig
     if (!aligned(codes, 2) || (weighted && !aligned(weights, 4))) return LFFN_E_ALIGN;
     const HashSpec h = bh_hash(bmats, block, n_factors);
     const int64_t pb = h.bh_prepared ? 0 : bh_pack_bytes(d, k, tau, h.block, n_factors);
-    const int64_t zb = bh_z_bytes(n, d, k, tau, weighted);
-    const int64_t need = sat_add(pb, zb);
+    const int64_t need = pb;
     if (workspace) {
         if (workspace_bytes < need) return LFFN_E_WORKSPACE;
         if (!aligned(workspace, 256)) return LFFN_E_ALIGN;
@@ -1641,13 +1616,11 @@ int hash_bh_core(const void *x, const float *bmats, uint16_t *codes, float *weig
     if (rc != LFFN_OK) return rc;
     float *apack = h.bh_prepared ? nullptr : sc.take<float>(pb);
     if (!h.bh_prepared && !apack) return LFFN_E_WORKSPACE;
-    float *zscratch = zb ? sc.take<float>(zb) : nullptr;
-    if (zb && !zscratch) return LFFN_E_WORKSPACE;
     HashOut out;
     out.codes = codes;
     out.weights = weighted ? weights : nullptr;
     return launch_hash_bh(x, h.bh_prepared ? nullptr : bmats, h.bh_prepared ? bmats : nullptr, apack, out, n, d, k,
-                          tau, h.block, n_factors, x_dtype, s, zscratch);
+                          tau, h.block, n_factors, x_dtype, s);
 }
 
 bool bh_shape_ok(int d, int k, int tau, int block, int n_factors)
@@ -1825,8 +1798,7 @@ int64_t lookupffn_workspace_bytes_bh_weighted(int64_t n_tokens, int d, int k, in
 {
     if (!bh_shape_ok(d, k, tau, block & ~LFFN_PREPARED, n_factors)) return 0;
     const int64_t pack = (block & LFFN_PREPARED) ? 0 : bh_pack_bytes(d, k, tau, block, n_factors);
-    return sat_add(sat_add(pack, bh_z_bytes(n_tokens, d, k, tau, true)),
-                   n_tokens > 0 ? forward_ws_bytes(n_tokens, k, tau, kWeighted) : 0);
+    return sat_add(pack, n_tokens > 0 ? forward_ws_bytes(n_tokens, k, tau, kWeighted) : 0);
 }
 
 int lookupffn_forward(const void *x, const int8_t *signs, const void *tables, void *y, int64_t n_tokens,
