@@ -306,10 +306,11 @@ __global__ __launch_bounds__(kRowThreads) void hash_row_kernel(HashArgs a)
             float v[kRowRegs];
 #pragma unroll
             for (int m = 0; m < kRowRegs; ++m) v[m] = xn[m];
-            // the next rows (this group's again, for its next projection) are fetched during this transform, a
-            // share of the registers after each round's butterflies: all at once, the requests fill the memory
-            // pipeline and the wave waits at their issue (26.7 against 27.9 us for 16384 rows of 768)
-            const long long gn = p + 1 < P ? g : g + n_waves;
+            // xn keeps this group's rows for its next projection; during the last projection's transform the next
+            // group's rows are fetched into it, a share of the registers after each round's butterflies: all at
+            // once, the requests fill the memory pipeline and the wave waits at their issue (26.7 against 27.9 us
+            // for 16384 rows of 768)
+            const bool fetch_next = p + 1 == P && g + n_waves < n_groups;
             const lds_u32x4 *cp = reinterpret_cast<const lds_u32x4 *>((uintptr_t)cbase) + p * (R + 1) * SLOT;
             // ---- a2: first diagonal ----
 #pragma unroll
@@ -345,9 +346,9 @@ __global__ __launch_bounds__(kRowThreads) void hash_row_kernel(HashArgs a)
                 row_reg_stage<16, kRowRegs>(v);
                 row_reg_stage<32, kRowRegs>(v);
                 __builtin_amdgcn_sched_barrier(0);
-                if (gn < n_groups) {
+                if (fetch_next) {
                     constexpr int SHARE = (kRowRegs + R - 1) / R;
-                    load_rows(gn, rd * SHARE, rd + 1 < R ? (rd + 1) * SHARE : kRowRegs);
+                    load_rows(g + n_waves, rd * SHARE, rd + 1 < R ? (rd + 1) * SHARE : kRowRegs);
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 // scale, negations undone, next diagonal
