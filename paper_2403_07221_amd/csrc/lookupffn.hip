@@ -23,7 +23,7 @@
 
 // Build parts.  This file compiles whole (LFFN_PART undefined) or as parts that are linked together, so
 // that the kernel families compile side by side: part 0 holds the C ABI, the host logic and the hash and
-// re-pack kernels; parts 1 .. 15 hold one family of kernel launchers each (declared just below).  No
+// re-pack kernels; parts 1 .. 16 hold one family of kernel launchers each (declared just below).  No
 // kernel is instantiated in two parts.
 #ifdef LFFN_PART
 #define LFFN_HAS(p) (LFFN_PART == (p))
@@ -47,6 +47,7 @@ int gather_direct_part(int kind, int lpt, const GatherArgs &a, bool probes, dim3
 int gather_direct_load();  // makes the runtime load part 1's code object now (lookupffn_init)
 // parts 2, 3: the LDS-staged gather kernel (plain sum; weighted and multi-probe)
 int gather_lds_plain_part(int tok, const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s);
+int gather_lds_plain13_part(const GatherLdsArgs &a, int fr, dim3 grid, size_t lds, hipStream_t s);  // part 16
 int gather_lds_weighted_part(int tok, const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s);
 int gather_lds_probes_part(int tok, const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s);
 // part 12: the lagged, bank-interleaved staged gather (prepared tables, tau <= 8)
@@ -132,10 +133,11 @@ int launch_gather_lds_fr(const GatherLdsArgs &a, dim3 grid, size_t lds, hipStrea
 }
 
 // fr = 16 KB copy rounds per table slice, sw = lanes per token (both fixed by the plan)
-template <int TOK, bool WEIGHTED = false>
+// SW8: this part also holds the 128-byte-slice form of TOK (part 16 holds the plain one with 13 slots)
+template <int TOK, bool WEIGHTED = false, bool SW8 = true>
 int launch_gather_lds_t(const GatherLdsArgs &a, int fr, int sw, dim3 grid, size_t lds, hipStream_t s)
 {
-    if constexpr (TOK <= 13) {
+    if constexpr (TOK <= 13 && SW8) {
         if (sw == 8)
             return fr == 4   ? launch_gather_lds_fr<TOK, 4, WEIGHTED, 8>(a, grid, lds, s)
                    : fr == 2 ? launch_gather_lds_fr<TOK, 2, WEIGHTED, 8>(a, grid, lds, s)
@@ -223,9 +225,21 @@ int gather_lds_plain_part(int tok, const GatherLdsArgs &a, int fr, int sw, dim3 
     if (tok <= 4) return launch_gather_lds_t<4>(a, fr, sw, grid, lds, s);
     if (tok <= 8) return launch_gather_lds_t<8>(a, fr, sw, grid, lds, s);
     if (tok <= 12) return launch_gather_lds_t<12>(a, fr, sw, grid, lds, s);
-    if (tok <= 13) return launch_gather_lds_t<13>(a, fr, sw, grid, lds, s);
+    if (tok <= 13 && sw == 8) return gather_lds_plain13_part(a, fr, grid, lds, s);
+    if (tok <= 13) return launch_gather_lds_t<13, false, false>(a, fr, sw, grid, lds, s);
     if (tok <= 16 && sw == 4) return launch_gather_lds_t<16>(a, fr, sw, grid, lds, s);
     return LFFN_E_UNSUPPORTED;
+}
+#endif
+
+#if LFFN_HAS(16)
+// The plain sum with 13 token slots and 128-byte slices -- the kernel of the 16384-token benchmark layer -- is
+// compiled on its own so that it can take the scheduler setting that suits it (see build.py).
+int gather_lds_plain13_part(const GatherLdsArgs &a, int fr, dim3 grid, size_t lds, hipStream_t s)
+{
+    return fr == 4   ? launch_gather_lds_fr<13, 4, false, 8>(a, grid, lds, s)
+           : fr == 2 ? launch_gather_lds_fr<13, 2, false, 8>(a, grid, lds, s)
+                     : launch_gather_lds_fr<13, 1, false, 8>(a, grid, lds, s);
 }
 #endif
 
