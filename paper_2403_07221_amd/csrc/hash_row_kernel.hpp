@@ -237,9 +237,10 @@ __global__ __launch_bounds__(kRowThreads) void hash_row_kernel(HashArgs a)
 
     // ---- a1: a token's row, zero-padded to N.  d is a multiple of 16 (host-checked): register m is in
     // range for every lane or for none.  A row past the end of the batch reads the last token's.
-    float xn[kRowRegs];  // the rows in flight
+    // xn holds the rows in flight as they come from memory: fp32 values, or the 16 bits of a bf16 / half element
+    // (widened where the rows are taken over, in one place, by a wave-uniform choice of the element type)
+    float xn[kRowRegs];
     auto load_rows = [&](long long g, int m0 = 0, int m1 = kRowRegs) {  // registers m0 .. m1 - 1
-        float (&v)[kRowRegs] = xn;
         const long long t = g * TOK + row;
         const long long t_ld = t < a.n ? t : a.n - 1;
         if (a.x_kind == kElemF32) {
@@ -247,17 +248,31 @@ __global__ __launch_bounds__(kRowThreads) void hash_row_kernel(HashArgs a)
 #pragma unroll
             for (int m = 0; m < kRowRegs; ++m) {
                 if (m < m0 || m >= m1) continue;
-                if constexpr (MFULL != 0) v[m] = m < MFULL ? xr[LPT * m] : 0.0f;
-                else v[m] = m < m_full ? xr[LPT * m] : 0.0f;
+                if constexpr (MFULL != 0) xn[m] = m < MFULL ? xr[LPT * m] : 0.0f;
+                else xn[m] = m < m_full ? xr[LPT * m] : 0.0f;
             }
         } else {
             const uint16_t *xr = static_cast<const uint16_t *>(a.x) + t_ld * a.d + c;
 #pragma unroll
             for (int m = 0; m < kRowRegs; ++m) {
                 if (m < m0 || m >= m1) continue;
-                if constexpr (MFULL != 0) v[m] = m < MFULL ? widen16(xr[LPT * m], a.x_kind) : 0.0f;
-                else v[m] = m < m_full ? widen16(xr[LPT * m], a.x_kind) : 0.0f;
+                uint32_t bits = 0u;
+                if constexpr (MFULL != 0) { if (m < MFULL) bits = xr[LPT * m]; }
+                else { if (m < m_full) bits = xr[LPT * m]; }
+                xn[m] = __uint_as_float(bits);
             }
+        }
+    };
+    auto take_rows = [&](float (&v)[kRowRegs]) {
+        if (a.x_kind == kElemF32) {
+#pragma unroll
+            for (int m = 0; m < kRowRegs; ++m) v[m] = xn[m];
+        } else if (a.x_kind == kElemBF16) {
+#pragma unroll
+            for (int m = 0; m < kRowRegs; ++m) v[m] = __uint_as_float(__float_as_uint(xn[m]) << 16);
+        } else {
+#pragma unroll
+            for (int m = 0; m < kRowRegs; ++m) v[m] = half_bits_to_float((uint16_t)__float_as_uint(xn[m]));
         }
     };
     if (gw < n_groups) load_rows(gw);  // in flight while the constants are built
@@ -304,8 +319,7 @@ __global__ __launch_bounds__(kRowThreads) void hash_row_kernel(HashArgs a)
         const bool t_ok = t < a.n;
         for (int p = 0; p < P; ++p) {
             float v[kRowRegs];
-#pragma unroll
-            for (int m = 0; m < kRowRegs; ++m) v[m] = xn[m];
+            take_rows(v);
             // xn keeps this group's rows for its next projection; during the last projection's transform the next
             // group's rows are fetched into it, a share of the registers after each round's butterflies: all at
             // once, the requests fill the memory pipeline and the wave waits at their issue (26.7 against 27.9 us
